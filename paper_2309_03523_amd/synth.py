@@ -1,0 +1,323 @@
+"""Seeded synthetic dynamic graphs, features, parameters and chunk sets.
+
+This module only *draws inputs*: it contains none of the layer's arithmetic
+(no aggregation, no normalisation, no recurrence).  Both the CPU oracle and the
+HIP path read the arrays it returns, so the two sides always see identical
+bytes.  NumPy only; every stream is derived from (seed, stream name), so adding
+a stream never shifts another one.
+
+The workloads stand in for the paper's data sets (Table 1: very dense next to
+very sparse snapshots, power-law degrees), which are not available here.
+"""
+from __future__ import annotations
+
+import zlib
+from dataclasses import dataclass, field
+from typing import List, Optional, Tuple
+
+import numpy as np
+
+
+def stream(seed: int, name: str) -> np.random.Generator:
+    """Independent generator for the named sub-stream of a seed."""
+    return np.random.default_rng(np.random.SeedSequence([int(seed), zlib.crc32(name.encode())]))
+
+
+# --------------------------------------------------------------------------- graphs
+
+
+@dataclass
+class Snapshot:
+    """One snapshot as CSR: rowptr int64[N+1], col int32[nnz] (sorted, unique, self-loop stored)."""
+
+    rowptr: np.ndarray
+    col: np.ndarray
+
+    @property
+    def nnz(self) -> int:
+        return int(self.rowptr[-1])
+
+
+@dataclass
+class DynamicGraph:
+    N: int
+    snaps: List[Snapshot]
+
+    @property
+    def T(self) -> int:
+        return len(self.snaps)
+
+    @property
+    def nnz(self) -> int:
+        return sum(s.nnz for s in self.snaps)
+
+
+def csr_from_undirected(N: int, u: np.ndarray, v: np.ndarray) -> Snapshot:
+    """CSR of the symmetric closure of the pairs (u,v), self-pairs and duplicates dropped,
+    plus one self-loop per vertex.  Columns ascending within a row."""
+    u = np.asarray(u, dtype=np.int64)
+    v = np.asarray(v, dtype=np.int64)
+    keep = u != v
+    u, v = u[keep], v[keep]
+    loops = np.arange(N, dtype=np.int64)
+    src = np.concatenate([u, v, loops])
+    dst = np.concatenate([v, u, loops])
+    key = np.unique(src * N + dst)  # sorted => row-major, columns ascending
+    row = key // N
+    col = (key - row * N).astype(np.int32)
+    rowptr = np.zeros(N + 1, dtype=np.int64)
+    np.cumsum(np.bincount(row, minlength=N), out=rowptr[1:])
+    return Snapshot(rowptr=rowptr, col=col)
+
+
+def erdos_renyi_snapshot(N: int, avg_deg: float, rng: np.random.Generator) -> Snapshot:
+    """G(n,p) with p = avg_deg/(N-1): the number of pairs is binomial, pairs uniform."""
+    n_pairs = N * (N - 1) // 2
+    m = int(rng.binomial(n_pairs, avg_deg / (N - 1)))
+    # uniform pairs with replacement; duplicates are dropped by the CSR builder, so draw a
+    # few more than m and trim after de-duplication to keep the expected count
+    u = rng.integers(0, N, size=int(m * 1.05) + 8)
+    v = rng.integers(0, N, size=u.size)
+    ok = u != v
+    u, v = u[ok], v[ok]
+    lo, hi = np.minimum(u, v), np.maximum(u, v)
+    _, first = np.unique(lo * N + hi, return_index=True)
+    first.sort()
+    first = first[:m]
+    return csr_from_undirected(N, lo[first], hi[first])
+
+
+def powerlaw_weights(N: int, alpha: float, rng: np.random.Generator) -> np.ndarray:
+    """Vertex weights rank^(-1/(alpha-1)) over a shuffled vertex order: the expected degree
+    sequence has tail exponent alpha."""
+    rank = rng.permutation(N).astype(np.float64) + 1.0
+    w = rank ** (-1.0 / (alpha - 1.0))
+    return w / w.sum()
+
+
+def chung_lu_snapshot(N: int, n_edges: int, w: np.ndarray, rng: np.random.Generator) -> Snapshot:
+    """n_edges endpoint pairs, both endpoints drawn proportionally to w."""
+    cdf = np.cumsum(w)
+    cdf[-1] = 1.0
+    u = np.searchsorted(cdf, rng.random(n_edges), side="right")
+    v = np.searchsorted(cdf, rng.random(n_edges), side="right")
+    return csr_from_undirected(N, u, v)
+
+
+def chung_lu_blocked_snapshot(N: int, n_edges: int, w: np.ndarray, bounds: np.ndarray,
+                              p_inside: float, rng: np.random.Generator) -> Snapshot:
+    """Like chung_lu_snapshot, but an edge keeps both endpoints inside one vertex range
+    (ranges given by `bounds`, ascending, bounds[0]=0, bounds[-1]=N) with probability
+    p_inside; the second endpoint is then drawn proportionally to w within that range."""
+    cdf = np.cumsum(w)
+    cdf[-1] = 1.0
+    u = np.searchsorted(cdf, rng.random(n_edges), side="right")
+    v = np.searchsorted(cdf, rng.random(n_edges), side="right")
+    inside = rng.random(n_edges) < p_inside
+    blk = np.searchsorted(bounds, u, side="right") - 1
+    cdf0 = np.concatenate([[0.0], cdf])
+    lo_mass = cdf0[bounds[blk]]
+    hi_mass = cdf0[bounds[blk + 1]]
+    r = lo_mass + rng.random(n_edges) * (hi_mass - lo_mass)
+    v_in = np.clip(np.searchsorted(cdf, r, side="right"), bounds[blk], bounds[blk + 1] - 1)
+    v = np.where(inside, v_in, v)
+    return csr_from_undirected(N, u, v)
+
+
+# --------------------------------------------------------------------------- chunks
+
+
+def uneven_ranges(N: int, n_ranges: int, rng: np.random.Generator, min_frac: float = 0.25) -> np.ndarray:
+    """Split [0,N) into n_ranges contiguous ranges of uneven width, each at least
+    min_frac of the mean width.  Returns the n_ranges+1 boundaries."""
+    mean = N / n_ranges
+    floor_w = int(min_frac * mean)
+    rest = N - floor_w * n_ranges
+    share = rng.dirichlet(np.ones(n_ranges))
+    extra = np.floor(share * rest).astype(np.int64)
+    extra[0] += rest - extra.sum()
+    widths = floor_w + extra
+    return np.concatenate([[0], np.cumsum(widths)]).astype(np.int64)
+
+
+def grid_chunks(T: int, window: int, bounds_per_window: List[np.ndarray]) -> np.ndarray:
+    """Chunks = time windows x vertex ranges, window-major.  int64 array [n,4] of
+    (v_lo, v_hi, t_lo, t_hi), half-open."""
+    out = []
+    for k, t_lo in enumerate(range(0, T, window)):
+        b = bounds_per_window[k]
+        for r in range(len(b) - 1):
+            out.append((int(b[r]), int(b[r + 1]), t_lo, min(T, t_lo + window)))
+    return np.asarray(out, dtype=np.int64).reshape(-1, 4)
+
+
+# --------------------------------------------------------------------------- parameters
+
+
+def xavier_uniform(rng: np.random.Generator, fan_out: int, fan_in: int) -> np.ndarray:
+    a = np.sqrt(6.0 / (fan_in + fan_out))
+    return rng.uniform(-a, a, size=(fan_out, fan_in)).astype(np.float32)
+
+
+def layer_params(seed: int, F: int, S: int, H: int, time_kind: str, n_struct_layers: int = 1,
+                 random_bias: bool = False) -> dict:
+    """Weights in (out, in) row-major order, Xavier-uniform.  Biases are zero unless
+    random_bias (tests use non-zero biases so that a dropped bias fails)."""
+    rng = stream(seed, "param")
+    g = {"gru": 3, "lstm": 4, "none": 0}[time_kind]
+    p = {}
+    dims_in = [F] + [S] * (n_struct_layers - 1)
+    for l, fin in enumerate(dims_in):
+        p[f"gcn{l}.weight"] = xavier_uniform(rng, S, fin)          # [S, fin]
+        p[f"gcn{l}.bias"] = np.zeros(S, np.float32)
+    if g:
+        p["rnn.weight_ih"] = xavier_uniform(rng, g * H, S)          # [gH, S]
+        p["rnn.weight_hh"] = xavier_uniform(rng, g * H, H)          # [gH, H]
+        p["rnn.bias_ih"] = np.zeros(g * H, np.float32)
+        p["rnn.bias_hh"] = np.zeros(g * H, np.float32)
+    if random_bias:
+        for k in p:
+            if k.endswith("bias") or ".bias_" in k:
+                p[k] = rng.uniform(-0.5, 0.5, size=p[k].shape).astype(np.float32)
+    return p
+
+
+# --------------------------------------------------------------------------- workloads
+
+
+@dataclass
+class Workload:
+    name: str
+    graph: DynamicGraph
+    chunks: np.ndarray                      # int64 [n,4]
+    F: int
+    S: int
+    H: int
+    time_kind: str                          # "gru" | "lstm" | "none"
+    n_struct_layers: int
+    X: np.ndarray                           # fp32 [T,N,F]
+    C: np.ndarray                           # fp32 [T,N,F] stale cache of layer-0 inputs
+    C1: Optional[np.ndarray]                # fp32 [T,N,S] stale cache of layer-1 inputs (2-layer only)
+    H0: Optional[np.ndarray]                # fp32 [sum chunk vertices, H] (then the cell state for LSTM)
+    params: dict = field(default_factory=dict)
+    notes: dict = field(default_factory=dict)
+
+    @property
+    def rows(self) -> int:
+        c = self.chunks
+        return int(((c[:, 1] - c[:, 0]) * (c[:, 3] - c[:, 2])).sum())
+
+
+def _normal_f32(rng: np.random.Generator, shape) -> np.ndarray:
+    return rng.standard_normal(size=shape, dtype=np.float32)
+
+
+def _h0_for(chunks: np.ndarray, H: int, time_kind: str, rng: np.random.Generator) -> Optional[np.ndarray]:
+    """Window-start state per chunk row: zeros for windows starting at t=0, a small
+    N(0, 0.1^2) state (a stale temporal neighbour) for later windows."""
+    if time_kind == "none":
+        return None
+    n_state = 2 if time_kind == "lstm" else 1
+    tot = int((chunks[:, 1] - chunks[:, 0]).sum())
+    h0 = np.zeros((n_state, tot, H), np.float32)
+    off = 0
+    for v_lo, v_hi, t_lo, _ in chunks:
+        n = int(v_hi - v_lo)
+        if t_lo > 0:
+            h0[:, off:off + n] = 0.1 * _normal_f32(rng, (n_state, n, H))
+        off += n
+    return h0.reshape(n_state * tot, H)
+
+
+def config1(seed: int = 0, random_bias: bool = False) -> Workload:
+    """Tiny GCN+GRU: 8 snapshots x 1000 vertices, G(n,p) average degree 8, F=S=H=32,
+    4 chunks of 250 contiguous vertices x all 8 snapshots, cache ~ N(0,1) independent of X."""
+    T, N, F = 8, 1000, 32
+    g_rng = stream(seed, "graph")
+    graph = DynamicGraph(N, [erdos_renyi_snapshot(N, 8.0, g_rng) for _ in range(T)])
+    bounds = np.arange(0, N + 1, 250, dtype=np.int64)
+    chunks = grid_chunks(T, T, [bounds])
+    X = _normal_f32(stream(seed, "feat"), (T, N, F))
+    C = _normal_f32(stream(seed, "cache"), (T, N, F))
+    return Workload("config1", graph, chunks, F, 32, 32, "gru", 1, X, C, None,
+                    _h0_for(chunks, 32, "gru", stream(seed, "h0")),
+                    layer_params(seed, F, 32, 32, "gru", 1, random_bias))
+
+
+def nonuniform_powerlaw(seed: int, T: int, N: int, F: int, S: int, H: int, edge_mu: float,
+                        edge_sigma: float, edge_clip: Tuple[int, int], alpha: float, window: int,
+                        n_ranges: int, time_kind: str = "gru", n_struct_layers: int = 1,
+                        uneven: bool = True, name: str = "config2",
+                        random_bias: bool = False) -> Workload:
+    """Snapshots with lognormal edge counts (dense next to sparse) and power-law degrees;
+    chunks = windows x uneven vertex ranges; cache = X + 0.1 N(0,1) (small drift since the
+    pass that filled it)."""
+    g_rng = stream(seed, "graph")
+    w = powerlaw_weights(N, alpha, stream(seed, "perm"))
+    n_edges = np.clip(np.exp(edge_mu + edge_sigma * g_rng.standard_normal(T)),
+                      edge_clip[0], edge_clip[1]).astype(np.int64)
+    graph = DynamicGraph(N, [chung_lu_snapshot(N, int(m), w, g_rng) for m in n_edges])
+    r_rng = stream(seed, "ranges")
+    n_win = (T + window - 1) // window
+    if uneven:
+        bounds = [uneven_ranges(N, n_ranges, r_rng) for _ in range(n_win)]
+    else:
+        bounds = [np.linspace(0, N, n_ranges + 1).astype(np.int64)] * n_win
+    chunks = grid_chunks(T, window, bounds)
+    X = _normal_f32(stream(seed, "feat"), (T, N, F))
+    C = _normal_f32(stream(seed, "cache"), (T, N, F))
+    C *= np.float32(0.1)
+    C += X
+    C1 = None
+    if n_struct_layers == 2:
+        C1 = _normal_f32(stream(seed, "cache1"), (T, N, S))
+    wl = Workload(name, graph, chunks, F, S, H, time_kind, n_struct_layers, X, C, C1,
+                  _h0_for(chunks, H, time_kind, stream(seed, "h0")),
+                  layer_params(seed, F, S, H, time_kind, n_struct_layers, random_bias))
+    wl.notes["edge_draws"] = n_edges
+    return wl
+
+
+def config2(seed: int = 0, scale: float = 1.0, random_bias: bool = False) -> Workload:
+    """Non-uniform GCN+GRU: 32 snapshots x 100k vertices, edge draws per snapshot
+    lognormal(ln 800k, 1) clipped to [80k, 8M], tail exponent 2.1, F=S=H=128, 64 chunks =
+    4 windows of 8 snapshots x 16 uneven vertex ranges.  `scale` < 1 shrinks N and the edge
+    counts together (same shape, for tests the oracle finishes in seconds)."""
+    N = max(64, int(100_000 * scale))
+    return nonuniform_powerlaw(seed, 32, N, 128, 128, 128, np.log(800_000 * scale), 1.0,
+                               (max(1, int(80_000 * scale)), max(2, int(8_000_000 * scale))),
+                               2.1, 8, 16, "gru", 1, True,
+                               "config2" if scale == 1.0 else f"config2@{scale:g}", random_bias)
+
+
+def random_small(seed: int, T: int, N: int, F: int, S: int, H: int, avg_deg: float,
+                 chunks: np.ndarray, time_kind: str = "gru", n_struct_layers: int = 1,
+                 hub: bool = False) -> Workload:
+    """Small random workload with arbitrary chunk set and non-zero biases, for tests."""
+    g_rng = stream(seed, "graph")
+    snaps = []
+    for _ in range(T):
+        if N > 1 and avg_deg > 0:
+            s = erdos_renyi_snapshot(N, min(avg_deg, N - 1.0), g_rng)
+        else:
+            s = csr_from_undirected(N, np.zeros(0, np.int64), np.zeros(0, np.int64))
+        snaps.append(s)
+    if hub and N > 2:
+        # one vertex adjacent to all others in the middle snapshot
+        t = T // 2
+        h = int(g_rng.integers(0, N))
+        others = np.array([i for i in range(N) if i != h], dtype=np.int64)
+        old = snaps[t]
+        rows = np.repeat(np.arange(N, dtype=np.int64), np.diff(old.rowptr))
+        snaps[t] = csr_from_undirected(N, np.concatenate([rows, np.full(N - 1, h)]),
+                                       np.concatenate([old.col.astype(np.int64), others]))
+    graph = DynamicGraph(N, snaps)
+    chunks = np.asarray(chunks, dtype=np.int64).reshape(-1, 4)
+    X = _normal_f32(stream(seed, "feat"), (T, N, F))
+    C = _normal_f32(stream(seed, "cache"), (T, N, F))
+    C1 = _normal_f32(stream(seed, "cache1"), (T, N, S)) if n_struct_layers == 2 else None
+    h0 = _h0_for(chunks, H, time_kind, stream(seed, "h0"))
+    if h0 is not None:  # make every window start non-trivial
+        h0 = (0.5 * _normal_f32(stream(seed, "h0b"), h0.shape)).astype(np.float32)
+    return Workload(f"small{seed}", graph, chunks, F, S, H, time_kind, n_struct_layers, X, C, C1, h0,
+                    layer_params(seed, F, S, H, time_kind, n_struct_layers, random_bias=True))
