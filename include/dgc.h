@@ -1,0 +1,175 @@
+/*
+ * dgc.h - C ABI of the fused-chunk dynamic-GNN layer for AMD MI355X (gfx950).
+ *
+ * The layer is the DGNN block of the paper's Section 2.1 (a structure encoder over every
+ * snapshot followed by a time encoder over every vertex's sequence), executed over a fused
+ * batch of graph chunks (Section 4: a chunk is a sub-graph across spatial and temporal
+ * boundaries; here a vertex range x a window of snapshots).  All chunks of a batch run in the
+ * same launches (spatial fusion, Section 5.1.1); a neighbour outside a row's own chunk range
+ * is read from a cache of earlier ("last transmitted") embeddings instead of the fresh input
+ * (Section 5.2); the recurrent state entering a step can be masked off per row (temporal
+ * fusion mask, Section 5.1.2).  Encoders: GCN convolution, GRU, LSTM (Section 6).
+ *
+ * Conventions
+ *  - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
+ *    host memory.  The library never frees caller memory and only borrows it while the work
+ *    it enqueued is running.
+ *  - All floating tensors are fp32, row-major, with a row pitch (ld*, in elements) that is a
+ *    multiple of 4 and a base address aligned to 16 bytes.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *  - forward / aggregate / gather only enqueue work: they return argument errors at once and
+ *    never synchronise the device.  create / set_param / get_param / packing synchronise.
+ *  - Every function returns DGC_OK (0) or an error code; dgc_last_error gives the text.
+ *  - A layer object is not thread-safe; different layers may be used from different threads.
+ */
+#ifndef DGC_H_
+#define DGC_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dgc_layer dgc_layer_t; /* opaque, owned by the library */
+
+typedef enum {
+  DGC_OK = 0,
+  DGC_ERR_INVALID_ARG = 1, /* null pointer, bad size, pitch or alignment, unknown name      */
+  DGC_ERR_BAD_GRAPH = 2,   /* CSR arrays violate the graph contract                          */
+  DGC_ERR_BAD_CHUNK = 3,   /* chunk empty, outside [0,N) x [0,T), or overlapping another     */
+  DGC_ERR_UNSUPPORTED = 4, /* a combination of options that is not built                     */
+  DGC_ERR_OOM = 5,         /* device or host allocation failed                               */
+  DGC_ERR_DEVICE = 6,      /* a HIP call failed (no device, launch error)                    */
+  DGC_ERR_STATE = 7        /* call order (backward before forward, ...)                      */
+} dgc_status_t;
+
+enum { DGC_STRUCT_GCN = 0 };
+enum { DGC_TIME_NONE = 0, DGC_TIME_GRU = 1, DGC_TIME_LSTM = 2 };
+enum { DGC_ACT_NONE = 0, DGC_ACT_RELU = 1 };
+enum { DGC_DTYPE_F32 = 0 };
+/* How rows of neighbours outside the chunk reach the aggregation (Section 5.2):
+ *  IN_PLACE the aggregation kernel reads the cache tensor directly;
+ *  STAGED   a gather kernel first copies each segment's de-duplicated halo rows (loaded once
+ *           per segment, Section 5.1.1) into a buffer that the aggregation then indexes
+ *           through the packed local column ids. */
+enum { DGC_GATHER_IN_PLACE = 0, DGC_GATHER_STAGED = 1 };
+
+/* A chunk: vertices [v_lo, v_hi) over snapshots [t_lo, t_hi). */
+typedef struct {
+  int64_t v_lo, v_hi;
+  int32_t t_lo, t_hi;
+} dgc_chunk_t;
+
+/* A dynamic graph (Section 2.1): T snapshots over the same N vertex ids.  rowptr / colidx
+ * are HOST arrays of T DEVICE pointers.  Snapshot t: rowptr[t] is int64[N+1] with
+ * rowptr[t][0] = 0; colidx[t] is int32[rowptr[t][N]], ascending and unique within a row, the
+ * self-loop (i,i) stored for every vertex, symmetric (undirected).  The arrays must stay
+ * valid and unchanged for the life of the layer. */
+typedef struct {
+  int32_t T;
+  int64_t N;
+  const int64_t* const* rowptr;
+  const int32_t* const* colidx;
+} dgc_graph_t;
+
+typedef struct {
+  int32_t struct_kind;     /* DGC_STRUCT_GCN                                                 */
+  int32_t n_struct_layers; /* 1 or 2 stacked GCN layers                                      */
+  int32_t time_kind;       /* DGC_TIME_*                                                     */
+  int32_t dtype;           /* DGC_DTYPE_F32                                                  */
+  int32_t F, S, H;         /* input dim, structure-encoder output dim, hidden dim.  S and H
+                              multiples of 32, at most 256; F at most 512                    */
+  int32_t act_hidden;      /* activation between stacked GCN layers                          */
+  int32_t act_out;         /* activation after the last GCN layer                            */
+  int32_t gather_mode;     /* DGC_GATHER_*                                                   */
+  int32_t validate_level;  /* 0: O(chunks) checks; 1: also O(nnz) checks of the CSR contract */
+  int32_t rows_per_group;  /* work list: rows per group (0 = default 16, at most 32)         */
+  int32_t long_nnz;        /* work list: rows longer than this are split (0 = default 1024)  */
+  int32_t part_nnz;        /* work list: non-zeros per part of a split row (0 = default 512) */
+} dgc_layer_desc_t;
+
+/* Build a layer for a fixed graph and a fixed set of chunks (the paper partitions once per
+ * training job, Section 7.5).  Validates, runs chunk-fusion packing on the device (Section
+ * 5.1.1: segment offsets, de-duplicated halo lists, local column ids, the row-group work
+ * list, per-row degree scaling), allocates the workspace and zero-initialised parameters.
+ *  desc, graph, chunks: host.  chunks must be non-empty, inside the graph and pairwise
+ *  disjoint in (vertex, snapshot) space, else DGC_ERR_BAD_CHUNK.
+ *  *out receives the layer (NULL on failure).  Synchronises `stream`. */
+dgc_status_t dgc_layer_create(const dgc_layer_desc_t* desc, const dgc_graph_t* graph,
+                              const dgc_chunk_t* chunks, int32_t n_chunks, void* stream,
+                              dgc_layer_t** out);
+
+/* Release the layer, its workspace and parameters.  NULL is accepted. */
+dgc_status_t dgc_layer_destroy(dgc_layer_t* layer);
+
+/* Parameters, fp32, (out, in) row-major as in the recurrent units Section 6 names:
+ *  "gcn0.weight" [S,F]  "gcn0.bias" [S]   "gcn1.weight" [S,S]  "gcn1.bias" [S]  (2 layers)
+ *  "rnn.weight_ih" [gH,S]  "rnn.weight_hh" [gH,H]  "rnn.bias_ih" [gH]  "rnn.bias_hh" [gH]
+ *  g = 3 (GRU, gate order r,z,n) or 4 (LSTM, gate order i,f,g,o).
+ * host_src / host_dst: host, numel elements; numel must equal the parameter's size. */
+dgc_status_t dgc_layer_set_param(dgc_layer_t* layer, const char* name, const float* host_src,
+                                 int64_t numel);
+dgc_status_t dgc_layer_get_param(dgc_layer_t* layer, const char* name, float* host_dst,
+                                 int64_t numel);
+
+/* Forward pass of the whole layer over the fused batch.
+ *  X  device [T,N,ldx]: input features x_{i,t} (Section 2.1).
+ *  C  device [T,N,ldc]: cache of stale input embeddings, read for every neighbour outside the
+ *     row's chunk vertex range (Section 5.2); may alias X (then chunking is invisible).
+ *  C1 device [T,N,ldc1]: cache of stale inputs of the second GCN layer; NULL unless
+ *     n_struct_layers = 2.
+ *  H0 device [n_state * V, H], V = sum of chunk vertex counts, chunk k's rows starting at the
+ *     sum of earlier chunks' vertex counts: state entering each chunk's first snapshot; for
+ *     LSTM n_state = 2, hidden states first, then cell states.  NULL = zeros.
+ *  reset_mask device uint8 [T,N] or NULL: a non-zero byte at (t,i) zeroes the state entering
+ *     step t of vertex i (Section 5.1.2).
+ *  Y  device [T,N,ldy]: output h_t (or the structure encoder's output if time_kind = NONE);
+ *     only rows covered by a chunk are written.
+ *  HN device, same shape as H0, or NULL: state after each chunk's last snapshot.
+ * X, C, C1, H0, reset_mask must not overlap Y or HN. */
+dgc_status_t dgc_layer_forward(dgc_layer_t* layer, const float* X, int64_t ldx, const float* C,
+                               int64_t ldc, const float* C1, int64_t ldc1, const float* H0,
+                               const uint8_t* reset_mask, float* Y, int64_t ldy, float* HN,
+                               void* stream);
+
+/* Backward pass (gradient of a loss w.r.t. parameters and optionally inputs).  Not built yet:
+ * returns DGC_ERR_UNSUPPORTED (DGC_ERR_STATE if no forward has run). */
+dgc_status_t dgc_layer_backward(dgc_layer_t* layer, const float* dY, int64_t lddy, float* dX,
+                                int64_t lddx, void* stream);
+
+/* Steps of the path on their own (for measurement and element-wise checks).
+ * dgc_layer_aggregate: the normalised neighbour aggregation of the first GCN layer,
+ *   M[row] = sum_j (d_i d_j)^(-1/2) src(t,j), d = stored row length in the full snapshot,
+ *   for every row of the fused batch in packed order (segment after segment, rows of a segment
+ *   in vertex order).  M device [rows, ldm], ldm >= F.
+ * dgc_layer_gather: the stale-cache gather of STAGED mode: halo device [halo_rows, ldh]
+ *   receives C[t, halo_idx[p], :] for every packed halo slot p.  Works in either mode. */
+dgc_status_t dgc_layer_aggregate(dgc_layer_t* layer, const float* X, int64_t ldx, const float* C,
+                                 int64_t ldc, float* M, int64_t ldm, void* stream);
+dgc_status_t dgc_layer_gather(dgc_layer_t* layer, const float* C, int64_t ldc, float* halo,
+                              int64_t ldh, void* stream);
+
+/* Read back a packing array (host_dst: host).  `what` and element types:
+ *  "seg_row_off" "seg_nnz_off" "halo_ptr"  int64 [n_segments+1]
+ *  "halo_idx" int32 [halo_ptr[n_segments]]   "col_local" int32 [seg_nnz_off[n_segments]]
+ *  "work_short" int32 [n][3] (segment, first local row, rows)
+ *  "work_long"  int32 [n][4] (segment, local row, part, parts)
+ *  "deg_inv_sqrt" fp32 [T*N]
+ * *needed_bytes (may be NULL) receives the array's size; data is copied only if
+ * capacity_bytes is large enough (else DGC_ERR_INVALID_ARG, with *needed_bytes set).
+ * Segments are ordered by chunk as given, then snapshot ascending. */
+dgc_status_t dgc_layer_packing(dgc_layer_t* layer, const char* what, void* host_dst,
+                               int64_t capacity_bytes, int64_t* needed_bytes);
+
+/* Text of the last error on this layer, or (layer = NULL) of the last failed create on the
+ * calling thread.  Never NULL; valid until the next call on the same layer / thread. */
+const char* dgc_last_error(const dgc_layer_t* layer);
+
+/* Library version, e.g. "dgc 0.1 gfx950". */
+const char* dgc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DGC_H_ */

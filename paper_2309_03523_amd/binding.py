@@ -1,0 +1,219 @@
+"""Thin ctypes binding of libdgc (include/dgc.h): argument marshalling only.
+
+Every step of the path runs inside the HIP library.  PyTorch supplies device memory and the
+stream.  There is no CPU fallback: if the library has not been built, or no GPU is present,
+the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes as ct
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdgc.so")
+
+TIME_KIND = {"none": 0, "gru": 1, "lstm": 2}
+ACT = {"none": 0, "relu": 1}
+GATHER = {"in_place": 0, "staged": 1}
+
+STATUS = {0: "DGC_OK", 1: "DGC_ERR_INVALID_ARG", 2: "DGC_ERR_BAD_GRAPH", 3: "DGC_ERR_BAD_CHUNK",
+          4: "DGC_ERR_UNSUPPORTED", 5: "DGC_ERR_OOM", 6: "DGC_ERR_DEVICE", 7: "DGC_ERR_STATE"}
+
+EXPORTS = ["dgc_layer_create", "dgc_layer_destroy", "dgc_layer_set_param", "dgc_layer_get_param",
+           "dgc_layer_forward", "dgc_layer_backward", "dgc_layer_aggregate", "dgc_layer_gather",
+           "dgc_layer_packing", "dgc_last_error", "dgc_version"]
+
+
+class DgcError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"{STATUS.get(code, code)}: {text}")
+        self.code = code
+
+
+class ChunkT(ct.Structure):
+    _fields_ = [("v_lo", ct.c_int64), ("v_hi", ct.c_int64), ("t_lo", ct.c_int32), ("t_hi", ct.c_int32)]
+
+
+class GraphT(ct.Structure):
+    _fields_ = [("T", ct.c_int32), ("N", ct.c_int64),
+                ("rowptr", ct.POINTER(ct.c_void_p)), ("colidx", ct.POINTER(ct.c_void_p))]
+
+
+class DescT(ct.Structure):
+    _fields_ = [(n, ct.c_int32) for n in
+                ("struct_kind", "n_struct_layers", "time_kind", "dtype", "F", "S", "H", "act_hidden",
+                 "act_out", "gather_mode", "validate_level", "rows_per_group", "long_nnz", "part_nnz")]
+
+
+_lib = None
+
+
+def load() -> ct.CDLL:
+    """Load libdgc.so (built in-tree by __graft_entry__.build()).  Raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = ct.CDLL(LIB_PATH)
+    vp, i32, i64 = ct.c_void_p, ct.c_int32, ct.c_int64
+    lib.dgc_layer_create.argtypes = [ct.POINTER(DescT), ct.POINTER(GraphT), ct.POINTER(ChunkT), i32, vp,
+                                     ct.POINTER(vp)]
+    lib.dgc_layer_destroy.argtypes = [vp]
+    lib.dgc_layer_set_param.argtypes = [vp, ct.c_char_p, vp, i64]
+    lib.dgc_layer_get_param.argtypes = [vp, ct.c_char_p, vp, i64]
+    lib.dgc_layer_forward.argtypes = [vp, vp, i64, vp, i64, vp, i64, vp, vp, vp, i64, vp, vp]
+    lib.dgc_layer_backward.argtypes = [vp, vp, i64, vp, i64, vp]
+    lib.dgc_layer_aggregate.argtypes = [vp, vp, i64, vp, i64, vp, i64, vp]
+    lib.dgc_layer_gather.argtypes = [vp, vp, i64, vp, i64, vp]
+    lib.dgc_layer_packing.argtypes = [vp, ct.c_char_p, vp, i64, ct.POINTER(i64)]
+    lib.dgc_last_error.argtypes = [vp]
+    lib.dgc_last_error.restype = ct.c_char_p
+    lib.dgc_version.restype = ct.c_char_p
+    for name in EXPORTS:
+        if name not in ("dgc_last_error", "dgc_version"):
+            getattr(lib, name).restype = ct.c_int
+    _lib = lib
+    return lib
+
+
+def version() -> str:
+    return load().dgc_version().decode()
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return ct.c_void_p(stream.cuda_stream)
+
+
+def _dev(t, name: str):
+    """Device pointer of a contiguous-in-the-last-dim CUDA tensor (or None)."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    return ct.c_void_p(t.data_ptr())
+
+
+def _ld(t, name: str) -> int:
+    if t is None:
+        return 0
+    if t.dim() != 3 or t.stride(2) != 1 or t.stride(0) != t.shape[1] * t.stride(1):
+        raise ValueError(f"{name} must be [T,N,ld] row-major (last dim contiguous, no gap between snapshots)")
+    return int(t.stride(1))
+
+
+_PACK_DTYPES = {"seg_row_off": np.int64, "seg_nnz_off": np.int64, "halo_ptr": np.int64,
+                "halo_idx": np.int32, "col_local": np.int32, "work_short": np.int32,
+                "work_long": np.int32, "deg_inv_sqrt": np.float32}
+
+
+class DgcLayer:
+    """dgc_layer_create / forward / backward / destroy with torch tensors as arguments.
+
+    rowptr, colidx: lists of T device tensors (int64 [N+1], int32 [nnz_t]).
+    chunks: array-like [n,4] of (v_lo, v_hi, t_lo, t_hi).
+    """
+
+    def __init__(self, rowptr, colidx, N: int, chunks, *, F: int, S: int, H: int, time_kind: str = "gru",
+                 n_struct_layers: int = 1, act_hidden: str = "relu", act_out: str = "none",
+                 gather_mode: str = "in_place", validate_level: int = 0, rows_per_group: int = 0,
+                 long_nnz: int = 0, part_nnz: int = 0, stream=None):
+        import torch
+        lib = load()
+        self._lib = lib
+        self._h = ct.c_void_p(None)
+        T = len(rowptr)
+        for r, c in zip(rowptr, colidx):
+            if r.dtype != torch.int64 or c.dtype != torch.int32 or not r.is_cuda or not c.is_cuda:
+                raise ValueError("rowptr must be int64 and colidx int32 device tensors")
+            if not r.is_contiguous() or not c.is_contiguous():
+                raise ValueError("CSR arrays must be contiguous")
+        self._keep = (list(rowptr), list(colidx))  # the layer borrows the CSR arrays for its life
+        rp = (ct.c_void_p * T)(*[r.data_ptr() for r in rowptr])
+        cj = (ct.c_void_p * T)(*[c.data_ptr() for c in colidx])
+        graph = GraphT(T, N, rp, cj)
+        ch = np.asarray(chunks, np.int64).reshape(-1, 4)
+        carr = (ChunkT * len(ch))(*[ChunkT(int(a), int(b), int(c), int(d)) for a, b, c, d in ch])
+        desc = DescT(0, n_struct_layers, TIME_KIND[time_kind], 0, F, S, H, ACT[act_hidden], ACT[act_out],
+                     GATHER[gather_mode], validate_level, rows_per_group, long_nnz, part_nnz)
+        rc = lib.dgc_layer_create(ct.byref(desc), ct.byref(graph), carr, len(ch), _stream_ptr(stream),
+                                  ct.byref(self._h))
+        if rc:
+            raise DgcError(rc, lib.dgc_last_error(None).decode())
+        self.T, self.N, self.F, self.S, self.H = T, N, F, S, H
+        self.time_kind, self.n_struct_layers = time_kind, n_struct_layers
+        self.chunks = ch
+        self.out_dim = H if time_kind != "none" else S
+
+    # -- lifetime
+    def destroy(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            self._lib.dgc_layer_destroy(self._h)
+            self._h = ct.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def _check(self, rc: int):
+        if rc:
+            raise DgcError(rc, self._lib.dgc_last_error(self._h).decode())
+
+    # -- parameters
+    def set_param(self, name: str, value: np.ndarray):
+        v = np.ascontiguousarray(value, np.float32)
+        self._check(self._lib.dgc_layer_set_param(self._h, name.encode(), v.ctypes.data_as(ct.c_void_p), v.size))
+
+    def set_params(self, params: dict):
+        for k, v in params.items():
+            self.set_param(k, v)
+
+    def get_param(self, name: str, shape) -> np.ndarray:
+        out = np.zeros(shape, np.float32)
+        self._check(self._lib.dgc_layer_get_param(self._h, name.encode(), out.ctypes.data_as(ct.c_void_p), out.size))
+        return out
+
+    # -- the path
+    def forward(self, X, C, Y, *, C1=None, H0=None, reset_mask=None, HN=None, stream=None):
+        self._check(self._lib.dgc_layer_forward(
+            self._h, _dev(X, "X"), _ld(X, "X"), _dev(C, "C"), _ld(C, "C"), _dev(C1, "C1"), _ld(C1, "C1"),
+            _dev(H0, "H0"), _dev(reset_mask, "reset_mask"), _dev(Y, "Y"), _ld(Y, "Y"), _dev(HN, "HN"),
+            _stream_ptr(stream)))
+        return Y
+
+    def backward(self, dY, dX=None, stream=None):
+        self._check(self._lib.dgc_layer_backward(self._h, _dev(dY, "dY"), _ld(dY, "dY"), _dev(dX, "dX"),
+                                                 _ld(dX, "dX"), _stream_ptr(stream)))
+
+    def aggregate(self, X, C, M, stream=None):
+        self._check(self._lib.dgc_layer_aggregate(self._h, _dev(X, "X"), _ld(X, "X"), _dev(C, "C"), _ld(C, "C"),
+                                                  _dev(M, "M"), int(M.stride(0)), _stream_ptr(stream)))
+        return M
+
+    def gather(self, C, halo, stream=None):
+        self._check(self._lib.dgc_layer_gather(self._h, _dev(C, "C"), _ld(C, "C"), _dev(halo, "halo"),
+                                               int(halo.stride(0)), _stream_ptr(stream)))
+        return halo
+
+    # -- inspection
+    def packing(self, what: str) -> np.ndarray:
+        need = ct.c_int64(0)
+        self._lib.dgc_layer_packing(self._h, what.encode(), None, 0, ct.byref(need))
+        dt = np.dtype(_PACK_DTYPES[what])
+        out = np.zeros(need.value // dt.itemsize, dt)
+        if out.size:
+            self._check(self._lib.dgc_layer_packing(self._h, what.encode(), out.ctypes.data_as(ct.c_void_p),
+                                                    out.nbytes, ct.byref(need)))
+        if what == "work_short":
+            out = out.reshape(-1, 3)
+        if what == "work_long":
+            out = out.reshape(-1, 4)
+        return out

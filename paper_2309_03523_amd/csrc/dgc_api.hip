@@ -1,0 +1,582 @@
+// C ABI of libdgc: argument checks, packing at create time, and the launch sequence of the
+// forward pass.  See include/dgc.h for the contract of every entry point.
+#include <algorithm>
+#include <cstring>
+#include <map>
+#include <new>
+
+#include "dgc_internal.h"
+
+using namespace dgc;
+
+namespace {
+
+thread_local std::string g_create_error = "";
+
+struct Param {
+  float* raw = nullptr;       // device, [n_out][n_in] or [n]
+  float4* packed = nullptr;   // device, fragment order (weights only)
+  int32_t n_out = 0, n_in = 0;  // n_in = 0: a bias vector of n_out elements
+  int64_t numel() const { return n_in ? (int64_t)n_out * n_in : n_out; }
+};
+
+}  // namespace
+
+struct dgc_layer {
+  dgc_layer_desc_t desc{};
+  int32_t T = 0;
+  int64_t N = 0;
+  int32_t n_chunks = 0;
+  int64_t nseg = 0, total_rows = 0, total_nnz = 0, total_halo = 0, total_state_rows = 0;
+  int64_t n_short = 0, n_long = 0, n_tiles = 0;
+  int32_t rows_per_group = 16, long_nnz = 1024, part_nnz = 512;
+  std::vector<dgc_chunk_t> chunks;
+  std::vector<Segment> segs_host;
+  std::vector<void*> allocs;          // everything hipMalloc'ed, freed in destroy
+  // device
+  const int64_t** d_rowptr = nullptr;
+  const int32_t** d_colidx = nullptr;
+  Segment* d_segs = nullptr;
+  ChunkInfo* d_chunks = nullptr;
+  DenseTile* d_tiles = nullptr;
+  float* d_dinv = nullptr;
+  int64_t* d_halo_ptr = nullptr;
+  int32_t* d_halo_idx = nullptr;
+  int32_t* d_col_local = nullptr;
+  int32_t* d_work_short = nullptr;
+  int32_t* d_work_long = nullptr;
+  float* d_M = nullptr; int64_t ldm = 0;         // aggregated rows of the current GCN layer
+  float* d_partial = nullptr;                    // split-row partial sums
+  float* d_halo = nullptr; int64_t ld_halo = 0;  // STAGED: gathered cache rows
+  float* d_Z1 = nullptr;                         // 2 layers: first layer's output [T,N,S]
+  std::map<std::string, Param> params;
+  bool forward_done = false;
+  std::string error;
+
+  GraphDev graph_dev() const { return GraphDev{T, N, d_rowptr, d_colidx}; }
+};
+
+namespace {
+
+dgc_status_t fail_create(dgc_status_t code, const std::string& msg) {
+  g_create_error = msg;
+  return code;
+}
+
+struct Failer {
+  dgc_layer* L;
+  dgc_status_t operator()(dgc_status_t code, const std::string& msg) const {
+    if (L) L->error = msg; else g_create_error = msg;
+    return code;
+  }
+};
+
+template <class T>
+hipError_t dev_alloc(dgc_layer* L, T** p, int64_t count) {
+  *p = nullptr;
+  if (count <= 0) count = 1;
+  void* v = nullptr;
+  hipError_t e = hipMalloc(&v, (size_t)count * sizeof(T));
+  if (e == hipSuccess) {
+    L->allocs.push_back(v);
+    *p = static_cast<T*>(v);
+  }
+  return e;
+}
+
+template <class T>
+void dev_free(dgc_layer* L, T* p) {
+  if (!p) return;
+  auto it = std::find(L->allocs.begin(), L->allocs.end(), static_cast<void*>(p));
+  if (it != L->allocs.end()) L->allocs.erase(it);
+  (void)hipFree(p);
+}
+
+void free_all(dgc_layer* L) {
+  for (void* p : L->allocs) (void)hipFree(p);
+  L->allocs.clear();
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+dgc_status_t check_desc(const dgc_layer_desc_t& d, std::string* msg) {
+  if (d.struct_kind != DGC_STRUCT_GCN) { *msg = "struct_kind: only DGC_STRUCT_GCN is built"; return DGC_ERR_UNSUPPORTED; }
+  if (d.dtype != DGC_DTYPE_F32) { *msg = "dtype: only DGC_DTYPE_F32 is built"; return DGC_ERR_UNSUPPORTED; }
+  if (d.n_struct_layers < 1 || d.n_struct_layers > 2) { *msg = "n_struct_layers must be 1 or 2"; return DGC_ERR_INVALID_ARG; }
+  if (d.time_kind < DGC_TIME_NONE || d.time_kind > DGC_TIME_LSTM) { *msg = "unknown time_kind"; return DGC_ERR_INVALID_ARG; }
+  if (d.F < 1 || d.F > 512) { *msg = "F must be in [1,512]"; return DGC_ERR_INVALID_ARG; }
+  if (d.S < 32 || d.S > 256 || d.S % 32) { *msg = "S must be a multiple of 32 in [32,256]"; return DGC_ERR_INVALID_ARG; }
+  if (d.time_kind != DGC_TIME_NONE && (d.H < 32 || d.H > 256 || d.H % 32)) {
+    *msg = "H must be a multiple of 32 in [32,256]"; return DGC_ERR_INVALID_ARG;
+  }
+  for (int32_t act : {d.act_hidden, d.act_out})
+    if (act != DGC_ACT_NONE && act != DGC_ACT_RELU) { *msg = "unknown activation"; return DGC_ERR_INVALID_ARG; }
+  if (d.gather_mode != DGC_GATHER_IN_PLACE && d.gather_mode != DGC_GATHER_STAGED) { *msg = "unknown gather_mode"; return DGC_ERR_INVALID_ARG; }
+  if (d.validate_level < 0 || d.validate_level > 1) { *msg = "validate_level must be 0 or 1"; return DGC_ERR_INVALID_ARG; }
+  if (d.rows_per_group < 0 || d.rows_per_group > 32) { *msg = "rows_per_group must be in [0,32]"; return DGC_ERR_INVALID_ARG; }
+  if (d.long_nnz < 0 || d.part_nnz < 0) { *msg = "long_nnz / part_nnz must be >= 0"; return DGC_ERR_INVALID_ARG; }
+  return DGC_OK;
+}
+
+// Chunks: non-empty, inside the graph, pairwise disjoint in (vertex, snapshot) space.
+dgc_status_t check_chunks(const dgc_chunk_t* c, int32_t n, int32_t T, int64_t N, std::string* msg) {
+  for (int32_t k = 0; k < n; ++k) {
+    if (c[k].v_lo < 0 || c[k].v_hi > N || c[k].v_lo >= c[k].v_hi || c[k].t_lo < 0 || c[k].t_hi > T ||
+        c[k].t_lo >= c[k].t_hi) {
+      *msg = "chunk " + std::to_string(k) + " is empty or outside the graph";
+      return DGC_ERR_BAD_CHUNK;
+    }
+    if (c[k].v_hi - c[k].v_lo > INT32_MAX) { *msg = "chunk too wide"; return DGC_ERR_BAD_CHUNK; }
+  }
+  // sweep over vertex starts; compare each chunk with the ones whose vertex range is still open
+  std::vector<int32_t> order(n);
+  for (int32_t k = 0; k < n; ++k) order[k] = k;
+  std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return c[a].v_lo < c[b].v_lo; });
+  std::vector<int32_t> open;
+  for (int32_t k : order) {
+    open.erase(std::remove_if(open.begin(), open.end(), [&](int32_t o) { return c[o].v_hi <= c[k].v_lo; }),
+               open.end());
+    for (int32_t o : open)
+      if (c[o].t_lo < c[k].t_hi && c[k].t_lo < c[o].t_hi) {
+        *msg = "chunks " + std::to_string(o) + " and " + std::to_string(k) + " overlap";
+        return DGC_ERR_BAD_CHUNK;
+      }
+    open.push_back(k);
+  }
+  return DGC_OK;
+}
+
+dgc_status_t add_param(dgc_layer* L, const std::string& name, int32_t n_out, int32_t n_in, hipStream_t st) {
+  Failer fail{L};
+  Param p;
+  p.n_out = n_out; p.n_in = n_in;
+  DGC_HIP_TRY(dev_alloc(L, &p.raw, p.numel()));
+  DGC_HIP_TRY(hipMemsetAsync(p.raw, 0, sizeof(float) * p.numel(), st));
+  if (n_in) {
+    const int64_t pe = packed_weight_elems(n_out, n_in);
+    float* pk = nullptr;
+    DGC_HIP_TRY(dev_alloc(L, &pk, pe));
+    DGC_HIP_TRY(hipMemsetAsync(pk, 0, sizeof(float) * pe, st));
+    p.packed = reinterpret_cast<float4*>(pk);
+  }
+  L->params[name] = p;
+  return DGC_OK;
+}
+
+dgc_status_t build_layer(dgc_layer* L, const dgc_graph_t* graph, hipStream_t st) {
+  Failer fail{L};
+  const dgc_layer_desc_t& d = L->desc;
+  const int32_t T = L->T;
+  const int64_t N = L->N;
+
+  // graph pointer tables
+  DGC_HIP_TRY(dev_alloc(L, &L->d_rowptr, T));
+  DGC_HIP_TRY(dev_alloc(L, &L->d_colidx, T));
+  DGC_HIP_TRY(hipMemcpyAsync(L->d_rowptr, graph->rowptr, sizeof(void*) * T, hipMemcpyHostToDevice, st));
+  DGC_HIP_TRY(hipMemcpyAsync(L->d_colidx, graph->colidx, sizeof(void*) * T, hipMemcpyHostToDevice, st));
+  const GraphDev g = L->graph_dev();
+
+  int32_t* d_flags = nullptr;
+  DGC_HIP_TRY(dev_alloc(L, &d_flags, 4));
+  DGC_HIP_TRY(hipMemsetAsync(d_flags, 0, sizeof(int32_t) * 4, st));
+  launch_validate_rowptr(g, d_flags, st);
+  int32_t flags[4] = {0, 0, 0, 0};
+  DGC_HIP_TRY(hipMemcpyAsync(flags, d_flags, sizeof(flags), hipMemcpyDeviceToHost, st));
+  DGC_HIP_TRY(hipStreamSynchronize(st));
+  if (flags[0]) return fail(DGC_ERR_BAD_GRAPH, "rowptr does not start at 0 or decreases");
+  if (d.validate_level >= 1) {
+    launch_validate_graph(g, d_flags, st);
+    DGC_HIP_TRY(hipMemcpyAsync(flags, d_flags, sizeof(flags), hipMemcpyDeviceToHost, st));
+    DGC_HIP_TRY(hipStreamSynchronize(st));
+    if (flags[0]) return fail(DGC_ERR_BAD_GRAPH, "rowptr does not start at 0 or decreases");
+    if (flags[1]) return fail(DGC_ERR_BAD_GRAPH, "a column index is out of range, unsorted or duplicated");
+    if (flags[2]) return fail(DGC_ERR_BAD_GRAPH, "a vertex has no stored self-loop");
+    if (flags[3]) return fail(DGC_ERR_BAD_GRAPH, "the adjacency is not symmetric");
+  }
+
+  // segments: (chunk as given, snapshot ascending)
+  std::vector<Segment>& segs = L->segs_host;
+  std::vector<ChunkInfo> cinfo(L->n_chunks);
+  int64_t row_off = 0, state_off = 0;
+  for (int32_t k = 0; k < L->n_chunks; ++k) {
+    const dgc_chunk_t& c = L->chunks[k];
+    cinfo[k] = ChunkInfo{c.v_lo, c.v_hi - c.v_lo, row_off, state_off, c.t_lo, c.t_hi - c.t_lo};
+    for (int32_t t = c.t_lo; t < c.t_hi; ++t) {
+      Segment s{};
+      s.row_off = row_off; s.v_lo = c.v_lo; s.v_hi = c.v_hi; s.t = t; s.chunk = k;
+      segs.push_back(s);
+      row_off += c.v_hi - c.v_lo;
+    }
+    state_off += c.v_hi - c.v_lo;
+  }
+  L->nseg = (int64_t)segs.size();
+  L->total_rows = row_off;
+  L->total_state_rows = state_off;
+  if (L->nseg > INT32_MAX) return fail(DGC_ERR_UNSUPPORTED, "too many segments");
+  DGC_HIP_TRY(dev_alloc(L, &L->d_segs, L->nseg));
+  DGC_HIP_TRY(hipMemcpyAsync(L->d_segs, segs.data(), sizeof(Segment) * L->nseg, hipMemcpyHostToDevice, st));
+  launch_segment_bounds(g, L->d_segs, L->nseg, st);
+  DGC_HIP_TRY(hipMemcpyAsync(segs.data(), L->d_segs, sizeof(Segment) * L->nseg, hipMemcpyDeviceToHost, st));
+  DGC_HIP_TRY(hipStreamSynchronize(st));
+  int64_t nnz_off = 0;
+  for (Segment& s : segs) {
+    const int64_t nnz = s.nnz_off;  // the kernel left the count here
+    if (nnz < 0) return fail(DGC_ERR_BAD_GRAPH, "negative segment size");
+    s.nnz_off = nnz_off;
+    nnz_off += nnz;
+  }
+  L->total_nnz = nnz_off;
+  DGC_HIP_TRY(hipMemcpyAsync(L->d_segs, segs.data(), sizeof(Segment) * L->nseg, hipMemcpyHostToDevice, st));
+  DGC_HIP_TRY(dev_alloc(L, &L->d_chunks, L->n_chunks));
+  DGC_HIP_TRY(hipMemcpyAsync(L->d_chunks, cinfo.data(), sizeof(ChunkInfo) * L->n_chunks, hipMemcpyHostToDevice, st));
+
+  // degree scaling
+  DGC_HIP_TRY(dev_alloc(L, &L->d_dinv, (int64_t)T * N));
+  launch_deg_inv_sqrt(g, L->d_dinv, st);
+
+  // halo lists: bitmap per segment -> ranks -> ids -> local columns
+  const int64_t wps = (N + 31) / 32;
+  const int64_t n_words = L->nseg * wps;
+  uint32_t* d_bitmap = nullptr;
+  int64_t *d_rank = nullptr, *d_tmp = nullptr, *d_total = nullptr;
+  DGC_HIP_TRY(dev_alloc(L, &d_bitmap, n_words));
+  DGC_HIP_TRY(dev_alloc(L, &d_rank, n_words));
+  DGC_HIP_TRY(dev_alloc(L, &d_tmp, std::max(scan_tmp_elems(n_words), scan_tmp_elems(L->total_rows))));
+  DGC_HIP_TRY(dev_alloc(L, &d_total, 1));
+  DGC_HIP_TRY(hipMemsetAsync(d_bitmap, 0, sizeof(uint32_t) * std::max<int64_t>(n_words, 1), st));
+  launch_mark_halo(g, L->d_segs, L->nseg, L->total_nnz, wps, d_bitmap, d_flags, st);
+  launch_popcount_words(d_bitmap, n_words, d_rank, st);
+  launch_exclusive_scan(d_rank, n_words, d_tmp, d_total, st);
+  DGC_HIP_TRY(hipMemcpyAsync(&L->total_halo, d_total, sizeof(int64_t), hipMemcpyDeviceToHost, st));
+  DGC_HIP_TRY(hipMemcpyAsync(flags, d_flags, sizeof(flags), hipMemcpyDeviceToHost, st));
+  DGC_HIP_TRY(hipStreamSynchronize(st));
+  if (flags[1]) return fail(DGC_ERR_BAD_GRAPH, "a column index is out of range");
+  DGC_HIP_TRY(dev_alloc(L, &L->d_halo_ptr, L->nseg + 1));
+  DGC_HIP_TRY(dev_alloc(L, &L->d_halo_idx, L->total_halo));
+  DGC_HIP_TRY(dev_alloc(L, &L->d_col_local, L->total_nnz));
+  launch_seg_halo_off(d_rank, L->nseg, wps, n_words, d_total, L->d_segs, L->d_halo_ptr, st);
+  launch_fill_halo(d_bitmap, d_rank, L->nseg, wps, L->d_halo_idx, st);
+  launch_col_local(g, L->d_segs, L->nseg, L->total_nnz, wps, d_bitmap, d_rank, L->d_col_local, st);
+  DGC_HIP_TRY(hipMemcpyAsync(segs.data(), L->d_segs, sizeof(Segment) * L->nseg, hipMemcpyDeviceToHost, st));
+
+  // work list: row groups (host arithmetic on the chunk table) and split rows (device)
+  {
+    std::vector<int32_t> ws;
+    const int32_t R = L->rows_per_group;
+    for (int64_t s = 0; s < L->nseg; ++s) {
+      const int64_t rows = segs[s].v_hi - segs[s].v_lo;
+      for (int64_t r = 0; r < rows; r += R) {
+        ws.push_back((int32_t)s);
+        ws.push_back((int32_t)r);
+        ws.push_back((int32_t)std::min<int64_t>(R, rows - r));
+      }
+    }
+    L->n_short = (int64_t)ws.size() / 3;
+    DGC_HIP_TRY(dev_alloc(L, &L->d_work_short, (int64_t)ws.size()));
+    DGC_HIP_TRY(hipMemcpyAsync(L->d_work_short, ws.data(), sizeof(int32_t) * ws.size(), hipMemcpyHostToDevice, st));
+    DGC_HIP_TRY(hipStreamSynchronize(st));  // ws goes out of scope
+  }
+  int64_t* d_cnt = nullptr;
+  DGC_HIP_TRY(dev_alloc(L, &d_cnt, L->total_rows));
+  launch_long_count(g, L->d_segs, L->nseg, L->total_rows, L->long_nnz, L->part_nnz, d_cnt, st);
+  launch_exclusive_scan(d_cnt, L->total_rows, d_tmp, d_total, st);
+  DGC_HIP_TRY(hipMemcpyAsync(&L->n_long, d_total, sizeof(int64_t), hipMemcpyDeviceToHost, st));
+  DGC_HIP_TRY(hipStreamSynchronize(st));
+  DGC_HIP_TRY(dev_alloc(L, &L->d_work_long, 4 * L->n_long));
+  launch_long_fill(g, L->d_segs, L->nseg, L->total_rows, L->long_nnz, L->part_nnz, d_cnt, L->d_work_long, st);
+
+  // dense tiles: 64 consecutive vertices of a chunk
+  {
+    std::vector<DenseTile> tiles;
+    for (int32_t k = 0; k < L->n_chunks; ++k)
+      for (int64_t v0 = 0; v0 < cinfo[k].nv; v0 += kTileRows)
+        tiles.push_back(DenseTile{k, (int32_t)v0, (int32_t)std::min<int64_t>(kTileRows, cinfo[k].nv - v0), 0});
+    L->n_tiles = (int64_t)tiles.size();
+    DGC_HIP_TRY(dev_alloc(L, &L->d_tiles, L->n_tiles));
+    DGC_HIP_TRY(hipMemcpyAsync(L->d_tiles, tiles.data(), sizeof(DenseTile) * tiles.size(), hipMemcpyHostToDevice, st));
+    DGC_HIP_TRY(hipStreamSynchronize(st));
+  }
+
+  // workspace
+  const int32_t Fmax = std::max(d.F, d.n_struct_layers == 2 ? d.S : 0);
+  L->ldm = (Fmax + 3) / 4 * 4;
+  DGC_HIP_TRY(dev_alloc(L, &L->d_M, L->total_rows * L->ldm));
+  DGC_HIP_TRY(dev_alloc(L, &L->d_partial, L->n_long * L->ldm));
+  if (d.gather_mode == DGC_GATHER_STAGED) {
+    L->ld_halo = L->ldm;
+    DGC_HIP_TRY(dev_alloc(L, &L->d_halo, L->total_halo * L->ld_halo));
+  }
+  if (d.n_struct_layers == 2) DGC_HIP_TRY(dev_alloc(L, &L->d_Z1, (int64_t)T * N * d.S));
+
+  // parameters
+  dgc_status_t rc;
+  if ((rc = add_param(L, "gcn0.weight", d.S, d.F, st)) != DGC_OK) return rc;
+  if ((rc = add_param(L, "gcn0.bias", d.S, 0, st)) != DGC_OK) return rc;
+  if (d.n_struct_layers == 2) {
+    if ((rc = add_param(L, "gcn1.weight", d.S, d.S, st)) != DGC_OK) return rc;
+    if ((rc = add_param(L, "gcn1.bias", d.S, 0, st)) != DGC_OK) return rc;
+  }
+  if (d.time_kind != DGC_TIME_NONE) {
+    const int32_t gH = (d.time_kind == DGC_TIME_LSTM ? 4 : 3) * d.H;
+    if ((rc = add_param(L, "rnn.weight_ih", gH, d.S, st)) != DGC_OK) return rc;
+    if ((rc = add_param(L, "rnn.weight_hh", gH, d.H, st)) != DGC_OK) return rc;
+    if ((rc = add_param(L, "rnn.bias_ih", gH, 0, st)) != DGC_OK) return rc;
+    if ((rc = add_param(L, "rnn.bias_hh", gH, 0, st)) != DGC_OK) return rc;
+  }
+  DGC_HIP_TRY(hipStreamSynchronize(st));
+  DGC_HIP_TRY(hipGetLastError());
+  // packing temporaries
+  dev_free(L, d_bitmap); dev_free(L, d_rank); dev_free(L, d_tmp); dev_free(L, d_total);
+  dev_free(L, d_cnt); dev_free(L, d_flags);
+  return DGC_OK;
+}
+
+dgc_status_t check_tensor(const Failer& fail, const char* name, const void* p, int64_t ld, int64_t min_ld,
+                          bool required) {
+  if (!p) return required ? fail(DGC_ERR_INVALID_ARG, std::string(name) + " is NULL") : DGC_OK;
+  if (!aligned16(p)) return fail(DGC_ERR_INVALID_ARG, std::string(name) + " is not 16-byte aligned");
+  if (ld < min_ld || ld % 4) return fail(DGC_ERR_INVALID_ARG, std::string(name) + ": pitch too small or not a multiple of 4");
+  return DGC_OK;
+}
+
+SpmmArgs spmm_args(dgc_layer* L, const float* fresh, int64_t ld_fresh, const float* stale, int64_t ld_stale,
+                   int32_t F, float* M, int64_t ldm) {
+  SpmmArgs a{};
+  a.g = L->graph_dev();
+  a.segs = L->d_segs;
+  a.work_short = L->d_work_short; a.n_short = L->n_short;
+  a.work_long = L->d_work_long; a.n_long = L->n_long;
+  a.dinv = L->d_dinv;
+  a.fresh = fresh; a.ld_fresh = ld_fresh;
+  a.stale = stale; a.ld_stale = ld_stale;
+  a.halo = nullptr; a.ld_halo = 0; a.col_local = nullptr;
+  a.F = F;
+  a.long_nnz = L->long_nnz; a.part_nnz = L->part_nnz;
+  a.partial = L->d_partial;
+  a.M = M; a.ldm = ldm;
+  return a;
+}
+
+// aggregation of one GCN layer, with or without the staged gather
+void run_aggregate(dgc_layer* L, const float* fresh, int64_t ld_fresh, const float* stale, int64_t ld_stale,
+                   int32_t F, float* M, int64_t ldm, hipStream_t st) {
+  SpmmArgs a = spmm_args(L, fresh, ld_fresh, stale, ld_stale, F, M, ldm);
+  if (L->desc.gather_mode == DGC_GATHER_STAGED) {
+    launch_gather(L->d_segs, L->nseg, L->d_halo_idx, L->d_halo_ptr, L->total_halo, L->N, stale, ld_stale, F,
+                  L->d_halo, L->ld_halo, st);
+    a.halo = L->d_halo; a.ld_halo = L->ld_halo; a.col_local = L->d_col_local;
+  }
+  launch_spmm(a, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* dgc_version(void) { return "dgc 0.1 gfx950"; }
+
+const char* dgc_last_error(const dgc_layer_t* layer) {
+  return layer ? layer->error.c_str() : g_create_error.c_str();
+}
+
+dgc_status_t dgc_layer_create(const dgc_layer_desc_t* desc, const dgc_graph_t* graph, const dgc_chunk_t* chunks,
+                              int32_t n_chunks, void* stream, dgc_layer_t** out) {
+  if (out) *out = nullptr;
+  if (!desc || !graph || !chunks || !out) return fail_create(DGC_ERR_INVALID_ARG, "NULL argument");
+  if (n_chunks < 1) return fail_create(DGC_ERR_INVALID_ARG, "n_chunks must be >= 1");
+  if (graph->T < 1 || graph->N < 1 || !graph->rowptr || !graph->colidx)
+    return fail_create(DGC_ERR_INVALID_ARG, "graph: T, N must be >= 1 and the pointer tables non-NULL");
+  if (graph->N > INT32_MAX) return fail_create(DGC_ERR_UNSUPPORTED, "N must fit in int32 (column ids are int32)");
+  for (int32_t t = 0; t < graph->T; ++t)
+    if (!graph->rowptr[t] || !graph->colidx[t]) return fail_create(DGC_ERR_INVALID_ARG, "graph: NULL snapshot pointer");
+  std::string msg;
+  dgc_status_t rc = check_desc(*desc, &msg);
+  if (rc != DGC_OK) return fail_create(rc, msg);
+  rc = check_chunks(chunks, n_chunks, graph->T, graph->N, &msg);
+  if (rc != DGC_OK) return fail_create(rc, msg);
+
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) != hipSuccess || n_dev < 1) {
+    (void)hipGetLastError();
+    return fail_create(DGC_ERR_DEVICE, "no HIP device");
+  }
+  dgc_layer* L = new (std::nothrow) dgc_layer();
+  if (!L) return fail_create(DGC_ERR_OOM, "host allocation failed");
+  L->desc = *desc;
+  L->T = graph->T; L->N = graph->N; L->n_chunks = n_chunks;
+  L->chunks.assign(chunks, chunks + n_chunks);
+  if (desc->rows_per_group) L->rows_per_group = desc->rows_per_group;
+  if (desc->long_nnz) L->long_nnz = desc->long_nnz;
+  if (desc->part_nnz) L->part_nnz = desc->part_nnz;
+  rc = build_layer(L, graph, static_cast<hipStream_t>(stream));
+  if (rc != DGC_OK) {
+    g_create_error = L->error;
+    if (rc == DGC_ERR_DEVICE && L->error.find("out of memory") != std::string::npos) rc = DGC_ERR_OOM;
+    (void)hipGetLastError();
+    free_all(L);
+    delete L;
+    return rc;
+  }
+  *out = L;
+  return DGC_OK;
+}
+
+dgc_status_t dgc_layer_destroy(dgc_layer_t* L) {
+  if (!L) return DGC_OK;
+  (void)hipDeviceSynchronize();
+  free_all(L);
+  delete L;
+  return DGC_OK;
+}
+
+dgc_status_t dgc_layer_set_param(dgc_layer_t* L, const char* name, const float* host_src, int64_t numel) {
+  if (!L) return DGC_ERR_INVALID_ARG;
+  Failer fail{L};
+  if (!name || !host_src) return fail(DGC_ERR_INVALID_ARG, "NULL argument");
+  auto it = L->params.find(name);
+  if (it == L->params.end()) return fail(DGC_ERR_INVALID_ARG, std::string("unknown parameter ") + name);
+  Param& p = it->second;
+  if (numel != p.numel()) return fail(DGC_ERR_INVALID_ARG, std::string(name) + ": wrong element count");
+  DGC_HIP_TRY(hipMemcpy(p.raw, host_src, sizeof(float) * numel, hipMemcpyHostToDevice));
+  if (p.packed) {
+    launch_pack_weight(p.raw, p.n_out, p.n_in, p.packed, nullptr);
+    DGC_HIP_TRY(hipDeviceSynchronize());
+  }
+  return DGC_OK;
+}
+
+dgc_status_t dgc_layer_get_param(dgc_layer_t* L, const char* name, float* host_dst, int64_t numel) {
+  if (!L) return DGC_ERR_INVALID_ARG;
+  Failer fail{L};
+  if (!name || !host_dst) return fail(DGC_ERR_INVALID_ARG, "NULL argument");
+  auto it = L->params.find(name);
+  if (it == L->params.end()) return fail(DGC_ERR_INVALID_ARG, std::string("unknown parameter ") + name);
+  if (numel != it->second.numel()) return fail(DGC_ERR_INVALID_ARG, std::string(name) + ": wrong element count");
+  DGC_HIP_TRY(hipMemcpy(host_dst, it->second.raw, sizeof(float) * numel, hipMemcpyDeviceToHost));
+  return DGC_OK;
+}
+
+dgc_status_t dgc_layer_aggregate(dgc_layer_t* L, const float* X, int64_t ldx, const float* C, int64_t ldc,
+                                 float* M, int64_t ldm, void* stream) {
+  if (!L) return DGC_ERR_INVALID_ARG;
+  Failer fail{L};
+  dgc_status_t rc;
+  if ((rc = check_tensor(fail, "X", X, ldx, L->desc.F, true)) != DGC_OK) return rc;
+  if ((rc = check_tensor(fail, "C", C, ldc, L->desc.F, true)) != DGC_OK) return rc;
+  if ((rc = check_tensor(fail, "M", M, ldm, L->desc.F, true)) != DGC_OK) return rc;
+  // the split-row scratch and the staged halo buffer are sized for pitch round_up(F,4)
+  if (ldm > L->ldm) return fail(DGC_ERR_INVALID_ARG, "M: pitch must not exceed round_up(F,4)");
+  run_aggregate(L, X, ldx, C, ldc, L->desc.F, M, ldm, static_cast<hipStream_t>(stream));
+  DGC_HIP_TRY(hipGetLastError());
+  return DGC_OK;
+}
+
+dgc_status_t dgc_layer_gather(dgc_layer_t* L, const float* C, int64_t ldc, float* halo, int64_t ldh, void* stream) {
+  if (!L) return DGC_ERR_INVALID_ARG;
+  Failer fail{L};
+  dgc_status_t rc;
+  if ((rc = check_tensor(fail, "C", C, ldc, L->desc.F, true)) != DGC_OK) return rc;
+  if ((rc = check_tensor(fail, "halo", halo, ldh, L->desc.F, true)) != DGC_OK) return rc;
+  launch_gather(L->d_segs, L->nseg, L->d_halo_idx, L->d_halo_ptr, L->total_halo, L->N, C, ldc, L->desc.F, halo, ldh,
+                static_cast<hipStream_t>(stream));
+  DGC_HIP_TRY(hipGetLastError());
+  return DGC_OK;
+}
+
+dgc_status_t dgc_layer_forward(dgc_layer_t* L, const float* X, int64_t ldx, const float* C, int64_t ldc,
+                               const float* C1, int64_t ldc1, const float* H0, const uint8_t* reset_mask, float* Y,
+                               int64_t ldy, float* HN, void* stream) {
+  if (!L) return DGC_ERR_INVALID_ARG;
+  Failer fail{L};
+  const dgc_layer_desc_t& d = L->desc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int32_t out_dim = d.time_kind == DGC_TIME_NONE ? d.S : d.H;
+  dgc_status_t rc;
+  if ((rc = check_tensor(fail, "X", X, ldx, d.F, true)) != DGC_OK) return rc;
+  if ((rc = check_tensor(fail, "C", C, ldc, d.F, true)) != DGC_OK) return rc;
+  if ((rc = check_tensor(fail, "Y", Y, ldy, out_dim, true)) != DGC_OK) return rc;
+  if ((rc = check_tensor(fail, "C1", C1, ldc1, d.S, d.n_struct_layers == 2)) != DGC_OK) return rc;
+  if (H0 && !aligned16(H0)) return fail(DGC_ERR_INVALID_ARG, "H0 is not 16-byte aligned");
+  if (HN && !aligned16(HN)) return fail(DGC_ERR_INVALID_ARG, "HN is not 16-byte aligned");
+  if (d.time_kind == DGC_TIME_NONE && (H0 || HN || reset_mask))
+    return fail(DGC_ERR_INVALID_ARG, "H0 / HN / reset_mask need a time encoder");
+
+  DenseArgs da{};
+  da.tiles = L->d_tiles; da.n_tiles = L->n_tiles; da.chunks = L->d_chunks;
+  da.N = L->N; da.total_state_rows = L->total_state_rows;
+  da.M = L->d_M; da.ldm = L->ldm;
+  da.S = d.S; da.H = d.H;
+  std::string why;
+
+  run_aggregate(L, X, ldx, C, ldc, d.F, L->d_M, L->ldm, st);
+  const char* last = "gcn0";
+  if (d.n_struct_layers == 2) {
+    // first layer for every row of the batch -> Z1 [T,N,S]; then aggregate Z1 | C1
+    da.K0 = d.F; da.act = d.act_hidden; da.time_kind = DGC_TIME_NONE;
+    da.Wg = L->params["gcn0.weight"].packed; da.bg = L->params["gcn0.bias"].raw;
+    da.Y = L->d_Z1; da.ldy = d.S;
+    if (!launch_dense(da, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
+    run_aggregate(L, L->d_Z1, d.S, C1, ldc1, d.S, L->d_M, L->ldm, st);
+    last = "gcn1";
+  }
+  da.K0 = d.n_struct_layers == 2 ? d.S : d.F;
+  da.act = d.act_out;
+  da.time_kind = d.time_kind;
+  da.Wg = L->params[std::string(last) + ".weight"].packed;
+  da.bg = L->params[std::string(last) + ".bias"].raw;
+  if (d.time_kind != DGC_TIME_NONE) {
+    da.Wih = L->params["rnn.weight_ih"].packed; da.Whh = L->params["rnn.weight_hh"].packed;
+    da.bih = L->params["rnn.bias_ih"].raw; da.bhh = L->params["rnn.bias_hh"].raw;
+  }
+  da.H0 = H0; da.reset_mask = reset_mask; da.Y = Y; da.ldy = ldy; da.HN = HN;
+  if (!launch_dense(da, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
+  DGC_HIP_TRY(hipGetLastError());
+  L->forward_done = true;
+  return DGC_OK;
+}
+
+dgc_status_t dgc_layer_backward(dgc_layer_t* L, const float* dY, int64_t lddy, float* dX, int64_t lddx, void* stream) {
+  (void)dY; (void)lddy; (void)dX; (void)lddx; (void)stream;
+  if (!L) return DGC_ERR_INVALID_ARG;
+  Failer fail{L};
+  if (!L->forward_done) return fail(DGC_ERR_STATE, "backward before forward");
+  return fail(DGC_ERR_UNSUPPORTED, "backward is not built");
+}
+
+dgc_status_t dgc_layer_packing(dgc_layer_t* L, const char* what, void* host_dst, int64_t capacity_bytes,
+                               int64_t* needed_bytes) {
+  if (!L) return DGC_ERR_INVALID_ARG;
+  Failer fail{L};
+  if (!what) return fail(DGC_ERR_INVALID_ARG, "NULL argument");
+  const std::string w(what);
+  const void* src = nullptr;
+  int64_t bytes = 0;
+  std::vector<int64_t> host_i64;
+  if (w == "seg_row_off" || w == "seg_nnz_off") {
+    host_i64.resize(L->nseg + 1);
+    for (int64_t s = 0; s < L->nseg; ++s)
+      host_i64[s] = w == "seg_row_off" ? L->segs_host[s].row_off : L->segs_host[s].nnz_off;
+    host_i64[L->nseg] = w == "seg_row_off" ? L->total_rows : L->total_nnz;
+    bytes = sizeof(int64_t) * (L->nseg + 1);
+  } else if (w == "halo_ptr") { src = L->d_halo_ptr; bytes = sizeof(int64_t) * (L->nseg + 1);
+  } else if (w == "halo_idx") { src = L->d_halo_idx; bytes = sizeof(int32_t) * L->total_halo;
+  } else if (w == "col_local") { src = L->d_col_local; bytes = sizeof(int32_t) * L->total_nnz;
+  } else if (w == "work_short") { src = L->d_work_short; bytes = sizeof(int32_t) * 3 * L->n_short;
+  } else if (w == "work_long") { src = L->d_work_long; bytes = sizeof(int32_t) * 4 * L->n_long;
+  } else if (w == "deg_inv_sqrt") { src = L->d_dinv; bytes = sizeof(float) * (int64_t)L->T * L->N;
+  } else {
+    return fail(DGC_ERR_INVALID_ARG, "unknown packing array " + w);
+  }
+  if (needed_bytes) *needed_bytes = bytes;
+  if (!host_dst || capacity_bytes < bytes)
+    return fail(DGC_ERR_INVALID_ARG, "destination too small for " + w);
+  if (bytes == 0) return DGC_OK;
+  if (!host_i64.empty()) {
+    std::memcpy(host_dst, host_i64.data(), (size_t)bytes);
+  } else {
+    DGC_HIP_TRY(hipMemcpy(host_dst, src, (size_t)bytes, hipMemcpyDeviceToHost));
+  }
+  return DGC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,145 @@
+// Internal declarations shared by the HIP translation units of libdgc.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "dgc.h"
+
+namespace dgc {
+
+constexpr int kWave = 64;
+constexpr int kTileRows = 64;  // rows of one dense tile (two 32-row MFMA blocks)
+
+// One (chunk, snapshot) pair of the fused batch.
+struct Segment {
+  int64_t row_off;   // first packed row
+  int64_t nnz_off;   // first packed non-zero
+  int64_t e0;        // rowptr[t][v_lo]: first stored non-zero of the segment in snapshot t
+  int64_t halo_off;  // first packed halo slot
+  int64_t v_lo, v_hi;
+  int32_t t;
+  int32_t chunk;
+};
+
+// Per-chunk data used by the dense kernels.
+struct ChunkInfo {
+  int64_t v_lo;
+  int64_t nv;
+  int64_t row_off0;  // packed row of (first snapshot, v_lo); snapshot s adds s*nv
+  int64_t state_off; // first row of the chunk in H0 / HN
+  int32_t t_lo;
+  int32_t w;
+};
+
+// A tile of up to kTileRows consecutive vertices of one chunk; the dense kernel walks the
+// chunk's window for it.
+struct DenseTile {
+  int32_t chunk;
+  int32_t v0;     // first vertex, relative to the chunk's v_lo
+  int32_t nrows;
+  int32_t pad;
+};
+
+struct GraphDev {
+  int32_t T;
+  int64_t N;
+  const int64_t* const* rowptr;  // device array [T] of device pointers
+  const int32_t* const* colidx;
+};
+
+#define DGC_HIP_TRY(expr)                                             \
+  do {                                                                \
+    hipError_t e_ = (expr);                                           \
+    if (e_ != hipSuccess) {                                           \
+      return fail(DGC_ERR_DEVICE, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+    }                                                                 \
+  } while (0)
+
+// ---- packing (dgc_pack.hip)
+void launch_segment_bounds(const GraphDev& g, Segment* segs, int64_t nseg, hipStream_t st);
+void launch_deg_inv_sqrt(const GraphDev& g, float* dinv, hipStream_t st);
+void launch_mark_halo(const GraphDev& g, const Segment* segs, int64_t nseg, int64_t total_nnz,
+                      int64_t words_per_seg, uint32_t* bitmap, int32_t* flags /*[4]*/, hipStream_t st);
+void launch_validate_rowptr(const GraphDev& g, int32_t* flags /*[4]*/, hipStream_t st);
+// exclusive scan of `n` int64 counts (in place); total written to *total_dev (device int64).
+// tmp must hold ceil(n/2048)+2 int64.
+void launch_exclusive_scan(int64_t* data, int64_t n, int64_t* tmp, int64_t* total_dev, hipStream_t st);
+int64_t scan_tmp_elems(int64_t n);
+void launch_popcount_words(const uint32_t* bitmap, int64_t n_words, int64_t* counts, hipStream_t st);
+void launch_fill_halo(const uint32_t* bitmap, const int64_t* word_rank, int64_t nseg,
+                      int64_t words_per_seg, int32_t* halo_idx, hipStream_t st);
+void launch_seg_halo_off(const int64_t* word_rank, int64_t nseg, int64_t words_per_seg,
+                         int64_t total_words, const int64_t* total_dev, Segment* segs,
+                         int64_t* halo_ptr, hipStream_t st);
+void launch_col_local(const GraphDev& g, const Segment* segs, int64_t nseg, int64_t total_nnz,
+                      int64_t words_per_seg, const uint32_t* bitmap, const int64_t* word_rank,
+                      int32_t* col_local, hipStream_t st);
+void launch_long_count(const GraphDev& g, const Segment* segs, int64_t nseg, int64_t total_rows,
+                       int32_t long_nnz, int32_t part_nnz, int64_t* counts, hipStream_t st);
+void launch_long_fill(const GraphDev& g, const Segment* segs, int64_t nseg, int64_t total_rows,
+                      int32_t long_nnz, int32_t part_nnz, const int64_t* offs, int32_t* work_long,
+                      hipStream_t st);
+void launch_validate_graph(const GraphDev& g, int32_t* flags /*[4]*/, hipStream_t st);
+
+// ---- aggregation / gather (dgc_spmm.hip)
+struct SpmmArgs {
+  GraphDev g;
+  const Segment* segs;
+  const int32_t* work_short;  // [n_short][3]
+  int64_t n_short;
+  const int32_t* work_long;   // [n_long][4]
+  int64_t n_long;
+  const float* dinv;          // [T*N]
+  const float* fresh; int64_t ld_fresh;   // [T,N,ld]: rows inside the chunk range
+  const float* stale; int64_t ld_stale;   // [T,N,ld]: cache rows (IN_PLACE)
+  const float* halo; int64_t ld_halo;     // packed halo rows (STAGED) or nullptr
+  const int32_t* col_local;               // STAGED only
+  int32_t F;
+  int32_t long_nnz, part_nnz;
+  float* partial;             // [n_long][ldm] scratch for split rows
+  float* M; int64_t ldm;      // [rows, ldm]; columns F..ldm-1 are written as zero
+};
+void launch_spmm(const SpmmArgs& a, hipStream_t st);
+void launch_gather(const Segment* segs, int64_t nseg, const int32_t* halo_idx, const int64_t* halo_ptr,
+                   int64_t total_halo, int64_t N, const float* C, int64_t ldc, int32_t F, float* halo,
+                   int64_t ldh, hipStream_t st);
+
+// ---- dense part (dgc_dense.hip)
+// Weights are kept in "fragment order" for the 32x32x2 fp32 MFMA: for W [n_out][n_in]
+// (row-major), packed[(jb*nkb + kb)*64 + lane] is the float4
+//   W[jb*32 + lane%32][kb*8 + (lane/32)*4 + 0..3]   (zero beyond n_in),  nkb = ceil(n_in/8).
+void launch_pack_weight(const float* W, int32_t n_out, int32_t n_in, float4* packed, hipStream_t st);
+inline int64_t packed_weight_elems(int32_t n_out, int32_t n_in) {
+  return (int64_t)(n_out / 32) * ((n_in + 7) / 8) * 64 * 4;
+}
+
+struct DenseArgs {
+  const DenseTile* tiles;
+  int64_t n_tiles;
+  const ChunkInfo* chunks;
+  int64_t N;
+  int64_t total_state_rows;     // V = sum of chunk vertex counts
+  const float* M; int64_t ldm;  // packed aggregated rows
+  int32_t K0;                   // columns of M that are used (input dim of the GCN layer)
+  int32_t S, H;
+  int32_t act;                  // activation after the GCN transform
+  int32_t time_kind;
+  const float4* Wg;             // packed GCN weight [S][K0]
+  const float* bg;              // [S]
+  const float4* Wih;            // packed [gH][S]
+  const float4* Whh;            // packed [gH][H]
+  const float* bih; const float* bhh;
+  const float* H0;
+  const uint8_t* reset_mask;
+  float* Y; int64_t ldy;        // [T,N,ldy]
+  float* HN;
+};
+// returns false if the (S,H,K0) combination has no kernel
+bool launch_dense(const DenseArgs& a, hipStream_t st, std::string* why);
+size_t dense_lds_bytes(int32_t K0, int32_t S, int32_t H);
+
+}  // namespace dgc

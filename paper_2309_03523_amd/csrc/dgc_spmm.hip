@@ -1,0 +1,268 @@
+// Normalised neighbour aggregation of the GCN convolution (the structure encoder Section 6
+// names) over the fused batch, and the stale-cache gather (Section 5.2).
+//
+//   M[row of (t,i)] = d_i^-1/2 * sum_j d_j^-1/2 * src(t,j)
+//   src(t,j) = fresh[t,j] if j lies in the row's chunk vertex range, else the cache row.
+//
+// HBM/L2-bound work: one wavefront owns one work item (a group of consecutive rows, or one
+// part of a split row).  The 64 lanes span the feature dimension (1, 2 or 4 floats each), so
+// every neighbour row is one fully coalesced load; column indices and their degree scalings
+// are fetched 64 at a time, one per lane, and handed out with v_readlane so that the row
+// address is wave-uniform.  Eight neighbour rows are in flight per wave.
+#include "dgc_internal.h"
+
+namespace dgc {
+namespace {
+
+constexpr int kInflight = 8;
+
+template <int VEC> struct Vec;
+template <> struct Vec<1> { using T = float; };
+template <> struct Vec<2> { using T = float2; };
+template <> struct Vec<4> { using T = float4; };
+
+template <int VEC>
+__device__ __forceinline__ void vload(float (&v)[VEC], const float* p) {
+  if constexpr (VEC == 1) { v[0] = *p; }
+  if constexpr (VEC == 2) { const float2 t = *reinterpret_cast<const float2*>(p); v[0] = t.x; v[1] = t.y; }
+  if constexpr (VEC == 4) {
+    const float4 t = *reinterpret_cast<const float4*>(p);
+    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+  }
+}
+
+template <int VEC>
+__device__ __forceinline__ void vstore(float* p, const float (&v)[VEC]) {
+  if constexpr (VEC == 1) { *p = v[0]; }
+  if constexpr (VEC == 2) { *reinterpret_cast<float2*>(p) = make_float2(v[0], v[1]); }
+  if constexpr (VEC == 4) { *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]); }
+}
+
+__device__ __forceinline__ int64_t readlane64(int64_t v, int lane) {
+  const int lo = __builtin_amdgcn_readlane((int)(v & 0xffffffff), lane);
+  const int hi = __builtin_amdgcn_readlane((int)(v >> 32), lane);
+  return ((int64_t)hi << 32) | (uint32_t)lo;
+}
+
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// Per-work-item constants, all wave-uniform.
+struct RowCtx {
+  const int32_t* cj;        // colidx of the snapshot
+  const int32_t* cl;        // col_local of the segment, indexed by (e - e0)   (STAGED)
+  const float* dinv_t;
+  const float* fresh_t; int64_t ld_fresh;
+  const float* stale_t; int64_t ld_stale;   // IN_PLACE: cache snapshot; STAGED: segment's halo rows
+  int64_t v_lo, v_hi, e0;
+};
+
+// acc += sum over stored non-zeros e in [ea, eb) of dinv[col] * src row, features fi..fi+VEC-1.
+template <int VEC, bool STAGED>
+__device__ __forceinline__ void accumulate_edges(const RowCtx& c, int64_t ea, int64_t eb, int lane, int fi,
+                                                 bool active, float (&acc)[VEC]) {
+  for (int64_t eb0 = ea; eb0 < eb; eb0 += kWave) {
+    const int m = (int)((eb - eb0) < kWave ? (eb - eb0) : kWave);
+    int j = 0, loc = 0;
+    float wj = 0.f;
+    if (lane < m) {
+      j = c.cj[eb0 + lane];
+      wj = c.dinv_t[j];
+      if constexpr (STAGED) loc = c.cl[eb0 - c.e0 + lane];
+    }
+    for (int k = 0; k < m; k += kInflight) {
+      float v[kInflight][VEC];
+      float w[kInflight];
+#pragma unroll
+      for (int u = 0; u < kInflight; ++u) {
+        w[u] = 0.f;
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) v[u][q] = 0.f;
+        if (k + u < m) {  // wave-uniform
+          const int jj = __builtin_amdgcn_readlane(j, k + u);
+          w[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wj), k + u));
+          const float* src;
+          if constexpr (STAGED) {
+            const int ll = __builtin_amdgcn_readlane(loc, k + u);
+            const int64_t nv = c.v_hi - c.v_lo;
+            src = ll < nv ? c.fresh_t + (c.v_lo + ll) * c.ld_fresh : c.stale_t + (ll - nv) * c.ld_stale;
+          } else {
+            src = (jj >= c.v_lo && jj < c.v_hi) ? c.fresh_t + (int64_t)jj * c.ld_fresh
+                                                : c.stale_t + (int64_t)jj * c.ld_stale;
+          }
+          if (active) vload<VEC>(v[u], src + fi);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kInflight; ++u)
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) acc[q] = fmaf(w[u], v[u][q], acc[q]);
+    }
+  }
+}
+
+template <bool STAGED>
+__device__ __forceinline__ RowCtx make_ctx(const SpmmArgs& a, const Segment& sg) {
+  RowCtx c;
+  c.cj = a.g.colidx[sg.t];
+  c.cl = STAGED ? a.col_local + sg.nnz_off : nullptr;
+  c.dinv_t = a.dinv + (int64_t)sg.t * a.g.N;
+  c.fresh_t = a.fresh + (int64_t)sg.t * a.g.N * a.ld_fresh;
+  c.ld_fresh = a.ld_fresh;
+  if (STAGED) {
+    c.stale_t = a.halo + sg.halo_off * a.ld_halo;
+    c.ld_stale = a.ld_halo;
+  } else {
+    c.stale_t = a.stale + (int64_t)sg.t * a.g.N * a.ld_stale;
+    c.ld_stale = a.ld_stale;
+  }
+  c.v_lo = sg.v_lo; c.v_hi = sg.v_hi; c.e0 = sg.e0;
+  return c;
+}
+
+template <int VEC>
+__device__ __forceinline__ void store_row(float* out, int fi, int F, int64_t ldm, const float (&acc)[VEC], float scale) {
+  if (fi >= ldm) return;
+  float o[VEC];
+#pragma unroll
+  for (int q = 0; q < VEC; ++q) o[q] = (fi + q < F) ? acc[q] * scale : 0.f;
+  vstore<VEC>(out + fi, o);
+}
+
+// One wave per group of consecutive rows of a segment.  Rows longer than long_nnz are left to
+// the split-row kernels.
+template <int VEC, bool STAGED>
+__global__ __launch_bounds__(256) void k_spmm_short(SpmmArgs a) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t item = (int64_t)blockIdx.x * (256 / kWave) + (threadIdx.x / kWave);
+  if (item >= a.n_short) return;
+  const int seg = uniform(a.work_short[3 * item + 0]);
+  const int r0 = uniform(a.work_short[3 * item + 1]);
+  const int n = uniform(a.work_short[3 * item + 2]);
+  const Segment sg = a.segs[seg];
+  const RowCtx c = make_ctx<STAGED>(a, sg);
+  const int64_t* rp = a.g.rowptr[sg.t] + sg.v_lo + r0;
+  const int64_t my_rp = lane <= n ? rp[lane] : 0;
+  for (int r = 0; r < n; ++r) {
+    const int64_t ea = readlane64(my_rp, r), eb = readlane64(my_rp, r + 1);
+    if (eb - ea > a.long_nnz) continue;
+    const float di = c.dinv_t[sg.v_lo + r0 + r];
+    float* out = a.M + (sg.row_off + r0 + r) * a.ldm;
+    for (int f0 = 0; f0 < a.ldm; f0 += kWave * VEC) {
+      const int fi = f0 + lane * VEC;
+      float acc[VEC];
+#pragma unroll
+      for (int q = 0; q < VEC; ++q) acc[q] = 0.f;
+      accumulate_edges<VEC, STAGED>(c, ea, eb, lane, fi, fi < a.F, acc);
+      store_row<VEC>(out, fi, a.F, a.ldm, acc, di);
+    }
+  }
+}
+
+// One wave per part of a split row: unscaled partial sums.
+template <int VEC, bool STAGED>
+__global__ __launch_bounds__(256) void k_spmm_long(SpmmArgs a) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t item = (int64_t)blockIdx.x * (256 / kWave) + (threadIdx.x / kWave);
+  if (item >= a.n_long) return;
+  const int seg = uniform(a.work_long[4 * item + 0]);
+  const int row = uniform(a.work_long[4 * item + 1]);
+  const int part = uniform(a.work_long[4 * item + 2]);
+  const Segment sg = a.segs[seg];
+  const RowCtx c = make_ctx<STAGED>(a, sg);
+  const int64_t* rp = a.g.rowptr[sg.t] + sg.v_lo + row;
+  const int64_t ra = rp[0], rb = rp[1];
+  const int64_t ea = ra + (int64_t)part * a.part_nnz;
+  const int64_t eb = (ea + a.part_nnz < rb) ? ea + a.part_nnz : rb;
+  float* out = a.partial + item * a.ldm;
+  for (int f0 = 0; f0 < a.ldm; f0 += kWave * VEC) {
+    const int fi = f0 + lane * VEC;
+    float acc[VEC];
+#pragma unroll
+    for (int q = 0; q < VEC; ++q) acc[q] = 0.f;
+    accumulate_edges<VEC, STAGED>(c, ea, eb, lane, fi, fi < a.F, acc);
+    store_row<VEC>(out, fi, a.F, a.ldm, acc, 1.0f);
+  }
+}
+
+// Sum the parts of each split row in part order (fixed order: results are reproducible).
+template <int VEC>
+__global__ __launch_bounds__(256) void k_spmm_long_reduce(SpmmArgs a) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t item = (int64_t)blockIdx.x * (256 / kWave) + (threadIdx.x / kWave);
+  if (item >= a.n_long) return;
+  if (uniform(a.work_long[4 * item + 2]) != 0) return;
+  const int seg = uniform(a.work_long[4 * item + 0]);
+  const int row = uniform(a.work_long[4 * item + 1]);
+  const int parts = uniform(a.work_long[4 * item + 3]);
+  const Segment sg = a.segs[seg];
+  const float di = a.dinv[(int64_t)sg.t * a.g.N + sg.v_lo + row];
+  float* out = a.M + (sg.row_off + row) * a.ldm;
+  for (int f0 = 0; f0 < a.ldm; f0 += kWave * VEC) {
+    const int fi = f0 + lane * VEC;
+    if (fi >= a.ldm) continue;
+    float acc[VEC];
+#pragma unroll
+    for (int q = 0; q < VEC; ++q) acc[q] = 0.f;
+    for (int p = 0; p < parts; ++p) {
+      float v[VEC];
+      vload<VEC>(v, a.partial + (item + p) * a.ldm + fi);
+#pragma unroll
+      for (int q = 0; q < VEC; ++q) acc[q] += v[q];
+    }
+    store_row<VEC>(out, fi, a.F, a.ldm, acc, di);
+  }
+}
+
+template <int VEC>
+void launch_spmm_v(const SpmmArgs& a, hipStream_t st) {
+  const bool staged = a.halo != nullptr;
+  const unsigned gs = (unsigned)((a.n_short + 3) / 4), gl = (unsigned)((a.n_long + 3) / 4);
+  if (gs) {
+    if (staged) hipLaunchKernelGGL((k_spmm_short<VEC, true>), gs, 256, 0, st, a);
+    else hipLaunchKernelGGL((k_spmm_short<VEC, false>), gs, 256, 0, st, a);
+  }
+  if (gl) {
+    if (staged) hipLaunchKernelGGL((k_spmm_long<VEC, true>), gl, 256, 0, st, a);
+    else hipLaunchKernelGGL((k_spmm_long<VEC, false>), gl, 256, 0, st, a);
+    hipLaunchKernelGGL((k_spmm_long_reduce<VEC>), gl, 256, 0, st, a);
+  }
+}
+
+// halo[p] = C[t(p), halo_idx[p], :] for every packed halo slot p.  One thread per float4.
+__global__ __launch_bounds__(256) void k_gather(const Segment* segs, int64_t nseg, const int32_t* halo_idx,
+                                                const int64_t* halo_ptr, int64_t total_halo, int64_t N,
+                                                const float* C, int64_t ldc, int32_t f4, float* halo,
+                                                int64_t ldh) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t p = idx / f4;
+  if (p >= total_halo) return;
+  const int c = (int)(idx - p * f4);
+  int64_t lo = 0, hi = nseg - 1;  // largest s with halo_ptr[s] <= p
+  while (lo < hi) {
+    const int64_t mid = (lo + hi + 1) >> 1;
+    if (halo_ptr[mid] <= p) lo = mid; else hi = mid - 1;
+  }
+  const int64_t t = segs[lo].t;
+  const float4 v = *reinterpret_cast<const float4*>(C + (t * N + halo_idx[p]) * ldc + 4 * c);
+  *reinterpret_cast<float4*>(halo + p * ldh + 4 * c) = v;
+}
+
+}  // namespace
+
+void launch_spmm(const SpmmArgs& a, hipStream_t st) {
+  if (a.F <= 64) launch_spmm_v<1>(a, st);
+  else if (a.F <= 128) launch_spmm_v<2>(a, st);
+  else launch_spmm_v<4>(a, st);
+}
+
+void launch_gather(const Segment* segs, int64_t nseg, const int32_t* halo_idx, const int64_t* halo_ptr,
+                   int64_t total_halo, int64_t N, const float* C, int64_t ldc, int32_t F, float* halo,
+                   int64_t ldh, hipStream_t st) {
+  const int32_t f4 = (F + 3) / 4;
+  const int64_t n = total_halo * f4;
+  if (n > 0)
+    hipLaunchKernelGGL(k_gather, (unsigned)((n + 255) / 256), 256, 0, st, segs, nseg, halo_idx, halo_ptr,
+                       total_halo, N, C, ldc, f4, halo, ldh);
+}
+
+}  // namespace dgc

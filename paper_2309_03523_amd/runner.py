@@ -1,0 +1,66 @@
+"""Plumbing between a synthetic Workload (host NumPy arrays) and the HIP layer: upload with
+torch, create the layer, load parameters, run.  No arithmetic of the method lives here."""
+from __future__ import annotations
+
+from typing import Optional
+
+import numpy as np
+
+from .binding import DgcLayer
+
+
+class DeviceWorkload:
+    """Device copies of a Workload's graph and tensors plus a created layer."""
+
+    def __init__(self, wl, *, gather_mode: str = "in_place", validate_level: int = 0, act_hidden: str = "relu",
+                 act_out: str = "none", pitch: Optional[int] = None, **layer_kw):
+        import torch
+        dev = torch.device("cuda:0")
+        self.wl = wl
+        g = wl.graph
+        self.rowptr = [torch.from_numpy(s.rowptr).to(dev) for s in g.snaps]
+        self.colidx = [torch.from_numpy(s.col).to(dev) for s in g.snaps]
+        self.layer = DgcLayer(self.rowptr, self.colidx, g.N, wl.chunks, F=wl.F, S=wl.S, H=wl.H,
+                              time_kind=wl.time_kind, n_struct_layers=wl.n_struct_layers,
+                              act_hidden=act_hidden, act_out=act_out, gather_mode=gather_mode,
+                              validate_level=validate_level, **layer_kw)
+        self.layer.set_params(wl.params)
+
+        def up(a, ld=None):
+            """[T,N,F] -> device tensor with row pitch ld (a multiple of 4)."""
+            if a is None:
+                return None
+            T, N, F = a.shape
+            ld = ld or (F + 3) // 4 * 4
+            buf = torch.full((T, N, ld), float("nan"), dtype=torch.float32, device=dev)
+            buf[:, :, :F] = torch.from_numpy(a).to(dev)
+            return buf[:, :, :F] if ld != F else buf
+
+        self.X = up(wl.X, pitch)
+        self.C = up(wl.C, pitch)
+        self.C1 = up(wl.C1)
+        self.H0 = torch.from_numpy(wl.H0).to(dev) if wl.H0 is not None else None
+        self.Y = torch.full((g.T, g.N, self.layer.out_dim), float("nan"), dtype=torch.float32, device=dev)
+
+    def forward(self, *, reset_mask=None, want_state: bool = False, use_h0: bool = True, C=None, C1=None):
+        import torch
+        rm = None
+        if reset_mask is not None:
+            rm = torch.from_numpy(np.ascontiguousarray(reset_mask, np.uint8)).to(self.Y.device)
+        HN = None
+        if want_state and self.wl.time_kind != "none":
+            n_state = 2 if self.wl.time_kind == "lstm" else 1
+            tot = int((self.wl.chunks[:, 1] - self.wl.chunks[:, 0]).sum())
+            HN = torch.full((n_state * tot, self.wl.H), float("nan"), dtype=torch.float32, device=self.Y.device)
+        self.layer.forward(self.X, self.C if C is None else C, self.Y, C1=self.C1 if C1 is None else C1,
+                           H0=self.H0 if use_h0 else None, reset_mask=rm, HN=HN)
+        torch.cuda.synchronize()
+        return (self.Y, HN) if want_state else self.Y
+
+
+def run_forward(wl, **kw) -> np.ndarray:
+    """Upload, run one forward pass on cuda:0, return Y as a host array."""
+    dw = DeviceWorkload(wl, **kw)
+    Y = dw.forward().cpu().numpy()
+    dw.layer.destroy()
+    return Y

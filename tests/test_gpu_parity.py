@@ -1,0 +1,229 @@
+"""Parity of the HIP path against the CPU oracle, element by element, through the C ABI.
+Integer packing is compared bit-exact; floating point with the floored relative error
+max |g - o| / max(|o|, 1e-2 * RMS(o)) <= 1e-4 (fp32)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2309_03523_amd import synth
+from refs import rel_err
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def torch_mod():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+def _dw(wl, **kw):
+    from paper_2309_03523_amd.runner import DeviceWorkload
+    return DeviceWorkload(wl, **kw)
+
+
+def _chunks_grid(N, T, v_cuts, t_cuts):
+    vb = [0, *v_cuts, N]
+    tb = [0, *t_cuts, T]
+    return [[vb[i], vb[i + 1], tb[k], tb[k + 1]] for k in range(len(tb) - 1) for i in range(len(vb) - 1)]
+
+
+# ------------------------------------------------------------------ packing (bit-exact)
+
+
+@pytest.mark.parametrize("seed,N,T,deg,hub", [(1, 70, 3, 4.0, True), (2, 333, 5, 9.0, True), (3, 33, 2, 0.0, False),
+                                               (4, 1000, 4, 20.0, True)])
+def test_packing_bit_exact(torch_mod, seed, N, T, deg, hub):
+    chunks = _chunks_grid(N, T, [N // 5, N // 2 + 3], [1] if T > 2 else [])
+    wl = synth.random_small(seed, T, N, 8, 32, 32, deg, chunks, "gru", hub=hub)
+    R, L, P = 8, 16, 5
+    dw = _dw(wl, rows_per_group=R, long_nnz=L, part_nnz=P, validate_level=1)
+    want = oracle.pack(wl.graph, wl.chunks)
+    want.update(oracle.worklist(wl.graph, wl.chunks, R, L, P))
+    for key, arr in want.items():
+        got = dw.layer.packing(key)
+        assert got.dtype == arr.dtype and got.shape == arr.shape, key
+        assert np.array_equal(got, arr), key
+    deg_all = np.concatenate([np.diff(s.rowptr) for s in wl.graph.snaps]).astype(np.float32)
+    dinv = dw.layer.packing("deg_inv_sqrt")
+    assert np.allclose(dinv, 1.0 / np.sqrt(deg_all.astype(np.float64)), rtol=2e-7, atol=0)
+    if hub:
+        assert len(want["work_long"]) > 0
+    dw.layer.destroy()
+
+
+# ------------------------------------------------------------------ gather + aggregation
+
+
+@pytest.mark.parametrize("mode", ["in_place", "staged"])
+@pytest.mark.parametrize("F", [5, 32, 100, 172, 300])
+def test_aggregation_matches_oracle(torch_mod, mode, F):
+    torch = torch_mod
+    N, T = 257, 3
+    chunks = _chunks_grid(N, T, [40, 41, 170], [2])
+    wl = synth.random_small(10 + F, T, N, F, 32, 32, 6.0, chunks, "gru", hub=True)
+    dw = _dw(wl, gather_mode=mode, rows_per_group=5, long_nnz=24, part_nnz=7)
+    ldm = (F + 3) // 4 * 4
+    M = torch.full((wl.rows, ldm), float("nan"), device="cuda")
+    dw.layer.aggregate(dw.X, dw.C, M)
+    torch.cuda.synchronize()
+    got = M.cpu().numpy()
+    assert np.all(got[:, F:] == 0.0)
+    off = 0
+    for c in wl.chunks:
+        want = oracle.aggregate_chunk(wl.graph, c, wl.X, wl.C).reshape(-1, F)
+        n = want.shape[0]
+        assert rel_err(got[off:off + n, :F], want) < TOL
+        off += n
+    # gather: halo buffer holds exactly the cache rows the halo list names
+    halo_ptr, halo_idx = dw.layer.packing("halo_ptr"), dw.layer.packing("halo_idx")
+    hb = torch.full((len(halo_idx), ldm), float("nan"), device="cuda")
+    dw.layer.gather(dw.C, hb)
+    torch.cuda.synchronize()
+    hb = hb.cpu().numpy()
+    s = 0
+    for v_lo, v_hi, t_lo, t_hi in wl.chunks.tolist():
+        for t in range(t_lo, t_hi):
+            ids = halo_idx[halo_ptr[s]:halo_ptr[s + 1]]
+            assert np.array_equal(hb[halo_ptr[s]:halo_ptr[s + 1], :F], wl.C[t, ids])
+            s += 1
+    dw.layer.destroy()
+
+
+# ------------------------------------------------------------------ whole layer
+
+
+def _oracle_y(wl, **kw):
+    return oracle.forward(wl.graph, wl.chunks, wl.params, wl.X, wl.C, time_kind=wl.time_kind,
+                          n_struct_layers=wl.n_struct_layers, C1=wl.C1, H0=wl.H0, return_state=True, **kw)
+
+
+def _compare_layer(torch, wl, dw, mask=None, **okw):
+    Y, HN = dw.forward(reset_mask=mask, want_state=True)
+    want_Y, want_HN = _oracle_y(wl, reset_mask=mask, **okw)
+    got = Y.cpu().numpy()
+    covered = ~np.isnan(want_Y)
+    assert np.array_equal(np.isnan(got), ~covered), "rows outside every chunk must stay untouched"
+    err = rel_err(got[covered], want_Y[covered])
+    assert err < TOL, err
+    if want_HN is not None:
+        e2 = rel_err(HN.cpu().numpy(), want_HN)
+        assert e2 < TOL, e2
+    return err
+
+
+@pytest.mark.parametrize("kind", ["gru", "lstm", "none"])
+@pytest.mark.parametrize("F,S,H", [(32, 32, 32), (20, 64, 32), (128, 128, 128), (172, 128, 128), (40, 96, 160),
+                                   (64, 256, 256)])
+def test_layer_matches_oracle(torch_mod, kind, F, S, H):
+    N, T = 203, 5
+    # ragged tiles (vertex counts 1, 63, 65, 74), windows of different length, a gap in coverage
+    chunks = [[0, 1, 0, 5], [1, 64, 0, 2], [1, 64, 2, 5], [64, 129, 0, 5], [129, 203, 1, 4]]
+    wl = synth.random_small(100 + F + S + H, T, N, F, S, H, 5.0, chunks, kind, hub=True)
+    dw = _dw(wl, rows_per_group=7, long_nnz=32, part_nnz=9)
+    _compare_layer(torch_mod, wl, dw)
+    if kind != "none":
+        mask = (synth.stream(5, "mask").random((T, N)) < 0.3).astype(np.uint8)
+        _compare_layer(torch_mod, wl, dw, mask=mask)
+    dw.layer.destroy()
+
+
+@pytest.mark.parametrize("kind", ["gru", "lstm", "none"])
+@pytest.mark.parametrize("mode", ["in_place", "staged"])
+def test_two_layer_gcn(torch_mod, kind, mode):
+    N, T, F, S, H = 150, 4, 44, 64, 64
+    chunks = _chunks_grid(N, T, [30, 100], [3])
+    wl = synth.random_small(77, T, N, F, S, H, 6.0, chunks, kind, n_struct_layers=2, hub=True)
+    dw = _dw(wl, gather_mode=mode, act_hidden="relu", act_out="none", long_nnz=20, part_nnz=8)
+    _compare_layer(torch_mod, wl, dw, act_hidden="relu", act_out="none")
+    dw.layer.destroy()
+    dw = _dw(wl, gather_mode=mode, act_hidden="none", act_out="relu")
+    _compare_layer(torch_mod, wl, dw, act_hidden="none", act_out="relu")
+    dw.layer.destroy()
+
+
+def test_no_h0_and_cache_aliasing_input(torch_mod):
+    """H0 = NULL means zeros; C aliased to X makes chunking invisible (equal to one big chunk)."""
+    N, T = 90, 4
+    wl = synth.random_small(31, T, N, 16, 32, 32, 4.0, _chunks_grid(N, T, [20, 55], []), "gru")
+    dw = _dw(wl)
+    Y = dw.forward(use_h0=False, C=dw.X).cpu().numpy()
+    whole = oracle.forward(wl.graph, [[0, N, 0, T]], wl.params, wl.X, wl.X, time_kind="gru")
+    assert rel_err(Y, whole) < TOL
+    dw.layer.destroy()
+
+
+def test_config1_full(torch_mod):
+    wl = synth.config1(seed=0, random_bias=True)
+    for mode in ("in_place", "staged"):
+        dw = _dw(wl, gather_mode=mode, validate_level=1)
+        _compare_layer(torch_mod, wl, dw)
+        dw.layer.destroy()
+
+
+def test_config2_scaled(torch_mod):
+    """Config 2 at 1/20 scale: same generator, same chunk grid, oracle finishes in seconds."""
+    wl = synth.config2(seed=0, scale=0.05, random_bias=True)
+    dw = _dw(wl)
+    _compare_layer(torch_mod, wl, dw)
+    dw.layer.destroy()
+
+
+# ------------------------------------------------------------------ error paths on the device
+
+
+def test_bad_graph_is_reported(torch_mod):
+    from paper_2309_03523_amd.binding import DgcError
+    wl = synth.random_small(9, 2, 40, 8, 32, 32, 4.0, [[0, 40, 0, 2]], "gru")
+    s = wl.graph.snaps[1]
+    # drop one direction of an edge: asymmetric
+    i = int(np.argmax(np.diff(s.rowptr) > 1))
+    e = int(s.rowptr[i])
+    if s.col[e] == i:
+        e += 1
+    col = np.delete(s.col, e)
+    rowptr = s.rowptr.copy()
+    rowptr[i + 1:] -= 1
+    wl.graph.snaps[1] = synth.Snapshot(rowptr, col)
+    with pytest.raises(DgcError) as ei:
+        _dw(wl, validate_level=1)
+    assert ei.value.code == 2 and "symmetric" in str(ei.value)
+    # a column out of range is caught even at validate_level 0
+    col2 = s.col.copy()
+    col2[3] = 40
+    wl.graph.snaps[1] = synth.Snapshot(s.rowptr, col2)
+    with pytest.raises(DgcError) as ei:
+        _dw(wl, validate_level=0)
+    assert ei.value.code == 2
+    # decreasing rowptr
+    rp = s.rowptr.copy()
+    rp[5] = rp[6] + 1
+    wl.graph.snaps[1] = synth.Snapshot(rp, s.col)
+    with pytest.raises(DgcError) as ei:
+        _dw(wl, validate_level=0)
+    assert ei.value.code == 2
+
+
+def test_forward_argument_errors(torch_mod):
+    torch = torch_mod
+    from paper_2309_03523_amd.binding import DgcError
+    wl = synth.random_small(12, 2, 40, 8, 32, 32, 4.0, [[0, 40, 0, 2]], "gru")
+    dw = _dw(wl)
+    bad = torch.zeros((2, 40, 6), device="cuda")[:, :, :5]  # pitch 6: not a multiple of 4
+    with pytest.raises(DgcError) as ei:
+        dw.layer.forward(bad, dw.C, dw.Y)
+    assert ei.value.code == 1
+    with pytest.raises(DgcError) as ei:
+        dw.layer.forward(dw.X, dw.C, torch.zeros((2, 40, 16), device="cuda"))  # Y narrower than H
+    assert ei.value.code == 1
+    with pytest.raises(DgcError) as ei:
+        dw.layer.backward(dw.Y)
+    assert ei.value.code == 7  # backward before forward
+    dw.forward()
+    with pytest.raises(DgcError) as ei:
+        dw.layer.backward(dw.Y)
+    assert ei.value.code == 4
+    dw.layer.destroy()
