@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused-chunk DGNN layer (GCN aggregation + transform + GRU) on one MI355X.
+
+A step is one forward pass of the whole layer over the fused batch of chunks of the named
+workload (default: config 2 of the benchmark spec: 32 snapshots x 100k vertices, F=S=H=128,
+64 chunks).  Inputs are generated once, uploaded, and resident in HBM before timing starts.
+Prints ONE JSON line: throughput in snapshot-vertex embeddings/s, the roofline of the dominant
+kernel (the fused dense + recurrent kernel, measured live with HIP events on the launch
+stream), and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config2s"])
+    ap.add_argument("--gather-mode", default="in_place", choices=["in_place", "staged"])
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    return ap.parse_args()
+
+
+def make_workload(name: str, seed: int):
+    from paper_2309_03523_amd import synth
+    if name == "config1":
+        return synth.config1(seed), "config1: 8 snapshots x 1000 vertices, ER avg deg 8, F=S=H=32, 4 chunks"
+    if name == "config2s":
+        return synth.config2(seed, scale=0.05), "config2 at 1/20 scale"
+    return synth.config2(seed), ("config2: 32 snapshots x 100k vertices, lognormal edge counts, power-law "
+                                 "degrees (tail 2.1), F=S=H=128, GCN+GRU, 64 chunks = 4 windows of 8 x 16 "
+                                 "uneven vertex ranges")
+
+
+def flops_per_row(wl) -> dict:
+    """Algorithmic flops per snapshot-vertex row of each step of the path."""
+    g = {"gru": 3, "lstm": 4, "none": 0}[wl.time_kind]
+    dense = 2 * wl.F * wl.S + (2 * wl.S * wl.S if wl.n_struct_layers == 2 else 0)
+    rnn = 2 * wl.S * g * wl.H + 2 * wl.H * g * wl.H
+    return {"transform": dense, "rnn": rnn}
+
+
+def cpu_baseline(wl, Y_gpu, target_seconds: float, seed: int) -> dict:
+    """Time the CPU oracle on a seeded sample of vertices of every chunk (all snapshots of the
+    chunk's window), sized from a short calibration run to about target_seconds.  Also returns
+    the parity of the GPU result on those rows."""
+    import numpy as np
+    import oracle
+    from paper_2309_03523_amd import synth
+
+    rng = synth.stream(seed, "bench-sample")
+    chunks = wl.chunks
+    widths = chunks[:, 1] - chunks[:, 0]
+    windows = chunks[:, 3] - chunks[:, 2]
+
+    def sample(per_chunk):
+        return [np.sort(rng.choice(int(w), size=min(int(w), per_chunk), replace=False)) + int(c[0])
+                for c, w in zip(chunks, widths)]
+
+    def run(sub):
+        t0 = time.perf_counter()
+        Y = oracle.forward(wl.graph, chunks, wl.params, wl.X, wl.C, time_kind=wl.time_kind,
+                           n_struct_layers=wl.n_struct_layers, C1=wl.C1, H0=wl.H0, subset=sub)
+        return Y, time.perf_counter() - t0
+
+    sub = sample(4)
+    _, dt = run(sub)
+    rows_cal = sum(len(s) * int(w) for s, w in zip(sub, windows))
+    rate = rows_cal / max(dt, 1e-6)
+    per_chunk = int(max(4, min(widths.max(), target_seconds * rate / max(1, int(windows.sum())))))
+    sub = sample(per_chunk)
+    Y, dt = run(sub)
+    rows = sum(len(s) * int(w) for s, w in zip(sub, windows))
+    mask = ~np.isnan(Y)
+    want = Y[mask].astype(np.float64)
+    got = Y_gpu[mask].astype(np.float64)
+    tau = 0.1 * float(np.sqrt(np.mean(want * want)))
+    err = float(np.max(np.abs(got - want) / np.maximum(np.abs(want), tau)))
+    return {"value": rows / dt, "unit": "embeddings/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"{per_chunk} seeded random vertices of each of the {len(chunks)} chunks over the chunk's "
+                      f"whole window = {rows} rows, {dt:.1f} s",
+            "gpu_max_rel_err_on_sample": err}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (chunks would shard across GPUs by chunk "
+              "assignment; no collective is built). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    from paper_2309_03523_amd.runner import DeviceWorkload
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+
+    t0 = time.perf_counter()
+    wl, desc = make_workload(args.workload, args.seed)
+    t_gen = time.perf_counter() - t0
+    g = wl.graph
+    rows = wl.rows
+
+    t0 = time.perf_counter()
+    dw = DeviceWorkload(wl, gather_mode=args.gather_mode)
+    torch.cuda.synchronize()
+    t_create = time.perf_counter() - t0
+    layer = dw.layer
+    stream = torch.cuda.current_stream()
+
+    def step():
+        layer.forward(dw.X, dw.C, dw.Y, C1=dw.C1, H0=dw.H0, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    value = rows * args.steps / elapsed
+
+    # per-stage device times of the same launches, HIP events on the launch stream
+    layer.set_profiling(True)
+    stage = np.zeros(4, np.float64)
+    n_prof = max(3, min(args.steps, 10))
+    for _ in range(n_prof):
+        step()
+        stage += layer.stage_times()
+    stage /= n_prof
+    layer.set_profiling(False)
+
+    fl = flops_per_row(wl)
+    dense_flops = (fl["transform"] + fl["rnn"]) * rows if wl.n_struct_layers == 1 else \
+        (2 * wl.S * wl.S + fl["rnn"]) * rows
+    dense_ms = float(stage[3])
+    achieved = dense_flops / (dense_ms * 1e-3) / 1e12
+    roofline = {"kernel": "k_dense (GCN transform + GRU gates, fused over the window)", "bound": "mfma",
+                "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                "flops_per_launch": dense_flops, "ms_per_launch": dense_ms}
+    # aggregation kernels: algorithmic (compulsory) bytes = X rows once + CSR + M written once
+    nnz = int(layer.packing("seg_nnz_off")[-1])
+    agg_bytes = rows * (wl.F * 4) + nnz * 4 + rows * 8 + rows * (wl.F * 4)
+    agg_ms = float(stage[0])
+    agg = {"kernel": "k_spmm_short + k_spmm_long + k_spmm_long_reduce", "bound": "hbm",
+           "achieved": agg_bytes / (agg_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+           "frac": agg_bytes / (agg_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None,
+           "bytes_per_launch": agg_bytes, "ms_per_launch": agg_ms,
+           "gather_traffic_GBs": nnz * wl.F * 4 / (agg_ms * 1e-3) / 1e9, "nnz": nnz}
+
+    out = {"metric": "snapshot-vertex embeddings/s per DGNN layer", "value": value, "unit": "embeddings/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+           "data": "synthetic",
+           "config": {"workload": desc, "rows": rows, "nnz": nnz, "gather_mode": args.gather_mode,
+                      "pass": "forward"},
+           "roofline": roofline, "roofline_aggregation": agg,
+           "stage_ms": {"aggregate0": float(stage[0]), "dense0": float(stage[1]), "aggregate1": float(stage[2]),
+                        "dense_rnn": float(stage[3])},
+           "setup_s": {"generate": t_gen, "upload_create_pack": t_create}}
+    if not args.no_cpu_baseline:
+        Y_gpu = dw.Y.cpu().numpy()
+        out["cpu_baseline"] = cpu_baseline(wl, Y_gpu, args.cpu_seconds, args.seed)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -150,6 +150,19 @@ dgc_status_t dgc_layer_aggregate(dgc_layer_t* layer, const float* X, int64_t ldx
 dgc_status_t dgc_layer_gather(dgc_layer_t* layer, const float* C, int64_t ldc, float* halo,
                               int64_t ldh, void* stream);
 
+/* Per-stage device time of a forward pass, from HIP events recorded on the caller's stream
+ * (for measurement; adds no synchronisation to forward itself).  Stages:
+ *  0 aggregation of the first GCN layer (gather + split-row reduction included)
+ *  1 first GCN layer's dense transform            (0 ms unless n_struct_layers = 2)
+ *  2 aggregation of the second GCN layer          (0 ms unless n_struct_layers = 2)
+ *  3 last GCN layer's dense transform fused with the time encoder
+ * dgc_layer_set_profiling: enable != 0 makes every later forward record the events.
+ * dgc_layer_stage_times: waits for the last profiled forward and writes DGC_N_STAGES
+ * durations in milliseconds to host_ms (host); DGC_ERR_STATE if none was enqueued. */
+#define DGC_N_STAGES 4
+dgc_status_t dgc_layer_set_profiling(dgc_layer_t* layer, int32_t enable);
+dgc_status_t dgc_layer_stage_times(dgc_layer_t* layer, float* host_ms);
+
 /* Read back a packing array (host_dst: host).  `what` and element types:
  *  "seg_row_off" "seg_nnz_off" "halo_ptr"  int64 [n_segments+1]
  *  "halo_idx" int32 [halo_ptr[n_segments]]   "col_local" int32 [seg_nnz_off[n_segments]]

@@ -24,7 +24,9 @@ STATUS = {0: "DGC_OK", 1: "DGC_ERR_INVALID_ARG", 2: "DGC_ERR_BAD_GRAPH", 3: "DGC
 
 EXPORTS = ["dgc_layer_create", "dgc_layer_destroy", "dgc_layer_set_param", "dgc_layer_get_param",
            "dgc_layer_forward", "dgc_layer_backward", "dgc_layer_aggregate", "dgc_layer_gather",
-           "dgc_layer_packing", "dgc_last_error", "dgc_version"]
+           "dgc_layer_packing", "dgc_layer_set_profiling", "dgc_layer_stage_times", "dgc_last_error",
+           "dgc_version"]
+N_STAGES = 4
 
 
 class DgcError(RuntimeError):
@@ -70,6 +72,8 @@ def load() -> ct.CDLL:
     lib.dgc_layer_aggregate.argtypes = [vp, vp, i64, vp, i64, vp, i64, vp]
     lib.dgc_layer_gather.argtypes = [vp, vp, i64, vp, i64, vp]
     lib.dgc_layer_packing.argtypes = [vp, ct.c_char_p, vp, i64, ct.POINTER(i64)]
+    lib.dgc_layer_set_profiling.argtypes = [vp, i32]
+    lib.dgc_layer_stage_times.argtypes = [vp, vp]
     lib.dgc_last_error.argtypes = [vp]
     lib.dgc_last_error.restype = ct.c_char_p
     lib.dgc_version.restype = ct.c_char_p
@@ -202,6 +206,16 @@ class DgcLayer:
         self._check(self._lib.dgc_layer_gather(self._h, _dev(C, "C"), _ld(C, "C"), _dev(halo, "halo"),
                                                int(halo.stride(0)), _stream_ptr(stream)))
         return halo
+
+    # -- measurement
+    def set_profiling(self, enable: bool):
+        self._check(self._lib.dgc_layer_set_profiling(self._h, int(bool(enable))))
+
+    def stage_times(self) -> np.ndarray:
+        """Milliseconds per stage of the last profiled forward (waits for it)."""
+        out = np.zeros(N_STAGES, np.float32)
+        self._check(self._lib.dgc_layer_stage_times(self._h, out.ctypes.data_as(ct.c_void_p)))
+        return out
 
     # -- inspection
     def packing(self, what: str) -> np.ndarray:

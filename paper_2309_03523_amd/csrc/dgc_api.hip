@@ -51,6 +51,9 @@ struct dgc_layer {
   float* d_Z1 = nullptr;                         // 2 layers: first layer's output [T,N,S]
   std::map<std::string, Param> params;
   bool forward_done = false;
+  bool profiling = false;
+  hipEvent_t ev[DGC_N_STAGES + 1] = {};   // stage boundaries of the last profiled forward
+  bool ev_valid = false;
   std::string error;
 
   GraphDev graph_dev() const { return GraphDev{T, N, d_rowptr, d_colidx}; }
@@ -424,6 +427,8 @@ dgc_status_t dgc_layer_create(const dgc_layer_desc_t* desc, const dgc_graph_t* g
 dgc_status_t dgc_layer_destroy(dgc_layer_t* L) {
   if (!L) return DGC_OK;
   (void)hipDeviceSynchronize();
+  for (hipEvent_t e : L->ev)
+    if (e) (void)hipEventDestroy(e);
   free_all(L);
   delete L;
   return DGC_OK;
@@ -508,7 +513,11 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* L, const float* X, int64_t ldx, cons
   da.S = d.S; da.H = d.H;
   std::string why;
 
+  const bool prof = L->profiling;
+  L->ev_valid = false;
+  if (prof) DGC_HIP_TRY(hipEventRecord(L->ev[0], st));
   run_aggregate(L, X, ldx, C, ldc, d.F, L->d_M, L->ldm, st);
+  if (prof) DGC_HIP_TRY(hipEventRecord(L->ev[1], st));
   const char* last = "gcn0";
   if (d.n_struct_layers == 2) {
     // first layer for every row of the batch -> Z1 [T,N,S]; then aggregate Z1 | C1
@@ -516,8 +525,13 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* L, const float* X, int64_t ldx, cons
     da.Wg = L->params["gcn0.weight"].packed; da.bg = L->params["gcn0.bias"].raw;
     da.Y = L->d_Z1; da.ldy = d.S;
     if (!launch_dense(da, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
+    if (prof) DGC_HIP_TRY(hipEventRecord(L->ev[2], st));
     run_aggregate(L, L->d_Z1, d.S, C1, ldc1, d.S, L->d_M, L->ldm, st);
+    if (prof) DGC_HIP_TRY(hipEventRecord(L->ev[3], st));
     last = "gcn1";
+  } else if (prof) {
+    DGC_HIP_TRY(hipEventRecord(L->ev[2], st));
+    DGC_HIP_TRY(hipEventRecord(L->ev[3], st));
   }
   da.K0 = d.n_struct_layers == 2 ? d.S : d.F;
   da.act = d.act_out;
@@ -530,8 +544,33 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* L, const float* X, int64_t ldx, cons
   }
   da.H0 = H0; da.reset_mask = reset_mask; da.Y = Y; da.ldy = ldy; da.HN = HN;
   if (!launch_dense(da, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
+  if (prof) {
+    DGC_HIP_TRY(hipEventRecord(L->ev[4], st));
+    L->ev_valid = true;
+  }
   DGC_HIP_TRY(hipGetLastError());
   L->forward_done = true;
+  return DGC_OK;
+}
+
+dgc_status_t dgc_layer_set_profiling(dgc_layer_t* L, int32_t enable) {
+  if (!L) return DGC_ERR_INVALID_ARG;
+  Failer fail{L};
+  if (enable && !L->ev[0]) {
+    for (int i = 0; i <= DGC_N_STAGES; ++i) DGC_HIP_TRY(hipEventCreate(&L->ev[i]));
+  }
+  L->profiling = enable != 0;
+  L->ev_valid = false;
+  return DGC_OK;
+}
+
+dgc_status_t dgc_layer_stage_times(dgc_layer_t* L, float* host_ms) {
+  if (!L) return DGC_ERR_INVALID_ARG;
+  Failer fail{L};
+  if (!host_ms) return fail(DGC_ERR_INVALID_ARG, "NULL argument");
+  if (!L->ev_valid) return fail(DGC_ERR_STATE, "no profiled forward has been enqueued");
+  DGC_HIP_TRY(hipEventSynchronize(L->ev[DGC_N_STAGES]));
+  for (int i = 0; i < DGC_N_STAGES; ++i) DGC_HIP_TRY(hipEventElapsedTime(&host_ms[i], L->ev[i], L->ev[i + 1]));
   return DGC_OK;
 }
 

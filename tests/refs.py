@@ -58,10 +58,10 @@ def brute_pack(graph, chunks) -> dict:
 
 
 def rel_err(got: np.ndarray, want: np.ndarray) -> float:
-    """max |got - want| / max(|want|, tau), tau = 1e-2 * RMS(want): the elementwise relative
+    """max |got - want| / max(|want|, tau), tau = 1e-1 * RMS(want): the elementwise relative
     error with a floor, since a plain relative error is unbounded near zero."""
     got = np.asarray(got, np.float64)
     want = np.asarray(want, np.float64)
-    tau = 1e-2 * float(np.sqrt(np.mean(want * want))) if want.size else 0.0
+    tau = 1e-1 * float(np.sqrt(np.mean(want * want))) if want.size else 0.0
     den = np.maximum(np.abs(want), max(tau, 1e-300))
     return float(np.max(np.abs(got - want) / den)) if want.size else 0.0
