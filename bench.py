@@ -34,6 +34,9 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain device copy of X (a kernel of known size, to scale rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -73,13 +76,16 @@ def cpu_baseline(wl, Y_gpu, target_seconds: float, seed: int) -> dict:
         return [np.sort(rng.choice(int(w), size=min(int(w), per_chunk), replace=False)) + int(c[0])
                 for c, w in zip(chunks, widths)]
 
+    out_dim = wl.H if wl.time_kind != "none" else wl.S
+
     def run(sub):
+        Y = np.full((wl.graph.T, wl.graph.N, out_dim), np.nan, np.float32)  # allocated outside the timed call
         t0 = time.perf_counter()
-        Y = oracle.forward(wl.graph, chunks, wl.params, wl.X, wl.C, time_kind=wl.time_kind,
-                           n_struct_layers=wl.n_struct_layers, C1=wl.C1, H0=wl.H0, subset=sub)
+        oracle.forward(wl.graph, chunks, wl.params, wl.X, wl.C, time_kind=wl.time_kind,
+                       n_struct_layers=wl.n_struct_layers, C1=wl.C1, H0=wl.H0, subset=sub, Y=Y)
         return Y, time.perf_counter() - t0
 
-    sub = sample(4)
+    sub = sample(32)
     _, dt = run(sub)
     rows_cal = sum(len(s) * int(w) for s, w in zip(sub, windows))
     rate = rows_cal / max(dt, 1e-6)
@@ -129,6 +135,12 @@ def main():
     def step():
         layer.forward(dw.X, dw.C, dw.Y, C1=dw.C1, H0=dw.H0, stream=stream)
 
+    if args.calib_copy:
+        scratch = torch.empty_like(dw.X)
+        scratch.copy_(dw.X)
+        torch.cuda.synchronize()
+        print(f"calib-copy: {dw.X.numel() * 4} bytes read and as many written", file=sys.stderr)
+        del scratch
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

@@ -94,31 +94,47 @@ int dgc_oracle_pack(int32_t T, int64_t N, const int64_t *const *rowptr, const in
 
 /* Row-group work list of the fused launch (the rule is this build's own; the paper only asks
  * that fused chunks execute together, Section 5.1.1).  Two lists:
- *  short list: every segment, in order, is cut into groups of `rows_per_group` consecutive
- *              rows (the last group of a segment may be smaller): (seg, first local row, rows).
- *              Rows longer than `long_nnz` stored non-zeros are left out of the sum there;
- *  long list : every such row, in (segment, row) order, is cut into ceil(nnz/part_nnz) parts
- *              of part_nnz non-zeros (the last may be smaller): (seg, local row, part, parts).
+ *  short list: segments are visited snapshot by snapshot (t ascending; within a snapshot in
+ *              chunk order), so that the rows being aggregated at any moment read the same
+ *              snapshot's features.  Every segment is cut into groups of `rows_per_group`
+ *              consecutive rows (the last group of a segment may be smaller):
+ *              (segment, first local row, rows).  Rows longer than `long_nnz` stored non-zeros
+ *              are left out of the sum there;
+ *  long list : every such row, in packed (segment, row) order, is cut into ceil(nnz/part_nnz)
+ *              parts of part_nnz non-zeros (the last may be smaller): (segment, local row,
+ *              part, parts).
+ * Segment numbers are those of dgc_oracle_pack (chunk as given, then snapshot).
  * Output arrays may be NULL to count only.  Returns 0; counts through n_short / n_long. */
 int dgc_oracle_worklist(int32_t T, int64_t N, const int64_t *const *rowptr, const int64_t *chunks,
                         int32_t n_chunks, int32_t rows_per_group, int32_t long_nnz,
                         int32_t part_nnz, int32_t *short_list /*[n][3]*/, int64_t *n_short,
                         int32_t *long_list /*[n][4]*/, int64_t *n_long) {
-  (void)T; (void)N;
+  (void)N;
   int64_t ns = 0, nl = 0, s = 0;
+  for (int32_t t = 0; t < T; ++t) {
+    int64_t seg0 = 0; /* first segment of chunk k */
+    for (int32_t k = 0; k < n_chunks; ++k) {
+      const int64_t v_lo = CH_VLO(chunks, k), v_hi = CH_VHI(chunks, k);
+      const int64_t t_lo = CH_TLO(chunks, k), t_hi = CH_THI(chunks, k);
+      if (t >= t_lo && t < t_hi) {
+        const int64_t seg = seg0 + (t - t_lo);
+        for (int64_t r = 0; r < v_hi - v_lo; r += rows_per_group) {
+          int64_t n = v_hi - v_lo - r;
+          if (n > rows_per_group) n = rows_per_group;
+          if (short_list) {
+            short_list[3 * ns + 0] = (int32_t)seg;
+            short_list[3 * ns + 1] = (int32_t)r;
+            short_list[3 * ns + 2] = (int32_t)n;
+          }
+          ++ns;
+        }
+      }
+      seg0 += t_hi - t_lo;
+    }
+  }
   for (int32_t k = 0; k < n_chunks; ++k) {
     const int64_t v_lo = CH_VLO(chunks, k), v_hi = CH_VHI(chunks, k);
     for (int64_t t = CH_TLO(chunks, k); t < CH_THI(chunks, k); ++t, ++s) {
-      for (int64_t r = 0; r < v_hi - v_lo; r += rows_per_group) {
-        int64_t n = v_hi - v_lo - r;
-        if (n > rows_per_group) n = rows_per_group;
-        if (short_list) {
-          short_list[3 * ns + 0] = (int32_t)s;
-          short_list[3 * ns + 1] = (int32_t)r;
-          short_list[3 * ns + 2] = (int32_t)n;
-        }
-        ++ns;
-      }
       for (int64_t i = v_lo; i < v_hi; ++i) {
         const int64_t nnz = rowptr[t][i + 1] - rowptr[t][i];
         if (nnz > long_nnz) {

@@ -264,9 +264,14 @@ dgc_status_t build_layer(dgc_layer* L, const dgc_graph_t* graph, hipStream_t st)
 
   // work list: row groups (host arithmetic on the chunk table) and split rows (device)
   {
+    // short list: snapshot by snapshot, so that concurrently resident waves gather from the
+    // same snapshot's feature rows (cache locality); within a snapshot in chunk order
     std::vector<int32_t> ws;
     const int32_t R = L->rows_per_group;
-    for (int64_t s = 0; s < L->nseg; ++s) {
+    std::vector<int64_t> order(L->nseg);
+    for (int64_t s = 0; s < L->nseg; ++s) order[s] = s;
+    std::stable_sort(order.begin(), order.end(), [&](int64_t a, int64_t b) { return segs[a].t < segs[b].t; });
+    for (int64_t s : order) {
       const int64_t rows = segs[s].v_hi - segs[s].v_lo;
       for (int64_t r = 0; r < rows; r += R) {
         ws.push_back((int32_t)s);

@@ -84,12 +84,17 @@ __device__ __forceinline__ void mma_k_loop(floatx16 (&acc)[NRB][4], const float*
 
 // KIND: DGC_TIME_*.  NRB: 32-row blocks per unit (1 or 2).  UPW: units per wave.
 // A unit is NRB row blocks x one 32-column block (x all gates).
+//
+// LDS holds two [64][ld] buffers that swap roles every step:
+//   P: the state h entering the step;   Q: the aggregated rows, then Z, then the new state.
+// Per step: load M -> Q and mask P | Z = act(Q W^T + b) in registers | Z -> Q | gate GEMMs read
+// Q and P | gate arithmetic writes the new h into Q | Q -> Y | swap(P, Q).
 template <int KIND, int NRB, int UPW>
-__global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int lda, int ldh) {
+__global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int ld) {
   extern __shared__ float smem[];
-  float* bufA = smem;                       // [64][lda]: aggregated rows, then Z
-  float* bufH = smem + kTileRows * lda;     // [64][ldh]: hidden state
-  int* mask_row = reinterpret_cast<int*>(bufH + (KIND == DGC_TIME_NONE ? 0 : kTileRows * ldh));
+  float* P = smem;
+  float* Q = smem + kTileRows * ld;
+  int* mask_row = reinterpret_cast<int*>(smem + 2 * kTileRows * ld);
 
   const DenseTile tile = a.tiles[blockIdx.x];
   const ChunkInfo ch = a.chunks[tile.chunk];
@@ -127,13 +132,13 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int lda, int
       const int r = idx / hf4, c4 = idx - r * hf4;
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
       if (a.H0 && r < nrows) v = *reinterpret_cast<const float4*>(a.H0 + (sbase + r) * H + 4 * c4);
-      *reinterpret_cast<float4*>(bufH + r * ldh + 4 * c4) = v;
+      *reinterpret_cast<float4*>(P + r * ld + 4 * c4) = v;
     }
   }
 
   for (int s = 0; s < ch.w; ++s) {
     const int64_t t = ch.t_lo + s;
-    // (a) aggregated rows of this step -> bufA, zero beyond K0 and beyond nrows
+    // (a) aggregated rows of this step -> Q, zero beyond K0 and beyond nrows
     {
       const float* Mrow0 = a.M + (ch.row_off0 + (int64_t)s * ch.nv + tile.v0) * a.ldm;
       const int nf4 = nkb0 * 2;
@@ -147,7 +152,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int lda, int
           if (4 * c4 + 3 >= K0) v.w = 0.f;
           if (4 * c4 >= K0) v.x = 0.f;
         }
-        *reinterpret_cast<float4*>(bufA + r * lda + 4 * c4) = v;
+        *reinterpret_cast<float4*>(Q + r * ld + 4 * c4) = v;
       }
     }
     // (b) temporal-fusion mask: zero the incoming state of masked rows (same thread <-> element
@@ -157,14 +162,14 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int lda, int
       for (int idx = tid; idx < kTileRows * hf4; idx += kThreads) {
         const int r = idx / hf4, c4 = idx - r * hf4;
         const int mk = (a.reset_mask && r < nrows) ? a.reset_mask[t * a.N + vbase + r] : 0;
-        if (mk) *reinterpret_cast<float4*>(bufH + r * ldh + 4 * c4) = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (mk) *reinterpret_cast<float4*>(P + r * ld + 4 * c4) = make_float4(0.f, 0.f, 0.f, 0.f);
         if (c4 == 0) mask_row[r] = mk;
       }
     }
     __syncthreads();
 
-    // (c) Z = act(M W^T + b) for this wave's units
-    float zreg[UPW][NRB][16];
+    // (c) Z = act(M W^T + b) for this wave's units, kept in the accumulators over the barrier
+    floatx16 zacc[UPW][NRB];
 #pragma unroll
     for (int ui = 0; ui < UPW; ++ui) {
       const int u = wave + kWaves * ui;
@@ -174,16 +179,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int lda, int
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) acc[rb][0] = (floatx16)(0.f);
         const float4* const wp[1] = {a.Wg + ((int64_t)jb * nkb0) * 64 + lane};
-        mma_k_loop<NRB, 1, 0, 0, 0, 0>(acc, bufA + (rb0 * 32 + l32) * lda + half * 4, lda, nkb0, wp);
-        const float bias = a.bg[jb * 32 + l32];
+        mma_k_loop<NRB, 1, 0, 0, 0, 0>(acc, Q + (rb0 * 32 + l32) * ld + half * 4, ld, nkb0, wp);
 #pragma unroll
-        for (int rb = 0; rb < NRB; ++rb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            float z = acc[rb][0][v] + bias;
-            if (a.act == DGC_ACT_RELU) z = fmaxf(z, 0.f);
-            zreg[ui][rb][v] = z;
-          }
+        for (int rb = 0; rb < NRB; ++rb) zacc[ui][rb] = acc[rb][0];
       }
     }
     __syncthreads();  // everyone has finished reading the aggregated rows
@@ -192,12 +190,15 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int lda, int
       const int u = wave + kWaves * ui;
       if (u < unitsS) {
         const int jb = u / RBU, rb0 = (u % RBU) * NRB;
+        const float bias = a.bg[jb * 32 + l32];
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             const int row = (rb0 + rb) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-            bufA[row * lda + jb * 32 + l32] = zreg[ui][rb][v];
+            float z = zacc[ui][rb][v] + bias;
+            if (a.act == DGC_ACT_RELU) z = fmaxf(z, 0.f);
+            Q[row * ld + jb * 32 + l32] = z;
           }
       }
     }
@@ -209,11 +210,13 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int lda, int
         const int r = idx / sf4, c4 = idx - r * sf4;
         if (r < nrows)
           *reinterpret_cast<float4*>(a.Y + (t * a.N + vbase + r) * a.ldy + 4 * c4) =
-              *reinterpret_cast<const float4*>(bufA + r * lda + 4 * c4);
+              *reinterpret_cast<const float4*>(Q + r * ld + 4 * c4);
       }
-      __syncthreads();  // bufA is overwritten by the next step's rows
+      __syncthreads();  // Q is overwritten by the next step's rows
     } else {
-      // (e) gate pre-activations and gate arithmetic
+      // (e) gate pre-activations.  With UPW > 1 a wave finishes unit after unit; the new state of
+      //     a unit can only be written once every wave has stopped reading Z and h, so the gate
+      //     values of earlier units wait in registers.
       float hnew[UPW][NRB][16];
 #pragma unroll
       for (int ui = 0; ui < UPW; ++ui) {
@@ -226,8 +229,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int lda, int
           for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
             for (int g = 0; g < 4; ++g) acc[rb][g] = (floatx16)(0.f);
-          const float* ldsZ = bufA + (rb0 * 32 + l32) * lda + half * 4;
-          const float* ldsHp = bufH + (rb0 * 32 + l32) * ldh + half * 4;
+          const float* ldsZ = Q + (rb0 * 32 + l32) * ld + half * 4;
+          const float* ldsHp = P + (rb0 * 32 + l32) * ld + half * 4;
           if constexpr (KIND == DGC_TIME_GRU) {
             // slots: 0 r, 1 z, 2 input part of n, 3 hidden part of n
             const float4* const wi[3] = {a.Wih + ((int64_t)(0 * njbH + jb) * nkbS) * 64 + lane,
@@ -236,8 +239,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int lda, int
             const float4* const wh[3] = {a.Whh + ((int64_t)(0 * njbH + jb) * nkbH) * 64 + lane,
                                          a.Whh + ((int64_t)(1 * njbH + jb) * nkbH) * 64 + lane,
                                          a.Whh + ((int64_t)(2 * njbH + jb) * nkbH) * 64 + lane};
-            mma_k_loop<NRB, 3, 0, 1, 2, 0>(acc, ldsZ, lda, nkbS, wi);
-            mma_k_loop<NRB, 3, 0, 1, 3, 0>(acc, ldsHp, ldh, nkbH, wh);
+            mma_k_loop<NRB, 3, 0, 1, 2, 0>(acc, ldsZ, ld, nkbS, wi);
+            mma_k_loop<NRB, 3, 0, 1, 3, 0>(acc, ldsHp, ld, nkbH, wh);
             const float b_r = a.bih[col] + a.bhh[col];
             const float b_z = a.bih[H + col] + a.bhh[H + col];
             const float b_in = a.bih[2 * H + col], b_hn = a.bhh[2 * H + col];
@@ -246,7 +249,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int lda, int
 #pragma unroll
               for (int v = 0; v < 16; ++v) {
                 const int row = (rb0 + rb) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-                const float hp = bufH[row * ldh + col];
+                const float hp = P[row * ld + col];
                 const float r = sigmoidf_(acc[rb][0][v] + b_r);
                 const float z = sigmoidf_(acc[rb][1][v] + b_z);
                 const float n = tanhf(acc[rb][2][v] + b_in + r * (acc[rb][3][v] + b_hn));
@@ -262,8 +265,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int lda, int
                                          a.Whh + ((int64_t)(1 * njbH + jb) * nkbH) * 64 + lane,
                                          a.Whh + ((int64_t)(2 * njbH + jb) * nkbH) * 64 + lane,
                                          a.Whh + ((int64_t)(3 * njbH + jb) * nkbH) * 64 + lane};
-            mma_k_loop<NRB, 4, 0, 1, 2, 3>(acc, ldsZ, lda, nkbS, wi);
-            mma_k_loop<NRB, 4, 0, 1, 2, 3>(acc, ldsHp, ldh, nkbH, wh);
+            mma_k_loop<NRB, 4, 0, 1, 2, 3>(acc, ldsZ, ld, nkbS, wi);
+            mma_k_loop<NRB, 4, 0, 1, 2, 3>(acc, ldsHp, ld, nkbH, wh);
             float bsum[4];
 #pragma unroll
             for (int g = 0; g < 4; ++g) bsum[g] = a.bih[g * H + col] + a.bhh[g * H + col];
@@ -295,22 +298,23 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int lda, int
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
               const int row = (rb0 + rb) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-              bufH[row * ldh + jb * 32 + l32] = hnew[ui][rb][v];
+              Q[row * ld + jb * 32 + l32] = hnew[ui][rb][v];
             }
         }
       }
       __syncthreads();
-      // (g) h_t -> Y, whole rows at a time
+      // (g) h_t -> Y, whole rows at a time; Q becomes the state buffer of the next step
       const int hf4 = H / 4;
       const bool last = (s == ch.w - 1) && a.HN;
       for (int idx = tid; idx < kTileRows * hf4; idx += kThreads) {
         const int r = idx / hf4, c4 = idx - r * hf4;
         if (r < nrows) {
-          const float4 v = *reinterpret_cast<const float4*>(bufH + r * ldh + 4 * c4);
+          const float4 v = *reinterpret_cast<const float4*>(Q + r * ld + 4 * c4);
           *reinterpret_cast<float4*>(a.Y + (t * a.N + vbase + r) * a.ldy + 4 * c4) = v;
           if (last) *reinterpret_cast<float4*>(a.HN + (sbase + r) * H + 4 * c4) = v;
         }
       }
+      float* tmp = P; P = Q; Q = tmp;
     }
   }
 
@@ -336,9 +340,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int lda, int
 
 template <int KIND, int NRB, int UPW>
 bool launch_k(const DenseArgs& a, hipStream_t st, std::string* why) {
-  const int Kp0 = ((a.K0 + 7) / 8) * 8;
-  const int lda = (Kp0 > a.S ? Kp0 : a.S) + 4;
-  const int ldh = a.H + 4;
+  const int ld = dense_ld(a.K0, a.S, KIND == DGC_TIME_NONE ? 0 : a.H);
   const size_t lds = dense_lds_bytes(a.K0, a.S, KIND == DGC_TIME_NONE ? 0 : a.H);
   static bool attr_done = false;  // per instantiation
   if (!attr_done) {
@@ -351,7 +353,7 @@ bool launch_k(const DenseArgs& a, hipStream_t st, std::string* why) {
     attr_done = true;
   }
   if (a.n_tiles > 0)
-    hipLaunchKernelGGL((k_dense<KIND, NRB, UPW>), (unsigned)a.n_tiles, kThreads, lds, st, a, lda, ldh);
+    hipLaunchKernelGGL((k_dense<KIND, NRB, UPW>), (unsigned)a.n_tiles, kThreads, lds, st, a, ld);
   return true;
 }
 
@@ -367,11 +369,17 @@ bool launch_kind(const DenseArgs& a, hipStream_t st, std::string* why) {
 
 }  // namespace
 
-size_t dense_lds_bytes(int32_t K0, int32_t S, int32_t H) {
+// common row stride of the two LDS buffers: widest of the three operands, +4 floats so that
+// float4 reads of 32 consecutive rows spread over the banks
+int dense_ld(int32_t K0, int32_t S, int32_t H) {
   const int Kp0 = ((K0 + 7) / 8) * 8;
-  const int lda = (Kp0 > S ? Kp0 : S) + 4;
-  const int ldh = H > 0 ? H + 4 : 0;
-  return sizeof(float) * (size_t)kTileRows * (lda + ldh) + sizeof(int) * kTileRows;
+  int m = Kp0 > S ? Kp0 : S;
+  if (H > m) m = H;
+  return m + 4;
+}
+
+size_t dense_lds_bytes(int32_t K0, int32_t S, int32_t H) {
+  return sizeof(float) * (size_t)kTileRows * 2 * dense_ld(K0, S, H) + sizeof(int) * kTileRows;
 }
 
 void launch_pack_weight(const float* W, int32_t n_out, int32_t n_in, float4* packed, hipStream_t st) {

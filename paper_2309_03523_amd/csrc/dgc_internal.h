@@ -141,5 +141,6 @@ struct DenseArgs {
 // returns false if the (S,H,K0) combination has no kernel
 bool launch_dense(const DenseArgs& a, hipStream_t st, std::string* why);
 size_t dense_lds_bytes(int32_t K0, int32_t S, int32_t H);
+int dense_ld(int32_t K0, int32_t S, int32_t H);
 
 }  // namespace dgc

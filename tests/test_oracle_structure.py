@@ -246,17 +246,22 @@ def test_worklist_rule():
     R, L, P = 4, 12, 5
     got = oracle.worklist(graph, chunks, R, L, P)
     short, long_ = [], []
+    seg_of = {}
     s = 0
-    for v_lo, v_hi, t_lo, t_hi in chunks.tolist():
+    for k, (v_lo, v_hi, t_lo, t_hi) in enumerate(chunks.tolist()):
         for t in range(t_lo, t_hi):
-            for r in range(0, v_hi - v_lo, R):
-                short.append((s, r, min(R, v_hi - v_lo - r)))
+            seg_of[(k, t)] = s
             deg = np.diff(graph.snaps[t].rowptr)
             for i in range(v_lo, v_hi):
                 if deg[i] > L:
                     parts = -(-int(deg[i]) // P)
                     long_ += [(s, i - v_lo, p, parts) for p in range(parts)]
             s += 1
+    for t in range(T):  # short list: snapshot by snapshot
+        for k, (v_lo, v_hi, t_lo, t_hi) in enumerate(chunks.tolist()):
+            if t_lo <= t < t_hi:
+                for r in range(0, v_hi - v_lo, R):
+                    short.append((seg_of[(k, t)], r, min(R, v_hi - v_lo - r)))
     assert got["work_short"].tolist() == [list(x) for x in short]
     assert got["work_long"].tolist() == [list(x) for x in long_]
     assert len(long_) > 0
