@@ -8,11 +8,13 @@
 // gate pre-activations and h never travel through HBM; h lives in LDS between steps.  All
 // chunks of the fused batch are tiles of the same launch.
 //
-// MFMA: v_mfma_f32_32x32x2f32.  Lane l supplies A[l%32][l/32] and B[l/32][l%32]; it receives
-// C[8*(v/4) + 4*(l/32) + v%4][l%32] in accumulator register v (0..15).  A operands (M, Z, h)
-// are read from LDS as float4 (four consecutive k per lane), B operands (weights) straight
-// from global memory / L2 in a pre-packed fragment order, so that every load is one contiguous
-// 1 KiB per wave and no LDS staging or barrier is needed for them.
+// MFMA: v_mfma_f32_32x32x2f32 computes D = A x B with lane l supplying A[l%32][l/32] and
+// B[l/32][l%32] and receiving D[8*(v/4) + 4*(l/32) + v%4][l%32] in accumulator register v.
+// The WEIGHTS are the A operand and the activations (M, Z, h) the B operand, so a lane ends up
+// with one activation row (l%32) and four consecutive output columns per register quad: Z and h
+// go back to the row-major LDS tile as float4.  Activations are read from LDS as float4 (four
+// consecutive k per lane); weights come straight from global memory / L2 in a pre-packed
+// fragment order, one contiguous 1 KiB per wave and load, with no LDS staging and no barrier.
 #include "dgc_internal.h"
 
 namespace dgc {
@@ -22,6 +24,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
+constexpr int kMaxPrefetch = 8;  // float4 per thread of the next step's aggregated rows
 
 __global__ void k_pack_weight(const float* W, int32_t n_out, int32_t n_in, float4* packed) {
   const int nkb = (n_in + 7) / 8;
@@ -40,46 +43,83 @@ __global__ void k_pack_weight(const float* W, int32_t n_out, int32_t n_in, float
   packed[idx] = make_float4(v[0], v[1], v[2], v[3]);
 }
 
-__device__ __forceinline__ float sigmoidf_(float x) { return 1.0f / (1.0f + expf(-x)); }
+// Gate non-linearities on the hardware exp2 / reciprocal units (about 1 ulp each): the
+// absolute error is ~1e-7, far inside the fp32 tolerance of the layer.
+__device__ __forceinline__ float sigmoid_fast(float x) { return __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
+__device__ __forceinline__ float tanh_fast(float x) { return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __expf(2.0f * x)); }
 
-// acc[rb][SLOTg] += A[rows of block rb][k] * W_g[cols][k], k over nkb blocks of 8.
-//  ldsA : LDS address of A[row l%32 of block 0][(l/32)*4]; block rb adds rb*32*lda
+__device__ __forceinline__ float f4get(const float4& v, int q) {
+  return q == 0 ? v.x : q == 1 ? v.y : q == 2 ? v.z : v.w;
+}
+
+// Visit every (row, float4 column) of a [64][wf4] tile once (wf4 <= 64), a whole row per half
+// wave or wave so that global accesses are contiguous; no integer division.
+template <class F>
+__device__ __forceinline__ void for_tile_f4(int tid, int wf4, F&& body) {
+  const int lane = tid & 63, wave = tid >> 6;
+  if (wf4 <= 32) {
+    const int c4 = lane & 31;
+    if (c4 < wf4)
+      for (int r = wave * 2 + (lane >> 5); r < kTileRows; r += 2 * kWaves) body(r, c4);
+  } else {
+    for (int r = wave; r < kTileRows; r += kWaves)
+      for (int c4 = lane; c4 < wf4; c4 += kWave) body(r, c4);
+  }
+}
+
+// Waves that are not issuing matrix instructions run at raised priority: their short VALU /
+// LDS / memory phases then are not starved by the other workgroup's MFMA stream on the same
+// SIMD, and they return to matrix work sooner.
+__device__ __forceinline__ void prio_matrix() { __builtin_amdgcn_s_setprio(0); }
+__device__ __forceinline__ void prio_other() { __builtin_amdgcn_s_setprio(2); }
+
+// One block of 8 k: acc[rb][slot g] += W_g (A operand) x activations (B operand).
+template <int NRB, int NG, int S0, int S1, int S2, int S3>
+__device__ __forceinline__ void mma_block(floatx16 (&acc)[NRB][4], const float4 (&w)[NG], const float4 (&x)[NRB]) {
+  constexpr int slot[4] = {S0, S1, S2, S3};
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+#pragma unroll
+      for (int rb = 0; rb < NRB; ++rb)
+        acc[rb][slot[g]] =
+            __builtin_amdgcn_mfma_f32_32x32x2f32(f4get(w[g], q), f4get(x[rb], q), acc[rb][slot[g]], 0, 0, 0);
+}
+
+// acc[rb][slot g] += X[rows of block rb][k] * W_g[cols][k], k over nkb blocks of 8.
+//  ldsX : LDS address of X[row l%32 of block 0][(l/32)*4]; block rb adds rb*32*ld
 //  wp[g]: packed weight fragments of gate g for this column block, already offset by lane;
 //         fragment kb is wp[g][kb*64]
+// Two register sets alternate so that the weight loads (L2 latency) of block kb+1 are in flight
+// while the 8*NG*NRB MFMAs of block kb issue.
 template <int NRB, int NG, int S0, int S1, int S2, int S3>
-__device__ __forceinline__ void mma_k_loop(floatx16 (&acc)[NRB][4], const float* ldsA, int lda, int nkb,
+__device__ __forceinline__ void mma_k_loop(floatx16 (&acc)[NRB][4], const float* ldsX, int ld, int nkb,
                                            const float4* const (&wp)[NG]) {
-  constexpr int slot[4] = {S0, S1, S2, S3};
-  float4 a_cur[NRB], b_cur[NG];
+  float4 w0[NG], w1[NG], x0[NRB], x1[NRB];
 #pragma unroll
-  for (int rb = 0; rb < NRB; ++rb) a_cur[rb] = *reinterpret_cast<const float4*>(ldsA + rb * 32 * lda);
+  for (int g = 0; g < NG; ++g) w0[g] = wp[g][0];
 #pragma unroll
-  for (int g = 0; g < NG; ++g) b_cur[g] = wp[g][0];
-  for (int kb = 0; kb < nkb; ++kb) {
-    float4 a_nxt[NRB], b_nxt[NG];
-    const int kn = kb + 1 < nkb ? kb + 1 : kb;
+  for (int rb = 0; rb < NRB; ++rb) x0[rb] = *reinterpret_cast<const float4*>(ldsX + rb * 32 * ld);
+  int kb = 0;
+  for (; kb + 1 < nkb; kb += 2) {
 #pragma unroll
-    for (int g = 0; g < NG; ++g) b_nxt[g] = wp[g][(int64_t)kn * 64];
+    for (int g = 0; g < NG; ++g) w1[g] = wp[g][(int64_t)(kb + 1) * 64];
 #pragma unroll
-    for (int rb = 0; rb < NRB; ++rb)
-      a_nxt[rb] = *reinterpret_cast<const float4*>(ldsA + rb * 32 * lda + kn * 8);
+    for (int rb = 0; rb < NRB; ++rb) x1[rb] = *reinterpret_cast<const float4*>(ldsX + rb * 32 * ld + (kb + 1) * 8);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_block<NRB, NG, S0, S1, S2, S3>(acc, w0, x0);
+    __builtin_amdgcn_sched_barrier(0);
+    const int kn = kb + 2 < nkb ? kb + 2 : nkb - 1;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
+    for (int g = 0; g < NG; ++g) w0[g] = wp[g][(int64_t)kn * 64];
 #pragma unroll
-      for (int g = 0; g < NG; ++g) {
-        const float bv = q == 0 ? b_cur[g].x : q == 1 ? b_cur[g].y : q == 2 ? b_cur[g].z : b_cur[g].w;
-#pragma unroll
-        for (int rb = 0; rb < NRB; ++rb) {
-          const float av = q == 0 ? a_cur[rb].x : q == 1 ? a_cur[rb].y : q == 2 ? a_cur[rb].z : a_cur[rb].w;
-          acc[rb][slot[g]] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[rb][slot[g]], 0, 0, 0);
-        }
-      }
-    }
-#pragma unroll
-    for (int rb = 0; rb < NRB; ++rb) a_cur[rb] = a_nxt[rb];
-#pragma unroll
-    for (int g = 0; g < NG; ++g) b_cur[g] = b_nxt[g];
+    for (int rb = 0; rb < NRB; ++rb) x0[rb] = *reinterpret_cast<const float4*>(ldsX + rb * 32 * ld + kn * 8);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_block<NRB, NG, S0, S1, S2, S3>(acc, w1, x1);
+    __builtin_amdgcn_sched_barrier(0);
   }
+  if (kb < nkb) mma_block<NRB, NG, S0, S1, S2, S3>(acc, w0, x0);
 }
 
 // KIND: DGC_TIME_*.  NRB: 32-row blocks per unit (1 or 2).  UPW: units per wave.
@@ -87,15 +127,18 @@ __device__ __forceinline__ void mma_k_loop(floatx16 (&acc)[NRB][4], const float*
 //
 // LDS holds two [64][ld] buffers that swap roles every step:
 //   P: the state h entering the step;   Q: the aggregated rows, then Z, then the new state.
-// Per step: load M -> Q and mask P | Z = act(Q W^T + b) in registers | Z -> Q | gate GEMMs read
-// Q and P | gate arithmetic writes the new h into Q | Q -> Y | swap(P, Q).
+// Per step: mask P | Z = act(Q W^T + b) in registers | Z -> Q | gate GEMMs read Q and P | the
+// next step's aggregated rows start loading into registers | gate arithmetic | new h -> Q and
+// the prefetched rows -> P | Q -> Y | swap(P, Q).
 template <int KIND, int NRB, int UPW>
 __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int ld) {
   extern __shared__ float smem[];
   float* P = smem;
   float* Q = smem + kTileRows * ld;
-  int* mask_row = reinterpret_cast<int*>(smem + 2 * kTileRows * ld);
+  int* mask_row = reinterpret_cast<int*>(smem + 2 * kTileRows * ld);   // [64]
+  float* gate_bias = smem + 2 * kTileRows * ld + kTileRows;            // [4][H]
 
+  prio_other();
   const DenseTile tile = a.tiles[blockIdx.x];
   const ChunkInfo ch = a.chunks[tile.chunk];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
@@ -108,6 +151,43 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int ld) {
   const int64_t V = a.total_state_rows;
   const int64_t vbase = ch.v_lo + tile.v0;            // first vertex of the tile
   const int64_t sbase = ch.state_off + tile.v0;       // first state row of the tile
+  const int nf4 = nkb0 * 2;                           // float4 per aggregated row in LDS
+  // The next step's rows are prefetched through registers when a row is a power-of-two number
+  // of float4 (K0 = 8..128): thread -> (row r0 + i*rpp, float4 column c4), no column masking.
+  const bool prefetch = KIND != DGC_TIME_NONE && K0 % 8 == 0 && (nf4 & (nf4 - 1)) == 0 && nf4 <= 32;
+  const int pf_c4 = tid & (nf4 - 1), pf_r0 = tid / nf4, pf_rpp = kThreads / nf4;
+
+  auto load_rows = [&](int s, float4 (&r)[kMaxPrefetch]) {
+    const float* src = a.M + (ch.row_off0 + (int64_t)s * ch.nv + tile.v0 + pf_r0) * a.ldm + 4 * pf_c4;
+#pragma unroll
+    for (int i = 0; i < kMaxPrefetch; ++i) {
+      const int row = pf_r0 + i * pf_rpp;
+      r[i] = row < nrows ? *reinterpret_cast<const float4*>(src + (int64_t)i * pf_rpp * a.ldm)
+                         : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  };
+  auto store_rows = [&](float* buf, const float4 (&r)[kMaxPrefetch]) {
+#pragma unroll
+    for (int i = 0; i < kMaxPrefetch; ++i) {
+      const int row = pf_r0 + i * pf_rpp;
+      if (row < kTileRows) *reinterpret_cast<float4*>(buf + row * ld + 4 * pf_c4) = r[i];
+    }
+  };
+  // the same, any width, straight to LDS
+  auto load_rows_direct = [&](int s, float* buf) {
+    const float* Mrow0 = a.M + (ch.row_off0 + (int64_t)s * ch.nv + tile.v0) * a.ldm;
+    for (int row = wave; row < kTileRows; row += kWaves) for (int c4 = lane; c4 < nf4; c4 += kWave) {
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (row < nrows && 4 * c4 < a.ldm) {
+        v = *reinterpret_cast<const float4*>(Mrow0 + (int64_t)row * a.ldm + 4 * c4);
+        if (4 * c4 + 1 >= K0) v.y = 0.f;
+        if (4 * c4 + 2 >= K0) v.z = 0.f;
+        if (4 * c4 + 3 >= K0) v.w = 0.f;
+        if (4 * c4 >= K0) v.x = 0.f;
+      }
+      *reinterpret_cast<float4*>(buf + row * ld + 4 * c4) = v;
+    }
+  };
 
   // LSTM cell state stays in registers, in accumulator layout, for the whole window
   float cst[UPW][NRB][16];
@@ -120,55 +200,52 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int ld) {
       for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const int row = (rb0 + rb) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-          const int col = jb * 32 + l32;
+          const int row = (rb0 + rb) * 32 + l32;
+          const int col = jb * 32 + 8 * (v / 4) + 4 * half + (v % 4);
           cst[ui][rb][v] = (a.H0 && u < unitsH && row < nrows) ? a.H0[(V + sbase + row) * H + col] : 0.f;
         }
     }
   }
   if constexpr (KIND != DGC_TIME_NONE) {
-    const int hf4 = H / 4;
-    for (int idx = tid; idx < kTileRows * hf4; idx += kThreads) {
-      const int r = idx / hf4, c4 = idx - r * hf4;
+    for_tile_f4(tid, H / 4, [&](int r, int c4) {
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
       if (a.H0 && r < nrows) v = *reinterpret_cast<const float4*>(a.H0 + (sbase + r) * H + 4 * c4);
       *reinterpret_cast<float4*>(P + r * ld + 4 * c4) = v;
+    });
+    // gate biases, pre-summed where the gate adds both: GRU rows r, z, n(input), n(hidden);
+    // LSTM rows i, f, g, o
+    for (int idx = tid; idx < 4 * H; idx += kThreads) {
+      const int g = idx / H, c = idx - g * H;
+      float b;
+      if (KIND == DGC_TIME_GRU) {
+        b = g < 2 ? a.bih[g * H + c] + a.bhh[g * H + c] : (g == 2 ? a.bih[2 * H + c] : a.bhh[2 * H + c]);
+      } else {
+        b = a.bih[g * H + c] + a.bhh[g * H + c];
+      }
+      gate_bias[idx] = b;
     }
   }
+  load_rows_direct(0, Q);
 
   for (int s = 0; s < ch.w; ++s) {
     const int64_t t = ch.t_lo + s;
-    // (a) aggregated rows of this step -> Q, zero beyond K0 and beyond nrows
-    {
-      const float* Mrow0 = a.M + (ch.row_off0 + (int64_t)s * ch.nv + tile.v0) * a.ldm;
-      const int nf4 = nkb0 * 2;
-      for (int idx = tid; idx < kTileRows * nf4; idx += kThreads) {
-        const int r = idx / nf4, c4 = idx - r * nf4;
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (r < nrows && 4 * c4 < a.ldm) {
-          v = *reinterpret_cast<const float4*>(Mrow0 + (int64_t)r * a.ldm + 4 * c4);
-          if (4 * c4 + 1 >= K0) v.y = 0.f;
-          if (4 * c4 + 2 >= K0) v.z = 0.f;
-          if (4 * c4 + 3 >= K0) v.w = 0.f;
-          if (4 * c4 >= K0) v.x = 0.f;
-        }
-        *reinterpret_cast<float4*>(Q + r * ld + 4 * c4) = v;
-      }
-    }
-    // (b) temporal-fusion mask: zero the incoming state of masked rows (same thread <-> element
-    //     mapping as the Y store at the end of the previous step, so no barrier in between)
+    if (s > 0 && !prefetch) load_rows_direct(s, Q);
+    // temporal-fusion mask: zero the incoming state of masked rows (same thread <-> element
+    // mapping as the Y store at the end of the previous step, so no barrier in between)
     if constexpr (KIND != DGC_TIME_NONE) {
-      const int hf4 = H / 4;
-      for (int idx = tid; idx < kTileRows * hf4; idx += kThreads) {
-        const int r = idx / hf4, c4 = idx - r * hf4;
-        const int mk = (a.reset_mask && r < nrows) ? a.reset_mask[t * a.N + vbase + r] : 0;
-        if (mk) *reinterpret_cast<float4*>(P + r * ld + 4 * c4) = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (c4 == 0) mask_row[r] = mk;
+      if (a.reset_mask) {
+        for_tile_f4(tid, H / 4, [&](int r, int c4) {
+          const int mk = r < nrows ? a.reset_mask[t * a.N + vbase + r] : 0;
+          if (mk) *reinterpret_cast<float4*>(P + r * ld + 4 * c4) = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (c4 == 0) mask_row[r] = mk;
+        });
+      } else if (s == 0 && tid < kTileRows) {
+        mask_row[tid] = 0;
       }
     }
     __syncthreads();
 
-    // (c) Z = act(M W^T + b) for this wave's units, kept in the accumulators over the barrier
+    // Z = act(M W^T + b) for this wave's units, kept in the accumulators over the barrier
     floatx16 zacc[UPW][NRB];
 #pragma unroll
     for (int ui = 0; ui < UPW; ++ui) {
@@ -179,7 +256,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int ld) {
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) acc[rb][0] = (floatx16)(0.f);
         const float4* const wp[1] = {a.Wg + ((int64_t)jb * nkb0) * 64 + lane};
+        prio_matrix();
         mma_k_loop<NRB, 1, 0, 0, 0, 0>(acc, Q + (rb0 * 32 + l32) * ld + half * 4, ld, nkb0, wp);
+        prio_other();
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) zacc[ui][rb] = acc[rb][0];
       }
@@ -190,41 +269,43 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int ld) {
       const int u = wave + kWaves * ui;
       if (u < unitsS) {
         const int jb = u / RBU, rb0 = (u % RBU) * NRB;
-        const float bias = a.bg[jb * 32 + l32];
 #pragma unroll
-        for (int rb = 0; rb < NRB; ++rb)
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const int c0 = jb * 32 + 8 * g4 + 4 * half;
+          const float4 bias = *reinterpret_cast<const float4*>(a.bg + c0);
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int row = (rb0 + rb) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-            float z = zacc[ui][rb][v] + bias;
-            if (a.act == DGC_ACT_RELU) z = fmaxf(z, 0.f);
-            Q[row * ld + jb * 32 + l32] = z;
+          for (int rb = 0; rb < NRB; ++rb) {
+            float4 z = make_float4(zacc[ui][rb][4 * g4 + 0] + bias.x, zacc[ui][rb][4 * g4 + 1] + bias.y,
+                                   zacc[ui][rb][4 * g4 + 2] + bias.z, zacc[ui][rb][4 * g4 + 3] + bias.w);
+            if (a.act == DGC_ACT_RELU) {
+              z.x = fmaxf(z.x, 0.f); z.y = fmaxf(z.y, 0.f); z.z = fmaxf(z.z, 0.f); z.w = fmaxf(z.w, 0.f);
+            }
+            *reinterpret_cast<float4*>(Q + ((rb0 + rb) * 32 + l32) * ld + c0) = z;
           }
+        }
       }
     }
     __syncthreads();
 
     if constexpr (KIND == DGC_TIME_NONE) {
-      const int sf4 = S / 4;
-      for (int idx = tid; idx < kTileRows * sf4; idx += kThreads) {
-        const int r = idx / sf4, c4 = idx - r * sf4;
+      for_tile_f4(tid, S / 4, [&](int r, int c4) {
         if (r < nrows)
           *reinterpret_cast<float4*>(a.Y + (t * a.N + vbase + r) * a.ldy + 4 * c4) =
               *reinterpret_cast<const float4*>(Q + r * ld + 4 * c4);
-      }
+      });
       __syncthreads();  // Q is overwritten by the next step's rows
     } else {
-      // (e) gate pre-activations.  With UPW > 1 a wave finishes unit after unit; the new state of
-      //     a unit can only be written once every wave has stopped reading Z and h, so the gate
-      //     values of earlier units wait in registers.
-      float hnew[UPW][NRB][16];
+      // Gate pre-activations and gate arithmetic, four consecutive columns at a time.  The new
+      // state can only be written once every wave has stopped reading Z and h, so it waits in
+      // registers over the barrier.
+      float4 hnew[UPW][NRB][4];
+      float4 mnext[kMaxPrefetch];
 #pragma unroll
       for (int ui = 0; ui < UPW; ++ui) {
         const int u = wave + kWaves * ui;
+        floatx16 acc[NRB][4];
+        const int jb = u / RBU, rb0 = (u % RBU) * NRB;
         if (u < unitsH) {
-          const int jb = u / RBU, rb0 = (u % RBU) * NRB;
-          const int col = jb * 32 + l32;
-          floatx16 acc[NRB][4];
 #pragma unroll
           for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
@@ -239,22 +320,10 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int ld) {
             const float4* const wh[3] = {a.Whh + ((int64_t)(0 * njbH + jb) * nkbH) * 64 + lane,
                                          a.Whh + ((int64_t)(1 * njbH + jb) * nkbH) * 64 + lane,
                                          a.Whh + ((int64_t)(2 * njbH + jb) * nkbH) * 64 + lane};
+            prio_matrix();
             mma_k_loop<NRB, 3, 0, 1, 2, 0>(acc, ldsZ, ld, nkbS, wi);
             mma_k_loop<NRB, 3, 0, 1, 3, 0>(acc, ldsHp, ld, nkbH, wh);
-            const float b_r = a.bih[col] + a.bhh[col];
-            const float b_z = a.bih[H + col] + a.bhh[H + col];
-            const float b_in = a.bih[2 * H + col], b_hn = a.bhh[2 * H + col];
-#pragma unroll
-            for (int rb = 0; rb < NRB; ++rb)
-#pragma unroll
-              for (int v = 0; v < 16; ++v) {
-                const int row = (rb0 + rb) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-                const float hp = P[row * ld + col];
-                const float r = sigmoidf_(acc[rb][0][v] + b_r);
-                const float z = sigmoidf_(acc[rb][1][v] + b_z);
-                const float n = tanhf(acc[rb][2][v] + b_in + r * (acc[rb][3][v] + b_hn));
-                hnew[ui][rb][v] = (1.0f - z) * n + z * hp;
-              }
+            prio_other();
           } else {
             // slots: 0 i, 1 f, 2 g, 3 o
             const float4* const wi[4] = {a.Wih + ((int64_t)(0 * njbH + jb) * nkbS) * 64 + lane,
@@ -265,28 +334,59 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int ld) {
                                          a.Whh + ((int64_t)(1 * njbH + jb) * nkbH) * 64 + lane,
                                          a.Whh + ((int64_t)(2 * njbH + jb) * nkbH) * 64 + lane,
                                          a.Whh + ((int64_t)(3 * njbH + jb) * nkbH) * 64 + lane};
+            prio_matrix();
             mma_k_loop<NRB, 4, 0, 1, 2, 3>(acc, ldsZ, ld, nkbS, wi);
             mma_k_loop<NRB, 4, 0, 1, 2, 3>(acc, ldsHp, ld, nkbH, wh);
-            float bsum[4];
+            prio_other();
+          }
+        }
+        if (u < unitsH) {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) bsum[g] = a.bih[g * H + col] + a.bhh[g * H + col];
+          for (int g4 = 0; g4 < 4; ++g4) {
+            const int c0 = jb * 32 + 8 * g4 + 4 * half;
+            float bs[4][4];
 #pragma unroll
-            for (int rb = 0; rb < NRB; ++rb)
+            for (int g = 0; g < 4; ++g) {
+              const float4 b = *reinterpret_cast<const float4*>(gate_bias + g * H + c0);
+              bs[g][0] = b.x; bs[g][1] = b.y; bs[g][2] = b.z; bs[g][3] = b.w;
+            }
 #pragma unroll
-              for (int v = 0; v < 16; ++v) {
-                const int row = (rb0 + rb) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-                const float cm = mask_row[row] ? 0.f : cst[ui][rb][v];
-                const float ig = sigmoidf_(acc[rb][0][v] + bsum[0]);
-                const float fg = sigmoidf_(acc[rb][1][v] + bsum[1]);
-                const float gg = tanhf(acc[rb][2][v] + bsum[2]);
-                const float og = sigmoidf_(acc[rb][3][v] + bsum[3]);
-                const float cn = fg * cm + ig * gg;
-                cst[ui][rb][v] = cn;
-                hnew[ui][rb][v] = og * tanhf(cn);
+            for (int rb = 0; rb < NRB; ++rb) {
+              float o[4];
+              if constexpr (KIND == DGC_TIME_GRU) {
+                const float4 hp4 = *reinterpret_cast<const float4*>(P + ((rb0 + rb) * 32 + l32) * ld + c0);
+                const float hp[4] = {hp4.x, hp4.y, hp4.z, hp4.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  const int v = 4 * g4 + e;
+                  const float r = sigmoid_fast(acc[rb][0][v] + bs[0][e]);
+                  const float z = sigmoid_fast(acc[rb][1][v] + bs[1][e]);
+                  const float n = tanh_fast(acc[rb][2][v] + bs[2][e] + r * (acc[rb][3][v] + bs[3][e]));
+                  o[e] = (1.0f - z) * n + z * hp[e];
+                }
+              } else {
+                const bool masked = mask_row[(rb0 + rb) * 32 + l32] != 0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  const int v = 4 * g4 + e;
+                  const float cm = masked ? 0.f : cst[ui][rb][v];
+                  const float ig = sigmoid_fast(acc[rb][0][v] + bs[0][e]);
+                  const float fg = sigmoid_fast(acc[rb][1][v] + bs[1][e]);
+                  const float gg = tanh_fast(acc[rb][2][v] + bs[2][e]);
+                  const float og = sigmoid_fast(acc[rb][3][v] + bs[3][e]);
+                  const float cn = fg * cm + ig * gg;
+                  cst[ui][rb][v] = cn;
+                  o[e] = og * tanh_fast(cn);
+                }
               }
+              hnew[ui][rb][g4] = make_float4(o[0], o[1], o[2], o[3]);
+            }
           }
         }
       }
+      // the accumulators are free: start fetching the next step's rows, so that their HBM latency
+      // hides behind the barriers and the Y store
+      if (prefetch && s + 1 < ch.w) load_rows(s + 1, mnext);
       __syncthreads();  // everyone has finished reading Z and the old state
 #pragma unroll
       for (int ui = 0; ui < UPW; ++ui) {
@@ -296,24 +396,23 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int ld) {
 #pragma unroll
           for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const int row = (rb0 + rb) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-              Q[row * ld + jb * 32 + l32] = hnew[ui][rb][v];
-            }
+            for (int g4 = 0; g4 < 4; ++g4)
+              *reinterpret_cast<float4*>(Q + ((rb0 + rb) * 32 + l32) * ld + jb * 32 + 8 * g4 + 4 * half) =
+                  hnew[ui][rb][g4];
         }
       }
       __syncthreads();
-      // (g) h_t -> Y, whole rows at a time; Q becomes the state buffer of the next step
-      const int hf4 = H / 4;
+      // h_t -> Y, whole rows at a time; Q becomes the state buffer of the next step
       const bool last = (s == ch.w - 1) && a.HN;
-      for (int idx = tid; idx < kTileRows * hf4; idx += kThreads) {
-        const int r = idx / hf4, c4 = idx - r * hf4;
+      for_tile_f4(tid, H / 4, [&](int r, int c4) {
         if (r < nrows) {
           const float4 v = *reinterpret_cast<const float4*>(Q + r * ld + 4 * c4);
           *reinterpret_cast<float4*>(a.Y + (t * a.N + vbase + r) * a.ldy + 4 * c4) = v;
           if (last) *reinterpret_cast<float4*>(a.HN + (sbase + r) * H + 4 * c4) = v;
         }
-      }
+      });
+      // P (the old state, no longer read) becomes the next step's Q
+      if (prefetch && s + 1 < ch.w) store_rows(P, mnext);
       float* tmp = P; P = Q; Q = tmp;
     }
   }
@@ -329,8 +428,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int ld) {
           for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-              const int row = (rb0 + rb) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-              if (row < nrows) a.HN[(V + sbase + row) * H + jb * 32 + l32] = cst[ui][rb][v];
+              const int row = (rb0 + rb) * 32 + l32;
+              const int col = jb * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+              if (row < nrows) a.HN[(V + sbase + row) * H + col] = cst[ui][rb][v];
             }
         }
       }
@@ -370,7 +470,7 @@ bool launch_kind(const DenseArgs& a, hipStream_t st, std::string* why) {
 }  // namespace
 
 // common row stride of the two LDS buffers: widest of the three operands, +4 floats so that
-// float4 reads of 32 consecutive rows spread over the banks
+// float4 accesses of 32 consecutive rows spread over the banks
 int dense_ld(int32_t K0, int32_t S, int32_t H) {
   const int Kp0 = ((K0 + 7) / 8) * 8;
   int m = Kp0 > S ? Kp0 : S;
@@ -379,7 +479,7 @@ int dense_ld(int32_t K0, int32_t S, int32_t H) {
 }
 
 size_t dense_lds_bytes(int32_t K0, int32_t S, int32_t H) {
-  return sizeof(float) * (size_t)kTileRows * 2 * dense_ld(K0, S, H) + sizeof(int) * kTileRows;
+  return sizeof(float) * ((size_t)kTileRows * 2 * dense_ld(K0, S, H) + kTileRows + 4 * (size_t)H);
 }
 
 void launch_pack_weight(const float* W, int32_t n_out, int32_t n_in, float4* packed, hipStream_t st) {
