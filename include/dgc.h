@@ -54,6 +54,12 @@ enum { DGC_DTYPE_F32 = 0 };
  *           per segment, Section 5.1.1) into a buffer that the aggregation then indexes
  *           through the packed local column ids. */
 enum { DGC_GATHER_IN_PLACE = 0, DGC_GATHER_STAGED = 1 };
+/* Which kernel runs the dense transform + time encoder:
+ *  AUTO  the wave-private kernel where it applies, else the workgroup-tile kernel;
+ *  TILE  64 vertices per workgroup, operands shared through LDS (any S, H up to 256);
+ *  WAVE  32 vertices per wavefront, hidden state kept in registers, no barriers
+ *        (S = H in {32, 64, 128}); DGC_ERR_UNSUPPORTED at forward otherwise. */
+enum { DGC_DENSE_AUTO = 0, DGC_DENSE_TILE = 1, DGC_DENSE_WAVE = 2 };
 
 /* A chunk: vertices [v_lo, v_hi) over snapshots [t_lo, t_hi). */
 typedef struct {
@@ -87,6 +93,7 @@ typedef struct {
   int32_t rows_per_group;  /* work list: rows per group (0 = default 16, at most 32)         */
   int32_t long_nnz;        /* work list: rows longer than this are split (0 = default 1024)  */
   int32_t part_nnz;        /* work list: non-zeros per part of a split row (0 = default 512) */
+  int32_t dense_kernel;    /* DGC_DENSE_*                                                    */
 } dgc_layer_desc_t;
 
 /* Build a layer for a fixed graph and a fixed set of chunks (the paper partitions once per

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libdgc.so")
 TIME_KIND = {"none": 0, "gru": 1, "lstm": 2}
 ACT = {"none": 0, "relu": 1}
 GATHER = {"in_place": 0, "staged": 1}
+DENSE = {"auto": 0, "tile": 1, "wave": 2}
 
 STATUS = {0: "DGC_OK", 1: "DGC_ERR_INVALID_ARG", 2: "DGC_ERR_BAD_GRAPH", 3: "DGC_ERR_BAD_CHUNK",
           4: "DGC_ERR_UNSUPPORTED", 5: "DGC_ERR_OOM", 6: "DGC_ERR_DEVICE", 7: "DGC_ERR_STATE"}
@@ -47,7 +48,8 @@ class GraphT(ct.Structure):
 class DescT(ct.Structure):
     _fields_ = [(n, ct.c_int32) for n in
                 ("struct_kind", "n_struct_layers", "time_kind", "dtype", "F", "S", "H", "act_hidden",
-                 "act_out", "gather_mode", "validate_level", "rows_per_group", "long_nnz", "part_nnz")]
+                 "act_out", "gather_mode", "validate_level", "rows_per_group", "long_nnz", "part_nnz",
+                 "dense_kernel")]
 
 
 _lib = None
@@ -127,7 +129,7 @@ class DgcLayer:
     def __init__(self, rowptr, colidx, N: int, chunks, *, F: int, S: int, H: int, time_kind: str = "gru",
                  n_struct_layers: int = 1, act_hidden: str = "relu", act_out: str = "none",
                  gather_mode: str = "in_place", validate_level: int = 0, rows_per_group: int = 0,
-                 long_nnz: int = 0, part_nnz: int = 0, stream=None):
+                 long_nnz: int = 0, part_nnz: int = 0, dense_kernel: str = "auto", stream=None):
         import torch
         lib = load()
         self._lib = lib
@@ -145,7 +147,7 @@ class DgcLayer:
         ch = np.asarray(chunks, np.int64).reshape(-1, 4)
         carr = (ChunkT * len(ch))(*[ChunkT(int(a), int(b), int(c), int(d)) for a, b, c, d in ch])
         desc = DescT(0, n_struct_layers, TIME_KIND[time_kind], 0, F, S, H, ACT[act_hidden], ACT[act_out],
-                     GATHER[gather_mode], validate_level, rows_per_group, long_nnz, part_nnz)
+                     GATHER[gather_mode], validate_level, rows_per_group, long_nnz, part_nnz, DENSE[dense_kernel])
         rc = lib.dgc_layer_create(ct.byref(desc), ct.byref(graph), carr, len(ch), _stream_ptr(stream),
                                   ct.byref(self._h))
         if rc:

@@ -39,6 +39,8 @@ struct dgc_layer {
   Segment* d_segs = nullptr;
   ChunkInfo* d_chunks = nullptr;
   DenseTile* d_tiles = nullptr;
+  DenseTile* d_tiles32 = nullptr;
+  int64_t n_tiles32 = 0;
   float* d_dinv = nullptr;
   int64_t* d_halo_ptr = nullptr;
   int32_t* d_halo_idx = nullptr;
@@ -117,6 +119,7 @@ dgc_status_t check_desc(const dgc_layer_desc_t& d, std::string* msg) {
   if (d.gather_mode != DGC_GATHER_IN_PLACE && d.gather_mode != DGC_GATHER_STAGED) { *msg = "unknown gather_mode"; return DGC_ERR_INVALID_ARG; }
   if (d.validate_level < 0 || d.validate_level > 1) { *msg = "validate_level must be 0 or 1"; return DGC_ERR_INVALID_ARG; }
   if (d.rows_per_group < 0 || d.rows_per_group > 32) { *msg = "rows_per_group must be in [0,32]"; return DGC_ERR_INVALID_ARG; }
+  if (d.dense_kernel < DGC_DENSE_AUTO || d.dense_kernel > DGC_DENSE_WAVE) { *msg = "unknown dense_kernel"; return DGC_ERR_INVALID_ARG; }
   if (d.long_nnz < 0 || d.part_nnz < 0) { *msg = "long_nnz / part_nnz must be >= 0"; return DGC_ERR_INVALID_ARG; }
   return DGC_OK;
 }
@@ -302,12 +305,19 @@ dgc_status_t build_layer(dgc_layer* L, const dgc_graph_t* graph, hipStream_t st)
     L->n_tiles = (int64_t)tiles.size();
     DGC_HIP_TRY(dev_alloc(L, &L->d_tiles, L->n_tiles));
     DGC_HIP_TRY(hipMemcpyAsync(L->d_tiles, tiles.data(), sizeof(DenseTile) * tiles.size(), hipMemcpyHostToDevice, st));
+    std::vector<DenseTile> tiles32;
+    for (int32_t k = 0; k < L->n_chunks; ++k)
+      for (int64_t v0 = 0; v0 < cinfo[k].nv; v0 += kWaveTileRows)
+        tiles32.push_back(DenseTile{k, (int32_t)v0, (int32_t)std::min<int64_t>(kWaveTileRows, cinfo[k].nv - v0), 0});
+    L->n_tiles32 = (int64_t)tiles32.size();
+    DGC_HIP_TRY(dev_alloc(L, &L->d_tiles32, L->n_tiles32));
+    DGC_HIP_TRY(hipMemcpyAsync(L->d_tiles32, tiles32.data(), sizeof(DenseTile) * tiles32.size(), hipMemcpyHostToDevice, st));
     DGC_HIP_TRY(hipStreamSynchronize(st));
   }
 
   // workspace
   const int32_t Fmax = std::max(d.F, d.n_struct_layers == 2 ? d.S : 0);
-  L->ldm = (Fmax + 3) / 4 * 4;
+  L->ldm = (Fmax + 7) / 8 * 8;  // whole k-blocks of 8; the aggregation zero-fills the pad columns
   DGC_HIP_TRY(dev_alloc(L, &L->d_M, L->total_rows * L->ldm));
   DGC_HIP_TRY(dev_alloc(L, &L->d_partial, L->n_long * L->ldm));
   if (d.gather_mode == DGC_GATHER_STAGED) {
@@ -474,8 +484,8 @@ dgc_status_t dgc_layer_aggregate(dgc_layer_t* L, const float* X, int64_t ldx, co
   if ((rc = check_tensor(fail, "X", X, ldx, L->desc.F, true)) != DGC_OK) return rc;
   if ((rc = check_tensor(fail, "C", C, ldc, L->desc.F, true)) != DGC_OK) return rc;
   if ((rc = check_tensor(fail, "M", M, ldm, L->desc.F, true)) != DGC_OK) return rc;
-  // the split-row scratch and the staged halo buffer are sized for pitch round_up(F,4)
-  if (ldm > L->ldm) return fail(DGC_ERR_INVALID_ARG, "M: pitch must not exceed round_up(F,4)");
+  // the split-row scratch and the staged halo buffer are sized for pitch round_up(F,8)
+  if (ldm > L->ldm) return fail(DGC_ERR_INVALID_ARG, "M: pitch must not exceed round_up(F,8)");
   run_aggregate(L, X, ldx, C, ldc, L->desc.F, M, ldm, static_cast<hipStream_t>(stream));
   DGC_HIP_TRY(hipGetLastError());
   return DGC_OK;
@@ -513,6 +523,7 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* L, const float* X, int64_t ldx, cons
 
   DenseArgs da{};
   da.tiles = L->d_tiles; da.n_tiles = L->n_tiles; da.chunks = L->d_chunks;
+  da.tiles32 = L->d_tiles32; da.n_tiles32 = L->n_tiles32; da.variant = d.dense_kernel;
   da.N = L->N; da.total_state_rows = L->total_state_rows;
   da.M = L->d_M; da.ldm = L->ldm;
   da.S = d.S; da.H = d.H;

@@ -489,6 +489,11 @@ void launch_pack_weight(const float* W, int32_t n_out, int32_t n_in, float4* pac
 }
 
 bool launch_dense(const DenseArgs& a, hipStream_t st, std::string* why) {
+  if (a.variant != DGC_DENSE_TILE && dense_wave_supported(a)) return launch_dense_wave(a, st, why);
+  if (a.variant == DGC_DENSE_WAVE) {
+    if (why) *why = "the wave-private dense kernel needs S = H in {32, 64, 128}";
+    return false;
+  }
   if (a.S % 32 || (a.time_kind != DGC_TIME_NONE && a.H % 32)) {
     if (why) *why = "S and H must be multiples of 32";
     return false;

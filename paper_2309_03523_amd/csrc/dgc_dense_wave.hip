@@ -1,0 +1,370 @@
+// Dense part of the layer, wave-private variant (S = H = 32, 64 or 128): one WAVEFRONT owns 32
+// vertices of a chunk and walks the chunk's window alone.  Rows of the GEMMs are independent,
+// so nothing is shared between waves: there is no workgroup barrier and no cross-wave LDS
+// traffic anywhere in the recurrence.
+//
+// With the weights as the MFMA's A operand and the activations as its B operand
+// (v_mfma_f32_32x32x2f32: lane l supplies A[l%32][l/32], B[l/32][l%32]; receives
+// D[8*(v/4) + 4*(l/32) + v%4][l%32] in register v), a lane receives, for activation row l%32,
+// the output columns 8*g4 + 4*(l/32) + e (g4, e = 0..3) of a 32-column block in registers
+// 4*g4 + e.  Read as the B operand of the NEXT product, the same lane has to supply
+// X[row l%32][k = 8*kb + 4*(l/32) + q]: the very same registers (kb = g4, q = e).  So the hidden
+// state h never leaves the registers between steps, and the gate arithmetic is elementwise in
+// that layout.  Z = act(M W^T + b) makes one trip through a wave-private LDS tile (it would
+// cost another 16*NJB registers), the aggregated rows M are read straight from global memory
+// as B operands, and the weights stream from L2 in pre-packed fragment order.
+#include "dgc_internal.h"
+
+namespace dgc {
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kRows = kWaveTileRows;  // 32
+constexpr int kXAhead = 4;            // k-blocks of aggregated rows in flight (HBM latency)
+
+__device__ __forceinline__ float sigmoid_fast(float x) { return __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
+__device__ __forceinline__ float tanh_fast(float x) { return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __expf(2.0f * x)); }
+__device__ __forceinline__ float f4get(const float4& v, int q) { return q == 0 ? v.x : q == 1 ? v.y : q == 2 ? v.z : v.w; }
+__device__ __forceinline__ float4 zero4() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+
+// acc[g] += W_g(k-block) x X(k-block) for NG weight fragments sharing one activation fragment
+template <int NG>
+__device__ __forceinline__ void mma8(floatx16 (&acc)[NG], const float4 (&w)[NG], const float4& x) {
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+      acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(f4get(w[g], q), f4get(x, q), acc[g], 0, 0, 0);
+}
+
+// wp[g]: wave-uniform base of gate g's fragments; fragment kb of this lane is wp[g][kb*64 + lane].
+// Keeping the base uniform lets the load use a scalar base register plus one small vector
+// offset instead of a 64-bit vector address per load.
+typedef int intx4 __attribute__((ext_vector_type(4)));
+
+// Weights are fetched with buffer loads: one 128-bit resource descriptor per matrix in scalar
+// registers, the lane's 16-byte slot as the only vector offset, and the fragment's position
+// (gate, column block, k-block) as a scalar byte offset.  No 64-bit vector address exists, so
+// the unrolled loops below do not drown in address registers.
+struct WeightStream {
+  __amdgpu_buffer_rsrc_t rsrc;
+  __device__ __forceinline__ float4 frag(int lane16, int soff_bytes) const {
+    const intx4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane16, soff_bytes, 0);
+    return make_float4(__int_as_float(v.x), __int_as_float(v.y), __int_as_float(v.z), __int_as_float(v.w));
+  }
+};
+__device__ __forceinline__ WeightStream make_stream(const float4* p, int64_t bytes) {
+  WeightStream w;
+  w.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float4*>(p), 0, (int)bytes, 0x00020000);
+  return w;
+}
+
+// fragment kb of NG gates; soff[g] = byte offset of gate g's fragment 0 (wave-uniform)
+template <int NG>
+__device__ __forceinline__ void load_w(float4 (&w)[NG], const WeightStream& ws, const int (&soff)[NG], int kb,
+                                       int lane16) {
+#pragma unroll
+  for (int g = 0; g < NG; ++g) w[g] = ws.frag(lane16, soff[g] + kb * 1024);
+}
+
+// K loop with the activation fragments in LDS (row l%32 of a [32][ldz] tile, float4 at k).
+template <int NG, int NKB>
+__device__ __forceinline__ void k_loop_lds(floatx16 (&acc)[NG], const float* ldsX, const WeightStream& ws,
+                                           const int (&soff)[NG], int lane16) {
+  static_assert(NKB % 2 == 0, "");
+  float4 w0[NG], w1[NG], x0, x1;
+  load_w<NG>(w0, ws, soff, 0, lane16);
+  x0 = *reinterpret_cast<const float4*>(ldsX);
+#pragma unroll
+  for (int kb = 0; kb < NKB; kb += 2) {
+    load_w<NG>(w1, ws, soff, kb + 1, lane16);
+    x1 = *reinterpret_cast<const float4*>(ldsX + (kb + 1) * 8);
+    __builtin_amdgcn_sched_barrier(0);
+    mma8<NG>(acc, w0, x0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (kb + 2 < NKB) {
+      load_w<NG>(w0, ws, soff, kb + 2, lane16);
+      x0 = *reinterpret_cast<const float4*>(ldsX + (kb + 2) * 8);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    mma8<NG>(acc, w1, x1);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// K loop with the activation fragments in registers: x[kb] for kb = 0..NKB-1 (NKB even).
+template <int NG, int NKB>
+__device__ __forceinline__ void k_loop_reg(floatx16 (&acc)[NG], const float4 (&x)[NKB], const WeightStream& ws,
+                                           const int (&soff)[NG], int lane16) {
+  static_assert(NKB % 2 == 0, "");
+  float4 w0[NG], w1[NG];
+  load_w<NG>(w0, ws, soff, 0, lane16);
+#pragma unroll
+  for (int kb = 0; kb < NKB; kb += 2) {
+    load_w<NG>(w1, ws, soff, kb + 1, lane16);
+    __builtin_amdgcn_sched_barrier(0);
+    mma8<NG>(acc, w0, x[kb]);
+    __builtin_amdgcn_sched_barrier(0);
+    if (kb + 2 < NKB) load_w<NG>(w0, ws, soff, kb + 2, lane16);
+    __builtin_amdgcn_sched_barrier(0);
+    mma8<NG>(acc, w1, x[kb + 1]);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// KIND: DGC_TIME_*;  NJB = S/32 = H/32.
+template <int KIND, int NJB>
+__global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dense_wave(DenseArgs a) {
+  // LDS, private to this wave (the workgroup is one wave):
+  //   zbuf [32][ldz] the Z tile | gbias [4][H] gate biases, pre-summed | zbias [S]
+  // (biases are read from LDS inside the step loop: as global loads they would be hoisted out
+  //  of it and held in hundreds of registers)
+  extern __shared__ __align__(16) float zbuf[];
+  constexpr int H = NJB * 32;
+  constexpr int NKB = NJB * 4;     // k-blocks of 8 over S or H
+  constexpr int ldz = H + 4;       // +4 floats: float4 accesses of 32 rows spread over the banks
+  float* gbias = zbuf + (KIND == DGC_TIME_NONE ? 0 : kRows * ldz);
+  float* zbias = gbias + (KIND == DGC_TIME_NONE ? 0 : 4 * H);
+  for (int i = threadIdx.x; i < H; i += kWave) {
+    zbias[i] = a.bg[i];
+    if constexpr (KIND == DGC_TIME_GRU) {
+      gbias[i] = a.bih[i] + a.bhh[i];
+      gbias[H + i] = a.bih[H + i] + a.bhh[H + i];
+      gbias[2 * H + i] = a.bih[2 * H + i];
+      gbias[3 * H + i] = a.bhh[2 * H + i];
+    }
+    if constexpr (KIND == DGC_TIME_LSTM) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) gbias[g * H + i] = a.bih[g * H + i] + a.bhh[g * H + i];
+    }
+  }
+  __syncthreads();
+
+  const DenseTile tile = a.tiles32[blockIdx.x];
+  const ChunkInfo ch = a.chunks[tile.chunk];
+  const int lane = threadIdx.x, l32 = lane & 31, half = lane >> 5;
+  const int nrows = tile.nrows;
+  const bool valid = l32 < nrows;
+  const int row = valid ? l32 : nrows - 1;   // rows past the tile's end recompute its last row; never stored
+  const int lane16 = lane * 16;
+  const int K0 = a.K0, nkb0 = (K0 + 7) / 8;
+  const WeightStream wsg = make_stream(a.Wg, (int64_t)NJB * nkb0 * 1024);
+  const WeightStream wsi = make_stream(a.Wih, (int64_t)(KIND == DGC_TIME_LSTM ? 4 : 3) * NJB * NKB * 1024);
+  const WeightStream wsh = make_stream(a.Whh, (int64_t)(KIND == DGC_TIME_LSTM ? 4 : 3) * NJB * NKB * 1024);
+  const int64_t V = a.total_state_rows;
+  const int64_t vrow = ch.v_lo + tile.v0 + row;          // this lane's vertex
+  const int64_t srow = ch.state_off + tile.v0 + row;     // this lane's state row
+
+  // state: h[kb] = columns 8*kb + 4*half .. +3 of this lane's row  (kb = 4*jb + g4)
+  float4 h[NKB], c[NKB];
+#pragma unroll
+  for (int kb = 0; kb < NKB; ++kb) {
+    h[kb] = zero4();
+    c[kb] = zero4();
+    if constexpr (KIND != DGC_TIME_NONE) {
+      if (a.H0) {
+        h[kb] = *reinterpret_cast<const float4*>(a.H0 + srow * H + 8 * kb + 4 * half);
+        if constexpr (KIND == DGC_TIME_LSTM)
+          c[kb] = *reinterpret_cast<const float4*>(a.H0 + (V + srow) * H + 8 * kb + 4 * half);
+      }
+    }
+  }
+
+  for (int s = 0; s < ch.w; ++s) {
+    const int64_t t = ch.t_lo + s;
+    // aggregated rows as B operand, straight from global memory: float4 at column 8*kb + 4*half
+    const float* mrow = a.M + (ch.row_off0 + (int64_t)s * ch.nv + tile.v0 + row) * a.ldm + 4 * half;
+    // (the library's M buffer has a pitch that is a multiple of 8 with zero pad columns, so a
+    //  k-block never needs masking)
+    auto load_x = [&](int kb) -> float4 { return *reinterpret_cast<const float4*>(mrow + 8 * kb); };
+    float4 xq[kXAhead];
+#pragma unroll
+    for (int i = 0; i < kXAhead; ++i) xq[i] = i < nkb0 ? load_x(i) : zero4();
+
+    // temporal-fusion mask on the incoming state (Section 5.1.2)
+    if constexpr (KIND != DGC_TIME_NONE) {
+      if (a.reset_mask && a.reset_mask[t * a.N + vrow]) {
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb) { h[kb] = zero4(); c[kb] = zero4(); }
+      }
+    }
+
+    // Z = act(M W^T + b): all NJB column blocks at once, they share the activation fragment
+    floatx16 zacc[NJB];
+#pragma unroll
+    for (int jb = 0; jb < NJB; ++jb) zacc[jb] = (floatx16)(0.f);
+    {
+      int soff[NJB];
+#pragma unroll
+      for (int jb = 0; jb < NJB; ++jb) soff[jb] = jb * nkb0 * 1024;
+      float4 w0[NJB], w1[NJB];
+      load_w<NJB>(w0, wsg, soff, 0, lane16);
+      for (int kb = 0; kb < nkb0; kb += kXAhead) {
+#pragma unroll
+        for (int i = 0; i < kXAhead; i += 2) {
+          // uniform guards: nkb0 need not be a multiple of kXAhead
+          if (kb + i < nkb0) {
+            load_w<NJB>(w1, wsg, soff, kb + i + 1 < nkb0 ? kb + i + 1 : kb + i, lane16);
+            const float4 x = xq[i];
+            if (kb + i + kXAhead < nkb0) xq[i] = load_x(kb + i + kXAhead);
+            __builtin_amdgcn_sched_barrier(0);
+            mma8<NJB>(zacc, w0, x);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          if (kb + i + 1 < nkb0) {
+            load_w<NJB>(w0, wsg, soff, kb + i + 2 < nkb0 ? kb + i + 2 : kb + i + 1, lane16);
+            const float4 x = xq[i + 1];
+            if (kb + i + 1 + kXAhead < nkb0) xq[i + 1] = load_x(kb + i + 1 + kXAhead);
+            __builtin_amdgcn_sched_barrier(0);
+            mma8<NJB>(zacc, w1, x);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+      }
+    }
+    float4 z[NKB];
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb) {
+      const float4 b = *reinterpret_cast<const float4*>(zbias + 8 * kb + 4 * half);
+      const int jb = kb / 4, g4 = kb % 4;
+      z[kb] = make_float4(zacc[jb][4 * g4 + 0] + b.x, zacc[jb][4 * g4 + 1] + b.y, zacc[jb][4 * g4 + 2] + b.z,
+                          zacc[jb][4 * g4 + 3] + b.w);
+      if (a.act == DGC_ACT_RELU) {
+        z[kb].x = fmaxf(z[kb].x, 0.f); z[kb].y = fmaxf(z[kb].y, 0.f);
+        z[kb].z = fmaxf(z[kb].z, 0.f); z[kb].w = fmaxf(z[kb].w, 0.f);
+      }
+    }
+
+    if constexpr (KIND == DGC_TIME_NONE) {
+      if (valid) {
+        float* y = a.Y + (t * a.N + vrow) * a.ldy + 4 * half;
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb) *reinterpret_cast<float4*>(y + 8 * kb) = z[kb];
+      }
+    } else {
+      // Z -> wave-private LDS tile (frees its registers for the gate accumulators)
+#pragma unroll
+      for (int kb = 0; kb < NKB; ++kb) *reinterpret_cast<float4*>(zbuf + l32 * ldz + 8 * kb + 4 * half) = z[kb];
+      __syncthreads();  // one wave: orders the LDS writes before the reads below
+      const float* ldsZ = zbuf + l32 * ldz + 4 * half;
+
+      float4 hn[NKB], cn[NKB];
+      constexpr int NG = KIND == DGC_TIME_GRU ? 3 : 4;
+#pragma unroll
+      for (int jb = 0; jb < NJB; ++jb) {
+        // GRU slots: 0 r, 1 z, 2 input part of n, 3 hidden part of n.  LSTM: i, f, g, o.
+        floatx16 acc[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) acc[g] = (floatx16)(0.f);
+        int soff[NG];
+#pragma unroll
+        for (int g = 0; g < NG; ++g) soff[g] = (g * NJB + jb) * NKB * 1024;
+        if constexpr (KIND == DGC_TIME_GRU) {
+          floatx16 ai[3] = {acc[0], acc[1], acc[2]};   // r, z, input part of n
+          k_loop_lds<3, NKB>(ai, ldsZ, wsi, soff, lane16);
+          floatx16 ah[3] = {ai[0], ai[1], acc[3]};     // r, z, hidden part of n
+          k_loop_reg<3, NKB>(ah, h, wsh, soff, lane16);
+          acc[0] = ah[0]; acc[1] = ah[1]; acc[2] = ai[2]; acc[3] = ah[2];
+        } else {
+          k_loop_lds<4, NKB>(acc, ldsZ, wsi, soff, lane16);
+          k_loop_reg<4, NKB>(acc, h, wsh, soff, lane16);
+        }
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const int kb = 4 * jb + g4, c0 = 8 * kb + 4 * half;
+          float o[4], oc[4];
+          float bs[4][4];
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const float4 b = *reinterpret_cast<const float4*>(gbias + g * H + c0);
+            bs[g][0] = b.x; bs[g][1] = b.y; bs[g][2] = b.z; bs[g][3] = b.w;
+          }
+          if constexpr (KIND == DGC_TIME_GRU) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int v = 4 * g4 + e;
+              const float r = sigmoid_fast(acc[0][v] + bs[0][e]);
+              const float zg = sigmoid_fast(acc[1][v] + bs[1][e]);
+              const float n = tanh_fast(acc[2][v] + bs[2][e] + r * (acc[3][v] + bs[3][e]));
+              o[e] = (1.0f - zg) * n + zg * f4get(h[kb], e);
+              oc[e] = 0.f;
+            }
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int v = 4 * g4 + e;
+              const float ig = sigmoid_fast(acc[0][v] + bs[0][e]);
+              const float fg = sigmoid_fast(acc[1][v] + bs[1][e]);
+              const float gg = tanh_fast(acc[2][v] + bs[2][e]);
+              const float og = sigmoid_fast(acc[3][v] + bs[3][e]);
+              oc[e] = fg * f4get(c[kb], e) + ig * gg;
+              o[e] = og * tanh_fast(oc[e]);
+            }
+          }
+          hn[kb] = make_float4(o[0], o[1], o[2], o[3]);
+          cn[kb] = make_float4(oc[0], oc[1], oc[2], oc[3]);
+        }
+      }
+      __syncthreads();  // the Z tile is rewritten in the next step
+      // h_t -> Y; the new state replaces the old one in place (same register layout)
+      float* y = a.Y + (t * a.N + vrow) * a.ldy + 4 * half;
+#pragma unroll
+      for (int kb = 0; kb < NKB; ++kb) {
+        h[kb] = hn[kb];
+        if constexpr (KIND == DGC_TIME_LSTM) c[kb] = cn[kb];
+        if (valid) *reinterpret_cast<float4*>(y + 8 * kb) = hn[kb];
+      }
+    }
+  }
+
+  if constexpr (KIND != DGC_TIME_NONE) {
+    if (a.HN && valid) {
+#pragma unroll
+      for (int kb = 0; kb < NKB; ++kb) {
+        *reinterpret_cast<float4*>(a.HN + srow * H + 8 * kb + 4 * half) = h[kb];
+        if constexpr (KIND == DGC_TIME_LSTM)
+          *reinterpret_cast<float4*>(a.HN + (V + srow) * H + 8 * kb + 4 * half) = c[kb];
+      }
+    }
+  }
+}
+
+template <int KIND, int NJB>
+bool launch_w(const DenseArgs& a, hipStream_t st, std::string* why) {
+  (void)why;
+  constexpr int ldz = NJB * 32 + 4;
+  const size_t lds = sizeof(float) * ((KIND == DGC_TIME_NONE ? 0 : kRows * ldz + 4 * NJB * 32) + NJB * 32);
+  if (a.n_tiles32 > 0)
+    hipLaunchKernelGGL((k_dense_wave<KIND, NJB>), (unsigned)a.n_tiles32, kWave, lds, st, a);
+  return true;
+}
+
+template <int KIND>
+bool launch_wk(const DenseArgs& a, hipStream_t st, std::string* why) {
+  switch (a.S / 32) {
+    case 1: return launch_w<KIND, 1>(a, st, why);
+    case 2: return launch_w<KIND, 2>(a, st, why);
+    case 4: return launch_w<KIND, 4>(a, st, why);
+  }
+  return false;
+}
+
+}  // namespace
+
+bool dense_wave_supported(const DenseArgs& a) {
+  const bool s_ok = a.S == 32 || a.S == 64 || a.S == 128;
+  const bool m_ok = a.ldm % 8 == 0 && a.ldm >= (a.K0 + 7) / 8 * 8;  // whole k-blocks, zero padded
+  return s_ok && m_ok && (a.time_kind == DGC_TIME_NONE || a.H == a.S);
+}
+
+bool launch_dense_wave(const DenseArgs& a, hipStream_t st, std::string* why) {
+  switch (a.time_kind) {
+    case DGC_TIME_NONE: return launch_wk<DGC_TIME_NONE>(a, st, why);
+    case DGC_TIME_GRU: return launch_wk<DGC_TIME_GRU>(a, st, why);
+    case DGC_TIME_LSTM: return launch_wk<DGC_TIME_LSTM>(a, st, why);
+  }
+  return false;
+}
+
+}  // namespace dgc

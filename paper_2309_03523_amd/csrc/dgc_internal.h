@@ -12,7 +12,8 @@
 namespace dgc {
 
 constexpr int kWave = 64;
-constexpr int kTileRows = 64;  // rows of one dense tile (two 32-row MFMA blocks)
+constexpr int kTileRows = 64;      // rows of one tile of the workgroup-tile dense kernel
+constexpr int kWaveTileRows = 32;  // rows of one tile of the wave-private dense kernel
 
 // One (chunk, snapshot) pair of the fused batch.
 struct Segment {
@@ -118,8 +119,11 @@ inline int64_t packed_weight_elems(int32_t n_out, int32_t n_in) {
 }
 
 struct DenseArgs {
-  const DenseTile* tiles;
+  const DenseTile* tiles;       // 64-row tiles
   int64_t n_tiles;
+  const DenseTile* tiles32;     // 32-row tiles
+  int64_t n_tiles32;
+  int32_t variant;              // DGC_DENSE_*
   const ChunkInfo* chunks;
   int64_t N;
   int64_t total_state_rows;     // V = sum of chunk vertex counts
@@ -140,6 +144,8 @@ struct DenseArgs {
 };
 // returns false if the (S,H,K0) combination has no kernel
 bool launch_dense(const DenseArgs& a, hipStream_t st, std::string* why);
+bool dense_wave_supported(const DenseArgs& a);
+bool launch_dense_wave(const DenseArgs& a, hipStream_t st, std::string* why);
 size_t dense_lds_bytes(int32_t K0, int32_t S, int32_t H);
 int dense_ld(int32_t K0, int32_t S, int32_t H);
 

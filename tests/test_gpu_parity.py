@@ -115,15 +115,18 @@ def _compare_layer(torch, wl, dw, mask=None, **okw):
     return err
 
 
+@pytest.mark.parametrize("dense", ["auto", "tile"])
 @pytest.mark.parametrize("kind", ["gru", "lstm", "none"])
-@pytest.mark.parametrize("F,S,H", [(32, 32, 32), (20, 64, 32), (128, 128, 128), (172, 128, 128), (40, 96, 160),
-                                   (64, 256, 256)])
-def test_layer_matches_oracle(torch_mod, kind, F, S, H):
+@pytest.mark.parametrize("F,S,H", [(32, 32, 32), (20, 64, 32), (77, 64, 64), (128, 128, 128), (172, 128, 128),
+                                   (40, 96, 160), (64, 256, 256)])
+def test_layer_matches_oracle(torch_mod, kind, F, S, H, dense):
+    """dense = auto runs the wave-private kernel where it applies (S = H in {32, 64, 128}) and the
+    workgroup-tile kernel elsewhere; dense = tile forces the latter everywhere."""
     N, T = 203, 5
     # ragged tiles (vertex counts 1, 63, 65, 74), windows of different length, a gap in coverage
     chunks = [[0, 1, 0, 5], [1, 64, 0, 2], [1, 64, 2, 5], [64, 129, 0, 5], [129, 203, 1, 4]]
     wl = synth.random_small(100 + F + S + H, T, N, F, S, H, 5.0, chunks, kind, hub=True)
-    dw = _dw(wl, rows_per_group=7, long_nnz=32, part_nnz=9)
+    dw = _dw(wl, rows_per_group=7, long_nnz=32, part_nnz=9, dense_kernel=dense)
     _compare_layer(torch_mod, wl, dw)
     if kind != "none":
         mask = (synth.stream(5, "mask").random((T, N)) < 0.3).astype(np.uint8)
