@@ -68,13 +68,20 @@ __device__ __forceinline__ void load_w(float4 (&w)[NG], const WeightStream& ws, 
   for (int g = 0; g < NG; ++g) w[g] = ws.frag(lane16, soff[g] + kb * 1024);
 }
 
+// The K loops below are chained: each one starts with its fragment 0 already in flight (wq,
+// requested by the loop before it) and, in its last pair of k-blocks, requests fragment 0 of
+// the loop that follows (ws_next / soff_next).  So the L2 latency of a loop's first weights
+// hides behind the tail of the previous loop and the gate arithmetic in between.
+
 // K loop with the activation fragments in LDS (row l%32 of a [32][ldz] tile, float4 at k).
-template <int NG, int NKB>
+template <int NG, int NKB, int NGN>
 __device__ __forceinline__ void k_loop_lds(floatx16 (&acc)[NG], const float* ldsX, const WeightStream& ws,
-                                           const int (&soff)[NG], int lane16) {
-  static_assert(NKB % 2 == 0, "");
+                                           const int (&soff)[NG], int lane16, float4 (&wq)[4],
+                                           const WeightStream& ws_next, const int (&soff_next)[NGN]) {
+  static_assert(NKB % 2 == 0 && NG <= 4 && NGN <= 4, "");
   float4 w0[NG], w1[NG], x0, x1;
-  load_w<NG>(w0, ws, soff, 0, lane16);
+#pragma unroll
+  for (int g = 0; g < NG; ++g) w0[g] = wq[g];
   x0 = *reinterpret_cast<const float4*>(ldsX);
 #pragma unroll
   for (int kb = 0; kb < NKB; kb += 2) {
@@ -86,6 +93,9 @@ __device__ __forceinline__ void k_loop_lds(floatx16 (&acc)[NG], const float* lds
     if (kb + 2 < NKB) {
       load_w<NG>(w0, ws, soff, kb + 2, lane16);
       x0 = *reinterpret_cast<const float4*>(ldsX + (kb + 2) * 8);
+    } else {
+#pragma unroll
+      for (int g = 0; g < NGN; ++g) wq[g] = ws_next.frag(lane16, soff_next[g]);
     }
     __builtin_amdgcn_sched_barrier(0);
     mma8<NG>(acc, w1, x1);
@@ -94,19 +104,26 @@ __device__ __forceinline__ void k_loop_lds(floatx16 (&acc)[NG], const float* lds
 }
 
 // K loop with the activation fragments in registers: x[kb] for kb = 0..NKB-1 (NKB even).
-template <int NG, int NKB>
+template <int NG, int NKB, int NGN>
 __device__ __forceinline__ void k_loop_reg(floatx16 (&acc)[NG], const float4 (&x)[NKB], const WeightStream& ws,
-                                           const int (&soff)[NG], int lane16) {
-  static_assert(NKB % 2 == 0, "");
+                                           const int (&soff)[NG], int lane16, float4 (&wq)[4],
+                                           const WeightStream& ws_next, const int (&soff_next)[NGN]) {
+  static_assert(NKB % 2 == 0 && NG <= 4 && NGN <= 4, "");
   float4 w0[NG], w1[NG];
-  load_w<NG>(w0, ws, soff, 0, lane16);
+#pragma unroll
+  for (int g = 0; g < NG; ++g) w0[g] = wq[g];
 #pragma unroll
   for (int kb = 0; kb < NKB; kb += 2) {
     load_w<NG>(w1, ws, soff, kb + 1, lane16);
     __builtin_amdgcn_sched_barrier(0);
     mma8<NG>(acc, w0, x[kb]);
     __builtin_amdgcn_sched_barrier(0);
-    if (kb + 2 < NKB) load_w<NG>(w0, ws, soff, kb + 2, lane16);
+    if (kb + 2 < NKB) {
+      load_w<NG>(w0, ws, soff, kb + 2, lane16);
+    } else {
+#pragma unroll
+      for (int g = 0; g < NGN; ++g) wq[g] = ws_next.frag(lane16, soff_next[g]);
+    }
     __builtin_amdgcn_sched_barrier(0);
     mma8<NG>(acc, w1, x[kb + 1]);
     __builtin_amdgcn_sched_barrier(0);
@@ -171,16 +188,40 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
     }
   }
 
+  // Aggregated rows as B operand, straight from global memory: float4 at column 8*kb + 4*half of
+  // this lane's row.  (The library's M buffer has a pitch that is a multiple of 8 with zero pad
+  // columns, so a k-block never needs masking.)
+  const float* mrow0 = a.M + (ch.row_off0 + tile.v0 + row) * a.ldm + 4 * half;
+  const int64_t mstep = ch.nv * a.ldm;
+  float4 xq[kXAhead];
+#pragma unroll
+  for (int i = 0; i < kXAhead; ++i) xq[i] = i < nkb0 ? *reinterpret_cast<const float4*>(mrow0 + 8 * i) : zero4();
+  // fragment 0 of the next K loop's weights (see k_loop_lds)
+  int soffg[NJB];
+#pragma unroll
+  for (int jb = 0; jb < NJB; ++jb) soffg[jb] = jb * nkb0 * 1024;
+  float4 wq[4];
+#pragma unroll
+  for (int jb = 0; jb < NJB; ++jb) wq[jb] = wsg.frag(lane16, soffg[jb]);
+
   for (int s = 0; s < ch.w; ++s) {
     const int64_t t = ch.t_lo + s;
-    // aggregated rows as B operand, straight from global memory: float4 at column 8*kb + 4*half
-    const float* mrow = a.M + (ch.row_off0 + (int64_t)s * ch.nv + tile.v0 + row) * a.ldm + 4 * half;
-    // (the library's M buffer has a pitch that is a multiple of 8 with zero pad columns, so a
-    //  k-block never needs masking)
+    const float* mrow = mrow0 + s * mstep;
     auto load_x = [&](int kb) -> float4 { return *reinterpret_cast<const float4*>(mrow + 8 * kb); };
-    float4 xq[kXAhead];
+    if (s > 0) {
 #pragma unroll
-    for (int i = 0; i < kXAhead; ++i) xq[i] = i < nkb0 ? load_x(i) : zero4();
+      for (int i = 0; i < kXAhead; ++i)
+        if (i < nkb0) xq[i] = load_x(i);
+      // h_{t-1} -> Y, issued after the loads above: memory operations retire in order, so loads
+      // issued behind these stores would wait for them
+      if constexpr (KIND != DGC_TIME_NONE) {
+        if (valid) {
+          float* y = a.Y + ((t - 1) * a.N + vrow) * a.ldy + 4 * half;
+#pragma unroll
+          for (int kb = 0; kb < NKB; ++kb) *reinterpret_cast<float4*>(y + 8 * kb) = h[kb];
+        }
+      }
+    }
 
     // temporal-fusion mask on the incoming state (Section 5.1.2)
     if constexpr (KIND != DGC_TIME_NONE) {
@@ -195,11 +236,10 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
 #pragma unroll
     for (int jb = 0; jb < NJB; ++jb) zacc[jb] = (floatx16)(0.f);
     {
-      int soff[NJB];
-#pragma unroll
-      for (int jb = 0; jb < NJB; ++jb) soff[jb] = jb * nkb0 * 1024;
+      const int (&soff)[NJB] = soffg;
       float4 w0[NJB], w1[NJB];
-      load_w<NJB>(w0, wsg, soff, 0, lane16);
+#pragma unroll
+      for (int jb = 0; jb < NJB; ++jb) w0[jb] = wq[jb];
       for (int kb = 0; kb < nkb0; kb += kXAhead) {
 #pragma unroll
         for (int i = 0; i < kXAhead; i += 2) {
@@ -222,6 +262,14 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
           }
         }
       }
+    }
+    constexpr int NG = KIND == DGC_TIME_LSTM ? 4 : 3;
+    if constexpr (KIND == DGC_TIME_NONE) {
+#pragma unroll
+      for (int jb = 0; jb < NJB; ++jb) wq[jb] = wsg.frag(lane16, soffg[jb]);   // next step's first weights
+    } else {
+#pragma unroll
+      for (int g = 0; g < NG; ++g) wq[g] = wsi.frag(lane16, (g * NJB) * NKB * 1024);  // gates of column block 0
     }
     float4 z[NKB];
 #pragma unroll
@@ -250,7 +298,6 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
       const float* ldsZ = zbuf + l32 * ldz + 4 * half;
 
       float4 hn[NKB], cn[NKB];
-      constexpr int NG = KIND == DGC_TIME_GRU ? 3 : 4;
 #pragma unroll
       for (int jb = 0; jb < NJB; ++jb) {
         // GRU slots: 0 r, 1 z, 2 input part of n, 3 hidden part of n.  LSTM: i, f, g, o.
@@ -260,15 +307,22 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
         int soff[NG];
 #pragma unroll
         for (int g = 0; g < NG; ++g) soff[g] = (g * NJB + jb) * NKB * 1024;
+        // what follows the hidden-state loop: the next column block's gates, or the next
+        // step's transform
+        int soff_next[NG];
+#pragma unroll
+        for (int g = 0; g < NG; ++g) soff_next[g] = (g * NJB + jb + 1) * NKB * 1024;
         if constexpr (KIND == DGC_TIME_GRU) {
           floatx16 ai[3] = {acc[0], acc[1], acc[2]};   // r, z, input part of n
-          k_loop_lds<3, NKB>(ai, ldsZ, wsi, soff, lane16);
+          k_loop_lds<3, NKB, 3>(ai, ldsZ, wsi, soff, lane16, wq, wsh, soff);
           floatx16 ah[3] = {ai[0], ai[1], acc[3]};     // r, z, hidden part of n
-          k_loop_reg<3, NKB>(ah, h, wsh, soff, lane16);
+          if (jb + 1 < NJB) k_loop_reg<3, NKB, 3>(ah, h, wsh, soff, lane16, wq, wsi, soff_next);
+          else k_loop_reg<3, NKB, NJB>(ah, h, wsh, soff, lane16, wq, wsg, soffg);
           acc[0] = ah[0]; acc[1] = ah[1]; acc[2] = ai[2]; acc[3] = ah[2];
         } else {
-          k_loop_lds<4, NKB>(acc, ldsZ, wsi, soff, lane16);
-          k_loop_reg<4, NKB>(acc, h, wsh, soff, lane16);
+          k_loop_lds<4, NKB, 4>(acc, ldsZ, wsi, soff, lane16, wq, wsh, soff);
+          if (jb + 1 < NJB) k_loop_reg<4, NKB, 4>(acc, h, wsh, soff, lane16, wq, wsi, soff_next);
+          else k_loop_reg<4, NKB, NJB>(acc, h, wsh, soff, lane16, wq, wsg, soffg);
         }
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
@@ -307,18 +361,22 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
         }
       }
       __syncthreads();  // the Z tile is rewritten in the next step
-      // h_t -> Y; the new state replaces the old one in place (same register layout)
-      float* y = a.Y + (t * a.N + vrow) * a.ldy + 4 * half;
+      // the new state replaces the old one in place (same register layout); it is written to Y
+      // at the top of the next step, behind that step's first loads
 #pragma unroll
       for (int kb = 0; kb < NKB; ++kb) {
         h[kb] = hn[kb];
         if constexpr (KIND == DGC_TIME_LSTM) c[kb] = cn[kb];
-        if (valid) *reinterpret_cast<float4*>(y + 8 * kb) = hn[kb];
       }
     }
   }
 
   if constexpr (KIND != DGC_TIME_NONE) {
+    if (valid) {  // the last step's output
+      float* y = a.Y + ((int64_t)(ch.t_lo + ch.w - 1) * a.N + vrow) * a.ldy + 4 * half;
+#pragma unroll
+      for (int kb = 0; kb < NKB; ++kb) *reinterpret_cast<float4*>(y + 8 * kb) = h[kb];
+    }
     if (a.HN && valid) {
 #pragma unroll
       for (int kb = 0; kb < NKB; ++kb) {

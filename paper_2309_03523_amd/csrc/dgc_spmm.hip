@@ -31,11 +31,18 @@ __device__ __forceinline__ void vload(float (&v)[VEC], const float* p) {
   }
 }
 
+// Output rows are written once and read later by another kernel: streaming stores, so that
+// they do not push the neighbour rows being re-read out of L2.
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 template <int VEC>
 __device__ __forceinline__ void vstore(float* p, const float (&v)[VEC]) {
-  if constexpr (VEC == 1) { *p = v[0]; }
-  if constexpr (VEC == 2) { *reinterpret_cast<float2*>(p) = make_float2(v[0], v[1]); }
-  if constexpr (VEC == 4) { *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]); }
+  if constexpr (VEC == 1) { __builtin_nontemporal_store(v[0], p); }
+  if constexpr (VEC == 2) { floatx2 t = {v[0], v[1]}; __builtin_nontemporal_store(t, reinterpret_cast<floatx2*>(p)); }
+  if constexpr (VEC == 4) {
+    floatx4 t = {v[0], v[1], v[2], v[3]};
+    __builtin_nontemporal_store(t, reinterpret_cast<floatx4*>(p));
+  }
 }
 
 __device__ __forceinline__ int64_t readlane64(int64_t v, int lane) {
@@ -65,9 +72,9 @@ __device__ __forceinline__ void accumulate_edges(const RowCtx& c, int64_t ea, in
     int j = 0, loc = 0;
     float wj = 0.f;
     if (lane < m) {
-      j = c.cj[eb0 + lane];
+      j = __builtin_nontemporal_load(c.cj + eb0 + lane);  // streamed once
       wj = c.dinv_t[j];
-      if constexpr (STAGED) loc = c.cl[eb0 - c.e0 + lane];
+      if constexpr (STAGED) loc = __builtin_nontemporal_load(c.cl + (eb0 - c.e0) + lane);
     }
     for (int k = 0; k < m; k += kInflight) {
       float v[kInflight][VEC];
