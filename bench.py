@@ -59,6 +59,18 @@ def flops_per_row(wl) -> dict:
     return {"transform": dense, "rnn": rnn}
 
 
+def measured_traffic(workload: str, gather_mode: str) -> dict:
+    """HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two separate runs of
+    this script, scaled by a plain copy of known size; figures and commands in profiles/).  They
+    cannot be collected inside a timed run, so they are read from the committed summary."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(f"{workload}/{gather_mode}", {})
+    except (OSError, ValueError):
+        return {}
+
+
 def cpu_baseline(wl, Y_gpu, target_seconds: float, seed: int) -> dict:
     """Time the CPU oracle on a seeded sample of vertices of every chunk (all snapshots of the
     chunk's window), sized from a short calibration run to about target_seconds.  Also returns
@@ -85,13 +97,16 @@ def cpu_baseline(wl, Y_gpu, target_seconds: float, seed: int) -> dict:
                        n_struct_layers=wl.n_struct_layers, C1=wl.C1, H0=wl.H0, subset=sub, Y=Y)
         return Y, time.perf_counter() - t0
 
-    sub = sample(32)
-    _, dt = run(sub)
-    rows_cal = sum(len(s) * int(w) for s, w in zip(sub, windows))
-    rate = rows_cal / max(dt, 1e-6)
-    per_chunk = int(max(4, min(widths.max(), target_seconds * rate / max(1, int(windows.sum())))))
-    sub = sample(per_chunk)
-    Y, dt = run(sub)
+    # grow the sample until one run takes about target_seconds (at most three tries)
+    per_chunk = 32
+    for _ in range(3):
+        sub = sample(per_chunk)
+        Y, dt = run(sub)
+        if dt >= 0.5 * target_seconds or per_chunk >= widths.max():
+            break
+        rows_now = sum(len(s) * int(w) for s, w in zip(sub, windows))
+        rate = rows_now / max(dt, 1e-6)
+        per_chunk = int(max(per_chunk + 1, min(widths.max(), target_seconds * rate / max(1, int(windows.sum())))))
     rows = sum(len(s) * int(w) for s, w in zip(sub, windows))
     mask = ~np.isnan(Y)
     want = Y[mask].astype(np.float64)
@@ -167,9 +182,10 @@ def main():
         (2 * wl.S * wl.S + fl["rnn"]) * rows
     dense_ms = float(stage[3])
     achieved = dense_flops / (dense_ms * 1e-3) / 1e12
-    roofline = {"kernel": "k_dense (GCN transform + GRU gates, fused over the window)", "bound": "mfma",
-                "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+    traffic = measured_traffic(args.workload, args.gather_mode)
+    roofline = {"kernel": "k_dense_wave / k_dense (GCN transform + time encoder, fused over the window)",
+                "bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic.get("dense"),
                 "flops_per_launch": dense_flops, "ms_per_launch": dense_ms}
     # aggregation kernels: algorithmic (compulsory) bytes = X rows once + CSR + M written once
     nnz = int(layer.packing("seg_nnz_off")[-1])
@@ -177,7 +193,7 @@ def main():
     agg_ms = float(stage[0])
     agg = {"kernel": "k_spmm_short + k_spmm_long + k_spmm_long_reduce", "bound": "hbm",
            "achieved": agg_bytes / (agg_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-           "frac": agg_bytes / (agg_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None,
+           "frac": agg_bytes / (agg_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": traffic.get("aggregation"),
            "bytes_per_launch": agg_bytes, "ms_per_launch": agg_ms,
            "gather_traffic_GBs": nnz * wl.F * 4 / (agg_ms * 1e-3) / 1e9, "nnz": nnz}
 
