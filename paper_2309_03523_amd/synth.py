@@ -290,6 +290,41 @@ def config2(seed: int = 0, scale: float = 1.0, random_bias: bool = False) -> Wor
                                "config2" if scale == 1.0 else f"config2@{scale:g}", random_bias)
 
 
+def config3(seed: int = 0, scale: float = 1.0, windows: int = 1, random_bias: bool = False) -> Workload:
+    """Large 2-layer GCN + LSTM: N = 2,000,000 * scale vertices, mean degree 20 with tail exponent
+    2.0, per-snapshot density varying 10x along a sinusoid of period 128 snapshots times
+    (1 + 0.1 N(0,1)), F = 172, S = H = 128, windows of 32 snapshots x 64 uneven vertex ranges;
+    an edge keeps both endpoints inside one vertex range with probability 0.85.  The full
+    config (128 snapshots) is run one 32-snapshot window at a time (memory-capped fusion,
+    Section 5.1.1); `windows` says how many of them this workload holds."""
+    N = max(256, int(2_000_000 * scale))
+    T = 32 * windows
+    F, S, H = 172, 128, 128
+    g_rng = stream(seed, "graph")
+    w = powerlaw_weights(N, 2.0, stream(seed, "perm"))
+    r_rng = stream(seed, "ranges")
+    bounds = [uneven_ranges(N, 64, r_rng) for _ in range(windows)]
+    t_all = np.arange(128)
+    dens = 10.0 ** (0.5 * np.sin(2 * np.pi * t_all / 128.0)) * (1.0 + 0.1 * g_rng.standard_normal(128))
+    dens = np.clip(dens, 0.05, None)
+    dens /= dens.mean()
+    snaps = []
+    for t in range(T):
+        n_edges = int(10 * N * dens[t])          # mean degree 20 = 2 * edges / N
+        snaps.append(chung_lu_blocked_snapshot(N, n_edges, w, bounds[t // 32], 0.85, g_rng))
+    graph = DynamicGraph(N, snaps)
+    chunks = grid_chunks(T, 32, bounds)
+    X = _normal_f32(stream(seed, "feat"), (T, N, F))
+    C = _normal_f32(stream(seed, "cache"), (T, N, F))
+    C *= np.float32(0.1)
+    C += X
+    C1 = _normal_f32(stream(seed, "cache1"), (T, N, S))
+    wl = Workload("config3" if scale == 1.0 else f"config3@{scale:g}", graph, chunks, F, S, H, "lstm", 2, X, C, C1,
+                  _h0_for(chunks, H, "lstm", stream(seed, "h0")),
+                  layer_params(seed, F, S, H, "lstm", 2, random_bias))
+    return wl
+
+
 def random_small(seed: int, T: int, N: int, F: int, S: int, H: int, avg_deg: float,
                  chunks: np.ndarray, time_kind: str = "gru", n_struct_layers: int = 1,
                  hub: bool = False) -> Workload:

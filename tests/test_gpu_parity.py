@@ -175,6 +175,15 @@ def test_config2_scaled(torch_mod):
     dw.layer.destroy()
 
 
+def test_config3_scaled(torch_mod):
+    """Config 3's layer (2 GCN layers, ReLU between them, LSTM; F = 172, S = H = 128; 64 uneven
+    ranges x a 32-snapshot window; 85 % of edge draws inside a range) at 1/200 of its vertex count."""
+    wl = synth.config3(seed=0, scale=0.005, random_bias=True)
+    dw = _dw(wl, act_hidden="relu", act_out="none")
+    _compare_layer(torch_mod, wl, dw, act_hidden="relu", act_out="none")
+    dw.layer.destroy()
+
+
 def test_config2_full_size(torch_mod):
     """Config 2 at full size, in the launch configuration bench.py times: packing bit-exact
     against the oracle's packer; outputs compared on a seeded sample of vertices of every chunk
