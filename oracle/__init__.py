@@ -195,3 +195,39 @@ def forward(graph, chunks, params: dict, X: np.ndarray, C: np.ndarray, *, time_k
     if rc:
         raise ValueError(f"dgc_oracle_forward failed: {rc}")
     return (Y, hN) if return_state else Y
+
+
+EVOLVE_PARAMS = ["evolve.W_init", "evolve.U_z", "evolve.V_z", "evolve.B_z", "evolve.U_r", "evolve.V_r",
+                 "evolve.B_r", "evolve.U_h", "evolve.V_h", "evolve.B_h"]
+
+
+def evolve(graph, chunks, params: dict, X: np.ndarray, C: np.ndarray, target: Optional[np.ndarray] = None,
+           want_grads: bool = False, Y: Optional[np.ndarray] = None):
+    """EvolveGCN-O layer: weights evolved by a matrix GRU, Y = relu(M W_t), mean-squared-error loss.
+    Returns dict(Y, loss, grads {name: float64 array}, Wt [T,F,S])."""
+    g = _Csr(graph)
+    ch = _chunks(chunks)
+    T, N = g.T, g.N
+    P = [np.ascontiguousarray(params[k], np.float64) for k in EVOLVE_PARAMS]
+    F, S = P[0].shape
+    assert X.shape == (T, N, F) and C.shape == (T, N, F)
+    parr = (ct.POINTER(ct.c_double) * 10)(*[_p(a, ct.c_double) for a in P])
+    if Y is None:
+        Y = np.full((T, N, S), np.nan, np.float32)
+    grads = [np.zeros_like(a) for a in P] if want_grads else None
+    garr = (ct.POINTER(ct.c_double) * 10)(*[_p(a, ct.c_double) for a in grads]) if want_grads else None
+    Wt = np.zeros((T, F, S), np.float64)
+    loss = ct.c_double(0.0)
+    if target is not None:
+        target = np.ascontiguousarray(target, np.float32)
+        assert target.shape == (T, N, S)
+    rc = lib().dgc_oracle_evolve(
+        ct.c_int32(T), ct.c_int64(N), g.rowptr, g.col, _p(ch, ct.c_int64), ct.c_int32(len(ch)), ct.c_int32(F),
+        ct.c_int32(S), _p(X, ct.c_float), ct.c_int64(X.strides[1] // 4), _p(C, ct.c_float),
+        ct.c_int64(C.strides[1] // 4), parr, _p(target, ct.c_float),
+        ct.c_int64(target.strides[1] // 4 if target is not None else 0), _p(Y, ct.c_float),
+        ct.c_int64(Y.strides[1] // 4), ct.byref(loss), garr, _p(Wt, ct.c_double))
+    if rc:
+        raise ValueError(f"dgc_oracle_evolve failed: {rc}")
+    return {"Y": Y, "loss": loss.value, "Wt": Wt,
+            "grads": dict(zip(EVOLVE_PARAMS, grads)) if want_grads else None}

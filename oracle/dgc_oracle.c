@@ -359,3 +359,160 @@ int dgc_oracle_threads(void) {
   return 1;
 #endif
 }
+
+/* ================================================================ EvolveGCN-O layer
+ * The paper names EvolveGCN among the DGNNs it targets (Section 1) without defining it; the
+ * definition used here is the "-O" variant of the work it cites: the GCN weight matrix is
+ * itself the state of a matrix GRU and evolves from snapshot to snapshot,
+ *     Zg = sig(Uz W + Vz W + Bz)        Rg = sig(Ur W + Vr W + Br)
+ *     Wc = tanh(Uh W + Vh (Rg * W) + Bh)   W' = (1 - Zg) * W + Zg * Wc        (* elementwise)
+ * with W = W_{t-1} [F][S] (W_{-1} = W_init), U., V. [F][F], B. [F][S]; the input of the GRU is
+ * the state itself.  Note the reset gate multiplies W BEFORE Vh (unlike the vertex GRU above).
+ * The weights are global: W_t is evolved over all T snapshots whatever the chunk windows are.
+ *     Y[t,i] = relu(M[t,i] W_t),  M = the chunked, cache-reading aggregation defined above.
+ * Loss: mean squared error against targets over all covered (t, i, s).
+ * Parameters are passed as one array P of 10 matrices in the order
+ *   W_init, Uz, Vz, Bz, Ur, Vr, Br, Uh, Vh, Bh      (row-major, double). */
+enum { EV_W = 0, EV_UZ, EV_VZ, EV_BZ, EV_UR, EV_VR, EV_BR, EV_UH, EV_VH, EV_BH, EV_NPAR };
+
+static int64_t ev_size(int k, int32_t F, int32_t S) {
+  return (k == EV_W || k == EV_BZ || k == EV_BR || k == EV_BH) ? (int64_t)F * S : (int64_t)F * F;
+}
+
+/* C[F][S] (+)= op(A)[F][F] * B[F][S];  ta: use A transposed */
+static void mm_fs(const double *A, const double *B, double *C, int32_t F, int32_t S, int ta, int add) {
+#pragma omp parallel for
+  for (int32_t i = 0; i < F; ++i)
+    for (int32_t j = 0; j < S; ++j) {
+      double acc = add ? C[(int64_t)i * S + j] : 0.0;
+      for (int32_t k = 0; k < F; ++k) acc += (ta ? A[(int64_t)k * F + i] : A[(int64_t)i * F + k]) * B[(int64_t)k * S + j];
+      C[(int64_t)i * S + j] = acc;
+    }
+}
+/* C[F][F] += A[F][S] * B[F][S]^T */
+static void mm_abt_add(const double *A, const double *B, double *C, int32_t F, int32_t S) {
+#pragma omp parallel for
+  for (int32_t i = 0; i < F; ++i)
+    for (int32_t j = 0; j < F; ++j) {
+      double acc = C[(int64_t)i * F + j];
+      for (int32_t k = 0; k < S; ++k) acc += A[(int64_t)i * S + k] * B[(int64_t)j * S + k];
+      C[(int64_t)i * F + j] = acc;
+    }
+}
+
+/* Evolve the weights: Wt [T][F][S]; optionally the gates Zg, Rg, Wc [T][F][S] (for backward). */
+static void ev_weights(int32_t T, int32_t F, int32_t S, const double *const *P, double *Wt, double *Zg,
+                       double *Rg, double *Wc) {
+  const int64_t n = (int64_t)F * S;
+  double *z = (double *)malloc(sizeof(double) * n), *r = (double *)malloc(sizeof(double) * n);
+  double *c = (double *)malloc(sizeof(double) * n), *rw = (double *)malloc(sizeof(double) * n);
+  for (int32_t t = 0; t < T; ++t) {
+    const double *W = t ? Wt + (int64_t)(t - 1) * n : P[EV_W];
+    mm_fs(P[EV_UZ], W, z, F, S, 0, 0); mm_fs(P[EV_VZ], W, z, F, S, 0, 1);
+    mm_fs(P[EV_UR], W, r, F, S, 0, 0); mm_fs(P[EV_VR], W, r, F, S, 0, 1);
+    for (int64_t e = 0; e < n; ++e) {
+      z[e] = sigmoid(z[e] + P[EV_BZ][e]);
+      r[e] = sigmoid(r[e] + P[EV_BR][e]);
+      rw[e] = r[e] * W[e];
+    }
+    mm_fs(P[EV_UH], W, c, F, S, 0, 0); mm_fs(P[EV_VH], rw, c, F, S, 0, 1);
+    for (int64_t e = 0; e < n; ++e) {
+      c[e] = tanh(c[e] + P[EV_BH][e]);
+      Wt[(int64_t)t * n + e] = (1.0 - z[e]) * W[e] + z[e] * c[e];
+      if (Zg) { Zg[(int64_t)t * n + e] = z[e]; Rg[(int64_t)t * n + e] = r[e]; Wc[(int64_t)t * n + e] = c[e]; }
+    }
+  }
+  free(z); free(r); free(c); free(rw);
+}
+
+/* Forward (Y, loss) and, if grads != NULL, the gradient of the loss w.r.t. the 10 parameter
+ * matrices (grads: array of 10 double arrays, overwritten).  Wt_out (optional): [T][F][S].
+ * target may be NULL (then loss = 0 and no backward).  Returns 0 or <0. */
+int dgc_oracle_evolve(int32_t T, int64_t N, const int64_t *const *rowptr, const int32_t *const *col,
+                      const int64_t *chunks, int32_t n_chunks, int32_t F, int32_t S, const float *X,
+                      int64_t ldx, const float *C, int64_t ldc, const double *const *P,
+                      const float *target, int64_t ldt, float *Y, int64_t ldy, double *loss_out,
+                      double *const *grads, double *Wt_out) {
+  const int64_t n = (int64_t)F * S;
+  double *Wt = (double *)malloc(sizeof(double) * T * n);
+  double *Zg = (double *)malloc(sizeof(double) * T * n), *Rg = (double *)malloc(sizeof(double) * T * n);
+  double *Wc = (double *)malloc(sizeof(double) * T * n);
+  double *dWd = (double *)calloc((size_t)(T * n), sizeof(double)); /* direct gradient of each W_t */
+  if (!Wt || !Zg || !Rg || !Wc || !dWd) return -1;
+  ev_weights(T, F, S, P, Wt, Zg, Rg, Wc);
+  if (Wt_out) memcpy(Wt_out, Wt, sizeof(double) * T * n);
+  int64_t count = 0;
+  for (int32_t k = 0; k < n_chunks; ++k)
+    count += (CH_VHI(chunks, k) - CH_VLO(chunks, k)) * (CH_THI(chunks, k) - CH_TLO(chunks, k)) * S;
+  double loss = 0.0;
+  for (int32_t k = 0; k < n_chunks; ++k) {
+    const int64_t v_lo = CH_VLO(chunks, k), v_hi = CH_VHI(chunks, k);
+    if (v_lo < 0 || v_hi > N || v_lo >= v_hi || CH_TLO(chunks, k) < 0 || CH_THI(chunks, k) > T) return -2;
+    for (int64_t t = CH_TLO(chunks, k); t < CH_THI(chunks, k); ++t) {
+      const double *W = Wt + t * n;
+      double *dW = dWd + t * n;
+      double *m = (double *)malloc(sizeof(double) * (size_t)F);
+      double *dp = (double *)malloc(sizeof(double) * (size_t)S);
+      for (int64_t i = v_lo; i < v_hi; ++i) { /* serial: the dW sum is taken in row order */
+        aggregate_row(N, rowptr[t], col[t], t, i, v_lo, v_hi, X, ldx, NULL, C, ldc, F, m);
+        float *y = Y + (t * N + i) * ldy;
+        for (int32_t s = 0; s < S; ++s) {
+          double acc = 0.0;
+          for (int32_t f = 0; f < F; ++f) acc += m[f] * W[(int64_t)f * S + s];
+          const double out = acc > 0.0 ? acc : 0.0;
+          y[s] = (float)out;
+          dp[s] = 0.0;
+          if (target) {
+            const double d = out - (double)target[(t * N + i) * ldt + s];
+            loss += d * d;
+            dp[s] = acc > 0.0 ? 2.0 * d / (double)count : 0.0;
+          }
+        }
+        if (target && grads)
+          for (int32_t f = 0; f < F; ++f)
+            for (int32_t s = 0; s < S; ++s) dW[(int64_t)f * S + s] += m[f] * dp[s];
+      }
+      free(m); free(dp);
+    }
+  }
+  if (loss_out) *loss_out = target ? loss / (double)count : 0.0;
+  if (target && grads) {
+    /* back-propagation through time over the weight recurrence */
+    for (int k = 0; k < EV_NPAR; ++k) memset(grads[k], 0, sizeof(double) * (size_t)ev_size(k, F, S));
+    double *G = (double *)calloc((size_t)n, sizeof(double));   /* dL/dW_t, total */
+    double *dWp = (double *)malloc(sizeof(double) * n), *dAz = (double *)malloc(sizeof(double) * n);
+    double *dAr = (double *)malloc(sizeof(double) * n), *dAh = (double *)malloc(sizeof(double) * n);
+    double *rw = (double *)malloc(sizeof(double) * n), *tmp = (double *)malloc(sizeof(double) * n);
+    for (int32_t t = T - 1; t >= 0; --t) {
+      const double *Wp = t ? Wt + (int64_t)(t - 1) * n : P[EV_W];
+      const double *z = Zg + (int64_t)t * n, *r = Rg + (int64_t)t * n, *c = Wc + (int64_t)t * n;
+      for (int64_t e = 0; e < n; ++e) {
+        G[e] += dWd[(int64_t)t * n + e];
+        const double dz = G[e] * (c[e] - Wp[e]), dc = G[e] * z[e];
+        dWp[e] = G[e] * (1.0 - z[e]);
+        dAh[e] = dc * (1.0 - c[e] * c[e]);
+        dAz[e] = dz * z[e] * (1.0 - z[e]);
+        rw[e] = r[e] * Wp[e];
+      }
+      mm_abt_add(dAh, Wp, grads[EV_UH], F, S);
+      mm_abt_add(dAh, rw, grads[EV_VH], F, S);
+      mm_fs(P[EV_VH], dAh, tmp, F, S, 1, 0); /* d(Rg * W) = Vh^T dAh */
+      for (int64_t e = 0; e < n; ++e) {
+        grads[EV_BH][e] += dAh[e];
+        dAr[e] = tmp[e] * Wp[e] * r[e] * (1.0 - r[e]);
+        dWp[e] += tmp[e] * r[e];
+      }
+      mm_fs(P[EV_UH], dAh, dWp, F, S, 1, 1);
+      mm_abt_add(dAz, Wp, grads[EV_UZ], F, S); mm_abt_add(dAz, Wp, grads[EV_VZ], F, S);
+      mm_abt_add(dAr, Wp, grads[EV_UR], F, S); mm_abt_add(dAr, Wp, grads[EV_VR], F, S);
+      for (int64_t e = 0; e < n; ++e) { grads[EV_BZ][e] += dAz[e]; grads[EV_BR][e] += dAr[e]; }
+      mm_fs(P[EV_UZ], dAz, dWp, F, S, 1, 1); mm_fs(P[EV_VZ], dAz, dWp, F, S, 1, 1);
+      mm_fs(P[EV_UR], dAr, dWp, F, S, 1, 1); mm_fs(P[EV_VR], dAr, dWp, F, S, 1, 1);
+      for (int64_t e = 0; e < n; ++e) G[e] = dWp[e];
+    }
+    for (int64_t e = 0; e < n; ++e) grads[EV_W][e] = G[e];
+    free(G); free(dWp); free(dAz); free(dAr); free(dAh); free(rw); free(tmp);
+  }
+  free(Wt); free(Zg); free(Rg); free(Wc); free(dWd);
+  return 0;
+}

@@ -182,6 +182,26 @@ def layer_params(seed: int, F: int, S: int, H: int, time_kind: str, n_struct_lay
     return p
 
 
+EVOLVE_PARAMS = ["evolve.W_init", "evolve.U_z", "evolve.V_z", "evolve.B_z", "evolve.U_r", "evolve.V_r",
+                 "evolve.B_r", "evolve.U_h", "evolve.V_h", "evolve.B_h"]
+
+
+def evolve_params(seed: int, F: int, S: int, random_bias: bool = False) -> dict:
+    """Parameters of the weight-evolving matrix GRU: W_init [F,S], U*, V* [F,F] Xavier-uniform,
+    B* [F,S] zero (or small random)."""
+    rng = stream(seed, "param")
+    p = {}
+    for name in EVOLVE_PARAMS:
+        kind = name.split(".")[1][0]
+        if kind == "W":
+            p[name] = xavier_uniform(rng, F, S)
+        elif kind in "UV":
+            p[name] = xavier_uniform(rng, F, F)
+        else:
+            p[name] = (rng.uniform(-0.2, 0.2, size=(F, S)) if random_bias else np.zeros((F, S))).astype(np.float32)
+    return p
+
+
 # --------------------------------------------------------------------------- workloads
 
 
