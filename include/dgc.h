@@ -44,7 +44,10 @@ typedef enum {
   DGC_ERR_STATE = 7        /* call order (backward before forward, ...)                      */
 } dgc_status_t;
 
-enum { DGC_STRUCT_GCN = 0 };
+/* Structure encoder: GCN convolution with fixed weights, or EvolveGCN-O (the GCN weight matrix
+ * is the state of a matrix GRU and evolves from snapshot to snapshot; Section 1 lists EvolveGCN
+ * among the DGNNs the method targets). */
+enum { DGC_STRUCT_GCN = 0, DGC_STRUCT_EVOLVE_GCN_O = 1 };
 enum { DGC_TIME_NONE = 0, DGC_TIME_GRU = 1, DGC_TIME_LSTM = 2 };
 enum { DGC_ACT_NONE = 0, DGC_ACT_RELU = 1 };
 enum { DGC_DTYPE_F32 = 0 };
@@ -80,7 +83,7 @@ typedef struct {
 } dgc_graph_t;
 
 typedef struct {
-  int32_t struct_kind;     /* DGC_STRUCT_GCN                                                 */
+  int32_t struct_kind;     /* DGC_STRUCT_*                                                   */
   int32_t n_struct_layers; /* 1 or 2 stacked GCN layers                                      */
   int32_t time_kind;       /* DGC_TIME_*                                                     */
   int32_t dtype;           /* DGC_DTYPE_F32                                                  */
@@ -114,6 +117,13 @@ dgc_status_t dgc_layer_destroy(dgc_layer_t* layer);
  *  "gcn0.weight" [S,F]  "gcn0.bias" [S]   "gcn1.weight" [S,S]  "gcn1.bias" [S]  (2 layers)
  *  "rnn.weight_ih" [gH,S]  "rnn.weight_hh" [gH,H]  "rnn.bias_ih" [gH]  "rnn.bias_hh" [gH]
  *  g = 3 (GRU, gate order r,z,n) or 4 (LSTM, gate order i,f,g,o).
+ * DGC_STRUCT_EVOLVE_GCN_O (needs F = S, time_kind NONE, one layer, act_out RELU) has instead
+ *  "evolve.W_init" [F,S] (in, out)   "evolve.U_z" "evolve.V_z" "evolve.U_r" "evolve.V_r"
+ *  "evolve.U_h" "evolve.V_h" [F,F]   "evolve.B_z" "evolve.B_r" "evolve.B_h" [F,S]:
+ *    Zg = sig(U_z W + V_z W + B_z)  Rg = sig(U_r W + V_r W + B_r)
+ *    Wc = tanh(U_h W + V_h (Rg*W) + B_h)   W_t = (1 - Zg)*W + Zg*Wc,   W = W_{t-1}, W_{-1} = W_init,
+ *  for t = 0..T-1 whatever the chunk windows are, and Y[t,i] = relu(M[t,i] W_t).
+ *  After dgc_layer_backward, "<name>.grad" reads the gradient of that parameter (get only).
  * host_src / host_dst: host, numel elements; numel must equal the parameter's size. */
 dgc_status_t dgc_layer_set_param(dgc_layer_t* layer, const char* name, const float* host_src,
                                  int64_t numel);
@@ -140,10 +150,22 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* layer, const float* X, int64_t ldx, 
                                const uint8_t* reset_mask, float* Y, int64_t ldy, float* HN,
                                void* stream);
 
-/* Backward pass (gradient of a loss w.r.t. parameters and optionally inputs).  Not built yet:
- * returns DGC_ERR_UNSUPPORTED (DGC_ERR_STATE if no forward has run). */
-dgc_status_t dgc_layer_backward(dgc_layer_t* layer, const float* dY, int64_t lddy, float* dX,
-                                int64_t lddx, void* stream);
+/* Backward pass: gradients of a scalar loss with respect to the layer's parameters, for the
+ * batch of the last dgc_layer_forward on this layer (the layer keeps the aggregated rows of that
+ * pass; a forward in between invalidates them).  Built for DGC_STRUCT_EVOLVE_GCN_O; other layers
+ * return DGC_ERR_UNSUPPORTED.  DGC_ERR_STATE if no forward has run.
+ *  Y      device [T,N,ldy]: the output that forward wrote, unchanged.
+ *  Exactly one of
+ *   dY     device [T,N,lddy]: gradient of the loss with respect to Y (rows not covered by a
+ *          chunk are ignored), or
+ *   target device [T,N,ldt]: the loss is the mean squared error between Y and target over all
+ *          covered elements; *loss_out (device float, may be NULL) receives its value.
+ *  dX must be NULL (input gradients are not built).
+ * The cache is a constant: no gradient flows into C.  Gradients are read with
+ * dgc_layer_get_param(layer, "<name>.grad", ...).  Enqueues work only. */
+dgc_status_t dgc_layer_backward(dgc_layer_t* layer, const float* Y, int64_t ldy, const float* dY,
+                                int64_t lddy, const float* target, int64_t ldt, float* loss_out,
+                                float* dX, int64_t lddx, void* stream);
 
 /* Steps of the path on their own (for measurement and element-wise checks).
  * dgc_layer_aggregate: the normalised neighbour aggregation of the first GCN layer,

@@ -19,6 +19,7 @@ TIME_KIND = {"none": 0, "gru": 1, "lstm": 2}
 ACT = {"none": 0, "relu": 1}
 GATHER = {"in_place": 0, "staged": 1}
 DENSE = {"auto": 0, "tile": 1, "wave": 2}
+STRUCT = {"gcn": 0, "evolve_gcn_o": 1}
 
 STATUS = {0: "DGC_OK", 1: "DGC_ERR_INVALID_ARG", 2: "DGC_ERR_BAD_GRAPH", 3: "DGC_ERR_BAD_CHUNK",
           4: "DGC_ERR_UNSUPPORTED", 5: "DGC_ERR_OOM", 6: "DGC_ERR_DEVICE", 7: "DGC_ERR_STATE"}
@@ -70,7 +71,7 @@ def load() -> ct.CDLL:
     lib.dgc_layer_set_param.argtypes = [vp, ct.c_char_p, vp, i64]
     lib.dgc_layer_get_param.argtypes = [vp, ct.c_char_p, vp, i64]
     lib.dgc_layer_forward.argtypes = [vp, vp, i64, vp, i64, vp, i64, vp, vp, vp, i64, vp, vp]
-    lib.dgc_layer_backward.argtypes = [vp, vp, i64, vp, i64, vp]
+    lib.dgc_layer_backward.argtypes = [vp, vp, i64, vp, i64, vp, i64, vp, vp, i64, vp]
     lib.dgc_layer_aggregate.argtypes = [vp, vp, i64, vp, i64, vp, i64, vp]
     lib.dgc_layer_gather.argtypes = [vp, vp, i64, vp, i64, vp]
     lib.dgc_layer_packing.argtypes = [vp, ct.c_char_p, vp, i64, ct.POINTER(i64)]
@@ -129,7 +130,8 @@ class DgcLayer:
     def __init__(self, rowptr, colidx, N: int, chunks, *, F: int, S: int, H: int, time_kind: str = "gru",
                  n_struct_layers: int = 1, act_hidden: str = "relu", act_out: str = "none",
                  gather_mode: str = "in_place", validate_level: int = 0, rows_per_group: int = 0,
-                 long_nnz: int = 0, part_nnz: int = 0, dense_kernel: str = "auto", stream=None):
+                 long_nnz: int = 0, part_nnz: int = 0, dense_kernel: str = "auto", struct_kind: str = "gcn",
+                 stream=None):
         import torch
         lib = load()
         self._lib = lib
@@ -146,7 +148,8 @@ class DgcLayer:
         graph = GraphT(T, N, rp, cj)
         ch = np.asarray(chunks, np.int64).reshape(-1, 4)
         carr = (ChunkT * len(ch))(*[ChunkT(int(a), int(b), int(c), int(d)) for a, b, c, d in ch])
-        desc = DescT(0, n_struct_layers, TIME_KIND[time_kind], 0, F, S, H, ACT[act_hidden], ACT[act_out],
+        desc = DescT(STRUCT[struct_kind], n_struct_layers, TIME_KIND[time_kind], 0, F, S, H, ACT[act_hidden],
+                     ACT[act_out],
                      GATHER[gather_mode], validate_level, rows_per_group, long_nnz, part_nnz, DENSE[dense_kernel])
         rc = lib.dgc_layer_create(ct.byref(desc), ct.byref(graph), carr, len(ch), _stream_ptr(stream),
                                   ct.byref(self._h))
@@ -195,9 +198,10 @@ class DgcLayer:
             _stream_ptr(stream)))
         return Y
 
-    def backward(self, dY, dX=None, stream=None):
-        self._check(self._lib.dgc_layer_backward(self._h, _dev(dY, "dY"), _ld(dY, "dY"), _dev(dX, "dX"),
-                                                 _ld(dX, "dX"), _stream_ptr(stream)))
+    def backward(self, Y, *, dY=None, target=None, loss_out=None, dX=None, stream=None):
+        self._check(self._lib.dgc_layer_backward(
+            self._h, _dev(Y, "Y"), _ld(Y, "Y"), _dev(dY, "dY"), _ld(dY, "dY"), _dev(target, "target"),
+            _ld(target, "target"), _dev(loss_out, "loss_out"), _dev(dX, "dX"), _ld(dX, "dX"), _stream_ptr(stream)))
 
     def aggregate(self, X, C, M, stream=None):
         self._check(self._lib.dgc_layer_aggregate(self._h, _dev(X, "X"), _ld(X, "X"), _dev(C, "C"), _ld(C, "C"),

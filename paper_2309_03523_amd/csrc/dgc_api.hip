@@ -51,6 +51,9 @@ struct dgc_layer {
   float* d_partial = nullptr;                    // split-row partial sums
   float* d_halo = nullptr; int64_t ld_halo = 0;  // STAGED: gathered cache rows
   float* d_Z1 = nullptr;                         // 2 layers: first layer's output [T,N,S]
+  float* d_zero_bias = nullptr;                  // [S] zeros (EvolveGCN-O has no bias)
+  EvolveWs evo{};                                // EvolveGCN-O workspace
+  bool has_grads = false;
   std::map<std::string, Param> params;
   bool forward_done = false;
   bool profiling = false;
@@ -105,7 +108,13 @@ void free_all(dgc_layer* L) {
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 dgc_status_t check_desc(const dgc_layer_desc_t& d, std::string* msg) {
-  if (d.struct_kind != DGC_STRUCT_GCN) { *msg = "struct_kind: only DGC_STRUCT_GCN is built"; return DGC_ERR_UNSUPPORTED; }
+  if (d.struct_kind != DGC_STRUCT_GCN && d.struct_kind != DGC_STRUCT_EVOLVE_GCN_O) {
+    *msg = "struct_kind: only DGC_STRUCT_GCN and DGC_STRUCT_EVOLVE_GCN_O are built"; return DGC_ERR_UNSUPPORTED;
+  }
+  if (d.struct_kind == DGC_STRUCT_EVOLVE_GCN_O &&
+      (d.time_kind != DGC_TIME_NONE || d.n_struct_layers != 1 || d.F != d.S || d.act_out != DGC_ACT_RELU)) {
+    *msg = "EvolveGCN-O needs time_kind NONE, one layer, F = S and act_out RELU"; return DGC_ERR_INVALID_ARG;
+  }
   if (d.dtype != DGC_DTYPE_F32) { *msg = "dtype: only DGC_DTYPE_F32 is built"; return DGC_ERR_UNSUPPORTED; }
   if (d.n_struct_layers < 1 || d.n_struct_layers > 2) { *msg = "n_struct_layers must be 1 or 2"; return DGC_ERR_INVALID_ARG; }
   if (d.time_kind < DGC_TIME_NONE || d.time_kind > DGC_TIME_LSTM) { *msg = "unknown time_kind"; return DGC_ERR_INVALID_ARG; }
@@ -166,6 +175,66 @@ dgc_status_t add_param(dgc_layer* L, const std::string& name, int32_t n_out, int
     p.packed = reinterpret_cast<float4*>(pk);
   }
   L->params[name] = p;
+  return DGC_OK;
+}
+
+const char* const kEvolveNames[EV_NPAR] = {"evolve.W_init", "evolve.U_z", "evolve.V_z", "evolve.B_z", "evolve.U_r",
+                                           "evolve.V_r",    "evolve.B_r", "evolve.U_h", "evolve.V_h", "evolve.B_h"};
+
+// EvolveGCN-O: parameters, their gradients, the evolved weights and the per-snapshot tile lists
+dgc_status_t build_evolve(dgc_layer* L, const std::vector<ChunkInfo>& cinfo, hipStream_t st) {
+  Failer fail{L};
+  const int32_t T = L->T, F = L->desc.F, S = L->desc.S;
+  const int64_t n = (int64_t)F * S;
+  EvolveWs& ev = L->evo;
+  ev.T = T; ev.F = F; ev.S = S;
+  for (int k = 0; k < EV_NPAR; ++k) {
+    const bool fs = (k == EV_W || k == EV_BZ || k == EV_BR || k == EV_BH);
+    Param p;                      // stored as [rows][cols] with n_out = rows, n_in = cols; never packed
+    p.n_out = F; p.n_in = fs ? S : F;
+    DGC_HIP_TRY(dev_alloc(L, &p.raw, p.numel()));
+    DGC_HIP_TRY(hipMemsetAsync(p.raw, 0, sizeof(float) * p.numel(), st));
+    L->params[kEvolveNames[k]] = p;
+    ev.P[k] = p.raw;
+    Param g = p;
+    DGC_HIP_TRY(dev_alloc(L, &g.raw, g.numel()));
+    DGC_HIP_TRY(hipMemsetAsync(g.raw, 0, sizeof(float) * g.numel(), st));
+    L->params[std::string(kEvolveNames[k]) + ".grad"] = g;
+    ev.G[k] = g.raw;
+  }
+  DGC_HIP_TRY(dev_alloc(L, &ev.Wt, T * n));
+  DGC_HIP_TRY(dev_alloc(L, &ev.Zg, T * n));
+  DGC_HIP_TRY(dev_alloc(L, &ev.Rg, T * n));
+  DGC_HIP_TRY(dev_alloc(L, &ev.Wc, T * n));
+  float* pk = nullptr;
+  DGC_HIP_TRY(dev_alloc(L, &pk, (int64_t)T * packed_weight_elems(S, F)));
+  ev.Wt_packed = reinterpret_cast<float4*>(pk);
+  float** tmps[6] = {&ev.tmp0, &ev.tmp1, &ev.tmp2, &ev.tmp3, &ev.tmp4, &ev.tmp5};
+  for (float** t : tmps) DGC_HIP_TRY(dev_alloc(L, t, n));
+  DGC_HIP_TRY(dev_alloc(L, &ev.dWd, T * n));
+  DGC_HIP_TRY(dev_alloc(L, &ev.partial, evolve_partial_elems(T, F, S)));
+  DGC_HIP_TRY(dev_alloc(L, &ev.loss_partial, evolve_loss_partial_elems(T)));
+  DGC_HIP_TRY(dev_alloc(L, &L->d_zero_bias, S));
+  DGC_HIP_TRY(hipMemsetAsync(L->d_zero_bias, 0, sizeof(float) * S, st));
+  // 32-row tiles of every snapshot, snapshot by snapshot, chunks in order
+  std::vector<DenseTile> items;
+  std::vector<int64_t> ptr(T + 1, 0);
+  for (int32_t t = 0; t < T; ++t) {
+    for (int32_t k = 0; k < L->n_chunks; ++k) {
+      if (t < cinfo[k].t_lo || t >= cinfo[k].t_lo + cinfo[k].w) continue;
+      for (int64_t v0 = 0; v0 < cinfo[k].nv; v0 += kWaveTileRows)
+        items.push_back(DenseTile{k, (int32_t)v0, (int32_t)std::min<int64_t>(kWaveTileRows, cinfo[k].nv - v0), 0});
+    }
+    ptr[t + 1] = (int64_t)items.size();
+  }
+  DenseTile* d_items = nullptr;
+  int64_t* d_ptr = nullptr;
+  DGC_HIP_TRY(dev_alloc(L, &d_items, (int64_t)items.size()));
+  DGC_HIP_TRY(dev_alloc(L, &d_ptr, T + 1));
+  DGC_HIP_TRY(hipMemcpyAsync(d_items, items.data(), sizeof(DenseTile) * items.size(), hipMemcpyHostToDevice, st));
+  DGC_HIP_TRY(hipMemcpyAsync(d_ptr, ptr.data(), sizeof(int64_t) * (T + 1), hipMemcpyHostToDevice, st));
+  DGC_HIP_TRY(hipStreamSynchronize(st));
+  ev.items = d_items; ev.item_ptr = d_ptr;
   return DGC_OK;
 }
 
@@ -328,6 +397,9 @@ dgc_status_t build_layer(dgc_layer* L, const dgc_graph_t* graph, hipStream_t st)
 
   // parameters
   dgc_status_t rc;
+  if (d.struct_kind == DGC_STRUCT_EVOLVE_GCN_O) {
+    if ((rc = build_evolve(L, cinfo, st)) != DGC_OK) return rc;
+  } else {
   if ((rc = add_param(L, "gcn0.weight", d.S, d.F, st)) != DGC_OK) return rc;
   if ((rc = add_param(L, "gcn0.bias", d.S, 0, st)) != DGC_OK) return rc;
   if (d.n_struct_layers == 2) {
@@ -340,6 +412,7 @@ dgc_status_t build_layer(dgc_layer* L, const dgc_graph_t* graph, hipStream_t st)
     if ((rc = add_param(L, "rnn.weight_hh", gH, d.H, st)) != DGC_OK) return rc;
     if ((rc = add_param(L, "rnn.bias_ih", gH, 0, st)) != DGC_OK) return rc;
     if ((rc = add_param(L, "rnn.bias_hh", gH, 0, st)) != DGC_OK) return rc;
+  }
   }
   DGC_HIP_TRY(hipStreamSynchronize(st));
   DGC_HIP_TRY(hipGetLastError());
@@ -456,6 +529,9 @@ dgc_status_t dgc_layer_set_param(dgc_layer_t* L, const char* name, const float* 
   auto it = L->params.find(name);
   if (it == L->params.end()) return fail(DGC_ERR_INVALID_ARG, std::string("unknown parameter ") + name);
   Param& p = it->second;
+  const std::string nm(name);
+  if (nm.size() > 5 && nm.compare(nm.size() - 5, 5, ".grad") == 0)
+    return fail(DGC_ERR_INVALID_ARG, "gradients are read-only");
   if (numel != p.numel()) return fail(DGC_ERR_INVALID_ARG, std::string(name) + ": wrong element count");
   DGC_HIP_TRY(hipMemcpy(p.raw, host_src, sizeof(float) * numel, hipMemcpyHostToDevice));
   if (p.packed) {
@@ -531,6 +607,8 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* L, const float* X, int64_t ldx, cons
 
   const bool prof = L->profiling;
   L->ev_valid = false;
+  const bool evolve = d.struct_kind == DGC_STRUCT_EVOLVE_GCN_O;
+  if (evolve) evolve_forward_weights(L->evo, st);  // before the first event: not part of stage 0
   if (prof) DGC_HIP_TRY(hipEventRecord(L->ev[0], st));
   run_aggregate(L, X, ldx, C, ldc, d.F, L->d_M, L->ldm, st);
   if (prof) DGC_HIP_TRY(hipEventRecord(L->ev[1], st));
@@ -539,6 +617,7 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* L, const float* X, int64_t ldx, cons
     // first layer for every row of the batch -> Z1 [T,N,S]; then aggregate Z1 | C1
     da.K0 = d.F; da.act = d.act_hidden; da.time_kind = DGC_TIME_NONE;
     da.Wg = L->params["gcn0.weight"].packed; da.bg = L->params["gcn0.bias"].raw;
+    da.wg_bytes = sizeof(float) * packed_weight_elems(d.S, d.F); da.wg_step_bytes = 0;
     da.Y = L->d_Z1; da.ldy = d.S;
     if (!launch_dense(da, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
     if (prof) DGC_HIP_TRY(hipEventRecord(L->ev[2], st));
@@ -552,8 +631,16 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* L, const float* X, int64_t ldx, cons
   da.K0 = d.n_struct_layers == 2 ? d.S : d.F;
   da.act = d.act_out;
   da.time_kind = d.time_kind;
-  da.Wg = L->params[std::string(last) + ".weight"].packed;
-  da.bg = L->params[std::string(last) + ".bias"].raw;
+  if (evolve) {
+    da.Wg = L->evo.Wt_packed;
+    da.bg = L->d_zero_bias;
+    da.wg_step_bytes = (int32_t)(sizeof(float) * packed_weight_elems(d.S, d.F));
+    da.wg_bytes = (int64_t)L->T * da.wg_step_bytes;
+  } else {
+    da.Wg = L->params[std::string(last) + ".weight"].packed;
+    da.bg = L->params[std::string(last) + ".bias"].raw;
+    da.wg_bytes = sizeof(float) * packed_weight_elems(d.S, da.K0); da.wg_step_bytes = 0;
+  }
   if (d.time_kind != DGC_TIME_NONE) {
     da.Wih = L->params["rnn.weight_ih"].packed; da.Whh = L->params["rnn.weight_hh"].packed;
     da.bih = L->params["rnn.bias_ih"].raw; da.bhh = L->params["rnn.bias_hh"].raw;
@@ -590,12 +677,35 @@ dgc_status_t dgc_layer_stage_times(dgc_layer_t* L, float* host_ms) {
   return DGC_OK;
 }
 
-dgc_status_t dgc_layer_backward(dgc_layer_t* L, const float* dY, int64_t lddy, float* dX, int64_t lddx, void* stream) {
-  (void)dY; (void)lddy; (void)dX; (void)lddx; (void)stream;
+dgc_status_t dgc_layer_backward(dgc_layer_t* L, const float* Y, int64_t ldy, const float* dY, int64_t lddy,
+                                const float* target, int64_t ldt, float* loss_out, float* dX, int64_t lddx,
+                                void* stream) {
+  (void)lddx;
   if (!L) return DGC_ERR_INVALID_ARG;
   Failer fail{L};
+  const dgc_layer_desc_t& d = L->desc;
   if (!L->forward_done) return fail(DGC_ERR_STATE, "backward before forward");
-  return fail(DGC_ERR_UNSUPPORTED, "backward is not built");
+  if (d.struct_kind != DGC_STRUCT_EVOLVE_GCN_O)
+    return fail(DGC_ERR_UNSUPPORTED, "backward is built for DGC_STRUCT_EVOLVE_GCN_O only");
+  if (dX) return fail(DGC_ERR_UNSUPPORTED, "input gradients are not built: dX must be NULL");
+  if ((dY != nullptr) == (target != nullptr))
+    return fail(DGC_ERR_INVALID_ARG, "give exactly one of dY and target");
+  dgc_status_t rc;
+  if ((rc = check_tensor(fail, "Y", Y, ldy, d.S, true)) != DGC_OK) return rc;
+  if ((rc = check_tensor(fail, "dY", dY, lddy, d.S, false)) != DGC_OK) return rc;
+  if ((rc = check_tensor(fail, "target", target, ldt, d.S, false)) != DGC_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  EvolveBwdIn in{};
+  in.chunks = L->d_chunks; in.N = L->N; in.M = L->d_M; in.ldm = L->ldm;
+  in.Y = Y; in.ldy = ldy; in.dY = dY; in.lddy = lddy; in.target = target; in.ldt = ldt;
+  in.count = L->total_rows * d.S;
+  in.loss_out = loss_out;
+  std::string why;
+  if (!evolve_backward_dw(L->evo, in, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
+  evolve_backward_bptt(L->evo, st);
+  DGC_HIP_TRY(hipGetLastError());
+  L->has_grads = true;
+  return DGC_OK;
 }
 
 dgc_status_t dgc_layer_packing(dgc_layer_t* L, const char* what, void* host_dst, int64_t capacity_bytes,

@@ -255,7 +255,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int ld) {
         floatx16 acc[NRB][4];
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) acc[rb][0] = (floatx16)(0.f);
-        const float4* const wp[1] = {a.Wg + ((int64_t)jb * nkb0) * 64 + lane};
+        const float4* const wp[1] = {a.Wg + (t * a.wg_step_bytes) / 16 + ((int64_t)jb * nkb0) * 64 + lane};
         prio_matrix();
         mma_k_loop<NRB, 1, 0, 0, 0, 0>(acc, Q + (rb0 * 32 + l32) * ld + half * 4, ld, nkb0, wp);
         prio_other();

@@ -74,11 +74,11 @@ __device__ __forceinline__ void load_w(float4 (&w)[NG], const WeightStream& ws, 
 // hides behind the tail of the previous loop and the gate arithmetic in between.
 
 // K loop with the activation fragments in LDS (row l%32 of a [32][ldz] tile, float4 at k).
-template <int NG, int NKB, int NGN>
+template <int NG, int NKB, int NGN, int NWQ>
 __device__ __forceinline__ void k_loop_lds(floatx16 (&acc)[NG], const float* ldsX, const WeightStream& ws,
-                                           const int (&soff)[NG], int lane16, float4 (&wq)[4],
+                                           const int (&soff)[NG], int lane16, float4 (&wq)[NWQ],
                                            const WeightStream& ws_next, const int (&soff_next)[NGN]) {
-  static_assert(NKB % 2 == 0 && NG <= 4 && NGN <= 4, "");
+  static_assert(NKB % 2 == 0 && NG <= NWQ && NGN <= NWQ, "");
   float4 w0[NG], w1[NG], x0, x1;
 #pragma unroll
   for (int g = 0; g < NG; ++g) w0[g] = wq[g];
@@ -104,11 +104,11 @@ __device__ __forceinline__ void k_loop_lds(floatx16 (&acc)[NG], const float* lds
 }
 
 // K loop with the activation fragments in registers: x[kb] for kb = 0..NKB-1 (NKB even).
-template <int NG, int NKB, int NGN>
+template <int NG, int NKB, int NGN, int NWQ>
 __device__ __forceinline__ void k_loop_reg(floatx16 (&acc)[NG], const float4 (&x)[NKB], const WeightStream& ws,
-                                           const int (&soff)[NG], int lane16, float4 (&wq)[4],
+                                           const int (&soff)[NG], int lane16, float4 (&wq)[NWQ],
                                            const WeightStream& ws_next, const int (&soff_next)[NGN]) {
-  static_assert(NKB % 2 == 0 && NG <= 4 && NGN <= 4, "");
+  static_assert(NKB % 2 == 0 && NG <= NWQ && NGN <= NWQ, "");
   float4 w0[NG], w1[NG];
 #pragma unroll
   for (int g = 0; g < NG; ++g) w0[g] = wq[g];
@@ -166,7 +166,7 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
   const int row = valid ? l32 : nrows - 1;   // rows past the tile's end recompute its last row; never stored
   const int lane16 = lane * 16;
   const int K0 = a.K0, nkb0 = (K0 + 7) / 8;
-  const WeightStream wsg = make_stream(a.Wg, (int64_t)NJB * nkb0 * 1024);
+  const WeightStream wsg = make_stream(a.Wg, a.wg_bytes);
   const WeightStream wsi = make_stream(a.Wih, (int64_t)(KIND == DGC_TIME_LSTM ? 4 : 3) * NJB * NKB * 1024);
   const WeightStream wsh = make_stream(a.Whh, (int64_t)(KIND == DGC_TIME_LSTM ? 4 : 3) * NJB * NKB * 1024);
   const int64_t V = a.total_state_rows;
@@ -197,10 +197,11 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
 #pragma unroll
   for (int i = 0; i < kXAhead; ++i) xq[i] = i < nkb0 ? *reinterpret_cast<const float4*>(mrow0 + 8 * i) : zero4();
   // fragment 0 of the next K loop's weights (see k_loop_lds)
+  // (with per-snapshot GCN weights, snapshot t's fragments start t * wg_step_bytes further on)
   int soffg[NJB];
 #pragma unroll
-  for (int jb = 0; jb < NJB; ++jb) soffg[jb] = jb * nkb0 * 1024;
-  float4 wq[4];
+  for (int jb = 0; jb < NJB; ++jb) soffg[jb] = jb * nkb0 * 1024 + ch.t_lo * a.wg_step_bytes;
+  float4 wq[NJB > 4 ? NJB : 4];
 #pragma unroll
   for (int jb = 0; jb < NJB; ++jb) wq[jb] = wsg.frag(lane16, soffg[jb]);
 
@@ -266,7 +267,10 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
     constexpr int NG = KIND == DGC_TIME_LSTM ? 4 : 3;
     if constexpr (KIND == DGC_TIME_NONE) {
 #pragma unroll
-      for (int jb = 0; jb < NJB; ++jb) wq[jb] = wsg.frag(lane16, soffg[jb]);   // next step's first weights
+      for (int jb = 0; jb < NJB; ++jb) {   // next step's first weights
+        soffg[jb] += a.wg_step_bytes;
+        wq[jb] = wsg.frag(lane16, soffg[jb]);
+      }
     } else {
 #pragma unroll
       for (int g = 0; g < NG; ++g) wq[g] = wsi.frag(lane16, (g * NJB) * NKB * 1024);  // gates of column block 0
@@ -312,17 +316,21 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
         int soff_next[NG];
 #pragma unroll
         for (int g = 0; g < NG; ++g) soff_next[g] = (g * NJB + jb + 1) * NKB * 1024;
+        if (jb + 1 == NJB) {
+#pragma unroll
+          for (int j2 = 0; j2 < NJB; ++j2) soffg[j2] += a.wg_step_bytes;
+        }
         if constexpr (KIND == DGC_TIME_GRU) {
           floatx16 ai[3] = {acc[0], acc[1], acc[2]};   // r, z, input part of n
-          k_loop_lds<3, NKB, 3>(ai, ldsZ, wsi, soff, lane16, wq, wsh, soff);
+          k_loop_lds<3, NKB, 3, 4>(ai, ldsZ, wsi, soff, lane16, wq, wsh, soff);
           floatx16 ah[3] = {ai[0], ai[1], acc[3]};     // r, z, hidden part of n
-          if (jb + 1 < NJB) k_loop_reg<3, NKB, 3>(ah, h, wsh, soff, lane16, wq, wsi, soff_next);
-          else k_loop_reg<3, NKB, NJB>(ah, h, wsh, soff, lane16, wq, wsg, soffg);
+          if (jb + 1 < NJB) k_loop_reg<3, NKB, 3, 4>(ah, h, wsh, soff, lane16, wq, wsi, soff_next);
+          else k_loop_reg<3, NKB, NJB, 4>(ah, h, wsh, soff, lane16, wq, wsg, soffg);
           acc[0] = ah[0]; acc[1] = ah[1]; acc[2] = ai[2]; acc[3] = ah[2];
         } else {
-          k_loop_lds<4, NKB, 4>(acc, ldsZ, wsi, soff, lane16, wq, wsh, soff);
-          if (jb + 1 < NJB) k_loop_reg<4, NKB, 4>(acc, h, wsh, soff, lane16, wq, wsi, soff_next);
-          else k_loop_reg<4, NKB, NJB>(acc, h, wsh, soff, lane16, wq, wsg, soffg);
+          k_loop_lds<4, NKB, 4, 4>(acc, ldsZ, wsi, soff, lane16, wq, wsh, soff);
+          if (jb + 1 < NJB) k_loop_reg<4, NKB, 4, 4>(acc, h, wsh, soff, lane16, wq, wsi, soff_next);
+          else k_loop_reg<4, NKB, NJB, 4>(acc, h, wsh, soff, lane16, wq, wsg, soffg);
         }
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
@@ -404,6 +412,8 @@ bool launch_wk(const DenseArgs& a, hipStream_t st, std::string* why) {
     case 1: return launch_w<KIND, 1>(a, st, why);
     case 2: return launch_w<KIND, 2>(a, st, why);
     case 4: return launch_w<KIND, 4>(a, st, why);
+    case 8:
+      if constexpr (KIND == DGC_TIME_NONE) return launch_w<KIND, 8>(a, st, why);
   }
   return false;
 }
@@ -411,7 +421,7 @@ bool launch_wk(const DenseArgs& a, hipStream_t st, std::string* why) {
 }  // namespace
 
 bool dense_wave_supported(const DenseArgs& a) {
-  const bool s_ok = a.S == 32 || a.S == 64 || a.S == 128;
+  const bool s_ok = a.S == 32 || a.S == 64 || a.S == 128 || (a.S == 256 && a.time_kind == DGC_TIME_NONE);
   const bool m_ok = a.ldm % 8 == 0 && a.ldm >= (a.K0 + 7) / 8 * 8;  // whole k-blocks, zero padded
   return s_ok && m_ok && (a.time_kind == DGC_TIME_NONE || a.H == a.S);
 }

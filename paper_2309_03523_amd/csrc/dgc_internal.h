@@ -132,7 +132,9 @@ struct DenseArgs {
   int32_t S, H;
   int32_t act;                  // activation after the GCN transform
   int32_t time_kind;
-  const float4* Wg;             // packed GCN weight [S][K0]
+  const float4* Wg;             // packed GCN weight [S][K0] (one per snapshot if wg_step_bytes != 0)
+  int64_t wg_bytes;             // size of the packed GCN weights
+  int32_t wg_step_bytes;        // distance between consecutive snapshots' packed weights, or 0
   const float* bg;              // [S]
   const float4* Wih;            // packed [gH][S]
   const float4* Whh;            // packed [gH][H]
@@ -148,5 +150,39 @@ bool dense_wave_supported(const DenseArgs& a);
 bool launch_dense_wave(const DenseArgs& a, hipStream_t st, std::string* why);
 size_t dense_lds_bytes(int32_t K0, int32_t S, int32_t H);
 int dense_ld(int32_t K0, int32_t S, int32_t H);
+
+// ---- EvolveGCN-O (dgc_evolve.hip)
+enum { EV_W = 0, EV_UZ, EV_VZ, EV_BZ, EV_UR, EV_VR, EV_BR, EV_UH, EV_VH, EV_BH, EV_NPAR };
+
+struct EvolveWs {
+  int32_t T, F, S;
+  const float* P[EV_NPAR];   // parameters (device, fp32): W_init, Uz, Vz, Bz, Ur, Vr, Br, Uh, Vh, Bh
+  float* G[EV_NPAR];         // their gradients
+  float *Wt, *Zg, *Rg, *Wc;  // [T][F][S]: evolved weights and the gates that produced them
+  float4* Wt_packed;         // every W_t^T in MFMA fragment order
+  float *tmp0, *tmp1, *tmp2, *tmp3, *tmp4, *tmp5;  // [F][S] scratch
+  float* dWd;                // [T][F][S] direct gradient of each W_t
+  float* partial;            // [T][split][F][S]
+  float* loss_partial;       // [T][split]
+  const DenseTile* items;    // 32-row tiles ordered by snapshot
+  const int64_t* item_ptr;   // [T+1]
+};
+
+struct EvolveBwdIn {
+  const ChunkInfo* chunks;
+  int64_t N;
+  const float* M; int64_t ldm;
+  const float* Y; int64_t ldy;
+  const float* dY; int64_t lddy;
+  const float* target; int64_t ldt;
+  int64_t count;             // number of output elements the loss averages over
+  float* loss_out;           // device, or nullptr
+};
+
+int64_t evolve_partial_elems(int32_t T, int32_t F, int32_t S);
+int64_t evolve_loss_partial_elems(int32_t T);
+void evolve_forward_weights(const EvolveWs& ws, hipStream_t st);
+bool evolve_backward_dw(const EvolveWs& ws, const EvolveBwdIn& in, hipStream_t st, std::string* why);
+void evolve_backward_bptt(const EvolveWs& ws, hipStream_t st);
 
 }  // namespace dgc

@@ -13,7 +13,7 @@ class DeviceWorkload:
     """Device copies of a Workload's graph and tensors plus a created layer."""
 
     def __init__(self, wl, *, gather_mode: str = "in_place", validate_level: int = 0, act_hidden: str = "relu",
-                 act_out: str = "none", pitch: Optional[int] = None, **layer_kw):
+                 act_out: str = "none", pitch: Optional[int] = None, struct_kind: str = "gcn", **layer_kw):
         import torch
         dev = torch.device("cuda:0")
         self.wl = wl
@@ -23,7 +23,7 @@ class DeviceWorkload:
         self.layer = DgcLayer(self.rowptr, self.colidx, g.N, wl.chunks, F=wl.F, S=wl.S, H=wl.H,
                               time_kind=wl.time_kind, n_struct_layers=wl.n_struct_layers,
                               act_hidden=act_hidden, act_out=act_out, gather_mode=gather_mode,
-                              validate_level=validate_level, **layer_kw)
+                              validate_level=validate_level, struct_kind=struct_kind, **layer_kw)
         self.layer.set_params(wl.params)
 
         def up(a, ld=None):

@@ -1,0 +1,84 @@
+"""Parity of the EvolveGCN-O path (weight evolution, forward, MSE loss, parameter gradients)
+against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2309_03523_amd import synth
+from refs import rel_err
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+def _workload(seed, T, N, F, chunks, deg=4.0):
+    wl = synth.random_small(seed, T, N, F, F, F, deg, chunks, "none", hub=True)
+    wl.params = synth.evolve_params(seed, F, F, random_bias=True)
+    return wl
+
+
+def _dw(wl, **kw):
+    from paper_2309_03523_amd.runner import DeviceWorkload
+    return DeviceWorkload(wl, struct_kind="evolve_gcn_o", act_out="relu", **kw)
+
+
+@pytest.mark.parametrize("F", [32, 64, 128, 256])
+@pytest.mark.parametrize("dense", ["auto", "tile"])
+def test_evolve_forward_and_gradients(F, dense):
+    import torch
+    T, N = 6, 150
+    chunks = [[0, 40, 0, 6], [40, 97, 0, 3], [40, 97, 3, 6], [97, 150, 0, 6]]
+    wl = _workload(300 + F, T, N, F, chunks)
+    target = synth.stream(F, "target").standard_normal((T, N, F)).astype(np.float32)
+    dw = _dw(wl, dense_kernel=dense, long_nnz=24, part_nnz=8)
+    Y = dw.forward()
+    want = oracle.evolve(wl.graph, wl.chunks, wl.params, wl.X, wl.C, target, want_grads=True)
+    got = Y.cpu().numpy()
+    assert rel_err(got, want["Y"]) < TOL
+    tgt = torch.from_numpy(target).cuda()
+    loss = torch.zeros(1, device="cuda")
+    dw.layer.backward(Y, target=tgt, loss_out=loss)
+    torch.cuda.synchronize()
+    assert abs(loss.item() - want["loss"]) < 1e-5 * want["loss"]
+    for name in oracle.EVOLVE_PARAMS:
+        g = dw.layer.get_param(name + ".grad", wl.params[name].shape)
+        e = rel_err(g, want["grads"][name])
+        assert e < 5e-4, (name, e)   # fp32 back-propagation through T chained matrix products
+    # explicit upstream gradient: dY = 2 (Y - target) / count reproduces the same gradients
+    dY = (2.0 * (Y - tgt) / float(wl.rows * F)).contiguous()
+    dw.layer.backward(Y, dY=dY)
+    torch.cuda.synchronize()
+    for name in oracle.EVOLVE_PARAMS:
+        g = dw.layer.get_param(name + ".grad", wl.params[name].shape)
+        assert rel_err(g, want["grads"][name]) < 5e-4, name
+    dw.layer.destroy()
+
+
+def test_evolve_argument_errors():
+    import torch
+    from paper_2309_03523_amd.binding import DgcError
+    wl = _workload(5, 2, 40, 32, [[0, 40, 0, 2]])
+    dw = _dw(wl)
+    with pytest.raises(DgcError) as ei:
+        dw.layer.backward(dw.Y, target=dw.Y)
+    assert ei.value.code == 7
+    Y = dw.forward()
+    with pytest.raises(DgcError) as ei:
+        dw.layer.backward(Y)
+    assert ei.value.code == 1
+    with pytest.raises(DgcError) as ei:
+        dw.layer.backward(Y, target=Y, dY=Y)
+    assert ei.value.code == 1
+    with pytest.raises(DgcError) as ei:
+        dw.layer.backward(Y, target=Y, dX=torch.zeros_like(dw.X))
+    assert ei.value.code == 4
+    with pytest.raises(DgcError) as ei:
+        dw.layer.set_param("evolve.U_z.grad", np.zeros((32, 32), np.float32))
+    assert ei.value.code == 1
+    dw.layer.destroy()
+    from paper_2309_03523_amd.runner import DeviceWorkload
+    with pytest.raises(DgcError) as ei:   # F != S
+        wl2 = synth.random_small(6, 2, 40, 64, 32, 32, 3.0, [[0, 40, 0, 2]], "none")
+        DeviceWorkload(wl2, struct_kind="evolve_gcn_o", act_out="relu")
+    assert ei.value.code == 1
