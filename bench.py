@@ -29,7 +29,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config2s", "config3w"])
+    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config2s", "config3w", "config4s"])
     ap.add_argument("--gather-mode", default="in_place", choices=["in_place", "staged"])
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -49,6 +49,11 @@ def make_workload(name: str, seed: int):
     if name == "config3w":
         return synth.config3(seed, scale=0.125), ("config3 at 1/8 of its vertex count, one 32-snapshot window: 250k "
                                                   "vertices, 2 GCN layers (172->128->128) + LSTM, 64 uneven ranges")
+    if name == "config4s":
+        wl, target = synth.config4(seed, scale=0.125)
+        wl.notes["target"] = target
+        return wl, ("config4 at 1/8 of its vertex count: EvolveGCN-O, 64 snapshots x 62.5k vertices, avg degree 16, "
+                    "F = S = 256, 32 chunks, forward + backward (MSE)")
     return synth.config2(seed), ("config2: 32 snapshots x 100k vertices, lognormal edge counts, power-law "
                                  "degrees (tail 2.1), F=S=H=128, GCN+GRU, 64 chunks = 4 windows of 8 x 16 "
                                  "uneven vertex ranges")
@@ -72,6 +77,55 @@ def measured_traffic(workload: str, gather_mode: str) -> dict:
             return json.load(f).get(f"{workload}/{gather_mode}", {})
     except (OSError, ValueError):
         return {}
+
+
+def evolve_report(args, wl, desc, dw, rows, value, ms_per_step, stage, t_gen, t_create, loss) -> dict:
+    """JSON line for the EvolveGCN-O workload: a step is forward + backward."""
+    import numpy as np
+    import oracle
+    F, S = wl.F, wl.S
+    nnz = int(dw.layer.packing("seg_nnz_off")[-1])
+    fwd_flops, bwd_flops = 2.0 * F * S * rows, 2.0 * F * S * rows
+    kernels = {
+        "dense_forward": {"kernel": "k_dense_wave<NONE> (Y = relu(M W_t), per-snapshot weights)", "bound": "mfma",
+                          "achieved": fwd_flops / (stage[3] * 1e-3) / 1e12, "peak": PEAK_FP32_MFMA_TFLOPS,
+                          "unit": "TFLOP/s", "ms_per_launch": float(stage[3])},
+        "weight_gradient": {"kernel": "k_dw_partial + k_dw_reduce (dW_t = M_t^T dP_t)", "bound": "mfma",
+                            "achieved": bwd_flops / (stage[5] * 1e-3) / 1e12, "peak": PEAK_FP32_MFMA_TFLOPS,
+                            "unit": "TFLOP/s", "ms_per_launch": float(stage[5])},
+    }
+    for k in kernels.values():
+        k["frac"] = k["achieved"] / k["peak"]
+        k["traffic"] = None
+    dom = max(kernels.values(), key=lambda k: k["ms_per_launch"])
+    out = {"metric": "snapshot-vertex embeddings/s per DGNN layer", "value": value, "unit": "embeddings/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": desc, "rows": rows, "nnz": nnz, "gather_mode": args.gather_mode,
+                      "pass": "forward+backward"},
+           "roofline": dom, "kernels": kernels,
+           "stage_ms": {"aggregate0": float(stage[0]), "dense_forward": float(stage[3]),
+                        "weight_evolution": float(stage[4]), "weight_gradient": float(stage[5]),
+                        "bptt": float(stage[6])},
+           "loss": float(loss.item()), "setup_s": {"generate": t_gen, "upload_create_pack": t_create}}
+    if not args.no_cpu_baseline:
+        # the oracle on a few whole chunks of the first window (forward + gradients)
+        import time as _t
+        sub = wl.chunks[:2]
+        t0 = _t.perf_counter()
+        o = oracle.evolve(wl.graph, sub, wl.params, wl.X, wl.C, wl.notes["target"], want_grads=True)
+        dt = _t.perf_counter() - t0
+        n_rows = int(((sub[:, 1] - sub[:, 0]) * (sub[:, 3] - sub[:, 2])).sum())
+        Yg = dw.Y.cpu().numpy()
+        m = ~np.isnan(o["Y"])
+        want = o["Y"][m].astype(np.float64)
+        tau = 0.1 * float(np.sqrt(np.mean(want * want)))
+        err = float(np.max(np.abs(Yg[m] - want) / np.maximum(np.abs(want), tau)))
+        out["cpu_baseline"] = {"value": n_rows / dt, "unit": "embeddings/s", "cores": oracle.threads(), "kind": "oracle",
+                               "sample": f"chunks 0 and 1 (of {len(wl.chunks)}) forward + gradients = {n_rows} rows, "
+                                         f"{dt:.1f} s (weight recurrence over all 64 snapshots included)",
+                               "gpu_max_rel_err_on_sample": err}
+    return out
 
 
 def cpu_baseline(wl, Y_gpu, target_seconds: float, seed: int) -> dict:
@@ -145,7 +199,11 @@ def main():
     rows = wl.rows
 
     t0 = time.perf_counter()
-    dw = DeviceWorkload(wl, gather_mode=args.gather_mode, act_hidden="relu", act_out="none")
+    evolve = "evolve.W_init" in wl.params
+    dw = DeviceWorkload(wl, gather_mode=args.gather_mode, act_hidden="relu",
+                        act_out="relu" if evolve else "none", struct_kind="evolve_gcn_o" if evolve else "gcn")
+    target = torch.from_numpy(wl.notes["target"]).cuda() if evolve else None
+    loss = torch.zeros(1, device="cuda") if evolve else None
     torch.cuda.synchronize()
     t_create = time.perf_counter() - t0
     layer = dw.layer
@@ -153,6 +211,8 @@ def main():
 
     def step():
         layer.forward(dw.X, dw.C, dw.Y, C1=dw.C1, H0=dw.H0, stream=stream)
+        if evolve:
+            layer.backward(dw.Y, target=target, loss_out=loss, stream=stream)
 
     if args.calib_copy:
         scratch = torch.empty_like(dw.X)
@@ -173,7 +233,7 @@ def main():
 
     # per-stage device times of the same launches, HIP events on the launch stream
     layer.set_profiling(True)
-    stage = np.zeros(4, np.float64)
+    stage = np.zeros(7, np.float64)
     n_prof = max(3, min(args.steps, 10))
     for _ in range(n_prof):
         step()
@@ -181,6 +241,9 @@ def main():
     stage /= n_prof
     layer.set_profiling(False)
 
+    if evolve:
+        print(json.dumps(evolve_report(args, wl, desc, dw, rows, value, ms_per_step, stage, t_gen, t_create, loss)))
+        return
     fl = flops_per_row(wl)
     # the last dense launch: last GCN layer's transform + time encoder
     dense_flops = (fl["transform"] + fl["rnn"]) * rows if wl.n_struct_layers == 1 else \

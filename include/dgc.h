@@ -179,16 +179,20 @@ dgc_status_t dgc_layer_aggregate(dgc_layer_t* layer, const float* X, int64_t ldx
 dgc_status_t dgc_layer_gather(dgc_layer_t* layer, const float* C, int64_t ldc, float* halo,
                               int64_t ldh, void* stream);
 
-/* Per-stage device time of a forward pass, from HIP events recorded on the caller's stream
- * (for measurement; adds no synchronisation to forward itself).  Stages:
+/* Per-stage device time, from HIP events recorded on the caller's stream (for measurement;
+ * adds no synchronisation to forward / backward themselves).  Stages:
  *  0 aggregation of the first GCN layer (gather + split-row reduction included)
  *  1 first GCN layer's dense transform            (0 ms unless n_struct_layers = 2)
  *  2 aggregation of the second GCN layer          (0 ms unless n_struct_layers = 2)
  *  3 last GCN layer's dense transform fused with the time encoder
- * dgc_layer_set_profiling: enable != 0 makes every later forward record the events.
- * dgc_layer_stage_times: waits for the last profiled forward and writes DGC_N_STAGES
- * durations in milliseconds to host_ms (host); DGC_ERR_STATE if none was enqueued. */
-#define DGC_N_STAGES 4
+ *  4 evolution of the GCN weights over the T snapshots   (EvolveGCN-O forward, else 0 ms)
+ *  5 backward: weight-gradient reduction over the rows of every snapshot (+ loss)
+ *  6 backward: back-propagation through time over the weight recurrence
+ * dgc_layer_set_profiling: enable != 0 makes every later forward / backward record the events.
+ * dgc_layer_stage_times: waits for the last profiled forward (and backward, if one followed it)
+ * and writes DGC_N_STAGES durations in milliseconds to host_ms (host); stages that did not run
+ * read 0; DGC_ERR_STATE if no profiled forward was enqueued. */
+#define DGC_N_STAGES 7
 dgc_status_t dgc_layer_set_profiling(dgc_layer_t* layer, int32_t enable);
 dgc_status_t dgc_layer_stage_times(dgc_layer_t* layer, float* host_ms);
 

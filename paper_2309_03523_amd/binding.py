@@ -28,7 +28,7 @@ EXPORTS = ["dgc_layer_create", "dgc_layer_destroy", "dgc_layer_set_param", "dgc_
            "dgc_layer_forward", "dgc_layer_backward", "dgc_layer_aggregate", "dgc_layer_gather",
            "dgc_layer_packing", "dgc_layer_set_profiling", "dgc_layer_stage_times", "dgc_last_error",
            "dgc_version"]
-N_STAGES = 4
+N_STAGES = 7
 
 
 class DgcError(RuntimeError):

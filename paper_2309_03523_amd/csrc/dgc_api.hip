@@ -57,8 +57,9 @@ struct dgc_layer {
   std::map<std::string, Param> params;
   bool forward_done = false;
   bool profiling = false;
-  hipEvent_t ev[DGC_N_STAGES + 1] = {};   // stage boundaries of the last profiled forward
-  bool ev_valid = false;
+  hipEvent_t ev[DGC_N_STAGES + 1] = {};   // forward: boundaries of stages 0..3
+  hipEvent_t evx[6] = {};                 // pairs around stage 4 (weight evolution), 5 and 6 (backward)
+  bool ev_valid = false, evx_fwd = false, evx_bwd = false;
   std::string error;
 
   GraphDev graph_dev() const { return GraphDev{T, N, d_rowptr, d_colidx}; }
@@ -517,6 +518,8 @@ dgc_status_t dgc_layer_destroy(dgc_layer_t* L) {
   (void)hipDeviceSynchronize();
   for (hipEvent_t e : L->ev)
     if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : L->evx)
+    if (e) (void)hipEventDestroy(e);
   free_all(L);
   delete L;
   return DGC_OK;
@@ -608,7 +611,12 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* L, const float* X, int64_t ldx, cons
   const bool prof = L->profiling;
   L->ev_valid = false;
   const bool evolve = d.struct_kind == DGC_STRUCT_EVOLVE_GCN_O;
-  if (evolve) evolve_forward_weights(L->evo, st);  // before the first event: not part of stage 0
+  L->evx_fwd = false;
+  if (evolve) {
+    if (prof) DGC_HIP_TRY(hipEventRecord(L->evx[0], st));
+    evolve_forward_weights(L->evo, st);
+    if (prof) { DGC_HIP_TRY(hipEventRecord(L->evx[1], st)); L->evx_fwd = true; }
+  }
   if (prof) DGC_HIP_TRY(hipEventRecord(L->ev[0], st));
   run_aggregate(L, X, ldx, C, ldc, d.F, L->d_M, L->ldm, st);
   if (prof) DGC_HIP_TRY(hipEventRecord(L->ev[1], st));
@@ -660,10 +668,11 @@ dgc_status_t dgc_layer_set_profiling(dgc_layer_t* L, int32_t enable) {
   if (!L) return DGC_ERR_INVALID_ARG;
   Failer fail{L};
   if (enable && !L->ev[0]) {
-    for (int i = 0; i <= DGC_N_STAGES; ++i) DGC_HIP_TRY(hipEventCreate(&L->ev[i]));
+    for (hipEvent_t& e : L->ev) DGC_HIP_TRY(hipEventCreate(&e));
+    for (hipEvent_t& e : L->evx) DGC_HIP_TRY(hipEventCreate(&e));
   }
   L->profiling = enable != 0;
-  L->ev_valid = false;
+  L->ev_valid = L->evx_fwd = L->evx_bwd = false;
   return DGC_OK;
 }
 
@@ -672,8 +681,15 @@ dgc_status_t dgc_layer_stage_times(dgc_layer_t* L, float* host_ms) {
   Failer fail{L};
   if (!host_ms) return fail(DGC_ERR_INVALID_ARG, "NULL argument");
   if (!L->ev_valid) return fail(DGC_ERR_STATE, "no profiled forward has been enqueued");
-  DGC_HIP_TRY(hipEventSynchronize(L->ev[DGC_N_STAGES]));
-  for (int i = 0; i < DGC_N_STAGES; ++i) DGC_HIP_TRY(hipEventElapsedTime(&host_ms[i], L->ev[i], L->ev[i + 1]));
+  for (int i = 0; i < DGC_N_STAGES; ++i) host_ms[i] = 0.f;
+  DGC_HIP_TRY(hipEventSynchronize(L->ev[4]));
+  for (int i = 0; i < 4; ++i) DGC_HIP_TRY(hipEventElapsedTime(&host_ms[i], L->ev[i], L->ev[i + 1]));
+  if (L->evx_fwd) DGC_HIP_TRY(hipEventElapsedTime(&host_ms[4], L->evx[0], L->evx[1]));
+  if (L->evx_bwd) {
+    DGC_HIP_TRY(hipEventSynchronize(L->evx[5]));
+    DGC_HIP_TRY(hipEventElapsedTime(&host_ms[5], L->evx[2], L->evx[3]));
+    DGC_HIP_TRY(hipEventElapsedTime(&host_ms[6], L->evx[4], L->evx[5]));
+  }
   return DGC_OK;
 }
 
@@ -701,8 +717,13 @@ dgc_status_t dgc_layer_backward(dgc_layer_t* L, const float* Y, int64_t ldy, con
   in.count = L->total_rows * d.S;
   in.loss_out = loss_out;
   std::string why;
+  const bool prof = L->profiling;
+  L->evx_bwd = false;
+  if (prof) DGC_HIP_TRY(hipEventRecord(L->evx[2], st));
   if (!evolve_backward_dw(L->evo, in, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
+  if (prof) { DGC_HIP_TRY(hipEventRecord(L->evx[3], st)); DGC_HIP_TRY(hipEventRecord(L->evx[4], st)); }
   evolve_backward_bptt(L->evo, st);
+  if (prof) { DGC_HIP_TRY(hipEventRecord(L->evx[5], st)); L->evx_bwd = true; }
   DGC_HIP_TRY(hipGetLastError());
   L->has_grads = true;
   return DGC_OK;

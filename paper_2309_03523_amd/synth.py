@@ -345,6 +345,27 @@ def config3(seed: int = 0, scale: float = 1.0, windows: int = 1, random_bias: bo
     return wl
 
 
+def config4(seed: int = 0, scale: float = 1.0, random_bias: bool = False):
+    """EvolveGCN-O layer: 64 snapshots x (500,000 * scale) vertices, average degree 16 with tail
+    exponent 2.2, F = S = 256, 32 chunks = 4 windows of 16 snapshots x 8 even vertex ranges,
+    cache = X + 0.1 N(0,1), MSE targets ~ N(0,1).  Returns (workload, target)."""
+    T, F = 64, 256
+    N = max(256, int(500_000 * scale))
+    g_rng = stream(seed, "graph")
+    w = powerlaw_weights(N, 2.2, stream(seed, "perm"))
+    graph = DynamicGraph(N, [chung_lu_snapshot(N, 8 * N, w, g_rng) for _ in range(T)])
+    bounds = [np.linspace(0, N, 9).astype(np.int64)] * 4
+    chunks = grid_chunks(T, 16, bounds)
+    X = _normal_f32(stream(seed, "feat"), (T, N, F))
+    C = _normal_f32(stream(seed, "cache"), (T, N, F))
+    C *= np.float32(0.1)
+    C += X
+    target = _normal_f32(stream(seed, "target"), (T, N, F))
+    wl = Workload("config4" if scale == 1.0 else f"config4@{scale:g}", graph, chunks, F, F, F, "none", 1, X, C,
+                  None, None, evolve_params(seed, F, F, random_bias))
+    return wl, target
+
+
 def random_small(seed: int, T: int, N: int, F: int, S: int, H: int, avg_deg: float,
                  chunks: np.ndarray, time_kind: str = "gru", n_struct_layers: int = 1,
                  hub: bool = False) -> Workload:
