@@ -202,7 +202,10 @@ dgc_status_t build_evolve(dgc_layer* L, const std::vector<ChunkInfo>& cinfo, hip
     DGC_HIP_TRY(hipMemsetAsync(g.raw, 0, sizeof(float) * g.numel(), st));
     L->params[std::string(kEvolveNames[k]) + ".grad"] = g;
     ev.G[k] = g.raw;
+    DGC_HIP_TRY(dev_alloc(L, &ev.Pd[k], n));
+    DGC_HIP_TRY(dev_alloc(L, &ev.Gd[k], n));
   }
+  DGC_HIP_TRY(dev_alloc(L, &ev.Wt_f32, T * n));
   DGC_HIP_TRY(dev_alloc(L, &ev.Wt, T * n));
   DGC_HIP_TRY(dev_alloc(L, &ev.Zg, T * n));
   DGC_HIP_TRY(dev_alloc(L, &ev.Rg, T * n));
@@ -210,8 +213,7 @@ dgc_status_t build_evolve(dgc_layer* L, const std::vector<ChunkInfo>& cinfo, hip
   float* pk = nullptr;
   DGC_HIP_TRY(dev_alloc(L, &pk, (int64_t)T * packed_weight_elems(S, F)));
   ev.Wt_packed = reinterpret_cast<float4*>(pk);
-  float** tmps[6] = {&ev.tmp0, &ev.tmp1, &ev.tmp2, &ev.tmp3, &ev.tmp4, &ev.tmp5};
-  for (float** t : tmps) DGC_HIP_TRY(dev_alloc(L, t, n));
+  for (double*& t : ev.tmp) DGC_HIP_TRY(dev_alloc(L, &t, n));
   DGC_HIP_TRY(dev_alloc(L, &ev.dWd, T * n));
   DGC_HIP_TRY(dev_alloc(L, &ev.partial, evolve_partial_elems(T, F, S)));
   DGC_HIP_TRY(dev_alloc(L, &ev.loss_partial, evolve_loss_partial_elems(T)));

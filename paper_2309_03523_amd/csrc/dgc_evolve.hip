@@ -5,9 +5,9 @@
 // evolved once per snapshot over all T snapshots (global, independent of the chunk windows),
 // Y[t,i] = relu(M[t,i] W_t), mean-squared-error loss, gradients of all ten parameter matrices.
 //
-// Kernels here: a wave-per-tile fp32 MFMA GEMM for the small (F x F)(F x S) products of the
-// weight recurrence and of its back-propagation through time (latency-bound: 64 waves per
-// launch), the elementwise gate kernels, and the one large kernel of the backward pass,
+// Kernels here: a double-precision MFMA kernel that fuses the small (F x F)(F x S) products of
+// one step of the weight recurrence, or of its back-propagation through time, with the gate
+// arithmetic that follows them (latency-bound), and the one large kernel of the backward pass,
 // dW_t = M_t^T dP_t reduced over all rows of snapshot t across the fused chunks.
 #include "dgc_internal.h"
 
@@ -19,96 +19,117 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 __device__ __forceinline__ float f4get(const float4& v, int q) { return q == 0 ? v.x : q == 1 ? v.y : q == 2 ? v.z : v.w; }
 __device__ __forceinline__ float sigmoidf_(float x) { return 1.0f / (1.0f + expf(-x)); }
 
-// C[M][N] (+)= op(A) op(B), one wave per 32 x 32 tile of C; K a multiple of 8.
-//  TA = false: A stored [M][K] (lda = K)      TA = true: A stored [K][M] (lda = M)
-//  TB = false: B stored [K][N] (ldb = N)      TB = true: B stored [N][K] (ldb = K)
-template <bool TA, bool TB>
-__global__ __launch_bounds__(64) void k_small_gemm(const float* A, const float* B, float* C, int M, int N, int K,
-                                                   int accumulate) {
-  const int lane = threadIdx.x, l32 = lane & 31, half = lane >> 5;
-  const int n0 = blockIdx.x * 32, m0 = blockIdx.y * 32;
-  const int lda = TA ? M : K, ldb = TB ? K : N;
-  floatx16 acc = (floatx16)(0.f);
-  for (int kb = 0; kb < K; kb += 8) {
-    const int k = kb + 4 * half;
-    float4 a, b;
-    if (TA) {
-      a = make_float4(A[(int64_t)(k + 0) * lda + m0 + l32], A[(int64_t)(k + 1) * lda + m0 + l32],
-                      A[(int64_t)(k + 2) * lda + m0 + l32], A[(int64_t)(k + 3) * lda + m0 + l32]);
-    } else {
-      a = *reinterpret_cast<const float4*>(A + (int64_t)(m0 + l32) * lda + k);
+// ---------------------------------------------------------------------------------------------
+// The weight recurrence and its back-propagation through time run in DOUBLE precision: W is the
+// state of a 64-step recurrence whose rounding errors feed every output row of every snapshot,
+// and the work is tiny (a handful of n x n x n products per step, n = F = S <= 256), so it is
+// latency-bound whatever the precision.  One kernel does every matrix step:
+//   tile(C) = [C +] sum_p op(A_p) op(B_p)   followed by an elementwise epilogue,
+// on v_mfma_f64_16x16x4f64 (lane l supplies A[l%16][l/16], B[l/16][l%16]; receives
+// D[4*v + l/16][l%16], v = 0..3).  A workgroup of 4 waves owns one 16 x 16 tile; the waves
+// split K and wave 0 adds their partial tiles in wave order (reproducible) and applies the
+// epilogue.  grid.z selects one of several independent jobs of a launch.
+typedef double doublex4 __attribute__((ext_vector_type(4)));
+
+struct EvProd { const double* A; const double* B; int ta, tb; };  // ta: A stored [K][M]; tb: B stored [N][K]
+enum { EPI_ADD = 0, EPI_ZR = 1, EPI_OUT = 2, EPI_BWD2 = 3, EPI_G = 4 };
+struct EvJob {
+  EvProd p[5];
+  int np;
+  double* C;           // EPI_ADD: C += sum
+  // operands of the epilogues (see k_ev_mm)
+  const double* bias;  // ZR, OUT: gate bias
+  const double* W;     // ZR, OUT, BWD2: previous weights
+  const double* z;     // OUT: update gate      BWD2: reset gate r
+  double* o0;          // ZR: gate out          OUT: Wc      BWD2: dAr     G: running gradient G
+  double* o1;          // ZR(r job): Rg*W       OUT: W_t     BWD2: dWp (+=)   G: dWp (read)
+  float* o2;           // OUT: W_t in fp32 (for the dense kernels)
+  double* o3;          // BWD2: gradient of B_r (+=)
+  int write_rw;        // ZR: this is the r job
+};
+struct EvJobs { EvJob j[4]; };
+
+__device__ __forceinline__ double sigmoidd(double x) { return 1.0 / (1.0 + exp(-x)); }
+
+template <int EPI>
+__global__ __launch_bounds__(256) void k_ev_mm(EvJobs jobs, int n) {
+  __shared__ double part[4][64][4];
+  const EvJob& J = jobs.j[blockIdx.z];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, kq = lane >> 4;
+  const int n0 = blockIdx.x * 16, m0 = blockIdx.y * 16;
+  const int kspan = n / 4;  // K = n, a quarter per wave; n is a multiple of 32
+  doublex4 acc = {0.0, 0.0, 0.0, 0.0};
+  for (int p = 0; p < J.np; ++p) {
+    const int ak = J.p[p].ta ? n : 1, am = J.p[p].ta ? 1 : n;   // strides of A along k and m
+    const int bk = J.p[p].tb ? 1 : n, bn = J.p[p].tb ? n : 1;
+    const int k0 = wave * kspan + kq;
+    const double* A = J.p[p].A + (int64_t)(m0 + l16) * am + (int64_t)k0 * ak;
+    const double* B = J.p[p].B + (int64_t)(n0 + l16) * bn + (int64_t)k0 * bk;
+    for (int k = 0; k < kspan; k += 8) {   // kspan is a multiple of 8
+      const double a0 = A[(int64_t)k * ak], a1 = A[(int64_t)(k + 4) * ak];
+      const double b0 = B[(int64_t)k * bk], b1 = B[(int64_t)(k + 4) * bk];
+      acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc, 0, 0, 0);
     }
-    if (TB) {
-      b = *reinterpret_cast<const float4*>(B + (int64_t)(n0 + l32) * ldb + k);
-    } else {
-      b = make_float4(B[(int64_t)(k + 0) * ldb + n0 + l32], B[(int64_t)(k + 1) * ldb + n0 + l32],
-                      B[(int64_t)(k + 2) * ldb + n0 + l32], B[(int64_t)(k + 3) * ldb + n0 + l32]);
-    }
-#pragma unroll
-    for (int q = 0; q < 4; ++q) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(f4get(a, q), f4get(b, q), acc, 0, 0, 0);
   }
 #pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const int row = m0 + 8 * (v / 4) + 4 * half + (v % 4);
-    float* c = C + (int64_t)row * N + n0 + l32;
-    *c = accumulate ? *c + acc[v] : acc[v];
+  for (int v = 0; v < 4; ++v) part[wave][lane][v] = acc[v];
+  __syncthreads();
+  if (wave != 0) return;
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    const double sum = ((part[0][lane][v] + part[1][lane][v]) + part[2][lane][v]) + part[3][lane][v];
+    const int64_t e = (int64_t)(m0 + 4 * v + kq) * n + n0 + l16;
+    if (EPI == EPI_ADD) {
+      J.C[e] += sum;
+    } else if (EPI == EPI_ZR) {
+      const double g = sigmoidd(sum + J.bias[e]);
+      J.o0[e] = g;
+      if (J.write_rw) J.o1[e] = g * J.W[e];
+    } else if (EPI == EPI_OUT) {
+      const double c = tanh(sum + J.bias[e]);
+      const double zz = J.z[e];
+      const double wn = (1.0 - zz) * J.W[e] + zz * c;
+      J.o0[e] = c;
+      J.o1[e] = wn;
+      J.o2[e] = (float)wn;
+    } else if (EPI == EPI_BWD2) {   // sum = Vh^T dAh = gradient of (Rg * W)
+      const double rr = J.z[e];
+      const double dar = sum * J.W[e] * rr * (1.0 - rr);
+      J.o0[e] = dar;
+      J.o1[e] += sum * rr;
+      J.o3[e] += dar;
+    } else {                        // EPI_G: G_{t-1} = dWp + sum
+      J.o0[e] = J.o1[e] + sum;
+    }
   }
 }
 
-// forward gates: z = sig(az + Bz), r = sig(ar + Br), rw = r * W
-__global__ void k_ev_zr(const float* az, const float* ar, const float* Bz, const float* Br, const float* W,
-                        float* z, float* r, float* rw, int64_t n) {
+// backward, first elementwise half of a step
+__global__ void k_ev_bwd1(double* G, const float* dWd, const double* z, const double* r, const double* c,
+                          const double* Wp, double* dWp, double* dAh, double* dAz, double* rw, double* gBh,
+                          double* gBz, int64_t n) {
   const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= n) return;
-  const float zz = sigmoidf_(az[e] + Bz[e]), rr = sigmoidf_(ar[e] + Br[e]);
-  z[e] = zz; r[e] = rr; rw[e] = rr * W[e];
-}
-
-// c = tanh(ah + Bh),  W' = (1 - z) W + z c
-__global__ void k_ev_out(const float* ah, const float* Bh, const float* z, const float* W, float* c, float* Wn,
-                         int64_t n) {
-  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= n) return;
-  const float cc = tanhf(ah[e] + Bh[e]);
-  c[e] = cc;
-  Wn[e] = (1.0f - z[e]) * W[e] + z[e] * cc;
-}
-
-// backward, first half of a step: G += direct gradient of W_t; gate gradients that need no GEMM
-__global__ void k_ev_bwd1(float* G, const float* dWd, const float* z, const float* r, const float* c,
-                          const float* Wp, float* dWp, float* dAh, float* dAz, float* rw, float* gBh, float* gBz,
-                          int64_t n) {
-  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= n) return;
-  const float g = G[e] + dWd[e];
-  G[e] = g;
-  const float zz = z[e], cc = c[e], wp = Wp[e];
-  const float dz = g * (cc - wp), dc = g * zz;
-  dWp[e] = g * (1.0f - zz);
-  const float ah = dc * (1.0f - cc * cc), azv = dz * zz * (1.0f - zz);
+  const double g = G[e] + (double)dWd[e];
+  const double zz = z[e], cc = c[e], wp = Wp[e];
+  const double dz = g * (cc - wp), dc = g * zz;
+  dWp[e] = g * (1.0 - zz);
+  const double ah = dc * (1.0 - cc * cc), azv = dz * zz * (1.0 - zz);
   dAh[e] = ah; dAz[e] = azv;
   rw[e] = r[e] * wp;
   gBh[e] += ah; gBz[e] += azv;
 }
 
-// second half: tmp = Vh^T dAh is the gradient of (Rg * W)
-__global__ void k_ev_bwd2(const float* tmp, const float* r, const float* Wp, float* dWp, float* dAr, float* gBr,
-                          int64_t n) {
+__global__ void k_to_double(double* dst, const float* src, int64_t n) {
   const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= n) return;
-  const float rr = r[e], tv = tmp[e];
-  const float arv = tv * Wp[e] * rr * (1.0f - rr);
-  dAr[e] = arv;
-  dWp[e] += tv * rr;
-  gBr[e] += arv;
+  if (e < n) dst[e] = (double)src[e];
 }
-
-__global__ void k_copy(float* dst, const float* src, int64_t n) {
+__global__ void k_to_float(float* dst, const double* src, int64_t n) {
   const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e < n) dst[e] = src[e];
+  if (e < n) dst[e] = (float)src[e];
 }
-
-__global__ void k_fill(float* dst, float v, int64_t n) {
+__global__ void k_fill_d(double* dst, double v, int64_t n) {
   const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (e < n) dst[e] = v;
 }
@@ -297,12 +318,9 @@ __global__ void k_loss_reduce(const float* loss_partial, int64_t n, float inv_co
 
 inline unsigned blocks_for(int64_t n) { return (unsigned)((n + 255) / 256); }
 
-void gemm(bool ta, bool tb, const float* A, const float* B, float* C, int M, int N, int K, bool acc, hipStream_t st) {
-  const dim3 grid(N / 32, M / 32);
-  if (!ta && !tb) hipLaunchKernelGGL((k_small_gemm<false, false>), grid, 64, 0, st, A, B, C, M, N, K, (int)acc);
-  if (ta && !tb) hipLaunchKernelGGL((k_small_gemm<true, false>), grid, 64, 0, st, A, B, C, M, N, K, (int)acc);
-  if (!ta && tb) hipLaunchKernelGGL((k_small_gemm<false, true>), grid, 64, 0, st, A, B, C, M, N, K, (int)acc);
-  if (ta && tb) hipLaunchKernelGGL((k_small_gemm<true, true>), grid, 64, 0, st, A, B, C, M, N, K, (int)acc);
+template <int EPI>
+void launch_mm(const EvJobs& jobs, int n_jobs, int n, hipStream_t st) {
+  hipLaunchKernelGGL((k_ev_mm<EPI>), dim3(n / 16, n / 16, n_jobs), 256, 0, st, jobs, n);
 }
 
 }  // namespace
@@ -310,25 +328,29 @@ void gemm(bool ta, bool tb, const float* A, const float* B, float* C, int M, int
 int64_t evolve_partial_elems(int32_t T, int32_t F, int32_t S) { return (int64_t)T * kSplit * F * S; }
 int64_t evolve_loss_partial_elems(int32_t T) { return (int64_t)T * kSplit; }
 
-// Evolve W_t for t = 0..T-1 (ws.Wt, gates ws.Zg/Rg/Wc) and pack every W_t for the dense kernels.
+// Evolve W_t for t = 0..T-1 (ws.Wt, gates ws.Zg/Rg/Wc, all double) and pack every W_t, rounded
+// to fp32, for the dense kernels.  Two launches per snapshot.
 void evolve_forward_weights(const EvolveWs& ws, hipStream_t st) {
-  const int F = ws.F, S = ws.S;
-  const int64_t n = (int64_t)F * S;
-  const unsigned nb = blocks_for(n);
+  const int n = ws.F;
+  const int64_t nn = (int64_t)n * n;
+  for (int k = 0; k < EV_NPAR; ++k) hipLaunchKernelGGL(k_to_double, blocks_for(nn), 256, 0, st, ws.Pd[k], ws.P[k], nn);
   for (int t = 0; t < ws.T; ++t) {
-    const float* W = t ? ws.Wt + (t - 1) * n : ws.P[EV_W];
-    float *z = ws.Zg + t * n, *r = ws.Rg + t * n, *c = ws.Wc + t * n, *Wn = ws.Wt + t * n;
-    gemm(false, false, ws.P[EV_UZ], W, ws.tmp0, F, S, F, false, st);
-    gemm(false, false, ws.P[EV_VZ], W, ws.tmp0, F, S, F, true, st);
-    gemm(false, false, ws.P[EV_UR], W, ws.tmp1, F, S, F, false, st);
-    gemm(false, false, ws.P[EV_VR], W, ws.tmp1, F, S, F, true, st);
-    hipLaunchKernelGGL(k_ev_zr, nb, 256, 0, st, ws.tmp0, ws.tmp1, ws.P[EV_BZ], ws.P[EV_BR], W, z, r, ws.tmp2, n);
-    gemm(false, false, ws.P[EV_UH], W, ws.tmp0, F, S, F, false, st);
-    gemm(false, false, ws.P[EV_VH], ws.tmp2, ws.tmp0, F, S, F, true, st);
-    hipLaunchKernelGGL(k_ev_out, nb, 256, 0, st, ws.tmp0, ws.P[EV_BH], z, W, c, Wn, n);
+    const double* W = t ? ws.Wt + (t - 1) * nn : ws.Pd[EV_W];
+    double *z = ws.Zg + t * nn, *r = ws.Rg + t * nn, *c = ws.Wc + t * nn, *Wn = ws.Wt + t * nn;
+    EvJobs zr{};
+    zr.j[0].p[0] = {ws.Pd[EV_UZ], W, 0, 0}; zr.j[0].p[1] = {ws.Pd[EV_VZ], W, 0, 0}; zr.j[0].np = 2;
+    zr.j[0].bias = ws.Pd[EV_BZ]; zr.j[0].W = W; zr.j[0].o0 = z; zr.j[0].write_rw = 0;
+    zr.j[1].p[0] = {ws.Pd[EV_UR], W, 0, 0}; zr.j[1].p[1] = {ws.Pd[EV_VR], W, 0, 0}; zr.j[1].np = 2;
+    zr.j[1].bias = ws.Pd[EV_BR]; zr.j[1].W = W; zr.j[1].o0 = r; zr.j[1].o1 = ws.tmp[2]; zr.j[1].write_rw = 1;
+    launch_mm<EPI_ZR>(zr, 2, n, st);
+    EvJobs out{};
+    out.j[0].p[0] = {ws.Pd[EV_UH], W, 0, 0}; out.j[0].p[1] = {ws.Pd[EV_VH], ws.tmp[2], 0, 0}; out.j[0].np = 2;
+    out.j[0].bias = ws.Pd[EV_BH]; out.j[0].W = W; out.j[0].z = z; out.j[0].o0 = c; out.j[0].o1 = Wn;
+    out.j[0].o2 = ws.Wt_f32 + t * nn;
+    launch_mm<EPI_OUT>(out, 1, n, st);
   }
-  const int64_t per = (int64_t)(S / 32) * ((F + 7) / 8) * 64;
-  hipLaunchKernelGGL(k_pack_weight_t, blocks_for(per * ws.T), 256, 0, st, ws.Wt, ws.T, F, S, ws.Wt_packed);
+  const int64_t per = (int64_t)(ws.S / 32) * ((ws.F + 7) / 8) * 64;
+  hipLaunchKernelGGL(k_pack_weight_t, blocks_for(per * ws.T), 256, 0, st, ws.Wt_f32, ws.T, ws.F, ws.S, ws.Wt_packed);
 }
 
 // dWd[t] for all t (and the loss), from the saved aggregated rows and the layer's output.
@@ -376,38 +398,42 @@ bool evolve_backward_dw(const EvolveWs& ws, const EvolveBwdIn& in, hipStream_t s
   return true;
 }
 
-// Back-propagation through time over the weight recurrence: fills ws.G[k] for the ten parameters.
+// Back-propagation through time over the weight recurrence (double precision, four launches
+// per snapshot); the gradients of the ten parameters end up in ws.G[k] as fp32.
 void evolve_backward_bptt(const EvolveWs& ws, hipStream_t st) {
-  const int F = ws.F, S = ws.S;
-  const int64_t n = (int64_t)F * S, nff = (int64_t)F * F;
-  const unsigned nb = blocks_for(n);
-  for (int k = 0; k < EV_NPAR; ++k) {
-    const int64_t sz = (k == EV_W || k == EV_BZ || k == EV_BR || k == EV_BH) ? n : nff;
-    hipLaunchKernelGGL(k_fill, blocks_for(sz), 256, 0, st, ws.G[k], 0.f, sz);
-  }
-  float* Gt = ws.G[EV_W];  // running dL/dW_t; ends as the gradient of W_init
+  const int n = ws.F;
+  const int64_t nn = (int64_t)n * n;
+  const unsigned nb = blocks_for(nn);
+  for (int k = 0; k < EV_NPAR; ++k) hipLaunchKernelGGL(k_fill_d, nb, 256, 0, st, ws.Gd[k], 0.0, nn);
+  double* Gt = ws.Gd[EV_W];  // running dL/dW_t; ends as the gradient of W_init
+  double *dWp = ws.tmp[0], *dAh = ws.tmp[1], *dAz = ws.tmp[2], *rw = ws.tmp[3], *dAr = ws.tmp[5];
   for (int t = ws.T - 1; t >= 0; --t) {
-    const float* Wp = t ? ws.Wt + (t - 1) * n : ws.P[EV_W];
-    const float *z = ws.Zg + t * n, *r = ws.Rg + t * n, *c = ws.Wc + t * n;
-    float *dWp = ws.tmp0, *dAh = ws.tmp1, *dAz = ws.tmp2, *rw = ws.tmp3, *tmp = ws.tmp4, *dAr = ws.tmp5;
-    hipLaunchKernelGGL(k_ev_bwd1, nb, 256, 0, st, Gt, ws.dWd + t * n, z, r, c, Wp, dWp, dAh, dAz, rw, ws.G[EV_BH],
-                       ws.G[EV_BZ], n);
-    gemm(false, true, dAh, Wp, ws.G[EV_UH], F, F, S, true, st);    // dUh += dAh Wp^T
-    gemm(false, true, dAh, rw, ws.G[EV_VH], F, F, S, true, st);    // dVh += dAh (Rg*Wp)^T
-    gemm(true, false, ws.P[EV_VH], dAh, tmp, F, S, F, false, st);  // Vh^T dAh
-    hipLaunchKernelGGL(k_ev_bwd2, nb, 256, 0, st, tmp, r, Wp, dWp, dAr, ws.G[EV_BR], n);
-    gemm(true, false, ws.P[EV_UH], dAh, dWp, F, S, F, true, st);
-    gemm(false, true, dAz, Wp, ws.G[EV_UZ], F, F, S, true, st);    // dUz += dAz Wp^T  (= dVz)
-    gemm(false, true, dAr, Wp, ws.G[EV_UR], F, F, S, true, st);    // dUr += dAr Wp^T  (= dVr)
-    gemm(true, false, ws.P[EV_UZ], dAz, dWp, F, S, F, true, st);
-    gemm(true, false, ws.P[EV_VZ], dAz, dWp, F, S, F, true, st);
-    gemm(true, false, ws.P[EV_UR], dAr, dWp, F, S, F, true, st);
-    gemm(true, false, ws.P[EV_VR], dAr, dWp, F, S, F, true, st);
-    hipLaunchKernelGGL(k_copy, nb, 256, 0, st, Gt, dWp, n);
+    const double* Wp = t ? ws.Wt + (t - 1) * nn : ws.Pd[EV_W];
+    const double *z = ws.Zg + t * nn, *r = ws.Rg + t * nn, *c = ws.Wc + t * nn;
+    hipLaunchKernelGGL(k_ev_bwd1, nb, 256, 0, st, Gt, ws.dWd + t * nn, z, r, c, Wp, dWp, dAh, dAz, rw, ws.Gd[EV_BH],
+                       ws.Gd[EV_BZ], nn);
+    EvJobs b2{};   // Vh^T dAh -> dAr, dWp += ., dB_r += .
+    b2.j[0].p[0] = {ws.Pd[EV_VH], dAh, 1, 0}; b2.j[0].np = 1;
+    b2.j[0].W = Wp; b2.j[0].z = r; b2.j[0].o0 = dAr; b2.j[0].o1 = dWp; b2.j[0].o3 = ws.Gd[EV_BR];
+    launch_mm<EPI_BWD2>(b2, 1, n, st);
+    EvJobs gr{};   // dUh += dAh Wp^T, dVh += dAh (Rg*Wp)^T, dUz += dAz Wp^T, dUr += dAr Wp^T
+    gr.j[0].p[0] = {dAh, Wp, 0, 1}; gr.j[0].np = 1; gr.j[0].C = ws.Gd[EV_UH];
+    gr.j[1].p[0] = {dAh, rw, 0, 1}; gr.j[1].np = 1; gr.j[1].C = ws.Gd[EV_VH];
+    gr.j[2].p[0] = {dAz, Wp, 0, 1}; gr.j[2].np = 1; gr.j[2].C = ws.Gd[EV_UZ];
+    gr.j[3].p[0] = {dAr, Wp, 0, 1}; gr.j[3].np = 1; gr.j[3].C = ws.Gd[EV_UR];
+    launch_mm<EPI_ADD>(gr, 4, n, st);
+    EvJobs g{};    // G_{t-1} = dWp + Uh^T dAh + (Uz + Vz)^T dAz + (Ur + Vr)^T dAr
+    g.j[0].p[0] = {ws.Pd[EV_UH], dAh, 1, 0}; g.j[0].p[1] = {ws.Pd[EV_UZ], dAz, 1, 0};
+    g.j[0].p[2] = {ws.Pd[EV_VZ], dAz, 1, 0}; g.j[0].p[3] = {ws.Pd[EV_UR], dAr, 1, 0};
+    g.j[0].p[4] = {ws.Pd[EV_VR], dAr, 1, 0}; g.j[0].np = 5;
+    g.j[0].o0 = Gt; g.j[0].o1 = dWp;
+    launch_mm<EPI_G>(g, 1, n, st);
   }
   // the input of the GRU is the state itself, so Uz, Vz (and Ur, Vr) receive identical gradients
-  hipLaunchKernelGGL(k_copy, blocks_for(nff), 256, 0, st, ws.G[EV_VZ], ws.G[EV_UZ], nff);
-  hipLaunchKernelGGL(k_copy, blocks_for(nff), 256, 0, st, ws.G[EV_VR], ws.G[EV_UR], nff);
+  for (int k = 0; k < EV_NPAR; ++k) {
+    const double* src = k == EV_VZ ? ws.Gd[EV_UZ] : k == EV_VR ? ws.Gd[EV_UR] : ws.Gd[k];
+    hipLaunchKernelGGL(k_to_float, nb, 256, 0, st, ws.G[k], src, nn);
+  }
 }
 
 }  // namespace dgc

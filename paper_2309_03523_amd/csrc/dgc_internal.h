@@ -157,10 +157,13 @@ enum { EV_W = 0, EV_UZ, EV_VZ, EV_BZ, EV_UR, EV_VR, EV_BR, EV_UH, EV_VH, EV_BH, 
 struct EvolveWs {
   int32_t T, F, S;
   const float* P[EV_NPAR];   // parameters (device, fp32): W_init, Uz, Vz, Bz, Ur, Vr, Br, Uh, Vh, Bh
-  float* G[EV_NPAR];         // their gradients
-  float *Wt, *Zg, *Rg, *Wc;  // [T][F][S]: evolved weights and the gates that produced them
-  float4* Wt_packed;         // every W_t^T in MFMA fragment order
-  float *tmp0, *tmp1, *tmp2, *tmp3, *tmp4, *tmp5;  // [F][S] scratch
+  float* G[EV_NPAR];         // their gradients (fp32, what the caller reads)
+  double* Pd[EV_NPAR];       // the parameters widened to double for the weight recurrence
+  double* Gd[EV_NPAR];       // gradient accumulators of the back-propagation through time
+  double *Wt, *Zg, *Rg, *Wc; // [T][F][S]: evolved weights and the gates that produced them
+  float* Wt_f32;             // [T][F][S]: W_t rounded to fp32
+  float4* Wt_packed;         // every W_t^T (fp32) in MFMA fragment order
+  double* tmp[6];            // [F][S] scratch
   float* dWd;                // [T][F][S] direct gradient of each W_t
   float* partial;            // [T][split][F][S]
   float* loss_partial;       // [T][split]
