@@ -397,3 +397,77 @@ def random_small(seed: int, T: int, N: int, F: int, S: int, H: int, avg_deg: flo
         h0 = (0.5 * _normal_f32(stream(seed, "h0b"), h0.shape)).astype(np.float32)
     return Workload(f"small{seed}", graph, chunks, F, S, H, time_kind, n_struct_layers, X, C, C1, h0,
                     layer_params(seed, F, S, H, time_kind, n_struct_layers, random_bias=True))
+
+
+# --------------------------------------------------------------------------- bf16 workloads
+
+
+def round_bf16(a: np.ndarray) -> np.ndarray:
+    """fp32 array whose values are exactly representable in bfloat16 (round to nearest even)."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(a.shape)
+
+
+def to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    """uint16 bit patterns of an fp32 array that is already bf16-representable."""
+    return (np.ascontiguousarray(a, dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16).reshape(a.shape)
+
+
+def from_bf16_bits(b: np.ndarray) -> np.ndarray:
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32).reshape(b.shape)
+
+
+DYSAT_PARAMS = ["gat.weight", "gat.att_src", "gat.att_dst", "attn.pos", "attn.weight_q", "attn.weight_k",
+                "attn.weight_v"]
+
+
+def dysat_params(seed: int, T: int, F: int, S: int, heads: int) -> dict:
+    """Parameters of the graph-attention + temporal self-attention layer, bf16-representable:
+    gat.weight [S,F] (out, in), gat.att_src / gat.att_dst [heads, S/heads], attn.pos [T,S],
+    attn.weight_q/k/v [S,S] (out, in).  Xavier-uniform; positions N(0, 0.1^2)."""
+    rng = stream(seed, "param")
+    D = S // heads
+    p = {
+        "gat.weight": xavier_uniform(rng, S, F),
+        "gat.att_src": xavier_uniform(rng, heads, D),
+        "gat.att_dst": xavier_uniform(rng, heads, D),
+        "attn.pos": (0.1 * rng.standard_normal((T, S))).astype(np.float32),
+        "attn.weight_q": xavier_uniform(rng, S, S),
+        "attn.weight_k": xavier_uniform(rng, S, S),
+        "attn.weight_v": xavier_uniform(rng, S, S),
+    }
+    return {k: round_bf16(v) for k, v in p.items()}
+
+
+def dysat_small(seed: int, T: int, N: int, F: int, heads: int, avg_deg: float, chunks, hub: bool = False):
+    """Small random graph-attention workload (S = F), all tensors bf16-representable."""
+    wl = random_small(seed, T, N, F, F, F, avg_deg, chunks, "none", hub=hub)
+    wl.X = round_bf16(wl.X)
+    wl.C = round_bf16(wl.C)
+    wl.params = dysat_params(seed, T, F, F, heads)
+    wl.notes["heads"] = heads
+    return wl
+
+
+def config5(seed: int = 0, scale: float = 1.0):
+    """Graph attention + causal temporal self-attention, bf16: 16 snapshots x (1,000,000 * scale)
+    vertices, average degree 12 with tail exponent 2.1, F = S = 128, 8 heads, 128 uneven vertex
+    ranges x one 16-snapshot window, cache = X + 0.1 N(0,1), MSE targets ~ N(0,1).
+    Returns (workload, target)."""
+    T, F, heads = 16, 128, 8
+    N = max(1024, int(1_000_000 * scale))
+    g_rng = stream(seed, "graph")
+    w = powerlaw_weights(N, 2.1, stream(seed, "perm"))
+    graph = DynamicGraph(N, [chung_lu_snapshot(N, 6 * N, w, g_rng) for _ in range(T)])
+    bounds = [uneven_ranges(N, 128, stream(seed, "ranges"))]
+    chunks = grid_chunks(T, 16, bounds)
+    X = _normal_f32(stream(seed, "feat"), (T, N, F))
+    C = _normal_f32(stream(seed, "cache"), (T, N, F))
+    C *= np.float32(0.1)
+    C += X
+    target = round_bf16(_normal_f32(stream(seed, "target"), (T, N, F)))
+    wl = Workload("config5" if scale == 1.0 else f"config5@{scale:g}", graph, chunks, F, F, F, "none", 1,
+                  round_bf16(X), round_bf16(C), None, None, dysat_params(seed, T, F, F, heads))
+    wl.notes["heads"] = heads
+    return wl, target
