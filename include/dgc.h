@@ -14,8 +14,9 @@
  *  - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
  *    host memory.  The library never frees caller memory and only borrows it while the work
  *    it enqueued is running.
- *  - All floating tensors are fp32, row-major, with a row pitch (ld*, in elements) that is a
- *    multiple of 4 and a base address aligned to 16 bytes.
+ *  - Floating tensors are row-major with a base address aligned to 16 bytes; their element type
+ *    is the layer's dtype: fp32 (row pitch ld*, in elements, a multiple of 4) or bfloat16 (pitch a
+ *    multiple of 8), passed as void*.  Parameters and their gradients are always fp32.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *  - forward / aggregate / gather only enqueue work: they return argument errors at once and
  *    never synchronise the device.  create / set_param / get_param / packing synchronise.
@@ -47,10 +48,20 @@ typedef enum {
 /* Structure encoder: GCN convolution with fixed weights, or EvolveGCN-O (the GCN weight matrix
  * is the state of a matrix GRU and evolves from snapshot to snapshot; Section 1 lists EvolveGCN
  * among the DGNNs the method targets). */
-enum { DGC_STRUCT_GCN = 0, DGC_STRUCT_EVOLVE_GCN_O = 1 };
-enum { DGC_TIME_NONE = 0, DGC_TIME_GRU = 1, DGC_TIME_LSTM = 2 };
+enum { DGC_STRUCT_GCN = 0, DGC_STRUCT_EVOLVE_GCN_O = 1, DGC_STRUCT_GAT = 2 };
+enum { DGC_TIME_NONE = 0, DGC_TIME_GRU = 1, DGC_TIME_LSTM = 2, DGC_TIME_SELF_ATTN = 3 };
 enum { DGC_ACT_NONE = 0, DGC_ACT_RELU = 1 };
-enum { DGC_DTYPE_F32 = 0 };
+enum { DGC_DTYPE_F32 = 0, DGC_DTYPE_BF16 = 1 };
+/* DGC_STRUCT_GAT + DGC_TIME_SELF_ATTN + DGC_DTYPE_BF16 (the three go together) is the DySAT-style
+ * DGNN of Sections 2.1 and 6: a one-layer graph attention structure encoder and a one-layer
+ * scaled dot-product self-attention time encoder in which every vertex attends, causally, to
+ * its own embeddings in the snapshots of the chunk's window.  Built for F = S = 128, heads = 8,
+ * windows of at most 16 snapshots; act_hidden / act_out / gather_mode / dense_kernel are ignored
+ * (ELU follows the structure encoder; neighbours are read in place):
+ *   z = W x for rows inside the chunk range, W c for cache rows;
+ *   e_ij^h = LeakyReLU_0.2(a_dst^h . z_i^h + a_src^h . z_j^h), alpha = softmax over the stored row,
+ *   g_i = ELU(sum_j alpha_ij z_j);  p_s = g_s + pos[s] (s = absolute snapshot index);
+ *   q, k, v = W_q p, W_k p, W_v p;  y_s^h = sum_{r <= s, r in window} softmax_r(q_s^h . k_r^h / 4) v_r^h. */
 /* How rows of neighbours outside the chunk reach the aggregation (Section 5.2):
  *  IN_PLACE the aggregation kernel reads the cache tensor directly;
  *  STAGED   a gather kernel first copies each segment's de-duplicated halo rows (loaded once
@@ -86,7 +97,7 @@ typedef struct {
   int32_t struct_kind;     /* DGC_STRUCT_*                                                   */
   int32_t n_struct_layers; /* 1 or 2 stacked GCN layers                                      */
   int32_t time_kind;       /* DGC_TIME_*                                                     */
-  int32_t dtype;           /* DGC_DTYPE_F32                                                  */
+  int32_t dtype;           /* DGC_DTYPE_*: element type of X, C, Y, dY, target               */
   int32_t F, S, H;         /* input dim, structure-encoder output dim, hidden dim.  S and H
                               multiples of 32, at most 256; F at most 512                    */
   int32_t act_hidden;      /* activation between stacked GCN layers                          */
@@ -97,6 +108,7 @@ typedef struct {
   int32_t long_nnz;        /* work list: rows longer than this are split (0 = default 1024)  */
   int32_t part_nnz;        /* work list: non-zeros per part of a split row (0 = default 512) */
   int32_t dense_kernel;    /* DGC_DENSE_*                                                    */
+  int32_t heads;           /* attention heads (DGC_STRUCT_GAT: 8; otherwise ignored)         */
 } dgc_layer_desc_t;
 
 /* Build a layer for a fixed graph and a fixed set of chunks (the paper partitions once per
@@ -123,6 +135,9 @@ dgc_status_t dgc_layer_destroy(dgc_layer_t* layer);
  *    Zg = sig(U_z W + V_z W + B_z)  Rg = sig(U_r W + V_r W + B_r)
  *    Wc = tanh(U_h W + V_h (Rg*W) + B_h)   W_t = (1 - Zg)*W + Zg*Wc,   W = W_{t-1}, W_{-1} = W_init,
  *  for t = 0..T-1 whatever the chunk windows are, and Y[t,i] = relu(M[t,i] W_t).
+ * DGC_STRUCT_GAT has "gat.weight" [S,F] (out, in)  "gat.att_src" "gat.att_dst" [heads, S/heads]
+ *  "attn.pos" [T,S]  "attn.weight_q" "attn.weight_k" "attn.weight_v" [S,S] (out, in); values are
+ *  rounded to bfloat16 where the kernels use them as matrix operands.
  *  After dgc_layer_backward, "<name>.grad" reads the gradient of that parameter (get only).
  * host_src / host_dst: host, numel elements; numel must equal the parameter's size. */
 dgc_status_t dgc_layer_set_param(dgc_layer_t* layer, const char* name, const float* host_src,
@@ -145,15 +160,17 @@ dgc_status_t dgc_layer_get_param(dgc_layer_t* layer, const char* name, float* ho
  *     only rows covered by a chunk are written.
  *  HN device, same shape as H0, or NULL: state after each chunk's last snapshot.
  * X, C, C1, H0, reset_mask must not overlap Y or HN. */
-dgc_status_t dgc_layer_forward(dgc_layer_t* layer, const float* X, int64_t ldx, const float* C,
-                               int64_t ldc, const float* C1, int64_t ldc1, const float* H0,
-                               const uint8_t* reset_mask, float* Y, int64_t ldy, float* HN,
+dgc_status_t dgc_layer_forward(dgc_layer_t* layer, const void* X, int64_t ldx, const void* C,
+                               int64_t ldc, const void* C1, int64_t ldc1, const float* H0,
+                               const uint8_t* reset_mask, void* Y, int64_t ldy, float* HN,
                                void* stream);
 
 /* Backward pass: gradients of a scalar loss with respect to the layer's parameters, for the
  * batch of the last dgc_layer_forward on this layer (the layer keeps the aggregated rows of that
- * pass; a forward in between invalidates them).  Built for DGC_STRUCT_EVOLVE_GCN_O; other layers
- * return DGC_ERR_UNSUPPORTED.  DGC_ERR_STATE if no forward has run.
+ * pass; a forward in between invalidates them).  Built for DGC_STRUCT_EVOLVE_GCN_O and
+ * DGC_STRUCT_GAT; other layers return DGC_ERR_UNSUPPORTED.  DGC_ERR_STATE if no forward has run.
+ * DGC_STRUCT_GAT needs a symmetric adjacency (its gradient with respect to a neighbour's
+ * projection is gathered through the reverse edge).
  *  Y      device [T,N,ldy]: the output that forward wrote, unchanged.
  *  Exactly one of
  *   dY     device [T,N,lddy]: gradient of the loss with respect to Y (rows not covered by a
@@ -163,9 +180,9 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* layer, const float* X, int64_t ldx, 
  *  dX must be NULL (input gradients are not built).
  * The cache is a constant: no gradient flows into C.  Gradients are read with
  * dgc_layer_get_param(layer, "<name>.grad", ...).  Enqueues work only. */
-dgc_status_t dgc_layer_backward(dgc_layer_t* layer, const float* Y, int64_t ldy, const float* dY,
-                                int64_t lddy, const float* target, int64_t ldt, float* loss_out,
-                                float* dX, int64_t lddx, void* stream);
+dgc_status_t dgc_layer_backward(dgc_layer_t* layer, const void* Y, int64_t ldy, const void* dY,
+                                int64_t lddy, const void* target, int64_t ldt, float* loss_out,
+                                void* dX, int64_t lddx, void* stream);
 
 /* Steps of the path on their own (for measurement and element-wise checks).
  * dgc_layer_aggregate: the normalised neighbour aggregation of the first GCN layer,
@@ -188,11 +205,17 @@ dgc_status_t dgc_layer_gather(dgc_layer_t* layer, const float* C, int64_t ldc, f
  *  4 evolution of the GCN weights over the T snapshots   (EvolveGCN-O forward, else 0 ms)
  *  5 backward: weight-gradient reduction over the rows of every snapshot (+ loss)
  *  6 backward: back-propagation through time over the weight recurrence
+ *  7 graph attention: projection of input and cache rows       (DGC_STRUCT_GAT forward)
+ *  8 graph attention: edge softmax + aggregation
+ *  9 temporal self-attention
+ * 10 backward: temporal self-attention and its weight gradients
+ * 11 backward: graph attention, gradients of the attention logits (row pass)
+ * 12 backward: graph attention, gradients of the projections (reverse-edge pass) and of W
  * dgc_layer_set_profiling: enable != 0 makes every later forward / backward record the events.
  * dgc_layer_stage_times: waits for the last profiled forward (and backward, if one followed it)
  * and writes DGC_N_STAGES durations in milliseconds to host_ms (host); stages that did not run
  * read 0; DGC_ERR_STATE if no profiled forward was enqueued. */
-#define DGC_N_STAGES 7
+#define DGC_N_STAGES 13
 dgc_status_t dgc_layer_set_profiling(dgc_layer_t* layer, int32_t enable);
 dgc_status_t dgc_layer_stage_times(dgc_layer_t* layer, float* host_ms);
 

@@ -15,11 +15,12 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdgc.so")
 
-TIME_KIND = {"none": 0, "gru": 1, "lstm": 2}
+TIME_KIND = {"none": 0, "gru": 1, "lstm": 2, "self_attn": 3}
 ACT = {"none": 0, "relu": 1}
 GATHER = {"in_place": 0, "staged": 1}
 DENSE = {"auto": 0, "tile": 1, "wave": 2}
-STRUCT = {"gcn": 0, "evolve_gcn_o": 1}
+STRUCT = {"gcn": 0, "evolve_gcn_o": 1, "gat": 2}
+DTYPE = {"f32": 0, "bf16": 1}
 
 STATUS = {0: "DGC_OK", 1: "DGC_ERR_INVALID_ARG", 2: "DGC_ERR_BAD_GRAPH", 3: "DGC_ERR_BAD_CHUNK",
           4: "DGC_ERR_UNSUPPORTED", 5: "DGC_ERR_OOM", 6: "DGC_ERR_DEVICE", 7: "DGC_ERR_STATE"}
@@ -28,7 +29,7 @@ EXPORTS = ["dgc_layer_create", "dgc_layer_destroy", "dgc_layer_set_param", "dgc_
            "dgc_layer_forward", "dgc_layer_backward", "dgc_layer_aggregate", "dgc_layer_gather",
            "dgc_layer_packing", "dgc_layer_set_profiling", "dgc_layer_stage_times", "dgc_last_error",
            "dgc_version"]
-N_STAGES = 7
+N_STAGES = 13
 
 
 class DgcError(RuntimeError):
@@ -50,7 +51,7 @@ class DescT(ct.Structure):
     _fields_ = [(n, ct.c_int32) for n in
                 ("struct_kind", "n_struct_layers", "time_kind", "dtype", "F", "S", "H", "act_hidden",
                  "act_out", "gather_mode", "validate_level", "rows_per_group", "long_nnz", "part_nnz",
-                 "dense_kernel")]
+                 "dense_kernel", "heads")]
 
 
 _lib = None
@@ -131,7 +132,7 @@ class DgcLayer:
                  n_struct_layers: int = 1, act_hidden: str = "relu", act_out: str = "none",
                  gather_mode: str = "in_place", validate_level: int = 0, rows_per_group: int = 0,
                  long_nnz: int = 0, part_nnz: int = 0, dense_kernel: str = "auto", struct_kind: str = "gcn",
-                 stream=None):
+                 dtype: str = "f32", heads: int = 0, stream=None):
         import torch
         lib = load()
         self._lib = lib
@@ -148,9 +149,10 @@ class DgcLayer:
         graph = GraphT(T, N, rp, cj)
         ch = np.asarray(chunks, np.int64).reshape(-1, 4)
         carr = (ChunkT * len(ch))(*[ChunkT(int(a), int(b), int(c), int(d)) for a, b, c, d in ch])
-        desc = DescT(STRUCT[struct_kind], n_struct_layers, TIME_KIND[time_kind], 0, F, S, H, ACT[act_hidden],
+        desc = DescT(STRUCT[struct_kind], n_struct_layers, TIME_KIND[time_kind], DTYPE[dtype], F, S, H, ACT[act_hidden],
                      ACT[act_out],
-                     GATHER[gather_mode], validate_level, rows_per_group, long_nnz, part_nnz, DENSE[dense_kernel])
+                     GATHER[gather_mode], validate_level, rows_per_group, long_nnz, part_nnz, DENSE[dense_kernel],
+                     heads)
         rc = lib.dgc_layer_create(ct.byref(desc), ct.byref(graph), carr, len(ch), _stream_ptr(stream),
                                   ct.byref(self._h))
         if rc:
@@ -158,7 +160,7 @@ class DgcLayer:
         self.T, self.N, self.F, self.S, self.H = T, N, F, S, H
         self.time_kind, self.n_struct_layers = time_kind, n_struct_layers
         self.chunks = ch
-        self.out_dim = H if time_kind != "none" else S
+        self.out_dim = H if time_kind in ("gru", "lstm") else S
 
     # -- lifetime
     def destroy(self):

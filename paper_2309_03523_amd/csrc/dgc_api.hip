@@ -53,6 +53,9 @@ struct dgc_layer {
   float* d_Z1 = nullptr;                         // 2 layers: first layer's output [T,N,S]
   float* d_zero_bias = nullptr;                  // [S] zeros (EvolveGCN-O has no bias)
   EvolveWs evo{};                                // EvolveGCN-O workspace
+  DysatWs dy{};                                  // graph attention + temporal attention workspace
+  hipEvent_t evd[8] = {};                        // its stage boundaries: forward 0..3, backward 4..7
+  bool evd_fwd = false, evd_bwd = false;
   bool has_grads = false;
   std::map<std::string, Param> params;
   bool forward_done = false;
@@ -109,14 +112,28 @@ void free_all(dgc_layer* L) {
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 dgc_status_t check_desc(const dgc_layer_desc_t& d, std::string* msg) {
-  if (d.struct_kind != DGC_STRUCT_GCN && d.struct_kind != DGC_STRUCT_EVOLVE_GCN_O) {
-    *msg = "struct_kind: only DGC_STRUCT_GCN and DGC_STRUCT_EVOLVE_GCN_O are built"; return DGC_ERR_UNSUPPORTED;
+  if (d.struct_kind != DGC_STRUCT_GCN && d.struct_kind != DGC_STRUCT_EVOLVE_GCN_O && d.struct_kind != DGC_STRUCT_GAT) {
+    *msg = "unknown struct_kind"; return DGC_ERR_INVALID_ARG;
+  }
+  const bool gat = d.struct_kind == DGC_STRUCT_GAT;
+  if (gat != (d.time_kind == DGC_TIME_SELF_ATTN) || gat != (d.dtype == DGC_DTYPE_BF16)) {
+    *msg = "DGC_STRUCT_GAT, DGC_TIME_SELF_ATTN and DGC_DTYPE_BF16 are built only together";
+    return DGC_ERR_UNSUPPORTED;
+  }
+  if (gat) {
+    if (d.F != 128 || d.S != 128 || d.heads != 8 || d.n_struct_layers != 1) {
+      *msg = "the graph attention layer is built for F = S = 128, heads = 8, one layer"; return DGC_ERR_UNSUPPORTED;
+    }
+    if (d.validate_level < 0 || d.validate_level > 1) { *msg = "validate_level must be 0 or 1"; return DGC_ERR_INVALID_ARG; }
+    if (d.rows_per_group < 0 || d.rows_per_group > 32) { *msg = "rows_per_group must be in [0,32]"; return DGC_ERR_INVALID_ARG; }
+    if (d.long_nnz < 0 || d.part_nnz < 0) { *msg = "long_nnz / part_nnz must be >= 0"; return DGC_ERR_INVALID_ARG; }
+    return DGC_OK;
   }
   if (d.struct_kind == DGC_STRUCT_EVOLVE_GCN_O &&
       (d.time_kind != DGC_TIME_NONE || d.n_struct_layers != 1 || d.F != d.S || d.act_out != DGC_ACT_RELU)) {
     *msg = "EvolveGCN-O needs time_kind NONE, one layer, F = S and act_out RELU"; return DGC_ERR_INVALID_ARG;
   }
-  if (d.dtype != DGC_DTYPE_F32) { *msg = "dtype: only DGC_DTYPE_F32 is built"; return DGC_ERR_UNSUPPORTED; }
+  if (d.dtype != DGC_DTYPE_F32) { *msg = "unknown dtype"; return DGC_ERR_INVALID_ARG; }
   if (d.n_struct_layers < 1 || d.n_struct_layers > 2) { *msg = "n_struct_layers must be 1 or 2"; return DGC_ERR_INVALID_ARG; }
   if (d.time_kind < DGC_TIME_NONE || d.time_kind > DGC_TIME_LSTM) { *msg = "unknown time_kind"; return DGC_ERR_INVALID_ARG; }
   if (d.F < 1 || d.F > 512) { *msg = "F must be in [1,512]"; return DGC_ERR_INVALID_ARG; }
@@ -238,6 +255,72 @@ dgc_status_t build_evolve(dgc_layer* L, const std::vector<ChunkInfo>& cinfo, hip
   DGC_HIP_TRY(hipMemcpyAsync(d_ptr, ptr.data(), sizeof(int64_t) * (T + 1), hipMemcpyHostToDevice, st));
   DGC_HIP_TRY(hipStreamSynchronize(st));
   ev.items = d_items; ev.item_ptr = d_ptr;
+  return DGC_OK;
+}
+
+const char* const kDysatNames[DY_NPAR] = {"gat.weight", "gat.att_src", "gat.att_dst", "attn.pos",
+                                          "attn.weight_q", "attn.weight_k", "attn.weight_v"};
+
+// graph attention + temporal self-attention: parameters, operand fragments, workspace
+dgc_status_t build_dysat(dgc_layer* L, const std::vector<ChunkInfo>& cinfo, hipStream_t st) {
+  Failer fail{L};
+  const int32_t T = L->T, S = L->desc.S, heads = L->desc.heads;
+  const int64_t N = L->N, TN = (int64_t)T * N;
+  DysatWs& w = L->dy;
+  w.T = T; w.N = N; w.n_chunks = L->n_chunks;
+  w.g = L->graph_dev(); w.segs = L->d_segs; w.nseg = L->nseg; w.chunks = L->d_chunks;
+  w.work_short = L->d_work_short; w.n_short = L->n_short; w.total_rows = L->total_rows;
+  for (const ChunkInfo& c : cinfo)
+    if (c.w > 16) return fail(DGC_ERR_UNSUPPORTED, "the temporal self-attention is built for windows of at most 16 snapshots");
+  const int32_t rows_of[DY_NPAR] = {S, heads, heads, T, S, S, S};
+  const int32_t cols_of[DY_NPAR] = {S, S / heads, S / heads, S, S, S, S};
+  for (int k = 0; k < DY_NPAR; ++k) {
+    Param p;
+    p.n_out = rows_of[k]; p.n_in = cols_of[k];
+    DGC_HIP_TRY(dev_alloc(L, &p.raw, p.numel()));
+    DGC_HIP_TRY(hipMemsetAsync(p.raw, 0, sizeof(float) * p.numel(), st));
+    L->params[kDysatNames[k]] = p;
+    w.P[k] = p.raw;
+    Param g = p;
+    DGC_HIP_TRY(dev_alloc(L, &g.raw, g.numel()));
+    DGC_HIP_TRY(hipMemsetAsync(g.raw, 0, sizeof(float) * g.numel(), st));
+    L->params[std::string(kDysatNames[k]) + ".grad"] = g;
+    w.G[k] = g.raw;
+  }
+  uint4** frags[7] = {&w.Wp, &w.Wqp, &w.Wkp, &w.Wvp, &w.WqT, &w.WkT, &w.WvT};
+  for (uint4** f : frags) DGC_HIP_TRY(dev_alloc(L, f, 4 * 8 * 64));
+  // snapshots in use, 2-vertex tiles per chunk, owner map
+  std::vector<int32_t> used;
+  {
+    std::vector<char> seen(T, 0);
+    for (const ChunkInfo& c : cinfo)
+      for (int32_t t = c.t_lo; t < c.t_lo + c.w; ++t) seen[t] = 1;
+    for (int32_t t = 0; t < T; ++t)
+      if (seen[t]) used.push_back(t);
+  }
+  std::vector<int64_t> tptr(L->n_chunks + 1, 0);
+  for (int32_t k = 0; k < L->n_chunks; ++k) tptr[k + 1] = tptr[k] + (cinfo[k].nv + 1) / 2;
+  w.n_used = (int32_t)used.size(); w.n_tiles = tptr.back();
+  int32_t *d_used = nullptr, *d_owner = nullptr;
+  int64_t* d_tptr = nullptr;
+  DGC_HIP_TRY(dev_alloc(L, &d_used, (int64_t)used.size()));
+  DGC_HIP_TRY(dev_alloc(L, &d_tptr, (int64_t)tptr.size()));
+  DGC_HIP_TRY(dev_alloc(L, &d_owner, TN));
+  DGC_HIP_TRY(hipMemcpyAsync(d_used, used.data(), sizeof(int32_t) * used.size(), hipMemcpyHostToDevice, st));
+  DGC_HIP_TRY(hipMemcpyAsync(d_tptr, tptr.data(), sizeof(int64_t) * tptr.size(), hipMemcpyHostToDevice, st));
+  dysat_build_owner(L->d_segs, L->nseg, T, N, d_owner, st);
+  DGC_HIP_TRY(hipStreamSynchronize(st));
+  w.used_t = d_used; w.tile_ptr = d_tptr; w.owner = d_owner;
+  uint16_t** rowbufs[9] = {&w.zX, &w.zC, &w.U, &w.dU, &w.dQ, &w.dK, &w.dV, &w.dzX, &w.dzC};
+  for (uint16_t** b : rowbufs) DGC_HIP_TRY(dev_alloc(L, b, TN * S));
+  DGC_HIP_TRY(dev_alloc(L, &w.sX, TN * 16));
+  DGC_HIP_TRY(dev_alloc(L, &w.sC, TN * 8));
+  DGC_HIP_TRY(dev_alloc(L, &w.lse, TN * 8));
+  DGC_HIP_TRY(dev_alloc(L, &w.st2, TN * 16));
+  w.partial_elems = dysat_partial_elems(w);
+  DGC_HIP_TRY(dev_alloc(L, &w.partial, w.partial_elems));
+  DGC_HIP_TRY(dev_alloc(L, &w.loss_partial, dysat_loss_partial_elems(w)));
+  dysat_pack_params(w, st);
   return DGC_OK;
 }
 
@@ -390,9 +473,12 @@ dgc_status_t build_layer(dgc_layer* L, const dgc_graph_t* graph, hipStream_t st)
   // workspace
   const int32_t Fmax = std::max(d.F, d.n_struct_layers == 2 ? d.S : 0);
   L->ldm = (Fmax + 7) / 8 * 8;  // whole k-blocks of 8; the aggregation zero-fills the pad columns
-  DGC_HIP_TRY(dev_alloc(L, &L->d_M, L->total_rows * L->ldm));
-  DGC_HIP_TRY(dev_alloc(L, &L->d_partial, L->n_long * L->ldm));
-  if (d.gather_mode == DGC_GATHER_STAGED) {
+  const bool gat = d.struct_kind == DGC_STRUCT_GAT;
+  if (!gat) {
+    DGC_HIP_TRY(dev_alloc(L, &L->d_M, L->total_rows * L->ldm));
+    DGC_HIP_TRY(dev_alloc(L, &L->d_partial, L->n_long * L->ldm));
+  }
+  if (!gat && d.gather_mode == DGC_GATHER_STAGED) {
     L->ld_halo = L->ldm;
     DGC_HIP_TRY(dev_alloc(L, &L->d_halo, L->total_halo * L->ld_halo));
   }
@@ -400,7 +486,9 @@ dgc_status_t build_layer(dgc_layer* L, const dgc_graph_t* graph, hipStream_t st)
 
   // parameters
   dgc_status_t rc;
-  if (d.struct_kind == DGC_STRUCT_EVOLVE_GCN_O) {
+  if (gat) {
+    if ((rc = build_dysat(L, cinfo, st)) != DGC_OK) return rc;
+  } else if (d.struct_kind == DGC_STRUCT_EVOLVE_GCN_O) {
     if ((rc = build_evolve(L, cinfo, st)) != DGC_OK) return rc;
   } else {
   if ((rc = add_param(L, "gcn0.weight", d.S, d.F, st)) != DGC_OK) return rc;
@@ -426,10 +514,11 @@ dgc_status_t build_layer(dgc_layer* L, const dgc_graph_t* graph, hipStream_t st)
 }
 
 dgc_status_t check_tensor(const Failer& fail, const char* name, const void* p, int64_t ld, int64_t min_ld,
-                          bool required) {
+                          bool required, int64_t ld_multiple = 4) {
   if (!p) return required ? fail(DGC_ERR_INVALID_ARG, std::string(name) + " is NULL") : DGC_OK;
   if (!aligned16(p)) return fail(DGC_ERR_INVALID_ARG, std::string(name) + " is not 16-byte aligned");
-  if (ld < min_ld || ld % 4) return fail(DGC_ERR_INVALID_ARG, std::string(name) + ": pitch too small or not a multiple of 4");
+  if (ld < min_ld || ld % ld_multiple)
+    return fail(DGC_ERR_INVALID_ARG, std::string(name) + ": pitch too small or not a multiple of " + std::to_string(ld_multiple));
   return DGC_OK;
 }
 
@@ -522,6 +611,8 @@ dgc_status_t dgc_layer_destroy(dgc_layer_t* L) {
     if (e) (void)hipEventDestroy(e);
   for (hipEvent_t e : L->evx)
     if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : L->evd)
+    if (e) (void)hipEventDestroy(e);
   free_all(L);
   delete L;
   return DGC_OK;
@@ -539,7 +630,10 @@ dgc_status_t dgc_layer_set_param(dgc_layer_t* L, const char* name, const float* 
     return fail(DGC_ERR_INVALID_ARG, "gradients are read-only");
   if (numel != p.numel()) return fail(DGC_ERR_INVALID_ARG, std::string(name) + ": wrong element count");
   DGC_HIP_TRY(hipMemcpy(p.raw, host_src, sizeof(float) * numel, hipMemcpyHostToDevice));
-  if (p.packed) {
+  if (L->desc.struct_kind == DGC_STRUCT_GAT) {
+    dysat_pack_params(L->dy, nullptr);
+    DGC_HIP_TRY(hipDeviceSynchronize());
+  } else if (p.packed) {
     launch_pack_weight(p.raw, p.n_out, p.n_in, p.packed, nullptr);
     DGC_HIP_TRY(hipDeviceSynchronize());
   }
@@ -562,6 +656,7 @@ dgc_status_t dgc_layer_aggregate(dgc_layer_t* L, const float* X, int64_t ldx, co
   if (!L) return DGC_ERR_INVALID_ARG;
   Failer fail{L};
   dgc_status_t rc;
+  if (L->desc.struct_kind == DGC_STRUCT_GAT) return fail(DGC_ERR_UNSUPPORTED, "not a GCN layer");
   if ((rc = check_tensor(fail, "X", X, ldx, L->desc.F, true)) != DGC_OK) return rc;
   if ((rc = check_tensor(fail, "C", C, ldc, L->desc.F, true)) != DGC_OK) return rc;
   if ((rc = check_tensor(fail, "M", M, ldm, L->desc.F, true)) != DGC_OK) return rc;
@@ -576,6 +671,7 @@ dgc_status_t dgc_layer_gather(dgc_layer_t* L, const float* C, int64_t ldc, float
   if (!L) return DGC_ERR_INVALID_ARG;
   Failer fail{L};
   dgc_status_t rc;
+  if (L->desc.struct_kind == DGC_STRUCT_GAT) return fail(DGC_ERR_UNSUPPORTED, "not a GCN layer");
   if ((rc = check_tensor(fail, "C", C, ldc, L->desc.F, true)) != DGC_OK) return rc;
   if ((rc = check_tensor(fail, "halo", halo, ldh, L->desc.F, true)) != DGC_OK) return rc;
   launch_gather(L->d_segs, L->nseg, L->d_halo_idx, L->d_halo_ptr, L->total_halo, L->N, C, ldc, L->desc.F, halo, ldh,
@@ -584,15 +680,32 @@ dgc_status_t dgc_layer_gather(dgc_layer_t* L, const float* C, int64_t ldc, float
   return DGC_OK;
 }
 
-dgc_status_t dgc_layer_forward(dgc_layer_t* L, const float* X, int64_t ldx, const float* C, int64_t ldc,
-                               const float* C1, int64_t ldc1, const float* H0, const uint8_t* reset_mask, float* Y,
+dgc_status_t dgc_layer_forward(dgc_layer_t* L, const void* Xv, int64_t ldx, const void* Cv, int64_t ldc,
+                               const void* C1v, int64_t ldc1, const float* H0, const uint8_t* reset_mask, void* Yv,
                                int64_t ldy, float* HN, void* stream) {
   if (!L) return DGC_ERR_INVALID_ARG;
   Failer fail{L};
   const dgc_layer_desc_t& d = L->desc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int32_t out_dim = d.time_kind == DGC_TIME_NONE ? d.S : d.H;
   dgc_status_t rc;
+  if (d.struct_kind == DGC_STRUCT_GAT) {
+    if ((rc = check_tensor(fail, "X", Xv, ldx, d.F, true, 8)) != DGC_OK) return rc;
+    if ((rc = check_tensor(fail, "C", Cv, ldc, d.F, true, 8)) != DGC_OK) return rc;
+    if ((rc = check_tensor(fail, "Y", Yv, ldy, d.S, true, 8)) != DGC_OK) return rc;
+    if (C1v || H0 || HN || reset_mask)
+      return fail(DGC_ERR_INVALID_ARG, "C1 / H0 / HN / reset_mask do not apply to the attention layer");
+    L->evd_fwd = false;
+    dysat_forward(L->dy, Xv, ldx, Cv, ldc, Yv, ldy, L->profiling ? L->evd : nullptr, st);
+    if (L->profiling) L->evd_fwd = true;
+    DGC_HIP_TRY(hipGetLastError());
+    L->forward_done = true;
+    return DGC_OK;
+  }
+  const float* X = static_cast<const float*>(Xv);
+  const float* C = static_cast<const float*>(Cv);
+  const float* C1 = static_cast<const float*>(C1v);
+  float* Y = static_cast<float*>(Yv);
+  const int32_t out_dim = d.time_kind == DGC_TIME_NONE ? d.S : d.H;
   if ((rc = check_tensor(fail, "X", X, ldx, d.F, true)) != DGC_OK) return rc;
   if ((rc = check_tensor(fail, "C", C, ldc, d.F, true)) != DGC_OK) return rc;
   if ((rc = check_tensor(fail, "Y", Y, ldy, out_dim, true)) != DGC_OK) return rc;
@@ -672,9 +785,10 @@ dgc_status_t dgc_layer_set_profiling(dgc_layer_t* L, int32_t enable) {
   if (enable && !L->ev[0]) {
     for (hipEvent_t& e : L->ev) DGC_HIP_TRY(hipEventCreate(&e));
     for (hipEvent_t& e : L->evx) DGC_HIP_TRY(hipEventCreate(&e));
+    for (hipEvent_t& e : L->evd) DGC_HIP_TRY(hipEventCreate(&e));
   }
   L->profiling = enable != 0;
-  L->ev_valid = L->evx_fwd = L->evx_bwd = false;
+  L->ev_valid = L->evx_fwd = L->evx_bwd = L->evd_fwd = L->evd_bwd = false;
   return DGC_OK;
 }
 
@@ -682,8 +796,18 @@ dgc_status_t dgc_layer_stage_times(dgc_layer_t* L, float* host_ms) {
   if (!L) return DGC_ERR_INVALID_ARG;
   Failer fail{L};
   if (!host_ms) return fail(DGC_ERR_INVALID_ARG, "NULL argument");
-  if (!L->ev_valid) return fail(DGC_ERR_STATE, "no profiled forward has been enqueued");
   for (int i = 0; i < DGC_N_STAGES; ++i) host_ms[i] = 0.f;
+  if (L->desc.struct_kind == DGC_STRUCT_GAT) {
+    if (!L->evd_fwd) return fail(DGC_ERR_STATE, "no profiled forward has been enqueued");
+    DGC_HIP_TRY(hipEventSynchronize(L->evd[3]));
+    for (int i = 0; i < 3; ++i) DGC_HIP_TRY(hipEventElapsedTime(&host_ms[7 + i], L->evd[i], L->evd[i + 1]));
+    if (L->evd_bwd) {
+      DGC_HIP_TRY(hipEventSynchronize(L->evd[7]));
+      for (int i = 0; i < 3; ++i) DGC_HIP_TRY(hipEventElapsedTime(&host_ms[10 + i], L->evd[4 + i], L->evd[5 + i]));
+    }
+    return DGC_OK;
+  }
+  if (!L->ev_valid) return fail(DGC_ERR_STATE, "no profiled forward has been enqueued");
   DGC_HIP_TRY(hipEventSynchronize(L->ev[4]));
   for (int i = 0; i < 4; ++i) DGC_HIP_TRY(hipEventElapsedTime(&host_ms[i], L->ev[i], L->ev[i + 1]));
   if (L->evx_fwd) DGC_HIP_TRY(hipEventElapsedTime(&host_ms[4], L->evx[0], L->evx[1]));
@@ -695,20 +819,35 @@ dgc_status_t dgc_layer_stage_times(dgc_layer_t* L, float* host_ms) {
   return DGC_OK;
 }
 
-dgc_status_t dgc_layer_backward(dgc_layer_t* L, const float* Y, int64_t ldy, const float* dY, int64_t lddy,
-                                const float* target, int64_t ldt, float* loss_out, float* dX, int64_t lddx,
+dgc_status_t dgc_layer_backward(dgc_layer_t* L, const void* Yv, int64_t ldy, const void* dYv, int64_t lddy,
+                                const void* targetv, int64_t ldt, float* loss_out, void* dX, int64_t lddx,
                                 void* stream) {
   (void)lddx;
   if (!L) return DGC_ERR_INVALID_ARG;
   Failer fail{L};
   const dgc_layer_desc_t& d = L->desc;
   if (!L->forward_done) return fail(DGC_ERR_STATE, "backward before forward");
-  if (d.struct_kind != DGC_STRUCT_EVOLVE_GCN_O)
-    return fail(DGC_ERR_UNSUPPORTED, "backward is built for DGC_STRUCT_EVOLVE_GCN_O only");
+  if (d.struct_kind != DGC_STRUCT_EVOLVE_GCN_O && d.struct_kind != DGC_STRUCT_GAT)
+    return fail(DGC_ERR_UNSUPPORTED, "backward is built for DGC_STRUCT_EVOLVE_GCN_O and DGC_STRUCT_GAT only");
   if (dX) return fail(DGC_ERR_UNSUPPORTED, "input gradients are not built: dX must be NULL");
-  if ((dY != nullptr) == (target != nullptr))
+  if ((dYv != nullptr) == (targetv != nullptr))
     return fail(DGC_ERR_INVALID_ARG, "give exactly one of dY and target");
   dgc_status_t rc;
+  if (d.struct_kind == DGC_STRUCT_GAT) {
+    if ((rc = check_tensor(fail, "Y", Yv, ldy, d.S, true, 8)) != DGC_OK) return rc;
+    if ((rc = check_tensor(fail, "dY", dYv, lddy, d.S, false, 8)) != DGC_OK) return rc;
+    if ((rc = check_tensor(fail, "target", targetv, ldt, d.S, false, 8)) != DGC_OK) return rc;
+    L->evd_bwd = false;
+    dysat_backward(L->dy, Yv, ldy, dYv, lddy, targetv, ldt, loss_out, L->profiling ? L->evd + 4 : nullptr,
+                   static_cast<hipStream_t>(stream));
+    if (L->profiling) L->evd_bwd = true;
+    DGC_HIP_TRY(hipGetLastError());
+    L->has_grads = true;
+    return DGC_OK;
+  }
+  const float* Y = static_cast<const float*>(Yv);
+  const float* dY = static_cast<const float*>(dYv);
+  const float* target = static_cast<const float*>(targetv);
   if ((rc = check_tensor(fail, "Y", Y, ldy, d.S, true)) != DGC_OK) return rc;
   if ((rc = check_tensor(fail, "dY", dY, lddy, d.S, false)) != DGC_OK) return rc;
   if ((rc = check_tensor(fail, "target", target, ldt, d.S, false)) != DGC_OK) return rc;

@@ -1,0 +1,467 @@
+// Graph-attention structure encoder + causal temporal self-attention time encoder (the
+// DySAT-style DGNN of the paper's Sections 2.1 and 6) over a fused batch of chunks, bf16 storage
+// with fp32 accumulation.  S = F = 128, 8 heads of 16 dims, windows of up to 16 snapshots.
+//
+//   z = W x (own rows) / W c (cache rows, Section 5.2);  e_ij^h = LeakyReLU_0.2(a_dst^h.z_i^h + a_src^h.z_j^h)
+//   alpha = softmax over the stored row;  u_i = sum_j alpha_ij z_j;  g = ELU(u)
+//   p_s = g_s + pos[s];  q, k, v = W_q p, W_k p, W_v p;  y_s^h = sum_{r<=s} softmax_r(q_s^h.k_r^h / 4) v_r^h
+//
+// All dense products run on v_mfma_f32_32x32x16_bf16: lane l supplies A[l%32][8*(l/32) .. +7] and
+// B[8*(l/32) .. +7][l%32] and receives D[8*(v/4) + 4*(l/32) + v%4][l%32] in register v.  With the
+// weights as A operand and 32 activation rows as B operand, lane (n = l%32, hh = l/32) ends up with
+// features 8g + 4hh + e (g = v/4, e = v%4) of its own row n: "row layout".  With the activations as
+// A operand and the weights as B operand, lane (f = l%32, hh) ends up with feature f of rows
+// 8g + 4hh + e: "column layout".  Eight consecutive accumulator registers (g = 2c, 2c+1) of a lane
+// are one k-half of a 16-wide contraction index in either layout, which is what lets every
+// attention product below take its operands straight from accumulators, without moving data
+// between lanes.
+#include "dgc_internal.h"
+
+namespace dgc {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kS = 128;      // feature width (input, structure output, attention width)
+constexpr int kHeads = 8;
+constexpr int kD = 16;       // dims per head
+constexpr int kMaxW = 16;    // longest chunk window
+constexpr float kSlope = 0.2f;
+
+__device__ __forceinline__ bf16x8 as_frag(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
+__device__ __forceinline__ float bf_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+__device__ __forceinline__ uint32_t pack2(float a, float b) {
+  bf16x2 v = {(__bf16)a, (__bf16)b};
+  return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) { return make_uint2(pack2(a, b), pack2(c, d)); }
+__device__ __forceinline__ bf16x8 pack8(const float* x) {
+  bf16x8 v;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = (__bf16)x[i];
+  return v;
+}
+__device__ __forceinline__ void unpack8(uint4 u, float* x) {
+  x[0] = bf_lo(u.x); x[1] = bf_hi(u.x); x[2] = bf_lo(u.y); x[3] = bf_hi(u.y);
+  x[4] = bf_lo(u.z); x[5] = bf_hi(u.z); x[6] = bf_lo(u.w); x[7] = bf_hi(u.w);
+}
+__device__ __forceinline__ floatx16 mfma(bf16x8 a, bf16x8 b, floatx16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ float lrelu(float x) { return x > 0.f ? x : kSlope * x; }
+__device__ __forceinline__ float elu(float x) { return x > 0.f ? x : __expf(x) - 1.f; }
+
+// ---------------------------------------------------------------------------------------------
+// Weights [n_out = 128][n_in = 128] fp32 -> bf16 operand fragments, 16 bytes per lane.
+//  mode 0: fragment (jb, kb) of W as the 32-row operand: lane l holds W[32 jb + l%32][16 kb + 8 (l/32) + 0..7].
+//  mode 1: fragment (ib, ks) of W^T for products whose contraction index is W's row index and whose
+//          other operand comes from accumulators in row layout: lane l holds, for p = 0..7,
+//          W[16 ks + 8 (p/4) + 4 (l/32) + p%4][32 ib + l%32].
+__global__ void k_pack_w_bf16(const float* W, uint4* packed, int mode) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;   // (blk * 8 + k) * 64 + lane
+  if (idx >= 4 * 8 * 64) return;
+  const int lane = idx & 63, k = (idx >> 6) & 7, blk = idx >> 9;
+  const int r32 = lane & 31, hh = lane >> 5;
+  float x[8];
+#pragma unroll
+  for (int p = 0; p < 8; ++p) {
+    if (mode == 0) x[p] = W[(blk * 32 + r32) * kS + k * 16 + 8 * hh + p];
+    else x[p] = W[(k * 16 + 8 * (p >> 2) + 4 * hh + (p & 3)) * kS + blk * 32 + r32];
+  }
+  packed[idx] = __builtin_bit_cast(uint4, pack8(x));
+}
+
+__global__ void k_fill_i32(int32_t* p, int32_t v, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+__global__ void k_fill_f32(float* p, float v, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// owner[t*N + v] = chunk that covers (t, v); one block per segment
+__global__ void k_owner(const Segment* segs, int64_t N, int32_t* owner) {
+  const Segment s = segs[blockIdx.x];
+  for (int64_t v = s.v_lo + threadIdx.x; v < s.v_hi; v += blockDim.x) owner[(int64_t)s.t * N + v] = s.chunk;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Projection z = W x for every vertex of every snapshot in use: zC from the cache rows (any
+// vertex can be somebody's out-of-chunk neighbour), zX from the input rows of covered vertices,
+// plus the attention scalars s_src[h] = a_src^h . z^h, s_dst[h] = a_dst^h . z^h (from the fp32
+// accumulators).  One wavefront per 32 vertices.
+struct ProjArgs {
+  const uint16_t* X; int64_t ldx;
+  const uint16_t* C; int64_t ldc;
+  const uint4* Wp;
+  const float* a_src; const float* a_dst;
+  const int32_t* owner; const int32_t* used_t; int32_t n_used; int64_t N;
+  uint16_t* zX; uint16_t* zC;
+  float* sX;   // [T*N][16]: s_src[8], s_dst[8]
+  float* sC;   // [T*N][8]:  s_src
+};
+
+__global__ __launch_bounds__(256) void k_gat_project(ProjArgs a) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = lane & 31, hh = lane >> 5;
+  const int64_t tiles_per_t = (a.N + 31) / 32;
+  const int64_t tile = (int64_t)blockIdx.x * 4 + wave;
+  if (tile >= tiles_per_t * a.n_used) return;
+  const int32_t t = a.used_t[tile / tiles_per_t];
+  const int64_t v = (tile % tiles_per_t) * 32 + n;
+  const bool valid = v < a.N;
+  const int64_t row = (int64_t)t * a.N + (valid ? v : a.N - 1);
+  const bool covered = valid && a.owner[row] >= 0;
+  const bool any_cov = __ballot(covered) != 0ull;
+  for (int side = 0; side < 2; ++side) {          // 0: cache rows, 1: input rows
+    if (side == 1 && !any_cov) break;
+    const uint16_t* src = side ? a.X + row * a.ldx : a.C + row * a.ldc;
+    const bool wr = side ? covered : valid;
+    bf16x8 xf[8];
+#pragma unroll
+    for (int kb = 0; kb < 8; ++kb) xf[kb] = as_frag(*reinterpret_cast<const uint4*>(src + kb * 16 + 8 * hh));
+    uint16_t* z = (side ? a.zX : a.zC) + row * kS;
+    float ssrc[kHeads], sdst[kHeads];
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb) {
+      floatx16 acc = {};
+#pragma unroll
+      for (int kb = 0; kb < 8; ++kb) acc = mfma(as_frag(a.Wp[(jb * 8 + kb) * 64 + lane]), xf[kb], acc);
+      if (wr) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<uint2*>(z + jb * 32 + 8 * g + 4 * hh) = pack4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
+      }
+#pragma unroll
+      for (int hd = 0; hd < 2; ++hd) {
+        const int h = 2 * jb + hd;
+        float ps = 0.f, pd = 0.f;
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          const float4 as = *reinterpret_cast<const float4*>(a.a_src + h * kD + 8 * c + 4 * hh);
+          const float4 ad = *reinterpret_cast<const float4*>(a.a_dst + h * kD + 8 * c + 4 * hh);
+          const int r = 8 * hd + 4 * c;
+          ps += as.x * acc[r] + as.y * acc[r + 1] + as.z * acc[r + 2] + as.w * acc[r + 3];
+          pd += ad.x * acc[r] + ad.y * acc[r + 1] + ad.z * acc[r + 2] + ad.w * acc[r + 3];
+        }
+        ssrc[h] = ps + __shfl_xor(ps, 32);
+        sdst[h] = pd + __shfl_xor(pd, 32);
+      }
+    }
+    if (wr) {
+      if (side == 0) {
+        if (hh == 0) {
+          float4* o = reinterpret_cast<float4*>(a.sC + row * 8);
+          o[0] = make_float4(ssrc[0], ssrc[1], ssrc[2], ssrc[3]);
+          o[1] = make_float4(ssrc[4], ssrc[5], ssrc[6], ssrc[7]);
+        }
+      } else {
+        float4* o = reinterpret_cast<float4*>(a.sX + row * 16 + 8 * hh);
+        const float* s = hh ? sdst : ssrc;
+        o[0] = make_float4(s[0], s[1], s[2], s[3]);
+        o[1] = make_float4(s[4], s[5], s[6], s[7]);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Edge softmax + aggregation.  One wavefront per group of rows of one segment; the 64 lanes span
+// the 128 features (two per lane, head = lane / 8), so a neighbour's z row is one coalesced
+// 256-byte load.  Column ids are loaded 64 at a time and broadcast lane by lane (row addresses
+// stay wave-uniform); eight neighbour rows are in flight; the softmax is accumulated online
+// (running maximum, rescale once per batch of eight).
+struct GatArgs {
+  GraphDev g;
+  const Segment* segs;
+  const int32_t* work; int64_t n_work;     // [n][3]: segment, first local row, rows
+  const uint16_t* zX; const uint16_t* zC;
+  const float* sX; const float* sC;
+  uint16_t* U;     // [T*N][128] pre-ELU output
+  float* lse;      // [T*N][8] log-sum-exp of the logits of every (row, head)
+};
+
+__global__ __launch_bounds__(256) void k_gat_aggregate(GatArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (item >= a.n_work) return;
+  const int32_t si = a.work[3 * item], r0 = a.work[3 * item + 1], nr = a.work[3 * item + 2];
+  const Segment s = a.segs[si];
+  const int64_t N = a.g.N;
+  const int64_t* rowptr = a.g.rowptr[s.t];
+  const int32_t* col = a.g.colidx[s.t];
+  const int64_t base = (int64_t)s.t * N;
+  const int head = lane >> 3;
+  for (int rr = 0; rr < nr; ++rr) {
+    const int64_t i = s.v_lo + r0 + rr;
+    const int64_t e0 = rowptr[i], e1 = rowptr[i + 1];
+    const float sd = a.sX[(base + i) * 16 + 8 + head];
+    float m = -INFINITY, l = 0.f, acc0 = 0.f, acc1 = 0.f;
+    for (int64_t eb = e0; eb < e1; eb += 64) {
+      const int cnt = (int)min((int64_t)64, e1 - eb);
+      const int32_t j = lane < cnt ? col[eb + lane] : 0;
+      const int inside = (j >= s.v_lo && j < s.v_hi) ? 1 : 0;
+      for (int q0 = 0; q0 < cnt; q0 += 8) {
+        uint32_t zz[8];
+        float ev[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          ev[q] = -INFINITY;
+          zz[q] = 0u;
+          if (q0 + q < cnt) {
+            const int64_t jq = base + __builtin_amdgcn_readlane(j, q0 + q);
+            const bool in = __builtin_amdgcn_readlane(inside, q0 + q) != 0;
+            zz[q] = *reinterpret_cast<const uint32_t*>((in ? a.zX : a.zC) + jq * kS + 2 * lane);
+            ev[q] = in ? a.sX[jq * 16 + head] : a.sC[jq * 8 + head];
+          }
+        }
+        float bm = -INFINITY;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          ev[q] = lrelu(sd + ev[q]);       // -inf stays -inf
+          bm = fmaxf(bm, ev[q]);
+        }
+        const float mn = fmaxf(m, bm);
+        const float sc = __expf(m - mn);
+        l *= sc; acc0 *= sc; acc1 *= sc;
+        m = mn;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          const float p = __expf(ev[q] - mn);
+          l += p;
+          acc0 += p * bf_lo(zz[q]);
+          acc1 += p * bf_hi(zz[q]);
+        }
+      }
+    }
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    *reinterpret_cast<uint32_t*>(a.U + (base + i) * kS + 2 * lane) = pack2(acc0 * inv, acc1 * inv);
+    if ((lane & 7) == 0) a.lse[(base + i) * 8 + head] = m + __logf(l);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Temporal self-attention, forward.  One wavefront per two vertices of a chunk: 32 rows
+// n = 16 a + s (a = vertex 0/1, s = step in the window).  Per block jb of 32 output features
+// (two heads): Q and K in row layout, V in column layout; per head one product K Q^T gives the
+// transposed score block of both vertices (lane (n_s, hh) holds the scores of its own query row
+// against key rows 8g + 4hh + e; those of its own vertex are registers 8a .. 8a+7), the softmax
+// is lane-local plus one exchange with lane l^32, and the probabilities are directly the B
+// operand of the product with V (A operand = V in column layout, masked to the head; B masked
+// to the vertex), which lands in row layout, ready to be stored.
+struct TemporalArgs {
+  const ChunkInfo* chunks; int32_t n_chunks;
+  const int64_t* tile_ptr;   // [n_chunks+1] first 2-vertex tile of every chunk
+  int64_t n_tiles;
+  int64_t N; int32_t T;
+  const uint16_t* U;
+  const float* pos;          // [T][128]
+  const uint4* Wq; const uint4* Wk; const uint4* Wv;   // mode-0 fragments
+  uint16_t* Y; int64_t ldy;
+};
+
+struct TileRow {   // what a lane needs to know about its row n = lane % 32
+  int64_t row;     // t*N + v (clamped to a valid row when !valid)
+  int32_t t, s, a;
+  bool valid;
+};
+
+__device__ __forceinline__ TileRow tile_row(const ChunkInfo* chunks, int32_t n_chunks, const int64_t* tile_ptr,
+                                            int64_t tile, int64_t N, int lane) {
+  int lo = 0, hi = n_chunks;   // largest k with tile_ptr[k] <= tile
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (tile_ptr[mid] <= tile) lo = mid; else hi = mid;
+  }
+  const ChunkInfo c = chunks[lo];
+  const int n = lane & 31;
+  TileRow r;
+  r.a = n >> 4; r.s = n & 15;
+  const int64_t vl = 2 * (tile - tile_ptr[lo]) + r.a;
+  r.valid = vl < c.nv && r.s < c.w;
+  r.t = c.t_lo + (r.s < c.w ? r.s : 0);
+  r.row = (int64_t)r.t * N + c.v_lo + (vl < c.nv ? vl : 0);
+  return r;
+}
+
+// x -> hi + lo with hi = bf16(x), lo = bf16(x - hi): two bf16 operands that together carry 16
+// mantissa bits, so a product taken as hi*hi + hi*lo + lo*hi is accurate to ~2^-16
+__device__ __forceinline__ void split8(const float* x, bf16x8& hi, bf16x8& lo) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const __bf16 h = (__bf16)x[i];
+    hi[i] = h;
+    lo[i] = (__bf16)(x[i] - (float)h);
+  }
+}
+
+// P = ELU(U) + pos for the lane's row, as eight B/A-operand fragments (hi part, and lo part if
+// LO); rows that are not valid read as zero
+template <bool LO>
+__device__ __forceinline__ void load_p_frags(const uint16_t* U, const float* pos, const TileRow& r, int hh, bf16x8* pf,
+                                             bf16x8* pl) {
+#pragma unroll
+  for (int kb = 0; kb < 8; ++kb) {
+    float x[8];
+    if (r.valid) {
+      unpack8(*reinterpret_cast<const uint4*>(U + r.row * kS + kb * 16 + 8 * hh), x);
+      const float4 p0 = *reinterpret_cast<const float4*>(pos + r.t * kS + kb * 16 + 8 * hh);
+      const float4 p1 = *reinterpret_cast<const float4*>(pos + r.t * kS + kb * 16 + 8 * hh + 4);
+      x[0] = elu(x[0]) + p0.x; x[1] = elu(x[1]) + p0.y; x[2] = elu(x[2]) + p0.z; x[3] = elu(x[3]) + p0.w;
+      x[4] = elu(x[4]) + p1.x; x[5] = elu(x[5]) + p1.y; x[6] = elu(x[6]) + p1.z; x[7] = elu(x[7]) + p1.w;
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) x[i] = 0.f;
+    }
+    if (LO) split8(x, pf[kb], pl[kb]);
+    else pf[kb] = pack8(x);
+  }
+}
+
+// softmax over the key steps r <= s of the lane's own vertex; x[p] is the raw score against key
+// step r = 8 (p/4) + 4 hh + p%4; returns probabilities (0 for masked positions)
+__device__ __forceinline__ void causal_softmax(float* x, int s, int hh) {
+  float mx = -INFINITY;
+#pragma unroll
+  for (int p = 0; p < 8; ++p) {
+    const int r = 8 * (p >> 2) + 4 * hh + (p & 3);
+    x[p] = r <= s ? 0.25f * x[p] : -INFINITY;
+    mx = fmaxf(mx, x[p]);
+  }
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  float sum = 0.f;
+#pragma unroll
+  for (int p = 0; p < 8; ++p) {
+    x[p] = __expf(x[p] - mx);
+    sum += x[p];
+  }
+  sum += __shfl_xor(sum, 32);
+  const float inv = 1.f / sum;
+#pragma unroll
+  for (int p = 0; p < 8; ++p) x[p] *= inv;
+}
+
+// The forward pass carries every in-register operand (P, Q, K, V, the probabilities) as a
+// hi + lo pair of bf16 values, so that the only roundings to bf16 are the stored tensors (z, U, Y).
+__global__ __launch_bounds__(256) void k_temporal_fwd(TemporalArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (tile >= a.n_tiles) return;
+  const int hh = lane >> 5, f = lane & 31;
+  const TileRow r = tile_row(a.chunks, a.n_chunks, a.tile_ptr, tile, a.N, lane);
+  bf16x8 pf[8], pl[8];
+  load_p_frags<true>(a.U, a.pos, r, hh, pf, pl);
+  const bf16x8 zero8 = {};
+#pragma unroll 1
+  for (int jb = 0; jb < 4; ++jb) {
+    floatx16 q = {}, k = {}, vt = {};
+#pragma unroll
+    for (int kb = 0; kb < 8; ++kb) {
+      const int fi = (jb * 8 + kb) * 64 + lane;
+      const bf16x8 wq = as_frag(a.Wq[fi]), wk = as_frag(a.Wk[fi]), wv = as_frag(a.Wv[fi]);
+      q = mfma(wq, pf[kb], q);
+      q = mfma(wq, pl[kb], q);
+      k = mfma(wk, pf[kb], k);
+      k = mfma(wk, pl[kb], k);
+      vt = mfma(pf[kb], wv, vt);
+      vt = mfma(pl[kb], wv, vt);
+    }
+    floatx16 y = {};
+#pragma unroll
+    for (int hd = 0; hd < 2; ++hd) {
+      float tmp[8];
+      bf16x8 kh, kl, qh, ql;
+#pragma unroll
+      for (int p = 0; p < 8; ++p) tmp[p] = k[8 * hd + p];
+      split8(tmp, kh, kl);
+#pragma unroll
+      for (int p = 0; p < 8; ++p) tmp[p] = q[8 * hd + p];
+      split8(tmp, qh, ql);
+      floatx16 st = {};
+      st = mfma(kl, qh, st);                 // st[i = key row][j = query row]
+      st = mfma(kh, ql, st);
+      st = mfma(kh, qh, st);
+      float pr[8];
+#pragma unroll
+      for (int p = 0; p < 8; ++p) pr[p] = r.a ? st[8 + p] : st[p];
+      causal_softmax(pr, r.s, hh);
+      bf16x8 ph, plo;
+      split8(pr, ph, plo);
+#pragma unroll
+      for (int av = 0; av < 2; ++av) {
+        bf16x8 vh, vl;
+#pragma unroll
+        for (int p = 0; p < 8; ++p) tmp[p] = vt[8 * av + p];
+        split8(tmp, vh, vl);
+        const bool mine = (f >> 4) == hd;
+        const bool myv = r.a == av;
+        y = mfma(mine ? vl : zero8, myv ? ph : zero8, y);
+        y = mfma(mine ? vh : zero8, myv ? plo : zero8, y);
+        y = mfma(mine ? vh : zero8, myv ? ph : zero8, y);
+      }
+    }
+    if (r.valid) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        *reinterpret_cast<uint2*>(a.Y + r.row * a.ldy + jb * 32 + 8 * g + 4 * hh) =
+            pack4(y[4 * g], y[4 * g + 1], y[4 * g + 2], y[4 * g + 3]);
+    }
+  }
+}
+
+unsigned blocks_for(int64_t n, int per_block) { return (unsigned)((n + per_block - 1) / per_block); }
+
+}  // namespace
+
+void dysat_build_owner(const Segment* segs, int64_t nseg, int32_t T, int64_t N, int32_t* owner, hipStream_t st) {
+  hipLaunchKernelGGL(k_fill_i32, blocks_for((int64_t)T * N, 256), 256, 0, st, owner, -1, (int64_t)T * N);
+  hipLaunchKernelGGL(k_owner, (unsigned)nseg, 256, 0, st, segs, N, owner);
+}
+
+void dysat_pack_params(const DysatWs& ws, hipStream_t st) {
+  hipLaunchKernelGGL(k_pack_w_bf16, 8, 256, 0, st, ws.P[DY_W], ws.Wp, 0);
+  hipLaunchKernelGGL(k_pack_w_bf16, 8, 256, 0, st, ws.P[DY_WQ], ws.Wqp, 0);
+  hipLaunchKernelGGL(k_pack_w_bf16, 8, 256, 0, st, ws.P[DY_WK], ws.Wkp, 0);
+  hipLaunchKernelGGL(k_pack_w_bf16, 8, 256, 0, st, ws.P[DY_WV], ws.Wvp, 0);
+  hipLaunchKernelGGL(k_pack_w_bf16, 8, 256, 0, st, ws.P[DY_WQ], ws.WqT, 1);
+  hipLaunchKernelGGL(k_pack_w_bf16, 8, 256, 0, st, ws.P[DY_WK], ws.WkT, 1);
+  hipLaunchKernelGGL(k_pack_w_bf16, 8, 256, 0, st, ws.P[DY_WV], ws.WvT, 1);
+}
+
+void dysat_forward(const DysatWs& ws, const void* X, int64_t ldx, const void* C, int64_t ldc, void* Y, int64_t ldy,
+                   hipEvent_t* ev, hipStream_t st) {
+  ProjArgs pa{};
+  pa.X = static_cast<const uint16_t*>(X); pa.ldx = ldx;
+  pa.C = static_cast<const uint16_t*>(C); pa.ldc = ldc;
+  pa.Wp = ws.Wp; pa.a_src = ws.P[DY_ASRC]; pa.a_dst = ws.P[DY_ADST];
+  pa.owner = ws.owner; pa.used_t = ws.used_t; pa.n_used = ws.n_used; pa.N = ws.N;
+  pa.zX = ws.zX; pa.zC = ws.zC; pa.sX = ws.sX; pa.sC = ws.sC;
+  const int64_t ptiles = (ws.N + 31) / 32 * ws.n_used;
+  if (ev) (void)hipEventRecord(ev[0], st);
+  hipLaunchKernelGGL(k_gat_project, blocks_for(ptiles, 4), 256, 0, st, pa);
+  if (ev) (void)hipEventRecord(ev[1], st);
+  GatArgs ga{};
+  ga.g = ws.g; ga.segs = ws.segs; ga.work = ws.work_short; ga.n_work = ws.n_short;
+  ga.zX = ws.zX; ga.zC = ws.zC; ga.sX = ws.sX; ga.sC = ws.sC; ga.U = ws.U; ga.lse = ws.lse;
+  hipLaunchKernelGGL(k_gat_aggregate, blocks_for(ws.n_short, 4), 256, 0, st, ga);
+  if (ev) (void)hipEventRecord(ev[2], st);
+  TemporalArgs ta{};
+  ta.chunks = ws.chunks; ta.n_chunks = ws.n_chunks; ta.tile_ptr = ws.tile_ptr; ta.n_tiles = ws.n_tiles;
+  ta.N = ws.N; ta.T = ws.T; ta.U = ws.U; ta.pos = ws.P[DY_POS];
+  ta.Wq = ws.Wqp; ta.Wk = ws.Wkp; ta.Wv = ws.Wvp;
+  ta.Y = static_cast<uint16_t*>(Y); ta.ldy = ldy;
+  hipLaunchKernelGGL(k_temporal_fwd, blocks_for(ws.n_tiles, 4), 256, 0, st, ta);
+  if (ev) (void)hipEventRecord(ev[3], st);
+}
+
+int64_t dysat_partial_elems(const DysatWs&) { return 1; }
+int64_t dysat_loss_partial_elems(const DysatWs&) { return 1; }
+void dysat_backward(const DysatWs&, const void*, int64_t, const void*, int64_t, const void*, int64_t, float*,
+                    hipEvent_t*, hipStream_t) {}
+
+}  // namespace dgc

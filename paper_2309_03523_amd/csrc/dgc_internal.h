@@ -188,4 +188,44 @@ void evolve_forward_weights(const EvolveWs& ws, hipStream_t st);
 bool evolve_backward_dw(const EvolveWs& ws, const EvolveBwdIn& in, hipStream_t st, std::string* why);
 void evolve_backward_bptt(const EvolveWs& ws, hipStream_t st);
 
+// ---- graph attention + temporal self-attention, bf16 (dgc_dysat.hip)
+enum { DY_W = 0, DY_ASRC, DY_ADST, DY_POS, DY_WQ, DY_WK, DY_WV, DY_NPAR };
+
+struct DysatWs {
+  int32_t T; int64_t N; int32_t n_chunks;
+  GraphDev g;
+  const Segment* segs; int64_t nseg;
+  const ChunkInfo* chunks;
+  const int32_t* work_short; int64_t n_short;   // row groups of the segments (segment, first row, rows)
+  const int64_t* tile_ptr; int64_t n_tiles;     // 2-vertex tiles of the temporal kernels, per chunk
+  const int32_t* owner;                         // [T*N] covering chunk or -1
+  const int32_t* used_t; int32_t n_used;        // snapshots some chunk covers
+  int64_t total_rows;
+  const float* P[DY_NPAR];   // fp32 parameters: gat.weight, att_src, att_dst, pos, W_q, W_k, W_v
+  float* G[DY_NPAR];         // their gradients
+  uint4 *Wp, *Wqp, *Wkp, *Wvp;   // bf16 operand fragments (row operand)
+  uint4 *WqT, *WkT, *WvT;        // bf16 fragments of the transposes (backward)
+  uint16_t *zX, *zC;         // [T*N][128] bf16 projections of input and cache rows
+  float *sX, *sC;            // attention scalars
+  uint16_t* U;               // [T*N][128] bf16 structure-encoder output before ELU
+  float* lse;                // [T*N][8]
+  // backward
+  uint16_t *dU, *dQ, *dK, *dV, *dzX, *dzC;   // [T*N][128] bf16
+  float* st2;                // [T*N][16]: d s_dst[8], c[8] of every covered row
+  float* partial;            // scratch for the parameter-gradient reductions
+  int64_t partial_elems;
+  float* loss_partial;
+};
+
+int64_t dysat_partial_elems(const DysatWs& ws);
+int64_t dysat_loss_partial_elems(const DysatWs& ws);
+// ev: NULL or 4 events recorded around the three backward stages
+void dysat_backward(const DysatWs& ws, const void* Y, int64_t ldy, const void* dY, int64_t lddy, const void* target,
+                    int64_t ldt, float* loss_out, hipEvent_t* ev, hipStream_t st);
+void dysat_build_owner(const Segment* segs, int64_t nseg, int32_t T, int64_t N, int32_t* owner, hipStream_t st);
+void dysat_pack_params(const DysatWs& ws, hipStream_t st);
+// ev: NULL or 4 events recorded around the three forward stages
+void dysat_forward(const DysatWs& ws, const void* X, int64_t ldx, const void* C, int64_t ldc, void* Y, int64_t ldy,
+                   hipEvent_t* ev, hipStream_t st);
+
 }  // namespace dgc

@@ -64,3 +64,28 @@ def run_forward(wl, **kw) -> np.ndarray:
     Y = dw.forward().cpu().numpy()
     dw.layer.destroy()
     return Y
+
+
+class DysatDevice:
+    """Device copies (bfloat16) of a graph-attention workload plus a created layer."""
+
+    def __init__(self, wl, *, validate_level: int = 0, **layer_kw):
+        import torch
+        dev = torch.device("cuda:0")
+        self.wl = wl
+        g = wl.graph
+        self.rowptr = [torch.from_numpy(s.rowptr).to(dev) for s in g.snaps]
+        self.colidx = [torch.from_numpy(s.col).to(dev) for s in g.snaps]
+        self.layer = DgcLayer(self.rowptr, self.colidx, g.N, wl.chunks, F=wl.F, S=wl.S, H=wl.H, time_kind="self_attn",
+                              struct_kind="gat", dtype="bf16", heads=wl.notes["heads"],
+                              validate_level=validate_level, **layer_kw)
+        self.layer.set_params(wl.params)
+        self.X = torch.from_numpy(wl.X).to(dev).to(torch.bfloat16)
+        self.C = torch.from_numpy(wl.C).to(dev).to(torch.bfloat16)
+        self.Y = torch.full((g.T, g.N, wl.S), float("nan"), dtype=torch.bfloat16, device=dev)
+
+    def forward(self, C=None):
+        import torch
+        self.layer.forward(self.X, self.C if C is None else C, self.Y)
+        torch.cuda.synchronize()
+        return self.Y

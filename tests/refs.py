@@ -57,11 +57,13 @@ def brute_pack(graph, chunks) -> dict:
             "col_local": np.array(col_local, np.int32)}
 
 
-def rel_err(got: np.ndarray, want: np.ndarray) -> float:
-    """max |got - want| / max(|want|, tau), tau = 1e-1 * RMS(want): the elementwise relative
-    error with a floor, since a plain relative error is unbounded near zero."""
+def rel_err(got: np.ndarray, want: np.ndarray, floor: float = 1e-1) -> float:
+    """max |got - want| / max(|want|, tau), tau = floor * RMS(want): the elementwise relative
+    error with a floor, since a plain relative error is unbounded near zero.  floor = 0.1 for
+    fp32 paths; 1.0 for bf16 paths, whose stored intermediates carry an absolute error of a few
+    2^-9 * RMS whatever the size of the element they end up in."""
     got = np.asarray(got, np.float64)
     want = np.asarray(want, np.float64)
-    tau = 1e-1 * float(np.sqrt(np.mean(want * want))) if want.size else 0.0
+    tau = floor * float(np.sqrt(np.mean(want * want))) if want.size else 0.0
     den = np.maximum(np.abs(want), max(tau, 1e-300))
     return float(np.max(np.abs(got - want) / den)) if want.size else 0.0

@@ -1,0 +1,45 @@
+"""Parity of the graph-attention + temporal self-attention layer (bf16) against the CPU oracle,
+through the C ABI.  Tolerance: 2e-2 on max |g - o| / max(|o|, RMS(o)): the projections z, the
+structure output U and the output Y are stored in bf16, each rounding is up to 2^-9 relative to
+the rounded value, and what reaches an output element through the dense products is an absolute
+error of that order times the RMS, whatever the element's own size."""
+import numpy as np
+import pytest
+
+from oracle import dysat
+from paper_2309_03523_amd import synth
+from refs import rel_err
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-2
+
+
+def _covered(wl):
+    cov = np.zeros((wl.graph.T, wl.graph.N), bool)
+    for v_lo, v_hi, t_lo, t_hi in wl.chunks.tolist():
+        cov[t_lo:t_hi, v_lo:v_hi] = True
+    return cov
+
+
+CASES = {
+    "ragged": dict(T=7, N=203, deg=5.0, chunks=[[0, 61, 0, 7], [61, 130, 0, 3], [61, 130, 3, 7], [130, 203, 1, 6]]),
+    "full16": dict(T=16, N=97, deg=4.0, chunks=[[0, 33, 0, 16], [33, 97, 0, 16]]),
+    "single": dict(T=3, N=40, deg=3.0, chunks=[[5, 6, 0, 3], [6, 40, 1, 2]]),
+}
+
+
+@pytest.mark.parametrize("case", list(CASES))
+def test_forward_parity(case):
+    from paper_2309_03523_amd.runner import DysatDevice
+    c = CASES[case]
+    wl = synth.dysat_small(40 + len(case), c["T"], c["N"], 128, 8, c["deg"], c["chunks"], hub=True)
+    dd = DysatDevice(wl, validate_level=1)
+    got = dd.forward().float().cpu().numpy()
+    want = dysat.forward(wl.graph, wl.chunks, wl.params, wl.X, wl.C, 8)["Y"]
+    cov = _covered(wl)
+    e = rel_err(got[cov], want[cov], floor=1.0)
+    print(f"{case}: Y rel_err {e:.3e}", flush=True)
+    assert e < TOL
+    assert np.isnan(got[~cov]).all()        # rows no chunk covers are not written
+    dd.layer.destroy()
