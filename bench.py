@@ -29,7 +29,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config2s", "config3w", "config4s"])
+    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config2s", "config3w", "config4s", "config5s", "config5"])
     ap.add_argument("--gather-mode", default="in_place", choices=["in_place", "staged"])
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -177,6 +177,108 @@ def cpu_baseline(wl, Y_gpu, target_seconds: float, seed: int) -> dict:
             "gpu_max_rel_err_on_sample": err}
 
 
+# Algorithmic HBM bytes per snapshot-vertex row of each stage of the graph-attention +
+# temporal-attention layer (kbar = stored non-zeros per row; the neighbour rows a stage gathers
+# are cache-served re-reads and are reported separately as gather traffic):
+def dysat_stage_bytes(kbar: float) -> dict:
+    csr = 4.0 * kbar + 8.0
+    return {
+        "project": 256 + 256 + 256 + 256 + 64 + 32,            # X, C in; zX, zC, s out
+        "edge_softmax": csr + 64 + 512 + 32,                    # CSR, own scalars; U (fp32), lse out
+        "temporal_fwd": 512 + 256,                              # U in; Y out
+        "temporal_bwd": 512 + 256 + 256 + 256 + 3 * 256 + 512 + 3 * 256,   # U, Y, target; dU, dQKV out; U, dQKV in (dW)
+        "gat_bwd_rows": csr + 256 + 512 + 96 + 64,              # dU, U, scalars in; d s_dst, c out
+        "gat_bwd_cols": csr + 4 * kbar + 4 + 512 + 96 + 512 + 512 + 512,    # CSR, owner; z, scalars; dz out; dz, X, C in (dW)
+    }
+
+
+def dysat_main(args):
+    """Workload of config 5: graph attention + causal temporal self-attention, bf16, forward +
+    backward against MSE targets."""
+    import numpy as np
+    import torch
+    from paper_2309_03523_amd import synth
+    from paper_2309_03523_amd.runner import DysatDevice
+
+    scale = 1.0 if args.workload == "config5" else 0.25
+    t0 = time.perf_counter()
+    wl, target = synth.config5(args.seed, scale)
+    t_gen = time.perf_counter() - t0
+    rows, nnz = wl.rows, wl.graph.nnz
+    t0 = time.perf_counter()
+    dd = DysatDevice(wl)
+    tgt = torch.from_numpy(target).cuda().to(torch.bfloat16)
+    loss = torch.zeros(1, device="cuda")
+    torch.cuda.synchronize()
+    t_create = time.perf_counter() - t0
+    layer, stream = dd.layer, torch.cuda.current_stream()
+
+    def step():
+        layer.forward(dd.X, dd.C, dd.Y, stream=stream)
+        layer.backward(dd.Y, target=tgt, loss_out=loss, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    layer.set_profiling(True)
+    stage = np.zeros(13, np.float64)
+    n_prof = max(3, min(args.steps, 10))
+    for _ in range(n_prof):
+        step()
+        stage += layer.stage_times()
+    stage /= n_prof
+    layer.set_profiling(False)
+    names = ["project", "edge_softmax", "temporal_fwd", "temporal_bwd", "gat_bwd_rows", "gat_bwd_cols"]
+    per_row = dysat_stage_bytes(nnz / rows)
+    kernels = {}
+    for i, nm in enumerate(names):
+        ms = float(stage[7 + i])
+        ach = per_row[nm] * rows / (ms * 1e-3) / 1e9
+        kernels[nm] = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
+                       "ms_per_launch": ms, "bytes_per_row": per_row[nm], "traffic": None}
+    for nm in ("edge_softmax", "gat_bwd_rows", "gat_bwd_cols"):
+        gather = (nnz / rows) * (256 + 32 + (96 if nm == "gat_bwd_cols" else 0)) * rows
+        kernels[nm]["gather_traffic_GBps"] = gather / (kernels[nm]["ms_per_launch"] * 1e-3) / 1e9
+    dom_name = max(kernels, key=lambda k: kernels[k]["ms_per_launch"])
+    dom = dict(kernels[dom_name], kernel=dom_name)
+    out = {"metric": "snapshot-vertex embeddings/s per DGNN layer", "value": rows * args.steps / elapsed,
+           "unit": "embeddings/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": 1e3 * elapsed / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"config5{'' if scale == 1.0 else ' at 1/4 of its vertex count'}: graph attention (8 heads x 16) + "
+                                  f"causal temporal self-attention, bf16, 16 snapshots x {wl.graph.N} vertices, avg degree 12, "
+                                  f"{len(wl.chunks)} uneven chunks, forward + backward (MSE)",
+                      "rows": rows, "nnz": nnz, "pass": "forward+backward"},
+           "roofline": dom, "kernels": kernels, "loss": float(loss.item()),
+           "setup_s": {"generate": t_gen, "upload_create_pack": t_create}}
+    if not args.no_cpu_baseline:
+        from oracle import dysat as odysat
+        # the oracle (torch CPU, float64, forward + gradients) on the narrowest chunks
+        order = np.argsort(wl.chunks[:, 1] - wl.chunks[:, 0])[:2]
+        sub = wl.chunks[order]
+        t0 = time.perf_counter()
+        o = odysat.gradients(wl.graph, sub, wl.params, wl.X, wl.C, 8, target=target)
+        dt = time.perf_counter() - t0
+        n_rows = int(((sub[:, 1] - sub[:, 0]) * (sub[:, 3] - sub[:, 2])).sum())
+        Yg = dd.Y.float().cpu().numpy()
+        errs = []
+        for v_lo, v_hi, t_lo, t_hi in sub.tolist():
+            want = o["Y"][t_lo:t_hi, v_lo:v_hi]
+            got = Yg[t_lo:t_hi, v_lo:v_hi]
+            rms = float(np.sqrt(np.mean(want * want)))
+            errs.append(float(np.max(np.abs(got - want) / np.maximum(np.abs(want), rms))))
+        out["cpu_baseline"] = {"value": n_rows / dt, "unit": "embeddings/s", "cores": torch.get_num_threads(),
+                               "kind": "oracle",
+                               "sample": f"the 2 narrowest chunks (of {len(wl.chunks)}), forward + gradients = {n_rows} rows, {dt:.1f} s",
+                               "gpu_max_rel_err_on_sample": max(errs)}
+    print(json.dumps(out))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -185,6 +287,12 @@ def main():
         sys.exit(2)
     import numpy as np
     import torch
+    if args.workload.startswith("config5"):
+        if not torch.cuda.is_available():
+            print("bench.py needs a GPU", file=sys.stderr)
+            sys.exit(2)
+        dysat_main(args)
+        return
 
     from paper_2309_03523_amd.runner import DeviceWorkload
 
@@ -233,7 +341,7 @@ def main():
 
     # per-stage device times of the same launches, HIP events on the launch stream
     layer.set_profiling(True)
-    stage = np.zeros(7, np.float64)
+    stage = np.zeros(13, np.float64)
     n_prof = max(3, min(args.steps, 10))
     for _ in range(n_prof):
         step()

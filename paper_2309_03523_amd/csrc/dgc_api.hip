@@ -311,8 +311,9 @@ dgc_status_t build_dysat(dgc_layer* L, const std::vector<ChunkInfo>& cinfo, hipS
   dysat_build_owner(L->d_segs, L->nseg, T, N, d_owner, st);
   DGC_HIP_TRY(hipStreamSynchronize(st));
   w.used_t = d_used; w.tile_ptr = d_tptr; w.owner = d_owner;
-  uint16_t** rowbufs[9] = {&w.zX, &w.zC, &w.U, &w.dU, &w.dQ, &w.dK, &w.dV, &w.dzX, &w.dzC};
+  uint16_t** rowbufs[8] = {&w.zX, &w.zC, &w.dU, &w.dQ, &w.dK, &w.dV, &w.dzX, &w.dzC};
   for (uint16_t** b : rowbufs) DGC_HIP_TRY(dev_alloc(L, b, TN * S));
+  DGC_HIP_TRY(dev_alloc(L, &w.U, TN * S));
   DGC_HIP_TRY(dev_alloc(L, &w.sX, TN * 16));
   DGC_HIP_TRY(dev_alloc(L, &w.sC, TN * 8));
   DGC_HIP_TRY(dev_alloc(L, &w.lse, TN * 8));
@@ -695,6 +696,7 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* L, const void* Xv, int64_t ldx, cons
     if (C1v || H0 || HN || reset_mask)
       return fail(DGC_ERR_INVALID_ARG, "C1 / H0 / HN / reset_mask do not apply to the attention layer");
     L->evd_fwd = false;
+    L->dy.X = Xv; L->dy.ldx = ldx; L->dy.C = Cv; L->dy.ldc = ldc;
     dysat_forward(L->dy, Xv, ldx, Cv, ldc, Yv, ldy, L->profiling ? L->evd : nullptr, st);
     if (L->profiling) L->evd_fwd = true;
     DGC_HIP_TRY(hipGetLastError());

@@ -1,59 +1,16 @@
 // Graph-attention structure encoder + causal temporal self-attention time encoder (the
 // DySAT-style DGNN of the paper's Sections 2.1 and 6) over a fused batch of chunks, bf16 storage
-// with fp32 accumulation.  S = F = 128, 8 heads of 16 dims, windows of up to 16 snapshots.
+// with fp32 accumulation: forward pass.  S = F = 128, 8 heads of 16 dims, windows of up to 16
+// snapshots.
 //
 //   z = W x (own rows) / W c (cache rows, Section 5.2);  e_ij^h = LeakyReLU_0.2(a_dst^h.z_i^h + a_src^h.z_j^h)
 //   alpha = softmax over the stored row;  u_i = sum_j alpha_ij z_j;  g = ELU(u)
 //   p_s = g_s + pos[s];  q, k, v = W_q p, W_k p, W_v p;  y_s^h = sum_{r<=s} softmax_r(q_s^h.k_r^h / 4) v_r^h
-//
-// All dense products run on v_mfma_f32_32x32x16_bf16: lane l supplies A[l%32][8*(l/32) .. +7] and
-// B[8*(l/32) .. +7][l%32] and receives D[8*(v/4) + 4*(l/32) + v%4][l%32] in register v.  With the
-// weights as A operand and 32 activation rows as B operand, lane (n = l%32, hh = l/32) ends up with
-// features 8g + 4hh + e (g = v/4, e = v%4) of its own row n: "row layout".  With the activations as
-// A operand and the weights as B operand, lane (f = l%32, hh) ends up with feature f of rows
-// 8g + 4hh + e: "column layout".  Eight consecutive accumulator registers (g = 2c, 2c+1) of a lane
-// are one k-half of a 16-wide contraction index in either layout, which is what lets every
-// attention product below take its operands straight from accumulators, without moving data
-// between lanes.
-#include "dgc_internal.h"
+#include "dgc_dysat_dev.h"
 
 namespace dgc {
+using namespace dysat;
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-
-constexpr int kS = 128;      // feature width (input, structure output, attention width)
-constexpr int kHeads = 8;
-constexpr int kD = 16;       // dims per head
-constexpr int kMaxW = 16;    // longest chunk window
-constexpr float kSlope = 0.2f;
-
-__device__ __forceinline__ bf16x8 as_frag(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
-__device__ __forceinline__ float bf_lo(uint32_t u) { return __uint_as_float(u << 16); }
-__device__ __forceinline__ float bf_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
-__device__ __forceinline__ uint32_t pack2(float a, float b) {
-  bf16x2 v = {(__bf16)a, (__bf16)b};
-  return __builtin_bit_cast(uint32_t, v);
-}
-__device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) { return make_uint2(pack2(a, b), pack2(c, d)); }
-__device__ __forceinline__ bf16x8 pack8(const float* x) {
-  bf16x8 v;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) v[i] = (__bf16)x[i];
-  return v;
-}
-__device__ __forceinline__ void unpack8(uint4 u, float* x) {
-  x[0] = bf_lo(u.x); x[1] = bf_hi(u.x); x[2] = bf_lo(u.y); x[3] = bf_hi(u.y);
-  x[4] = bf_lo(u.z); x[5] = bf_hi(u.z); x[6] = bf_lo(u.w); x[7] = bf_hi(u.w);
-}
-__device__ __forceinline__ floatx16 mfma(bf16x8 a, bf16x8 b, floatx16 c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-}
-__device__ __forceinline__ float lrelu(float x) { return x > 0.f ? x : kSlope * x; }
-__device__ __forceinline__ float elu(float x) { return x > 0.f ? x : __expf(x) - 1.f; }
 
 // ---------------------------------------------------------------------------------------------
 // Weights [n_out = 128][n_in = 128] fp32 -> bf16 operand fragments, 16 bytes per lane.
@@ -76,10 +33,6 @@ __global__ void k_pack_w_bf16(const float* W, uint4* packed, int mode) {
 }
 
 __global__ void k_fill_i32(int32_t* p, int32_t v, int64_t n) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = v;
-}
-__global__ void k_fill_f32(float* p, float v, int64_t n) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
 }
@@ -182,7 +135,7 @@ struct GatArgs {
   const int32_t* work; int64_t n_work;     // [n][3]: segment, first local row, rows
   const uint16_t* zX; const uint16_t* zC;
   const float* sX; const float* sC;
-  uint16_t* U;     // [T*N][128] pre-ELU output
+  float* U;        // [T*N][128] pre-ELU output (fp32: every later stage is sensitive to it)
   float* lse;      // [T*N][8] log-sum-exp of the logits of every (row, head)
 };
 
@@ -240,7 +193,7 @@ __global__ __launch_bounds__(256) void k_gat_aggregate(GatArgs a) {
       }
     }
     const float inv = l > 0.f ? 1.f / l : 0.f;
-    *reinterpret_cast<uint32_t*>(a.U + (base + i) * kS + 2 * lane) = pack2(acc0 * inv, acc1 * inv);
+    *reinterpret_cast<float2*>(a.U + (base + i) * kS + 2 * lane) = make_float2(acc0 * inv, acc1 * inv);
     if ((lane & 7) == 0) a.lse[(base + i) * 8 + head] = m + __logf(l);
   }
 }
@@ -254,74 +207,18 @@ __global__ __launch_bounds__(256) void k_gat_aggregate(GatArgs a) {
 // is lane-local plus one exchange with lane l^32, and the probabilities are directly the B
 // operand of the product with V (A operand = V in column layout, masked to the head; B masked
 // to the vertex), which lands in row layout, ready to be stored.
+// Every in-register operand (P, Q, K, V, the probabilities) is carried as a hi + lo pair of bf16
+// values, so that the only roundings to bf16 are those of the stored tensors (z, U, Y).
 struct TemporalArgs {
   const ChunkInfo* chunks; int32_t n_chunks;
   const int64_t* tile_ptr;   // [n_chunks+1] first 2-vertex tile of every chunk
   int64_t n_tiles;
   int64_t N; int32_t T;
-  const uint16_t* U;
+  const float* U;
   const float* pos;          // [T][128]
   const uint4* Wq; const uint4* Wk; const uint4* Wv;   // mode-0 fragments
   uint16_t* Y; int64_t ldy;
 };
-
-struct TileRow {   // what a lane needs to know about its row n = lane % 32
-  int64_t row;     // t*N + v (clamped to a valid row when !valid)
-  int32_t t, s, a;
-  bool valid;
-};
-
-__device__ __forceinline__ TileRow tile_row(const ChunkInfo* chunks, int32_t n_chunks, const int64_t* tile_ptr,
-                                            int64_t tile, int64_t N, int lane) {
-  int lo = 0, hi = n_chunks;   // largest k with tile_ptr[k] <= tile
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (tile_ptr[mid] <= tile) lo = mid; else hi = mid;
-  }
-  const ChunkInfo c = chunks[lo];
-  const int n = lane & 31;
-  TileRow r;
-  r.a = n >> 4; r.s = n & 15;
-  const int64_t vl = 2 * (tile - tile_ptr[lo]) + r.a;
-  r.valid = vl < c.nv && r.s < c.w;
-  r.t = c.t_lo + (r.s < c.w ? r.s : 0);
-  r.row = (int64_t)r.t * N + c.v_lo + (vl < c.nv ? vl : 0);
-  return r;
-}
-
-// x -> hi + lo with hi = bf16(x), lo = bf16(x - hi): two bf16 operands that together carry 16
-// mantissa bits, so a product taken as hi*hi + hi*lo + lo*hi is accurate to ~2^-16
-__device__ __forceinline__ void split8(const float* x, bf16x8& hi, bf16x8& lo) {
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const __bf16 h = (__bf16)x[i];
-    hi[i] = h;
-    lo[i] = (__bf16)(x[i] - (float)h);
-  }
-}
-
-// P = ELU(U) + pos for the lane's row, as eight B/A-operand fragments (hi part, and lo part if
-// LO); rows that are not valid read as zero
-template <bool LO>
-__device__ __forceinline__ void load_p_frags(const uint16_t* U, const float* pos, const TileRow& r, int hh, bf16x8* pf,
-                                             bf16x8* pl) {
-#pragma unroll
-  for (int kb = 0; kb < 8; ++kb) {
-    float x[8];
-    if (r.valid) {
-      unpack8(*reinterpret_cast<const uint4*>(U + r.row * kS + kb * 16 + 8 * hh), x);
-      const float4 p0 = *reinterpret_cast<const float4*>(pos + r.t * kS + kb * 16 + 8 * hh);
-      const float4 p1 = *reinterpret_cast<const float4*>(pos + r.t * kS + kb * 16 + 8 * hh + 4);
-      x[0] = elu(x[0]) + p0.x; x[1] = elu(x[1]) + p0.y; x[2] = elu(x[2]) + p0.z; x[3] = elu(x[3]) + p0.w;
-      x[4] = elu(x[4]) + p1.x; x[5] = elu(x[5]) + p1.y; x[6] = elu(x[6]) + p1.z; x[7] = elu(x[7]) + p1.w;
-    } else {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) x[i] = 0.f;
-    }
-    if (LO) split8(x, pf[kb], pl[kb]);
-    else pf[kb] = pack8(x);
-  }
-}
 
 // softmax over the key steps r <= s of the lane's own vertex; x[p] is the raw score against key
 // step r = 8 (p/4) + 4 hh + p%4; returns probabilities (0 for masked positions)
@@ -346,8 +243,6 @@ __device__ __forceinline__ void causal_softmax(float* x, int s, int hh) {
   for (int p = 0; p < 8; ++p) x[p] *= inv;
 }
 
-// The forward pass carries every in-register operand (P, Q, K, V, the probabilities) as a
-// hi + lo pair of bf16 values, so that the only roundings to bf16 are the stored tensors (z, U, Y).
 __global__ __launch_bounds__(256) void k_temporal_fwd(TemporalArgs a) {
   const int lane = threadIdx.x & 63;
   const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -414,8 +309,6 @@ __global__ __launch_bounds__(256) void k_temporal_fwd(TemporalArgs a) {
   }
 }
 
-unsigned blocks_for(int64_t n, int per_block) { return (unsigned)((n + per_block - 1) / per_block); }
-
 }  // namespace
 
 void dysat_build_owner(const Segment* segs, int64_t nseg, int32_t T, int64_t N, int32_t* owner, hipStream_t st) {
@@ -458,10 +351,5 @@ void dysat_forward(const DysatWs& ws, const void* X, int64_t ldx, const void* C,
   hipLaunchKernelGGL(k_temporal_fwd, blocks_for(ws.n_tiles, 4), 256, 0, st, ta);
   if (ev) (void)hipEventRecord(ev[3], st);
 }
-
-int64_t dysat_partial_elems(const DysatWs&) { return 1; }
-int64_t dysat_loss_partial_elems(const DysatWs&) { return 1; }
-void dysat_backward(const DysatWs&, const void*, int64_t, const void*, int64_t, const void*, int64_t, float*,
-                    hipEvent_t*, hipStream_t) {}
 
 }  // namespace dgc

@@ -207,9 +207,11 @@ struct DysatWs {
   uint4 *WqT, *WkT, *WvT;        // bf16 fragments of the transposes (backward)
   uint16_t *zX, *zC;         // [T*N][128] bf16 projections of input and cache rows
   float *sX, *sC;            // attention scalars
-  uint16_t* U;               // [T*N][128] bf16 structure-encoder output before ELU
+  float* U;                  // [T*N][128] fp32 structure-encoder output before ELU
   float* lse;                // [T*N][8]
   // backward
+  const void* X; int64_t ldx;                // inputs of the last forward (read again by backward)
+  const void* C; int64_t ldc;
   uint16_t *dU, *dQ, *dK, *dV, *dzX, *dzC;   // [T*N][128] bf16
   float* st2;                // [T*N][16]: d s_dst[8], c[8] of every covered row
   float* partial;            // scratch for the parameter-gradient reductions

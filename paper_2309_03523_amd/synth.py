@@ -404,9 +404,14 @@ def random_small(seed: int, T: int, N: int, F: int, S: int, H: int, avg_deg: flo
 
 def round_bf16(a: np.ndarray) -> np.ndarray:
     """fp32 array whose values are exactly representable in bfloat16 (round to nearest even)."""
-    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
-    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
-    return u.astype(np.uint32).view(np.float32).reshape(a.shape)
+    out = np.array(a, dtype=np.float32, order="C")          # a copy; finite values only
+    flat = out.reshape(-1).view(np.uint32)
+    step = 1 << 24
+    for lo in range(0, flat.size, step):                    # in pieces: no array-sized temporaries
+        u = flat[lo:lo + step]
+        u += ((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF)
+        u &= np.uint32(0xFFFF0000)
+    return out
 
 
 def to_bf16_bits(a: np.ndarray) -> np.ndarray:
@@ -466,8 +471,9 @@ def config5(seed: int = 0, scale: float = 1.0):
     C = _normal_f32(stream(seed, "cache"), (T, N, F))
     C *= np.float32(0.1)
     C += X
+    X, C = round_bf16(X), round_bf16(C)
     target = round_bf16(_normal_f32(stream(seed, "target"), (T, N, F)))
     wl = Workload("config5" if scale == 1.0 else f"config5@{scale:g}", graph, chunks, F, F, F, "none", 1,
-                  round_bf16(X), round_bf16(C), None, None, dysat_params(seed, T, F, F, heads))
+                  X, C, None, None, dysat_params(seed, T, F, F, heads))
     wl.notes["heads"] = heads
     return wl, target
