@@ -318,6 +318,26 @@ dgc_status_t build_dysat(dgc_layer* L, const std::vector<ChunkInfo>& cinfo, hipS
   DGC_HIP_TRY(dev_alloc(L, &w.sC, TN * 8));
   DGC_HIP_TRY(dev_alloc(L, &w.lse, TN * 8));
   DGC_HIP_TRY(dev_alloc(L, &w.st2, TN * 16));
+  // split rows: those of the covered rows come from the packing; the reverse-edge pass walks every
+  // vertex of the snapshots in use and gets its own list
+  w.long_nnz = L->long_nnz; w.part_nnz = L->part_nnz;
+  w.work_long = L->d_work_long; w.n_long = L->n_long;
+  {
+    int32_t* d_cnt = nullptr;
+    int32_t n_parts = 0;
+    DGC_HIP_TRY(dev_alloc(L, &d_cnt, 1));
+    DGC_HIP_TRY(hipMemsetAsync(d_cnt, 0, sizeof(int32_t), st));
+    dysat_cols_long(w.g, w.used_t, w.n_used, w.long_nnz, w.part_nnz, d_cnt, nullptr, st);
+    DGC_HIP_TRY(hipMemcpyAsync(&n_parts, d_cnt, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    DGC_HIP_TRY(hipStreamSynchronize(st));
+    int32_t* d_list = nullptr;
+    DGC_HIP_TRY(dev_alloc(L, &d_list, 4 * (int64_t)n_parts));
+    DGC_HIP_TRY(hipMemsetAsync(d_cnt, 0, sizeof(int32_t), st));
+    if (n_parts > 0) dysat_cols_long(w.g, w.used_t, w.n_used, w.long_nnz, w.part_nnz, d_cnt, d_list, st);
+    DGC_HIP_TRY(hipStreamSynchronize(st));
+    w.cols_long = d_list; w.n_cols_long = n_parts;
+  }
+  DGC_HIP_TRY(dev_alloc(L, &w.long_partial, dysat_long_partial_elems(w)));
   w.partial_elems = dysat_partial_elems(w);
   DGC_HIP_TRY(dev_alloc(L, &w.partial, w.partial_elems));
   DGC_HIP_TRY(dev_alloc(L, &w.loss_partial, dysat_loss_partial_elems(w)));

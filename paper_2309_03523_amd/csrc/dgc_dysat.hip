@@ -15,9 +15,8 @@ namespace {
 // ---------------------------------------------------------------------------------------------
 // Weights [n_out = 128][n_in = 128] fp32 -> bf16 operand fragments, 16 bytes per lane.
 //  mode 0: fragment (jb, kb) of W as the 32-row operand: lane l holds W[32 jb + l%32][16 kb + 8 (l/32) + 0..7].
-//  mode 1: fragment (ib, ks) of W^T for products whose contraction index is W's row index and whose
-//          other operand comes from accumulators in row layout: lane l holds, for p = 0..7,
-//          W[16 ks + 8 (p/4) + 4 (l/32) + p%4][32 ib + l%32].
+//  mode 1: fragment (ib, ks) of W^T, for products whose contraction index is W's row index:
+//          lane l holds W[16 ks + 8 (l/32) + 0..7][32 ib + l%32].
 __global__ void k_pack_w_bf16(const float* W, uint4* packed, int mode) {
   const int idx = blockIdx.x * blockDim.x + threadIdx.x;   // (blk * 8 + k) * 64 + lane
   if (idx >= 4 * 8 * 64) return;
@@ -27,7 +26,7 @@ __global__ void k_pack_w_bf16(const float* W, uint4* packed, int mode) {
 #pragma unroll
   for (int p = 0; p < 8; ++p) {
     if (mode == 0) x[p] = W[(blk * 32 + r32) * kS + k * 16 + 8 * hh + p];
-    else x[p] = W[(k * 16 + 8 * (p >> 2) + 4 * hh + (p & 3)) * kS + blk * 32 + r32];
+    else x[p] = W[(k * 16 + 8 * hh + p) * kS + blk * 32 + r32];
   }
   packed[idx] = __builtin_bit_cast(uint4, pack8(x));
 }
@@ -128,16 +127,74 @@ __global__ __launch_bounds__(256) void k_gat_project(ProjArgs a) {
 // the 128 features (two per lane, head = lane / 8), so a neighbour's z row is one coalesced
 // 256-byte load.  Column ids are loaded 64 at a time and broadcast lane by lane (row addresses
 // stay wave-uniform); eight neighbour rows are in flight; the softmax is accumulated online
-// (running maximum, rescale once per batch of eight).
+// (running maximum, rescale once per batch of eight).  Rows longer than long_nnz (hubs of the
+// power-law graphs) are cut into parts of part_nnz non-zeros, one wavefront each; a part leaves
+// its (maximum, sum, weighted sum) in a scratch record and a second kernel merges the records of
+// a row in part order.
 struct GatArgs {
   GraphDev g;
   const Segment* segs;
   const int32_t* work; int64_t n_work;     // [n][3]: segment, first local row, rows
+  const int32_t* work_long; int64_t n_long;   // [n][4]: segment, local row, part, parts
+  int32_t long_nnz, part_nnz;
+  float* long_partial;                     // [n_long][kLongRec]
   const uint16_t* zX; const uint16_t* zC;
   const float* sX; const float* sC;
   float* U;        // [T*N][128] pre-ELU output (fp32: every later stage is sensitive to it)
   float* lse;      // [T*N][8] log-sum-exp of the logits of every (row, head)
 };
+
+struct SoftAcc { float m, l, a0, a1; };
+
+// online softmax-weighted sum over the stored non-zeros [e0, e1) of row i of segment s
+__device__ __forceinline__ SoftAcc gat_row_range(const GatArgs& a, const Segment& s, const int32_t* col, int64_t base,
+                                                 float sd, int64_t e0, int64_t e1, int lane, int head) {
+  SoftAcc r{-INFINITY, 0.f, 0.f, 0.f};
+  for (int64_t eb = e0; eb < e1; eb += 64) {
+    const int cnt = (int)min((int64_t)64, e1 - eb);
+    const int32_t j = lane < cnt ? col[eb + lane] : 0;
+    const int inside = (j >= s.v_lo && j < s.v_hi) ? 1 : 0;
+    for (int q0 = 0; q0 < cnt; q0 += 8) {
+      uint32_t zz[8];
+      float ev[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        ev[q] = -INFINITY;
+        zz[q] = 0u;
+        if (q0 + q < cnt) {
+          const int64_t jq = base + __builtin_amdgcn_readlane(j, q0 + q);
+          const bool in = __builtin_amdgcn_readlane(inside, q0 + q) != 0;
+          zz[q] = *reinterpret_cast<const uint32_t*>((in ? a.zX : a.zC) + jq * kS + 2 * lane);
+          ev[q] = in ? a.sX[jq * 16 + head] : a.sC[jq * 8 + head];
+        }
+      }
+      float bm = -INFINITY;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        ev[q] = lrelu(sd + ev[q]);       // -inf stays -inf
+        bm = fmaxf(bm, ev[q]);
+      }
+      const float mn = fmaxf(r.m, bm);
+      const float sc = __expf(r.m - mn);
+      r.l *= sc; r.a0 *= sc; r.a1 *= sc;
+      r.m = mn;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const float p = __expf(ev[q] - mn);
+        r.l += p;
+        r.a0 += p * bf_lo(zz[q]);
+        r.a1 += p * bf_hi(zz[q]);
+      }
+    }
+  }
+  return r;
+}
+
+__device__ __forceinline__ void gat_row_store(const GatArgs& a, int64_t row, const SoftAcc& r, int lane, int head) {
+  const float inv = r.l > 0.f ? 1.f / r.l : 0.f;
+  *reinterpret_cast<float2*>(a.U + row * kS + 2 * lane) = make_float2(r.a0 * inv, r.a1 * inv);
+  if ((lane & 7) == 0) a.lse[row * 8 + head] = r.m + __logf(r.l);
+}
 
 __global__ __launch_bounds__(256) void k_gat_aggregate(GatArgs a) {
   const int lane = threadIdx.x & 63;
@@ -145,57 +202,66 @@ __global__ __launch_bounds__(256) void k_gat_aggregate(GatArgs a) {
   if (item >= a.n_work) return;
   const int32_t si = a.work[3 * item], r0 = a.work[3 * item + 1], nr = a.work[3 * item + 2];
   const Segment s = a.segs[si];
-  const int64_t N = a.g.N;
   const int64_t* rowptr = a.g.rowptr[s.t];
   const int32_t* col = a.g.colidx[s.t];
-  const int64_t base = (int64_t)s.t * N;
+  const int64_t base = (int64_t)s.t * a.g.N;
   const int head = lane >> 3;
   for (int rr = 0; rr < nr; ++rr) {
     const int64_t i = s.v_lo + r0 + rr;
     const int64_t e0 = rowptr[i], e1 = rowptr[i + 1];
+    if (e1 - e0 > a.long_nnz) continue;    // split rows: k_gat_aggregate_long
     const float sd = a.sX[(base + i) * 16 + 8 + head];
-    float m = -INFINITY, l = 0.f, acc0 = 0.f, acc1 = 0.f;
-    for (int64_t eb = e0; eb < e1; eb += 64) {
-      const int cnt = (int)min((int64_t)64, e1 - eb);
-      const int32_t j = lane < cnt ? col[eb + lane] : 0;
-      const int inside = (j >= s.v_lo && j < s.v_hi) ? 1 : 0;
-      for (int q0 = 0; q0 < cnt; q0 += 8) {
-        uint32_t zz[8];
-        float ev[8];
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-          ev[q] = -INFINITY;
-          zz[q] = 0u;
-          if (q0 + q < cnt) {
-            const int64_t jq = base + __builtin_amdgcn_readlane(j, q0 + q);
-            const bool in = __builtin_amdgcn_readlane(inside, q0 + q) != 0;
-            zz[q] = *reinterpret_cast<const uint32_t*>((in ? a.zX : a.zC) + jq * kS + 2 * lane);
-            ev[q] = in ? a.sX[jq * 16 + head] : a.sC[jq * 8 + head];
-          }
-        }
-        float bm = -INFINITY;
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-          ev[q] = lrelu(sd + ev[q]);       // -inf stays -inf
-          bm = fmaxf(bm, ev[q]);
-        }
-        const float mn = fmaxf(m, bm);
-        const float sc = __expf(m - mn);
-        l *= sc; acc0 *= sc; acc1 *= sc;
-        m = mn;
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-          const float p = __expf(ev[q] - mn);
-          l += p;
-          acc0 += p * bf_lo(zz[q]);
-          acc1 += p * bf_hi(zz[q]);
-        }
-      }
-    }
-    const float inv = l > 0.f ? 1.f / l : 0.f;
-    *reinterpret_cast<float2*>(a.U + (base + i) * kS + 2 * lane) = make_float2(acc0 * inv, acc1 * inv);
-    if ((lane & 7) == 0) a.lse[(base + i) * 8 + head] = m + __logf(l);
+    const SoftAcc r = gat_row_range(a, s, col, base, sd, e0, e1, lane, head);
+    gat_row_store(a, base + i, r, lane, head);
   }
+}
+
+// record of one part of a split row: weighted sum [128], maximum [8], sum [8]
+constexpr int kLongRec = 144;
+
+__global__ __launch_bounds__(256) void k_gat_aggregate_long(GatArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (item >= a.n_long) return;
+  const int32_t* w = a.work_long + 4 * item;
+  const Segment s = a.segs[w[0]];
+  const int64_t i = s.v_lo + w[1];
+  const int64_t* rowptr = a.g.rowptr[s.t];
+  const int64_t base = (int64_t)s.t * a.g.N;
+  const int head = lane >> 3;
+  const int64_t e0 = rowptr[i] + (int64_t)w[2] * a.part_nnz, e1 = min(rowptr[i + 1], e0 + a.part_nnz);
+  const float sd = a.sX[(base + i) * 16 + 8 + head];
+  const SoftAcc r = gat_row_range(a, s, a.g.colidx[s.t], base, sd, e0, e1, lane, head);
+  float* rec = a.long_partial + item * kLongRec;
+  *reinterpret_cast<float2*>(rec + 2 * lane) = make_float2(r.a0, r.a1);
+  if ((lane & 7) == 0) {
+    rec[128 + head] = r.m;
+    rec[136 + head] = r.l;
+  }
+}
+
+// one wavefront per split row (the item of its part 0) merges the parts in order
+__global__ __launch_bounds__(256) void k_gat_aggregate_merge(GatArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (item >= a.n_long) return;
+  const int32_t* w = a.work_long + 4 * item;
+  if (w[2] != 0) return;
+  const Segment s = a.segs[w[0]];
+  const int head = lane >> 3;
+  const int parts = w[3];
+  float mx = -INFINITY;
+  for (int p = 0; p < parts; ++p) mx = fmaxf(mx, a.long_partial[(item + p) * kLongRec + 128 + head]);
+  SoftAcc r{mx, 0.f, 0.f, 0.f};
+  for (int p = 0; p < parts; ++p) {
+    const float* rec = a.long_partial + (item + p) * kLongRec;
+    const float sc = __expf(rec[128 + head] - mx);
+    const float2 v = *reinterpret_cast<const float2*>(rec + 2 * lane);
+    r.l += sc * rec[136 + head];
+    r.a0 += sc * v.x;
+    r.a1 += sc * v.y;
+  }
+  gat_row_store(a, (int64_t)s.t * a.g.N + s.v_lo + w[1], r, lane, head);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -243,22 +309,36 @@ __device__ __forceinline__ void causal_softmax(float* x, int s, int hh) {
   for (int p = 0; p < 8; ++p) x[p] *= inv;
 }
 
-__global__ __launch_bounds__(256) void k_temporal_fwd(TemporalArgs a) {
-  const int lane = threadIdx.x & 63;
-  const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (tile >= a.n_tiles) return;
+// The three weight matrices (96 KB of fragments) are staged in LDS once per workgroup; the
+// workgroup's waves then walk the tiles with a grid stride and never synchronise again.
+constexpr int kFragsPerW = 4 * 8 * 64;   // uint4 fragments of one 128 x 128 weight
+
+__device__ __forceinline__ void stage_weights(uint4* lds, const uint4* w0, const uint4* w1, const uint4* w2) {
+  for (int i = threadIdx.x; i < kFragsPerW; i += blockDim.x) {
+    lds[i] = w0[i];
+    lds[kFragsPerW + i] = w1[i];
+    lds[2 * kFragsPerW + i] = w2[i];
+  }
+  __syncthreads();
+}
+
+__global__ __launch_bounds__(512) void k_temporal_fwd(TemporalArgs a) {
+  extern __shared__ uint4 wlds[];
+  stage_weights(wlds, a.Wq, a.Wk, a.Wv);
+  const int lane = threadIdx.x & 63, nw = blockDim.x >> 6;
   const int hh = lane >> 5, f = lane & 31;
+  const bf16x8 zero8 = {};
+  for (int64_t tile = (int64_t)blockIdx.x * nw + (threadIdx.x >> 6); tile < a.n_tiles; tile += (int64_t)gridDim.x * nw) {
   const TileRow r = tile_row(a.chunks, a.n_chunks, a.tile_ptr, tile, a.N, lane);
   bf16x8 pf[8], pl[8];
   load_p_frags<true>(a.U, a.pos, r, hh, pf, pl);
-  const bf16x8 zero8 = {};
 #pragma unroll 1
   for (int jb = 0; jb < 4; ++jb) {
     floatx16 q = {}, k = {}, vt = {};
 #pragma unroll
     for (int kb = 0; kb < 8; ++kb) {
       const int fi = (jb * 8 + kb) * 64 + lane;
-      const bf16x8 wq = as_frag(a.Wq[fi]), wk = as_frag(a.Wk[fi]), wv = as_frag(a.Wv[fi]);
+      const bf16x8 wq = as_frag(wlds[fi]), wk = as_frag(wlds[kFragsPerW + fi]), wv = as_frag(wlds[2 * kFragsPerW + fi]);
       q = mfma(wq, pf[kb], q);
       q = mfma(wq, pl[kb], q);
       k = mfma(wk, pf[kb], k);
@@ -307,6 +387,7 @@ __global__ __launch_bounds__(256) void k_temporal_fwd(TemporalArgs a) {
             pack4(y[4 * g], y[4 * g + 1], y[4 * g + 2], y[4 * g + 3]);
     }
   }
+  }
 }
 
 }  // namespace
@@ -340,15 +421,31 @@ void dysat_forward(const DysatWs& ws, const void* X, int64_t ldx, const void* C,
   if (ev) (void)hipEventRecord(ev[1], st);
   GatArgs ga{};
   ga.g = ws.g; ga.segs = ws.segs; ga.work = ws.work_short; ga.n_work = ws.n_short;
+  ga.work_long = ws.work_long; ga.n_long = ws.n_long; ga.long_nnz = ws.long_nnz; ga.part_nnz = ws.part_nnz;
+  ga.long_partial = ws.long_partial;
   ga.zX = ws.zX; ga.zC = ws.zC; ga.sX = ws.sX; ga.sC = ws.sC; ga.U = ws.U; ga.lse = ws.lse;
   hipLaunchKernelGGL(k_gat_aggregate, blocks_for(ws.n_short, 4), 256, 0, st, ga);
+  if (ws.n_long > 0) {
+    hipLaunchKernelGGL(k_gat_aggregate_long, blocks_for(ws.n_long, 4), 256, 0, st, ga);
+    hipLaunchKernelGGL(k_gat_aggregate_merge, blocks_for(ws.n_long, 4), 256, 0, st, ga);
+  }
   if (ev) (void)hipEventRecord(ev[2], st);
   TemporalArgs ta{};
   ta.chunks = ws.chunks; ta.n_chunks = ws.n_chunks; ta.tile_ptr = ws.tile_ptr; ta.n_tiles = ws.n_tiles;
   ta.N = ws.N; ta.T = ws.T; ta.U = ws.U; ta.pos = ws.P[DY_POS];
   ta.Wq = ws.Wqp; ta.Wk = ws.Wkp; ta.Wv = ws.Wvp;
   ta.Y = static_cast<uint16_t*>(Y); ta.ldy = ldy;
-  hipLaunchKernelGGL(k_temporal_fwd, blocks_for(ws.n_tiles, 4), 256, 0, st, ta);
+  {
+    static bool attr_set = false;   // dynamic LDS above 64 KB has to be allowed once per kernel
+    const size_t lds = sizeof(uint4) * 3 * kFragsPerW;
+    if (!attr_set) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_temporal_fwd), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds);
+      attr_set = true;
+    }
+    const unsigned grid = (unsigned)std::min<int64_t>(256, (ws.n_tiles + 7) / 8);
+    hipLaunchKernelGGL(k_temporal_fwd, grid, 512, lds, st, ta);
+  }
   if (ev) (void)hipEventRecord(ev[3], st);
 }
 

@@ -24,15 +24,12 @@ struct TemporalBwdArgs {
   int64_t N; int32_t T;
   const float* U; const float* pos;
   const uint4 *Wq, *Wk, *Wv;       // row-operand fragments
-  const uint4 *WqT, *WkT, *WvT;    // fragments of the transposes
   const uint16_t* Y; int64_t ldy;          // with target: dY = scale * (Y - target)
   const uint16_t* dY; int64_t lddy;        // or the upstream gradient itself
   const uint16_t* target; int64_t ldt;
   float scale;
-  uint16_t *dU, *dQ, *dK, *dV;
-  float* dpos_partial;   // [n_waves][T][128], zero on entry
-  float* loss_partial;   // [n_waves]
-  int32_t n_waves;
+  uint16_t *dQ, *dK, *dV;
+  float* loss_partial;   // [gridDim.x * waves per block]
 };
 
 // upstream gradient of n consecutive features (n = 8 or 4) of one row; adds (Y - target)^2 to *sq
@@ -69,63 +66,43 @@ __device__ __forceinline__ void load_dy(const TemporalBwdArgs& a, int64_t row, i
   }
 }
 
-__device__ __forceinline__ void flush_dpos(float* slot, int t_lo, int T, int lane, floatx16* acc) {
-  const int n = lane & 31, hh = lane >> 5, s = n & 15;
-#pragma unroll
-  for (int ib = 0; ib < 4; ++ib) {
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[ib][v] += __shfl_xor(acc[ib][v], 16);   // the two vertices of the tile
-    if (n < 16 && t_lo + s < T) {
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        float4* p = reinterpret_cast<float4*>(slot + (int64_t)(t_lo + s) * kS + ib * 32 + 8 * g + 4 * hh);
-        float4 o = *p;
-        o.x += acc[ib][4 * g]; o.y += acc[ib][4 * g + 1]; o.z += acc[ib][4 * g + 2]; o.w += acc[ib][4 * g + 3];
-        *p = o;
-      }
-    }
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[ib][v] = 0.f;
+constexpr int kFragsPerW = 4 * 8 * 64;   // uint4 fragments of one 128 x 128 weight
+
+__device__ __forceinline__ void stage_weights(uint4* lds, const uint4* w0, const uint4* w1, const uint4* w2) {
+  for (int i = threadIdx.x; i < kFragsPerW; i += blockDim.x) {
+    lds[i] = w0[i];
+    lds[kFragsPerW + i] = w1[i];
+    lds[2 * kFragsPerW + i] = w2[i];
   }
+  __syncthreads();
 }
 
-// Temporal self-attention, backward.  One wavefront (= one workgroup) walks a contiguous range
-// of 2-vertex tiles.  Per tile it recomputes P, Q, K, V (Q, K also in column layout), then per
-// head the score block in both orientations: "query-major" (lane = query row, registers = key
-// steps) gives the softmax statistics, delta = sum_r p dp and dS for dQ; "key-major" (lane = key
-// row, registers = query steps; statistics of the query rows come through LDS) gives p and dS
-// for dV and dK.  dQ, dK, dV land in row layout, are stored (bf16) for the weight-gradient
-// kernel and feed, as B operands, the products with the transposed weights that give dP.
-// dU = dP * ELU'(U); the column sums of dP per snapshot (gradient of the position table) are
-// kept in registers and flushed to the wave's own slot when the window start changes.
-__global__ __launch_bounds__(64) void k_temporal_bwd(TemporalBwdArgs a) {
-  __shared__ float sh[2][32];
-  const int lane = threadIdx.x;
-  const int hh = lane >> 5, f = lane & 31, n = lane & 31;
-  const int64_t per = (a.n_tiles + a.n_waves - 1) / a.n_waves;
-  const int64_t tile0 = (int64_t)blockIdx.x * per, tile1 = min(a.n_tiles, tile0 + per);
-  floatx16 dpos[4] = {};
-  int cur_tlo = -1;
+// Temporal self-attention, backward, first half: dQ, dK, dV (and the loss).  The workgroup stages
+// W_q, W_k, W_v in LDS; each of its waves then walks 2-vertex tiles with a grid stride.  Per tile
+// it recomputes P, Q, K, V (Q, K also in column layout), then per head the score block in both
+// orientations: "query-major" (lane = query row, registers = key steps) gives the softmax
+// statistics, delta = sum_r p dp and dS for dQ; "key-major" (lane = key row, registers = query
+// steps; the statistics of the query rows are fetched from their lanes) gives p and dS for dV
+// and dK.  All operands are hi + lo pairs.  dQ, dK, dV land in row layout and are stored (bf16).
+__global__ __launch_bounds__(256) void k_temporal_bwd(TemporalBwdArgs a) {
+  extern __shared__ uint4 wlds[];
+  stage_weights(wlds, a.Wq, a.Wk, a.Wv);
+  const int lane = threadIdx.x & 63, nw = blockDim.x >> 6, wave = threadIdx.x >> 6;
+  const int hh = lane >> 5, f = lane & 31;
   float sq = 0.f;
   const bf16x8 zero8 = {};
   const bf16x8 sel0 = sel_frag(0, lane), sel1 = sel_frag(1, lane);
-  float* slot = a.dpos_partial + (int64_t)blockIdx.x * a.T * kS;
-  for (int64_t tile = tile0; tile < tile1; ++tile) {
+  for (int64_t tile = (int64_t)blockIdx.x * nw + wave; tile < a.n_tiles; tile += (int64_t)gridDim.x * nw) {
     const TileRow r = tile_row(a.chunks, a.n_chunks, a.tile_ptr, tile, a.N, lane);
-    if (r.t_lo != cur_tlo) {
-      if (cur_tlo >= 0) flush_dpos(slot, cur_tlo, a.T, lane, dpos);
-      cur_tlo = r.t_lo;
-    }
     bf16x8 pf[8], pl[8];
     load_p_frags<true>(a.U, a.pos, r, hh, pf, pl);
-    floatx16 dP[4] = {};
 #pragma unroll 1
     for (int jb = 0; jb < 4; ++jb) {
       floatx16 q = {}, k = {}, v = {}, qt = {}, kt = {}, dyt = {};
 #pragma unroll
       for (int kb = 0; kb < 8; ++kb) {
         const int fi = (jb * 8 + kb) * 64 + lane;
-        const bf16x8 wq = as_frag(a.Wq[fi]), wk = as_frag(a.Wk[fi]), wv = as_frag(a.Wv[fi]);
+        const bf16x8 wq = as_frag(wlds[fi]), wk = as_frag(wlds[kFragsPerW + fi]), wv = as_frag(wlds[2 * kFragsPerW + fi]);
         q = mfma2b(wq, pf[kb], pl[kb], q);
         k = mfma2b(wk, pf[kb], pl[kb], k);
         v = mfma2b(wv, pf[kb], pl[kb], v);
@@ -183,11 +160,7 @@ __global__ __launch_bounds__(64) void k_temporal_bwd(TemporalBwdArgs a) {
         delta += __shfl_xor(delta, 32);
 #pragma unroll
         for (int p = 0; p < 8; ++p) dst[p] = 0.25f * pr[p] * (dst[p] - delta);
-        if (hh == 0) {
-          sh[0][n] = mx + __logf(sum);
-          sh[1][n] = delta;
-        }
-        __syncthreads();
+        const float my_lse = mx + __logf(sum);
         floatx16 s2 = {}, dp2 = {};
         s2 = mfma3(qh, ql, kh, kl, s2);         // [query row][key row]
         dp2 = mfma3(dyh, dyl, vh, vl, dp2);
@@ -195,12 +168,11 @@ __global__ __launch_bounds__(64) void k_temporal_bwd(TemporalBwdArgs a) {
 #pragma unroll
         for (int p = 0; p < 8; ++p) {
           const int sq_ = 8 * (p >> 2) + 4 * hh + (p & 3);    // query step of this register
-          const float lse = sh[0][16 * r.a + sq_], dl = sh[1][16 * r.a + sq_];
+          const float lse = __shfl(my_lse, 16 * r.a + sq_), dl = __shfl(delta, 16 * r.a + sq_);
           const float x = 0.25f * (r.a ? s2[8 + p] : s2[p]);
           p2[p] = r.s <= sq_ ? __expf(x - lse) : 0.f;
           ds2[p] = 0.25f * p2[p] * ((r.a ? dp2[8 + p] : dp2[p]) - dl);
         }
-        __syncthreads();
         bf16x8 dsth, dstl, ds2h, ds2l, p2h, p2l;
         split8(dst, dsth, dstl);
         split8(ds2, ds2h, ds2l);
@@ -227,28 +199,98 @@ __global__ __launch_bounds__(64) void k_temporal_bwd(TemporalBwdArgs a) {
           *reinterpret_cast<uint2*>(a.dV + o) = pack4(dv[4 * g], dv[4 * g + 1], dv[4 * g + 2], dv[4 * g + 3]);
         }
       }
+    }
+  }
 #pragma unroll
-      for (int c = 0; c < 2; ++c) {
-        const int ks = 2 * jb + c;
-        bf16x8 bqh, bql, bkh, bkl, bvh, bvl;
-        split8v(dq, 8 * c, bqh, bql);
-        split8v(dk, 8 * c, bkh, bkl);
-        split8v(dv, 8 * c, bvh, bvl);
+  for (int o = 32; o > 0; o >>= 1) sq += __shfl_xor(sq, o);
+  if (lane == 0) a.loss_partial[blockIdx.x * nw + wave] = sq;
+}
+
+// Temporal self-attention, backward, second half: dP = dQ W_q + dK W_k + dV W_v from the stored
+// gradients, dU = dP * ELU'(U), and the gradient of the position table (column sums of dP per
+// snapshot).  Rows are the covered vertices of the snapshots in use, 32 per tile; the transposed
+// weights are staged in LDS; dQ/dK/dV row fragments are B operands as they come from memory.
+// Every wave sums dP over its tiles in registers (lane = row slot) and, when the snapshot
+// changes, adds the 32 row slots and writes the sums to its own slot of the scratch buffer.
+struct TemporalBwd2Args {
+  const int32_t* used_t; int32_t n_used; int64_t N; int32_t T;
+  const int32_t* owner;
+  const float* U;
+  const uint4 *WqT, *WkT, *WvT;
+  const uint16_t *dQ, *dK, *dV;
+  uint16_t* dU;
+  float* dpos_partial;   // [gridDim.x * waves per block][T][128], zero on entry
+};
+
+__device__ __forceinline__ void flush_dpos(float* slot, int t, int lane, floatx16* acc) {
+  const int n = lane & 31, hh = lane >> 5;
 #pragma unroll
-        for (int ib = 0; ib < 4; ++ib) {
-          const int fi = (ib * 8 + ks) * 64 + lane;
-          dP[ib] = mfma2b(as_frag(a.WqT[fi]), bqh, bql, dP[ib]);
-          dP[ib] = mfma2b(as_frag(a.WkT[fi]), bkh, bkl, dP[ib]);
-          dP[ib] = mfma2b(as_frag(a.WvT[fi]), bvh, bvl, dP[ib]);
-        }
+  for (int ib = 0; ib < 4; ++ib) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      float x = acc[ib][v];
+      x += __shfl_xor(x, 1); x += __shfl_xor(x, 2); x += __shfl_xor(x, 4); x += __shfl_xor(x, 8); x += __shfl_xor(x, 16);
+      acc[ib][v] = x;
+    }
+    if (n == 0) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float4* p = reinterpret_cast<float4*>(slot + (int64_t)t * kS + ib * 32 + 8 * g + 4 * hh);
+        float4 o = *p;
+        o.x += acc[ib][4 * g]; o.y += acc[ib][4 * g + 1]; o.z += acc[ib][4 * g + 2]; o.w += acc[ib][4 * g + 3];
+        *p = o;
+      }
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[ib][v] = 0.f;
+  }
+}
+
+__global__ __launch_bounds__(512) void k_temporal_bwd2(TemporalBwd2Args a) {
+  extern __shared__ uint4 wlds[];
+  stage_weights(wlds, a.WqT, a.WkT, a.WvT);
+  const int lane = threadIdx.x & 63, nw = blockDim.x >> 6, wave = threadIdx.x >> 6;
+  const int n = lane & 31, hh = lane >> 5;
+  const int64_t tiles_per_t = (a.N + 31) / 32, n_tiles = tiles_per_t * a.n_used;
+  const int64_t gw = (int64_t)blockIdx.x * nw + wave, n_gw = (int64_t)gridDim.x * nw;
+  const int64_t per = (n_tiles + n_gw - 1) / n_gw;
+  const int64_t tile0 = gw * per, tile1 = min(n_tiles, tile0 + per);
+  float* slot = a.dpos_partial + gw * a.T * kS;
+  floatx16 dpos[4] = {};
+  int cur_t = -1;
+  for (int64_t tile = tile0; tile < tile1; ++tile) {
+    const int32_t t = a.used_t[tile / tiles_per_t];
+    if (t != cur_t) {
+      if (cur_t >= 0) flush_dpos(slot, cur_t, lane, dpos);
+      cur_t = t;
+    }
+    const int64_t v = (tile % tiles_per_t) * 32 + n;
+    const bool valid = v < a.N;
+    const int64_t row = (int64_t)t * a.N + (valid ? v : a.N - 1);
+    const bool ok = valid && a.owner[row] >= 0;
+    floatx16 dP[4] = {};
+#pragma unroll 2
+    for (int ks = 0; ks < 8; ++ks) {
+      uint4 uq = make_uint4(0, 0, 0, 0), uk = uq, uv = uq;
+      if (ok) {
+        uq = *reinterpret_cast<const uint4*>(a.dQ + row * kS + ks * 16 + 8 * hh);
+        uk = *reinterpret_cast<const uint4*>(a.dK + row * kS + ks * 16 + 8 * hh);
+        uv = *reinterpret_cast<const uint4*>(a.dV + row * kS + ks * 16 + 8 * hh);
+      }
+#pragma unroll
+      for (int ib = 0; ib < 4; ++ib) {
+        const int fi = (ib * 8 + ks) * 64 + lane;
+        dP[ib] = mfma(as_frag(wlds[fi]), as_frag(uq), dP[ib]);
+        dP[ib] = mfma(as_frag(wlds[kFragsPerW + fi]), as_frag(uk), dP[ib]);
+        dP[ib] = mfma(as_frag(wlds[2 * kFragsPerW + fi]), as_frag(uv), dP[ib]);
       }
     }
 #pragma unroll
     for (int ib = 0; ib < 4; ++ib) {
-      if (r.valid) {
+      if (ok) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const int64_t o = r.row * kS + ib * 32 + 8 * g + 4 * hh;
+          const int64_t o = row * kS + ib * 32 + 8 * g + 4 * hh;
           const float4 u = *reinterpret_cast<const float4*>(a.U + o);
           *reinterpret_cast<uint2*>(a.dU + o) = pack4(dP[ib][4 * g] * delu(u.x), dP[ib][4 * g + 1] * delu(u.y),
                                                      dP[ib][4 * g + 2] * delu(u.z), dP[ib][4 * g + 3] * delu(u.w));
@@ -257,10 +299,7 @@ __global__ __launch_bounds__(64) void k_temporal_bwd(TemporalBwdArgs a) {
       dpos[ib] += dP[ib];
     }
   }
-  if (cur_tlo >= 0) flush_dpos(slot, cur_tlo, a.T, lane, dpos);
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) sq += __shfl_xor(sq, o);
-  if (lane == 0) a.loss_partial[blockIdx.x] = sq;
+  if (cur_t >= 0) flush_dpos(slot, cur_t, lane, dpos);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -364,14 +403,25 @@ __global__ __launch_bounds__(256) void k_dw_bf16(DwBf16Args a) {
   }
 }
 
-// out[e] = scale * sum over slots (ascending) of partial[slot * stride + e]
-__global__ void k_reduce_slots(const float* partial, int64_t n_slots, int64_t stride, int64_t n_elem, float scale,
-                               float* out) {
-  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= n_elem) return;
+// out[e] = scale * sum over slots of partial[slot * stride + e].  A block of 1024 threads covers 64
+// elements x 16 slot groups (group g adds slots g, g+16, ... in ascending order); the 16 group
+// sums are then added in group order, so the result does not depend on the launch.
+__global__ __launch_bounds__(1024) void k_reduce_slots(const float* partial, int64_t n_slots, int64_t stride,
+                                                       int64_t n_elem, float scale, float* out) {
+  __shared__ float sh[16][64];
+  const int el = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  const int64_t e = (int64_t)blockIdx.x * 64 + el;
   float s = 0.f;
-  for (int64_t k = 0; k < n_slots; ++k) s += partial[k * stride + e];
-  out[e] = scale * s;
+  if (e < n_elem)
+    for (int64_t k = grp; k < n_slots; k += 16) s += partial[k * stride + e];
+  sh[grp][el] = s;
+  __syncthreads();
+  if (grp == 0 && e < n_elem) {
+    float t = 0.f;
+#pragma unroll
+    for (int g = 0; g < 16; ++g) t += sh[g][el];
+    out[e] = scale * t;
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -379,10 +429,18 @@ __global__ void k_reduce_slots(const float* partial, int64_t n_slots, int64_t st
 // d s_dst_i^h = sum_j dpre_ij^h,  dpre = alpha (du_i^h . z_j^h - c_i^h) LeakyReLU'(e_ij^h).
 // Lane = (neighbour slot lane/8, head lane%8): eight neighbours at a time, each lane reads its
 // head's 32-byte slice of the neighbour's z row and does the 16-dim dot product on its own.
+// Rows longer than long_nnz are cut into parts (one wavefront each) whose sums a merge kernel
+// adds in part order.
+constexpr int kLongRec = 144;    // floats per scratch record of a part of a split row (forward, row pass)
+constexpr int kColsRec = 272;    // same, reverse-edge pass
+
 struct GatBwdRowsArgs {
   GraphDev g;
   const Segment* segs;
   const int32_t* work; int64_t n_work;
+  const int32_t* work_long; int64_t n_long;
+  int32_t long_nnz, part_nnz;
+  float* long_partial;
   const uint16_t* zX; const uint16_t* zC;
   const float* sX; const float* sC;
   const float* U; const uint16_t* dU;
@@ -395,60 +453,106 @@ __device__ __forceinline__ void load16(const uint16_t* p, float* x) {
   unpack8(reinterpret_cast<const uint4*>(p)[1], x + 8);
 }
 
+// du_i^h (16 values) and c_i^h for the lane's head
+__device__ __forceinline__ float load_du_c(const GatBwdRowsArgs& a, int64_t row, int h, float* du) {
+  load16(a.dU + row * kS + 16 * h, du);
+  float c = 0.f;
+#pragma unroll
+  for (int d4 = 0; d4 < 4; ++d4) {
+    const float4 x = *reinterpret_cast<const float4*>(a.U + row * kS + 16 * h + 4 * d4);
+    c += du[4 * d4] * x.x + du[4 * d4 + 1] * x.y + du[4 * d4 + 2] * x.z + du[4 * d4 + 3] * x.w;
+  }
+  return c;
+}
+
+// this lane's share (its neighbour slot) of sum_j dpre_ij^h over the non-zeros [e0, e1) of row i
+__device__ __forceinline__ float gat_bwd_row_range(const GatBwdRowsArgs& a, const Segment& s, const int32_t* col,
+                                                   int64_t base, const float* du, float c, float sd, float lse,
+                                                   int64_t e0, int64_t e1, int lane) {
+  const int slot = lane >> 3, h = lane & 7;
+  float dsd = 0.f;
+  for (int64_t eb = e0; eb < e1; eb += 64) {
+    const int cnt = (int)min((int64_t)64, e1 - eb);
+    const int32_t jl = lane < cnt ? col[eb + lane] : 0;
+    for (int q0 = 0; q0 < cnt; q0 += 8) {
+      const int32_t j = __shfl(jl, q0 + slot);
+      if (q0 + slot < cnt) {
+        const bool in = j >= s.v_lo && j < s.v_hi;
+        float z[16];
+        load16((in ? a.zX : a.zC) + (base + j) * kS + 16 * h, z);
+        const float ss = in ? a.sX[(base + j) * 16 + h] : a.sC[(base + j) * 8 + h];
+        const float e = sd + ss;
+        const float al = __expf(lrelu(e) - lse);
+        float da = 0.f;
+#pragma unroll
+        for (int d = 0; d < 16; ++d) da += du[d] * z[d];
+        dsd += al * (da - c) * (e > 0.f ? 1.f : kSlope);
+      }
+    }
+  }
+  dsd += __shfl_xor(dsd, 8);
+  dsd += __shfl_xor(dsd, 16);
+  dsd += __shfl_xor(dsd, 32);
+  return dsd;
+}
+
 __global__ __launch_bounds__(256) void k_gat_bwd_rows(GatBwdRowsArgs a) {
   const int lane = threadIdx.x & 63;
   const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (item >= a.n_work) return;
   const int32_t si = a.work[3 * item], r0 = a.work[3 * item + 1], nr = a.work[3 * item + 2];
   const Segment s = a.segs[si];
-  const int64_t N = a.g.N;
   const int64_t* rowptr = a.g.rowptr[s.t];
   const int32_t* col = a.g.colidx[s.t];
-  const int64_t base = (int64_t)s.t * N;
+  const int64_t base = (int64_t)s.t * a.g.N;
   const int slot = lane >> 3, h = lane & 7;
   for (int rr = 0; rr < nr; ++rr) {
     const int64_t i = s.v_lo + r0 + rr;
     const int64_t e0 = rowptr[i], e1 = rowptr[i + 1];
-    float du[16], u[16];
-    load16(a.dU + (base + i) * kS + 16 * h, du);
-#pragma unroll
-    for (int d4 = 0; d4 < 4; ++d4) {
-      const float4 x = *reinterpret_cast<const float4*>(a.U + (base + i) * kS + 16 * h + 4 * d4);
-      u[4 * d4] = x.x; u[4 * d4 + 1] = x.y; u[4 * d4 + 2] = x.z; u[4 * d4 + 3] = x.w;
-    }
-    float c = 0.f;
-#pragma unroll
-    for (int d = 0; d < 16; ++d) c += du[d] * u[d];
-    const float sd = a.sX[(base + i) * 16 + 8 + h];
-    const float lse = a.lse[(base + i) * 8 + h];
-    float dsd = 0.f;
-    for (int64_t eb = e0; eb < e1; eb += 64) {
-      const int cnt = (int)min((int64_t)64, e1 - eb);
-      const int32_t jl = lane < cnt ? col[eb + lane] : 0;
-      for (int q0 = 0; q0 < cnt; q0 += 8) {
-        const int32_t j = __shfl(jl, q0 + slot);
-        if (q0 + slot < cnt) {
-          const bool in = j >= s.v_lo && j < s.v_hi;
-          float z[16];
-          load16((in ? a.zX : a.zC) + (base + j) * kS + 16 * h, z);
-          const float ss = in ? a.sX[(base + j) * 16 + h] : a.sC[(base + j) * 8 + h];
-          const float e = sd + ss;
-          const float al = __expf(lrelu(e) - lse);
-          float da = 0.f;
-#pragma unroll
-          for (int d = 0; d < 16; ++d) da += du[d] * z[d];
-          dsd += al * (da - c) * (e > 0.f ? 1.f : kSlope);
-        }
-      }
-    }
-    dsd += __shfl_xor(dsd, 8);
-    dsd += __shfl_xor(dsd, 16);
-    dsd += __shfl_xor(dsd, 32);
+    if (e1 - e0 > a.long_nnz) continue;
+    float du[16];
+    const float c = load_du_c(a, base + i, h, du);
+    const float dsd = gat_bwd_row_range(a, s, col, base, du, c, a.sX[(base + i) * 16 + 8 + h],
+                                        a.lse[(base + i) * 8 + h], e0, e1, lane);
     if (slot == 0) {
       a.st2[(base + i) * 16 + h] = dsd;
       a.st2[(base + i) * 16 + 8 + h] = c;
     }
   }
+}
+
+__global__ __launch_bounds__(256) void k_gat_bwd_rows_long(GatBwdRowsArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (item >= a.n_long) return;
+  const int32_t* w = a.work_long + 4 * item;
+  const Segment s = a.segs[w[0]];
+  const int64_t i = s.v_lo + w[1];
+  const int64_t* rowptr = a.g.rowptr[s.t];
+  const int64_t base = (int64_t)s.t * a.g.N;
+  const int slot = lane >> 3, h = lane & 7;
+  const int64_t e0 = rowptr[i] + (int64_t)w[2] * a.part_nnz, e1 = min(rowptr[i + 1], e0 + a.part_nnz);
+  float du[16];
+  const float c = load_du_c(a, base + i, h, du);
+  const float dsd = gat_bwd_row_range(a, s, a.g.colidx[s.t], base, du, c, a.sX[(base + i) * 16 + 8 + h],
+                                      a.lse[(base + i) * 8 + h], e0, e1, lane);
+  if (slot == 0) {
+    a.long_partial[item * kLongRec + h] = dsd;
+    if (w[2] == 0) a.st2[(base + i) * 16 + 8 + h] = c;
+  }
+}
+
+__global__ void k_gat_bwd_rows_merge(GatBwdRowsArgs a) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t item = idx >> 3;
+  const int h = (int)(idx & 7);
+  if (item >= a.n_long) return;
+  const int32_t* w = a.work_long + 4 * item;
+  if (w[2] != 0) return;
+  const Segment s = a.segs[w[0]];
+  float dsd = 0.f;
+  for (int p = 0; p < w[3]; ++p) dsd += a.long_partial[(item + p) * kLongRec + h];
+  a.st2[((int64_t)s.t * a.g.N + s.v_lo + w[1]) * 16 + h] = dsd;
 }
 
 // Graph attention backward, reverse-edge pass: for every vertex j of every snapshot in use, the
@@ -457,20 +561,108 @@ __global__ __launch_bounds__(256) void k_gat_bwd_rows(GatBwdRowsArgs a) {
 // row (the adjacency is symmetric):
 //   dz_j += alpha_ij du_i,   d s_src_j^h += dpre_ij^h,
 // then  dzX_j += d s_dst_j a_dst + d s_srcX_j a_src,  dzC_j += d s_srcC_j a_src, and the gradients
-// of a_src, a_dst are accumulated per wave.  Lanes span the 128 features (two per lane).
+// of a_src, a_dst are accumulated per wave.  Lanes span the 128 features (two per lane).  Long
+// rows are split as in the other passes (list of (snapshot, vertex, part, parts)).
 struct GatBwdColsArgs {
   GraphDev g;
   const int32_t* used_t; int32_t n_used;
   const int32_t* owner;
+  const int32_t* cols_long; int64_t n_cols_long;
+  int32_t long_nnz, part_nnz;
+  float* long_partial;
   const uint16_t* zX; const uint16_t* zC;
   const float* sX; const float* sC;
   const uint16_t* dU;
   const float* lse; const float* st2;
   const float* a_src; const float* a_dst;
   uint16_t* dzX; uint16_t* dzC;
-  float* da_partial;    // [n_waves][2][128]: d a_src, d a_dst
+  float* da_partial;    // [n_waves + n_cols_long][2][128]: d a_src, d a_dst
   int32_t n_waves;
 };
+
+struct ColOwn {      // what a wave keeps about its own vertex j
+  int32_t oj;
+  float zx0, zx1, zc0, zc1, ssx, ssc;
+};
+struct ColAcc { float ax0, ax1, ac0, ac1, dsx, dsc; };
+
+__device__ __forceinline__ ColOwn col_own(const GatBwdColsArgs& a, int64_t row, int lane, int head) {
+  ColOwn o;
+  o.oj = a.owner[row];
+  const uint32_t zc = *reinterpret_cast<const uint32_t*>(a.zC + row * kS + 2 * lane);
+  const uint32_t zx = o.oj >= 0 ? *reinterpret_cast<const uint32_t*>(a.zX + row * kS + 2 * lane) : 0u;
+  o.zx0 = bf_lo(zx); o.zx1 = bf_hi(zx); o.zc0 = bf_lo(zc); o.zc1 = bf_hi(zc);
+  o.ssx = o.oj >= 0 ? a.sX[row * 16 + head] : 0.f;
+  o.ssc = a.sC[row * 8 + head];
+  return o;
+}
+
+__device__ __forceinline__ ColAcc gat_bwd_col_range(const GatBwdColsArgs& a, const int32_t* col, int64_t base,
+                                                    const ColOwn& o, int64_t e0, int64_t e1, int lane, int head) {
+  ColAcc r{0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int64_t eb = e0; eb < e1; eb += 64) {
+    const int cnt = (int)min((int64_t)64, e1 - eb);
+    const int32_t il = lane < cnt ? col[eb + lane] : 0;
+    const int32_t ol = lane < cnt ? a.owner[base + il] : -1;
+    for (int q0 = 0; q0 < cnt; q0 += 8) {
+      uint32_t dv[8];
+      float sd[8], ls[8], cc[8];
+      int same[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        same[q] = -1;   // -1: not a covered row, skip
+        dv[q] = 0u; sd[q] = 0.f; ls[q] = 0.f; cc[q] = 0.f;
+        if (q0 + q < cnt) {
+          const int32_t oi = __builtin_amdgcn_readlane(ol, q0 + q);
+          if (oi >= 0) {
+            const int64_t ri = base + __builtin_amdgcn_readlane(il, q0 + q);
+            same[q] = oi == o.oj ? 1 : 0;
+            dv[q] = *reinterpret_cast<const uint32_t*>(a.dU + ri * kS + 2 * lane);
+            sd[q] = a.sX[ri * 16 + 8 + head];
+            ls[q] = a.lse[ri * 8 + head];
+            cc[q] = a.st2[ri * 16 + 8 + head];
+          }
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        if (same[q] < 0) continue;      // wave-uniform
+        const bool sm = same[q] != 0;
+        const float d0 = bf_lo(dv[q]), d1 = bf_hi(dv[q]);
+        const float e = sd[q] + (sm ? o.ssx : o.ssc);
+        const float al = __expf(lrelu(e) - ls[q]);
+        float da = d0 * (sm ? o.zx0 : o.zc0) + d1 * (sm ? o.zx1 : o.zc1);
+        da += __shfl_xor(da, 1);
+        da += __shfl_xor(da, 2);
+        da += __shfl_xor(da, 4);
+        const float dpre = al * (da - cc[q]) * (e > 0.f ? 1.f : kSlope);
+        if (sm) { r.ax0 += al * d0; r.ax1 += al * d1; r.dsx += dpre; }
+        else { r.ac0 += al * d0; r.ac1 += al * d1; r.dsc += dpre; }
+      }
+    }
+  }
+  return r;
+}
+
+struct AttVec { float as0, as1, ad0, ad1, gas0, gas1, gad0, gad1; };
+
+__device__ __forceinline__ void gat_bwd_col_finish(const GatBwdColsArgs& a, int64_t row, const ColOwn& o,
+                                                   const ColAcc& r, AttVec& v, int lane, int head) {
+  if (o.oj >= 0) {
+    const float dsd = a.st2[row * 16 + head];
+    *reinterpret_cast<uint32_t*>(a.dzX + row * kS + 2 * lane) =
+        pack2(r.ax0 + dsd * v.ad0 + r.dsx * v.as0, r.ax1 + dsd * v.ad1 + r.dsx * v.as1);
+    v.gad0 += dsd * o.zx0; v.gad1 += dsd * o.zx1;
+    v.gas0 += r.dsx * o.zx0; v.gas1 += r.dsx * o.zx1;
+  }
+  *reinterpret_cast<uint32_t*>(a.dzC + row * kS + 2 * lane) = pack2(r.ac0 + r.dsc * v.as0, r.ac1 + r.dsc * v.as1);
+  v.gas0 += r.dsc * o.zc0; v.gas1 += r.dsc * o.zc1;
+}
+
+__device__ __forceinline__ void att_store(float* slot, const AttVec& v, int lane) {
+  slot[2 * lane] = v.gas0; slot[2 * lane + 1] = v.gas1;
+  slot[kS + 2 * lane] = v.gad0; slot[kS + 2 * lane + 1] = v.gad1;
+}
 
 __global__ __launch_bounds__(256) void k_gat_bwd_cols(GatBwdColsArgs a) {
   const int lane = threadIdx.x & 63;
@@ -478,9 +670,7 @@ __global__ __launch_bounds__(256) void k_gat_bwd_cols(GatBwdColsArgs a) {
   const int64_t N = a.g.N;
   const int64_t groups_per_t = (N + 15) / 16, n_items = groups_per_t * a.n_used;
   const int head = lane >> 3;
-  const float as0 = a.a_src[2 * lane], as1 = a.a_src[2 * lane + 1];
-  const float ad0 = a.a_dst[2 * lane], ad1 = a.a_dst[2 * lane + 1];
-  float gas0 = 0.f, gas1 = 0.f, gad0 = 0.f, gad1 = 0.f;
+  AttVec v{a.a_src[2 * lane], a.a_src[2 * lane + 1], a.a_dst[2 * lane], a.a_dst[2 * lane + 1], 0.f, 0.f, 0.f, 0.f};
   for (int64_t item = wave; item < n_items; item += a.n_waves) {
     const int32_t t = a.used_t[item / groups_per_t];
     const int64_t j0 = (item % groups_per_t) * 16;
@@ -490,70 +680,74 @@ __global__ __launch_bounds__(256) void k_gat_bwd_cols(GatBwdColsArgs a) {
     const int nr = (int)min((int64_t)16, N - j0);
     for (int rr = 0; rr < nr; ++rr) {
       const int64_t j = j0 + rr;
-      const int32_t oj = a.owner[base + j];
-      const uint32_t zc = *reinterpret_cast<const uint32_t*>(a.zC + (base + j) * kS + 2 * lane);
-      const uint32_t zx = oj >= 0 ? *reinterpret_cast<const uint32_t*>(a.zX + (base + j) * kS + 2 * lane) : 0u;
-      const float zx0 = bf_lo(zx), zx1 = bf_hi(zx), zc0 = bf_lo(zc), zc1 = bf_hi(zc);
-      const float ssx = oj >= 0 ? a.sX[(base + j) * 16 + head] : 0.f;
-      const float ssc = a.sC[(base + j) * 8 + head];
-      float ax0 = 0.f, ax1 = 0.f, ac0 = 0.f, ac1 = 0.f, dsx = 0.f, dsc = 0.f;
       const int64_t e0 = rowptr[j], e1 = rowptr[j + 1];
-      for (int64_t eb = e0; eb < e1; eb += 64) {
-        const int cnt = (int)min((int64_t)64, e1 - eb);
-        const int32_t il = lane < cnt ? col[eb + lane] : 0;
-        const int32_t ol = lane < cnt ? a.owner[base + il] : -1;
-        for (int q0 = 0; q0 < cnt; q0 += 8) {
-          uint32_t dv[8];
-          float sd[8], ls[8], cc[8];
-          int same[8];
-#pragma unroll
-          for (int q = 0; q < 8; ++q) {
-            same[q] = -1;   // -1: skip
-            dv[q] = 0u; sd[q] = 0.f; ls[q] = 0.f; cc[q] = 0.f;
-            if (q0 + q < cnt) {
-              const int32_t oi = __builtin_amdgcn_readlane(ol, q0 + q);
-              if (oi >= 0) {
-                const int64_t ri = base + __builtin_amdgcn_readlane(il, q0 + q);
-                same[q] = oi == oj ? 1 : 0;
-                dv[q] = *reinterpret_cast<const uint32_t*>(a.dU + ri * kS + 2 * lane);
-                sd[q] = a.sX[ri * 16 + 8 + head];
-                ls[q] = a.lse[ri * 8 + head];
-                cc[q] = a.st2[ri * 16 + 8 + head];
-              }
-            }
-          }
-#pragma unroll
-          for (int q = 0; q < 8; ++q) {
-            if (same[q] < 0) continue;      // wave-uniform
-            const bool sm = same[q] != 0;
-            const float d0 = bf_lo(dv[q]), d1 = bf_hi(dv[q]);
-            const float e = sd[q] + (sm ? ssx : ssc);
-            const float al = __expf(lrelu(e) - ls[q]);
-            float da = d0 * (sm ? zx0 : zc0) + d1 * (sm ? zx1 : zc1);
-            da += __shfl_xor(da, 1);
-            da += __shfl_xor(da, 2);
-            da += __shfl_xor(da, 4);
-            const float dpre = al * (da - cc[q]) * (e > 0.f ? 1.f : kSlope);
-            if (sm) { ax0 += al * d0; ax1 += al * d1; dsx += dpre; }
-            else { ac0 += al * d0; ac1 += al * d1; dsc += dpre; }
-          }
-        }
-      }
-      if (oj >= 0) {
-        const float dsd = a.st2[(base + j) * 16 + head];
-        *reinterpret_cast<uint32_t*>(a.dzX + (base + j) * kS + 2 * lane) =
-            pack2(ax0 + dsd * ad0 + dsx * as0, ax1 + dsd * ad1 + dsx * as1);
-        gad0 += dsd * zx0; gad1 += dsd * zx1;
-        gas0 += dsx * zx0; gas1 += dsx * zx1;
-      }
-      *reinterpret_cast<uint32_t*>(a.dzC + (base + j) * kS + 2 * lane) = pack2(ac0 + dsc * as0, ac1 + dsc * as1);
-      gas0 += dsc * zc0; gas1 += dsc * zc1;
+      if (e1 - e0 > a.long_nnz) continue;
+      const ColOwn o = col_own(a, base + j, lane, head);
+      const ColAcc r = gat_bwd_col_range(a, col, base, o, e0, e1, lane, head);
+      gat_bwd_col_finish(a, base + j, o, r, v, lane, head);
     }
   }
-  if (wave < a.n_waves) {
-    float* o = a.da_partial + (int64_t)wave * 2 * kS;
-    o[2 * lane] = gas0; o[2 * lane + 1] = gas1;
-    o[kS + 2 * lane] = gad0; o[kS + 2 * lane + 1] = gad1;
+  att_store(a.da_partial + (int64_t)wave * 2 * kS, v, lane);
+}
+
+__global__ __launch_bounds__(256) void k_gat_bwd_cols_long(GatBwdColsArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (item >= a.n_cols_long) return;
+  const int32_t* w = a.cols_long + 4 * item;   // snapshot, vertex, part, parts
+  const int64_t base = (int64_t)w[0] * a.g.N, j = w[1];
+  const int head = lane >> 3;
+  const int64_t* rowptr = a.g.rowptr[w[0]];
+  const int64_t e0 = rowptr[j] + (int64_t)w[2] * a.part_nnz, e1 = min(rowptr[j + 1], e0 + a.part_nnz);
+  const ColOwn o = col_own(a, base + j, lane, head);
+  const ColAcc r = gat_bwd_col_range(a, a.g.colidx[w[0]], base, o, e0, e1, lane, head);
+  float* rec = a.long_partial + item * kColsRec;
+  *reinterpret_cast<float4*>(rec + 4 * lane) = make_float4(r.ax0, r.ax1, r.ac0, r.ac1);
+  if ((lane & 7) == 0) {
+    rec[256 + head] = r.dsx;
+    rec[264 + head] = r.dsc;
+  }
+}
+
+__global__ __launch_bounds__(256) void k_gat_bwd_cols_merge(GatBwdColsArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (item >= a.n_cols_long) return;
+  const int32_t* w = a.cols_long + 4 * item;
+  const int head = lane >> 3;
+  AttVec v{a.a_src[2 * lane], a.a_src[2 * lane + 1], a.a_dst[2 * lane], a.a_dst[2 * lane + 1], 0.f, 0.f, 0.f, 0.f};
+  if (w[2] == 0) {
+    const int64_t row = (int64_t)w[0] * a.g.N + w[1];
+    ColAcc r{0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int p = 0; p < w[3]; ++p) {
+      const float* rec = a.long_partial + (item + p) * kColsRec;
+      const float4 x = *reinterpret_cast<const float4*>(rec + 4 * lane);
+      r.ax0 += x.x; r.ax1 += x.y; r.ac0 += x.z; r.ac1 += x.w;
+      r.dsx += rec[256 + head];
+      r.dsc += rec[264 + head];
+    }
+    const ColOwn o = col_own(a, row, lane, head);
+    gat_bwd_col_finish(a, row, o, r, v, lane, head);
+  }
+  att_store(a.da_partial + ((int64_t)a.n_waves + item) * 2 * kS, v, lane);   // zeros for the other parts
+}
+
+// list of the split rows of the reverse-edge pass: count, then fill (the order of the rows in
+// the list is arbitrary; the parts of a row are consecutive)
+__global__ void k_cols_long(GraphDev g, const int32_t* used_t, int32_t n_used, int32_t long_nnz, int32_t part_nnz,
+                            int32_t* counter, int32_t* list) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= g.N * n_used) return;
+  const int32_t t = used_t[idx / g.N];
+  const int64_t v = idx % g.N;
+  const int64_t deg = g.rowptr[t][v + 1] - g.rowptr[t][v];
+  if (deg <= long_nnz) return;
+  const int32_t parts = (int32_t)((deg + part_nnz - 1) / part_nnz);
+  const int32_t at = atomicAdd(counter, parts);
+  if (!list) return;
+  for (int32_t p = 0; p < parts; ++p) {
+    list[4 * (at + p)] = t; list[4 * (at + p) + 1] = (int32_t)v;
+    list[4 * (at + p) + 2] = p; list[4 * (at + p) + 3] = parts;
   }
 }
 
@@ -567,7 +761,16 @@ constexpr int kColsBlocks = 1024;  // workgroups of the reverse-edge pass (4 slo
 
 // scratch layout: [weight-gradient slots | position-gradient slots | attention-vector slots]
 int64_t dysat_partial_elems(const DysatWs& ws) {
-  return (int64_t)kDwGroups * 3 * kS * kS + (int64_t)kTbwdWaves * ws.T * kS + (int64_t)kColsBlocks * 4 * 2 * kS;
+  return (int64_t)kDwGroups * 3 * kS * kS + (int64_t)kTbwdWaves * ws.T * kS +
+         ((int64_t)kColsBlocks * 4 + ws.n_cols_long) * 2 * kS;
+}
+int64_t dysat_long_partial_elems(const DysatWs& ws) {
+  return std::max<int64_t>(ws.n_long * kLongRec, ws.n_cols_long * kColsRec);
+}
+void dysat_cols_long(const GraphDev& g, const int32_t* used_t, int32_t n_used, int32_t long_nnz, int32_t part_nnz,
+                     int32_t* counter, int32_t* list, hipStream_t st) {
+  hipLaunchKernelGGL(k_cols_long, blocks_for(g.N * n_used, 256), 256, 0, st, g, used_t, n_used, long_nnz, part_nnz,
+                     counter, list);
 }
 int64_t dysat_loss_partial_elems(const DysatWs&) { return kTbwdWaves; }
 
@@ -577,30 +780,48 @@ void dysat_backward(const DysatWs& ws, const void* Y, int64_t ldy, const void* d
   float* dpos_slots = dw_slots + (int64_t)kDwGroups * 3 * kS * kS;
   float* da_slots = dpos_slots + (int64_t)kTbwdWaves * ws.T * kS;
   const int64_t count = ws.total_rows * kS;
-  const int n_tw = (int)std::min<int64_t>(kTbwdWaves, ws.n_tiles);
   const int64_t tiles32 = (ws.N + 31) / 32 * ws.n_used;
   const int groups = (int)std::min<int64_t>(kDwGroups, tiles32);
 
-  // (1) temporal attention
+  // (1) temporal attention: dQ, dK, dV (+ loss), then dP -> dU and the position-table gradient
+  const size_t lds = sizeof(uint4) * 3 * kFragsPerW;
+  {
+    static bool attr_set = false;   // dynamic LDS above 64 KB has to be allowed once per kernel
+    if (!attr_set) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_temporal_bwd), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds);
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_temporal_bwd2),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      attr_set = true;
+    }
+  }
+  const int grid_a = (int)std::min<int64_t>(256, (ws.n_tiles + 3) / 4);
+  const int grid_b = (int)std::min<int64_t>(kTbwdWaves / 8, (tiles32 + 7) / 8);
+  const int n_tw = grid_b * 8;
   hipLaunchKernelGGL(k_fill_f32, blocks_for((int64_t)n_tw * ws.T * kS, 256), 256, 0, st, dpos_slots, 0.f,
                      (int64_t)n_tw * ws.T * kS);
   if (ev) (void)hipEventRecord(ev[0], st);
   TemporalBwdArgs ta{};
   ta.chunks = ws.chunks; ta.n_chunks = ws.n_chunks; ta.tile_ptr = ws.tile_ptr; ta.n_tiles = ws.n_tiles;
   ta.N = ws.N; ta.T = ws.T; ta.U = ws.U; ta.pos = ws.P[DY_POS];
-  ta.Wq = ws.Wqp; ta.Wk = ws.Wkp; ta.Wv = ws.Wvp; ta.WqT = ws.WqT; ta.WkT = ws.WkT; ta.WvT = ws.WvT;
+  ta.Wq = ws.Wqp; ta.Wk = ws.Wkp; ta.Wv = ws.Wvp;
   ta.Y = static_cast<const uint16_t*>(Y); ta.ldy = ldy;
   ta.dY = static_cast<const uint16_t*>(dY); ta.lddy = lddy;
   ta.target = static_cast<const uint16_t*>(target); ta.ldt = ldt;
   ta.scale = 2.0f / (float)count;
-  ta.dU = ws.dU; ta.dQ = ws.dQ; ta.dK = ws.dK; ta.dV = ws.dV;
-  ta.dpos_partial = dpos_slots; ta.loss_partial = ws.loss_partial; ta.n_waves = n_tw;
-  hipLaunchKernelGGL(k_temporal_bwd, n_tw, 64, 0, st, ta);
-  hipLaunchKernelGGL(k_reduce_slots, blocks_for((int64_t)ws.T * kS, 256), 256, 0, st, dpos_slots, (int64_t)n_tw,
-                     (int64_t)ws.T * kS, (int64_t)ws.T * kS, 1.f, ws.G[DY_POS]);
+  ta.dQ = ws.dQ; ta.dK = ws.dK; ta.dV = ws.dV;
+  ta.loss_partial = ws.loss_partial;
+  hipLaunchKernelGGL(k_temporal_bwd, grid_a, 256, lds, st, ta);
   if (target && loss_out)
-    hipLaunchKernelGGL(k_reduce_slots, 1, 64, 0, st, ws.loss_partial, (int64_t)n_tw, (int64_t)1, (int64_t)1,
+    hipLaunchKernelGGL(k_reduce_slots, 1, 1024, 0, st, ws.loss_partial, (int64_t)grid_a * 4, (int64_t)1, (int64_t)1,
                        1.0f / (float)count, loss_out);
+  TemporalBwd2Args tb{};
+  tb.used_t = ws.used_t; tb.n_used = ws.n_used; tb.N = ws.N; tb.T = ws.T; tb.owner = ws.owner; tb.U = ws.U;
+  tb.WqT = ws.WqT; tb.WkT = ws.WkT; tb.WvT = ws.WvT; tb.dQ = ws.dQ; tb.dK = ws.dK; tb.dV = ws.dV;
+  tb.dU = ws.dU; tb.dpos_partial = dpos_slots;
+  hipLaunchKernelGGL(k_temporal_bwd2, grid_b, 512, lds, st, tb);
+  hipLaunchKernelGGL(k_reduce_slots, blocks_for((int64_t)ws.T * kS, 64), 1024, 0, st, dpos_slots, (int64_t)n_tw,
+                     (int64_t)ws.T * kS, (int64_t)ws.T * kS, 1.f, ws.G[DY_POS]);
   // (2) dW_q, dW_k, dW_v = sum over rows of d{q,k,v}^T P
   DwBf16Args da{};
   da.used_t = ws.used_t; da.n_used = ws.n_used; da.N = ws.N; da.owner = ws.owner; da.covered_only = 1;
@@ -609,7 +830,7 @@ void dysat_backward(const DysatWs& ws, const void* Y, int64_t ldy, const void* d
   da.partial = dw_slots; da.n_groups = groups;
   hipLaunchKernelGGL((k_dw_bf16<3, true>), groups, 256, 0, st, da);
   for (int gi = 0; gi < 3; ++gi)
-    hipLaunchKernelGGL(k_reduce_slots, blocks_for(kS * kS, 256), 256, 0, st, dw_slots + (int64_t)gi * kS * kS,
+    hipLaunchKernelGGL(k_reduce_slots, blocks_for(kS * kS, 64), 1024, 0, st, dw_slots + (int64_t)gi * kS * kS,
                        (int64_t)groups, (int64_t)3 * kS * kS, (int64_t)kS * kS, 1.f, ws.G[DY_WQ + gi]);
   if (ev) (void)hipEventRecord(ev[1], st);
   // (3) graph attention, row pass
@@ -617,7 +838,13 @@ void dysat_backward(const DysatWs& ws, const void* Y, int64_t ldy, const void* d
   ra.g = ws.g; ra.segs = ws.segs; ra.work = ws.work_short; ra.n_work = ws.n_short;
   ra.zX = ws.zX; ra.zC = ws.zC; ra.sX = ws.sX; ra.sC = ws.sC; ra.U = ws.U; ra.dU = ws.dU; ra.lse = ws.lse;
   ra.st2 = ws.st2;
+  ra.work_long = ws.work_long; ra.n_long = ws.n_long; ra.long_nnz = ws.long_nnz; ra.part_nnz = ws.part_nnz;
+  ra.long_partial = ws.long_partial;
   hipLaunchKernelGGL(k_gat_bwd_rows, blocks_for(ws.n_short, 4), 256, 0, st, ra);
+  if (ws.n_long > 0) {
+    hipLaunchKernelGGL(k_gat_bwd_rows_long, blocks_for(ws.n_long, 4), 256, 0, st, ra);
+    hipLaunchKernelGGL(k_gat_bwd_rows_merge, blocks_for(ws.n_long * 8, 256), 256, 0, st, ra);
+  }
   if (ev) (void)hipEventRecord(ev[2], st);
   // (4) reverse-edge pass
   const int64_t items = (ws.N + 15) / 16 * ws.n_used;
@@ -627,11 +854,17 @@ void dysat_backward(const DysatWs& ws, const void* Y, int64_t ldy, const void* d
   ca.zX = ws.zX; ca.zC = ws.zC; ca.sX = ws.sX; ca.sC = ws.sC; ca.dU = ws.dU; ca.lse = ws.lse; ca.st2 = ws.st2;
   ca.a_src = ws.P[DY_ASRC]; ca.a_dst = ws.P[DY_ADST];
   ca.dzX = ws.dzX; ca.dzC = ws.dzC; ca.da_partial = da_slots; ca.n_waves = cblocks * 4;
+  ca.cols_long = ws.cols_long; ca.n_cols_long = ws.n_cols_long; ca.long_nnz = ws.long_nnz; ca.part_nnz = ws.part_nnz;
+  ca.long_partial = ws.long_partial;
   hipLaunchKernelGGL(k_gat_bwd_cols, cblocks, 256, 0, st, ca);
-  hipLaunchKernelGGL(k_reduce_slots, 1, 128, 0, st, da_slots, (int64_t)cblocks * 4, (int64_t)2 * kS, (int64_t)kS, 1.f,
-                     ws.G[DY_ASRC]);
-  hipLaunchKernelGGL(k_reduce_slots, 1, 128, 0, st, da_slots + kS, (int64_t)cblocks * 4, (int64_t)2 * kS, (int64_t)kS,
-                     1.f, ws.G[DY_ADST]);
+  if (ws.n_cols_long > 0) {
+    hipLaunchKernelGGL(k_gat_bwd_cols_long, blocks_for(ws.n_cols_long, 4), 256, 0, st, ca);
+    hipLaunchKernelGGL(k_gat_bwd_cols_merge, blocks_for(ws.n_cols_long, 4), 256, 0, st, ca);
+  }
+  const int64_t da_n = (int64_t)cblocks * 4 + ws.n_cols_long;
+  hipLaunchKernelGGL(k_reduce_slots, 2, 1024, 0, st, da_slots, da_n, (int64_t)2 * kS, (int64_t)kS, 1.f, ws.G[DY_ASRC]);
+  hipLaunchKernelGGL(k_reduce_slots, 2, 1024, 0, st, da_slots + kS, da_n, (int64_t)2 * kS, (int64_t)kS, 1.f,
+                     ws.G[DY_ADST]);
   // (5) dW = sum over covered rows of dzX^T x  +  sum over all rows of dzC^T c
   DwBf16Args dx = da;
   dx.A = static_cast<const uint16_t*>(ws.X); dx.lda = ws.ldx; dx.Uf = nullptr; dx.covered_only = 1;
@@ -641,7 +874,7 @@ void dysat_backward(const DysatWs& ws, const void* Y, int64_t ldy, const void* d
   dc.A = static_cast<const uint16_t*>(ws.C); dc.lda = ws.ldc; dc.covered_only = 0;
   dc.G[0] = ws.dzC; dc.partial = dw_slots + (int64_t)groups * kS * kS;
   hipLaunchKernelGGL((k_dw_bf16<1, false>), groups, 256, 0, st, dc);
-  hipLaunchKernelGGL(k_reduce_slots, blocks_for(kS * kS, 256), 256, 0, st, dw_slots, (int64_t)2 * groups,
+  hipLaunchKernelGGL(k_reduce_slots, blocks_for(kS * kS, 64), 1024, 0, st, dw_slots, (int64_t)2 * groups,
                      (int64_t)kS * kS, (int64_t)kS * kS, 1.f, ws.G[DY_W]);
   if (ev) (void)hipEventRecord(ev[3], st);
 }

@@ -217,9 +217,19 @@ struct DysatWs {
   float* partial;            // scratch for the parameter-gradient reductions
   int64_t partial_elems;
   float* loss_partial;
+  // rows longer than long_nnz are cut into parts of part_nnz non-zeros
+  int32_t long_nnz, part_nnz;
+  const int32_t* work_long; int64_t n_long;        // covered rows: (segment, local row, part, parts)
+  const int32_t* cols_long; int64_t n_cols_long;   // all vertices: (snapshot, vertex, part, parts)
+  float* long_partial;                             // one record per part
 };
 
 int64_t dysat_partial_elems(const DysatWs& ws);
+int64_t dysat_long_partial_elems(const DysatWs& ws);
+// list of the split rows among all vertices of the snapshots in use; *counter (device, zero on
+// entry) receives the number of parts; list may be NULL (count only)
+void dysat_cols_long(const GraphDev& g, const int32_t* used_t, int32_t n_used, int32_t long_nnz, int32_t part_nnz,
+                     int32_t* counter, int32_t* list, hipStream_t st);
 int64_t dysat_loss_partial_elems(const DysatWs& ws);
 // ev: NULL or 4 events recorded around the three backward stages
 void dysat_backward(const DysatWs& ws, const void* Y, int64_t ldy, const void* dY, int64_t lddy, const void* target,

@@ -26,6 +26,8 @@ CASES = {
     "ragged": dict(T=7, N=203, deg=5.0, chunks=[[0, 61, 0, 7], [61, 130, 0, 3], [61, 130, 3, 7], [130, 203, 1, 6]]),
     "full16": dict(T=16, N=97, deg=4.0, chunks=[[0, 33, 0, 16], [33, 97, 0, 16]]),
     "single": dict(T=3, N=40, deg=3.0, chunks=[[5, 6, 0, 3], [6, 40, 1, 2]]),
+    # rows longer than 24 non-zeros (the hub, and more at degree 9) are split into parts of 8
+    "split": dict(T=6, N=150, deg=9.0, chunks=[[0, 70, 0, 6], [70, 150, 0, 4]], kw=dict(long_nnz=24, part_nnz=8)),
 }
 
 
@@ -34,7 +36,7 @@ def test_forward_parity(case):
     from paper_2309_03523_amd.runner import DysatDevice
     c = CASES[case]
     wl = synth.dysat_small(40 + len(case), c["T"], c["N"], 128, 8, c["deg"], c["chunks"], hub=True)
-    dd = DysatDevice(wl, validate_level=1)
+    dd = DysatDevice(wl, validate_level=1, **c.get("kw", {}))
     got = dd.forward().float().cpu().numpy()
     want = dysat.forward(wl.graph, wl.chunks, wl.params, wl.X, wl.C, 8)["Y"]
     cov = _covered(wl)
@@ -55,7 +57,7 @@ def test_backward_parity(case, mode):
     c = CASES[case]
     wl = synth.dysat_small(40 + len(case), c["T"], c["N"], 128, 8, c["deg"], c["chunks"], hub=True)
     extra = synth.round_bf16(synth.stream(3, "extra").standard_normal(wl.X.shape).astype(np.float32))
-    dd = DysatDevice(wl)
+    dd = DysatDevice(wl, **c.get("kw", {}))
     dd.forward()
     dev = torch.from_numpy(extra).cuda().to(torch.bfloat16)
     if mode == "target":
