@@ -317,7 +317,8 @@ dgc_status_t build_dysat(dgc_layer* L, const std::vector<ChunkInfo>& cinfo, hipS
   DGC_HIP_TRY(dev_alloc(L, &w.sX, TN * 16));
   DGC_HIP_TRY(dev_alloc(L, &w.sC, TN * 8));
   DGC_HIP_TRY(dev_alloc(L, &w.lse, TN * 8));
-  DGC_HIP_TRY(dev_alloc(L, &w.st2, TN * 16));
+  DGC_HIP_TRY(dev_alloc(L, &w.st2, TN * 32));
+  DGC_HIP_TRY(dev_alloc(L, &w.dss, TN * 16));
   // split rows: those of the covered rows come from the packing; the reverse-edge pass walks every
   // vertex of the snapshots in use and gets its own list
   w.long_nnz = L->long_nnz; w.part_nnz = L->part_nnz;
@@ -338,6 +339,27 @@ dgc_status_t build_dysat(dgc_layer* L, const std::vector<ChunkInfo>& cinfo, hipS
     w.cols_long = d_list; w.n_cols_long = n_parts;
   }
   DGC_HIP_TRY(dev_alloc(L, &w.long_partial, dysat_long_partial_elems(w)));
+  {
+    // edge codes of the reverse-edge pass: one byte per stored non-zero of the snapshots in use
+    std::vector<int64_t> off(T, 0);
+    std::vector<const int64_t*> rp(T);
+    DGC_HIP_TRY(hipMemcpy(rp.data(), L->d_rowptr, sizeof(void*) * T, hipMemcpyDeviceToHost));
+    int64_t total = 0;
+    for (int32_t t : used) {
+      int64_t nnz = 0;
+      DGC_HIP_TRY(hipMemcpy(&nnz, rp[t] + N, sizeof(int64_t), hipMemcpyDeviceToHost));
+      off[t] = total;
+      total += nnz;
+    }
+    int64_t* d_off = nullptr;
+    uint8_t* d_code = nullptr;
+    DGC_HIP_TRY(dev_alloc(L, &d_off, T));
+    DGC_HIP_TRY(dev_alloc(L, &d_code, total));
+    DGC_HIP_TRY(hipMemcpy(d_off, off.data(), sizeof(int64_t) * T, hipMemcpyHostToDevice));
+    dysat_edge_code(w.g, w.used_t, w.n_used, w.owner, d_off, d_code, st);
+    DGC_HIP_TRY(hipStreamSynchronize(st));
+    w.ecode = d_code; w.ecode_off = d_off;
+  }
   w.partial_elems = dysat_partial_elems(w);
   DGC_HIP_TRY(dev_alloc(L, &w.partial, w.partial_elems));
   DGC_HIP_TRY(dev_alloc(L, &w.loss_partial, dysat_loss_partial_elems(w)));

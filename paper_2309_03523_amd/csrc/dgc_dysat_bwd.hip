@@ -308,7 +308,8 @@ __global__ __launch_bounds__(512) void k_temporal_bwd2(TemporalBwd2Args a) {
 // the vertices of the snapshots in use, 32 per tile.  A workgroup of 4 waves walks a contiguous
 // range of tiles; wave w owns output rows [32w, 32w+32) of every dW_G.  Both operands need the
 // row index as contraction index, i.e. column layout: obtained from natural row fragments with
-// the selection products described above.
+// the selection products described above.  Eight waves per workgroup: wave w owns output rows
+// [32 (w%4), +32) and input columns [64 (w/4), +64) of every dW_G.
 struct DwBf16Args {
   const int32_t* used_t; int32_t n_used; int64_t N;
   const int32_t* owner; int32_t covered_only;
@@ -320,27 +321,27 @@ struct DwBf16Args {
 };
 
 template <int NG, bool AU>
-__global__ __launch_bounds__(256) void k_dw_bf16(DwBf16Args a) {
-  const int lane = threadIdx.x & 63, ob = threadIdx.x >> 6;
+__global__ __launch_bounds__(512) void k_dw_bf16(DwBf16Args a) {
+  const int lane = threadIdx.x & 63, ob = (threadIdx.x >> 6) & 3, ih = threadIdx.x >> 8;
   const int n = lane & 31, hh = lane >> 5;
   const int64_t tiles_per_t = (a.N + 31) / 32, n_tiles = tiles_per_t * a.n_used;
   const int64_t per = (n_tiles + a.n_groups - 1) / a.n_groups;
   const int64_t tile0 = (int64_t)blockIdx.x * per, tile1 = min(n_tiles, tile0 + per);
   const bf16x8 sel0 = sel_frag(0, lane), sel1 = sel_frag(1, lane);
-  floatx16 acc[NG][4] = {};
+  floatx16 acc[NG][2] = {};
   for (int64_t tile = tile0; tile < tile1; ++tile) {
     const int32_t t = a.used_t[tile / tiles_per_t];
     const int64_t v = (tile % tiles_per_t) * 32 + n;
     const bool valid = v < a.N;
     const int64_t row = (int64_t)t * a.N + (valid ? v : a.N - 1);
     const bool ok = valid && (!a.covered_only || a.owner[row] >= 0);
-    bf16x8 at[4][2], al[4][2];
+    bf16x8 at[2][2], al[2][2];
 #pragma unroll
-    for (int jb = 0; jb < 4; ++jb) {
+    for (int jb = 0; jb < 2; ++jb) {
       floatx16 tr = {}, trl = {};
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
-        const int off = (2 * jb + c) * 16 + 8 * hh;
+        const int off = (2 * (2 * ih + jb) + c) * 16 + 8 * hh;
         if (AU) {
           float x[8];
           if (ok) {
@@ -382,7 +383,7 @@ __global__ __launch_bounds__(256) void k_dw_bf16(DwBf16Args a) {
       }
       const bf16x8 g0 = pack8v(tr, 0), g1 = pack8v(tr, 8);
 #pragma unroll
-      for (int ib = 0; ib < 4; ++ib) {
+      for (int ib = 0; ib < 2; ++ib) {
         acc[gi][ib] = mfma(g0, at[ib][0], acc[gi][ib]);
         acc[gi][ib] = mfma(g1, at[ib][1], acc[gi][ib]);
         if (AU) {
@@ -396,10 +397,10 @@ __global__ __launch_bounds__(256) void k_dw_bf16(DwBf16Args a) {
   for (int gi = 0; gi < NG; ++gi) {
     float* out = a.partial + ((int64_t)blockIdx.x * NG + gi) * kS * kS;
 #pragma unroll
-    for (int ib = 0; ib < 4; ++ib)
+    for (int ib = 0; ib < 2; ++ib)
 #pragma unroll
       for (int vv = 0; vv < 16; ++vv)
-        out[(ob * 32 + 8 * (vv >> 2) + 4 * hh + (vv & 3)) * kS + ib * 32 + n] = acc[gi][ib][vv];
+        out[(ob * 32 + 8 * (vv >> 2) + 4 * hh + (vv & 3)) * kS + (2 * ih + ib) * 32 + n] = acc[gi][ib][vv];
   }
 }
 
@@ -432,7 +433,6 @@ __global__ __launch_bounds__(1024) void k_reduce_slots(const float* partial, int
 // Rows longer than long_nnz are cut into parts (one wavefront each) whose sums a merge kernel
 // adds in part order.
 constexpr int kLongRec = 144;    // floats per scratch record of a part of a split row (forward, row pass)
-constexpr int kColsRec = 272;    // same, reverse-edge pass
 
 struct GatBwdRowsArgs {
   GraphDev g;
@@ -445,7 +445,7 @@ struct GatBwdRowsArgs {
   const float* sX; const float* sC;
   const float* U; const uint16_t* dU;
   const float* lse;
-  float* st2;     // [T*N][16]: d s_dst[8], c[8]
+  float4* st2;    // [T*N][8]: per head (s_dst, lse, c, d s_dst): what the reverse-edge pass needs of a row
 };
 
 __device__ __forceinline__ void load16(const uint16_t* p, float* x) {
@@ -512,12 +512,9 @@ __global__ __launch_bounds__(256) void k_gat_bwd_rows(GatBwdRowsArgs a) {
     if (e1 - e0 > a.long_nnz) continue;
     float du[16];
     const float c = load_du_c(a, base + i, h, du);
-    const float dsd = gat_bwd_row_range(a, s, col, base, du, c, a.sX[(base + i) * 16 + 8 + h],
-                                        a.lse[(base + i) * 8 + h], e0, e1, lane);
-    if (slot == 0) {
-      a.st2[(base + i) * 16 + h] = dsd;
-      a.st2[(base + i) * 16 + 8 + h] = c;
-    }
+    const float sd = a.sX[(base + i) * 16 + 8 + h], lse = a.lse[(base + i) * 8 + h];
+    const float dsd = gat_bwd_row_range(a, s, col, base, du, c, sd, lse, e0, e1, lane);
+    if (slot == 0) a.st2[(base + i) * 8 + h] = make_float4(sd, lse, c, dsd);
   }
 }
 
@@ -538,7 +535,7 @@ __global__ __launch_bounds__(256) void k_gat_bwd_rows_long(GatBwdRowsArgs a) {
                                       a.lse[(base + i) * 8 + h], e0, e1, lane);
   if (slot == 0) {
     a.long_partial[item * kLongRec + h] = dsd;
-    if (w[2] == 0) a.st2[(base + i) * 16 + 8 + h] = c;
+    a.long_partial[item * kLongRec + 8 + h] = c;
   }
 }
 
@@ -552,7 +549,8 @@ __global__ void k_gat_bwd_rows_merge(GatBwdRowsArgs a) {
   const Segment s = a.segs[w[0]];
   float dsd = 0.f;
   for (int p = 0; p < w[3]; ++p) dsd += a.long_partial[(item + p) * kLongRec + h];
-  a.st2[((int64_t)s.t * a.g.N + s.v_lo + w[1]) * 16 + h] = dsd;
+  const int64_t row = (int64_t)s.t * a.g.N + s.v_lo + w[1];
+  a.st2[row * 8 + h] = make_float4(a.sX[row * 16 + 8 + h], a.lse[row * 8 + h], a.long_partial[item * kLongRec + 8 + h], dsd);
 }
 
 // Graph attention backward, reverse-edge pass: for every vertex j of every snapshot in use, the
@@ -567,127 +565,194 @@ struct GatBwdColsArgs {
   GraphDev g;
   const int32_t* used_t; int32_t n_used;
   const int32_t* owner;
+  const uint8_t* ecode;          // per stored non-zero (j, i) of the snapshots in use: 0 = row i is not covered,
+  const int64_t* ecode_off;      //   1 = i and j are rows of the same chunk, 2 = of different chunks; [T] first entry
   const int32_t* cols_long; int64_t n_cols_long;
   int32_t long_nnz, part_nnz;
   float* long_partial;
   const uint16_t* zX; const uint16_t* zC;
   const float* sX; const float* sC;
   const uint16_t* dU;
-  const float* lse; const float* st2;
+  const float4* st2;
   const float* a_src; const float* a_dst;
   uint16_t* dzX; uint16_t* dzC;
-  float* da_partial;    // [n_waves + n_cols_long][2][128]: d a_src, d a_dst
-  int32_t n_waves;
+  float* dss;           // [T*N][16]: d s_src of the row as an in-chunk neighbour [8], as a cache row [8]
 };
 
-struct ColOwn {      // what a wave keeps about its own vertex j
+constexpr int kColsRec = 272;    // floats per scratch record of a part of a split row: dzX[128], dzC[128], dsx[8], dsc[8]
+
+// Lane layout of the reverse-edge pass: lane = 16 * slot + sub.  The four slots work on four
+// neighbours at a time; the 16 sub-lanes of a slot span the 128 features (8 per lane, one
+// 16-byte load), two sub-lanes per head.
+struct ColOwn {      // what a lane keeps about the wave's own vertex j
   int32_t oj;
-  float zx0, zx1, zc0, zc1, ssx, ssc;
+  float zx[8], zc[8], ssx, ssc;
 };
-struct ColAcc { float ax0, ax1, ac0, ac1, dsx, dsc; };
+struct ColAcc { float ax[8], ac[8], dsx, dsc; };
 
-__device__ __forceinline__ ColOwn col_own(const GatBwdColsArgs& a, int64_t row, int lane, int head) {
+__device__ __forceinline__ float quad_xor1(float x) {   // value of lane l^1
+  return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x), 0xB1, 0xF, 0xF, true));
+}
+// sum over the four slots (lanes l, l^16, l^32, l^48), same result in all of them
+__device__ __forceinline__ float slot_sum(float x) {
+  auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  const float y = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  auto q = __builtin_amdgcn_permlane32_swap(__float_as_uint(y), __float_as_uint(y), false, false);
+  return __uint_as_float(q[0]) + __uint_as_float(q[1]);
+}
+
+__device__ __forceinline__ ColOwn col_own(const GatBwdColsArgs& a, int64_t row, int sub) {
   ColOwn o;
+  const int head = sub >> 1;
+  // zX / sX of a vertex no chunk covers hold stale values: they are never used (no neighbour
+  // can be "of the same chunk"), and loading them unconditionally keeps the loads independent
   o.oj = a.owner[row];
-  const uint32_t zc = *reinterpret_cast<const uint32_t*>(a.zC + row * kS + 2 * lane);
-  const uint32_t zx = o.oj >= 0 ? *reinterpret_cast<const uint32_t*>(a.zX + row * kS + 2 * lane) : 0u;
-  o.zx0 = bf_lo(zx); o.zx1 = bf_hi(zx); o.zc0 = bf_lo(zc); o.zc1 = bf_hi(zc);
-  o.ssx = o.oj >= 0 ? a.sX[row * 16 + head] : 0.f;
+  unpack8(*reinterpret_cast<const uint4*>(a.zC + row * kS + 8 * sub), o.zc);
+  unpack8(*reinterpret_cast<const uint4*>(a.zX + row * kS + 8 * sub), o.zx);
+  o.ssx = a.sX[row * 16 + head];
   o.ssc = a.sC[row * 8 + head];
   return o;
 }
 
-__device__ __forceinline__ ColAcc gat_bwd_col_range(const GatBwdColsArgs& a, const int32_t* col, int64_t base,
-                                                    const ColOwn& o, int64_t e0, int64_t e1, int lane, int head) {
-  ColAcc r{0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+// contributions of the stored non-zeros [e0, e1) of row j; the four slots are already summed.
+// il / cl: column id and code of non-zero e0 + lane (the first 64), loaded by the caller so that
+// they are in flight while the previous row is being processed.
+__device__ __forceinline__ ColAcc gat_bwd_col_range(const GatBwdColsArgs& a, const int32_t* col, const uint8_t* code,
+                                                    int64_t base, const ColOwn& o, int64_t e0, int64_t e1,
+                                                    int32_t il, int32_t cl, int lane) {
+  const int slot = lane >> 4, sub = lane & 15, head = sub >> 1;
+  ColAcc r;
+#pragma unroll
+  for (int d = 0; d < 8; ++d) { r.ax[d] = 0.f; r.ac[d] = 0.f; }
+  r.dsx = 0.f; r.dsc = 0.f;
   for (int64_t eb = e0; eb < e1; eb += 64) {
     const int cnt = (int)min((int64_t)64, e1 - eb);
-    const int32_t il = lane < cnt ? col[eb + lane] : 0;
-    const int32_t ol = lane < cnt ? a.owner[base + il] : -1;
+    if (eb != e0) {
+      il = lane < cnt ? col[eb + lane] : 0;
+      cl = lane < cnt ? code[eb + lane] : 0;
+    }
     for (int q0 = 0; q0 < cnt; q0 += 8) {
-      uint32_t dv[8];
-      float sd[8], ls[8], cc[8];
-      int same[8];
+      uint4 dv[2];
+      float4 st[2];
+      int32_t cc[2];
 #pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        same[q] = -1;   // -1: not a covered row, skip
-        dv[q] = 0u; sd[q] = 0.f; ls[q] = 0.f; cc[q] = 0.f;
-        if (q0 + q < cnt) {
-          const int32_t oi = __builtin_amdgcn_readlane(ol, q0 + q);
-          if (oi >= 0) {
-            const int64_t ri = base + __builtin_amdgcn_readlane(il, q0 + q);
-            same[q] = oi == o.oj ? 1 : 0;
-            dv[q] = *reinterpret_cast<const uint32_t*>(a.dU + ri * kS + 2 * lane);
-            sd[q] = a.sX[ri * 16 + 8 + head];
-            ls[q] = a.lse[ri * 8 + head];
-            cc[q] = a.st2[ri * 16 + 8 + head];
-          }
+      for (int u = 0; u < 2; ++u) {
+        const int idx = q0 + 4 * u + slot;
+        const int32_t ii = __shfl(il, idx);
+        const int32_t cs = __shfl(cl, idx);   // outside the select: every lane has to take part
+        cc[u] = idx < cnt ? cs : 0;
+        dv[u] = make_uint4(0, 0, 0, 0);
+        st[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (cc[u] != 0) {
+          dv[u] = *reinterpret_cast<const uint4*>(a.dU + (base + ii) * kS + 8 * sub);
+          st[u] = a.st2[(base + ii) * 8 + head];
         }
       }
 #pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        if (same[q] < 0) continue;      // wave-uniform
-        const bool sm = same[q] != 0;
-        const float d0 = bf_lo(dv[q]), d1 = bf_hi(dv[q]);
-        const float e = sd[q] + (sm ? o.ssx : o.ssc);
-        const float al = __expf(lrelu(e) - ls[q]);
-        float da = d0 * (sm ? o.zx0 : o.zc0) + d1 * (sm ? o.zx1 : o.zc1);
-        da += __shfl_xor(da, 1);
-        da += __shfl_xor(da, 2);
-        da += __shfl_xor(da, 4);
-        const float dpre = al * (da - cc[q]) * (e > 0.f ? 1.f : kSlope);
-        if (sm) { r.ax0 += al * d0; r.ax1 += al * d1; r.dsx += dpre; }
-        else { r.ac0 += al * d0; r.ac1 += al * d1; r.dsc += dpre; }
+      for (int u = 0; u < 2; ++u) {
+        float du[8];
+        unpack8(dv[u], du);
+        const bool sm = cc[u] == 1;
+        const float e = st[u].x + (sm ? o.ssx : o.ssc);
+        float al = __expf(lrelu(e) - st[u].y);
+        float da = 0.f;
+#pragma unroll
+        for (int d = 0; d < 8; ++d) da += du[d] * (sm ? o.zx[d] : o.zc[d]);
+        da += quad_xor1(da);
+        al = cc[u] != 0 ? al : 0.f;
+        const float dpre = al * (da - st[u].z) * (e > 0.f ? 1.f : kSlope);
+        const float alx = sm ? al : 0.f, alc = sm ? 0.f : al;
+#pragma unroll
+        for (int d = 0; d < 8; ++d) {
+          r.ax[d] += alx * du[d];
+          r.ac[d] += alc * du[d];
+        }
+        r.dsx += sm ? dpre : 0.f;
+        r.dsc += sm ? 0.f : dpre;
       }
     }
   }
+#pragma unroll
+  for (int d = 0; d < 8; ++d) {
+    r.ax[d] = slot_sum(r.ax[d]);
+    r.ac[d] = slot_sum(r.ac[d]);
+  }
+  r.dsx = slot_sum(r.dsx);
+  r.dsc = slot_sum(r.dsc);
   return r;
 }
 
-struct AttVec { float as0, as1, ad0, ad1, gas0, gas1, gad0, gad1; };
+struct AttVec { float as[8], ad[8]; };
 
-__device__ __forceinline__ void gat_bwd_col_finish(const GatBwdColsArgs& a, int64_t row, const ColOwn& o,
-                                                   const ColAcc& r, AttVec& v, int lane, int head) {
-  if (o.oj >= 0) {
-    const float dsd = a.st2[row * 16 + head];
-    *reinterpret_cast<uint32_t*>(a.dzX + row * kS + 2 * lane) =
-        pack2(r.ax0 + dsd * v.ad0 + r.dsx * v.as0, r.ax1 + dsd * v.ad1 + r.dsx * v.as1);
-    v.gad0 += dsd * o.zx0; v.gad1 += dsd * o.zx1;
-    v.gas0 += r.dsx * o.zx0; v.gas1 += r.dsx * o.zx1;
+__device__ __forceinline__ AttVec att_init(const GatBwdColsArgs& a, int sub) {
+  AttVec v;
+#pragma unroll
+  for (int d = 0; d < 8; ++d) {
+    v.as[d] = a.a_src[8 * sub + d];
+    v.ad[d] = a.a_dst[8 * sub + d];
   }
-  *reinterpret_cast<uint32_t*>(a.dzC + row * kS + 2 * lane) = pack2(r.ac0 + r.dsc * v.as0, r.ac1 + r.dsc * v.as1);
-  v.gas0 += r.dsc * o.zc0; v.gas1 += r.dsc * o.zc1;
+  return v;
 }
 
-__device__ __forceinline__ void att_store(float* slot, const AttVec& v, int lane) {
-  slot[2 * lane] = v.gas0; slot[2 * lane + 1] = v.gas1;
-  slot[kS + 2 * lane] = v.gad0; slot[kS + 2 * lane + 1] = v.gad1;
+__device__ __forceinline__ void gat_bwd_col_finish(const GatBwdColsArgs& a, int64_t row, const ColOwn& o,
+                                                   const ColAcc& r, const AttVec& v, int lane) {
+  const int slot = lane >> 4, sub = lane & 15, head = sub >> 1;
+  if (slot != 0) return;
+  float out[8];
+  if (o.oj >= 0) {
+    const float dsd = a.st2[row * 8 + head].w;
+#pragma unroll
+    for (int d = 0; d < 8; ++d) out[d] = r.ax[d] + dsd * v.ad[d] + r.dsx * v.as[d];
+    *reinterpret_cast<uint4*>(a.dzX + row * kS + 8 * sub) = __builtin_bit_cast(uint4, pack8(out));
+  }
+#pragma unroll
+  for (int d = 0; d < 8; ++d) out[d] = r.ac[d] + r.dsc * v.as[d];
+  *reinterpret_cast<uint4*>(a.dzC + row * kS + 8 * sub) = __builtin_bit_cast(uint4, pack8(out));
+  if ((sub & 1) == 0) {
+    a.dss[row * 16 + head] = r.dsx;
+    a.dss[row * 16 + 8 + head] = r.dsc;
+  }
 }
 
 __global__ __launch_bounds__(256) void k_gat_bwd_cols(GatBwdColsArgs a) {
   const int lane = threadIdx.x & 63;
-  const int wave = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int64_t N = a.g.N;
   const int64_t groups_per_t = (N + 15) / 16, n_items = groups_per_t * a.n_used;
-  const int head = lane >> 3;
-  AttVec v{a.a_src[2 * lane], a.a_src[2 * lane + 1], a.a_dst[2 * lane], a.a_dst[2 * lane + 1], 0.f, 0.f, 0.f, 0.f};
-  for (int64_t item = wave; item < n_items; item += a.n_waves) {
-    const int32_t t = a.used_t[item / groups_per_t];
-    const int64_t j0 = (item % groups_per_t) * 16;
-    const int64_t* rowptr = a.g.rowptr[t];
-    const int32_t* col = a.g.colidx[t];
-    const int64_t base = (int64_t)t * N;
-    const int nr = (int)min((int64_t)16, N - j0);
-    for (int rr = 0; rr < nr; ++rr) {
-      const int64_t j = j0 + rr;
-      const int64_t e0 = rowptr[j], e1 = rowptr[j + 1];
-      if (e1 - e0 > a.long_nnz) continue;
-      const ColOwn o = col_own(a, base + j, lane, head);
-      const ColAcc r = gat_bwd_col_range(a, col, base, o, e0, e1, lane, head);
-      gat_bwd_col_finish(a, base + j, o, r, v, lane, head);
+  const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (item >= n_items) return;
+  const int sub = lane & 15;
+  const AttVec v = att_init(a, sub);
+  const int32_t t = a.used_t[item / groups_per_t];
+  const int64_t j0 = (item % groups_per_t) * 16;
+  const int32_t* col = a.g.colidx[t];
+  const uint8_t* code = a.ecode + a.ecode_off[t];
+  const int64_t base = (int64_t)t * N;
+  const int nr = (int)min((int64_t)16, N - j0);
+  // row pointers of the whole group at once; the next row's column ids and codes are requested
+  // before the current row is processed
+  const int64_t rp = a.g.rowptr[t][j0 + min(lane, nr)];
+  const int32_t rlo = (int32_t)(rp & 0xffffffff), rhi = (int32_t)(rp >> 32);
+  auto row_ptr = [&](int r) {
+    return ((int64_t)__builtin_amdgcn_readlane(rhi, r) << 32) | (uint32_t)__builtin_amdgcn_readlane(rlo, r);
+  };
+  int64_t e0 = row_ptr(0), e1 = row_ptr(1);
+  int32_t il = e0 + lane < e1 ? col[e0 + lane] : 0;
+  int32_t cl = e0 + lane < e1 ? code[e0 + lane] : 0;
+  for (int rr = 0; rr < nr; ++rr) {
+    int64_t ne0 = e1, ne1 = e1;
+    int32_t nil = 0, ncl = 0;
+    if (rr + 1 < nr) {
+      ne1 = row_ptr(rr + 2);
+      nil = ne0 + lane < ne1 ? col[ne0 + lane] : 0;
+      ncl = ne0 + lane < ne1 ? code[ne0 + lane] : 0;
     }
+    if (e1 - e0 <= a.long_nnz) {
+      const ColOwn o = col_own(a, base + j0 + rr, sub);
+      const ColAcc r = gat_bwd_col_range(a, col, code, base, o, e0, e1, il, cl, lane);
+      gat_bwd_col_finish(a, base + j0 + rr, o, r, v, lane);
+    }
+    e0 = ne0; e1 = ne1; il = nil; cl = ncl;
   }
-  att_store(a.da_partial + (int64_t)wave * 2 * kS, v, lane);
 }
 
 __global__ __launch_bounds__(256) void k_gat_bwd_cols_long(GatBwdColsArgs a) {
@@ -696,16 +761,27 @@ __global__ __launch_bounds__(256) void k_gat_bwd_cols_long(GatBwdColsArgs a) {
   if (item >= a.n_cols_long) return;
   const int32_t* w = a.cols_long + 4 * item;   // snapshot, vertex, part, parts
   const int64_t base = (int64_t)w[0] * a.g.N, j = w[1];
-  const int head = lane >> 3;
+  const int sub = lane & 15;
   const int64_t* rowptr = a.g.rowptr[w[0]];
   const int64_t e0 = rowptr[j] + (int64_t)w[2] * a.part_nnz, e1 = min(rowptr[j + 1], e0 + a.part_nnz);
-  const ColOwn o = col_own(a, base + j, lane, head);
-  const ColAcc r = gat_bwd_col_range(a, a.g.colidx[w[0]], base, o, e0, e1, lane, head);
-  float* rec = a.long_partial + item * kColsRec;
-  *reinterpret_cast<float4*>(rec + 4 * lane) = make_float4(r.ax0, r.ax1, r.ac0, r.ac1);
-  if ((lane & 7) == 0) {
-    rec[256 + head] = r.dsx;
-    rec[264 + head] = r.dsc;
+  const ColOwn o = col_own(a, base + j, sub);
+  const int32_t* col = a.g.colidx[w[0]];
+  const uint8_t* code = a.ecode + a.ecode_off[w[0]];
+  const int32_t il = e0 + lane < e1 ? col[e0 + lane] : 0;
+  const int32_t cl = e0 + lane < e1 ? code[e0 + lane] : 0;
+  const ColAcc r = gat_bwd_col_range(a, col, code, base, o, e0, e1, il, cl, lane);
+  if ((lane >> 4) == 0) {
+    float* rec = a.long_partial + item * kColsRec;
+    float4* x = reinterpret_cast<float4*>(rec + 8 * sub);
+    x[0] = make_float4(r.ax[0], r.ax[1], r.ax[2], r.ax[3]);
+    x[1] = make_float4(r.ax[4], r.ax[5], r.ax[6], r.ax[7]);
+    float4* c = reinterpret_cast<float4*>(rec + kS + 8 * sub);
+    c[0] = make_float4(r.ac[0], r.ac[1], r.ac[2], r.ac[3]);
+    c[1] = make_float4(r.ac[4], r.ac[5], r.ac[6], r.ac[7]);
+    if ((sub & 1) == 0) {
+      rec[256 + (sub >> 1)] = r.dsx;
+      rec[264 + (sub >> 1)] = r.dsc;
+    }
   }
 }
 
@@ -714,22 +790,82 @@ __global__ __launch_bounds__(256) void k_gat_bwd_cols_merge(GatBwdColsArgs a) {
   const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (item >= a.n_cols_long) return;
   const int32_t* w = a.cols_long + 4 * item;
-  const int head = lane >> 3;
-  AttVec v{a.a_src[2 * lane], a.a_src[2 * lane + 1], a.a_dst[2 * lane], a.a_dst[2 * lane + 1], 0.f, 0.f, 0.f, 0.f};
-  if (w[2] == 0) {
-    const int64_t row = (int64_t)w[0] * a.g.N + w[1];
-    ColAcc r{0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int p = 0; p < w[3]; ++p) {
-      const float* rec = a.long_partial + (item + p) * kColsRec;
-      const float4 x = *reinterpret_cast<const float4*>(rec + 4 * lane);
-      r.ax0 += x.x; r.ax1 += x.y; r.ac0 += x.z; r.ac1 += x.w;
-      r.dsx += rec[256 + head];
-      r.dsc += rec[264 + head];
+  if (w[2] != 0) return;
+  const int sub = lane & 15;
+  const AttVec v = att_init(a, sub);
+  const int64_t row = (int64_t)w[0] * a.g.N + w[1];
+  ColAcc r;
+#pragma unroll
+  for (int d = 0; d < 8; ++d) { r.ax[d] = 0.f; r.ac[d] = 0.f; }
+  r.dsx = 0.f; r.dsc = 0.f;
+  for (int p = 0; p < w[3]; ++p) {
+    const float* rec = a.long_partial + (item + p) * kColsRec;
+#pragma unroll
+    for (int d = 0; d < 8; ++d) {
+      r.ax[d] += rec[8 * sub + d];
+      r.ac[d] += rec[kS + 8 * sub + d];
     }
-    const ColOwn o = col_own(a, row, lane, head);
-    gat_bwd_col_finish(a, row, o, r, v, lane, head);
+    r.dsx += rec[256 + (sub >> 1)];
+    r.dsc += rec[264 + (sub >> 1)];
   }
-  att_store(a.da_partial + ((int64_t)a.n_waves + item) * 2 * kS, v, lane);   // zeros for the other parts
+  const ColOwn o = col_own(a, row, sub);
+  gat_bwd_col_finish(a, row, o, r, v, lane);
+}
+
+// Gradients of the attention vectors, a streaming pass over every vertex of the snapshots in use:
+//   d a_dst^h += d s_dst_i^h z_i^h (covered rows, own projection),
+//   d a_src^h += d s_srcX_i^h zX_i^h (covered rows) + d s_srcC_i^h zC_i^h (all rows).
+// Lanes span the 128 features; each wave walks rows with a grid stride and leaves its sums in its
+// own slot.
+struct AttGradArgs {
+  const int32_t* used_t; int32_t n_used; int64_t N;
+  const int32_t* owner;
+  const uint16_t* zX; const uint16_t* zC;
+  const float4* st2; const float* dss;
+  float* da_partial;    // [waves][2][128]: d a_src, d a_dst
+};
+
+__global__ __launch_bounds__(256) void k_att_grad(AttGradArgs a) {
+  const int lane = threadIdx.x & 63, head = lane >> 3;
+  const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = (int64_t)gridDim.x * 4;
+  const int64_t n_rows = a.N * a.n_used;
+  float gs0 = 0.f, gs1 = 0.f, gd0 = 0.f, gd1 = 0.f;
+  for (int64_t r0 = wave * 8; r0 < n_rows; r0 += n_waves * 8) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int64_t idx = r0 + k;
+      if (idx >= n_rows) break;
+      const int64_t row = (int64_t)a.used_t[idx / a.N] * a.N + idx % a.N;
+      const uint32_t zc = *reinterpret_cast<const uint32_t*>(a.zC + row * kS + 2 * lane);
+      const float dsc = a.dss[row * 16 + 8 + head];
+      gs0 += dsc * bf_lo(zc); gs1 += dsc * bf_hi(zc);
+      if (a.owner[row] >= 0) {
+        const uint32_t zx = *reinterpret_cast<const uint32_t*>(a.zX + row * kS + 2 * lane);
+        const float dsx = a.dss[row * 16 + head], dsd = a.st2[row * 8 + head].w;
+        gs0 += dsx * bf_lo(zx); gs1 += dsx * bf_hi(zx);
+        gd0 += dsd * bf_lo(zx); gd1 += dsd * bf_hi(zx);
+      }
+    }
+  }
+  float* o = a.da_partial + wave * 2 * kS;
+  o[2 * lane] = gs0; o[2 * lane + 1] = gs1;
+  o[kS + 2 * lane] = gd0; o[kS + 2 * lane + 1] = gd1;
+}
+
+// code of every stored non-zero (j, i) of snapshot t: see GatBwdColsArgs
+__global__ void k_edge_code(GraphDev g, const int32_t* used_t, int32_t n_used, const int32_t* owner,
+                            const int64_t* ecode_off, uint8_t* ecode) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= g.N * n_used) return;
+  const int32_t t = used_t[idx / g.N];
+  const int64_t j = idx % g.N, base = (int64_t)t * g.N;
+  const int32_t oj = owner[base + j];
+  const int32_t* col = g.colidx[t];
+  uint8_t* out = ecode + ecode_off[t];
+  for (int64_t e = g.rowptr[t][j]; e < g.rowptr[t][j + 1]; ++e) {
+    const int32_t oi = owner[base + col[e]];
+    out[e] = oi < 0 ? 0 : (oi == oj ? 1 : 2);
+  }
 }
 
 // list of the split rows of the reverse-edge pass: count, then fill (the order of the rows in
@@ -762,10 +898,14 @@ constexpr int kColsBlocks = 1024;  // workgroups of the reverse-edge pass (4 slo
 // scratch layout: [weight-gradient slots | position-gradient slots | attention-vector slots]
 int64_t dysat_partial_elems(const DysatWs& ws) {
   return (int64_t)kDwGroups * 3 * kS * kS + (int64_t)kTbwdWaves * ws.T * kS +
-         ((int64_t)kColsBlocks * 4 + ws.n_cols_long) * 2 * kS;
+         (int64_t)kColsBlocks * 4 * 2 * kS;
 }
 int64_t dysat_long_partial_elems(const DysatWs& ws) {
   return std::max<int64_t>(ws.n_long * kLongRec, ws.n_cols_long * kColsRec);
+}
+void dysat_edge_code(const GraphDev& g, const int32_t* used_t, int32_t n_used, const int32_t* owner,
+                     const int64_t* ecode_off, uint8_t* ecode, hipStream_t st) {
+  hipLaunchKernelGGL(k_edge_code, blocks_for(g.N * n_used, 256), 256, 0, st, g, used_t, n_used, owner, ecode_off, ecode);
 }
 void dysat_cols_long(const GraphDev& g, const int32_t* used_t, int32_t n_used, int32_t long_nnz, int32_t part_nnz,
                      int32_t* counter, int32_t* list, hipStream_t st) {
@@ -828,7 +968,7 @@ void dysat_backward(const DysatWs& ws, const void* Y, int64_t ldy, const void* d
   da.A = nullptr; da.lda = 0; da.Uf = ws.U; da.pos = ws.P[DY_POS];
   da.G[0] = ws.dQ; da.G[1] = ws.dK; da.G[2] = ws.dV;
   da.partial = dw_slots; da.n_groups = groups;
-  hipLaunchKernelGGL((k_dw_bf16<3, true>), groups, 256, 0, st, da);
+  hipLaunchKernelGGL((k_dw_bf16<3, true>), groups, 512, 0, st, da);
   for (int gi = 0; gi < 3; ++gi)
     hipLaunchKernelGGL(k_reduce_slots, blocks_for(kS * kS, 64), 1024, 0, st, dw_slots + (int64_t)gi * kS * kS,
                        (int64_t)groups, (int64_t)3 * kS * kS, (int64_t)kS * kS, 1.f, ws.G[DY_WQ + gi]);
@@ -837,7 +977,7 @@ void dysat_backward(const DysatWs& ws, const void* Y, int64_t ldy, const void* d
   GatBwdRowsArgs ra{};
   ra.g = ws.g; ra.segs = ws.segs; ra.work = ws.work_short; ra.n_work = ws.n_short;
   ra.zX = ws.zX; ra.zC = ws.zC; ra.sX = ws.sX; ra.sC = ws.sC; ra.U = ws.U; ra.dU = ws.dU; ra.lse = ws.lse;
-  ra.st2 = ws.st2;
+  ra.st2 = reinterpret_cast<float4*>(ws.st2);
   ra.work_long = ws.work_long; ra.n_long = ws.n_long; ra.long_nnz = ws.long_nnz; ra.part_nnz = ws.part_nnz;
   ra.long_partial = ws.long_partial;
   hipLaunchKernelGGL(k_gat_bwd_rows, blocks_for(ws.n_short, 4), 256, 0, st, ra);
@@ -846,22 +986,28 @@ void dysat_backward(const DysatWs& ws, const void* Y, int64_t ldy, const void* d
     hipLaunchKernelGGL(k_gat_bwd_rows_merge, blocks_for(ws.n_long * 8, 256), 256, 0, st, ra);
   }
   if (ev) (void)hipEventRecord(ev[2], st);
-  // (4) reverse-edge pass
+  // (4) reverse-edge pass, then the gradients of the attention vectors
   const int64_t items = (ws.N + 15) / 16 * ws.n_used;
-  const int cblocks = (int)std::min<int64_t>(kColsBlocks, (items + 3) / 4);
   GatBwdColsArgs ca{};
   ca.g = ws.g; ca.used_t = ws.used_t; ca.n_used = ws.n_used; ca.owner = ws.owner;
-  ca.zX = ws.zX; ca.zC = ws.zC; ca.sX = ws.sX; ca.sC = ws.sC; ca.dU = ws.dU; ca.lse = ws.lse; ca.st2 = ws.st2;
+  ca.ecode = ws.ecode; ca.ecode_off = ws.ecode_off;
+  ca.zX = ws.zX; ca.zC = ws.zC; ca.sX = ws.sX; ca.sC = ws.sC; ca.dU = ws.dU;
+  ca.st2 = reinterpret_cast<const float4*>(ws.st2);
   ca.a_src = ws.P[DY_ASRC]; ca.a_dst = ws.P[DY_ADST];
-  ca.dzX = ws.dzX; ca.dzC = ws.dzC; ca.da_partial = da_slots; ca.n_waves = cblocks * 4;
+  ca.dzX = ws.dzX; ca.dzC = ws.dzC; ca.dss = ws.dss;
   ca.cols_long = ws.cols_long; ca.n_cols_long = ws.n_cols_long; ca.long_nnz = ws.long_nnz; ca.part_nnz = ws.part_nnz;
   ca.long_partial = ws.long_partial;
-  hipLaunchKernelGGL(k_gat_bwd_cols, cblocks, 256, 0, st, ca);
+  hipLaunchKernelGGL(k_gat_bwd_cols, blocks_for(items, 4), 256, 0, st, ca);
   if (ws.n_cols_long > 0) {
     hipLaunchKernelGGL(k_gat_bwd_cols_long, blocks_for(ws.n_cols_long, 4), 256, 0, st, ca);
     hipLaunchKernelGGL(k_gat_bwd_cols_merge, blocks_for(ws.n_cols_long, 4), 256, 0, st, ca);
   }
-  const int64_t da_n = (int64_t)cblocks * 4 + ws.n_cols_long;
+  AttGradArgs ag{};
+  ag.used_t = ws.used_t; ag.n_used = ws.n_used; ag.N = ws.N; ag.owner = ws.owner; ag.zX = ws.zX; ag.zC = ws.zC;
+  ag.st2 = reinterpret_cast<const float4*>(ws.st2); ag.dss = ws.dss; ag.da_partial = da_slots;
+  const int ablocks = (int)std::min<int64_t>(kColsBlocks, (ws.N * ws.n_used + 31) / 32);
+  hipLaunchKernelGGL(k_att_grad, ablocks, 256, 0, st, ag);
+  const int64_t da_n = (int64_t)ablocks * 4;
   hipLaunchKernelGGL(k_reduce_slots, 2, 1024, 0, st, da_slots, da_n, (int64_t)2 * kS, (int64_t)kS, 1.f, ws.G[DY_ASRC]);
   hipLaunchKernelGGL(k_reduce_slots, 2, 1024, 0, st, da_slots + kS, da_n, (int64_t)2 * kS, (int64_t)kS, 1.f,
                      ws.G[DY_ADST]);
@@ -869,11 +1015,11 @@ void dysat_backward(const DysatWs& ws, const void* Y, int64_t ldy, const void* d
   DwBf16Args dx = da;
   dx.A = static_cast<const uint16_t*>(ws.X); dx.lda = ws.ldx; dx.Uf = nullptr; dx.covered_only = 1;
   dx.G[0] = ws.dzX; dx.partial = dw_slots;
-  hipLaunchKernelGGL((k_dw_bf16<1, false>), groups, 256, 0, st, dx);
+  hipLaunchKernelGGL((k_dw_bf16<1, false>), groups, 512, 0, st, dx);
   DwBf16Args dc = dx;
   dc.A = static_cast<const uint16_t*>(ws.C); dc.lda = ws.ldc; dc.covered_only = 0;
   dc.G[0] = ws.dzC; dc.partial = dw_slots + (int64_t)groups * kS * kS;
-  hipLaunchKernelGGL((k_dw_bf16<1, false>), groups, 256, 0, st, dc);
+  hipLaunchKernelGGL((k_dw_bf16<1, false>), groups, 512, 0, st, dc);
   hipLaunchKernelGGL(k_reduce_slots, blocks_for(kS * kS, 64), 1024, 0, st, dw_slots, (int64_t)2 * groups,
                      (int64_t)kS * kS, (int64_t)kS * kS, 1.f, ws.G[DY_W]);
   if (ev) (void)hipEventRecord(ev[3], st);

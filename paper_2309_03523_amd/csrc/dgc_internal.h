@@ -213,7 +213,8 @@ struct DysatWs {
   const void* X; int64_t ldx;                // inputs of the last forward (read again by backward)
   const void* C; int64_t ldc;
   uint16_t *dU, *dQ, *dK, *dV, *dzX, *dzC;   // [T*N][128] bf16
-  float* st2;                // [T*N][16]: d s_dst[8], c[8] of every covered row
+  float* st2;                // [T*N][8][4]: per head (s_dst, lse, c, d s_dst) of every covered row
+  float* dss;                // [T*N][16]: d s_src of every vertex, as in-chunk neighbour [8] and as cache row [8]
   float* partial;            // scratch for the parameter-gradient reductions
   int64_t partial_elems;
   float* loss_partial;
@@ -222,7 +223,12 @@ struct DysatWs {
   const int32_t* work_long; int64_t n_long;        // covered rows: (segment, local row, part, parts)
   const int32_t* cols_long; int64_t n_cols_long;   // all vertices: (snapshot, vertex, part, parts)
   float* long_partial;                             // one record per part
+  // per stored non-zero (j, i) of the snapshots in use: 0 = row i not covered, 1 = i and j rows of
+  // the same chunk, 2 = rows of different chunks; snapshot t starts at ecode_off[t]
+  const uint8_t* ecode; const int64_t* ecode_off;
 };
+void dysat_edge_code(const GraphDev& g, const int32_t* used_t, int32_t n_used, const int32_t* owner,
+                     const int64_t* ecode_off, uint8_t* ecode, hipStream_t st);
 
 int64_t dysat_partial_elems(const DysatWs& ws);
 int64_t dysat_long_partial_elems(const DysatWs& ws);
