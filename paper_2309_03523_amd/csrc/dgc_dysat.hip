@@ -327,9 +327,10 @@ __global__ __launch_bounds__(512) void k_temporal_fwd(TemporalArgs a) {
   stage_weights(wlds, a.Wq, a.Wk, a.Wv);
   const int lane = threadIdx.x & 63, nw = blockDim.x >> 6;
   const int hh = lane >> 5, f = lane & 31;
-  const bf16x8 zero8 = {};
+  const uint32_t m_head[2] = {(f >> 4) == 0 ? 0xffffffffu : 0u, (f >> 4) == 1 ? 0xffffffffu : 0u};
   for (int64_t tile = (int64_t)blockIdx.x * nw + (threadIdx.x >> 6); tile < a.n_tiles; tile += (int64_t)gridDim.x * nw) {
   const TileRow r = tile_row(a.chunks, a.n_chunks, a.tile_ptr, tile, a.N, lane);
+  const uint32_t m_vert[2] = {r.a == 0 ? 0xffffffffu : 0u, r.a == 1 ? 0xffffffffu : 0u};
   bf16x8 pf[8], pl[8];
   load_p_frags<true>(a.U, a.pos, r, hh, pf, pl);
 #pragma unroll 1
@@ -373,11 +374,12 @@ __global__ __launch_bounds__(512) void k_temporal_fwd(TemporalArgs a) {
 #pragma unroll
         for (int p = 0; p < 8; ++p) tmp[p] = vt[8 * av + p];
         split8(tmp, vh, vl);
-        const bool mine = (f >> 4) == hd;
-        const bool myv = r.a == av;
-        y = mfma(mine ? vl : zero8, myv ? ph : zero8, y);
-        y = mfma(mine ? vh : zero8, myv ? plo : zero8, y);
-        y = mfma(mine ? vh : zero8, myv ? ph : zero8, y);
+        vh = and_mask(vh, m_head[hd]);
+        vl = and_mask(vl, m_head[hd]);
+        const bf16x8 pa = and_mask(ph, m_vert[av]), pb = and_mask(plo, m_vert[av]);
+        y = mfma(vl, pa, y);
+        y = mfma(vh, pb, y);
+        y = mfma(vh, pa, y);
       }
     }
     if (r.valid) {

@@ -32,37 +32,41 @@ struct TemporalBwdArgs {
   float* loss_partial;   // [gridDim.x * waves per block]
 };
 
-// upstream gradient of n consecutive features (n = 8 or 4) of one row; adds (Y - target)^2 to *sq
-template <int NV>
-__device__ __forceinline__ void load_dy(const TemporalBwdArgs& a, int64_t row, int off, bool valid, float* out, float* sq) {
-  if (!valid) {
-#pragma unroll
-    for (int i = 0; i < NV; ++i) out[i] = 0.f;
-    return;
-  }
-  float y[8], g[8];
-  if (a.dY) {
-    if (NV == 8) unpack8(*reinterpret_cast<const uint4*>(a.dY + row * a.lddy + off), out);
-    else {
-      const uint2 u = *reinterpret_cast<const uint2*>(a.dY + row * a.lddy + off);
-      out[0] = bf_lo(u.x); out[1] = bf_hi(u.x); out[2] = bf_lo(u.y); out[3] = bf_hi(u.y);
+// value of lane l^32
+__device__ __forceinline__ float xor32(float x, int hh) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(hh ? r[0] : r[1]);
+}
+
+// raw 16-byte pieces of the upstream gradient (or of Y and the target) of features [off, off+8)
+struct DyRaw { uint4 a, b; };
+
+__device__ __forceinline__ DyRaw load_dy_raw(const TemporalBwdArgs& a, int64_t row, int off, bool valid) {
+  DyRaw r;
+  r.a = make_uint4(0, 0, 0, 0);
+  r.b = r.a;
+  if (valid) {
+    if (a.dY) {
+      r.a = *reinterpret_cast<const uint4*>(a.dY + row * a.lddy + off);
+    } else {
+      r.a = *reinterpret_cast<const uint4*>(a.Y + row * a.ldy + off);
+      r.b = *reinterpret_cast<const uint4*>(a.target + row * a.ldt + off);
     }
-    return;
   }
-  if (NV == 8) {
-    unpack8(*reinterpret_cast<const uint4*>(a.Y + row * a.ldy + off), y);
-    unpack8(*reinterpret_cast<const uint4*>(a.target + row * a.ldt + off), g);
-  } else {
-    const uint2 u = *reinterpret_cast<const uint2*>(a.Y + row * a.ldy + off);
-    const uint2 w = *reinterpret_cast<const uint2*>(a.target + row * a.ldt + off);
-    y[0] = bf_lo(u.x); y[1] = bf_hi(u.x); y[2] = bf_lo(u.y); y[3] = bf_hi(u.y);
-    g[0] = bf_lo(w.x); g[1] = bf_hi(w.x); g[2] = bf_lo(w.y); g[3] = bf_hi(w.y);
-  }
+  return r;
+}
+// -> dL/dY of those 8 features; adds (Y - target)^2 to sq (rows that are not valid give zeros)
+__device__ __forceinline__ void dy_from_raw(const TemporalBwdArgs& a, const DyRaw& r, float* out, float& sq) {
+  unpack8(r.a, out);
+  if (!a.dY) {
+    float g[8];
+    unpack8(r.b, g);
 #pragma unroll
-  for (int i = 0; i < NV; ++i) {
-    const float d = y[i] - g[i];
-    out[i] = a.scale * d;
-    if (sq) *sq += d * d;
+    for (int i = 0; i < 8; ++i) {
+      const float d = out[i] - g[i];
+      out[i] = a.scale * d;
+      sq += d * d;
+    }
   }
 }
 
@@ -79,25 +83,42 @@ __device__ __forceinline__ void stage_weights(uint4* lds, const uint4* w0, const
 
 // Temporal self-attention, backward, first half: dQ, dK, dV (and the loss).  The workgroup stages
 // W_q, W_k, W_v in LDS; each of its waves then walks 2-vertex tiles with a grid stride.  Per tile
-// it recomputes P, Q, K, V (Q, K also in column layout), then per head the score block in both
-// orientations: "query-major" (lane = query row, registers = key steps) gives the softmax
-// statistics, delta = sum_r p dp and dS for dQ; "key-major" (lane = key row, registers = query
-// steps; the statistics of the query rows are fetched from their lanes) gives p and dS for dV
-// and dK.  All operands are hi + lo pairs.  dQ, dK, dV land in row layout and are stored (bf16).
+// it recomputes P, Q, K, V (Q, K also in column layout).  Per head, the "query-major" score block
+// (lane = query row, registers = key steps) gives the probabilities p, delta = sum_r p dp and dS;
+// dQ needs dS in that orientation, dK and dV need dS and p "key-major" (lane = key row,
+// registers = query steps): those are obtained by one product each with a selection operand
+// (a 16 x 16 transpose per vertex on the matrix core, exact for the hi and the lo part).
+// All operands are hi + lo pairs.  dQ, dK, dV land in row layout and are stored (bf16).
 __global__ __launch_bounds__(256) void k_temporal_bwd(TemporalBwdArgs a) {
   extern __shared__ uint4 wlds[];
   stage_weights(wlds, a.Wq, a.Wk, a.Wv);
   const int lane = threadIdx.x & 63, nw = blockDim.x >> 6, wave = threadIdx.x >> 6;
   const int hh = lane >> 5, f = lane & 31;
   float sq = 0.f;
-  const bf16x8 zero8 = {};
+  const uint32_t m_head[2] = {(f >> 4) == 0 ? 0xffffffffu : 0u, (f >> 4) == 1 ? 0xffffffffu : 0u};
   const bf16x8 sel0 = sel_frag(0, lane), sel1 = sel_frag(1, lane);
+  bf16x8 selT;     // B operand: element p of lane (j, hh) is 1 where step 8 (p/4) + 4 hh + p%4 == j % 16
+#pragma unroll
+  for (int p = 0; p < 8; ++p) selT[p] = (8 * (p >> 2) + 4 * hh + (p & 3) == (lane & 15)) ? (__bf16)1.0f : (__bf16)0.0f;
   for (int64_t tile = (int64_t)blockIdx.x * nw + wave; tile < a.n_tiles; tile += (int64_t)gridDim.x * nw) {
     const TileRow r = tile_row(a.chunks, a.n_chunks, a.tile_ptr, tile, a.N, lane);
+    const uint32_t m_vert[2] = {r.a == 0 ? 0xffffffffu : 0u, r.a == 1 ? 0xffffffffu : 0u};
+    DyRaw raw[2];
+    raw[0] = load_dy_raw(a, r.row, 8 * hh, r.valid);
+    raw[1] = load_dy_raw(a, r.row, 16 + 8 * hh, r.valid);
     bf16x8 pf[8], pl[8];
     load_p_frags<true>(a.U, a.pos, r, hh, pf, pl);
 #pragma unroll 1
     for (int jb = 0; jb < 4; ++jb) {
+      // dL/dY of features [32 jb, 32 jb + 32): d8[c] = natural fragment kb = 2 jb + c; the next
+      // block's pieces are requested now
+      float d8[2][8];
+      dy_from_raw(a, raw[0], d8[0], sq);
+      dy_from_raw(a, raw[1], d8[1], sq);
+      if (jb < 3) {
+        raw[0] = load_dy_raw(a, r.row, (2 * jb + 2) * 16 + 8 * hh, r.valid);
+        raw[1] = load_dy_raw(a, r.row, (2 * jb + 3) * 16 + 8 * hh, r.valid);
+      }
       floatx16 q = {}, k = {}, v = {}, qt = {}, kt = {}, dyt = {};
 #pragma unroll
       for (int kb = 0; kb < 8; ++kb) {
@@ -110,13 +131,10 @@ __global__ __launch_bounds__(256) void k_temporal_bwd(TemporalBwdArgs a) {
         kt = mfma2a(pf[kb], pl[kb], wk, kt);
       }
       {
-        float d8[8];
         bf16x8 dh, dl;
-        load_dy<8>(a, r.row, (2 * jb) * 16 + 8 * hh, r.valid, d8, &sq);
-        split8(d8, dh, dl);
+        split8(d8[0], dh, dl);
         dyt = mfma2a(dh, dl, sel0, dyt);
-        load_dy<8>(a, r.row, (2 * jb + 1) * 16 + 8 * hh, r.valid, d8, &sq);
-        split8(d8, dh, dl);
+        split8(d8[1], dh, dl);
         dyt = mfma2a(dh, dl, sel1, dyt);
       }
       floatx16 dq = {}, dk = {}, dv = {};
@@ -126,10 +144,20 @@ __global__ __launch_bounds__(256) void k_temporal_bwd(TemporalBwdArgs a) {
         split8v(k, 8 * hd, kh, kl);
         split8v(q, 8 * hd, qh, ql);
         split8v(v, 8 * hd, vh, vl);
-        float d8[8];
-        load_dy<4>(a, r.row, jb * 32 + 16 * hd + 4 * hh, r.valid, d8, nullptr);
-        load_dy<4>(a, r.row, jb * 32 + 16 * hd + 8 + 4 * hh, r.valid, d8 + 4, nullptr);
-        split8(d8, dyh, dyl);
+        {
+          // dL/dY of the head's 16 dims in row-layout order: dims 8 c + 4 hh + e; the half c == hh is
+          // in the lane's own natural fragment, the other half in lane l^32's
+          float x[8];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float lo4 = d8[hd][e], hi4 = d8[hd][4 + e];   // static indices: a lane-dependent index
+            const float other = xor32(hh ? lo4 : hi4, hh);       // would be lowered to a chain of selects
+            const float own = hh ? hi4 : lo4;
+            x[e] = hh ? other : own;
+            x[4 + e] = hh ? own : other;
+          }
+          split8(x, dyh, dyl);
+        }
         floatx16 st = {}, dpt = {};
         st = mfma3(kh, kl, qh, ql, st);         // [key row][query row]
         dpt = mfma3(vh, vl, dyh, dyl, dpt);
@@ -141,14 +169,14 @@ __global__ __launch_bounds__(256) void k_temporal_bwd(TemporalBwdArgs a) {
           pr[p] = rk <= r.s ? 0.25f * (r.a ? st[8 + p] : st[p]) : -INFINITY;
           mx = fmaxf(mx, pr[p]);
         }
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        mx = fmaxf(mx, xor32(mx, hh));
         float sum = 0.f;
 #pragma unroll
         for (int p = 0; p < 8; ++p) {
           pr[p] = __expf(pr[p] - mx);
           sum += pr[p];
         }
-        sum += __shfl_xor(sum, 32);
+        sum += xor32(sum, hh);
         const float inv = 1.f / sum;
         float delta = 0.f;
 #pragma unroll
@@ -157,37 +185,40 @@ __global__ __launch_bounds__(256) void k_temporal_bwd(TemporalBwdArgs a) {
           dst[p] = r.a ? dpt[8 + p] : dpt[p];
           delta += pr[p] * dst[p];
         }
-        delta += __shfl_xor(delta, 32);
+        delta += xor32(delta, hh);
 #pragma unroll
         for (int p = 0; p < 8; ++p) dst[p] = 0.25f * pr[p] * (dst[p] - delta);
-        const float my_lse = mx + __logf(sum);
-        floatx16 s2 = {}, dp2 = {};
-        s2 = mfma3(qh, ql, kh, kl, s2);         // [query row][key row]
-        dp2 = mfma3(dyh, dyl, vh, vl, dp2);
-        float p2[8], ds2[8];
+        bf16x8 dsth, dstl, prh, prl;
+        split8(dst, dsth, dstl);
+        split8(pr, prh, prl);
+        // key-major copies: T[i = query row][j = key row]
+        floatx16 t0 = {}, t1 = {}, t2 = {}, t3 = {};
+        t0 = mfma(dsth, selT, t0);
+        t1 = mfma(dstl, selT, t1);
+        t2 = mfma(prh, selT, t2);
+        t3 = mfma(prl, selT, t3);
+        // own-vertex half of the registers, blended arithmetically (a select here gets merged with the
+        // packing below into per-element selects on 16-bit halves)
+        const float fa0 = r.a ? 0.f : 1.f, fa1 = 1.f - fa0;
+        float tx[4][8];
 #pragma unroll
         for (int p = 0; p < 8; ++p) {
-          const int sq_ = 8 * (p >> 2) + 4 * hh + (p & 3);    // query step of this register
-          const float lse = __shfl(my_lse, 16 * r.a + sq_), dl = __shfl(delta, 16 * r.a + sq_);
-          const float x = 0.25f * (r.a ? s2[8 + p] : s2[p]);
-          p2[p] = r.s <= sq_ ? __expf(x - lse) : 0.f;
-          ds2[p] = 0.25f * p2[p] * ((r.a ? dp2[8 + p] : dp2[p]) - dl);
+          tx[0][p] = fa0 * t0[p] + fa1 * t0[8 + p];
+          tx[1][p] = fa0 * t1[p] + fa1 * t1[8 + p];
+          tx[2][p] = fa0 * t2[p] + fa1 * t2[8 + p];
+          tx[3][p] = fa0 * t3[p] + fa1 * t3[8 + p];
         }
-        bf16x8 dsth, dstl, ds2h, ds2l, p2h, p2l;
-        split8(dst, dsth, dstl);
-        split8(ds2, ds2h, ds2l);
-        split8(p2, p2h, p2l);
-        const bool mine = (f >> 4) == hd;
+        const bf16x8 ds2h = pack8(tx[0]), ds2l = pack8(tx[1]), p2h = pack8(tx[2]), p2l = pack8(tx[3]);
 #pragma unroll
         for (int av = 0; av < 2; ++av) {
-          const bool myv = r.a == av;
+          const uint32_t mv = m_vert[av], mh = m_head[hd];
           bf16x8 ah, al;
           split8v(kt, 8 * av, ah, al);
-          dq = mfma3(mine ? ah : zero8, mine ? al : zero8, myv ? dsth : zero8, myv ? dstl : zero8, dq);
+          dq = mfma3(and_mask(ah, mh), and_mask(al, mh), and_mask(dsth, mv), and_mask(dstl, mv), dq);
           split8v(qt, 8 * av, ah, al);
-          dk = mfma3(mine ? ah : zero8, mine ? al : zero8, myv ? ds2h : zero8, myv ? ds2l : zero8, dk);
+          dk = mfma3(and_mask(ah, mh), and_mask(al, mh), and_mask(ds2h, mv), and_mask(ds2l, mv), dk);
           split8v(dyt, 8 * av, ah, al);
-          dv = mfma3(mine ? ah : zero8, mine ? al : zero8, myv ? p2h : zero8, myv ? p2l : zero8, dv);
+          dv = mfma3(and_mask(ah, mh), and_mask(al, mh), and_mask(p2h, mv), and_mask(p2l, mv), dv);
         }
       }
       if (r.valid) {

@@ -68,6 +68,14 @@ __device__ __forceinline__ void split8(const float* x, bf16x8& hi, bf16x8& lo) {
   }
 }
 
+// x where m is all ones, zero where m is zero (a select on the packed dwords: selecting on a
+// vector of eight 16-bit elements would be unpacked element by element)
+__device__ __forceinline__ bf16x8 and_mask(bf16x8 x, uint32_t m) {
+  uint4 u = __builtin_bit_cast(uint4, x);
+  u.x &= m; u.y &= m; u.z &= m; u.w &= m;
+  return __builtin_bit_cast(bf16x8, u);
+}
+
 __device__ __forceinline__ void split8v(const floatx16& v, int off, bf16x8& hi, bf16x8& lo) {
 #pragma unroll
   for (int p = 0; p < 8; ++p) {
