@@ -33,7 +33,7 @@ def test_exports_every_declared_symbol(lib):
 
 def _create(lib, desc_kw=None, chunks=((0, 4, 0, 2),), T=2, N=4, null_snapshot=False):
     d = dict(struct_kind=0, n_struct_layers=1, time_kind=1, dtype=0, F=8, S=32, H=32, act_hidden=0, act_out=0,
-             gather_mode=0, validate_level=0, rows_per_group=0, long_nnz=0, part_nnz=0, dense_kernel=0)
+             gather_mode=0, validate_level=0, rows_per_group=0, long_nnz=0, part_nnz=0, dense_kernel=0, heads=0)
     d.update(desc_kw or {})
     desc = binding.DescT(*[d[n] for n, _ in binding.DescT._fields_])
     fake = 0x1000  # never dereferenced: every check below fails before the device is used
@@ -53,8 +53,16 @@ def test_create_rejects_bad_descriptors(lib):
     assert _create(lib, dict(F=0))[0] == 1
     assert _create(lib, dict(n_struct_layers=3))[0] == 1
     assert _create(lib, dict(time_kind=9))[0] == 1
+    assert _create(lib, dict(dtype=7))[0] == 1
+    assert _create(lib, dict(struct_kind=5))[0] == 1
+    # graph attention, temporal self-attention and bf16 only come together, in one shape
     assert _create(lib, dict(dtype=1))[0] == 4
     assert _create(lib, dict(struct_kind=2))[0] == 4
+    assert _create(lib, dict(time_kind=3))[0] == 4
+    gat = dict(struct_kind=2, time_kind=3, dtype=1, F=128, S=128, H=128, heads=8)
+    assert _create(lib, dict(gat, heads=4))[0] == 4
+    assert _create(lib, dict(gat, F=64))[0] == 4
+    assert _create(lib, dict(gat), chunks=((0, 5, 0, 2),))[0] == 3
     assert _create(lib, dict(rows_per_group=64))[0] == 1
     assert _create(lib, null_snapshot=True)[0] == 1
 

@@ -201,3 +201,9 @@ def test_cache_is_a_constant_but_its_projection_carries_weight_gradient():
     X2[:, 5:] += 3.0          # inputs of vertices outside the only chunk are never read
     c = dysat.gradients(wl.graph, wl.chunks, wl.params, X2, wl.C, 2, dY=dY)["grads"]["gat.weight"]
     np.testing.assert_array_equal(a, c)
+
+
+def test_oracle_module_is_test_only():
+    import os
+    text = open(os.path.join(os.path.dirname(dysat.__file__), "dysat.py")).read()
+    assert "TEST INFRASTRUCTURE ONLY" in text and "paper_2309_03523_amd" not in text
