@@ -53,7 +53,7 @@ struct ProjArgs {
   const uint4* Wp;
   const float* a_src; const float* a_dst;
   const int32_t* owner; const int32_t* used_t; int32_t n_used; int64_t N;
-  uint16_t* zX; uint16_t* zC;
+  uint16_t* zX; uint16_t* zC;   // half precision
   float* sX;   // [T*N][16]: s_src[8], s_dst[8]
   float* sC;   // [T*N][8]:  s_src
 };
@@ -87,7 +87,7 @@ __global__ __launch_bounds__(256) void k_gat_project(ProjArgs a) {
       if (wr) {
 #pragma unroll
         for (int g = 0; g < 4; ++g)
-          *reinterpret_cast<uint2*>(z + jb * 32 + 8 * g + 4 * hh) = pack4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
+          *reinterpret_cast<uint2*>(z + jb * 32 + 8 * g + 4 * hh) = packh4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
       }
 #pragma unroll
       for (int hd = 0; hd < 2; ++hd) {
@@ -182,8 +182,8 @@ __device__ __forceinline__ SoftAcc gat_row_range(const GatArgs& a, const Segment
       for (int q = 0; q < 8; ++q) {
         const float p = __expf(ev[q] - mn);
         r.l += p;
-        r.a0 += p * bf_lo(zz[q]);
-        r.a1 += p * bf_hi(zz[q]);
+        r.a0 += p * h_lo(zz[q]);
+        r.a1 += p * h_hi(zz[q]);
       }
     }
   }

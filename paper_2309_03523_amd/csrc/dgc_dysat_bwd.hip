@@ -510,7 +510,9 @@ __device__ __forceinline__ float gat_bwd_row_range(const GatBwdRowsArgs& a, cons
       if (q0 + slot < cnt) {
         const bool in = j >= s.v_lo && j < s.v_hi;
         float z[16];
-        load16((in ? a.zX : a.zC) + (base + j) * kS + 16 * h, z);
+        const uint16_t* zp = (in ? a.zX : a.zC) + (base + j) * kS + 16 * h;   // half precision
+        unpackh8(reinterpret_cast<const uint4*>(zp)[0], z);
+        unpackh8(reinterpret_cast<const uint4*>(zp)[1], z + 8);
         const float ss = in ? a.sX[(base + j) * 16 + h] : a.sC[(base + j) * 8 + h];
         const float e = sd + ss;
         const float al = __expf(lrelu(e) - lse);
@@ -638,8 +640,8 @@ __device__ __forceinline__ ColOwn col_own(const GatBwdColsArgs& a, int64_t row, 
   // zX / sX of a vertex no chunk covers hold stale values: they are never used (no neighbour
   // can be "of the same chunk"), and loading them unconditionally keeps the loads independent
   o.oj = a.owner[row];
-  unpack8(*reinterpret_cast<const uint4*>(a.zC + row * kS + 8 * sub), o.zc);
-  unpack8(*reinterpret_cast<const uint4*>(a.zX + row * kS + 8 * sub), o.zx);
+  unpackh8(*reinterpret_cast<const uint4*>(a.zC + row * kS + 8 * sub), o.zc);
+  unpackh8(*reinterpret_cast<const uint4*>(a.zX + row * kS + 8 * sub), o.zx);
   o.ssx = a.sX[row * 16 + head];
   o.ssc = a.sC[row * 8 + head];
   return o;
@@ -869,12 +871,12 @@ __global__ __launch_bounds__(256) void k_att_grad(AttGradArgs a) {
       const int64_t row = (int64_t)a.used_t[idx / a.N] * a.N + idx % a.N;
       const uint32_t zc = *reinterpret_cast<const uint32_t*>(a.zC + row * kS + 2 * lane);
       const float dsc = a.dss[row * 16 + 8 + head];
-      gs0 += dsc * bf_lo(zc); gs1 += dsc * bf_hi(zc);
+      gs0 += dsc * h_lo(zc); gs1 += dsc * h_hi(zc);
       if (a.owner[row] >= 0) {
         const uint32_t zx = *reinterpret_cast<const uint32_t*>(a.zX + row * kS + 2 * lane);
         const float dsx = a.dss[row * 16 + head], dsd = a.st2[row * 8 + head].w;
-        gs0 += dsx * bf_lo(zx); gs1 += dsx * bf_hi(zx);
-        gd0 += dsd * bf_lo(zx); gd1 += dsd * bf_hi(zx);
+        gs0 += dsx * h_lo(zx); gs1 += dsx * h_hi(zx);
+        gd0 += dsd * h_lo(zx); gd1 += dsd * h_hi(zx);
       }
     }
   }

@@ -50,6 +50,23 @@ __device__ __forceinline__ void unpack8(uint4 u, float* x) {
   x[0] = bf_lo(u.x); x[1] = bf_hi(u.x); x[2] = bf_lo(u.y); x[3] = bf_hi(u.y);
   x[4] = bf_lo(u.z); x[5] = bf_hi(u.z); x[6] = bf_lo(u.w); x[7] = bf_hi(u.w);
 }
+// The projections z are kept in IEEE half precision: they are O(1) values that only the vector
+// units read (the neighbour gathers), so the format is free, and at the same 2 bytes per element
+// half precision rounds four times finer than bf16; the rounding of z is what dominates the error
+// of the whole layer.
+typedef _Float16 halfx2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float h_lo(uint32_t u) { return (float)__builtin_bit_cast(halfx2, u)[0]; }
+__device__ __forceinline__ float h_hi(uint32_t u) { return (float)__builtin_bit_cast(halfx2, u)[1]; }
+__device__ __forceinline__ uint32_t packh2(float a, float b) {
+  halfx2 v = {(_Float16)a, (_Float16)b};
+  return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ uint2 packh4(float a, float b, float c, float d) { return make_uint2(packh2(a, b), packh2(c, d)); }
+__device__ __forceinline__ void unpackh8(uint4 u, float* x) {
+  x[0] = h_lo(u.x); x[1] = h_hi(u.x); x[2] = h_lo(u.y); x[3] = h_hi(u.y);
+  x[4] = h_lo(u.z); x[5] = h_hi(u.z); x[6] = h_lo(u.w); x[7] = h_hi(u.w);
+}
+
 __device__ __forceinline__ floatx16 mfma(bf16x8 a, bf16x8 b, floatx16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }

@@ -205,7 +205,7 @@ struct DysatWs {
   float* G[DY_NPAR];         // their gradients
   uint4 *Wp, *Wqp, *Wkp, *Wvp;   // bf16 operand fragments (row operand)
   uint4 *WqT, *WkT, *WvT;        // bf16 fragments of the transposes (backward)
-  uint16_t *zX, *zC;         // [T*N][128] bf16 projections of input and cache rows
+  uint16_t *zX, *zC;         // [T*N][128] half-precision projections of input and cache rows
   float *sX, *sC;            // attention scalars
   float* U;                  // [T*N][128] fp32 structure-encoder output before ELU
   float* lse;                // [T*N][8]
