@@ -235,12 +235,18 @@ def dysat_main(args):
     layer.set_profiling(False)
     names = ["project", "edge_softmax", "temporal_fwd", "temporal_bwd", "gat_bwd_rows", "gat_bwd_cols"]
     per_row = dysat_stage_bytes(nnz / rows)
+    try:      # HBM bytes per launch measured with rocprofv3 --pmc (profiles/), for the workload they were taken on
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
+            measured = json.load(f).get(args.workload, {})
+    except (OSError, ValueError):
+        measured = {}
     kernels = {}
     for i, nm in enumerate(names):
         ms = float(stage[7 + i])
         ach = per_row[nm] * rows / (ms * 1e-3) / 1e9
         kernels[nm] = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
-                       "ms_per_launch": ms, "bytes_per_row": per_row[nm], "traffic": None}
+                       "ms_per_launch": ms, "bytes_per_row": per_row[nm],
+                       "traffic": measured.get(nm, {}).get("total")}
     for nm in ("edge_softmax", "gat_bwd_rows", "gat_bwd_cols"):
         gather = (nnz / rows) * (256 + 32 + (96 if nm == "gat_bwd_cols" else 0)) * rows
         kernels[nm]["gather_traffic_GBps"] = gather / (kernels[nm]["ms_per_launch"] * 1e-3) / 1e9
