@@ -29,7 +29,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config2s", "config3w", "config4s", "config5s", "config5"])
+    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config2s", "config3w", "config4s", "config4", "config5s", "config5"])
     ap.add_argument("--gather-mode", default="in_place", choices=["in_place", "staged"])
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -42,6 +42,7 @@ def parse_args():
 
 def make_workload(name: str, seed: int):
     from paper_2309_03523_amd import synth
+    synth.progress = lambda msg: print(msg, file=sys.stderr, flush=True)
     if name == "config1":
         return synth.config1(seed), "config1: 8 snapshots x 1000 vertices, ER avg deg 8, F=S=H=32, 4 chunks"
     if name == "config2s":
@@ -49,10 +50,12 @@ def make_workload(name: str, seed: int):
     if name == "config3w":
         return synth.config3(seed, scale=0.125), ("config3 at 1/8 of its vertex count, one 32-snapshot window: 250k "
                                                   "vertices, 2 GCN layers (172->128->128) + LSTM, 64 uneven ranges")
-    if name == "config4s":
-        wl, target = synth.config4(seed, scale=0.125)
+    if name in ("config4s", "config4"):
+        scale = 0.125 if name == "config4s" else 1.0
+        wl, target = synth.config4(seed, scale=scale)
         wl.notes["target"] = target
-        return wl, ("config4 at 1/8 of its vertex count: EvolveGCN-O, 64 snapshots x 62.5k vertices, avg degree 16, "
+        return wl, (("config4 at 1/8 of its vertex count" if name == "config4s" else "config4") +
+                    f": EvolveGCN-O, 64 snapshots x {wl.graph.N} vertices, avg degree 16, "
                     "F = S = 256, 32 chunks, forward + backward (MSE)")
     return synth.config2(seed), ("config2: 32 snapshots x 100k vertices, lognormal edge counts, power-law "
                                  "degrees (tail 2.1), F=S=H=128, GCN+GRU, 64 chunks = 4 windows of 8 x 16 "
@@ -201,6 +204,7 @@ def dysat_main(args):
     from paper_2309_03523_amd.runner import DysatDevice
 
     scale = 1.0 if args.workload == "config5" else 0.25
+    synth.progress = lambda msg: print(msg, file=sys.stderr, flush=True)
     t0 = time.perf_counter()
     wl, target = synth.config5(args.seed, scale)
     t_gen = time.perf_counter() - t0

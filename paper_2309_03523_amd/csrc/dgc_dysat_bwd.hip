@@ -864,20 +864,31 @@ __global__ __launch_bounds__(256) void k_att_grad(AttGradArgs a) {
   const int64_t n_rows = a.N * a.n_used;
   float gs0 = 0.f, gs1 = 0.f, gd0 = 0.f, gd1 = 0.f;
   for (int64_t r0 = wave * 8; r0 < n_rows; r0 += n_waves * 8) {
+    // eight rows in flight: all loads first (rows past the end and the input-side data of rows no
+    // chunk covers are read from a valid row and weighted by zero)
+    uint32_t zc[8], zx[8];
+    float dsc[8], dsx[8], dsd[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
-      const int64_t idx = r0 + k;
-      if (idx >= n_rows) break;
+      const int64_t idx = min(r0 + k, n_rows - 1);
       const int64_t row = (int64_t)a.used_t[idx / a.N] * a.N + idx % a.N;
-      const uint32_t zc = *reinterpret_cast<const uint32_t*>(a.zC + row * kS + 2 * lane);
-      const float dsc = a.dss[row * 16 + 8 + head];
-      gs0 += dsc * h_lo(zc); gs1 += dsc * h_hi(zc);
-      if (a.owner[row] >= 0) {
-        const uint32_t zx = *reinterpret_cast<const uint32_t*>(a.zX + row * kS + 2 * lane);
-        const float dsx = a.dss[row * 16 + head], dsd = a.st2[row * 8 + head].w;
-        gs0 += dsx * h_lo(zx); gs1 += dsx * h_hi(zx);
-        gd0 += dsd * h_lo(zx); gd1 += dsd * h_hi(zx);
-      }
+      const float live = r0 + k < n_rows ? 1.f : 0.f;
+      const float cov = a.owner[row] >= 0 ? live : 0.f;
+      zc[k] = *reinterpret_cast<const uint32_t*>(a.zC + row * kS + 2 * lane);
+      zx[k] = *reinterpret_cast<const uint32_t*>(a.zX + row * kS + 2 * lane);
+      dsc[k] = live * a.dss[row * 16 + 8 + head];
+      dsx[k] = cov * a.dss[row * 16 + head];
+      dsd[k] = cov * a.st2[row * 8 + head].w;
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      // 0 * (stale value) must stay 0: the input-side buffers of uncovered rows are never written
+      const float x0 = dsx[k] != 0.f || dsd[k] != 0.f ? h_lo(zx[k]) : 0.f;
+      const float x1 = dsx[k] != 0.f || dsd[k] != 0.f ? h_hi(zx[k]) : 0.f;
+      gs0 += dsc[k] * h_lo(zc[k]) + dsx[k] * x0;
+      gs1 += dsc[k] * h_hi(zc[k]) + dsx[k] * x1;
+      gd0 += dsd[k] * x0;
+      gd1 += dsd[k] * x1;
     }
   }
   float* o = a.da_partial + wave * 2 * kS;

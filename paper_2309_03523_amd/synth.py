@@ -228,7 +228,25 @@ class Workload:
         return int(((c[:, 1] - c[:, 0]) * (c[:, 3] - c[:, 2])).sum())
 
 
+# Optional progress sink for the large generators: set to a callable taking one string (bench.py
+# points it at stderr so that a long generation is seen to be alive); None = silent.
+progress = None
+
+
+def _say(msg: str) -> None:
+    if progress is not None:
+        progress(msg)
+
+
 def _normal_f32(rng: np.random.Generator, shape) -> np.ndarray:
+    """N(0,1) fp32.  Tensors [T, ...] are drawn snapshot by snapshot (the same stream as one call)."""
+    if len(shape) == 3 and shape[0] > 1:
+        out = np.empty(shape, np.float32)
+        for t in range(shape[0]):
+            out[t] = rng.standard_normal(size=shape[1:], dtype=np.float32)
+            if (t + 1) % 8 == 0:
+                _say(f"  normal tensor {tuple(shape)}: {t + 1}/{shape[0]} snapshots")
+        return out
     return rng.standard_normal(size=shape, dtype=np.float32)
 
 
@@ -353,7 +371,12 @@ def config4(seed: int = 0, scale: float = 1.0, random_bias: bool = False):
     N = max(256, int(500_000 * scale))
     g_rng = stream(seed, "graph")
     w = powerlaw_weights(N, 2.2, stream(seed, "perm"))
-    graph = DynamicGraph(N, [chung_lu_snapshot(N, 8 * N, w, g_rng) for _ in range(T)])
+    snaps = []
+    for t in range(T):
+        snaps.append(chung_lu_snapshot(N, 8 * N, w, g_rng))
+        if (t + 1) % 8 == 0:
+            _say(f"  graph: {t + 1}/{T} snapshots")
+    graph = DynamicGraph(N, snaps)
     bounds = [np.linspace(0, N, 9).astype(np.int64)] * 4
     chunks = grid_chunks(T, 16, bounds)
     X = _normal_f32(stream(seed, "feat"), (T, N, F))
@@ -464,7 +487,12 @@ def config5(seed: int = 0, scale: float = 1.0):
     N = max(1024, int(1_000_000 * scale))
     g_rng = stream(seed, "graph")
     w = powerlaw_weights(N, 2.1, stream(seed, "perm"))
-    graph = DynamicGraph(N, [chung_lu_snapshot(N, 6 * N, w, g_rng) for _ in range(T)])
+    snaps = []
+    for t in range(T):
+        snaps.append(chung_lu_snapshot(N, 6 * N, w, g_rng))
+        if (t + 1) % 4 == 0:
+            _say(f"  graph: {t + 1}/{T} snapshots")
+    graph = DynamicGraph(N, snaps)
     bounds = [uneven_ranges(N, 128, stream(seed, "ranges"))]
     chunks = grid_chunks(T, 16, bounds)
     X = _normal_f32(stream(seed, "feat"), (T, N, F))
@@ -477,3 +505,14 @@ def config5(seed: int = 0, scale: float = 1.0):
                   X, C, None, None, dysat_params(seed, T, F, F, heads))
     wl.notes["heads"] = heads
     return wl, target
+
+
+# --------------------------------------------------------------------------- vertex presence
+
+
+def presence(seed: int, T: int, N: int, p_lo: float = 0.15, p_hi: float = 1.0) -> np.ndarray:
+    """uint8 [T,N]: vertex i is present in snapshot t with its own probability p_i ~ U(p_lo, p_hi),
+    independently per snapshot: sequences of very different lengths, with gaps."""
+    rng = stream(seed, "presence")
+    p = rng.uniform(p_lo, p_hi, size=N)
+    return (rng.random((T, N)) < p[None, :]).astype(np.uint8)
