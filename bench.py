@@ -29,7 +29,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config2s", "config3w", "config4s", "config4", "config5s", "config5"])
+    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config2s", "config2tf", "config3w", "config4s", "config4", "config5s", "config5"])
     ap.add_argument("--gather-mode", default="in_place", choices=["in_place", "staged"])
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -47,6 +47,12 @@ def make_workload(name: str, seed: int):
         return synth.config1(seed), "config1: 8 snapshots x 1000 vertices, ER avg deg 8, F=S=H=32, 4 chunks"
     if name == "config2s":
         return synth.config2(seed, scale=0.05), "config2 at 1/20 scale"
+    if name == "config2tf":
+        wl = synth.config2(seed)
+        wl.H0 = None      # fused sequences start from a zero state
+        wl.notes["present"] = synth.presence(seed, wl.graph.T, wl.graph.N)
+        return wl, ("config2 with temporal fusion: every vertex present in a snapshot with its own probability "
+                    "U(0.15, 1); sequences concatenated into lanes of 8 (first-fit decreasing) instead of padded")
     if name == "config3w":
         return synth.config3(seed, scale=0.125), ("config3 at 1/8 of its vertex count, one 32-snapshot window: 250k "
                                                   "vertices, 2 GCN layers (172->128->128) + LSTM, 64 uneven ranges")
@@ -289,6 +295,36 @@ def dysat_main(args):
     print(json.dumps(out))
 
 
+def cpu_baseline_tfusion(wl, Y_gpu, seed: int) -> dict:
+    """Oracle of the temporally fused layer on a seeded sample of vertices of every chunk:
+    structure encoder by the C oracle, then every sampled vertex's own sequence."""
+    import numpy as np
+    import oracle
+    from oracle import tfusion
+    from paper_2309_03523_amd import synth
+    rng = synth.stream(seed, "bench-sample")
+    present = wl.notes["present"]
+    sub = [np.sort(rng.choice(int(c[1] - c[0]), size=min(int(c[1] - c[0]), 48), replace=False)) + int(c[0])
+           for c in wl.chunks]
+    t0 = time.perf_counter()
+    Z = oracle.forward(wl.graph, wl.chunks, wl.params, wl.X, wl.C, time_kind="none", n_struct_layers=1,
+                       act_hidden="relu", act_out="none", subset=sub)
+    mask = np.zeros(present.shape, np.uint8)
+    for c, s in zip(wl.chunks, sub):
+        mask[c[2]:c[3], s] = present[c[2]:c[3], s]
+    want = tfusion.run_separate(np.nan_to_num(Z).astype(np.float64), mask, wl.chunks, wl.params, wl.time_kind)
+    dt = time.perf_counter() - t0
+    m = ~np.isnan(want)
+    w = want[m]
+    tau = 0.1 * float(np.sqrt(np.mean(w * w)))
+    err = float(np.max(np.abs(Y_gpu[m] - w) / np.maximum(np.abs(w), tau)))
+    n_rows = int(m.any(axis=2).sum())
+    return {"value": n_rows / dt, "unit": "embeddings/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"48 seeded random vertices of each of the {len(wl.chunks)} chunks, their present snapshots = "
+                      f"{n_rows} rows, {dt:.1f} s (structure encoder in C with OpenMP, sequences in NumPy)",
+            "gpu_max_rel_err_on_sample": err}
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -326,6 +362,23 @@ def main():
     t_create = time.perf_counter() - t0
     layer = dw.layer
     stream = torch.cuda.current_stream()
+    tfuse = None
+    if "present" in wl.notes:
+        present = wl.notes["present"]
+        t0 = time.perf_counter()
+        layer.set_presence(torch.from_numpy(present).cuda())
+        cov = np.zeros(present.shape, bool)
+        for v_lo, v_hi, t_lo, t_hi in wl.chunks.tolist():
+            cov[t_lo:t_hi, v_lo:v_hi] = True
+        padded_rows = rows
+        rows = int((present.astype(bool) & cov).sum())       # embeddings actually produced
+        n_lanes = int(layer.packing("lane_ptr")[-1])
+        window = int((wl.chunks[:, 3] - wl.chunks[:, 2]).max())
+        live = present.astype(bool) & cov
+        nnz_present = int(sum(int(np.diff(sn.rowptr)[live[t]].sum()) for t, sn in enumerate(wl.graph.snaps)))
+        tfuse = {"present_rows": rows, "padded_rows": padded_rows, "nnz_present_rows": nnz_present, "lanes": n_lanes,
+                 "lane_slots": n_lanes * window, "lane_fill": rows / max(1, n_lanes * window),
+                 "pack_s": time.perf_counter() - t0}
 
     def step():
         layer.forward(dw.X, dw.C, dw.Y, C1=dw.C1, H0=dw.H0, stream=stream)
@@ -364,8 +417,9 @@ def main():
         return
     fl = flops_per_row(wl)
     # the last dense launch: last GCN layer's transform + time encoder
-    dense_flops = (fl["transform"] + fl["rnn"]) * rows if wl.n_struct_layers == 1 else \
-        (2 * wl.S * wl.S + fl["rnn"]) * rows
+    dense_rows = tfuse["lane_slots"] if tfuse else rows     # the kernel also computes the empty slots
+    dense_flops = (fl["transform"] + fl["rnn"]) * dense_rows if wl.n_struct_layers == 1 else \
+        (2 * wl.S * wl.S + fl["rnn"]) * dense_rows
     dense_ms = float(stage[3])
     achieved = dense_flops / (dense_ms * 1e-3) / 1e12
     traffic = measured_traffic(args.workload, args.gather_mode)
@@ -375,13 +429,20 @@ def main():
                 "flops_per_launch": dense_flops, "ms_per_launch": dense_ms}
     # aggregation kernels: algorithmic (compulsory) bytes = X rows once + CSR + M written once
     nnz = int(layer.packing("seg_nnz_off")[-1])
-    agg_bytes = rows * (wl.F * 4) + nnz * 4 + rows * 8 + rows * (wl.F * 4)
+    if tfuse:
+        # only the rows of present vertices are aggregated (and written, in lane order); every
+        # row of X can still be somebody's neighbour
+        nnz_agg = tfuse["nnz_present_rows"]
+        agg_bytes = tfuse["padded_rows"] * (wl.F * 4) + nnz_agg * 4 + rows * 8 + rows * (wl.F * 4)
+    else:
+        nnz_agg = nnz
+        agg_bytes = rows * (wl.F * 4) + nnz * 4 + rows * 8 + rows * (wl.F * 4)
     agg_ms = float(stage[0])
     agg = {"kernel": "k_spmm_short + k_spmm_long + k_spmm_long_reduce", "bound": "hbm",
            "achieved": agg_bytes / (agg_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
            "frac": agg_bytes / (agg_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": traffic.get("aggregation"),
            "bytes_per_launch": agg_bytes, "ms_per_launch": agg_ms,
-           "gather_traffic_GBs": nnz * wl.F * 4 / (agg_ms * 1e-3) / 1e9, "nnz": nnz}
+           "gather_traffic_GBs": nnz_agg * wl.F * 4 / (agg_ms * 1e-3) / 1e9, "nnz": nnz_agg}
 
     out = {"metric": "snapshot-vertex embeddings/s per DGNN layer", "value": value, "unit": "embeddings/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -393,9 +454,15 @@ def main():
            "stage_ms": {"aggregate0": float(stage[0]), "dense0": float(stage[1]), "aggregate1": float(stage[2]),
                         "dense_rnn": float(stage[3])},
            "setup_s": {"generate": t_gen, "upload_create_pack": t_create}}
+    if tfuse:
+        out["temporal_fusion"] = tfuse
+        out["roofline"]["kernel"] += " over the lanes, incl. the scatter of the outputs back to their rows"
     if not args.no_cpu_baseline:
         Y_gpu = dw.Y.cpu().numpy()
-        out["cpu_baseline"] = cpu_baseline(wl, Y_gpu, args.cpu_seconds, args.seed)
+        if tfuse:
+            out["cpu_baseline"] = cpu_baseline_tfusion(wl, Y_gpu, args.seed)
+        else:
+            out["cpu_baseline"] = cpu_baseline(wl, Y_gpu, args.cpu_seconds, args.seed)
     print(json.dumps(out))
 
 

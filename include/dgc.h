@@ -165,6 +165,20 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* layer, const void* X, int64_t ldx, c
                                const uint8_t* reset_mask, void* Y, int64_t ldy, float* HN,
                                void* stream);
 
+/* Temporal fusion (Section 5.1.2).  present device uint8 [T,N]: a non-zero byte says that vertex
+ * i exists in snapshot t.  The sequence of a vertex in a chunk is then the ascending list of the
+ * window's snapshots in which it is present; instead of padding every sequence to the window,
+ * the sequences of a chunk are concatenated into lanes as long as the window (first-fit
+ * decreasing: sequences by length descending then vertex ascending, each into the first lane in
+ * order of creation with room for all of it) and the first slot of every sequence carries a reset
+ * flag (the paper's mask: the state entering that step is zero).  After this call
+ * dgc_layer_forward runs the time encoder over the lanes: Y is written only for present rows of
+ * the chunks, a vertex's state is carried over the snapshots it is absent from, and H0, HN and
+ * reset_mask must be NULL.  For DGC_STRUCT_GCN with DGC_TIME_GRU / DGC_TIME_LSTM; can be called
+ * once per layer (DGC_ERR_STATE otherwise); `present` is only read during the call.
+ * Synchronises `stream`. */
+dgc_status_t dgc_layer_set_presence(dgc_layer_t* layer, const uint8_t* present, void* stream);
+
 /* Backward pass: gradients of a scalar loss with respect to the layer's parameters, for the
  * batch of the last dgc_layer_forward on this layer (the layer keeps the aggregated rows of that
  * pass; a forward in between invalidates them).  Built for DGC_STRUCT_EVOLVE_GCN_O and
@@ -225,6 +239,9 @@ dgc_status_t dgc_layer_stage_times(dgc_layer_t* layer, float* host_ms);
  *  "work_short" int32 [n][3] (segment, first local row, rows)
  *  "work_long"  int32 [n][4] (segment, local row, part, parts)
  *  "deg_inv_sqrt" fp32 [T*N]
+ *  after dgc_layer_set_presence (DGC_ERR_STATE before): "lane_ptr" int64 [n_chunks+1] first lane of
+ *  every chunk; "slot_row" int64 [Lmax][n_lanes] (Lmax = longest window, n_lanes = lane_ptr[n_chunks]):
+ *  t*N + i of the row in that slot, -1 = empty; "slot_reset" uint8 [Lmax][n_lanes]
  * *needed_bytes (may be NULL) receives the array's size; data is copied only if
  * capacity_bytes is large enough (else DGC_ERR_INVALID_ARG, with *needed_bytes set).
  * Segments are ordered by chunk as given, then snapshot ascending. */

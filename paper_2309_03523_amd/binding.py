@@ -27,7 +27,7 @@ STATUS = {0: "DGC_OK", 1: "DGC_ERR_INVALID_ARG", 2: "DGC_ERR_BAD_GRAPH", 3: "DGC
 
 EXPORTS = ["dgc_layer_create", "dgc_layer_destroy", "dgc_layer_set_param", "dgc_layer_get_param",
            "dgc_layer_forward", "dgc_layer_backward", "dgc_layer_aggregate", "dgc_layer_gather",
-           "dgc_layer_packing", "dgc_layer_set_profiling", "dgc_layer_stage_times", "dgc_last_error",
+           "dgc_layer_packing", "dgc_layer_set_presence", "dgc_layer_set_profiling", "dgc_layer_stage_times", "dgc_last_error",
            "dgc_version"]
 N_STAGES = 13
 
@@ -76,6 +76,7 @@ def load() -> ct.CDLL:
     lib.dgc_layer_aggregate.argtypes = [vp, vp, i64, vp, i64, vp, i64, vp]
     lib.dgc_layer_gather.argtypes = [vp, vp, i64, vp, i64, vp]
     lib.dgc_layer_packing.argtypes = [vp, ct.c_char_p, vp, i64, ct.POINTER(i64)]
+    lib.dgc_layer_set_presence.argtypes = [vp, vp, vp]
     lib.dgc_layer_set_profiling.argtypes = [vp, i32]
     lib.dgc_layer_stage_times.argtypes = [vp, vp]
     lib.dgc_last_error.argtypes = [vp]
@@ -118,7 +119,8 @@ def _ld(t, name: str) -> int:
 
 _PACK_DTYPES = {"seg_row_off": np.int64, "seg_nnz_off": np.int64, "halo_ptr": np.int64,
                 "halo_idx": np.int32, "col_local": np.int32, "work_short": np.int32,
-                "work_long": np.int32, "deg_inv_sqrt": np.float32}
+                "work_long": np.int32, "deg_inv_sqrt": np.float32, "lane_ptr": np.int64, "slot_row": np.int64,
+                "slot_reset": np.uint8}
 
 
 class DgcLayer:
@@ -205,6 +207,12 @@ class DgcLayer:
             self._h, _dev(Y, "Y"), _ld(Y, "Y"), _dev(dY, "dY"), _ld(dY, "dY"), _dev(target, "target"),
             _ld(target, "target"), _dev(loss_out, "loss_out"), _dev(dX, "dX"), _ld(dX, "dX"), _stream_ptr(stream)))
 
+    def set_presence(self, present, stream=None):
+        """present: uint8 device tensor [T,N]; switches the layer to temporal fusion."""
+        if not present.is_cuda or present.dtype.itemsize != 1 or not present.is_contiguous():
+            raise ValueError("present must be a contiguous uint8 device tensor [T,N]")
+        self._check(self._lib.dgc_layer_set_presence(self._h, _dev(present, "present"), _stream_ptr(stream)))
+
     def aggregate(self, X, C, M, stream=None):
         self._check(self._lib.dgc_layer_aggregate(self._h, _dev(X, "X"), _ld(X, "X"), _dev(C, "C"), _ld(C, "C"),
                                                   _dev(M, "M"), int(M.stride(0)), _stream_ptr(stream)))
@@ -228,7 +236,9 @@ class DgcLayer:
     # -- inspection
     def packing(self, what: str) -> np.ndarray:
         need = ct.c_int64(0)
-        self._lib.dgc_layer_packing(self._h, what.encode(), None, 0, ct.byref(need))
+        rc = self._lib.dgc_layer_packing(self._h, what.encode(), None, 0, ct.byref(need))
+        if rc not in (0, 1):     # 1 = destination too small: the size query itself
+            self._check(rc)
         dt = np.dtype(_PACK_DTYPES[what])
         out = np.zeros(need.value // dt.itemsize, dt)
         if out.size:

@@ -4,6 +4,7 @@
 #include <cstring>
 #include <map>
 #include <new>
+#include <set>
 
 #include "dgc_internal.h"
 
@@ -56,6 +57,8 @@ struct dgc_layer {
   DysatWs dy{};                                  // graph attention + temporal attention workspace
   hipEvent_t evd[8] = {};                        // its stage boundaries: forward 0..3, backward 4..7
   bool evd_fwd = false, evd_bwd = false;
+  TFusion tf{};                                  // temporal-fusion packing (dgc_layer_set_presence)
+  std::vector<ChunkInfo> cinfo_host;
   bool has_grads = false;
   std::map<std::string, Param> params;
   bool forward_done = false;
@@ -413,6 +416,7 @@ dgc_status_t build_layer(dgc_layer* L, const dgc_graph_t* graph, hipStream_t st)
     }
     state_off += c.v_hi - c.v_lo;
   }
+  L->cinfo_host = cinfo;
   L->nseg = (int64_t)segs.size();
   L->total_rows = row_off;
   L->total_state_rows = state_off;
@@ -580,13 +584,15 @@ SpmmArgs spmm_args(dgc_layer* L, const float* fresh, int64_t ld_fresh, const flo
   a.long_nnz = L->long_nnz; a.part_nnz = L->part_nnz;
   a.partial = L->d_partial;
   a.M = M; a.ldm = ldm;
+  a.row_map = nullptr;
   return a;
 }
 
 // aggregation of one GCN layer, with or without the staged gather
 void run_aggregate(dgc_layer* L, const float* fresh, int64_t ld_fresh, const float* stale, int64_t ld_stale,
-                   int32_t F, float* M, int64_t ldm, hipStream_t st) {
+                   int32_t F, float* M, int64_t ldm, hipStream_t st, const int64_t* row_map = nullptr) {
   SpmmArgs a = spmm_args(L, fresh, ld_fresh, stale, ld_stale, F, M, ldm);
+  a.row_map = row_map;
   if (L->desc.gather_mode == DGC_GATHER_STAGED) {
     launch_gather(L->d_segs, L->nseg, L->d_halo_idx, L->d_halo_ptr, L->total_halo, L->N, stale, ld_stale, F,
                   L->d_halo, L->ld_halo, st);
@@ -777,7 +783,10 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* L, const void* Xv, int64_t ldx, cons
     if (prof) { DGC_HIP_TRY(hipEventRecord(L->evx[1], st)); L->evx_fwd = true; }
   }
   if (prof) DGC_HIP_TRY(hipEventRecord(L->ev[0], st));
-  run_aggregate(L, X, ldx, C, ldc, d.F, L->d_M, L->ldm, st);
+  // with temporal fusion the aggregation that feeds the time encoder writes its rows in lane
+  // order and skips the rows of absent vertices
+  const bool tfl1 = L->tf.built && d.n_struct_layers == 1, tfl2 = L->tf.built && d.n_struct_layers == 2;
+  run_aggregate(L, X, ldx, C, ldc, d.F, tfl1 ? L->tf.Mv : L->d_M, L->ldm, st, tfl1 ? L->tf.row_map : nullptr);
   if (prof) DGC_HIP_TRY(hipEventRecord(L->ev[1], st));
   const char* last = "gcn0";
   if (d.n_struct_layers == 2) {
@@ -788,7 +797,7 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* L, const void* Xv, int64_t ldx, cons
     da.Y = L->d_Z1; da.ldy = d.S;
     if (!launch_dense(da, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
     if (prof) DGC_HIP_TRY(hipEventRecord(L->ev[2], st));
-    run_aggregate(L, L->d_Z1, d.S, C1, ldc1, d.S, L->d_M, L->ldm, st);
+    run_aggregate(L, L->d_Z1, d.S, C1, ldc1, d.S, tfl2 ? L->tf.Mv : L->d_M, L->ldm, st, tfl2 ? L->tf.row_map : nullptr);
     if (prof) DGC_HIP_TRY(hipEventRecord(L->ev[3], st));
     last = "gcn1";
   } else if (prof) {
@@ -813,7 +822,18 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* L, const void* Xv, int64_t ldx, cons
     da.bih = L->params["rnn.bias_ih"].raw; da.bhh = L->params["rnn.bias_hh"].raw;
   }
   da.H0 = H0; da.reset_mask = reset_mask; da.Y = Y; da.ldy = ldy; da.HN = HN;
-  if (!launch_dense(da, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
+  if (L->tf.built) {
+    // temporal fusion: the dense + recurrent kernels over the lanes of every chunk with the
+    // packing's reset flags, outputs back to their (snapshot, vertex) rows
+    const TFusion& tf = L->tf;
+    if (H0 || HN || reset_mask)
+      return fail(DGC_ERR_INVALID_ARG, "with temporal fusion H0, HN and reset_mask must be NULL");
+    da.tiles = tf.tiles_v; da.n_tiles = tf.n_tiles_v; da.tiles32 = tf.tiles32_v; da.n_tiles32 = tf.n_tiles32_v;
+    da.chunks = tf.chunks_v; da.N = tf.n_lanes; da.total_state_rows = tf.n_lanes;
+    da.M = tf.Mv; da.reset_mask = tf.slot_reset; da.Y = tf.Yv; da.ldy = out_dim;
+    if (tf.n_lanes > 0 && !launch_dense(da, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
+    tf_scatter(tf.Yv, out_dim, tf.slot_row, (int64_t)tf.Lmax * tf.n_lanes, Y, ldy, st);
+  } else if (!launch_dense(da, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
   if (prof) {
     DGC_HIP_TRY(hipEventRecord(L->ev[4], st));
     L->ev_valid = true;
@@ -914,6 +934,98 @@ dgc_status_t dgc_layer_backward(dgc_layer_t* L, const void* Yv, int64_t ldy, con
   return DGC_OK;
 }
 
+dgc_status_t dgc_layer_set_presence(dgc_layer_t* L, const uint8_t* present, void* stream) {
+  if (!L) return DGC_ERR_INVALID_ARG;
+  Failer fail{L};
+  const dgc_layer_desc_t& d = L->desc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (!present) return fail(DGC_ERR_INVALID_ARG, "present is NULL");
+  if (d.struct_kind != DGC_STRUCT_GCN || d.time_kind == DGC_TIME_NONE)
+    return fail(DGC_ERR_UNSUPPORTED, "temporal fusion needs a GCN layer with a recurrent time encoder");
+  if (L->tf.built) return fail(DGC_ERR_STATE, "the presence mask of a layer can be set once");
+  TFusion& tf = L->tf;
+  const int32_t nc = L->n_chunks;
+  const std::vector<ChunkInfo>& ci = L->cinfo_host;
+  int64_t max_nv = 1;
+  for (const ChunkInfo& c : ci) { max_nv = std::max(max_nv, c.nv); tf.Lmax = std::max(tf.Lmax, c.w); }
+  // sequence lengths (device) -> lanes by first-fit decreasing (host arithmetic on the lengths)
+  int32_t* d_len = nullptr;
+  DGC_HIP_TRY(dev_alloc(L, &d_len, L->total_state_rows));
+  tf_lengths(present, L->d_chunks, nc, max_nv, L->N, d_len, st);
+  std::vector<int32_t> len(L->total_state_rows), lane_of(L->total_state_rows, -1), off_of(L->total_state_rows, 0);
+  DGC_HIP_TRY(hipMemcpyAsync(len.data(), d_len, sizeof(int32_t) * len.size(), hipMemcpyDeviceToHost, st));
+  DGC_HIP_TRY(hipStreamSynchronize(st));
+  std::vector<int64_t> lane_ptr(nc + 1, 0);
+  std::vector<ChunkInfo> cv(nc);
+  int64_t rows_v = 0;
+  for (int32_t k = 0; k < nc; ++k) {
+    const ChunkInfo& c = ci[k];
+    // order: length descending, vertex ascending; each sequence into the first lane (in order of
+    // creation) with room for all of it.  by_free[f] = lanes of this chunk with f free slots.
+    std::vector<int32_t> order;
+    for (int64_t v = 0; v < c.nv; ++v)
+      if (len[c.state_off + v] > 0) order.push_back((int32_t)v);
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int32_t a, int32_t b) { return len[c.state_off + a] > len[c.state_off + b]; });
+    std::vector<std::set<int32_t>> by_free(c.w + 1);
+    int32_t n_l = 0;
+    for (int32_t v : order) {
+      const int32_t n = len[c.state_off + v];
+      int32_t best = -1, bf = 0;
+      for (int32_t f = n; f <= c.w; ++f)
+        if (!by_free[f].empty() && (best < 0 || *by_free[f].begin() < best)) { best = *by_free[f].begin(); bf = f; }
+      if (best < 0) { best = n_l++; bf = c.w; } else by_free[bf].erase(by_free[bf].begin());
+      lane_of[c.state_off + v] = (int32_t)(lane_ptr[k] + best);
+      off_of[c.state_off + v] = c.w - bf;
+      by_free[bf - n].insert(best);
+    }
+    lane_ptr[k + 1] = lane_ptr[k] + n_l;
+    cv[k] = ChunkInfo{lane_ptr[k], n_l, rows_v, lane_ptr[k], 0, c.w};
+    rows_v += (int64_t)n_l * c.w;
+  }
+  tf.n_lanes = lane_ptr[nc];
+  tf.rows_v = rows_v;
+  if (tf.n_lanes > INT32_MAX) return fail(DGC_ERR_UNSUPPORTED, "too many lanes");
+  const int64_t n_slots = (int64_t)tf.Lmax * tf.n_lanes;
+  int32_t *d_lane = nullptr, *d_off = nullptr;
+  DGC_HIP_TRY(dev_alloc(L, &d_lane, L->total_state_rows));
+  DGC_HIP_TRY(dev_alloc(L, &d_off, L->total_state_rows));
+  DGC_HIP_TRY(dev_alloc(L, &tf.lane_ptr, nc + 1));
+  DGC_HIP_TRY(dev_alloc(L, &tf.slot_row, n_slots));
+  DGC_HIP_TRY(dev_alloc(L, &tf.slot_src, n_slots));
+  DGC_HIP_TRY(dev_alloc(L, &tf.slot_reset, n_slots));
+  DGC_HIP_TRY(dev_alloc(L, &tf.row_map, L->total_rows));
+  DGC_HIP_TRY(dev_alloc(L, &tf.chunks_v, nc));
+  DGC_HIP_TRY(hipMemcpyAsync(d_lane, lane_of.data(), sizeof(int32_t) * lane_of.size(), hipMemcpyHostToDevice, st));
+  DGC_HIP_TRY(hipMemcpyAsync(d_off, off_of.data(), sizeof(int32_t) * off_of.size(), hipMemcpyHostToDevice, st));
+  DGC_HIP_TRY(hipMemcpyAsync(tf.lane_ptr, lane_ptr.data(), sizeof(int64_t) * (nc + 1), hipMemcpyHostToDevice, st));
+  DGC_HIP_TRY(hipMemcpyAsync(tf.chunks_v, cv.data(), sizeof(ChunkInfo) * nc, hipMemcpyHostToDevice, st));
+  tf_fill(present, L->d_chunks, nc, max_nv, L->N, d_lane, d_off, tf.n_lanes, tf.Lmax, tf.chunks_v, L->total_rows,
+          tf.slot_row, tf.slot_src, tf.row_map, tf.slot_reset, st);
+  // tiles of the virtual chunks
+  std::vector<DenseTile> t64, t32;
+  for (int32_t k = 0; k < nc; ++k) {
+    for (int64_t v0 = 0; v0 < cv[k].nv; v0 += kTileRows)
+      t64.push_back(DenseTile{k, (int32_t)v0, (int32_t)std::min<int64_t>(kTileRows, cv[k].nv - v0), 0});
+    for (int64_t v0 = 0; v0 < cv[k].nv; v0 += kWaveTileRows)
+      t32.push_back(DenseTile{k, (int32_t)v0, (int32_t)std::min<int64_t>(kWaveTileRows, cv[k].nv - v0), 0});
+  }
+  tf.n_tiles_v = (int64_t)t64.size(); tf.n_tiles32_v = (int64_t)t32.size();
+  DGC_HIP_TRY(dev_alloc(L, &tf.tiles_v, tf.n_tiles_v));
+  DGC_HIP_TRY(dev_alloc(L, &tf.tiles32_v, tf.n_tiles32_v));
+  DGC_HIP_TRY(hipMemcpyAsync(tf.tiles_v, t64.data(), sizeof(DenseTile) * t64.size(), hipMemcpyHostToDevice, st));
+  DGC_HIP_TRY(hipMemcpyAsync(tf.tiles32_v, t32.data(), sizeof(DenseTile) * t32.size(), hipMemcpyHostToDevice, st));
+  const int32_t out_dim = d.H;
+  DGC_HIP_TRY(dev_alloc(L, &tf.Mv, rows_v * L->ldm));
+  DGC_HIP_TRY(hipMemsetAsync(tf.Mv, 0, sizeof(float) * (size_t)std::max<int64_t>(rows_v * L->ldm, 1), st));  // empty slots stay zero
+  DGC_HIP_TRY(dev_alloc(L, &tf.Yv, n_slots * out_dim));
+  DGC_HIP_TRY(hipStreamSynchronize(st));
+  DGC_HIP_TRY(hipGetLastError());
+  dev_free(L, d_len); dev_free(L, d_lane); dev_free(L, d_off);
+  tf.built = true;
+  return DGC_OK;
+}
+
 dgc_status_t dgc_layer_packing(dgc_layer_t* L, const char* what, void* host_dst, int64_t capacity_bytes,
                                int64_t* needed_bytes) {
   if (!L) return DGC_ERR_INVALID_ARG;
@@ -935,6 +1047,12 @@ dgc_status_t dgc_layer_packing(dgc_layer_t* L, const char* what, void* host_dst,
   } else if (w == "work_short") { src = L->d_work_short; bytes = sizeof(int32_t) * 3 * L->n_short;
   } else if (w == "work_long") { src = L->d_work_long; bytes = sizeof(int32_t) * 4 * L->n_long;
   } else if (w == "deg_inv_sqrt") { src = L->d_dinv; bytes = sizeof(float) * (int64_t)L->T * L->N;
+  } else if (w == "lane_ptr" || w == "slot_row" || w == "slot_reset") {
+    if (!L->tf.built) return fail(DGC_ERR_STATE, "no temporal-fusion packing: call dgc_layer_set_presence first");
+    const int64_t n = (int64_t)L->tf.Lmax * L->tf.n_lanes;
+    if (w == "lane_ptr") { src = L->tf.lane_ptr; bytes = sizeof(int64_t) * (L->n_chunks + 1); }
+    else if (w == "slot_row") { src = L->tf.slot_row; bytes = sizeof(int64_t) * n; }
+    else { src = L->tf.slot_reset; bytes = n; }
   } else {
     return fail(DGC_ERR_INVALID_ARG, "unknown packing array " + w);
   }

@@ -103,6 +103,7 @@ struct SpmmArgs {
   int32_t long_nnz, part_nnz;
   float* partial;             // [n_long][ldm] scratch for split rows
   float* M; int64_t ldm;      // [rows, ldm]; columns F..ldm-1 are written as zero
+  const int64_t* row_map;     // nullptr, or [rows]: row of M that packed row r goes to (< 0: skip the row)
 };
 void launch_spmm(const SpmmArgs& a, hipStream_t st);
 void launch_gather(const Segment* segs, int64_t nseg, const int32_t* halo_idx, const int64_t* halo_ptr,
@@ -245,5 +246,33 @@ void dysat_pack_params(const DysatWs& ws, hipStream_t st);
 // ev: NULL or 4 events recorded around the three forward stages
 void dysat_forward(const DysatWs& ws, const void* X, int64_t ldx, const void* C, int64_t ldc, void* Y, int64_t ldy,
                    hipEvent_t* ev, hipStream_t st);
+
+// ---- temporal fusion (dgc_tfusion.hip)
+struct TFusion {
+  bool built = false;
+  int64_t n_lanes = 0;       // lanes of all chunks
+  int32_t Lmax = 0;          // longest window
+  int64_t rows_v = 0;        // sum over chunks of lanes x window
+  int64_t* lane_ptr = nullptr;    // [n_chunks+1] first lane of every chunk
+  int64_t* slot_row = nullptr;    // [Lmax][n_lanes] t*N + i of the row in the slot, -1 = empty
+  int64_t* slot_src = nullptr;    // [Lmax][n_lanes] packed row of the aggregated rows, -1 = empty
+  int64_t* row_map = nullptr;     // [total rows] inverse: packed row -> row of Mv (lane order), -1 = absent
+  uint8_t* slot_reset = nullptr;  // [Lmax][n_lanes] 1 on the first slot of every sequence
+  ChunkInfo* chunks_v = nullptr;  // the lanes of chunk k as a chunk: v_lo = first lane, nv = lanes, t_lo = 0
+  DenseTile* tiles_v = nullptr; int64_t n_tiles_v = 0;
+  DenseTile* tiles32_v = nullptr; int64_t n_tiles32_v = 0;
+  float* Mv = nullptr;            // [rows_v][ldm] aggregated rows in lane order
+  float* Yv = nullptr;            // [Lmax][n_lanes][out_dim]
+};
+void tf_lengths(const uint8_t* present, const ChunkInfo* chunks, int32_t n_chunks, int64_t max_nv, int64_t N,
+                int32_t* seq_len, hipStream_t st);
+void tf_fill(const uint8_t* present, const ChunkInfo* chunks, int32_t n_chunks, int64_t max_nv, int64_t N,
+             const int32_t* seq_lane, const int32_t* seq_off, int64_t n_lanes, int32_t Lmax, const ChunkInfo* chunks_v,
+             int64_t total_rows, int64_t* slot_row, int64_t* slot_src, int64_t* row_map, uint8_t* slot_reset,
+             hipStream_t st);
+void tf_gather(const float* M, int64_t ldm, const int64_t* slot_src, const int64_t* lane_ptr, const ChunkInfo* chunks_v,
+               int32_t n_chunks, int64_t n_lanes, int32_t Lmax, float* Mv, hipStream_t st);
+void tf_scatter(const float* Yv, int32_t out_dim, const int64_t* slot_row, int64_t n_slots, float* Y, int64_t ldy,
+                hipStream_t st);
 
 }  // namespace dgc

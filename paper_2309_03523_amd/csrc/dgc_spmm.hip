@@ -149,11 +149,15 @@ __global__ __launch_bounds__(256) void k_spmm_short(SpmmArgs a) {
   const RowCtx c = make_ctx<STAGED>(a, sg);
   const int64_t* rp = a.g.rowptr[sg.t] + sg.v_lo + r0;
   const int64_t my_rp = lane <= n ? rp[lane] : 0;
+  // optional output permutation: row_map[packed row] = row of M to write, < 0 = row not wanted
+  const int64_t my_map = a.row_map ? (lane < n ? a.row_map[sg.row_off + r0 + lane] : -1) : sg.row_off + r0 + lane;
   for (int r = 0; r < n; ++r) {
     const int64_t ea = readlane64(my_rp, r), eb = readlane64(my_rp, r + 1);
     if (eb - ea > a.long_nnz) continue;
+    const int64_t orow = readlane64(my_map, r);
+    if (orow < 0) continue;
     const float di = c.dinv_t[sg.v_lo + r0 + r];
-    float* out = a.M + (sg.row_off + r0 + r) * a.ldm;
+    float* out = a.M + orow * a.ldm;
     for (int f0 = 0; f0 < a.ldm; f0 += kWave * VEC) {
       const int fi = f0 + lane * VEC;
       float acc[VEC];
@@ -203,7 +207,9 @@ __global__ __launch_bounds__(256) void k_spmm_long_reduce(SpmmArgs a) {
   const int parts = uniform(a.work_long[4 * item + 3]);
   const Segment sg = a.segs[seg];
   const float di = a.dinv[(int64_t)sg.t * a.g.N + sg.v_lo + row];
-  float* out = a.M + (sg.row_off + row) * a.ldm;
+  const int64_t orow = a.row_map ? a.row_map[sg.row_off + row] : sg.row_off + row;
+  if (orow < 0) return;
+  float* out = a.M + orow * a.ldm;
   for (int f0 = 0; f0 < a.ldm; f0 += kWave * VEC) {
     const int fi = f0 + lane * VEC;
     if (fi >= a.ldm) continue;

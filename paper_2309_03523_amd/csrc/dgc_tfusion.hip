@@ -1,0 +1,127 @@
+// Temporal fusion (Section 5.1.2 of the paper): the sequences of the vertices of a chunk (the
+// snapshots of the window in which a vertex is present) are concatenated into lanes as long as
+// the window instead of being padded, and a reset flag on the first slot of every sequence keeps
+// the state of one sequence out of the next (the paper's mask).  The lanes of a chunk form a
+// "virtual chunk" (lanes x window) that the dense + recurrent kernels process unchanged: the
+// aggregation writes its rows directly in lane order (and skips the rows of absent vertices), the
+// outputs are scattered back after.
+//
+// Device side here: sequence lengths, the slot tables, the two permutation copies.  The packing
+// rule itself (first-fit decreasing, see tf_assign_lanes in dgc_api.hip) is host arithmetic on
+// the lengths.
+#include "dgc_internal.h"
+
+namespace dgc {
+namespace {
+
+unsigned nblocks(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
+
+// seq_len[state row of (chunk k, vertex)] = number of snapshots of the window with the vertex present
+__global__ void k_tf_lengths(const uint8_t* present, const ChunkInfo* chunks, int64_t N, int32_t* seq_len) {
+  const ChunkInfo c = chunks[blockIdx.y];
+  const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (v >= c.nv) return;
+  int32_t n = 0;
+  for (int32_t s = 0; s < c.w; ++s) n += present[(int64_t)(c.t_lo + s) * N + c.v_lo + v] != 0;
+  seq_len[c.state_off + v] = n;
+}
+
+// slot tables from the lane / first slot assigned to every sequence
+__global__ void k_tf_fill(const uint8_t* present, const ChunkInfo* chunks, int64_t N, const int32_t* seq_lane,
+                          const int32_t* seq_off, int64_t n_lanes, const ChunkInfo* chunks_v, int64_t* slot_row,
+                          int64_t* slot_src, int64_t* row_map, uint8_t* slot_reset) {
+  const ChunkInfo c = chunks[blockIdx.y];
+  const ChunkInfo cv = chunks_v[blockIdx.y];
+  const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (v >= c.nv) return;
+  const int32_t lane = seq_lane[c.state_off + v];
+  if (lane < 0) return;
+  int32_t slot = seq_off[c.state_off + v];
+  slot_reset[(int64_t)slot * n_lanes + lane] = 1;
+  for (int32_t s = 0; s < c.w; ++s) {
+    const int64_t t = c.t_lo + s;
+    if (!present[t * N + c.v_lo + v]) continue;
+    slot_row[(int64_t)slot * n_lanes + lane] = t * N + c.v_lo + v;
+    slot_src[(int64_t)slot * n_lanes + lane] = c.row_off0 + (int64_t)s * c.nv + v;
+    row_map[c.row_off0 + (int64_t)s * c.nv + v] = cv.row_off0 + (int64_t)slot * cv.nv + (lane - cv.v_lo);
+    ++slot;
+  }
+}
+
+__global__ void k_tf_fill_i64(int64_t* p, int64_t v, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// largest k with lane_ptr[k] <= lane
+__device__ __forceinline__ int chunk_of_lane(const int64_t* lane_ptr, int n_chunks, int64_t lane) {
+  int lo = 0, hi = n_chunks;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (lane_ptr[mid] <= lane) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+// Mv[virtual packed row of (slot, lane)] = M[slot_src] (zero for an empty slot); one thread per float4
+__global__ void k_tf_gather(const float* M, int64_t ldm, const int64_t* slot_src, const int64_t* lane_ptr,
+                            const ChunkInfo* chunks_v, int n_chunks, int64_t n_lanes, int32_t Lmax, float* Mv) {
+  const int64_t q = ldm / 4;
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)Lmax * n_lanes * q) return;
+  const int64_t sl = idx / q, c4 = idx - sl * q;
+  const int64_t slot = sl / n_lanes, lane = sl - slot * n_lanes;
+  const ChunkInfo c = chunks_v[chunk_of_lane(lane_ptr, n_chunks, lane)];
+  if (slot >= c.w) return;
+  const int64_t src = slot_src[sl];
+  float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (src >= 0) x = reinterpret_cast<const float4*>(M + src * ldm)[c4];
+  reinterpret_cast<float4*>(Mv + (c.row_off0 + slot * c.nv + (lane - c.v_lo)) * ldm)[c4] = x;
+}
+
+// Y[slot_row] = Yv[slot, lane]; one thread per float4
+__global__ void k_tf_scatter(const float* Yv, int32_t out_dim, const int64_t* slot_row, int64_t n_slots, float* Y,
+                             int64_t ldy) {
+  const int64_t q = out_dim / 4;
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n_slots * q) return;
+  const int64_t sl = idx / q, c4 = idx - sl * q;
+  const int64_t row = slot_row[sl];
+  if (row < 0) return;
+  reinterpret_cast<float4*>(Y + row * ldy)[c4] = reinterpret_cast<const float4*>(Yv + sl * out_dim)[c4];
+}
+
+}  // namespace
+
+void tf_lengths(const uint8_t* present, const ChunkInfo* chunks, int32_t n_chunks, int64_t max_nv, int64_t N,
+                int32_t* seq_len, hipStream_t st) {
+  hipLaunchKernelGGL(k_tf_lengths, dim3(nblocks(max_nv, 256), n_chunks), 256, 0, st, present, chunks, N, seq_len);
+}
+
+void tf_fill(const uint8_t* present, const ChunkInfo* chunks, int32_t n_chunks, int64_t max_nv, int64_t N,
+             const int32_t* seq_lane, const int32_t* seq_off, int64_t n_lanes, int32_t Lmax, const ChunkInfo* chunks_v,
+             int64_t total_rows, int64_t* slot_row, int64_t* slot_src, int64_t* row_map, uint8_t* slot_reset,
+             hipStream_t st) {
+  const int64_t n = (int64_t)Lmax * n_lanes;
+  hipLaunchKernelGGL(k_tf_fill_i64, nblocks(n, 256), 256, 0, st, slot_row, (int64_t)-1, n);
+  hipLaunchKernelGGL(k_tf_fill_i64, nblocks(n, 256), 256, 0, st, slot_src, (int64_t)-1, n);
+  hipLaunchKernelGGL(k_tf_fill_i64, nblocks(total_rows, 256), 256, 0, st, row_map, (int64_t)-1, total_rows);
+  (void)hipMemsetAsync(slot_reset, 0, (size_t)n, st);
+  hipLaunchKernelGGL(k_tf_fill, dim3(nblocks(max_nv, 256), n_chunks), 256, 0, st, present, chunks, N, seq_lane, seq_off,
+                     n_lanes, chunks_v, slot_row, slot_src, row_map, slot_reset);
+}
+
+void tf_gather(const float* M, int64_t ldm, const int64_t* slot_src, const int64_t* lane_ptr, const ChunkInfo* chunks_v,
+               int32_t n_chunks, int64_t n_lanes, int32_t Lmax, float* Mv, hipStream_t st) {
+  const int64_t n = (int64_t)Lmax * n_lanes * (ldm / 4);
+  hipLaunchKernelGGL(k_tf_gather, nblocks(n, 256), 256, 0, st, M, ldm, slot_src, lane_ptr, chunks_v, n_chunks, n_lanes,
+                     Lmax, Mv);
+}
+
+void tf_scatter(const float* Yv, int32_t out_dim, const int64_t* slot_row, int64_t n_slots, float* Y, int64_t ldy,
+                hipStream_t st) {
+  hipLaunchKernelGGL(k_tf_scatter, nblocks(n_slots * (out_dim / 4), 256), 256, 0, st, Yv, out_dim, slot_row, n_slots, Y,
+                     ldy);
+}
+
+}  // namespace dgc

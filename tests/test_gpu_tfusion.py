@@ -1,0 +1,72 @@
+"""Temporal fusion on the GPU against the oracle: the lane packing bit-exact, the layer's output on
+every present row within the fp32 tolerance, absent rows untouched."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import tfusion
+from paper_2309_03523_amd import synth
+from refs import rel_err
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+CHUNKS = [[0, 70, 0, 8], [70, 201, 0, 5], [70, 201, 5, 8], [201, 260, 2, 8]]
+
+
+def _run(kind, S, n_layers, seed, dense="auto"):
+    import torch
+    from paper_2309_03523_amd.runner import DeviceWorkload
+    T, N, F = 8, 260, 48
+    wl = synth.random_small(seed, T, N, F, S, S, 4.0, CHUNKS, kind, n_struct_layers=n_layers, hub=True)
+    present = synth.presence(seed, T, N)
+    dw = DeviceWorkload(wl, dense_kernel=dense)
+    dw.layer.set_presence(torch.from_numpy(present).cuda())
+    got_pack = {k: dw.layer.packing(k) for k in ("lane_ptr", "slot_row", "slot_reset")}
+    want_pack = tfusion.pack(present, wl.chunks)
+    np.testing.assert_array_equal(got_pack["lane_ptr"], want_pack["lane_ptr"])
+    np.testing.assert_array_equal(got_pack["slot_row"].reshape(want_pack["slot_row"].shape), want_pack["slot_row"])
+    np.testing.assert_array_equal(got_pack["slot_reset"].reshape(want_pack["slot_reset"].shape), want_pack["slot_reset"])
+    Y = dw.forward(use_h0=False).cpu().numpy()
+    Z = oracle.forward(wl.graph, wl.chunks, wl.params, wl.X, wl.C, time_kind="none", n_struct_layers=n_layers,
+                       C1=wl.C1, act_hidden="relu", act_out="none").astype(np.float64)
+    want = tfusion.run_separate(np.nan_to_num(Z), present, wl.chunks, wl.params, kind)
+    m = ~np.isnan(want)
+    assert m.sum() > 500
+    e = rel_err(Y[m], want[m])
+    print(f"{kind} S={S} layers={n_layers} {dense}: lanes {want_pack['slot_row'].shape[1]} for "
+          f"{int(m.any(axis=2).sum())} present rows, rel_err {e:.3e}", flush=True)
+    assert e < TOL
+    assert np.isnan(Y[~m.any(axis=2)]).all()       # absent and uncovered rows are not written
+    return dw
+
+
+@pytest.mark.parametrize("kind,S,n_layers,dense", [("gru", 64, 1, "auto"), ("gru", 96, 1, "tile"), ("lstm", 128, 1, "auto"),
+                                                   ("lstm", 32, 2, "auto")])
+def test_temporal_fusion_parity(kind, S, n_layers, dense):
+    dw = _run(kind, S, n_layers, 20 + S, dense)
+    dw.layer.destroy()
+
+
+def test_temporal_fusion_errors():
+    import torch
+    from paper_2309_03523_amd.binding import DgcError
+    from paper_2309_03523_amd.runner import DeviceWorkload
+    dw = _run("gru", 32, 1, 7)
+    present = torch.ones(8, 260, dtype=torch.uint8, device="cuda")
+    with pytest.raises(DgcError) as ei:          # once per layer
+        dw.layer.set_presence(present)
+    assert ei.value.code == 7
+    with pytest.raises(DgcError) as ei:          # no initial states with fused sequences
+        dw.forward(use_h0=True)
+    assert ei.value.code == 1
+    dw.layer.destroy()
+    wl = synth.random_small(3, 4, 40, 32, 32, 32, 3.0, [[0, 40, 0, 4]], "none")
+    dw2 = DeviceWorkload(wl)
+    with pytest.raises(DgcError) as ei:          # needs a recurrent time encoder
+        dw2.layer.set_presence(torch.ones(4, 40, dtype=torch.uint8, device="cuda"))
+    assert ei.value.code == 4
+    with pytest.raises(DgcError) as ei:          # no packing to read
+        dw2.layer.packing("slot_row")
+    assert ei.value.code == 7
+    dw2.layer.destroy()
