@@ -992,7 +992,6 @@ dgc_status_t dgc_layer_set_presence(dgc_layer_t* L, const uint8_t* present, void
   DGC_HIP_TRY(dev_alloc(L, &d_off, L->total_state_rows));
   DGC_HIP_TRY(dev_alloc(L, &tf.lane_ptr, nc + 1));
   DGC_HIP_TRY(dev_alloc(L, &tf.slot_row, n_slots));
-  DGC_HIP_TRY(dev_alloc(L, &tf.slot_src, n_slots));
   DGC_HIP_TRY(dev_alloc(L, &tf.slot_reset, n_slots));
   DGC_HIP_TRY(dev_alloc(L, &tf.row_map, L->total_rows));
   DGC_HIP_TRY(dev_alloc(L, &tf.chunks_v, nc));
@@ -1001,7 +1000,7 @@ dgc_status_t dgc_layer_set_presence(dgc_layer_t* L, const uint8_t* present, void
   DGC_HIP_TRY(hipMemcpyAsync(tf.lane_ptr, lane_ptr.data(), sizeof(int64_t) * (nc + 1), hipMemcpyHostToDevice, st));
   DGC_HIP_TRY(hipMemcpyAsync(tf.chunks_v, cv.data(), sizeof(ChunkInfo) * nc, hipMemcpyHostToDevice, st));
   tf_fill(present, L->d_chunks, nc, max_nv, L->N, d_lane, d_off, tf.n_lanes, tf.Lmax, tf.chunks_v, L->total_rows,
-          tf.slot_row, tf.slot_src, tf.row_map, tf.slot_reset, st);
+          tf.slot_row, tf.row_map, tf.slot_reset, st);
   // tiles of the virtual chunks
   std::vector<DenseTile> t64, t32;
   for (int32_t k = 0; k < nc; ++k) {

@@ -255,7 +255,6 @@ struct TFusion {
   int64_t rows_v = 0;        // sum over chunks of lanes x window
   int64_t* lane_ptr = nullptr;    // [n_chunks+1] first lane of every chunk
   int64_t* slot_row = nullptr;    // [Lmax][n_lanes] t*N + i of the row in the slot, -1 = empty
-  int64_t* slot_src = nullptr;    // [Lmax][n_lanes] packed row of the aggregated rows, -1 = empty
   int64_t* row_map = nullptr;     // [total rows] inverse: packed row -> row of Mv (lane order), -1 = absent
   uint8_t* slot_reset = nullptr;  // [Lmax][n_lanes] 1 on the first slot of every sequence
   ChunkInfo* chunks_v = nullptr;  // the lanes of chunk k as a chunk: v_lo = first lane, nv = lanes, t_lo = 0
@@ -268,10 +267,7 @@ void tf_lengths(const uint8_t* present, const ChunkInfo* chunks, int32_t n_chunk
                 int32_t* seq_len, hipStream_t st);
 void tf_fill(const uint8_t* present, const ChunkInfo* chunks, int32_t n_chunks, int64_t max_nv, int64_t N,
              const int32_t* seq_lane, const int32_t* seq_off, int64_t n_lanes, int32_t Lmax, const ChunkInfo* chunks_v,
-             int64_t total_rows, int64_t* slot_row, int64_t* slot_src, int64_t* row_map, uint8_t* slot_reset,
-             hipStream_t st);
-void tf_gather(const float* M, int64_t ldm, const int64_t* slot_src, const int64_t* lane_ptr, const ChunkInfo* chunks_v,
-               int32_t n_chunks, int64_t n_lanes, int32_t Lmax, float* Mv, hipStream_t st);
+             int64_t total_rows, int64_t* slot_row, int64_t* row_map, uint8_t* slot_reset, hipStream_t st);
 void tf_scatter(const float* Yv, int32_t out_dim, const int64_t* slot_row, int64_t n_slots, float* Y, int64_t ldy,
                 hipStream_t st);
 

@@ -6,7 +6,7 @@
 // aggregation writes its rows directly in lane order (and skips the rows of absent vertices), the
 // outputs are scattered back after.
 //
-// Device side here: sequence lengths, the slot tables, the two permutation copies.  The packing
+// Device side here: sequence lengths, the slot tables and the row map, the copy of the outputs.  The packing
 // rule itself (first-fit decreasing, see tf_assign_lanes in dgc_api.hip) is host arithmetic on
 // the lengths.
 #include "dgc_internal.h"
@@ -29,7 +29,7 @@ __global__ void k_tf_lengths(const uint8_t* present, const ChunkInfo* chunks, in
 // slot tables from the lane / first slot assigned to every sequence
 __global__ void k_tf_fill(const uint8_t* present, const ChunkInfo* chunks, int64_t N, const int32_t* seq_lane,
                           const int32_t* seq_off, int64_t n_lanes, const ChunkInfo* chunks_v, int64_t* slot_row,
-                          int64_t* slot_src, int64_t* row_map, uint8_t* slot_reset) {
+                          int64_t* row_map, uint8_t* slot_reset) {
   const ChunkInfo c = chunks[blockIdx.y];
   const ChunkInfo cv = chunks_v[blockIdx.y];
   const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -42,7 +42,6 @@ __global__ void k_tf_fill(const uint8_t* present, const ChunkInfo* chunks, int64
     const int64_t t = c.t_lo + s;
     if (!present[t * N + c.v_lo + v]) continue;
     slot_row[(int64_t)slot * n_lanes + lane] = t * N + c.v_lo + v;
-    slot_src[(int64_t)slot * n_lanes + lane] = c.row_off0 + (int64_t)s * c.nv + v;
     row_map[c.row_off0 + (int64_t)s * c.nv + v] = cv.row_off0 + (int64_t)slot * cv.nv + (lane - cv.v_lo);
     ++slot;
   }
@@ -51,32 +50,6 @@ __global__ void k_tf_fill(const uint8_t* present, const ChunkInfo* chunks, int64
 __global__ void k_tf_fill_i64(int64_t* p, int64_t v, int64_t n) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
-}
-
-// largest k with lane_ptr[k] <= lane
-__device__ __forceinline__ int chunk_of_lane(const int64_t* lane_ptr, int n_chunks, int64_t lane) {
-  int lo = 0, hi = n_chunks;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (lane_ptr[mid] <= lane) lo = mid; else hi = mid;
-  }
-  return lo;
-}
-
-// Mv[virtual packed row of (slot, lane)] = M[slot_src] (zero for an empty slot); one thread per float4
-__global__ void k_tf_gather(const float* M, int64_t ldm, const int64_t* slot_src, const int64_t* lane_ptr,
-                            const ChunkInfo* chunks_v, int n_chunks, int64_t n_lanes, int32_t Lmax, float* Mv) {
-  const int64_t q = ldm / 4;
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= (int64_t)Lmax * n_lanes * q) return;
-  const int64_t sl = idx / q, c4 = idx - sl * q;
-  const int64_t slot = sl / n_lanes, lane = sl - slot * n_lanes;
-  const ChunkInfo c = chunks_v[chunk_of_lane(lane_ptr, n_chunks, lane)];
-  if (slot >= c.w) return;
-  const int64_t src = slot_src[sl];
-  float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (src >= 0) x = reinterpret_cast<const float4*>(M + src * ldm)[c4];
-  reinterpret_cast<float4*>(Mv + (c.row_off0 + slot * c.nv + (lane - c.v_lo)) * ldm)[c4] = x;
 }
 
 // Y[slot_row] = Yv[slot, lane]; one thread per float4
@@ -100,22 +73,13 @@ void tf_lengths(const uint8_t* present, const ChunkInfo* chunks, int32_t n_chunk
 
 void tf_fill(const uint8_t* present, const ChunkInfo* chunks, int32_t n_chunks, int64_t max_nv, int64_t N,
              const int32_t* seq_lane, const int32_t* seq_off, int64_t n_lanes, int32_t Lmax, const ChunkInfo* chunks_v,
-             int64_t total_rows, int64_t* slot_row, int64_t* slot_src, int64_t* row_map, uint8_t* slot_reset,
-             hipStream_t st) {
+             int64_t total_rows, int64_t* slot_row, int64_t* row_map, uint8_t* slot_reset, hipStream_t st) {
   const int64_t n = (int64_t)Lmax * n_lanes;
   hipLaunchKernelGGL(k_tf_fill_i64, nblocks(n, 256), 256, 0, st, slot_row, (int64_t)-1, n);
-  hipLaunchKernelGGL(k_tf_fill_i64, nblocks(n, 256), 256, 0, st, slot_src, (int64_t)-1, n);
   hipLaunchKernelGGL(k_tf_fill_i64, nblocks(total_rows, 256), 256, 0, st, row_map, (int64_t)-1, total_rows);
   (void)hipMemsetAsync(slot_reset, 0, (size_t)n, st);
   hipLaunchKernelGGL(k_tf_fill, dim3(nblocks(max_nv, 256), n_chunks), 256, 0, st, present, chunks, N, seq_lane, seq_off,
-                     n_lanes, chunks_v, slot_row, slot_src, row_map, slot_reset);
-}
-
-void tf_gather(const float* M, int64_t ldm, const int64_t* slot_src, const int64_t* lane_ptr, const ChunkInfo* chunks_v,
-               int32_t n_chunks, int64_t n_lanes, int32_t Lmax, float* Mv, hipStream_t st) {
-  const int64_t n = (int64_t)Lmax * n_lanes * (ldm / 4);
-  hipLaunchKernelGGL(k_tf_gather, nblocks(n, 256), 256, 0, st, M, ldm, slot_src, lane_ptr, chunks_v, n_chunks, n_lanes,
-                     Lmax, Mv);
+                     n_lanes, chunks_v, slot_row, row_map, slot_reset);
 }
 
 void tf_scatter(const float* Yv, int32_t out_dim, const int64_t* slot_row, int64_t n_slots, float* Y, int64_t ldy,
