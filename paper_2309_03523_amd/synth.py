@@ -516,3 +516,32 @@ def presence(seed: int, T: int, N: int, p_lo: float = 0.15, p_hi: float = 1.0) -
     rng = stream(seed, "presence")
     p = rng.uniform(p_lo, p_hi, size=N)
     return (rng.random((T, N)) < p[None, :]).astype(np.uint8)
+
+
+# --------------------------------------------------------------------------- embedding drift
+
+
+def drifted_copies(seed: int, R: int, F: int, median: float = 0.34, sigma: float = 1.0,
+                   unchanged: float = 0.1):
+    """Current embeddings E ~ N(0,1) [R,F] and the copies L sent last, fp32.  Row r has drifted by a
+    Gaussian vector whose length is log-normal (median `median`, log-std `sigma`): about 85 % of the
+    distances are below 1, a long tail above, as in the distance CDFs the paper plots; a fraction
+    `unchanged` of the rows has not moved at all (L = E bit for bit)."""
+    rng = stream(seed, "drift")
+    E = _normal_f32(rng, (R, F))
+    length = np.exp(rng.normal(np.log(median), sigma, size=R)).astype(np.float32)
+    length[rng.random(R) < unchanged] = 0.0
+    L = np.empty_like(E)
+    step = 1 << 18
+    for a in range(0, R, step):
+        b = min(R, a + step)
+        d = rng.standard_normal((b - a, F), dtype=np.float32)
+        d *= (length[a:b] / np.sqrt(np.float32(F)))[:, None]
+        np.subtract(E[a:b], d, out=L[a:b])
+    return E, L
+
+
+def boundary_rows(seed: int, R: int, frac: float) -> np.ndarray:
+    """Ascending int64 subset of range(R): each row is a candidate with probability `frac`."""
+    rng = stream(seed, "boundary")
+    return np.flatnonzero(rng.random(R) < frac).astype(np.int64)
