@@ -29,7 +29,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config2s", "config2tf", "config3w", "config4s", "config4", "config5s", "config5"])
+    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config2s", "config2tf", "config3w", "config4s", "config4", "config5s", "config5", "stale"])
     ap.add_argument("--gather-mode", default="in_place", choices=["in_place", "staged"])
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -325,6 +325,85 @@ def cpu_baseline_tfusion(wl, Y_gpu, seed: int) -> dict:
             "gpu_max_rel_err_on_sample": err}
 
 
+def stale_main(args):
+    """The device stale filter (Section 5.2) over the embedding table of config 2: one step = one
+    epoch's filter over every (snapshot, vertex) row.  Two embedding tables alternate as the current
+    one, so that every step meets the same distances and sends the same rows."""
+    import numpy as np
+    import torch
+    from paper_2309_03523_amd import binding, synth
+    R, F = 32 * 100_000, 128
+    l1, l_prev = 1.0, 0.5
+    t0 = time.perf_counter()
+    E, L0 = synth.drifted_copies(args.seed, R, F, kind="triangular")
+    t_gen = time.perf_counter() - t0
+    factor = binding.stale_theta_factor(l1, l_prev, "printed")
+    Ed, Ld, Ad = torch.from_numpy(E).cuda(), torch.from_numpy(L0).cuda(), torch.from_numpy(L0).cuda()
+    dist = torch.empty(R, device="cuda")
+    send_idx = torch.empty(R, dtype=torch.int64, device="cuda")
+    send_buf = torch.empty(R, F, device="cuda")
+    result = torch.zeros(24, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(binding.stale_workspace_bytes(R), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+    kw = dict(factor=factor, dist=dist, send_idx=send_idx, send_buf=send_buf, result=result, workspace=ws, stream=stream)
+
+    binding.stale_filter(Ed, Ld, **kw)                       # first epoch, checked against the oracle below
+    torch.cuda.synchronize()
+    first = {"res": result.cpu().numpy().view(binding.STALE_RESULT_DTYPE)[0].copy(), "dist": dist.cpu().numpy(),
+             "L_new": Ld.cpu().numpy()}
+    first["send_idx"] = send_idx.cpu().numpy()[:int(first["res"]["n_send"])]
+    tables = [Ad, Ed]                                        # the copies now swing between the two tables
+
+    def step(i):
+        binding.stale_filter(tables[i & 1], Ld, **kw)
+
+    for i in range(2 * ((args.warmup + 1) // 2)):
+        step(i)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev[0].record(stream)
+    for i in range(args.steps):
+        step(i)
+    ev[1].record(stream)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    dev_ms = ev[0].elapsed_time(ev[1]) / args.steps
+    n_send = int(result.cpu().numpy().view(binding.STALE_RESULT_DTYPE)[0]["n_send"])
+    assert n_send == int(first["res"]["n_send"]), "the alternating epochs do not send the same rows"
+    bytes_per_step = R * (8 * F + 4) + n_send * (12 * F + 8)
+    out = {"metric": "embedding rows filtered/s (stale filter)", "value": R * args.steps / elapsed, "unit": "rows/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "stale filter over config 2's embedding table: 3.2 M rows x 128, every row a "
+                                  "candidate, drift lengths triangular on [0, 2], threshold factor of the printed "
+                                  "equation at l_prev = l_1 / 2", "rows": R, "F": F, "sent_rows": n_send,
+                      "theta_factor": factor},
+           "roofline": {"kernel": "k_stale_dist + k_stale_count + scan + k_stale_compact (one filter call)",
+                        "bound": "hbm", "achieved": bytes_per_step / (dev_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                        "unit": "GB/s", "frac": bytes_per_step / (dev_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                        "traffic": measured_traffic("stale", "in_place").get("filter"),
+                        "bytes_per_launch": bytes_per_step, "ms_per_launch": dev_ms},
+           "setup_s": {"generate": t_gen}}
+    if not args.no_cpu_baseline:
+        from oracle import stale
+        t0 = time.perf_counter()
+        want = stale.stale_filter(E, L0, factor=stale.theta_factor(l1, l_prev))
+        t_cpu = time.perf_counter() - t0
+        scale = want["D"]
+        sure = np.abs(want["dist"] - want["theta"]) > 1e-5 * scale
+        sent = np.zeros(R, bool)
+        sent[first["send_idx"]] = True
+        ok = bool((sent[sure] == (want["dist"] > want["theta"])[sure]).all()) and \
+            bool((first["L_new"][first["send_idx"]] == E[first["send_idx"]]).all())
+        out["cpu_baseline"] = {"value": R / t_cpu, "unit": "rows/s", "cores": 1, "kind": "oracle",
+                               "sample": f"the whole table, first epoch, {t_cpu:.1f} s (NumPy float64)",
+                               "gpu_max_rel_err_on_sample": float(np.abs(first["dist"] - want["dist"]).max() / scale),
+                               "gpu_decisions_match": ok, "rows_in_rounding_band": int((~sure).sum())}
+    print(json.dumps(out))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -333,6 +412,12 @@ def main():
         sys.exit(2)
     import numpy as np
     import torch
+    if args.workload == "stale":
+        if not torch.cuda.is_available():
+            print("bench.py needs a GPU", file=sys.stderr)
+            sys.exit(2)
+        stale_main(args)
+        return
     if args.workload.startswith("config5"):
         if not torch.cuda.is_available():
             print("bench.py needs a GPU", file=sys.stderr)

@@ -248,8 +248,47 @@ dgc_status_t dgc_layer_stage_times(dgc_layer_t* layer, float* host_ms);
 dgc_status_t dgc_layer_packing(dgc_layer_t* layer, const char* what, void* host_dst,
                                int64_t capacity_bytes, int64_t* needed_bytes);
 
-/* Text of the last error on this layer, or (layer = NULL) of the last failed create on the
- * calling thread.  Never NULL; valid until the next call on the same layer / thread. */
+/* Adaptive stale-embedding filter (Section 5.2): an embedding is transmitted again only if its L2
+ * distance to the copy transmitted last exceeds a threshold that follows the training loss.  The
+ * paper computes the distances on the CPU; here the whole step runs on the device.
+ *
+ * dgc_stale_theta_factor (host arithmetic): theta_r / D_r of the section's threshold equation from
+ *   the initial loss l1 (> 0) and the loss of the epoch before, norm = (l1 - l_prev) / l1:
+ *   DGC_THETA_PRINTED 1 / (1 + exp(norm)), the equation as printed (falls from 1/2 while the loss falls);
+ *   DGC_THETA_SIGMOID 1 / (1 + exp(-norm)), the sign under which the threshold grows as the text
+ *   around the equation says.  Returns a negative value for arguments outside the domain.
+ *
+ * dgc_stale_filter: E device [R, lde] current embeddings (fp32), L device [R, ldl] the copies
+ *   transmitted last (updated in place; must not overlap E).  Candidates: the rows listed in `rows`
+ *   (device int64 [n_rows], ascending; entries outside [0, R) are skipped and counted in
+ *   result->n_invalid), or every row if rows = NULL (then n_rows = 0).  For candidate c:
+ *     dist[c] = || E[row] - L[row] ||_2 over the first F columns (fp32 arithmetic);
+ *     D = max dist;  threshold = factor * D if factor >= 0, else `theta` (>= 0);
+ *     row is transmitted iff dist[c] > threshold (compared in fp32).
+ *   send_idx (device int64, room for every candidate) receives the transmitted row numbers in
+ *   candidate order; send_buf (device [n, lds], may be NULL) row k receives E[send_idx[k]]; L[row]
+ *   <- E[row] for the transmitted rows, every other row of L is left as it is.  result (device)
+ *   receives the count, D and the threshold used.  dist device fp32 [candidates], 16-byte aligned.
+ *   workspace: device, 8-byte aligned, at least dgc_stale_workspace_bytes(candidates) bytes,
+ *   contents irrelevant before and after.  Enqueues work only (no synchronisation, no allocation,
+ *   no memset); argument errors return at once with the text in dgc_last_error(NULL). */
+enum { DGC_THETA_PRINTED = 0, DGC_THETA_SIGMOID = 1 };
+typedef struct {
+  int64_t n_send;    /* rows transmitted                        */
+  float D;           /* largest distance among the candidates   */
+  float theta;       /* threshold the selection used            */
+  int64_t n_invalid; /* listed rows outside [0, R)              */
+} dgc_stale_result_t;
+double dgc_stale_theta_factor(double l1, double l_prev, int32_t variant);
+int64_t dgc_stale_workspace_bytes(int64_t n_candidates);
+dgc_status_t dgc_stale_filter(const float* E, int64_t lde, float* L, int64_t ldl, int64_t R, int32_t F,
+                              const int64_t* rows, int64_t n_rows, double factor, double theta,
+                              float* dist, int64_t* send_idx, float* send_buf, int64_t lds,
+                              dgc_stale_result_t* result, void* workspace, int64_t workspace_bytes,
+                              void* stream);
+
+/* Text of the last error on this layer, or (layer = NULL) of the last failed create or layer-less
+ * call on the calling thread.  Never NULL; valid until the next call on the same layer / thread. */
 const char* dgc_last_error(const dgc_layer_t* layer);
 
 /* Library version, e.g. "dgc 0.1 gfx950". */

@@ -28,7 +28,8 @@ STATUS = {0: "DGC_OK", 1: "DGC_ERR_INVALID_ARG", 2: "DGC_ERR_BAD_GRAPH", 3: "DGC
 EXPORTS = ["dgc_layer_create", "dgc_layer_destroy", "dgc_layer_set_param", "dgc_layer_get_param",
            "dgc_layer_forward", "dgc_layer_backward", "dgc_layer_aggregate", "dgc_layer_gather",
            "dgc_layer_packing", "dgc_layer_set_presence", "dgc_layer_set_profiling", "dgc_layer_stage_times", "dgc_last_error",
-           "dgc_version"]
+           "dgc_version", "dgc_stale_theta_factor", "dgc_stale_workspace_bytes", "dgc_stale_filter"]
+THETA_VARIANT = {"printed": 0, "sigmoid": 1}
 N_STAGES = 13
 
 
@@ -82,8 +83,14 @@ def load() -> ct.CDLL:
     lib.dgc_last_error.argtypes = [vp]
     lib.dgc_last_error.restype = ct.c_char_p
     lib.dgc_version.restype = ct.c_char_p
+    lib.dgc_stale_theta_factor.argtypes = [ct.c_double, ct.c_double, i32]
+    lib.dgc_stale_theta_factor.restype = ct.c_double
+    lib.dgc_stale_workspace_bytes.argtypes = [i64]
+    lib.dgc_stale_workspace_bytes.restype = i64
+    lib.dgc_stale_filter.argtypes = [vp, i64, vp, i64, i64, i32, vp, i64, ct.c_double, ct.c_double, vp, vp, vp, i64,
+                                     vp, vp, i64, vp]
     for name in EXPORTS:
-        if name not in ("dgc_last_error", "dgc_version"):
+        if name not in ("dgc_last_error", "dgc_version", "dgc_stale_theta_factor", "dgc_stale_workspace_bytes"):
             getattr(lib, name).restype = ct.c_int
     _lib = lib
     return lib
@@ -249,3 +256,45 @@ class DgcLayer:
         if what == "work_long":
             out = out.reshape(-1, 4)
         return out
+
+
+# --------------------------------------------------------------------------- stale filter
+
+STALE_RESULT_DTYPE = np.dtype([("n_send", np.int64), ("D", np.float32), ("theta", np.float32),
+                               ("n_invalid", np.int64)])
+
+
+def stale_theta_factor(l1: float, l_prev: float, variant: str = "printed") -> float:
+    f = load().dgc_stale_theta_factor(float(l1), float(l_prev), THETA_VARIANT[variant])
+    if f < 0:
+        raise ValueError("stale_theta_factor: l1 must be > 0 and l_prev finite")
+    return f
+
+
+def stale_workspace_bytes(n_candidates: int) -> int:
+    return int(load().dgc_stale_workspace_bytes(int(n_candidates)))
+
+
+def stale_filter(E, L, *, F=None, rows=None, n_rows=None, factor=None, theta=None, dist, send_idx, send_buf=None, result,
+                 workspace, stream=None):
+    """dgc_stale_filter on device tensors: E, L [R, ld] fp32; rows int64 or None (n_rows: how many of
+    its entries count, default all; torch gives an empty tensor a NULL pointer, so an empty list is a
+    non-empty tensor with n_rows = 0); dist fp32 and
+    send_idx int64 with one entry per candidate; send_buf [n, ld] or None; result: 24-byte device
+    tensor (view it with STALE_RESULT_DTYPE after a synchronisation); workspace: device bytes.
+    Exactly one of factor / theta.  Only enqueues."""
+    if (factor is None) == (theta is None):
+        raise ValueError("give exactly one of factor and theta")
+    for name, t in (("E", E), ("L", L)):
+        if t.dim() != 2 or t.stride(1) != 1:
+            raise ValueError(f"{name} must be [R, ld] with a contiguous last dimension")
+    lib = load()
+    rc = lib.dgc_stale_filter(
+        _dev(E, "E"), int(E.stride(0)), _dev(L, "L"), int(L.stride(0)), int(E.shape[0]),
+        int(E.shape[1] if F is None else F), _dev(rows, "rows"), 0 if rows is None else int(rows.numel() if n_rows is None else n_rows),
+        -1.0 if factor is None else float(factor), 0.0 if theta is None else float(theta), _dev(dist, "dist"),
+        _dev(send_idx, "send_idx"), _dev(send_buf, "send_buf"), 0 if send_buf is None else int(send_buf.stride(0)),
+        _dev(result, "result"), _dev(workspace, "workspace"), int(workspace.numel() * workspace.element_size()),
+        _stream_ptr(stream))
+    if rc != 0:
+        raise DgcError(rc, lib.dgc_last_error(None).decode())

@@ -23,6 +23,10 @@ struct Param {
 
 }  // namespace
 
+namespace dgc {
+void set_thread_error(const std::string& msg) { g_create_error = msg; }
+}  // namespace dgc
+
 struct dgc_layer {
   dgc_layer_desc_t desc{};
   int32_t T = 0;

@@ -60,6 +60,9 @@ struct GraphDev {
     }                                                                 \
   } while (0)
 
+// text that dgc_last_error(NULL) returns on the calling thread (dgc_api.hip)
+void set_thread_error(const std::string& msg);
+
 // ---- packing (dgc_pack.hip)
 void launch_segment_bounds(const GraphDev& g, Segment* segs, int64_t nseg, hipStream_t st);
 void launch_deg_inv_sqrt(const GraphDev& g, float* dinv, hipStream_t st);

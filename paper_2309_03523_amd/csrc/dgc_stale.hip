@@ -1,0 +1,282 @@
+// Adaptive stale-embedding filter (Section 5.2 of the paper) on the device: the L2 distance of
+// every candidate row to the copy transmitted last, the largest distance D, the threshold, the
+// ascending list of the rows that exceed it, their values packed as the message, and the update
+// of the stored copies.  An HBM-bound scan: every candidate row of E and L is read once.
+//
+// Launch sequence (nothing synchronises, no float atomics, the result is the same run to run):
+//   k_stale_init      result = {0, 0, 0}
+//   k_stale_dist      dist[c], block maxima folded into D with an integer max on the float's bits
+//                     (distances are >= 0, so the bit patterns order like the values)
+//   k_stale_count     candidates above the threshold per block of kSelTile
+//   exclusive scan    of the block counts
+//   k_stale_compact   send_idx in ascending order, copies of the selected rows
+#include <cmath>
+
+#include "dgc_internal.h"
+
+namespace dgc {
+namespace {
+
+constexpr int kSelBlock = 256;
+constexpr int kSelPer = 8;
+constexpr int kSelTile = kSelBlock * kSelPer;  // candidates per block of the two selection kernels
+constexpr int kDistUnroll = 4;                  // row groups a wave keeps in flight
+
+struct StaleArgs {
+  const float* E; int64_t lde;
+  float* L; int64_t ldl;
+  const int64_t* rows;  // nullptr: candidate c is row c
+  int64_t R;            // rows of E and L
+  int64_t n;            // candidates
+  int32_t F;
+  double factor;        // >= 0: threshold = factor * D; < 0: threshold = theta
+  double theta;
+  float* dist;
+  int64_t* send_idx;
+  float* send_buf; int64_t lds;
+  dgc_stale_result_t* result;
+  int64_t* counts;      // [blocks of kSelTile]
+  const int64_t* total;
+};
+
+__global__ void k_stale_init(dgc_stale_result_t* r) {
+  r->n_send = 0; r->D = 0.f; r->theta = 0.f; r->n_invalid = 0;
+}
+
+__device__ __forceinline__ float sqdiff4(const float4 a, const float4 b) {
+  const float x = a.x - b.x, y = a.y - b.y, z = a.z - b.z, w = a.w - b.w;
+  return x * x + y * y + z * z + w * w;
+}
+
+// LPR lanes share a row (a float4 each per sweep of 4*LPR columns), 64/LPR rows per wave and
+// sweep, kDistUnroll sweeps in flight.
+template <int LPR>
+__global__ __launch_bounds__(256) void k_stale_dist(StaleArgs a) {
+  constexpr int RPW = 64 / LPR;
+  const int lane = threadIdx.x & 63, sub = lane % LPR, grp = lane / LPR;
+  const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+  float dmax = 0.f;
+  for (int64_t base = wave * (RPW * kDistUnroll); base < a.n; base += n_waves * (RPW * kDistUnroll)) {
+    float acc[kDistUnroll];
+#pragma unroll
+    for (int u = 0; u < kDistUnroll; ++u) {
+      const int64_t c = base + u * RPW + grp;
+      acc[u] = 0.f;
+      const int64_t r = c < a.n ? (a.rows ? a.rows[c] : c) : -1;
+      if (c < a.n && (r < 0 || r >= a.R)) {  // a listed row outside the tensors: distance 0, counted
+        if (sub == 0) atomicAdd(reinterpret_cast<unsigned long long*>(&a.result->n_invalid), 1ull);
+      } else if (c < a.n) {
+        const float* e = a.E + r * a.lde;
+        const float* l = a.L + r * a.ldl;
+        for (int col = sub * 4; col < a.F; col += LPR * 4) {
+          if (col + 4 <= a.F) {
+            acc[u] += sqdiff4(*reinterpret_cast<const float4*>(e + col), *reinterpret_cast<const float4*>(l + col));
+          } else {
+            for (int k = col; k < a.F; ++k) { const float d = e[k] - l[k]; acc[u] += d * d; }
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kDistUnroll; ++u) {
+      float s = acc[u];
+#pragma unroll
+      for (int m = LPR / 2; m >= 1; m >>= 1) s += __shfl_xor(s, m);
+      const int64_t c = base + u * RPW + grp;
+      if (sub == 0 && c < a.n) {
+        const float d = sqrtf(s);
+        a.dist[c] = d;
+        dmax = fmaxf(dmax, d);
+      }
+    }
+  }
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) dmax = fmaxf(dmax, __shfl_xor(dmax, m));
+  __shared__ float wmax[4];
+  if (lane == 0) wmax[threadIdx.x >> 6] = dmax;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const float m = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+    atomicMax(reinterpret_cast<unsigned int*>(&a.result->D), __float_as_uint(m));
+  }
+}
+
+__device__ __forceinline__ float threshold_of(const StaleArgs& a) {
+  return a.factor >= 0.0 ? (float)(a.factor * (double)a.result->D) : (float)a.theta;
+}
+
+// bit k of the result: candidate first + k exists and is above the threshold
+__device__ __forceinline__ unsigned flags_of(const StaleArgs& a, int64_t first, float th) {
+  unsigned f = 0;
+  if (first + kSelPer <= a.n) {
+    const float4 d0 = *reinterpret_cast<const float4*>(a.dist + first);
+    const float4 d1 = *reinterpret_cast<const float4*>(a.dist + first + 4);
+    f = (d0.x > th) | (d0.y > th) << 1 | (d0.z > th) << 2 | (d0.w > th) << 3 | (d1.x > th) << 4 | (d1.y > th) << 5 |
+        (d1.z > th) << 6 | (d1.w > th) << 7;
+  } else {
+    for (int k = 0; k < kSelPer; ++k)
+      if (first + k < a.n && a.dist[first + k] > th) f |= 1u << k;
+  }
+  return f;
+}
+
+__global__ __launch_bounds__(kSelBlock) void k_stale_count(StaleArgs a) {
+  const float th = threshold_of(a);
+  const int64_t first = (int64_t)blockIdx.x * kSelTile + threadIdx.x * kSelPer;
+  int cnt = __popc(flags_of(a, first, th));
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) cnt += __shfl_xor(cnt, m);
+  __shared__ int wsum[kSelBlock / 64];
+  if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = cnt;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int s = 0;
+    for (int w = 0; w < kSelBlock / 64; ++w) s += wsum[w];
+    a.counts[blockIdx.x] = s;
+  }
+}
+
+// counts now holds the exclusive scan.  Thread order = candidate order, so the block's selected
+// rows land in ascending order; they are then copied LPR lanes to a row.
+template <int LPR>
+__global__ __launch_bounds__(kSelBlock) void k_stale_compact(StaleArgs a) {
+  __shared__ int64_t sel_row[kSelTile];
+  __shared__ int wbase[kSelBlock / 64 + 1];
+  const float th = threshold_of(a);
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int64_t first = (int64_t)blockIdx.x * kSelTile + threadIdx.x * kSelPer;
+  const unsigned f = flags_of(a, first, th);
+  const int cnt = __popc(f);
+  int incl = cnt;  // inclusive scan over the wave
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1) {
+    const int v = __shfl_up(incl, m);
+    if (lane >= m) incl += v;
+  }
+  if (lane == 63) wbase[w + 1] = incl;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    wbase[0] = 0;
+    for (int i = 1; i <= kSelBlock / 64; ++i) wbase[i] += wbase[i - 1];
+  }
+  __syncthreads();
+  const int64_t off = a.counts[blockIdx.x];
+  int pos = wbase[w] + incl - cnt;
+  for (int k = 0; k < kSelPer; ++k)
+    if (f >> k & 1) {
+      const int64_t r = a.rows ? a.rows[first + k] : first + k;
+      sel_row[pos] = r;
+      a.send_idx[off + pos] = r;
+      ++pos;
+    }
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    a.result->n_send = *a.total;
+    a.result->theta = th;
+  }
+  __syncthreads();
+  const int n_sel = wbase[kSelBlock / 64];
+  constexpr int RPB = kSelBlock / LPR;
+  const int sub = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+  for (int i = grp; i < n_sel; i += RPB) {
+    const int64_t r = sel_row[i];
+    const float* e = a.E + r * a.lde;
+    float* l = a.L + r * a.ldl;
+    float* s = a.send_buf ? a.send_buf + (off + i) * a.lds : nullptr;
+    for (int col = sub * 4; col < a.F; col += LPR * 4) {
+      if (col + 4 <= a.F) {
+        const float4 v = *reinterpret_cast<const float4*>(e + col);
+        *reinterpret_cast<float4*>(l + col) = v;
+        if (s) *reinterpret_cast<float4*>(s + col) = v;
+      } else {
+        for (int k = col; k < a.F; ++k) { l[k] = e[k]; if (s) s[k] = e[k]; }
+      }
+    }
+  }
+}
+
+int64_t sel_blocks(int64_t n) { return (n + kSelTile - 1) / kSelTile; }
+
+template <int LPR>
+void launch_all(const StaleArgs& a, int64_t* scan_tmp, int64_t* total, hipStream_t st) {
+  constexpr int RPW = 64 / LPR;
+  const int64_t per_block = 4 * RPW * kDistUnroll;
+  const unsigned grid = (unsigned)std::min<int64_t>((a.n + per_block - 1) / per_block, 256 * 32);
+  hipLaunchKernelGGL(k_stale_dist<LPR>, grid, 256, 0, st, a);
+  const unsigned nb = (unsigned)sel_blocks(a.n);
+  hipLaunchKernelGGL(k_stale_count, nb, kSelBlock, 0, st, a);
+  launch_exclusive_scan(a.counts, nb, scan_tmp, total, st);
+  hipLaunchKernelGGL(k_stale_compact<LPR>, nb, kSelBlock, 0, st, a);
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+}  // namespace
+}  // namespace dgc
+
+using namespace dgc;
+
+extern "C" {
+
+double dgc_stale_theta_factor(double l1, double l_prev, int32_t variant) {
+  if (!(l1 > 0.0) || !std::isfinite(l_prev) || (variant != DGC_THETA_PRINTED && variant != DGC_THETA_SIGMOID)) return -1.0;
+  const double norm = (l1 - l_prev) / l1;
+  return 1.0 / (1.0 + std::exp(variant == DGC_THETA_PRINTED ? norm : -norm));
+}
+
+int64_t dgc_stale_workspace_bytes(int64_t n_candidates) {
+  if (n_candidates < 0) return -1;
+  const int64_t nb = sel_blocks(n_candidates);
+  return 8 * (nb + 1 + scan_tmp_elems(nb) + 1);
+}
+
+dgc_status_t dgc_stale_filter(const float* E, int64_t lde, float* L, int64_t ldl, int64_t R, int32_t F,
+                              const int64_t* rows, int64_t n_rows, double factor, double theta, float* dist,
+                              int64_t* send_idx, float* send_buf, int64_t lds, dgc_stale_result_t* result,
+                              void* workspace, int64_t workspace_bytes, void* stream) {
+  auto bad = [](dgc_status_t code, const char* msg) { set_thread_error(msg); return code; };
+  if (!E || !L || !result || !workspace) return bad(DGC_ERR_INVALID_ARG, "stale filter: NULL argument");
+  if (R < 0 || F < 1 || F > 4096) return bad(DGC_ERR_INVALID_ARG, "stale filter: R must be >= 0 and F in [1, 4096]");
+  if (lde < F || ldl < F || lde % 4 || ldl % 4 || !aligned16(E) || !aligned16(L))
+    return bad(DGC_ERR_INVALID_ARG, "stale filter: E, L need a pitch >= F that is a multiple of 4 and 16-byte alignment");
+  if (send_buf && (lds < F || lds % 4 || !aligned16(send_buf)))
+    return bad(DGC_ERR_INVALID_ARG, "stale filter: send_buf needs a pitch >= F that is a multiple of 4 and 16-byte alignment");
+  if (rows ? n_rows < 0 || n_rows > R : n_rows != 0)
+    return bad(DGC_ERR_INVALID_ARG, "stale filter: n_rows must be in [0, R] with a row list and 0 without");
+  const int64_t n = rows ? n_rows : R;
+  if (n > 0 && (!dist || !send_idx || !aligned16(dist)))
+    return bad(DGC_ERR_INVALID_ARG, "stale filter: dist (16-byte aligned) and send_idx must hold one entry per candidate");
+  if (!(factor >= 0.0) && !(theta >= 0.0))
+    return bad(DGC_ERR_INVALID_ARG, "stale filter: give factor >= 0, or factor < 0 and theta >= 0");
+  if (factor >= 0.0 && !std::isfinite(factor)) return bad(DGC_ERR_INVALID_ARG, "stale filter: factor is not finite");
+  if (workspace_bytes < dgc_stale_workspace_bytes(n) || (reinterpret_cast<uintptr_t>(workspace) & 7))
+    return bad(DGC_ERR_INVALID_ARG, "stale filter: workspace too small (dgc_stale_workspace_bytes) or not 8-byte aligned");
+  {  // E and L are read and written by different blocks of one launch: they must not overlap
+    const char* e0 = reinterpret_cast<const char*>(E); const char* e1 = e0 + 4 * (R * lde);
+    const char* l0 = reinterpret_cast<const char*>(L); const char* l1 = l0 + 4 * (R * ldl);
+    if (R > 0 && e0 < l1 && l0 < e1) return bad(DGC_ERR_INVALID_ARG, "stale filter: E and L overlap");
+  }
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipLaunchKernelGGL(k_stale_init, 1, 1, 0, st, result);
+  if (n > 0) {
+    const int64_t nb = sel_blocks(n);
+    int64_t* ws = static_cast<int64_t*>(workspace);
+    StaleArgs a{};
+    a.E = E; a.lde = lde; a.L = L; a.ldl = ldl; a.rows = rows; a.R = R; a.n = n; a.F = F;
+    a.factor = factor >= 0.0 ? factor : -1.0; a.theta = theta;
+    a.dist = dist; a.send_idx = send_idx; a.send_buf = send_buf; a.lds = lds; a.result = result;
+    a.counts = ws; a.total = ws + nb + 1;
+    int64_t* scan_tmp = ws + nb + 2;
+    int64_t* total = ws + nb + 1;
+    if (F <= 16) launch_all<4>(a, scan_tmp, total, st);
+    else if (F <= 32) launch_all<8>(a, scan_tmp, total, st);
+    else if (F <= 64) launch_all<16>(a, scan_tmp, total, st);
+    else if (F <= 128) launch_all<32>(a, scan_tmp, total, st);
+    else launch_all<64>(a, scan_tmp, total, st);
+  }
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return bad(DGC_ERR_DEVICE, hipGetErrorString(e));
+  return DGC_OK;
+}
+
+}  // extern "C"

@@ -522,21 +522,30 @@ def presence(seed: int, T: int, N: int, p_lo: float = 0.15, p_hi: float = 1.0) -
 
 
 def drifted_copies(seed: int, R: int, F: int, median: float = 0.34, sigma: float = 1.0,
-                   unchanged: float = 0.1):
+                   unchanged: float = 0.1, kind: str = "lognormal", d_max: float = 2.0):
     """Current embeddings E ~ N(0,1) [R,F] and the copies L sent last, fp32.  Row r has drifted by a
-    Gaussian vector whose length is log-normal (median `median`, log-std `sigma`): about 85 % of the
-    distances are below 1, a long tail above, as in the distance CDFs the paper plots; a fraction
-    `unchanged` of the rows has not moved at all (L = E bit for bit)."""
+    Gaussian vector of a drawn length; a fraction `unchanged` of the rows has not moved at all
+    (L = E bit for bit).  kind="lognormal": lengths log-normal (median `median`, log-std `sigma`):
+    about 85 % of the distances below 1 and a long tail above, as in the distance CDFs the paper
+    plots.  kind="triangular": length = d_max (1 - sqrt(U)), i.e. a fraction (1 - x)^2 of the rows
+    lies beyond x times the largest distance: 49 / 25 / 9 / 1 % at x = 0.3 / 0.5 / 0.7 / 0.9, the
+    traffic left over at those static thresholds in the paper's accuracy table (its Amazon and
+    Epinion rows) within a few points."""
     rng = stream(seed, "drift")
     E = _normal_f32(rng, (R, F))
-    length = np.exp(rng.normal(np.log(median), sigma, size=R)).astype(np.float32)
+    if kind == "lognormal":
+        length = np.exp(rng.normal(np.log(median), sigma, size=R)).astype(np.float32)
+    elif kind == "triangular":
+        length = (d_max * (1.0 - np.sqrt(rng.random(R)))).astype(np.float32)
+    else:
+        raise ValueError(kind)
     length[rng.random(R) < unchanged] = 0.0
     L = np.empty_like(E)
     step = 1 << 18
     for a in range(0, R, step):
         b = min(R, a + step)
         d = rng.standard_normal((b - a, F), dtype=np.float32)
-        d *= (length[a:b] / np.sqrt(np.float32(F)))[:, None]
+        d *= (length[a:b] / np.sqrt((d * d).sum(axis=1)).clip(1e-30))[:, None]   # drift of exactly that length
         np.subtract(E[a:b], d, out=L[a:b])
     return E, L
 

@@ -103,3 +103,25 @@ def test_product_does_not_import_the_oracle():
                 assert "dgc_oracle" not in text, f
     assert "paper_2309_03523_amd" not in open(os.path.join(ROOT, "oracle", "__init__.py")).read()
     assert np.True_
+
+
+def test_stale_threshold_factor_and_host_checks(lib):
+    import math
+    lib.dgc_stale_theta_factor.restype = ct.c_double
+    lib.dgc_stale_theta_factor.argtypes = [ct.c_double, ct.c_double, ct.c_int32]
+    lib.dgc_stale_workspace_bytes.restype = ct.c_int64
+    lib.dgc_stale_workspace_bytes.argtypes = [ct.c_int64]
+    f = lib.dgc_stale_theta_factor
+    assert f(2.0, 2.0, 0) == 0.5 and f(2.0, 2.0, 1) == 0.5               # no loss decrease yet
+    assert abs(f(3.0, 0.0, 0) - 1.0 / (1.0 + math.e)) < 1e-15            # the equation as printed, norm = 1
+    assert abs(f(3.0, 0.0, 1) - math.e / (1.0 + math.e)) < 1e-15
+    assert abs(f(1.0, 0.3, 0) + f(1.0, 0.3, 1) - 1.0) < 1e-15
+    assert f(0.0, 1.0, 0) < 0 and f(1.0, 1.0, 7) < 0 and f(1.0, float("nan"), 0) < 0
+    w = [lib.dgc_stale_workspace_bytes(n) for n in (0, 1, 2048, 2049, 10 ** 7)]
+    assert w[0] > 0 and all(a <= b for a, b in zip(w, w[1:])) and lib.dgc_stale_workspace_bytes(-1) < 0
+    lib.dgc_stale_filter.restype = ct.c_int
+    lib.dgc_stale_filter.argtypes = [ct.c_void_p, ct.c_int64, ct.c_void_p, ct.c_int64, ct.c_int64, ct.c_int32,
+                                     ct.c_void_p, ct.c_int64, ct.c_double, ct.c_double, ct.c_void_p, ct.c_void_p,
+                                     ct.c_void_p, ct.c_int64, ct.c_void_p, ct.c_void_p, ct.c_int64, ct.c_void_p]
+    assert lib.dgc_stale_filter(None, 0, None, 0, 0, 0, None, 0, 0.5, 0.0, None, None, None, 0, None, None, 0, None) == 1
+    assert b"stale filter" in lib.dgc_last_error(None)
