@@ -29,7 +29,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config2s", "config2tf", "config3w", "config4s", "config4", "config5s", "config5", "stale"])
+    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config2s", "config2tf", "config3w", "config4s", "config4", "config5s", "config5", "stale", "fusion"])
     ap.add_argument("--gather-mode", default="in_place", choices=["in_place", "staged"])
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -404,6 +404,75 @@ def stale_main(args):
     print(json.dumps(out))
 
 
+def fusion_main(args):
+    """Spatial-fusion selection (Section 5.1.1) on config 2: one step = the device estimate of the rows
+    every pair of the 64 chunks would load twice; the greedy selection under a memory cap follows."""
+    import numpy as np
+    import torch
+    from paper_2309_03523_amd import binding
+    from paper_2309_03523_amd.runner import DeviceWorkload
+    t0 = time.perf_counter()
+    wl, desc = make_workload("config2", args.seed)
+    t_gen = time.perf_counter() - t0
+    dw = DeviceWorkload(wl)
+    layer = dw.layer
+    stream = torch.cuda.current_stream()
+    S = layer.shared_rows(stream)
+    for _ in range(args.warmup):
+        layer.shared_rows(stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        layer.shared_rows(stream)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms = 1e3 * elapsed / args.steps
+    rows = wl.graph.T * wl.graph.N
+    halo = int(layer.packing("halo_ptr")[-1])
+    own = wl.rows
+    n = len(wl.chunks)
+    pairs = int(np.triu(S).sum())                       # counter increments of the pair kernel
+    marks = own + halo                                  # bits set by the marking kernel
+    ch = np.asarray(wl.chunks)
+    mem = ((ch[:, 1] - ch[:, 0]) * (ch[:, 3] - ch[:, 2])).astype(np.int64) * (wl.F + wl.S + wl.H) * 4
+    seg_halo = np.diff(layer.packing("halo_ptr"))
+    win = ch[:, 3] - ch[:, 2]
+    mem += np.add.reduceat(seg_halo, np.concatenate([[0], np.cumsum(win)[:-1]])) * wl.F * 4
+    cap = int(mem.sum() // 8)
+    t0 = time.perf_counter()
+    grp = binding.fusion_select(S, mem, cap)
+    t_sel = time.perf_counter() - t0
+    saved = int(sum(S[a, b] for a in range(n) for b in range(a + 1, n) if grp[a] == grp[b]))
+    # LDS integer atomics: 32 banks x one atomic per clock x 256 CUs x 2.4 GHz
+    peak = 256 * 32 * 2.4
+    out = {"metric": "(snapshot, vertex) rows scanned/s (redundant-loading estimate between chunks)",
+           "value": rows * args.steps / elapsed, "unit": "rows/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u64",
+           "data": "synthetic",
+           "config": {"workload": "spatial-fusion selection on " + desc, "chunks": n, "rows": rows,
+                      "halo_entries": halo, "pair_increments": pairs},
+           "roofline": {"kernel": "k_fs_pairs<true> (+ k_fs_zero, k_fs_mark; whole call incl. the 32 KB read-back)",
+                        "bound": "alu", "achieved": pairs / (ms * 1e-3) / 1e9, "peak": peak, "unit": "Gatomic/s",
+                        "frac": pairs / (ms * 1e-3) / 1e9 / peak, "traffic": None,
+                        "ops_per_launch": pairs, "ms_per_launch": ms,
+                        "hbm_bytes_algorithmic": marks * 8 + halo * 4 + rows * 8 * 2},
+           "selection": {"cap_bytes": cap, "groups": int(grp.max()) + 1, "largest_group_bytes": int(np.bincount(grp, weights=mem).max()),
+                         "rows_loaded_once_instead_of_twice": saved, "of_all_shared": pairs, "select_s": t_sel},
+           "setup_s": {"generate": t_gen}}
+    if not args.no_cpu_baseline:
+        from oracle import fusion
+        k = 16
+        t0 = time.perf_counter()
+        want = fusion.shared_rows(wl.graph, wl.chunks[:k])
+        t_cpu = time.perf_counter() - t0
+        sample_rows = int(sum((c[1] - c[0]) * (c[3] - c[2]) for c in ch[:k]))
+        out["cpu_baseline"] = {"value": sample_rows / t_cpu, "unit": "rows/s", "cores": 1, "kind": "oracle",
+                               "sample": f"load sets and pairwise intersections of the first {k} chunks ({sample_rows} "
+                                         f"own rows), {t_cpu:.1f} s (Python sets)",
+                               "gpu_matches_bit_exact": bool((S[:k, :k] == want).all())}
+    print(json.dumps(out))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -412,11 +481,11 @@ def main():
         sys.exit(2)
     import numpy as np
     import torch
-    if args.workload == "stale":
+    if args.workload in ("stale", "fusion"):
         if not torch.cuda.is_available():
             print("bench.py needs a GPU", file=sys.stderr)
             sys.exit(2)
-        stale_main(args)
+        (stale_main if args.workload == "stale" else fusion_main)(args)
         return
     if args.workload.startswith("config5"):
         if not torch.cuda.is_available():

@@ -248,6 +248,35 @@ dgc_status_t dgc_layer_stage_times(dgc_layer_t* layer, float* host_ms);
 dgc_status_t dgc_layer_packing(dgc_layer_t* layer, const char* what, void* host_dst,
                                int64_t capacity_bytes, int64_t* needed_bytes);
 
+/* Spatial-fusion selection (Section 5.1.1) and chunk assignment (Section 4.2, Algorithm 1).
+ *
+ * dgc_layer_shared_rows: the estimate of redundant loading between the chunks of the layer.  A
+ *   chunk loads its own (snapshot, vertex) rows and, per snapshot of its window, the neighbours of
+ *   its rows outside its vertex range; host_out (host int64 [n_chunks][n_chunks], symmetric, zero
+ *   diagonal) entry (a, b) receives the number of rows both a and b load - loaded twice when the
+ *   two are processed one after the other, once when they are fused.  Computed on the device from
+ *   the packing; the first call allocates a bitmap of T*N*ceil(n_chunks/64) 8-byte words that the
+ *   layer keeps (DGC_ERR_OOM if it does not fit); synchronises `stream`.
+ *
+ * dgc_fusion_select (host arithmetic): greedy fusion under a memory cap.  Every chunk starts as
+ *   its own group; repeatedly, among the pairs of groups whose memories (sums of mem[], the
+ *   per-chunk memory the caller measured) add up to at most `cap`, the pair with the largest shared
+ *   amount (sum of shared[] over the members) is fused; ties go to the pair with the smallest
+ *   (first, second) group, a group being named by its smallest member; stops when no pair fits.
+ *   shared: int64 [n][n] symmetric, non-negative.  group_out int32 [n]: group of every chunk,
+ *   groups numbered in ascending order of their smallest member.
+ *
+ * dgc_chunk_assign (host arithmetic): Algorithm 1.  Chunks in decreasing order of the predicted
+ *   workload g[] (ties: smaller index first); chunk a goes to the GPU m with the largest
+ *   s_m = (g_bar - sum of g over Q_m) * (sum of h(a, a') over a' in Q_m), g_bar = sum(g) / n_gpus,
+ *   Q_m = the chunks already on m; equal scores go to the GPU with the smaller assigned load, then
+ *   the smaller index.  g double [n], h double [n][n], x_out int32 [n].
+ * The last two return DGC_ERR_INVALID_ARG with the text in dgc_last_error(NULL). */
+dgc_status_t dgc_layer_shared_rows(dgc_layer_t* layer, int64_t* host_out, void* stream);
+dgc_status_t dgc_fusion_select(int32_t n, const int64_t* shared, const int64_t* mem, int64_t cap,
+                               int32_t* group_out);
+dgc_status_t dgc_chunk_assign(int32_t n, const double* g, const double* h, int32_t n_gpus, int32_t* x_out);
+
 /* Adaptive stale-embedding filter (Section 5.2): an embedding is transmitted again only if its L2
  * distance to the copy transmitted last exceeds a threshold that follows the training loss.  The
  * paper computes the distances on the CPU; here the whole step runs on the device.

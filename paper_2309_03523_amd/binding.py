@@ -28,7 +28,8 @@ STATUS = {0: "DGC_OK", 1: "DGC_ERR_INVALID_ARG", 2: "DGC_ERR_BAD_GRAPH", 3: "DGC
 EXPORTS = ["dgc_layer_create", "dgc_layer_destroy", "dgc_layer_set_param", "dgc_layer_get_param",
            "dgc_layer_forward", "dgc_layer_backward", "dgc_layer_aggregate", "dgc_layer_gather",
            "dgc_layer_packing", "dgc_layer_set_presence", "dgc_layer_set_profiling", "dgc_layer_stage_times", "dgc_last_error",
-           "dgc_version", "dgc_stale_theta_factor", "dgc_stale_workspace_bytes", "dgc_stale_filter"]
+           "dgc_version", "dgc_stale_theta_factor", "dgc_stale_workspace_bytes", "dgc_stale_filter",
+           "dgc_layer_shared_rows", "dgc_fusion_select", "dgc_chunk_assign"]
 THETA_VARIANT = {"printed": 0, "sigmoid": 1}
 N_STAGES = 13
 
@@ -83,6 +84,9 @@ def load() -> ct.CDLL:
     lib.dgc_last_error.argtypes = [vp]
     lib.dgc_last_error.restype = ct.c_char_p
     lib.dgc_version.restype = ct.c_char_p
+    lib.dgc_layer_shared_rows.argtypes = [vp, vp, vp]
+    lib.dgc_fusion_select.argtypes = [i32, vp, vp, i64, vp]
+    lib.dgc_chunk_assign.argtypes = [i32, vp, vp, i32, vp]
     lib.dgc_stale_theta_factor.argtypes = [ct.c_double, ct.c_double, i32]
     lib.dgc_stale_theta_factor.restype = ct.c_double
     lib.dgc_stale_workspace_bytes.argtypes = [i64]
@@ -230,6 +234,13 @@ class DgcLayer:
                                                int(halo.stride(0)), _stream_ptr(stream)))
         return halo
 
+    def shared_rows(self, stream=None) -> np.ndarray:
+        """int64 [n_chunks, n_chunks]: rows every pair of chunks would load twice."""
+        n = len(self.chunks)
+        out = np.zeros((n, n), np.int64)
+        self._check(self._lib.dgc_layer_shared_rows(self._h, out.ctypes.data_as(ct.c_void_p), _stream_ptr(stream)))
+        return out
+
     # -- measurement
     def set_profiling(self, enable: bool):
         self._check(self._lib.dgc_layer_set_profiling(self._h, int(bool(enable))))
@@ -298,3 +309,36 @@ def stale_filter(E, L, *, F=None, rows=None, n_rows=None, factor=None, theta=Non
         _stream_ptr(stream))
     if rc != 0:
         raise DgcError(rc, lib.dgc_last_error(None).decode())
+
+
+# --------------------------------------------------------------------------- fusion selection, assignment
+
+
+def fusion_select(shared: np.ndarray, mem: np.ndarray, cap: int) -> np.ndarray:
+    shared = np.ascontiguousarray(shared, np.int64)
+    mem = np.ascontiguousarray(mem, np.int64)
+    n = mem.size
+    if shared.shape != (n, n):
+        raise ValueError("shared must be [n, n]")
+    out = np.zeros(n, np.int32)
+    lib = load()
+    rc = lib.dgc_fusion_select(n, shared.ctypes.data_as(ct.c_void_p), mem.ctypes.data_as(ct.c_void_p), int(cap),
+                               out.ctypes.data_as(ct.c_void_p))
+    if rc != 0:
+        raise DgcError(rc, lib.dgc_last_error(None).decode())
+    return out
+
+
+def chunk_assign(g: np.ndarray, h: np.ndarray, n_gpus: int) -> np.ndarray:
+    g = np.ascontiguousarray(g, np.float64)
+    h = np.ascontiguousarray(h, np.float64)
+    n = g.size
+    if h.shape != (n, n):
+        raise ValueError("h must be [n, n]")
+    out = np.zeros(n, np.int32)
+    lib = load()
+    rc = lib.dgc_chunk_assign(n, g.ctypes.data_as(ct.c_void_p), h.ctypes.data_as(ct.c_void_p), int(n_gpus),
+                              out.ctypes.data_as(ct.c_void_p))
+    if rc != 0:
+        raise DgcError(rc, lib.dgc_last_error(None).decode())
+    return out

@@ -62,6 +62,8 @@ struct dgc_layer {
   hipEvent_t evd[8] = {};                        // its stage boundaries: forward 0..3, backward 4..7
   bool evd_fwd = false, evd_bwd = false;
   TFusion tf{};                                  // temporal-fusion packing (dgc_layer_set_presence)
+  unsigned long long* fs_mask = nullptr;         // loader bitmap and pair counters of dgc_layer_shared_rows,
+  unsigned long long* fs_out = nullptr;          // allocated by its first call
   std::vector<ChunkInfo> cinfo_host;
   bool has_grads = false;
   std::map<std::string, Param> params;
@@ -935,6 +937,33 @@ dgc_status_t dgc_layer_backward(dgc_layer_t* L, const void* Yv, int64_t ldy, con
   if (prof) { DGC_HIP_TRY(hipEventRecord(L->evx[5], st)); L->evx_bwd = true; }
   DGC_HIP_TRY(hipGetLastError());
   L->has_grads = true;
+  return DGC_OK;
+}
+
+dgc_status_t dgc_layer_shared_rows(dgc_layer_t* L, int64_t* host_out, void* stream) {
+  if (!L) return DGC_ERR_INVALID_ARG;
+  Failer fail{L};
+  if (!host_out) return fail(DGC_ERR_INVALID_ARG, "host_out is NULL");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int32_t n = L->n_chunks;
+  if (!L->fs_mask) {
+    if (dev_alloc(L, &L->fs_mask, shared_rows_mask_words(L->T, L->N, n)) != hipSuccess) {
+      L->fs_mask = nullptr;
+      return fail(DGC_ERR_OOM, "shared rows: the loader bitmap does not fit the device");
+    }
+    if (dev_alloc(L, &L->fs_out, (int64_t)n * n) != hipSuccess) {
+      L->fs_mask = nullptr;    // the bitmap stays in the layer's allocation list and is freed with it
+      return fail(DGC_ERR_OOM, "shared rows: out of device memory");
+    }
+  }
+  launch_shared_rows(L->d_segs, L->nseg, L->d_halo_ptr, L->d_halo_idx, L->T, L->N, n, L->fs_mask, L->fs_out, st);
+  hipError_t e = hipMemcpyAsync(host_out, L->fs_out, sizeof(int64_t) * (size_t)n * n, hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  if (e != hipSuccess) return fail(DGC_ERR_DEVICE, std::string("shared rows: ") + hipGetErrorString(e));
+  for (int32_t a = 0; a < n; ++a) {      // the kernel fills the upper triangle
+    host_out[(int64_t)a * n + a] = 0;
+    for (int32_t b = a + 1; b < n; ++b) host_out[(int64_t)b * n + a] = host_out[(int64_t)a * n + b];
+  }
   return DGC_OK;
 }
 

@@ -89,6 +89,12 @@ void launch_long_fill(const GraphDev& g, const Segment* segs, int64_t nseg, int6
                       hipStream_t st);
 void launch_validate_graph(const GraphDev& g, int32_t* flags /*[4]*/, hipStream_t st);
 
+// ---- redundant-loading estimate between chunks (dgc_fusion.hip)
+// mask: T*N*ceil(n_chunks/64) words, out: n_chunks*n_chunks counters (upper triangle is filled)
+int64_t shared_rows_mask_words(int32_t T, int64_t N, int32_t n_chunks);
+void launch_shared_rows(const Segment* segs, int64_t nseg, const int64_t* halo_ptr, const int32_t* halo_idx, int32_t T,
+                        int64_t N, int32_t n_chunks, unsigned long long* mask, unsigned long long* out, hipStream_t st);
+
 // ---- aggregation / gather (dgc_spmm.hip)
 struct SpmmArgs {
   GraphDev g;

@@ -125,3 +125,30 @@ def test_stale_threshold_factor_and_host_checks(lib):
                                      ct.c_void_p, ct.c_int64, ct.c_void_p, ct.c_void_p, ct.c_int64, ct.c_void_p]
     assert lib.dgc_stale_filter(None, 0, None, 0, 0, 0, None, 0, 0.5, 0.0, None, None, None, 0, None, None, 0, None) == 1
     assert b"stale filter" in lib.dgc_last_error(None)
+
+
+def test_fusion_select_and_chunk_assign_match_the_oracle():
+    # host arithmetic behind the C ABI: no GPU needed
+    from oracle import fusion
+    from paper_2309_03523_amd import binding
+    rng = np.random.default_rng(0)
+    for trial in range(25):
+        n = int(rng.integers(1, 24))
+        sh = rng.integers(0, 40, (n, n))
+        sh = np.triu(sh, 1) + np.triu(sh, 1).T
+        sh[rng.random((n, n)) < 0.3] = 0
+        sh = np.minimum(sh, sh.T)
+        mem = rng.integers(0, 20, n)
+        cap = int(rng.integers(5, 70))
+        np.testing.assert_array_equal(binding.fusion_select(sh, mem, cap), fusion.select_fusion(sh, mem, cap))
+        g = rng.integers(1, 50, n).astype(float)          # integer-valued: sums are exact in any order
+        h = rng.integers(0, 9, (n, n)).astype(float)
+        h = np.triu(h, 1) + np.triu(h, 1).T
+        for n_gpus in (1, 2, 3, 8):
+            np.testing.assert_array_equal(binding.chunk_assign(g, h, n_gpus), fusion.assign_chunks(g, h, n_gpus))
+    with pytest.raises(binding.DgcError, match="symmetric"):
+        binding.fusion_select(np.array([[0, 1], [2, 0]]), np.array([1, 1]), 5)
+    with pytest.raises(binding.DgcError, match="negative memory"):
+        binding.fusion_select(np.zeros((2, 2), np.int64), np.array([1, -1]), 5)
+    with pytest.raises(binding.DgcError, match="n_gpus"):
+        binding.chunk_assign(np.ones(2), np.zeros((2, 2)), 0)
