@@ -29,7 +29,7 @@ EXPORTS = ["dgc_layer_create", "dgc_layer_destroy", "dgc_layer_set_param", "dgc_
            "dgc_layer_forward", "dgc_layer_backward", "dgc_layer_aggregate", "dgc_layer_gather",
            "dgc_layer_packing", "dgc_layer_set_presence", "dgc_layer_set_profiling", "dgc_layer_stage_times", "dgc_last_error",
            "dgc_version", "dgc_stale_theta_factor", "dgc_stale_workspace_bytes", "dgc_stale_filter",
-           "dgc_layer_shared_rows", "dgc_fusion_select", "dgc_chunk_assign"]
+           "dgc_layer_shared_rows", "dgc_fusion_select", "dgc_chunk_assign", "dgc_chunk_generate"]
 THETA_VARIANT = {"printed": 0, "sigmoid": 1}
 N_STAGES = 13
 
@@ -84,6 +84,7 @@ def load() -> ct.CDLL:
     lib.dgc_last_error.argtypes = [vp]
     lib.dgc_last_error.restype = ct.c_char_p
     lib.dgc_version.restype = ct.c_char_p
+    lib.dgc_chunk_generate.argtypes = [ct.POINTER(GraphT), i32, i32, i64, i32, vp, ct.POINTER(i32), ct.POINTER(i32), vp]
     lib.dgc_layer_shared_rows.argtypes = [vp, vp, vp]
     lib.dgc_fusion_select.argtypes = [i32, vp, vp, i64, vp]
     lib.dgc_chunk_assign.argtypes = [i32, vp, vp, i32, vp]
@@ -342,3 +343,24 @@ def chunk_assign(g: np.ndarray, h: np.ndarray, n_gpus: int) -> np.ndarray:
     if rc != 0:
         raise DgcError(rc, lib.dgc_last_error(None).decode())
     return out
+
+
+# --------------------------------------------------------------------------- chunk generation
+
+
+def chunk_generate(rowptr, colidx, N: int, *, w_s: int, w_t: int, cap: int, max_iters: int, labels, stream=None):
+    """dgc_chunk_generate: rowptr / colidx lists of T device tensors, labels int32 device tensor
+    [T*N] (written).  Returns (iterations, converged)."""
+    T = len(rowptr)
+    rp = (ct.c_void_p * T)(*[r.data_ptr() for r in rowptr])
+    cj = (ct.c_void_p * T)(*[c.data_ptr() for c in colidx])
+    graph = GraphT(T, N, rp, cj)
+    if labels.numel() != T * N or labels.element_size() != 4 or not labels.is_contiguous():
+        raise ValueError("labels must be a contiguous int32 device tensor of T*N elements")
+    it, conv = ct.c_int32(0), ct.c_int32(0)
+    lib = load()
+    rc = lib.dgc_chunk_generate(ct.byref(graph), int(w_s), int(w_t), int(cap), int(max_iters), _dev(labels, "labels"),
+                                ct.byref(it), ct.byref(conv), _stream_ptr(stream))
+    if rc != 0:
+        raise DgcError(rc, lib.dgc_last_error(None).decode())
+    return it.value, bool(conv.value)

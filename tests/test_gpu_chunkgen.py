@@ -1,0 +1,72 @@
+"""Label-propagation chunk generation on the GPU (Section 4.1) against the oracle: labels of every
+super-vertex, the iteration count and the convergence flag, bit for bit."""
+import numpy as np
+import pytest
+
+from oracle import chunkgen
+from paper_2309_03523_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(graph, w_s, w_t, cap, max_iters):
+    import torch
+    from paper_2309_03523_amd import binding
+    rp = [torch.from_numpy(s.rowptr).cuda() for s in graph.snaps]
+    ci = [torch.from_numpy(s.col).cuda() for s in graph.snaps]
+    labels = torch.full((graph.T * graph.N,), -5, dtype=torch.int32, device="cuda")
+    it, conv = binding.chunk_generate(rp, ci, graph.N, w_s=w_s, w_t=w_t, cap=cap, max_iters=max_iters, labels=labels)
+    return labels.cpu().numpy().astype(np.int64), it, conv
+
+
+def _graph(seed, T, N, avg_deg, hub):
+    return synth.random_small(seed, T, N, 4, 32, 32, avg_deg, [[0, N, 0, T]], "gru", hub=hub).graph
+
+
+CASES = {
+    "hub_260": dict(g=lambda: _graph(5, 8, 260, 4.0, True), w=(2, 1), cap=64, iters=500),
+    "hub_3000_three_passes": dict(g=lambda: _graph(6, 2, 3000, 5.0, True), w=(1, 1), cap=400, iters=500),
+    "dense_rows_around_the_split": dict(g=lambda: _graph(7, 3, 400, 30.0, False), w=(1, 3), cap=10 ** 9, iters=500),
+    "no_temporal_weight": dict(g=lambda: _graph(8, 4, 300, 4.0, False), w=(1, 0), cap=50, iters=500),
+    "no_spatial_weight": dict(g=lambda: _graph(9, 5, 200, 4.0, True), w=(0, 1), cap=3, iters=500),
+    "cap_one_nothing_moves": dict(g=lambda: _graph(10, 2, 150, 4.0, False), w=(1, 1), cap=1, iters=500),
+    "stopped_early": dict(g=lambda: _graph(11, 4, 500, 6.0, True), w=(2, 1), cap=100, iters=3),
+    "single_snapshot": dict(g=lambda: _graph(12, 1, 700, 8.0, True), w=(1, 1), cap=10 ** 9, iters=500),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_labels_match_oracle(name):
+    c = CASES[name]
+    g = c["g"]()
+    want = chunkgen.propagate(g, c["w"][0], c["w"][1], c["cap"], c["iters"])
+    got, it, conv = _run(g, c["w"][0], c["w"][1], c["cap"], c["iters"])
+    deg = max(int(np.diff(s.rowptr).max()) for s in g.snaps)
+    sizes = np.bincount(want["labels"])
+    print(f"{name}: {g.T * g.N} super-vertices, longest row {deg}, {want['iterations']} iterations, "
+          f"{int((sizes > 0).sum())} chunks, largest {int(sizes.max())}, converged {want['converged']}", flush=True)
+    assert (it, conv) == (want["iterations"], want["converged"])
+    np.testing.assert_array_equal(got, want["labels"])
+    if name == "cap_one_nothing_moves":
+        assert got.tolist() == list(range(g.T * g.N))
+    if name == "stopped_early":
+        assert not conv and it == 3
+
+
+def test_bad_graph_and_arguments():
+    import torch
+    from paper_2309_03523_amd import binding
+    g = _graph(13, 2, 50, 4.0, False)
+    rp = [torch.from_numpy(s.rowptr).cuda() for s in g.snaps]
+    ci = [torch.from_numpy(s.col).cuda() for s in g.snaps]
+    labels = torch.zeros(100, dtype=torch.int32, device="cuda")
+    kw = dict(w_s=1, w_t=1, cap=10, max_iters=5, labels=labels)
+    bad = ci[1].clone()
+    bad[3] = 49 if int(bad[3]) != 49 else 48          # breaks order or symmetry, stays in range
+    with pytest.raises(binding.DgcError, match="graph contract"):
+        binding.chunk_generate(rp, [ci[0], bad], g.N, **kw)
+    with pytest.raises(binding.DgcError, match="weights"):
+        binding.chunk_generate(rp, ci, g.N, **{**kw, "w_s": -1})
+    with pytest.raises(binding.DgcError, match="cap"):
+        binding.chunk_generate(rp, ci, g.N, **{**kw, "cap": 0})
+    binding.chunk_generate(rp, ci, g.N, **kw)
