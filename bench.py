@@ -29,7 +29,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config2s", "config2tf", "config3w", "config4s", "config4", "config5s", "config5", "stale", "fusion"])
+    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config2s", "config2tf", "config3w", "config4s", "config4", "config5s", "config5", "stale", "fusion", "chunkgen"])
     ap.add_argument("--gather-mode", default="in_place", choices=["in_place", "staged"])
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -473,6 +473,79 @@ def fusion_main(args):
     print(json.dumps(out))
 
 
+def chunkgen_main(args):
+    """Chunk generation by weighted label propagation (Section 4.1) on config 2's graph: one step =
+    one whole generation (all iterations until no label changes)."""
+    import numpy as np
+    import torch
+    from paper_2309_03523_amd import binding, synth
+    synth.progress = lambda msg: print(msg, file=sys.stderr, flush=True)
+    w_s, w_t, cap, max_iters = 2, 1, 25_000 * 8, 1000     # two structure layers : one time layer; chunks of config 2's size
+    t0 = time.perf_counter()
+    g = synth.config2_graph(args.seed)
+    t_gen = time.perf_counter() - t0
+    rp = [torch.from_numpy(s.rowptr).cuda() for s in g.snaps]
+    ci = [torch.from_numpy(s.col).cuda() for s in g.snaps]
+    n = g.T * g.N
+    labels = torch.empty(n, dtype=torch.int32, device="cuda")
+    kw = dict(w_s=w_s, w_t=w_t, cap=cap, max_iters=max_iters, labels=labels)
+    for _ in range(min(args.warmup, 1)):
+        binding.chunk_generate(rp, ci, g.N, **kw)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        iters, conv = binding.chunk_generate(rp, ci, g.N, **kw)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms = 1e3 * elapsed / args.steps
+    edges = g.nnz - n + 2 * (g.T - 1) * g.N               # directed super-graph edges
+    lab = labels.cpu().numpy()
+    sizes = np.bincount(lab, minlength=n)
+    sizes = sizes[sizes > 0]
+    # weight inside chunks / total weight (each undirected edge once), on the host from the labels
+    inside = 0
+    for t, sn in enumerate(g.snaps):
+        row = np.repeat(np.arange(g.N, dtype=np.int64), np.diff(sn.rowptr))
+        l = lab[t * g.N:(t + 1) * g.N]
+        inside += w_s * (int((l[row] == l[sn.col]).sum()) - g.N) // 2
+        if t + 1 < g.T:
+            inside += w_t * int((l == lab[(t + 1) * g.N:(t + 2) * g.N]).sum())
+    total = w_s * (g.nnz - n) // 2 + w_t * (g.T - 1) * g.N
+    bytes_iter = 4 * g.nnz + 24 * n
+    out = {"metric": "super-graph edge visits/s (label propagation, all iterations of one chunk generation)",
+           "value": edges * iters * args.steps / elapsed, "unit": "edges/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": min(args.warmup, 1), "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "i32", "data": "synthetic",
+           "config": {"workload": "chunk generation on config 2's graph: 32 snapshots x 100k vertices, "
+                                  f"w_spatial = {w_s}, w_temporal = {w_t}, size limit {cap}", "super_vertices": n,
+                      "directed_edges": edges, "iterations": iters, "converged": conv},
+           "roofline": {"kernel": "k_cg_propose_short + k_cg_propose_long + k_cg_decide_short + k_cg_decide_long, per iteration",
+                        "bound": "hbm", "achieved": bytes_iter * iters / (ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                        "frac": bytes_iter * iters / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                        "traffic": measured_traffic("chunkgen", "in_place").get("iteration"),
+                        "bytes_per_launch": bytes_iter, "ms_per_launch": ms / iters},
+           "chunks": {"count": int(sizes.size), "largest": int(sizes.max()), "median": float(np.median(sizes)),
+                      "weight_inside_chunks": inside, "total_weight": total, "inside_fraction": inside / total},
+           "setup_s": {"generate": t_gen}}
+    if not args.no_cpu_baseline:
+        from oracle import chunkgen
+        small = synth.config2_graph(args.seed, scale=0.003)
+        srp = [torch.from_numpy(s.rowptr).cuda() for s in small.snaps]
+        sci = [torch.from_numpy(s.col).cuda() for s in small.snaps]
+        slab = torch.empty(small.T * small.N, dtype=torch.int32, device="cuda")
+        s_it, s_conv = binding.chunk_generate(srp, sci, small.N, w_s=w_s, w_t=w_t, cap=cap // 333, max_iters=max_iters, labels=slab)
+        t0 = time.perf_counter()
+        want = chunkgen.propagate(small, w_s, w_t, cap // 333, max_iters)
+        t_cpu = time.perf_counter() - t0
+        s_edges = small.nnz - small.T * small.N + 2 * (small.T - 1) * small.N
+        out["cpu_baseline"] = {"value": s_edges * want["iterations"] / t_cpu, "unit": "edges/s", "cores": 1, "kind": "oracle",
+                               "sample": f"the same generator at 3/1000 of the vertex count ({small.T * small.N} super-vertices, "
+                                         f"{want['iterations']} iterations), {t_cpu:.1f} s (Python loops)",
+                               "gpu_matches_bit_exact": bool((slab.cpu().numpy() == want["labels"]).all()
+                                                             and s_it == want["iterations"] and s_conv == want["converged"])}
+    print(json.dumps(out))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -481,6 +554,12 @@ def main():
         sys.exit(2)
     import numpy as np
     import torch
+    if args.workload == "chunkgen":
+        if not torch.cuda.is_available():
+            print("bench.py needs a GPU", file=sys.stderr)
+            sys.exit(2)
+        chunkgen_main(args)
+        return
     if args.workload in ("stale", "fusion"):
         if not torch.cuda.is_available():
             print("bench.py needs a GPU", file=sys.stderr)

@@ -23,9 +23,11 @@ here, so that the procedure is deterministic, parallel and certain to end:
     fewer than `cap` vertices carried it when the iteration started (the limit is soft: several
     vertices may take the same label in one iteration);
   * a vertex wants to change only if its candidate scores strictly more than its own label does;
-  * of two adjacent vertices that both want to change, only the one with the smaller index does
-    (so no two neighbours change in the same iteration, every change raises the total weight of
-    the edges inside chunks, and the procedure ends);
+  * of two adjacent vertices that both want to change, only the one that comes first in the
+    iteration's order does (so no two neighbours change in the same iteration, every change raises
+    the total weight of the edges inside chunks, and the procedure ends); the order of iteration r
+    (0-based) is by h(x xor (r * 0x9E3779B9 mod 2^32)), then by x, with h a fixed 32-bit mixing
+    function - an order by index alone makes long chains of vertices that wait for each other;
   * it stops when nobody wants to change, or after `max_iters` iterations.
 """
 from __future__ import annotations
@@ -51,6 +53,22 @@ def neighbours(graph, x: int, w_s: int, w_t: int) -> list:
     return out
 
 
+def _h(v: int) -> int:
+    """32-bit mixing function (xor-shift-multiply), a bijection."""
+    v &= 0xFFFFFFFF
+    v ^= v >> 16
+    v = (v * 0x7FEB352D) & 0xFFFFFFFF
+    v ^= v >> 15
+    v = (v * 0x846CA68B) & 0xFFFFFFFF
+    v ^= v >> 16
+    return v
+
+
+def order_key(x: int, r: int) -> tuple:
+    """Position of vertex x in the order of iteration r."""
+    return (_h(x ^ ((r * 0x9E3779B9) & 0xFFFFFFFF)), x)
+
+
 def _scores(graph, labels, x, w_s, w_t) -> dict:
     sc = {}
     for u, w in neighbours(graph, x, w_s, w_t):
@@ -59,8 +77,8 @@ def _scores(graph, labels, x, w_s, w_t) -> dict:
     return sc
 
 
-def iteration(graph, labels: np.ndarray, w_s: int, w_t: int, cap: int):
-    """One iteration.  Returns (new labels, number of vertices that changed)."""
+def iteration(graph, labels: np.ndarray, w_s: int, w_t: int, cap: int, r: int = 0):
+    """Iteration r.  Returns (new labels, number of vertices that changed)."""
     n = labels.size
     size = np.bincount(labels, minlength=n)
     want = np.full(n, -1, np.int64)
@@ -81,7 +99,7 @@ def iteration(graph, labels: np.ndarray, w_s: int, w_t: int, cap: int):
     for x in range(n):
         if want[x] < 0:
             continue
-        if all(not (want[u] >= 0 and u < x) for u, w in neighbours(graph, x, w_s, w_t)):
+        if all(not (want[u] >= 0 and order_key(u, r) < order_key(x, r)) for u, w in neighbours(graph, x, w_s, w_t)):
             new[x] = want[x]
             changed += 1
     return new, changed
@@ -93,7 +111,7 @@ def propagate(graph, w_s: int, w_t: int, cap: int, max_iters: int) -> dict:
     it = 0
     converged = False
     while it < max_iters:
-        labels, changed = iteration(graph, labels, w_s, w_t, cap)
+        labels, changed = iteration(graph, labels, w_s, w_t, cap, it)
         it += 1
         if changed == 0:
             converged = True

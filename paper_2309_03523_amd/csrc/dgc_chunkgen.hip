@@ -7,15 +7,19 @@
 //            takes as candidate the admissible one (carried by fewer than `cap` vertices) with
 //            the largest score, ties to the label carried by fewer vertices, then to the smaller
 //            label; it wants to change if the candidate scores strictly more than its own label;
-//   decide   a vertex that wants to change does so unless a neighbour with a smaller index also
-//            wants to (no two neighbours change together, so every change raises the weight
-//            inside chunks and the iteration count is bounded); chunk sizes follow.
+//   decide   a vertex that wants to change does so unless a neighbour that also wants to comes
+//            before it in the iteration's order (a hash of vertex and iteration, then the index):
+//            no two neighbours change together, so every change raises the weight inside chunks
+//            and the iteration count is bounded; the hashed order keeps chains of waiting
+//            vertices short.  Chunk sizes follow.
 // Scores are integers: sums and the integer atomics on the sizes are exact in any order.
 //
 // Rows of at most kShort neighbours: one thread each, neighbour labels in a private LDS strip,
-// scores by comparing all pairs.  Longer rows (a list built once): one workgroup each, scores in
-// an LDS hash table, in several passes over disjoint label classes when the row is longer than
-// the table can take.
+// scores by comparing all pairs.  Longer rows (two lists built once): one wavefront (up to kMid
+// neighbours) or one 256-thread workgroup each, scores in an LDS hash table sized to the row, in
+// several passes over disjoint label classes when the row holds more distinct labels than the
+// table takes; the pass count that worked is remembered per row (labels merge as the propagation
+// goes on) and doubled when a table fills up.
 #include <algorithm>
 
 #include "dgc_internal.h"
@@ -25,8 +29,9 @@ namespace {
 
 constexpr int kBlock = 256;
 constexpr int kShort = 32;            // neighbours (spatial + temporal) a thread handles alone
-constexpr int kSlots = 4096;          // hash table of the long-row kernel
-constexpr int kPerPass = 1024;        // distinct labels a pass is sized for
+constexpr int kMid = 448;             // up to here a wavefront with a 1024-slot table (never more than one pass)
+constexpr int kMidSlots = 1024;
+constexpr int kBigSlots = 8192;       // table of the workgroup-per-row kernel
 constexpr uint32_t kTemporal = 0x80000000u;
 
 struct CgArgs {
@@ -36,8 +41,10 @@ struct CgArgs {
   int32_t* labels;       // [T*N]
   int32_t* want;         // [T*N] candidate, or -1
   int32_t* size;         // [T*N] vertices per label
-  const int32_t* long_rows; int32_t n_long;
-  int32_t* counters;     // [0] vertices changed this iteration, [1] long-row list fill, [2] hash overflow
+  const int32_t* rows;   // list of the long-row kernel at hand
+  int32_t* passes_hint;  // per entry of that list: pass count that last worked (0 = none yet)
+  uint32_t salt;         // changes with the iteration: order of the decide step
+  int32_t* counters;     // [0] vertices changed this iteration, [1] / [2] list fills, [3] hash overflow
 };
 
 struct Best {            // ordered by (score desc, size asc, label asc)
@@ -62,14 +69,27 @@ __global__ void k_cg_init(CgArgs a, int64_t n) {
   a.want[x] = -1;
 }
 
-__global__ void k_cg_count_long(CgArgs a, int64_t n, int32_t* list) {
+__global__ void k_cg_count_long(CgArgs a, int64_t n, int32_t* mid, int32_t* big) {
   const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (x >= n) return;
   const int32_t t = (int32_t)(x / a.g.N);
-  if (degree_of(a.g, t, x - (int64_t)t * a.g.N) > kShort) {
-    const int32_t k = atomicAdd(&a.counters[1], 1);
-    if (list) list[k] = (int32_t)x;
-  }
+  const int32_t d = degree_of(a.g, t, x - (int64_t)t * a.g.N);
+  if (d <= kShort) return;
+  const int which = d <= kMid ? 1 : 2;
+  const int32_t k = atomicAdd(&a.counters[which], 1);
+  int32_t* list = which == 1 ? mid : big;
+  if (list) list[k] = (int32_t)x;
+}
+
+__device__ __forceinline__ uint32_t mix(uint32_t v) {   // a bijection on 32 bits
+  v ^= v >> 16; v *= 0x7feb352du; v ^= v >> 15; v *= 0x846ca68bu; v ^= v >> 16;
+  return v;
+}
+
+// true if wanting neighbour u comes before x in this iteration's order
+__device__ __forceinline__ bool before(uint32_t salt, int64_t u, int64_t x) {
+  const uint32_t pu = mix((uint32_t)u ^ salt), px = mix((uint32_t)x ^ salt);
+  return pu != px ? pu < px : u < x;
 }
 
 // ---- short rows
@@ -82,7 +102,7 @@ __global__ __launch_bounds__(kBlock) void k_cg_propose_short(CgArgs a, int64_t n
   const int64_t* rp = a.g.rowptr[t];
   const int64_t e0 = rp[i], e1 = rp[i + 1];
   const int d = (int)(e1 - e0) - 1 + (t > 0) + (t + 1 < a.g.T);
-  if (d > kShort) return;                        // the long-row kernel's
+  if (d > kShort) return;                        // the long-row kernels'
   uint32_t* s = strip + threadIdx.x;
   int k = 0;
   const int32_t* col = a.g.colidx[t];
@@ -135,27 +155,23 @@ __global__ __launch_bounds__(kBlock) void k_cg_decide_short(CgArgs a, int64_t n)
   const int64_t* rp = a.g.rowptr[t];
   const int64_t e0 = rp[i], e1 = rp[i + 1];
   if ((int)(e1 - e0) - 1 + (t > 0) + (t + 1 < a.g.T) > kShort) return;
-  if (t > 0 && a.want[x - a.g.N] >= 0) return;   // the earlier copy has the smaller index
+  if (t > 0 && a.want[x - a.g.N] >= 0 && before(a.salt, x - a.g.N, x)) return;
+  if (t + 1 < a.g.T && a.want[x + a.g.N] >= 0 && before(a.salt, x + a.g.N, x)) return;
   const int32_t* col = a.g.colidx[t];
   const int64_t base = (int64_t)t * a.g.N;
-  for (int64_t e = e0; e < e1; ++e) {            // columns ascend: only those below i can block
+  for (int64_t e = e0; e < e1; ++e) {
     const int32_t j = col[e];
-    if (j >= i) break;
-    if (a.want[base + j] >= 0) return;
+    if (j != i && a.want[base + j] >= 0 && before(a.salt, base + j, x)) return;
   }
   apply_change(a, x, w);
 }
 
-// ---- long rows
-__device__ __forceinline__ uint32_t mix(uint32_t v) {   // a bijection on 32 bits
-  v ^= v >> 16; v *= 0x7feb352du; v ^= v >> 15; v *= 0x846ca68bu; v ^= v >> 16;
-  return v;
-}
-
-__device__ __forceinline__ Best block_best(Best b, Best* red) {
+// ---- long rows: one workgroup of THREADS per row, hash table of at most SLOTS entries
+template <int THREADS>
+__device__ __forceinline__ Best group_best(Best b, Best* red) {
   red[threadIdx.x] = b;
   __syncthreads();
-  for (int s = kBlock / 2; s > 0; s >>= 1) {
+  for (int s = THREADS / 2; s > 0; s >>= 1) {
     if (threadIdx.x < s) {
       const Best o = red[threadIdx.x + s];
       Best& m = red[threadIdx.x];
@@ -168,13 +184,15 @@ __device__ __forceinline__ Best block_best(Best b, Best* red) {
   return r;
 }
 
-__global__ __launch_bounds__(kBlock) void k_cg_propose_long(CgArgs a) {
-  __shared__ int32_t key[kSlots];
-  __shared__ uint32_t val[kSlots];
-  __shared__ Best red[kBlock];
+template <int THREADS, int SLOTS>
+__global__ __launch_bounds__(THREADS) void k_cg_propose_long(CgArgs a) {
+  __shared__ int32_t key[SLOTS];
+  __shared__ uint32_t val[SLOTS];
+  __shared__ Best red[THREADS];
   __shared__ uint32_t own_score;
+  __shared__ int n_keys;
   __shared__ int overflow;
-  const int64_t x = a.long_rows[blockIdx.x];
+  const int64_t x = a.rows[blockIdx.x];
   const int32_t t = (int32_t)(x / a.g.N);
   const int64_t i = x - (int64_t)t * a.g.N;
   const int64_t e0 = a.g.rowptr[t][i], e1 = a.g.rowptr[t][i + 1];
@@ -182,14 +200,21 @@ __global__ __launch_bounds__(kBlock) void k_cg_propose_long(CgArgs a) {
   const int64_t base = (int64_t)t * a.g.N;
   const int32_t own_label = a.labels[x];
   const int64_t n_sp = e1 - e0;                  // stored entries, self-loop included
-  uint32_t passes = (uint32_t)((n_sp + 2 + kPerPass - 1) / kPerPass);
-  for (;;) {                                     // again with twice the passes if a table overflowed
+  // table sized to the row: at least twice its entries when that fits
+  int slots = 64;
+  while (slots < SLOTS && slots < 2 * (n_sp + 2)) slots *= 2;
+  const int limit = slots / 4 * 3;               // distinct labels a pass may hold
+  const int32_t hint = a.passes_hint[blockIdx.x];
+  uint32_t passes = hint > 0 ? (uint32_t)max(1, hint / 2) : (uint32_t)((n_sp + 2 + limit - 1) / limit);
+  for (;;) {                                     // again with twice the passes if a table filled up
     Best best{0u, 0, -1};
     if (threadIdx.x == 0) { own_score = 0; overflow = 0; }
     for (uint32_t p = 0; p < passes; ++p) {
-      for (int sidx = threadIdx.x; sidx < kSlots; sidx += kBlock) { key[sidx] = -1; val[sidx] = 0; }
+      for (int sidx = threadIdx.x; sidx < slots; sidx += THREADS) { key[sidx] = -1; val[sidx] = 0; }
+      if (threadIdx.x == 0) n_keys = 0;
       __syncthreads();
-      for (int64_t e = threadIdx.x; e < n_sp + 2; e += kBlock) {
+      for (int64_t e = threadIdx.x; e < n_sp + 2; e += THREADS) {
+        if (*(volatile int*)&overflow) break;
         int32_t lab; uint32_t w;
         if (e < n_sp) {
           const int32_t j = col[e0 + e];
@@ -205,16 +230,16 @@ __global__ __launch_bounds__(kBlock) void k_cg_propose_long(CgArgs a) {
         if (w == 0) continue;
         const uint32_t h = mix((uint32_t)lab);
         if (h % passes != p) continue;
-        uint32_t slot = (h / passes) & (kSlots - 1);
-        int probes = 0;
-        for (;; slot = (slot + 1) & (kSlots - 1)) {
+        uint32_t slot = (h / passes) & (slots - 1);
+        for (int probes = 0; probes < slots; ++probes, slot = (slot + 1) & (slots - 1)) {
           const int32_t prev = atomicCAS(&key[slot], -1, lab);
+          if (prev == -1 && atomicAdd(&n_keys, 1) >= limit) overflow = 1;
           if (prev == -1 || prev == lab) { atomicAdd(&val[slot], w); break; }
-          if (++probes >= kSlots) { overflow = 1; break; }
         }
       }
       __syncthreads();
-      for (int sidx = threadIdx.x; sidx < kSlots; sidx += kBlock) {
+      if (overflow) break;                       // the same for the whole workgroup
+      for (int sidx = threadIdx.x; sidx < slots; sidx += THREADS) {
         const int32_t lab = key[sidx];
         if (lab < 0) continue;
         if (lab == own_label) { own_score = val[sidx]; continue; }
@@ -227,22 +252,26 @@ __global__ __launch_bounds__(kBlock) void k_cg_propose_long(CgArgs a) {
     }
     const int ovf = overflow;
     const uint32_t own = own_score;
-    best = block_best(best, red);
+    best = group_best<THREADS>(best, red);
     if (!ovf) {
-      if (threadIdx.x == 0) a.want[x] = (best.label >= 0 && best.score > own) ? best.label : -1;
+      if (threadIdx.x == 0) {
+        a.want[x] = (best.label >= 0 && best.score > own) ? best.label : -1;
+        a.passes_hint[blockIdx.x] = (int32_t)passes;
+      }
       return;
     }
     if (passes > (1u << 20)) {                   // cannot happen with a bijective mix; leave a trace and stop
-      if (threadIdx.x == 0) { a.want[x] = -1; atomicAdd(&a.counters[2], 1); }
+      if (threadIdx.x == 0) { a.want[x] = -1; atomicAdd(&a.counters[3], 1); }
       return;
     }
     passes *= 2;
   }
 }
 
-__global__ __launch_bounds__(kBlock) void k_cg_decide_long(CgArgs a) {
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void k_cg_decide_long(CgArgs a) {
   __shared__ int blocked;
-  const int64_t x = a.long_rows[blockIdx.x];
+  const int64_t x = a.rows[blockIdx.x];
   const int32_t w = a.want[x];
   if (w < 0) return;                             // the same for the whole workgroup
   const int32_t t = (int32_t)(x / a.g.N);
@@ -250,11 +279,13 @@ __global__ __launch_bounds__(kBlock) void k_cg_decide_long(CgArgs a) {
   const int64_t e0 = a.g.rowptr[t][i], e1 = a.g.rowptr[t][i + 1];
   const int32_t* col = a.g.colidx[t];
   const int64_t base = (int64_t)t * a.g.N;
-  if (threadIdx.x == 0) blocked = (t > 0 && a.want[x - a.g.N] >= 0) ? 1 : 0;
+  if (threadIdx.x == 0)
+    blocked = ((t > 0 && a.want[x - a.g.N] >= 0 && before(a.salt, x - a.g.N, x)) ||
+               (t + 1 < a.g.T && a.want[x + a.g.N] >= 0 && before(a.salt, x + a.g.N, x))) ? 1 : 0;
   __syncthreads();
-  for (int64_t e = e0 + threadIdx.x; e < e1; e += kBlock) {
+  for (int64_t e = e0 + threadIdx.x; e < e1; e += THREADS) {
     const int32_t j = col[e];
-    if (j < i && a.want[base + j] >= 0) blocked = 1;
+    if (j != i && a.want[base + j] >= 0 && before(a.salt, base + j, x)) blocked = 1;
   }
   __syncthreads();
   if (threadIdx.x == 0 && !blocked) apply_change(a, x, w);
@@ -300,7 +331,7 @@ extern "C" dgc_status_t dgc_chunk_generate(const dgc_graph_t* graph, int32_t w_s
   } while (0)
 
   const int64_t** d_rp = nullptr; const int32_t** d_ci = nullptr;
-  int32_t *want = nullptr, *size = nullptr, *counters = nullptr, *list = nullptr;
+  int32_t *want = nullptr, *size = nullptr, *counters = nullptr, *mid = nullptr, *big = nullptr, *hints = nullptr;
   CG_TRY(alloc((void**)&d_rp, sizeof(void*) * graph->T));
   CG_TRY(alloc((void**)&d_ci, sizeof(void*) * graph->T));
   CG_TRY(alloc((void**)&want, sizeof(int32_t) * n));
@@ -332,28 +363,36 @@ extern "C" dgc_status_t dgc_chunk_generate(const dgc_graph_t* graph, int32_t w_s
   a.labels = labels; a.want = want; a.size = size; a.counters = counters;
   int32_t host_c[4] = {0, 0, 0, 0};
   hipLaunchKernelGGL(k_cg_init, grid_of(n), kBlock, 0, st, a, n);
-  hipLaunchKernelGGL(k_cg_count_long, grid_of(n), kBlock, 0, st, a, n, (int32_t*)nullptr);
+  hipLaunchKernelGGL(k_cg_count_long, grid_of(n), kBlock, 0, st, a, n, (int32_t*)nullptr, (int32_t*)nullptr);
   CG_TRY(hipMemcpyAsync(host_c, counters, sizeof(host_c), hipMemcpyDeviceToHost, st));
   CG_TRY(hipStreamSynchronize(st));
-  const int32_t n_long = host_c[1];
-  if (n_long > 0) {
-    CG_TRY(alloc((void**)&list, sizeof(int32_t) * n_long));
+  const int32_t n_mid = host_c[1], n_big = host_c[2];
+  if (n_mid + n_big > 0) {
+    CG_TRY(alloc((void**)&mid, sizeof(int32_t) * n_mid));
+    CG_TRY(alloc((void**)&big, sizeof(int32_t) * n_big));
+    CG_TRY(alloc((void**)&hints, sizeof(int32_t) * (n_mid + n_big)));
+    CG_TRY(hipMemsetAsync(hints, 0, sizeof(int32_t) * (n_mid + n_big), st));
     CG_TRY(hipMemsetAsync(counters, 0, sizeof(int32_t) * 4, st));
-    hipLaunchKernelGGL(k_cg_count_long, grid_of(n), kBlock, 0, st, a, n, list);
+    hipLaunchKernelGGL(k_cg_count_long, grid_of(n), kBlock, 0, st, a, n, mid, big);
   }
-  a.long_rows = list; a.n_long = n_long;
+  CgArgs am = a, ab = a;
+  am.rows = mid; am.passes_hint = hints;
+  ab.rows = big; ab.passes_hint = hints + n_mid;
 
   int32_t it = 0, converged = 0;
   while (it < max_iters) {
     CG_TRY(hipMemsetAsync(counters, 0, sizeof(int32_t), st));
+    a.salt = am.salt = ab.salt = (uint32_t)it * 0x9E3779B9u;
     hipLaunchKernelGGL(k_cg_propose_short, grid_of(n), kBlock, 0, st, a, n);
-    if (n_long > 0) hipLaunchKernelGGL(k_cg_propose_long, (unsigned)n_long, kBlock, 0, st, a);
+    if (n_mid > 0) hipLaunchKernelGGL((k_cg_propose_long<64, kMidSlots>), (unsigned)n_mid, 64, 0, st, am);
+    if (n_big > 0) hipLaunchKernelGGL((k_cg_propose_long<kBlock, kBigSlots>), (unsigned)n_big, kBlock, 0, st, ab);
     hipLaunchKernelGGL(k_cg_decide_short, grid_of(n), kBlock, 0, st, a, n);
-    if (n_long > 0) hipLaunchKernelGGL(k_cg_decide_long, (unsigned)n_long, kBlock, 0, st, a);
+    if (n_mid > 0) hipLaunchKernelGGL(k_cg_decide_long<64>, (unsigned)n_mid, 64, 0, st, am);
+    if (n_big > 0) hipLaunchKernelGGL(k_cg_decide_long<kBlock>, (unsigned)n_big, kBlock, 0, st, ab);
     CG_TRY(hipMemcpyAsync(host_c, counters, sizeof(host_c), hipMemcpyDeviceToHost, st));
     CG_TRY(hipStreamSynchronize(st));
     ++it;
-    if (host_c[2]) { release(); return bad(DGC_ERR_UNSUPPORTED, "chunk generate: a label table overflowed"); }
+    if (host_c[3]) { release(); return bad(DGC_ERR_UNSUPPORTED, "chunk generate: a label table overflowed"); }
     if (host_c[0] == 0) { converged = 1; break; }
   }
   CG_TRY(hipGetLastError());

@@ -282,6 +282,22 @@ def config1(seed: int = 0, random_bias: bool = False) -> Workload:
                     layer_params(seed, F, 32, 32, "gru", 1, random_bias))
 
 
+def _nonuniform_graph(seed: int, T: int, N: int, edge_mu: float, edge_sigma: float, edge_clip: Tuple[int, int],
+                      alpha: float):
+    g_rng = stream(seed, "graph")
+    w = powerlaw_weights(N, alpha, stream(seed, "perm"))
+    n_edges = np.clip(np.exp(edge_mu + edge_sigma * g_rng.standard_normal(T)),
+                      edge_clip[0], edge_clip[1]).astype(np.int64)
+    return DynamicGraph(N, [chung_lu_snapshot(N, int(m), w, g_rng) for m in n_edges]), n_edges
+
+
+def config2_graph(seed: int = 0, scale: float = 1.0) -> DynamicGraph:
+    """The dynamic graph of config2(seed, scale) alone (no features)."""
+    N = max(64, int(100_000 * scale))
+    return _nonuniform_graph(seed, 32, N, np.log(800_000 * scale), 1.0,
+                             (max(1, int(80_000 * scale)), max(2, int(8_000_000 * scale))), 2.1)[0]
+
+
 def nonuniform_powerlaw(seed: int, T: int, N: int, F: int, S: int, H: int, edge_mu: float,
                         edge_sigma: float, edge_clip: Tuple[int, int], alpha: float, window: int,
                         n_ranges: int, time_kind: str = "gru", n_struct_layers: int = 1,
@@ -290,11 +306,7 @@ def nonuniform_powerlaw(seed: int, T: int, N: int, F: int, S: int, H: int, edge_
     """Snapshots with lognormal edge counts (dense next to sparse) and power-law degrees;
     chunks = windows x uneven vertex ranges; cache = X + 0.1 N(0,1) (small drift since the
     pass that filled it)."""
-    g_rng = stream(seed, "graph")
-    w = powerlaw_weights(N, alpha, stream(seed, "perm"))
-    n_edges = np.clip(np.exp(edge_mu + edge_sigma * g_rng.standard_normal(T)),
-                      edge_clip[0], edge_clip[1]).astype(np.int64)
-    graph = DynamicGraph(N, [chung_lu_snapshot(N, int(m), w, g_rng) for m in n_edges])
+    graph, n_edges = _nonuniform_graph(seed, T, N, edge_mu, edge_sigma, edge_clip, alpha)
     r_rng = stream(seed, "ranges")
     n_win = (T + window - 1) // window
     if uneven:

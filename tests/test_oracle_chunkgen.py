@@ -69,15 +69,33 @@ def test_edge_weights_decide_between_spatial_and_temporal_neighbours():
 def test_one_iteration_by_hand():
     # path 0 - 1 - 2, one snapshot, all weights 1, labels 0, 1, 2.
     # candidates: 0 -> 1, 1 -> 0 (tie between 0 and 2, smaller label), 2 -> 1; all want to change
-    # (own score 0).  0 changes (no smaller neighbour wants); 1 is blocked by 0; 2 is blocked by 1.
+    # (own score 0).  The order of iteration 0 is 0, 1, 2 (h(0) = 0 < h(1) < h(2)): 0 changes (no
+    # earlier neighbour wants); 1 is blocked by 0; 2 is blocked by 1.
     g = _graph(3, [[(0, 1), (1, 2)]])
-    lab, changed = chunkgen.iteration(g, chunkgen.initial_labels(1, 3), 1, 1, cap=10)
+    assert sorted(range(3), key=lambda x: chunkgen.order_key(x, 0)) == [0, 1, 2]
+    lab, changed = chunkgen.iteration(g, chunkgen.initial_labels(1, 3), 1, 1, cap=10, r=0)
     assert lab.tolist() == [1, 1, 2] and changed == 1
     # next: 0 has label 1 with score 1 (stays); 1 has own score 1, candidate 2 scores 1: not strictly more;
     # 2 -> 1 scores 1 > 0: changes.
-    lab, changed = chunkgen.iteration(g, lab, 1, 1, cap=10)
+    lab, changed = chunkgen.iteration(g, lab, 1, 1, cap=10, r=1)
     assert lab.tolist() == [1, 1, 1] and changed == 1
-    assert chunkgen.iteration(g, lab, 1, 1, cap=10)[1] == 0
+    assert chunkgen.iteration(g, lab, 1, 1, cap=10, r=2)[1] == 0
+
+
+def test_order_of_an_iteration_decides_between_adjacent_vertices():
+    # two vertices, one edge: both want the other's label; exactly the one that comes first in the
+    # iteration's order changes, and the order is not the index order in every iteration
+    g = _graph(2, [[(0, 1)]])
+    firsts = set()
+    for r in range(40):
+        lab, changed = chunkgen.iteration(g, chunkgen.initial_labels(1, 2), 1, 1, cap=10, r=r)
+        first = min(range(2), key=lambda x: chunkgen.order_key(x, r))
+        assert changed == 1 and lab[first] == 1 - first and lab[1 - first] == 1 - first
+        firsts.add(first)
+    assert firsts == {0, 1}
+    # the mixing function is a bijection on a sample and spreads consecutive inputs
+    hs = [chunkgen._h(v) for v in range(5000)]
+    assert len(set(hs)) == 5000 and chunkgen._h(0) == 0 and max(hs) > 2 ** 31 > min(hs[1:])
 
 
 def test_size_limit_holds_labels_back():
@@ -90,9 +108,9 @@ def test_size_limit_holds_labels_back():
     assert capped["converged"] and sizes.max() <= 3 + 1 and (sizes > 0).sum() >= 2
     # a label that had reached the limit when an iteration started gains no vertex in it
     lab = chunkgen.initial_labels(1, 8)
-    for _ in range(10):
+    for r in range(10):
         before = np.bincount(lab, minlength=8)
-        lab, changed = chunkgen.iteration(g, lab, 1, 1, cap=3)
+        lab, changed = chunkgen.iteration(g, lab, 1, 1, cap=3, r=r)
         after = np.bincount(lab, minlength=8)
         assert (after[before >= 3] <= before[before >= 3]).all()
         if not changed:
@@ -108,7 +126,7 @@ def test_every_iteration_raises_the_weight_inside_chunks(seed):
     prev = chunkgen.inside_weight(g, lab, ws, wt)
     assert prev == 0
     for it in range(200):
-        lab, changed = chunkgen.iteration(g, lab, ws, wt, cap=10 ** 9)
+        lab, changed = chunkgen.iteration(g, lab, ws, wt, cap=10 ** 9, r=it)
         cur = chunkgen.inside_weight(g, lab, ws, wt)
         if changed == 0:
             assert cur == prev
