@@ -281,6 +281,7 @@ dgc_status_t build_dysat(dgc_layer* L, const std::vector<ChunkInfo>& cinfo, hipS
   w.work_short = L->d_work_short; w.n_short = L->n_short; w.total_rows = L->total_rows;
   for (const ChunkInfo& c : cinfo)
     if (c.w > 16) return fail(DGC_ERR_UNSUPPORTED, "the temporal self-attention is built for windows of at most 16 snapshots");
+  if (L->T > 4096) return fail(DGC_ERR_UNSUPPORTED, "the attention layer is built for at most 4096 snapshots");
   const int32_t rows_of[DY_NPAR] = {S, heads, heads, T, S, S, S};
   const int32_t cols_of[DY_NPAR] = {S, S / heads, S / heads, S, S, S, S};
   for (int k = 0; k < DY_NPAR; ++k) {

@@ -351,6 +351,67 @@ struct DwBf16Args {
   int32_t n_groups;
 };
 
+// Raw operand rows of one 32-row tile as they come from memory, requested ahead of their use
+// (loads return in order, so waiting for older registers does not wait for younger requests):
+//  - bf16 x bf16 products: both sides of the next tile are requested before the current tile is
+//    multiplied;
+//  - the ELU(U) + pos variant with three accumulator sets has no room for a second tile: the
+//    gradient rows of the current tile are requested before U is converted, and U of the next tile
+//    as soon as the conversion has used up the current one; the position rows of the snapshots a
+//    workgroup meets are staged in LDS once.
+template <bool AU>
+struct DwRawA {
+  float4 u[AU ? 8 : 1];   // AU: fp32 rows of U, [jb][c][half]
+  uint4 a[AU ? 1 : 4];    // otherwise: bf16 rows of A, [jb][c]
+  int32_t k;              // index of the tile's snapshot among the snapshots in use
+  bool ok;
+};
+
+struct DwRow {
+  int64_t row;
+  int32_t k;
+  bool ok;
+};
+
+__device__ __forceinline__ DwRow dw_row(const DwBf16Args& a, int64_t tile, int64_t tiles_per_t, int n) {
+  DwRow r;
+  r.k = (int32_t)(tile / tiles_per_t);
+  const int64_t v = (tile % tiles_per_t) * 32 + n;
+  const bool valid = v < a.N;
+  r.row = (int64_t)a.used_t[r.k] * a.N + (valid ? v : a.N - 1);    // always a row of the tensors
+  r.ok = valid && (!a.covered_only || a.owner[r.row] >= 0);       // rows that do not count are zeroed when used
+  return r;
+}
+
+template <bool AU>
+__device__ __forceinline__ void dw_load_a(const DwBf16Args& a, const DwRow& rw, int hh, int ih, DwRawA<AU>& r) {
+  r.ok = rw.ok;
+  r.k = rw.k;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int off = (2 * (2 * ih + (q >> 1)) + (q & 1)) * 16 + 8 * hh;
+    if (AU) {
+      r.u[2 * q] = *reinterpret_cast<const float4*>(a.Uf + rw.row * kS + off);
+      r.u[2 * q + 1] = *reinterpret_cast<const float4*>(a.Uf + rw.row * kS + off + 4);
+    } else {
+      r.a[q] = *reinterpret_cast<const uint4*>(a.A + rw.row * a.lda + off);
+    }
+  }
+}
+
+template <int NG>
+__device__ __forceinline__ void dw_load_g(const DwBf16Args& a, const DwRow& rw, int hh, int ob, uint4 (&g)[NG][2]) {
+#pragma unroll
+  for (int gi = 0; gi < NG; ++gi)
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+      g[gi][c] = *reinterpret_cast<const uint4*>(a.G[gi] + rw.row * kS + (2 * ob + c) * 16 + 8 * hh);
+}
+
+__device__ __forceinline__ uint4 keep_if(bool ok, uint4 u) {
+  return make_uint4(ok ? u.x : 0u, ok ? u.y : 0u, ok ? u.z : 0u, ok ? u.w : 0u);
+}
+
 template <int NG, bool AU>
 __global__ __launch_bounds__(512) void k_dw_bf16(DwBf16Args a) {
   const int lane = threadIdx.x & 63, ob = (threadIdx.x >> 6) & 3, ih = threadIdx.x >> 8;
@@ -360,40 +421,56 @@ __global__ __launch_bounds__(512) void k_dw_bf16(DwBf16Args a) {
   const int64_t tile0 = (int64_t)blockIdx.x * per, tile1 = min(n_tiles, tile0 + per);
   const bf16x8 sel0 = sel_frag(0, lane), sel1 = sel_frag(1, lane);
   floatx16 acc[NG][2] = {};
+  extern __shared__ float pos_lds[];   // AU: position rows of the snapshots of tiles [tile0, tile1)
+  const int32_t k0 = (int32_t)(tile0 / tiles_per_t);
+  if (AU) {
+    if (tile0 < tile1) {
+      const int32_t nk = (int32_t)((tile1 - 1) / tiles_per_t) - k0 + 1;
+      for (int i = threadIdx.x; i < nk * kS; i += 512) pos_lds[i] = a.pos[(int64_t)a.used_t[k0 + i / kS] * kS + (i % kS)];
+    }
+    __syncthreads();
+  }
+  DwRawA<AU> ra;
+  uint4 rg[NG][2];
+  if (tile0 < tile1) {
+    const DwRow rw = dw_row(a, tile0, tiles_per_t, n);
+    dw_load_a<AU>(a, rw, hh, ih, ra);
+    if (!AU) dw_load_g<NG>(a, rw, hh, ob, rg);
+  }
   for (int64_t tile = tile0; tile < tile1; ++tile) {
-    const int32_t t = a.used_t[tile / tiles_per_t];
-    const int64_t v = (tile % tiles_per_t) * 32 + n;
-    const bool valid = v < a.N;
-    const int64_t row = (int64_t)t * a.N + (valid ? v : a.N - 1);
-    const bool ok = valid && (!a.covered_only || a.owner[row] >= 0);
+    const bool ok = ra.ok;
+    const bool more = tile + 1 < tile1;
+    DwRow rn{};
+    if (more) rn = dw_row(a, tile + 1, tiles_per_t, n);
+    DwRawA<AU> na;
+    uint4 ng[NG][2];
+    if (AU) {
+      dw_load_g<NG>(a, dw_row(a, tile, tiles_per_t, n), hh, ob, rg);
+    } else if (more) {
+      dw_load_a<AU>(a, rn, hh, ih, na);
+      dw_load_g<NG>(a, rn, hh, ob, ng);
+    }
     bf16x8 at[2][2], al[2][2];
 #pragma unroll
     for (int jb = 0; jb < 2; ++jb) {
       floatx16 tr = {}, trl = {};
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
-        const int off = (2 * (2 * ih + jb) + c) * 16 + 8 * hh;
         if (AU) {
+          const float4 u0 = ra.u[(jb * 2 + c) * 2], u1 = ra.u[(jb * 2 + c) * 2 + 1];
+          const float* pp = pos_lds + (ra.k - k0) * kS + (2 * (2 * ih + jb) + c) * 16 + 8 * hh;
+          const float4 p0 = *reinterpret_cast<const float4*>(pp), p1 = *reinterpret_cast<const float4*>(pp + 4);
           float x[8];
-          if (ok) {
-            const float4 u0 = *reinterpret_cast<const float4*>(a.Uf + row * kS + off);
-            const float4 u1 = *reinterpret_cast<const float4*>(a.Uf + row * kS + off + 4);
-            const float4 p0 = *reinterpret_cast<const float4*>(a.pos + t * kS + off);
-            const float4 p1 = *reinterpret_cast<const float4*>(a.pos + t * kS + off + 4);
-            x[0] = elu(u0.x) + p0.x; x[1] = elu(u0.y) + p0.y; x[2] = elu(u0.z) + p0.z; x[3] = elu(u0.w) + p0.w;
-            x[4] = elu(u1.x) + p1.x; x[5] = elu(u1.y) + p1.y; x[6] = elu(u1.z) + p1.z; x[7] = elu(u1.w) + p1.w;
-          } else {
+          x[0] = elu(u0.x) + p0.x; x[1] = elu(u0.y) + p0.y; x[2] = elu(u0.z) + p0.z; x[3] = elu(u0.w) + p0.w;
+          x[4] = elu(u1.x) + p1.x; x[5] = elu(u1.y) + p1.y; x[6] = elu(u1.z) + p1.z; x[7] = elu(u1.w) + p1.w;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) x[i] = 0.f;
-          }
+          for (int i = 0; i < 8; ++i) x[i] = ok ? x[i] : 0.f;
           bf16x8 xh, xl;
           split8(x, xh, xl);
           tr = mfma(xh, c ? sel1 : sel0, tr);
           trl = mfma(xl, c ? sel1 : sel0, trl);
         } else {
-          uint4 u = make_uint4(0, 0, 0, 0);
-          if (ok) u = *reinterpret_cast<const uint4*>(a.A + row * a.lda + off);
-          tr = mfma(as_frag(u), c ? sel1 : sel0, tr);
+          tr = mfma(as_frag(keep_if(ok, ra.a[jb * 2 + c])), c ? sel1 : sel0, tr);
         }
       }
       at[jb][0] = pack8v(tr, 0);
@@ -403,15 +480,12 @@ __global__ __launch_bounds__(512) void k_dw_bf16(DwBf16Args a) {
         al[jb][1] = pack8v(trl, 8);
       }
     }
+    if (AU && more) dw_load_a<AU>(a, rn, hh, ih, ra);   // U of this tile is used up: request the next tile's
 #pragma unroll
     for (int gi = 0; gi < NG; ++gi) {
       floatx16 tr = {};
 #pragma unroll
-      for (int c = 0; c < 2; ++c) {
-        uint4 u = make_uint4(0, 0, 0, 0);
-        if (ok) u = *reinterpret_cast<const uint4*>(a.G[gi] + row * kS + (2 * ob + c) * 16 + 8 * hh);
-        tr = mfma(as_frag(u), c ? sel1 : sel0, tr);
-      }
+      for (int c = 0; c < 2; ++c) tr = mfma(as_frag(keep_if(ok, rg[gi][c])), c ? sel1 : sel0, tr);
       const bf16x8 g0 = pack8v(tr, 0), g1 = pack8v(tr, 8);
 #pragma unroll
       for (int ib = 0; ib < 2; ++ib) {
@@ -422,6 +496,11 @@ __global__ __launch_bounds__(512) void k_dw_bf16(DwBf16Args a) {
           acc[gi][ib] = mfma(g1, al[ib][1], acc[gi][ib]);
         }
       }
+    }
+    if (!AU && more) {
+      ra = na;
+#pragma unroll
+      for (int gi = 0; gi < NG; ++gi) { rg[gi][0] = ng[gi][0]; rg[gi][1] = ng[gi][1]; }
     }
   }
 #pragma unroll
@@ -1012,7 +1091,12 @@ void dysat_backward(const DysatWs& ws, const void* Y, int64_t ldy, const void* d
   da.A = nullptr; da.lda = 0; da.Uf = ws.U; da.pos = ws.P[DY_POS];
   da.G[0] = ws.dQ; da.G[1] = ws.dK; da.G[2] = ws.dV;
   da.partial = dw_slots; da.n_groups = groups;
-  hipLaunchKernelGGL((k_dw_bf16<3, true>), groups, 512, 0, st, da);
+  {  // LDS: the position rows of the snapshots one workgroup's tile range can touch
+    const int64_t tiles_per_t = (ws.N + 31) / 32, n_tiles = tiles_per_t * ws.n_used;
+    const int64_t per = (n_tiles + groups - 1) / groups;
+    const size_t pos_lds = sizeof(float) * kS * (size_t)((per + tiles_per_t - 1) / tiles_per_t + 1);
+    hipLaunchKernelGGL((k_dw_bf16<3, true>), groups, 512, pos_lds, st, da);
+  }
   for (int gi = 0; gi < 3; ++gi)
     hipLaunchKernelGGL(k_reduce_slots, blocks_for(kS * kS, 64), 1024, 0, st, dw_slots + (int64_t)gi * kS * kS,
                        (int64_t)groups, (int64_t)3 * kS * kS, (int64_t)kS * kS, 1.f, ws.G[DY_WQ + gi]);
