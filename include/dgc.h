@@ -309,15 +309,16 @@ dgc_status_t dgc_chunk_assign(int32_t n, const double* g, const double* h, int32
  *   DGC_THETA_SIGMOID 1 / (1 + exp(-norm)), the sign under which the threshold grows as the text
  *   around the equation says.  Returns a negative value for arguments outside the domain.
  *
- * dgc_stale_filter: E device [R, lde] current embeddings (fp32), L device [R, ldl] the copies
- *   transmitted last (updated in place; must not overlap E).  Candidates: the rows listed in `rows`
+ * dgc_stale_filter: E device [R, lde] current embeddings, L device [R, ldl] the copies transmitted
+ *   last (updated in place; must not overlap E); element type `dtype` (DGC_DTYPE_F32 or
+ *   DGC_DTYPE_BF16), pitches in elements and multiples of 16 bytes, 16-byte aligned.  Candidates: the rows listed in `rows`
  *   (device int64 [n_rows], ascending; entries outside [0, R) are skipped and counted in
  *   result->n_invalid), or every row if rows = NULL (then n_rows = 0).  For candidate c:
  *     dist[c] = || E[row] - L[row] ||_2 over the first F columns (fp32 arithmetic);
  *     D = max dist;  threshold = factor * D if factor >= 0, else `theta` (>= 0);
  *     row is transmitted iff dist[c] > threshold (compared in fp32).
  *   send_idx (device int64, room for every candidate) receives the transmitted row numbers in
- *   candidate order; send_buf (device [n, lds], may be NULL) row k receives E[send_idx[k]]; L[row]
+ *   candidate order; send_buf (device [n, lds], same element type, may be NULL) row k receives E[send_idx[k]]; L[row]
  *   <- E[row] for the transmitted rows, every other row of L is left as it is.  result (device)
  *   receives the count, D and the threshold used.  dist device fp32 [candidates], 16-byte aligned.
  *   workspace: device, 8-byte aligned, at least dgc_stale_workspace_bytes(candidates) bytes,
@@ -332,9 +333,9 @@ typedef struct {
 } dgc_stale_result_t;
 double dgc_stale_theta_factor(double l1, double l_prev, int32_t variant);
 int64_t dgc_stale_workspace_bytes(int64_t n_candidates);
-dgc_status_t dgc_stale_filter(const float* E, int64_t lde, float* L, int64_t ldl, int64_t R, int32_t F,
-                              const int64_t* rows, int64_t n_rows, double factor, double theta,
-                              float* dist, int64_t* send_idx, float* send_buf, int64_t lds,
+dgc_status_t dgc_stale_filter(const void* E, int64_t lde, void* L, int64_t ldl, int64_t R, int32_t F,
+                              int32_t dtype, const int64_t* rows, int64_t n_rows, double factor, double theta,
+                              float* dist, int64_t* send_idx, void* send_buf, int64_t lds,
                               dgc_stale_result_t* result, void* workspace, int64_t workspace_bytes,
                               void* stream);
 

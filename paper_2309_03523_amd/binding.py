@@ -92,7 +92,7 @@ def load() -> ct.CDLL:
     lib.dgc_stale_theta_factor.restype = ct.c_double
     lib.dgc_stale_workspace_bytes.argtypes = [i64]
     lib.dgc_stale_workspace_bytes.restype = i64
-    lib.dgc_stale_filter.argtypes = [vp, i64, vp, i64, i64, i32, vp, i64, ct.c_double, ct.c_double, vp, vp, vp, i64,
+    lib.dgc_stale_filter.argtypes = [vp, i64, vp, i64, i64, i32, i32, vp, i64, ct.c_double, ct.c_double, vp, vp, vp, i64,
                                      vp, vp, i64, vp]
     for name in EXPORTS:
         if name not in ("dgc_last_error", "dgc_version", "dgc_stale_theta_factor", "dgc_stale_workspace_bytes"):
@@ -289,7 +289,7 @@ def stale_workspace_bytes(n_candidates: int) -> int:
 
 def stale_filter(E, L, *, F=None, rows=None, n_rows=None, factor=None, theta=None, dist, send_idx, send_buf=None, result,
                  workspace, stream=None):
-    """dgc_stale_filter on device tensors: E, L [R, ld] fp32; rows int64 or None (n_rows: how many of
+    """dgc_stale_filter on device tensors: E, L [R, ld] fp32 or bfloat16; rows int64 or None (n_rows: how many of
     its entries count, default all; torch gives an empty tensor a NULL pointer, so an empty list is a
     non-empty tensor with n_rows = 0); dist fp32 and
     send_idx int64 with one entry per candidate; send_buf [n, ld] or None; result: 24-byte device
@@ -300,10 +300,12 @@ def stale_filter(E, L, *, F=None, rows=None, n_rows=None, factor=None, theta=Non
     for name, t in (("E", E), ("L", L)):
         if t.dim() != 2 or t.stride(1) != 1:
             raise ValueError(f"{name} must be [R, ld] with a contiguous last dimension")
+    if E.dtype != L.dtype or (send_buf is not None and send_buf.dtype != E.dtype):
+        raise ValueError("E, L and send_buf must have the same element type")
     lib = load()
     rc = lib.dgc_stale_filter(
         _dev(E, "E"), int(E.stride(0)), _dev(L, "L"), int(L.stride(0)), int(E.shape[0]),
-        int(E.shape[1] if F is None else F), _dev(rows, "rows"), 0 if rows is None else int(rows.numel() if n_rows is None else n_rows),
+        int(E.shape[1] if F is None else F), DTYPE["bf16" if E.element_size() == 2 else "f32"], _dev(rows, "rows"), 0 if rows is None else int(rows.numel() if n_rows is None else n_rows),
         -1.0 if factor is None else float(factor), 0.0 if theta is None else float(theta), _dev(dist, "dist"),
         _dev(send_idx, "send_idx"), _dev(send_buf, "send_buf"), 0 if send_buf is None else int(send_buf.stride(0)),
         _dev(result, "result"), _dev(workspace, "workspace"), int(workspace.numel() * workspace.element_size()),

@@ -23,8 +23,8 @@ constexpr int kSelTile = kSelBlock * kSelPer;  // candidates per block of the tw
 constexpr int kDistUnroll = 4;                  // row groups a wave keeps in flight
 
 struct StaleArgs {
-  const float* E; int64_t lde;
-  float* L; int64_t ldl;
+  const void* E; int64_t lde;   // rows of float or bfloat16 (the kernels' element type), pitches in elements
+  void* L; int64_t ldl;
   const int64_t* rows;  // nullptr: candidate c is row c
   int64_t R;            // rows of E and L
   int64_t n;            // candidates
@@ -33,7 +33,7 @@ struct StaleArgs {
   double theta;
   float* dist;
   int64_t* send_idx;
-  float* send_buf; int64_t lds;
+  void* send_buf; int64_t lds;
   dgc_stale_result_t* result;
   int64_t* counts;      // [blocks of kSelTile]
   const int64_t* total;
@@ -43,15 +43,35 @@ __global__ void k_stale_init(dgc_stale_result_t* r) {
   r->n_send = 0; r->D = 0.f; r->theta = 0.f; r->n_invalid = 0;
 }
 
-__device__ __forceinline__ float sqdiff4(const float4 a, const float4 b) {
-  const float x = a.x - b.x, y = a.y - b.y, z = a.z - b.z, w = a.w - b.w;
-  return x * x + y * y + z * z + w * w;
-}
+// Element types: float, or bfloat16 carried as uint16_t (its bits are the top half of a float's).
+template <class T> struct Elem;
+template <> struct Elem<float> {
+  static constexpr int kPerVec = 4;   // elements in a 16-byte vector
+  static __device__ __forceinline__ float get(float v) { return v; }
+  static __device__ __forceinline__ float sqdiff(const uint4 a, const uint4 b) {
+    const float x = __uint_as_float(a.x) - __uint_as_float(b.x), y = __uint_as_float(a.y) - __uint_as_float(b.y);
+    const float z = __uint_as_float(a.z) - __uint_as_float(b.z), w = __uint_as_float(a.w) - __uint_as_float(b.w);
+    return x * x + y * y + z * z + w * w;
+  }
+};
+template <> struct Elem<uint16_t> {
+  static constexpr int kPerVec = 8;
+  static __device__ __forceinline__ float get(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
+  static __device__ __forceinline__ float sq2(uint32_t a, uint32_t b) {
+    const float x = __uint_as_float(a << 16) - __uint_as_float(b << 16);
+    const float y = __uint_as_float(a & 0xffff0000u) - __uint_as_float(b & 0xffff0000u);
+    return x * x + y * y;
+  }
+  static __device__ __forceinline__ float sqdiff(const uint4 a, const uint4 b) {
+    return sq2(a.x, b.x) + sq2(a.y, b.y) + sq2(a.z, b.z) + sq2(a.w, b.w);
+  }
+};
 
-// LPR lanes share a row (a float4 each per sweep of 4*LPR columns), 64/LPR rows per wave and
-// sweep, kDistUnroll sweeps in flight.
-template <int LPR>
+// LPR lanes share a row (a 16-byte vector each per sweep of LPR vectors), 64/LPR rows per wave
+// and sweep, kDistUnroll sweeps in flight.
+template <int LPR, class T>
 __global__ __launch_bounds__(256) void k_stale_dist(StaleArgs a) {
+  constexpr int EPV = Elem<T>::kPerVec;
   constexpr int RPW = 64 / LPR;
   const int lane = threadIdx.x & 63, sub = lane % LPR, grp = lane / LPR;
   const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
@@ -67,13 +87,13 @@ __global__ __launch_bounds__(256) void k_stale_dist(StaleArgs a) {
       if (c < a.n && (r < 0 || r >= a.R)) {  // a listed row outside the tensors: distance 0, counted
         if (sub == 0) atomicAdd(reinterpret_cast<unsigned long long*>(&a.result->n_invalid), 1ull);
       } else if (c < a.n) {
-        const float* e = a.E + r * a.lde;
-        const float* l = a.L + r * a.ldl;
-        for (int col = sub * 4; col < a.F; col += LPR * 4) {
-          if (col + 4 <= a.F) {
-            acc[u] += sqdiff4(*reinterpret_cast<const float4*>(e + col), *reinterpret_cast<const float4*>(l + col));
+        const T* e = static_cast<const T*>(a.E) + r * a.lde;
+        const T* l = static_cast<const T*>(a.L) + r * a.ldl;
+        for (int col = sub * EPV; col < a.F; col += LPR * EPV) {
+          if (col + EPV <= a.F) {
+            acc[u] += Elem<T>::sqdiff(*reinterpret_cast<const uint4*>(e + col), *reinterpret_cast<const uint4*>(l + col));
           } else {
-            for (int k = col; k < a.F; ++k) { const float d = e[k] - l[k]; acc[u] += d * d; }
+            for (int k = col; k < a.F; ++k) { const float d = Elem<T>::get(e[k]) - Elem<T>::get(l[k]); acc[u] += d * d; }
           }
         }
       }
@@ -139,8 +159,9 @@ __global__ __launch_bounds__(kSelBlock) void k_stale_count(StaleArgs a) {
 
 // counts now holds the exclusive scan.  Thread order = candidate order, so the block's selected
 // rows land in ascending order; they are then copied LPR lanes to a row.
-template <int LPR>
+template <int LPR, class T>
 __global__ __launch_bounds__(kSelBlock) void k_stale_compact(StaleArgs a) {
+  constexpr int EPV = Elem<T>::kPerVec;
   __shared__ int64_t sel_row[kSelTile];
   __shared__ int wbase[kSelBlock / 64 + 1];
   const float th = threshold_of(a);
@@ -180,14 +201,14 @@ __global__ __launch_bounds__(kSelBlock) void k_stale_compact(StaleArgs a) {
   const int sub = threadIdx.x % LPR, grp = threadIdx.x / LPR;
   for (int i = grp; i < n_sel; i += RPB) {
     const int64_t r = sel_row[i];
-    const float* e = a.E + r * a.lde;
-    float* l = a.L + r * a.ldl;
-    float* s = a.send_buf ? a.send_buf + (off + i) * a.lds : nullptr;
-    for (int col = sub * 4; col < a.F; col += LPR * 4) {
-      if (col + 4 <= a.F) {
-        const float4 v = *reinterpret_cast<const float4*>(e + col);
-        *reinterpret_cast<float4*>(l + col) = v;
-        if (s) *reinterpret_cast<float4*>(s + col) = v;
+    const T* e = static_cast<const T*>(a.E) + r * a.lde;
+    T* l = static_cast<T*>(a.L) + r * a.ldl;
+    T* s = a.send_buf ? static_cast<T*>(a.send_buf) + (off + i) * a.lds : nullptr;
+    for (int col = sub * EPV; col < a.F; col += LPR * EPV) {
+      if (col + EPV <= a.F) {
+        const uint4 v = *reinterpret_cast<const uint4*>(e + col);
+        *reinterpret_cast<uint4*>(l + col) = v;
+        if (s) *reinterpret_cast<uint4*>(s + col) = v;
       } else {
         for (int k = col; k < a.F; ++k) { l[k] = e[k]; if (s) s[k] = e[k]; }
       }
@@ -197,16 +218,26 @@ __global__ __launch_bounds__(kSelBlock) void k_stale_compact(StaleArgs a) {
 
 int64_t sel_blocks(int64_t n) { return (n + kSelTile - 1) / kSelTile; }
 
-template <int LPR>
+template <int LPR, class T>
 void launch_all(const StaleArgs& a, int64_t* scan_tmp, int64_t* total, hipStream_t st) {
   constexpr int RPW = 64 / LPR;
   const int64_t per_block = 4 * RPW * kDistUnroll;
   const unsigned grid = (unsigned)std::min<int64_t>((a.n + per_block - 1) / per_block, 256 * 32);
-  hipLaunchKernelGGL(k_stale_dist<LPR>, grid, 256, 0, st, a);
+  hipLaunchKernelGGL((k_stale_dist<LPR, T>), grid, 256, 0, st, a);
   const unsigned nb = (unsigned)sel_blocks(a.n);
   hipLaunchKernelGGL(k_stale_count, nb, kSelBlock, 0, st, a);
   launch_exclusive_scan(a.counts, nb, scan_tmp, total, st);
-  hipLaunchKernelGGL(k_stale_compact<LPR>, nb, kSelBlock, 0, st, a);
+  hipLaunchKernelGGL((k_stale_compact<LPR, T>), nb, kSelBlock, 0, st, a);
+}
+
+template <class T>
+void launch_for_width(const StaleArgs& a, int64_t* scan_tmp, int64_t* total, hipStream_t st) {
+  const int vecs = (a.F + Elem<T>::kPerVec - 1) / Elem<T>::kPerVec;   // 16-byte vectors per row
+  if (vecs <= 4) launch_all<4, T>(a, scan_tmp, total, st);
+  else if (vecs <= 8) launch_all<8, T>(a, scan_tmp, total, st);
+  else if (vecs <= 16) launch_all<16, T>(a, scan_tmp, total, st);
+  else if (vecs <= 32) launch_all<32, T>(a, scan_tmp, total, st);
+  else launch_all<64, T>(a, scan_tmp, total, st);
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -230,17 +261,19 @@ int64_t dgc_stale_workspace_bytes(int64_t n_candidates) {
   return 8 * (nb + 1 + scan_tmp_elems(nb) + 1);
 }
 
-dgc_status_t dgc_stale_filter(const float* E, int64_t lde, float* L, int64_t ldl, int64_t R, int32_t F,
+dgc_status_t dgc_stale_filter(const void* E, int64_t lde, void* L, int64_t ldl, int64_t R, int32_t F, int32_t dtype,
                               const int64_t* rows, int64_t n_rows, double factor, double theta, float* dist,
-                              int64_t* send_idx, float* send_buf, int64_t lds, dgc_stale_result_t* result,
+                              int64_t* send_idx, void* send_buf, int64_t lds, dgc_stale_result_t* result,
                               void* workspace, int64_t workspace_bytes, void* stream) {
   auto bad = [](dgc_status_t code, const char* msg) { set_thread_error(msg); return code; };
   if (!E || !L || !result || !workspace) return bad(DGC_ERR_INVALID_ARG, "stale filter: NULL argument");
   if (R < 0 || F < 1 || F > 4096) return bad(DGC_ERR_INVALID_ARG, "stale filter: R must be >= 0 and F in [1, 4096]");
-  if (lde < F || ldl < F || lde % 4 || ldl % 4 || !aligned16(E) || !aligned16(L))
-    return bad(DGC_ERR_INVALID_ARG, "stale filter: E, L need a pitch >= F that is a multiple of 4 and 16-byte alignment");
-  if (send_buf && (lds < F || lds % 4 || !aligned16(send_buf)))
-    return bad(DGC_ERR_INVALID_ARG, "stale filter: send_buf needs a pitch >= F that is a multiple of 4 and 16-byte alignment");
+  if (dtype != DGC_DTYPE_F32 && dtype != DGC_DTYPE_BF16) return bad(DGC_ERR_INVALID_ARG, "stale filter: unknown dtype");
+  const int epv = dtype == DGC_DTYPE_F32 ? 4 : 8, esz = 16 / epv;   // elements per 16 bytes, bytes per element
+  if (lde < F || ldl < F || lde % epv || ldl % epv || !aligned16(E) || !aligned16(L))
+    return bad(DGC_ERR_INVALID_ARG, "stale filter: E, L need a pitch >= F that is a multiple of 16 bytes and 16-byte alignment");
+  if (send_buf && (lds < F || lds % epv || !aligned16(send_buf)))
+    return bad(DGC_ERR_INVALID_ARG, "stale filter: send_buf needs a pitch >= F that is a multiple of 16 bytes and 16-byte alignment");
   if (rows ? n_rows < 0 || n_rows > R : n_rows != 0)
     return bad(DGC_ERR_INVALID_ARG, "stale filter: n_rows must be in [0, R] with a row list and 0 without");
   const int64_t n = rows ? n_rows : R;
@@ -252,8 +285,8 @@ dgc_status_t dgc_stale_filter(const float* E, int64_t lde, float* L, int64_t ldl
   if (workspace_bytes < dgc_stale_workspace_bytes(n) || (reinterpret_cast<uintptr_t>(workspace) & 7))
     return bad(DGC_ERR_INVALID_ARG, "stale filter: workspace too small (dgc_stale_workspace_bytes) or not 8-byte aligned");
   {  // E and L are read and written by different blocks of one launch: they must not overlap
-    const char* e0 = reinterpret_cast<const char*>(E); const char* e1 = e0 + 4 * (R * lde);
-    const char* l0 = reinterpret_cast<const char*>(L); const char* l1 = l0 + 4 * (R * ldl);
+    const char* e0 = reinterpret_cast<const char*>(E); const char* e1 = e0 + esz * (R * lde);
+    const char* l0 = reinterpret_cast<const char*>(L); const char* l1 = l0 + esz * (R * ldl);
     if (R > 0 && e0 < l1 && l0 < e1) return bad(DGC_ERR_INVALID_ARG, "stale filter: E and L overlap");
   }
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -268,11 +301,8 @@ dgc_status_t dgc_stale_filter(const float* E, int64_t lde, float* L, int64_t ldl
     a.counts = ws; a.total = ws + nb + 1;
     int64_t* scan_tmp = ws + nb + 2;
     int64_t* total = ws + nb + 1;
-    if (F <= 16) launch_all<4>(a, scan_tmp, total, st);
-    else if (F <= 32) launch_all<8>(a, scan_tmp, total, st);
-    else if (F <= 64) launch_all<16>(a, scan_tmp, total, st);
-    else if (F <= 128) launch_all<32>(a, scan_tmp, total, st);
-    else launch_all<64>(a, scan_tmp, total, st);
+    if (dtype == DGC_DTYPE_F32) launch_for_width<float>(a, scan_tmp, total, st);
+    else launch_for_width<uint16_t>(a, scan_tmp, total, st);
   }
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return bad(DGC_ERR_DEVICE, hipGetErrorString(e));

@@ -120,10 +120,10 @@ def test_stale_threshold_factor_and_host_checks(lib):
     w = [lib.dgc_stale_workspace_bytes(n) for n in (0, 1, 2048, 2049, 10 ** 7)]
     assert w[0] > 0 and all(a <= b for a, b in zip(w, w[1:])) and lib.dgc_stale_workspace_bytes(-1) < 0
     lib.dgc_stale_filter.restype = ct.c_int
-    lib.dgc_stale_filter.argtypes = [ct.c_void_p, ct.c_int64, ct.c_void_p, ct.c_int64, ct.c_int64, ct.c_int32,
+    lib.dgc_stale_filter.argtypes = [ct.c_void_p, ct.c_int64, ct.c_void_p, ct.c_int64, ct.c_int64, ct.c_int32, ct.c_int32,
                                      ct.c_void_p, ct.c_int64, ct.c_double, ct.c_double, ct.c_void_p, ct.c_void_p,
                                      ct.c_void_p, ct.c_int64, ct.c_void_p, ct.c_void_p, ct.c_int64, ct.c_void_p]
-    assert lib.dgc_stale_filter(None, 0, None, 0, 0, 0, None, 0, 0.5, 0.0, None, None, None, 0, None, None, 0, None) == 1
+    assert lib.dgc_stale_filter(None, 0, None, 0, 0, 0, 0, None, 0, 0.5, 0.0, None, None, None, 0, None, None, 0, None) == 1
     assert b"stale filter" in lib.dgc_last_error(None)
 
 

@@ -13,21 +13,22 @@ DIST_TOL = 2e-6     # relative, fp32 sum of F <= 512 squared differences against
 BAND = 1e-5         # rows this close (relative) to the threshold may fall either way
 
 
-def _device_filter(E, L, ld, rows, factor, theta, with_buf=True):
+def _device_filter(E, L, ld, rows, factor, theta, with_buf=True, bf16=False):
     import torch
     from paper_2309_03523_amd import binding
     R, F = E.shape
-    Ed = torch.full((R, ld), float("nan"), device="cuda")
-    Ld = torch.full((R, ld), float("nan"), device="cuda")
-    Ed[:, :F] = torch.from_numpy(E).cuda()
-    Ld[:, :F] = torch.from_numpy(L).cuda()
+    dt = torch.bfloat16 if bf16 else torch.float32      # bf16: E and L hold bf16-representable values already
+    Ed = torch.full((R, ld), float("nan"), device="cuda", dtype=dt)
+    Ld = torch.full((R, ld), float("nan"), device="cuda", dtype=dt)
+    Ed[:, :F] = torch.from_numpy(E).cuda().to(dt)
+    Ld[:, :F] = torch.from_numpy(L).cuda().to(dt)
     rd = None if rows is None else torch.from_numpy(rows).cuda()
     if rows is not None and rows.size == 0:     # an empty list is still a list: keep its pointer non-NULL
         rd = torch.zeros(1, dtype=torch.int64, device="cuda")
     n = R if rows is None else rows.size
     dist = torch.full((max(n, 1),), -1.0, device="cuda")
     send_idx = torch.full((max(n, 1),), -7, dtype=torch.int64, device="cuda")
-    send_buf = torch.full((max(n, 1), ld), float("nan"), device="cuda") if with_buf else None
+    send_buf = torch.full((max(n, 1), ld), float("nan"), device="cuda", dtype=dt) if with_buf else None
     result = torch.zeros(24, dtype=torch.uint8, device="cuda")
     ws = torch.empty(binding.stale_workspace_bytes(n), dtype=torch.uint8, device="cuda")
     binding.stale_filter(Ed, Ld, F=F, rows=rd, n_rows=None if rows is None else rows.size, factor=factor, theta=theta, dist=dist, send_idx=send_idx,
@@ -36,8 +37,8 @@ def _device_filter(E, L, ld, rows, factor, theta, with_buf=True):
     res = result.cpu().numpy().view(binding.STALE_RESULT_DTYPE)[0]
     k = int(res["n_send"])
     return {"dist": dist.cpu().numpy()[:n], "send_idx": send_idx.cpu().numpy()[:k],
-            "send_buf": None if send_buf is None else send_buf.cpu().numpy()[:k, :F],
-            "L_new": Ld.cpu().numpy()[:, :F], "pad": Ld.cpu().numpy()[:, F:], "res": res,
+            "send_buf": None if send_buf is None else send_buf.float().cpu().numpy()[:k, :F],
+            "L_new": Ld.float().cpu().numpy()[:, :F], "pad": Ld.float().cpu().numpy()[:, F:], "res": res,
             "tail_idx": send_idx.cpu().numpy()[k:n]}
 
 
@@ -76,6 +77,9 @@ CASES = {
     "f300_two_sweeps": dict(R=700, F=300, ld=300, frac=None, factor=0.5),
     "f16_small": dict(R=70, F=16, ld=16, frac=None, factor=0.1),
     "theta_zero": dict(R=3000, F=64, ld=64, frac=None, theta=0.0),
+    "bf16_f128": dict(R=5000, F=128, ld=128, frac=None, factor=0.3, bf16=True),
+    "bf16_f100_subset_tail": dict(R=3000, F=100, ld=104, frac=0.4, theta=0.8, bf16=True),
+    "bf16_f520_two_sweeps": dict(R=600, F=520, ld=520, frac=None, factor=0.5, bf16=True),
     "factor_one": dict(R=3000, F=64, ld=64, frac=0.5, factor=1.0),
 }
 
@@ -84,8 +88,10 @@ CASES = {
 def test_filter_matches_oracle(name):
     c = CASES[name]
     E, L = synth.drifted_copies(11, c["R"], c["F"])
+    if c.get("bf16"):
+        E, L = synth.round_bf16(E), synth.round_bf16(L)
     rows = None if c["frac"] is None else synth.boundary_rows(11, c["R"], c["frac"])
-    got = _device_filter(E, L, c["ld"], rows, c.get("factor"), c.get("theta"))
+    got = _device_filter(E, L, c["ld"], rows, c.get("factor"), c.get("theta"), bf16=bool(c.get("bf16")))
     want, sure = _check(E, L, rows, c.get("factor"), c.get("theta"), got)
     print(f"{name}: {got['send_idx'].size} of {want['dist'].size} candidates sent, D {want['D']:.4f}, theta "
           f"{want['theta']:.4f}, {int((~sure).sum())} rows inside the rounding band", flush=True)
