@@ -624,6 +624,19 @@ def main():
         torch.cuda.synchronize()
         print(f"calib-copy: {dw.X.numel() * 4} bytes read and as many written", file=sys.stderr)
         del scratch
+    # measured HBM ceiling next to the published one: a plain device copy of X (read + write)
+    copy_GBs = None
+    if dw.X.numel() * dw.X.element_size() >= (1 << 28) and not evolve:
+        scratch = torch.empty_like(dw.X)
+        scratch.copy_(dw.X)
+        cm = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        cm[0].record(stream)
+        for _ in range(5):
+            scratch.copy_(dw.X)
+        cm[1].record(stream)
+        torch.cuda.synchronize()
+        copy_GBs = 5 * 2 * dw.X.numel() * dw.X.element_size() / (cm[0].elapsed_time(cm[1]) * 1e-3) / 1e9
+        del scratch
     for _ in range(args.warmup):
         step()
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # per-step device times
@@ -691,7 +704,7 @@ def main():
            "roofline": roofline, "roofline_aggregation": agg,
            "stage_ms": {"aggregate0": float(stage[0]), "dense0": float(stage[1]), "aggregate1": float(stage[2]),
                         "dense_rnn": float(stage[3])},
-           "device_ms_per_step": step_stats,
+           "device_ms_per_step": step_stats, "measured_hbm_copy_GBs": copy_GBs,
            "setup_s": {"generate": t_gen, "upload_create_pack": t_create}}
     if tfuse:
         out["temporal_fusion"] = tfuse

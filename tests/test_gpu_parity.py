@@ -134,6 +134,17 @@ def test_layer_matches_oracle(torch_mod, kind, F, S, H, dense):
     dw.layer.destroy()
 
 
+@pytest.mark.parametrize("kind", ["gru", "lstm"])
+def test_maximum_dimensions(torch_mod, kind):
+    """The largest dimensions the descriptor allows: F = 512, S = H = 256."""
+    N, T = 140, 3
+    chunks = [[0, 70, 0, 3], [70, 140, 0, 2], [70, 140, 2, 3]]
+    wl = synth.random_small(9, T, N, 512, 256, 256, 5.0, chunks, kind, hub=True)
+    dw = _dw(wl)
+    _compare_layer(torch_mod, wl, dw)
+    dw.layer.destroy()
+
+
 @pytest.mark.parametrize("kind", ["gru", "lstm", "none"])
 @pytest.mark.parametrize("mode", ["in_place", "staged"])
 def test_two_layer_gcn(torch_mod, kind, mode):
