@@ -6,6 +6,7 @@ from typing import Optional
 
 import numpy as np
 
+from . import synth
 from .binding import DgcLayer
 
 
@@ -33,7 +34,10 @@ class DeviceWorkload:
             T, N, F = a.shape
             ld = ld or (F + 3) // 4 * 4
             buf = torch.full((T, N, ld), float("nan"), dtype=torch.float32, device=dev)
-            buf[:, :, :F] = torch.from_numpy(a).to(dev)
+            for t in range(T):      # snapshot by snapshot: no second full-size device copy
+                buf[t, :, :F] = torch.from_numpy(a[t]).to(dev)
+                if a.nbytes >= (1 << 32) and (t + 1) % max(1, T // 4) == 0 and synth.progress:
+                    synth.progress(f"  upload {tuple(a.shape)}: {t + 1}/{T} snapshots")
             return buf[:, :, :F] if ld != F else buf
 
         self.X = up(wl.X, pitch)
