@@ -99,7 +99,10 @@ typedef struct {
   int32_t time_kind;       /* DGC_TIME_*                                                     */
   int32_t dtype;           /* DGC_DTYPE_*: element type of X, C, Y, dY, target               */
   int32_t F, S, H;         /* input dim, structure-encoder output dim, hidden dim.  S and H
-                              multiples of 32, at most 256; F at most 512                    */
+                              multiples of 32, at most 256; F at most 512.  Where the
+                              workgroup-tile kernel runs (DGC_DENSE_TILE, or S, H outside what
+                              DGC_DENSE_WAVE takes) its operand tile lives in LDS:
+                              max(F rounded up to 8, S, H) <= 304, else DGC_ERR_UNSUPPORTED   */
   int32_t act_hidden;      /* activation between stacked GCN layers                          */
   int32_t act_out;         /* activation after the last GCN layer                            */
   int32_t gather_mode;     /* DGC_GATHER_*                                                   */

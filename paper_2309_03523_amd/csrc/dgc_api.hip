@@ -157,6 +157,19 @@ dgc_status_t check_desc(const dgc_layer_desc_t& d, std::string* msg) {
   if (d.rows_per_group < 0 || d.rows_per_group > 32) { *msg = "rows_per_group must be in [0,32]"; return DGC_ERR_INVALID_ARG; }
   if (d.dense_kernel < DGC_DENSE_AUTO || d.dense_kernel > DGC_DENSE_WAVE) { *msg = "unknown dense_kernel"; return DGC_ERR_INVALID_ARG; }
   if (d.long_nnz < 0 || d.part_nnz < 0) { *msg = "long_nnz / part_nnz must be >= 0"; return DGC_ERR_INVALID_ARG; }
+  // Where the workgroup-tile kernel runs a dense stage, its operand tile must fit the 160 KB of LDS.
+  auto tile_kernel_runs = [&](int32_t S, int32_t H, int32_t kind) {
+    const bool s_ok = S == 32 || S == 64 || S == 128 || (S == 256 && kind == DGC_TIME_NONE);
+    return d.dense_kernel == DGC_DENSE_TILE || !(s_ok && (kind == DGC_TIME_NONE || H == S));
+  };
+  auto fits = [&](int32_t K0, int32_t S, int32_t H, int32_t kind) {
+    return !tile_kernel_runs(S, H, kind) || dense_lds_bytes(K0, S, kind == DGC_TIME_NONE ? 0 : H) <= 160 * 1024;
+  };
+  const bool two = d.n_struct_layers == 2;
+  if (!fits(two ? d.S : d.F, d.S, d.H, d.time_kind) || (two && !fits(d.F, d.S, 0, DGC_TIME_NONE))) {
+    *msg = "these dimensions need the workgroup-tile kernel, whose tile holds max(F rounded up to 8, S, H) <= 304 columns";
+    return DGC_ERR_UNSUPPORTED;
+  }
   return DGC_OK;
 }
 

@@ -134,15 +134,26 @@ def test_layer_matches_oracle(torch_mod, kind, F, S, H, dense):
     dw.layer.destroy()
 
 
-@pytest.mark.parametrize("kind", ["gru", "lstm"])
-def test_maximum_dimensions(torch_mod, kind):
-    """The largest dimensions the descriptor allows: F = 512, S = H = 256."""
+@pytest.mark.parametrize("kind,F,S,H", [("gru", 512, 128, 128), ("lstm", 512, 128, 128), ("none", 512, 256, 256),
+                                        ("gru", 304, 256, 256), ("lstm", 300, 256, 256)])
+def test_maximum_dimensions(torch_mod, kind, F, S, H):
+    """The largest dimensions that run: F = 512 with the wave-private kernel, max(F, S, H) = 304
+    columns where the workgroup-tile kernel (its tile lives in LDS) has to run."""
     N, T = 140, 3
     chunks = [[0, 70, 0, 3], [70, 140, 0, 2], [70, 140, 2, 3]]
-    wl = synth.random_small(9, T, N, 512, 256, 256, 5.0, chunks, kind, hub=True)
+    wl = synth.random_small(9, T, N, F, S, H, 5.0, chunks, kind, hub=True)
     dw = _dw(wl)
     _compare_layer(torch_mod, wl, dw)
     dw.layer.destroy()
+
+
+def test_dimensions_beyond_the_tile_are_refused_at_create(torch_mod):
+    from paper_2309_03523_amd.binding import DgcError
+    wl = synth.random_small(9, 2, 40, 512, 256, 256, 4.0, [[0, 40, 0, 2]], "gru")
+    with pytest.raises(DgcError, match="workgroup-tile kernel"):
+        _dw(wl)
+    with pytest.raises(DgcError, match="workgroup-tile kernel"):
+        _dw(synth.random_small(9, 2, 40, 312, 128, 128, 4.0, [[0, 40, 0, 2]], "gru"), dense_kernel="tile")
 
 
 @pytest.mark.parametrize("kind", ["gru", "lstm", "none"])
