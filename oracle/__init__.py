@@ -202,9 +202,9 @@ EVOLVE_PARAMS = ["evolve.W_init", "evolve.U_z", "evolve.V_z", "evolve.B_z", "evo
 
 
 def evolve(graph, chunks, params: dict, X: np.ndarray, C: np.ndarray, target: Optional[np.ndarray] = None,
-           want_grads: bool = False, Y: Optional[np.ndarray] = None):
+           want_grads: bool = False, Y: Optional[np.ndarray] = None, want_dx: bool = False):
     """EvolveGCN-O layer: weights evolved by a matrix GRU, Y = relu(M W_t), mean-squared-error loss.
-    Returns dict(Y, loss, grads {name: float64 array}, Wt [T,F,S])."""
+    Returns dict(Y, loss, grads {name: float64 array}, Wt [T,F,S], dX [T,N,F] float64 if want_dx)."""
     g = _Csr(graph)
     ch = _chunks(chunks)
     T, N = g.T, g.N
@@ -217,6 +217,7 @@ def evolve(graph, chunks, params: dict, X: np.ndarray, C: np.ndarray, target: Op
     grads = [np.zeros_like(a) for a in P] if want_grads else None
     garr = (ct.POINTER(ct.c_double) * 10)(*[_p(a, ct.c_double) for a in grads]) if want_grads else None
     Wt = np.zeros((T, F, S), np.float64)
+    dX = np.zeros((T, N, F), np.float64) if want_dx else None
     loss = ct.c_double(0.0)
     if target is not None:
         target = np.ascontiguousarray(target, np.float32)
@@ -226,8 +227,8 @@ def evolve(graph, chunks, params: dict, X: np.ndarray, C: np.ndarray, target: Op
         ct.c_int32(S), _p(X, ct.c_float), ct.c_int64(X.strides[1] // 4), _p(C, ct.c_float),
         ct.c_int64(C.strides[1] // 4), parr, _p(target, ct.c_float),
         ct.c_int64(target.strides[1] // 4 if target is not None else 0), _p(Y, ct.c_float),
-        ct.c_int64(Y.strides[1] // 4), ct.byref(loss), garr, _p(Wt, ct.c_double))
+        ct.c_int64(Y.strides[1] // 4), ct.byref(loss), garr, _p(Wt, ct.c_double), _p(dX, ct.c_double))
     if rc:
         raise ValueError(f"dgc_oracle_evolve failed: {rc}")
-    return {"Y": Y, "loss": loss.value, "Wt": Wt,
+    return {"Y": Y, "loss": loss.value, "Wt": Wt, "dX": dX,
             "grads": dict(zip(EVOLVE_PARAMS, grads)) if want_grads else None}

@@ -427,12 +427,14 @@ static void ev_weights(int32_t T, int32_t F, int32_t S, const double *const *P, 
 
 /* Forward (Y, loss) and, if grads != NULL, the gradient of the loss w.r.t. the 10 parameter
  * matrices (grads: array of 10 double arrays, overwritten).  Wt_out (optional): [T][F][S].
- * target may be NULL (then loss = 0 and no backward).  Returns 0 or <0. */
+ * dX (optional, [T][N][F] doubles, zero on entry): the gradient w.r.t. the input rows; a row's
+ * gradient comes from the rows of its own chunk that read it as a neighbour - the cache is a
+ * constant.  target may be NULL (then loss = 0 and no backward).  Returns 0 or <0. */
 int dgc_oracle_evolve(int32_t T, int64_t N, const int64_t *const *rowptr, const int32_t *const *col,
                       const int64_t *chunks, int32_t n_chunks, int32_t F, int32_t S, const float *X,
                       int64_t ldx, const float *C, int64_t ldc, const double *const *P,
                       const float *target, int64_t ldt, float *Y, int64_t ldy, double *loss_out,
-                      double *const *grads, double *Wt_out) {
+                      double *const *grads, double *Wt_out, double *dX) {
   const int64_t n = (int64_t)F * S;
   double *Wt = (double *)malloc(sizeof(double) * T * n);
   double *Zg = (double *)malloc(sizeof(double) * T * n), *Rg = (double *)malloc(sizeof(double) * T * n);
@@ -453,6 +455,7 @@ int dgc_oracle_evolve(int32_t T, int64_t N, const int64_t *const *rowptr, const 
       double *dW = dWd + t * n;
       double *m = (double *)malloc(sizeof(double) * (size_t)F);
       double *dp = (double *)malloc(sizeof(double) * (size_t)S);
+      double *dm = (double *)malloc(sizeof(double) * (size_t)F);
       for (int64_t i = v_lo; i < v_hi; ++i) { /* serial: the dW sum is taken in row order */
         aggregate_row(N, rowptr[t], col[t], t, i, v_lo, v_hi, X, ldx, NULL, C, ldc, F, m);
         float *y = Y + (t * N + i) * ldy;
@@ -471,8 +474,23 @@ int dgc_oracle_evolve(int32_t T, int64_t N, const int64_t *const *rowptr, const 
         if (target && grads)
           for (int32_t f = 0; f < F; ++f)
             for (int32_t s = 0; s < S; ++s) dW[(int64_t)f * S + s] += m[f] * dp[s];
+        if (target && dX) { /* dL/dm_i = W_t dp_i, handed to the in-chunk neighbours with the edge's weight */
+          const int64_t *rp = rowptr[t];
+          const double d_i = (double)(rp[i + 1] - rp[i]);
+          for (int32_t f = 0; f < F; ++f) {
+            double acc = 0.0;
+            for (int32_t s = 0; s < S; ++s) acc += W[(int64_t)f * S + s] * dp[s];
+            dm[f] = acc;
+          }
+          for (int64_t e = rp[i]; e < rp[i + 1]; ++e) {
+            const int64_t j = col[t][e];
+            if (j < v_lo || j >= v_hi) continue;
+            const double w = 1.0 / sqrt(d_i * (double)(rp[j + 1] - rp[j]));
+            for (int32_t f = 0; f < F; ++f) dX[(t * N + j) * (int64_t)F + f] += w * dm[f];
+          }
+        }
       }
-      free(m); free(dp);
+      free(m); free(dp); free(dm);
     }
   }
   if (loss_out) *loss_out = target ? loss / (double)count : 0.0;

@@ -10,8 +10,9 @@ from paper_2309_03523_amd import synth
 from refs import dense_norm_adj, edges_of
 
 
-def _torch_layer(wl, chunks, P, target):
-    """The layer by its definition with torch ops on dense matrices; returns (Y, loss)."""
+def _torch_layer(wl, chunks, P, target, Xt=None):
+    """The layer by its definition with torch ops on dense matrices; returns (Y, loss).
+    Xt: the input as a torch tensor (to differentiate with respect to it)."""
     T, N = wl.graph.T, wl.graph.N
     W = P["evolve.W_init"]
     rows, tgts = [], []
@@ -28,7 +29,8 @@ def _torch_layer(wl, chunks, P, target):
         for t in range(t_lo, t_hi):
             Ahat = torch.from_numpy(dense_norm_adj(N, edges_of(wl.graph.snaps[t])))
             mix = torch.from_numpy(wl.C[t].astype(np.float64)).clone()
-            mix[v_lo:v_hi] = torch.from_numpy(wl.X[t, v_lo:v_hi].astype(np.float64))
+            mix[v_lo:v_hi] = (torch.from_numpy(wl.X[t, v_lo:v_hi].astype(np.float64)) if Xt is None
+                              else Xt[t, v_lo:v_hi])
             y = torch.relu(Ahat[v_lo:v_hi] @ mix @ Ws[t])
             Y[t, v_lo:v_hi] = y.detach()
             sq = sq + ((y - torch.from_numpy(target[t, v_lo:v_hi].astype(np.float64))) ** 2).sum()
@@ -43,10 +45,14 @@ def test_evolve_forward_and_gradients_equal_torch_autograd(F, S):
     wl = synth.random_small(91, T, N, F, 32, 32, 3.0, chunks, "none", hub=True)
     params = synth.evolve_params(7, F, S, random_bias=True)
     target = synth.stream(7, "target").standard_normal((T, N, S)).astype(np.float32)
-    got = oracle.evolve(wl.graph, chunks, params, wl.X, wl.C, target, want_grads=True)
+    got = oracle.evolve(wl.graph, chunks, params, wl.X, wl.C, target, want_grads=True, want_dx=True)
     P = {k: torch.tensor(v.astype(np.float64), requires_grad=True) for k, v in params.items()}
-    Y, loss, Ws = _torch_layer(wl, chunks, P, target)
+    Xt = torch.tensor(wl.X.astype(np.float64), requires_grad=True)
+    Y, loss, Ws = _torch_layer(wl, chunks, P, target, Xt)
     loss.backward()
+    # gradient w.r.t. the input rows: only through the rows of the same chunk (the cache is a constant)
+    gx = Xt.grad.numpy()
+    assert np.abs(got["dX"] - gx).max() < 1e-12 * max(1.0, np.abs(gx).max()) and np.abs(gx).max() > 0
     assert np.abs(got["Wt"] - Ws.detach().numpy()).max() < 1e-12
     assert np.nanmax(np.abs(got["Y"] - Y.numpy())) < 1e-5
     assert abs(got["loss"] - loss.item()) < 1e-10 * max(1.0, abs(loss.item()))
