@@ -34,6 +34,8 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--with-dx", action="store_true",
+                    help="EvolveGCN-O workloads: the backward pass also computes the gradient of the input rows")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain device copy of X (a kernel of known size, to scale rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -111,7 +113,7 @@ def evolve_report(args, wl, desc, dw, rows, value, ms_per_step, stage, t_gen, t_
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": desc, "rows": rows, "nnz": nnz, "gather_mode": args.gather_mode,
-                      "pass": "forward+backward"},
+                      "pass": "forward+backward" + (" incl. input gradient" if args.with_dx else "")},
            "roofline": dom, "kernels": kernels,
            "stage_ms": {"aggregate0": float(stage[0]), "dense_forward": float(stage[3]),
                         "weight_evolution": float(stage[4]), "weight_gradient": float(stage[5]),
@@ -620,10 +622,12 @@ def main():
                  "lane_slots": n_lanes * window, "lane_fill": rows / max(1, n_lanes * window),
                  "pack_s": time.perf_counter() - t0}
 
+    dX = torch.empty_like(dw.X) if (evolve and args.with_dx) else None
+
     def step():
         layer.forward(dw.X, dw.C, dw.Y, C1=dw.C1, H0=dw.H0, stream=stream)
         if evolve:
-            layer.backward(dw.Y, target=target, loss_out=loss, stream=stream)
+            layer.backward(dw.Y, target=target, loss_out=loss, dX=dX, stream=stream)
 
     if args.calib_copy:
         scratch = torch.empty_like(dw.X)

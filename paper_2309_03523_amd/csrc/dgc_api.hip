@@ -62,6 +62,11 @@ struct dgc_layer {
   hipEvent_t evd[8] = {};                        // its stage boundaries: forward 0..3, backward 4..7
   bool evd_fwd = false, evd_bwd = false;
   TFusion tf{};                                  // temporal-fusion packing (dgc_layer_set_presence)
+  // input-gradient pass of EvolveGCN-O, allocated by the first backward that asks for dX
+  float* d_dM = nullptr;                         // [T*N][F] gradient of the aggregated rows
+  int64_t* d_rowidx = nullptr;                   // [total rows] packed row -> t*N + v
+  float4* d_Wt_plain = nullptr;                  // every W_t as (out = F, in = S) fragments
+  bool m_saved = false;                          // d_M holds the aggregated rows of the last forward
   unsigned long long* fs_mask = nullptr;         // loader bitmap and pair counters of dgc_layer_shared_rows,
   unsigned long long* fs_out = nullptr;          // allocated by its first call
   std::vector<ChunkInfo> cinfo_host;
@@ -605,6 +610,8 @@ SpmmArgs spmm_args(dgc_layer* L, const float* fresh, int64_t ld_fresh, const flo
   a.partial = L->d_partial;
   a.M = M; a.ldm = ldm;
   a.row_map = nullptr;
+  a.ld_out = 0;
+  a.skip_stale = false;
   return a;
 }
 
@@ -860,6 +867,7 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* L, const void* Xv, int64_t ldx, cons
   }
   DGC_HIP_TRY(hipGetLastError());
   L->forward_done = true;
+  L->m_saved = true;
   return DGC_OK;
 }
 
@@ -906,14 +914,14 @@ dgc_status_t dgc_layer_stage_times(dgc_layer_t* L, float* host_ms) {
 dgc_status_t dgc_layer_backward(dgc_layer_t* L, const void* Yv, int64_t ldy, const void* dYv, int64_t lddy,
                                 const void* targetv, int64_t ldt, float* loss_out, void* dX, int64_t lddx,
                                 void* stream) {
-  (void)lddx;
   if (!L) return DGC_ERR_INVALID_ARG;
   Failer fail{L};
   const dgc_layer_desc_t& d = L->desc;
   if (!L->forward_done) return fail(DGC_ERR_STATE, "backward before forward");
   if (d.struct_kind != DGC_STRUCT_EVOLVE_GCN_O && d.struct_kind != DGC_STRUCT_GAT)
     return fail(DGC_ERR_UNSUPPORTED, "backward is built for DGC_STRUCT_EVOLVE_GCN_O and DGC_STRUCT_GAT only");
-  if (dX) return fail(DGC_ERR_UNSUPPORTED, "input gradients are not built: dX must be NULL");
+  if (dX && d.struct_kind != DGC_STRUCT_EVOLVE_GCN_O)
+    return fail(DGC_ERR_UNSUPPORTED, "input gradients are built for DGC_STRUCT_EVOLVE_GCN_O only: dX must be NULL");
   if ((dYv != nullptr) == (targetv != nullptr))
     return fail(DGC_ERR_INVALID_ARG, "give exactly one of dY and target");
   dgc_status_t rc;
@@ -935,6 +943,8 @@ dgc_status_t dgc_layer_backward(dgc_layer_t* L, const void* Yv, int64_t ldy, con
   if ((rc = check_tensor(fail, "Y", Y, ldy, d.S, true)) != DGC_OK) return rc;
   if ((rc = check_tensor(fail, "dY", dY, lddy, d.S, false)) != DGC_OK) return rc;
   if ((rc = check_tensor(fail, "target", target, ldt, d.S, false)) != DGC_OK) return rc;
+  if ((rc = check_tensor(fail, "dX", static_cast<const float*>(dX), lddx, d.F, false)) != DGC_OK) return rc;
+  if (!L->m_saved) return fail(DGC_ERR_STATE, "the rows saved by forward were used up by a backward that computed dX: run forward again");
   hipStream_t st = static_cast<hipStream_t>(stream);
   EvolveBwdIn in{};
   in.chunks = L->d_chunks; in.N = L->N; in.M = L->d_M; in.ldm = L->ldm;
@@ -949,6 +959,40 @@ dgc_status_t dgc_layer_backward(dgc_layer_t* L, const void* Yv, int64_t ldy, con
   if (prof) { DGC_HIP_TRY(hipEventRecord(L->evx[3], st)); DGC_HIP_TRY(hipEventRecord(L->evx[4], st)); }
   evolve_backward_bptt(L->evo, st);
   if (prof) { DGC_HIP_TRY(hipEventRecord(L->evx[5], st)); L->evx_bwd = true; }
+  if (dX) {
+    // dX[t, j] = sum over the rows i of j's chunk that store j of (d_i d_j)^-1/2 dM[t, i],  dM = dP W_t^T:
+    // dP into the buffer of the aggregated rows (the weight gradient above was their last reader), the
+    // dense kernel with W_t as an (out = F, in = S) weight, then the aggregation kernels on dM with
+    // the neighbours outside the chunk range left out (the cache is a constant) and the adjacency's symmetry.
+    int64_t max_nv = 1;
+    int32_t max_w = 1;
+    for (const ChunkInfo& c : L->cinfo_host) { max_nv = std::max(max_nv, c.nv); max_w = std::max(max_w, c.w); }
+    if (!L->d_dM) {
+      DGC_HIP_TRY(dev_alloc(L, &L->d_dM, (int64_t)L->T * L->N * d.F));
+      DGC_HIP_TRY(dev_alloc(L, &L->d_rowidx, L->total_rows));
+      DGC_HIP_TRY(dev_alloc(L, &L->d_Wt_plain, (int64_t)L->T * packed_weight_elems(d.F, d.S) / 4));
+      evolve_row_index(L->d_chunks, L->n_chunks, max_nv, max_w, L->N, L->d_rowidx, st);
+    }
+    L->m_saved = false;
+    evolve_backward_dp(in, L->n_chunks, max_nv, max_w, d.S, L->d_M, L->ldm, st);
+    evolve_pack_weights_plain(L->evo, L->d_Wt_plain, st);
+    DenseArgs da{};
+    da.tiles = L->d_tiles; da.n_tiles = L->n_tiles; da.chunks = L->d_chunks;
+    da.tiles32 = L->d_tiles32; da.n_tiles32 = L->n_tiles32; da.variant = d.dense_kernel;
+    da.N = L->N; da.total_state_rows = L->total_state_rows;
+    da.M = L->d_M; da.ldm = L->ldm;
+    da.K0 = d.S; da.S = d.F; da.H = 0; da.act = DGC_ACT_NONE; da.time_kind = DGC_TIME_NONE;
+    da.Wg = L->d_Wt_plain; da.bg = L->d_zero_bias;
+    da.wg_step_bytes = (int32_t)(sizeof(float) * packed_weight_elems(d.F, d.S));
+    da.wg_bytes = (int64_t)L->T * da.wg_step_bytes;
+    da.Y = L->d_dM; da.ldy = d.F;
+    if (!launch_dense(da, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
+    SpmmArgs sa = spmm_args(L, L->d_dM, d.F, L->d_dM, d.F, d.F, static_cast<float*>(dX), d.F);
+    sa.ld_out = lddx;
+    sa.row_map = L->d_rowidx;
+    sa.skip_stale = true;
+    launch_spmm(sa, st);
+  }
   DGC_HIP_TRY(hipGetLastError());
   L->has_grads = true;
   return DGC_OK;

@@ -318,6 +318,55 @@ __global__ void k_loss_reduce(const float* loss_partial, int64_t n, float inv_co
 
 inline unsigned blocks_for(int64_t n) { return (unsigned)((n + 255) / 256); }
 
+// W_t [F][S] for all t -> fragment order of W_t itself as an (out = F, in = S) weight: the dense
+// kernel then computes dM = dP W_t^T
+__global__ void k_pack_weight_plain(const float* Wt, int32_t T, int32_t F, int32_t S, float4* packed) {
+  const int nkb = (S + 7) / 8;
+  const int64_t per = (int64_t)(F / 32) * nkb * 64;
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= per * T) return;
+  const int64_t t = idx / per, i = idx - t * per;
+  const int lane = (int)(i & 63);
+  const int64_t fr = i >> 6;
+  const int kb = (int)(fr % nkb), jb = (int)(fr / nkb);
+  const int out = jb * 32 + (lane & 31);      // row f of W_t
+  const int k0 = kb * 8 + (lane >> 5) * 4;    // column s of W_t
+  const float* W = Wt + t * (int64_t)F * S + (int64_t)out * S;
+  float v[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) v[q] = (k0 + q < S) ? W[k0 + q] : 0.f;
+  packed[idx] = make_float4(v[0], v[1], v[2], v[3]);
+}
+
+// dP of every covered row, written to the packed row of (chunk, snapshot, vertex); one thread per float4
+__global__ void k_ev_dp(EvolveBwdIn in, int32_t S, float inv_count2, float* dP, int64_t ldp) {
+  const ChunkInfo ch = in.chunks[blockIdx.z];
+  const int32_t s = blockIdx.y;
+  if (s >= ch.w) return;
+  const int64_t q = S / 4;
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= ch.nv * q) return;
+  const int64_t v = idx / q, c4 = idx - v * q;
+  const int64_t row = (int64_t)(ch.t_lo + s) * in.N + ch.v_lo + v;
+  const float4 y = *reinterpret_cast<const float4*>(in.Y + row * in.ldy + 4 * c4);
+  const float4 g = in.target ? *reinterpret_cast<const float4*>(in.target + row * in.ldt + 4 * c4)
+                             : *reinterpret_cast<const float4*>(in.dY + row * in.lddy + 4 * c4);
+  const float yy[4] = {y.x, y.y, y.z, y.w}, gg[4] = {g.x, g.y, g.z, g.w};
+  float o[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+    o[e] = yy[e] > 0.f ? (in.target ? (yy[e] - gg[e]) * inv_count2 : gg[e]) : 0.f;
+  *reinterpret_cast<float4*>(dP + (ch.row_off0 + (int64_t)s * ch.nv + v) * ldp + 4 * c4) = make_float4(o[0], o[1], o[2], o[3]);
+}
+
+__global__ void k_ev_row_index(const ChunkInfo* chunks, int64_t N, int64_t* idx) {
+  const ChunkInfo ch = chunks[blockIdx.z];
+  const int32_t s = blockIdx.y;
+  const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= ch.w || v >= ch.nv) return;
+  idx[ch.row_off0 + (int64_t)s * ch.nv + v] = (int64_t)(ch.t_lo + s) * N + ch.v_lo + v;
+}
+
 template <int EPI>
 void launch_mm(const EvJobs& jobs, int n_jobs, int n, hipStream_t st) {
   hipLaunchKernelGGL((k_ev_mm<EPI>), dim3(n / 16, n / 16, n_jobs), 256, 0, st, jobs, n);
@@ -351,6 +400,23 @@ void evolve_forward_weights(const EvolveWs& ws, hipStream_t st) {
   }
   const int64_t per = (int64_t)(ws.S / 32) * ((ws.F + 7) / 8) * 64;
   hipLaunchKernelGGL(k_pack_weight_t, blocks_for(per * ws.T), 256, 0, st, ws.Wt_f32, ws.T, ws.F, ws.S, ws.Wt_packed);
+}
+
+void evolve_backward_dp(const EvolveBwdIn& in, int32_t n_chunks, int64_t max_nv, int32_t max_w, int32_t S, float* dP,
+                        int64_t ldp, hipStream_t st) {
+  hipLaunchKernelGGL(k_ev_dp, dim3(blocks_for(max_nv * (S / 4)), (unsigned)max_w, (unsigned)n_chunks), 256, 0, st, in, S,
+                     2.0f / (float)in.count, dP, ldp);
+}
+
+void evolve_row_index(const ChunkInfo* chunks, int32_t n_chunks, int64_t max_nv, int32_t max_w, int64_t N, int64_t* idx,
+                      hipStream_t st) {
+  hipLaunchKernelGGL(k_ev_row_index, dim3(blocks_for(max_nv), (unsigned)max_w, (unsigned)n_chunks), 256, 0, st, chunks, N,
+                     idx);
+}
+
+void evolve_pack_weights_plain(const EvolveWs& ws, float4* packed, hipStream_t st) {
+  const int64_t per = (int64_t)(ws.F / 32) * ((ws.S + 7) / 8) * 64;
+  hipLaunchKernelGGL(k_pack_weight_plain, blocks_for(per * ws.T), 256, 0, st, ws.Wt_f32, ws.T, ws.F, ws.S, packed);
 }
 
 // dWd[t] for all t (and the loss), from the saved aggregated rows and the layer's output.

@@ -113,6 +113,8 @@ struct SpmmArgs {
   float* partial;             // [n_long][ldm] scratch for split rows
   float* M; int64_t ldm;      // [rows, ldm]; columns F..ldm-1 are written as zero
   const int64_t* row_map;     // nullptr, or [rows]: row of M that packed row r goes to (< 0: skip the row)
+  int64_t ld_out;             // pitch of the rows of M if it differs from the written width ldm (0 = ldm)
+  bool skip_stale;            // neighbours outside the row's chunk range contribute nothing
 };
 void launch_spmm(const SpmmArgs& a, hipStream_t st);
 void launch_gather(const Segment* segs, int64_t nseg, const int32_t* halo_idx, const int64_t* halo_ptr,
@@ -196,6 +198,13 @@ int64_t evolve_partial_elems(int32_t T, int32_t F, int32_t S);
 int64_t evolve_loss_partial_elems(int32_t T);
 void evolve_forward_weights(const EvolveWs& ws, hipStream_t st);
 bool evolve_backward_dw(const EvolveWs& ws, const EvolveBwdIn& in, hipStream_t st, std::string* why);
+// input-gradient pass: dP = dL/d(pre-activation) of every covered row into packed rows [rows][ldp];
+// the packed-row -> t*N + v table; every W_t as (out = F, in = S) fragments for dM = dP W_t^T
+void evolve_backward_dp(const EvolveBwdIn& in, int32_t n_chunks, int64_t max_nv, int32_t max_w, int32_t S, float* dP,
+                        int64_t ldp, hipStream_t st);
+void evolve_row_index(const ChunkInfo* chunks, int32_t n_chunks, int64_t max_nv, int32_t max_w, int64_t N, int64_t* idx,
+                      hipStream_t st);
+void evolve_pack_weights_plain(const EvolveWs& ws, float4* packed, hipStream_t st);
 void evolve_backward_bptt(const EvolveWs& ws, hipStream_t st);
 
 // ---- graph attention + temporal self-attention, bf16 (dgc_dysat.hip)

@@ -61,6 +61,7 @@ struct RowCtx {
   const float* fresh_t; int64_t ld_fresh;
   const float* stale_t; int64_t ld_stale;   // IN_PLACE: cache snapshot; STAGED: segment's halo rows
   int64_t v_lo, v_hi, e0;
+  bool skip_stale;          // neighbours outside the range contribute nothing (input-gradient pass)
 };
 
 // acc += sum over stored non-zeros e in [ea, eb) of dinv[col] * src row, features fi..fi+VEC-1.
@@ -93,8 +94,9 @@ __device__ __forceinline__ void accumulate_edges(const RowCtx& c, int64_t ea, in
             const int64_t nv = c.v_hi - c.v_lo;
             src = ll < nv ? c.fresh_t + (c.v_lo + ll) * c.ld_fresh : c.stale_t + (ll - nv) * c.ld_stale;
           } else {
-            src = (jj >= c.v_lo && jj < c.v_hi) ? c.fresh_t + (int64_t)jj * c.ld_fresh
-                                                : c.stale_t + (int64_t)jj * c.ld_stale;
+            const bool in = jj >= c.v_lo && jj < c.v_hi;   // wave-uniform
+            src = in ? c.fresh_t + (int64_t)jj * c.ld_fresh : c.stale_t + (int64_t)jj * c.ld_stale;
+            if (!in && c.skip_stale) { w[u] = 0.f; continue; }
           }
           if (active) vload<VEC>(v[u], src + fi);
         }
@@ -123,6 +125,7 @@ __device__ __forceinline__ RowCtx make_ctx(const SpmmArgs& a, const Segment& sg)
     c.ld_stale = a.ld_stale;
   }
   c.v_lo = sg.v_lo; c.v_hi = sg.v_hi; c.e0 = sg.e0;
+  c.skip_stale = a.skip_stale;
   return c;
 }
 
@@ -157,7 +160,7 @@ __global__ __launch_bounds__(256) void k_spmm_short(SpmmArgs a) {
     const int64_t orow = readlane64(my_map, r);
     if (orow < 0) continue;
     const float di = c.dinv_t[sg.v_lo + r0 + r];
-    float* out = a.M + orow * a.ldm;
+    float* out = a.M + orow * (a.ld_out ? a.ld_out : a.ldm);
     for (int f0 = 0; f0 < a.ldm; f0 += kWave * VEC) {
       const int fi = f0 + lane * VEC;
       float acc[VEC];
@@ -209,7 +212,7 @@ __global__ __launch_bounds__(256) void k_spmm_long_reduce(SpmmArgs a) {
   const float di = a.dinv[(int64_t)sg.t * a.g.N + sg.v_lo + row];
   const int64_t orow = a.row_map ? a.row_map[sg.row_off + row] : sg.row_off + row;
   if (orow < 0) return;
-  float* out = a.M + orow * a.ldm;
+  float* out = a.M + orow * (a.ld_out ? a.ld_out : a.ldm);
   for (int f0 = 0; f0 < a.ldm; f0 += kWave * VEC) {
     const int fi = f0 + lane * VEC;
     if (fi >= a.ldm) continue;

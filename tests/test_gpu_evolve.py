@@ -55,6 +55,42 @@ def test_evolve_forward_and_gradients(F, dense):
     dw.layer.destroy()
 
 
+@pytest.mark.parametrize("F,dense,pitch", [(32, "auto", 32), (64, "tile", 68), (128, "auto", 128), (256, "auto", 260)])
+def test_evolve_input_gradient(F, dense, pitch):
+    """dL/dX: through the rows of a row's own chunk only (the cache is a constant); rows outside
+    every chunk and the pitch padding stay untouched; the saved rows are used up by it."""
+    import torch
+    from paper_2309_03523_amd.binding import DgcError
+    T, N = 6, 150
+    chunks = [[0, 40, 0, 6], [40, 97, 0, 3], [40, 97, 3, 6], [97, 150, 1, 5]]
+    wl = _workload(500 + F, T, N, F, chunks)
+    target = synth.stream(F, "target").standard_normal((T, N, F)).astype(np.float32)
+    dw = _dw(wl, dense_kernel=dense, long_nnz=24, part_nnz=8)
+    Y = dw.forward()
+    want = oracle.evolve(wl.graph, wl.chunks, wl.params, wl.X, wl.C, target, want_grads=True, want_dx=True)
+    tgt = torch.from_numpy(target).cuda()
+    buf = torch.full((T, N, pitch), float("nan"), device="cuda")
+    dX = buf[:, :, :F]
+    dw.layer.backward(Y, target=tgt, dX=dX)
+    torch.cuda.synchronize()
+    got = dX.cpu().numpy()
+    covered = ~np.isnan(want["Y"]).any(axis=2)
+    assert np.isnan(got[~covered]).all() and not np.isnan(got[covered]).any()
+    assert np.isnan(buf[:, :, F:].cpu().numpy()).all()
+    e = rel_err(got[covered], want["dX"][covered])
+    print(f"F={F} {dense}: dX rel_err {e:.3e}, max |dX| {np.abs(want['dX']).max():.3e}", flush=True)
+    assert e < TOL and np.abs(want["dX"][covered]).max() > 0
+    for name in oracle.EVOLVE_PARAMS:      # the parameter gradients of the same call are unaffected
+        g = dw.layer.get_param(name + ".grad", wl.params[name].shape)
+        assert rel_err(g, want["grads"][name]) < TOL, name
+    with pytest.raises(DgcError, match="forward again"):
+        dw.layer.backward(Y, target=tgt)
+    dw.forward()
+    dw.layer.backward(Y, target=tgt)         # fine again after a forward
+    torch.cuda.synchronize()
+    dw.layer.destroy()
+
+
 @pytest.mark.parametrize("F", [64, 256])
 def test_evolve_long_recurrence(F):
     """64 snapshots: the weight recurrence and its back-propagation run the full length of the
@@ -99,9 +135,9 @@ def test_evolve_argument_errors():
     with pytest.raises(DgcError) as ei:
         dw.layer.backward(Y, target=Y, dY=Y)
     assert ei.value.code == 1
-    with pytest.raises(DgcError) as ei:
-        dw.layer.backward(Y, target=Y, dX=torch.zeros_like(dw.X))
-    assert ei.value.code == 4
+    with pytest.raises(DgcError) as ei:      # dX with a pitch that is not a multiple of 4 floats
+        dw.layer.backward(Y, target=Y, dX=torch.zeros(dw.X.shape[0], dw.X.shape[1], 34, device="cuda")[:, :, :32])
+    assert ei.value.code == 1
     with pytest.raises(DgcError) as ei:
         dw.layer.set_param("evolve.U_z.grad", np.zeros((32, 32), np.float32))
     assert ei.value.code == 1
