@@ -1,0 +1,70 @@
+"""Seeded random small shapes through the graph-attention + temporal self-attention layer (forward
+and all parameter gradients) against the oracle: tiny vertex counts, windows of 1 to 16 snapshots,
+one-vertex chunks, gaps in the coverage, split rows."""
+import numpy as np
+import pytest
+
+from oracle import dysat
+from paper_2309_03523_amd import synth
+from refs import rel_err
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-2
+
+
+def _random_chunks(rng, N, T):
+    cuts = sorted(set([0, N] + rng.integers(0, N + 1, size=rng.integers(0, 3)).tolist()))
+    chunks = []
+    for a, b in zip(cuts, cuts[1:]):
+        tcuts = sorted(set([0, T] + rng.integers(0, T + 1, size=rng.integers(0, 2)).tolist()))
+        for t0, t1 in zip(tcuts, tcuts[1:]):
+            if rng.random() < 0.85:
+                chunks.append([a, b, t0, t1])
+    if not chunks:
+        chunks = [[0, N, 0, T]]
+    return [chunks[k] for k in rng.permutation(len(chunks))]
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shape(seed):
+    import torch
+    from paper_2309_03523_amd.runner import DysatDevice
+    rng = np.random.default_rng(3000 + seed)
+    N = int(rng.choice([1, 2, 3, 31, 33, 64, 90]))
+    T = int(rng.choice([1, 2, 5, 16]))
+    chunks = _random_chunks(rng, N, T)
+    wl = synth.dysat_small(4000 + seed, T, N, 128, 8, float(rng.choice([0.0, 2.0, 7.0])), chunks,
+                           hub=bool(rng.integers(0, 2)))
+    kw = {}
+    if rng.random() < 0.5:
+        kw = dict(long_nnz=int(rng.choice([4, 16])), part_nnz=int(rng.choice([3, 8])))
+    dd = DysatDevice(wl, validate_level=1, **kw)
+    cov = np.zeros((T, N), bool)
+    for v_lo, v_hi, t_lo, t_hi in wl.chunks.tolist():
+        cov[t_lo:t_hi, v_lo:v_hi] = True
+    got = dd.forward().float().cpu().numpy()
+    want = dysat.forward(wl.graph, wl.chunks, wl.params, wl.X, wl.C, 8)["Y"]
+    e = rel_err(got[cov], want[cov], floor=1.0)
+    assert np.isnan(got[~cov]).all()
+    extra = synth.round_bf16(synth.stream(seed, "extra").standard_normal(wl.X.shape).astype(np.float32))
+    wg = dysat.gradients(wl.graph, wl.chunks, wl.params, wl.X, wl.C, 8, target=extra)
+    grads, loss = dd.backward(target=torch.from_numpy(extra).cuda().to(torch.bfloat16))
+    # a gradient that is identically zero (one neighbour per row: the edge softmax is 1 whatever the logits;
+    # one step per window: the same for the temporal softmax) has no scale of its own: measure it
+    # against the largest gradient of the layer
+    scale = max(float(np.abs(v).max()) for v in wg["grads"].values())
+    errs = {}
+    for name in dysat.PARAMS:
+        w = wg["grads"][name]
+        errs[name] = (rel_err(grads[name], w, floor=1.0) if np.abs(w).max() > 0
+                      else float(np.abs(grads[name]).max()) / scale)
+    print(f"seed {seed}: N={N} T={T} chunks={len(chunks)} rows={int(cov.sum())} {kw}: Y {e:.2e}, grads "
+          f"{max(errs.values()):.2e}", flush=True)
+    assert e < TOL
+    assert abs(loss - wg["loss"]) < 2e-3 * wg["loss"]
+    # gradients that are sums over very few rows see the stored bf16 gradients' rounding unaveraged
+    tol = TOL if cov.sum() >= 64 else 2 * TOL
+    for name, v in errs.items():
+        assert v < tol, (name, v)
+    dd.layer.destroy()
