@@ -75,17 +75,18 @@ void tf_fill(const uint8_t* present, const ChunkInfo* chunks, int32_t n_chunks, 
              const int32_t* seq_lane, const int32_t* seq_off, int64_t n_lanes, int32_t Lmax, const ChunkInfo* chunks_v,
              int64_t total_rows, int64_t* slot_row, int64_t* row_map, uint8_t* slot_reset, hipStream_t st) {
   const int64_t n = (int64_t)Lmax * n_lanes;
-  hipLaunchKernelGGL(k_tf_fill_i64, nblocks(n, 256), 256, 0, st, slot_row, (int64_t)-1, n);
+  if (n > 0) hipLaunchKernelGGL(k_tf_fill_i64, nblocks(n, 256), 256, 0, st, slot_row, (int64_t)-1, n);   // no lanes: nobody present
   hipLaunchKernelGGL(k_tf_fill_i64, nblocks(total_rows, 256), 256, 0, st, row_map, (int64_t)-1, total_rows);
-  (void)hipMemsetAsync(slot_reset, 0, (size_t)n, st);
+  if (n > 0) (void)hipMemsetAsync(slot_reset, 0, (size_t)n, st);
   hipLaunchKernelGGL(k_tf_fill, dim3(nblocks(max_nv, 256), n_chunks), 256, 0, st, present, chunks, N, seq_lane, seq_off,
                      n_lanes, chunks_v, slot_row, row_map, slot_reset);
 }
 
 void tf_scatter(const float* Yv, int32_t out_dim, const int64_t* slot_row, int64_t n_slots, float* Y, int64_t ldy,
                 hipStream_t st) {
-  hipLaunchKernelGGL(k_tf_scatter, nblocks(n_slots * (out_dim / 4), 256), 256, 0, st, Yv, out_dim, slot_row, n_slots, Y,
-                     ldy);
+  if (n_slots > 0)
+    hipLaunchKernelGGL(k_tf_scatter, nblocks(n_slots * (out_dim / 4), 256), 256, 0, st, Yv, out_dim, slot_row, n_slots, Y,
+                       ldy);
 }
 
 }  // namespace dgc

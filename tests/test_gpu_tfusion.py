@@ -70,3 +70,45 @@ def test_temporal_fusion_errors():
         dw2.layer.packing("slot_row")
     assert ei.value.code == 7
     dw2.layer.destroy()
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_temporal_fusion_random_shapes(seed):
+    """Random chunk sets and presence patterns: nobody present, everybody present, tiny vertex
+    counts, windows of one snapshot, gaps in the coverage."""
+    import torch
+    from paper_2309_03523_amd.runner import DeviceWorkload
+    rng = np.random.default_rng(5000 + seed)
+    N = int(rng.choice([1, 2, 7, 33, 64, 100]))
+    T = int(rng.integers(1, 7))
+    cuts = sorted(set([0, N] + rng.integers(0, N + 1, size=rng.integers(0, 3)).tolist()))
+    chunks = []
+    for a, b in zip(cuts, cuts[1:]):
+        tcuts = sorted(set([0, T] + rng.integers(0, T + 1, size=rng.integers(0, 3)).tolist()))
+        chunks += [[a, b, t0, t1] for t0, t1 in zip(tcuts, tcuts[1:]) if rng.random() < 0.85]
+    if not chunks:
+        chunks = [[0, N, 0, T]]
+    kind = str(rng.choice(["gru", "lstm"]))
+    S = int(rng.choice([32, 64]))
+    layers = int(rng.choice([1, 2]))
+    wl = synth.random_small(6000 + seed, T, N, 5, S, S, 3.0, chunks, kind, n_struct_layers=layers)
+    p_lo, p_hi = [(0.0, 0.0), (1.0, 1.0), (0.1, 1.0), (0.0, 0.6)][seed % 4]
+    present = synth.presence(seed, T, N, p_lo, p_hi)
+    dw = DeviceWorkload(wl, dense_kernel=str(rng.choice(["auto", "tile"])))
+    dw.layer.set_presence(torch.from_numpy(present).cuda())
+    want_pack = tfusion.pack(present, wl.chunks)
+    np.testing.assert_array_equal(dw.layer.packing("lane_ptr"), want_pack["lane_ptr"])
+    np.testing.assert_array_equal(dw.layer.packing("slot_row").reshape(want_pack["slot_row"].shape), want_pack["slot_row"])
+    np.testing.assert_array_equal(dw.layer.packing("slot_reset").reshape(want_pack["slot_reset"].shape),
+                                  want_pack["slot_reset"])
+    Y = dw.forward(use_h0=False).cpu().numpy()
+    Z = oracle.forward(wl.graph, wl.chunks, wl.params, wl.X, wl.C, time_kind="none", n_struct_layers=layers,
+                       C1=wl.C1, act_hidden="relu", act_out="none").astype(np.float64)
+    want = tfusion.run_separate(np.nan_to_num(Z), present, wl.chunks, wl.params, kind)
+    m = ~np.isnan(want)
+    print(f"seed {seed}: N={N} T={T} chunks={len(chunks)} {kind} S={S} layers={layers} p=({p_lo},{p_hi}) "
+          f"present rows {int(m.any(axis=2).sum())}, lanes {want_pack['slot_row'].shape[1]}", flush=True)
+    if m.any():
+        assert rel_err(Y[m], want[m]) < TOL
+    assert np.isnan(Y[~m.any(axis=2)]).all()
+    dw.layer.destroy()
