@@ -32,6 +32,10 @@ CASES = {
     "cap_one_nothing_moves": dict(g=lambda: _graph(10, 2, 150, 4.0, False), w=(1, 1), cap=1, iters=500),
     "stopped_early": dict(g=lambda: _graph(11, 4, 500, 6.0, True), w=(2, 1), cap=100, iters=3),
     "single_snapshot": dict(g=lambda: _graph(12, 1, 700, 8.0, True), w=(1, 1), cap=10 ** 9, iters=500),
+    "one_vertex_one_snapshot": dict(g=lambda: _graph(13, 1, 1, 0.0, False), w=(1, 1), cap=5, iters=10),
+    "one_vertex_over_time": dict(g=lambda: _graph(14, 6, 1, 0.0, False), w=(1, 2), cap=4, iters=50),
+    "no_edges": dict(g=lambda: _graph(15, 3, 40, 0.0, False), w=(3, 1), cap=10 ** 9, iters=50),
+    "row_of_exactly_32_and_33": dict(g=lambda: _graph(16, 2, 34, 40.0, False), w=(1, 1), cap=10 ** 9, iters=200),
 }
 
 

@@ -25,6 +25,10 @@ CASES = {
     "130_chunks_global_counters": lambda: synth.random_small(7, 2, 260, 8, 32, 32, 5.0, _strips(260, 2, 2), "gru"),
     "single_chunk": lambda: synth.random_small(8, 2, 100, 8, 32, 32, 5.0, [[0, 100, 0, 2]], "gru"),
     "partial_cover": lambda: synth.random_small(9, 4, 200, 8, 32, 32, 5.0, [[10, 60, 1, 3], [100, 180, 0, 4]], "gru"),
+    "one_vertex_chunks": lambda: synth.random_small(10, 2, 5, 8, 32, 32, 3.0, _strips(5, 2, 1), "gru", hub=True),
+    "no_edges": lambda: synth.random_small(11, 3, 50, 8, 32, 32, 0.0, _strips(50, 3, 10), "gru"),
+    "exactly_128_chunks": lambda: synth.random_small(12, 1, 256, 8, 32, 32, 6.0, _strips(256, 1, 2), "gru", hub=True),
+    "129_chunks": lambda: synth.random_small(13, 1, 258, 8, 32, 32, 6.0, _strips(258, 1, 2), "gru", hub=True),
 }
 
 

@@ -77,6 +77,9 @@ CASES = {
     "f300_two_sweeps": dict(R=700, F=300, ld=300, frac=None, factor=0.5),
     "f16_small": dict(R=70, F=16, ld=16, frac=None, factor=0.1),
     "theta_zero": dict(R=3000, F=64, ld=64, frac=None, theta=0.0),
+    "one_row_one_column": dict(R=1, F=1, ld=4, frac=None, factor=0.5),
+    "two_rows_bf16": dict(R=2, F=3, ld=8, frac=None, theta=0.0, bf16=True),
+    "widest": dict(R=40, F=4096, ld=4096, frac=None, factor=0.3),
     "bf16_f128": dict(R=5000, F=128, ld=128, frac=None, factor=0.3, bf16=True),
     "bf16_f100_subset_tail": dict(R=3000, F=100, ld=104, frac=0.4, theta=0.8, bf16=True),
     "bf16_f520_two_sweeps": dict(R=600, F=520, ld=520, frac=None, factor=0.5, bf16=True),
