@@ -147,3 +147,41 @@ def test_evolve_argument_errors():
         wl2 = synth.random_small(6, 2, 40, 64, 32, 32, 3.0, [[0, 40, 0, 2]], "none")
         DeviceWorkload(wl2, struct_kind="evolve_gcn_o", act_out="relu")
     assert ei.value.code == 1
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_evolve_random_shapes(seed):
+    """Tiny vertex counts, one snapshot, gaps in the coverage: forward, loss, parameter and input gradients."""
+    import torch
+    rng = np.random.default_rng(7000 + seed)
+    N = int(rng.choice([1, 2, 3, 33, 70]))
+    T = int(rng.integers(1, 6))
+    F = int(rng.choice([32, 64]))
+    cuts = sorted(set([0, N] + rng.integers(0, N + 1, size=rng.integers(0, 3)).tolist()))
+    chunks = []
+    for a, b in zip(cuts, cuts[1:]):
+        tcuts = sorted(set([0, T] + rng.integers(0, T + 1, size=rng.integers(0, 3)).tolist()))
+        chunks += [[a, b, t0, t1] for t0, t1 in zip(tcuts, tcuts[1:]) if rng.random() < 0.85]
+    if not chunks:
+        chunks = [[0, N, 0, T]]
+    wl = _workload(8000 + seed, T, N, F, chunks, deg=float(rng.choice([0.0, 2.0, 5.0])))
+    target = synth.stream(seed, "target").standard_normal((T, N, F)).astype(np.float32)
+    dw = _dw(wl, dense_kernel=str(rng.choice(["auto", "tile"])))
+    Y = dw.forward()
+    want = oracle.evolve(wl.graph, wl.chunks, wl.params, wl.X, wl.C, target, want_grads=True, want_dx=True)
+    covered = ~np.isnan(want["Y"]).any(axis=2)
+    got = Y.cpu().numpy()
+    assert rel_err(got[covered], want["Y"][covered]) < TOL and np.isnan(got[~covered]).all()
+    loss = torch.zeros(1, device="cuda")
+    dX = torch.full((T, N, F), float("nan"), device="cuda")
+    dw.layer.backward(Y, target=torch.from_numpy(target).cuda(), loss_out=loss, dX=dX)
+    torch.cuda.synchronize()
+    assert abs(loss.item() - want["loss"]) < 1e-5 * want["loss"]
+    gx = dX.cpu().numpy()
+    e = rel_err(gx[covered], want["dX"][covered])
+    print(f"seed {seed}: N={N} T={T} F={F} chunks={len(chunks)} rows={int(covered.sum())}: dX {e:.2e}", flush=True)
+    assert e < TOL and np.isnan(gx[~covered]).all()
+    for name in oracle.EVOLVE_PARAMS:
+        g = dw.layer.get_param(name + ".grad", wl.params[name].shape)
+        assert rel_err(g, want["grads"][name]) < TOL, name
+    dw.layer.destroy()
