@@ -105,9 +105,10 @@ def evolve_report(args, wl, desc, dw, rows, value, ms_per_step, stage, t_gen, t_
                             "achieved": bwd_flops / (stage[5] * 1e-3) / 1e12, "peak": PEAK_FP32_MFMA_TFLOPS,
                             "unit": "TFLOP/s", "ms_per_launch": float(stage[5])},
     }
-    for k in kernels.values():
+    traffic = measured_traffic(args.workload, args.gather_mode)
+    for name, k in kernels.items():
         k["frac"] = k["achieved"] / k["peak"]
-        k["traffic"] = None
+        k["traffic"] = traffic.get(name)
     dom = max(kernels.values(), key=lambda k: k["ms_per_launch"])
     out = {"metric": "snapshot-vertex embeddings/s per DGNN layer", "value": value, "unit": "embeddings/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
