@@ -15,7 +15,12 @@ Definitions used here (the paper gives the idea and the mask equation, not a pac
     the chunk's window; a sequence occupies consecutive slots.  Lanes are numbered chunk after
     chunk in order of creation.
   * The first slot of every sequence carries a reset flag: the state entering that step is zero
-    (the mask of the paper's update-gate equation, applied wherever the incoming state appears).
+    (the mask of the paper's update-gate equation, applied wherever the incoming state appears),
+    or, if initial states are given, the state row of that (chunk, vertex): H0 / HN hold one row per
+    (chunk, vertex) in chunk order (for an LSTM the cell rows follow all hidden rows), as without
+    fusion.  HN receives the state after the vertex's last present snapshot of the window; a vertex
+    that is absent throughout keeps its state (HN row = H0 row).  Chained windows then equal one
+    long window.
 """
 from __future__ import annotations
 
@@ -93,28 +98,47 @@ def lstm_step(P, x, h, c):
     return o * np.tanh(c), c
 
 
-def run_separate(Z: np.ndarray, present: np.ndarray, chunks, params: dict, time_kind: str) -> np.ndarray:
+def state_rows(chunks) -> np.ndarray:
+    """First state row of every chunk (rows are (chunk, vertex) in chunk order) and the total."""
+    ch = np.asarray(chunks, np.int64).reshape(-1, 4)
+    return np.concatenate([[0], np.cumsum(ch[:, 1] - ch[:, 0])])
+
+
+def run_separate(Z: np.ndarray, present: np.ndarray, chunks, params: dict, time_kind: str, H0=None,
+                 return_state: bool = False):
     """Time encoder over every vertex's own sequence, one chunk and one vertex at a time.
-    Z [T,N,S] float64: structure-encoder output.  Returns Y [T,N,H], NaN where nothing is computed."""
+    Z [T,N,S] float64: structure-encoder output.  Returns Y [T,N,H], NaN where nothing is computed
+    (and, with return_state, HN laid out like H0)."""
     T, N, _ = Z.shape
     H = params["rnn.weight_hh"].shape[1]
     Y = np.full((T, N, H), np.nan)
-    for seqs in sequences(present, chunks):
+    ch = np.asarray(chunks, np.int64).reshape(-1, 4)
+    off = state_rows(ch)
+    V = int(off[-1])
+    n_state = 2 if time_kind == "lstm" else 1
+    HN = np.zeros((n_state * V, H)) if H0 is None else np.array(H0, np.float64, copy=True)
+    for k, seqs in enumerate(sequences(present, ch)):
         for i, ts in seqs:
-            h = np.zeros((1, H))
-            c = np.zeros((1, H))
+            row = int(off[k] + i - ch[k, 0])
+            h = HN[row][None].copy()
+            c = HN[V + row][None].copy() if time_kind == "lstm" else np.zeros((1, H))
             for t in ts:
                 if time_kind == "gru":
                     h = gru_step(params, Z[t, i][None], h)
                 else:
                     h, c = lstm_step(params, Z[t, i][None], h, c)
                 Y[t, i] = h[0]
-    return Y
+            HN[row] = h[0]
+            if time_kind == "lstm":
+                HN[V + row] = c[0]
+    return (Y, HN) if return_state else Y
 
 
-def run_lanes(Z: np.ndarray, packing: dict, params: dict, time_kind: str) -> np.ndarray:
-    """The same over the packed lanes: all lanes step together, slot by slot; the reset flag
-    zeroes the incoming state (the paper's mask).  Results are scattered back to [T,N,H]."""
+def run_lanes(Z: np.ndarray, packing: dict, params: dict, time_kind: str, chunks=None, H0=None,
+              return_state: bool = False):
+    """The same over the packed lanes: all lanes step together, slot by slot; on a reset flag the
+    incoming state is replaced (the paper's mask) by zero or, with H0, by the state row of the
+    sequence that starts there (needs `chunks` to find it).  Results are scattered back to [T,N,H]."""
     T, N, S = Z.shape
     H = params["rnn.weight_hh"].shape[1]
     slot_row, slot_reset = packing["slot_row"], packing["slot_reset"]
@@ -123,13 +147,39 @@ def run_lanes(Z: np.ndarray, packing: dict, params: dict, time_kind: str) -> np.
     Y = np.full((T * N, H), np.nan)
     h = np.zeros((n_lanes, H))
     c = np.zeros((n_lanes, H))
+    srow = None
+    if chunks is not None:     # state row of the sequence that occupies each slot
+        ch = np.asarray(chunks, np.int64).reshape(-1, 4)
+        off = state_rows(ch)
+        V = int(off[-1])
+        lane_chunk = np.searchsorted(packing["lane_ptr"], np.arange(n_lanes), side="right") - 1
+        srow = np.full((L, n_lanes), -1, np.int64)
+        for lane in range(n_lanes):
+            k = lane_chunk[lane]
+            for s in range(L):
+                if slot_row[s, lane] >= 0:
+                    srow[s, lane] = off[k] + slot_row[s, lane] % N - ch[k, 0]
+        n_state = 2 if time_kind == "lstm" else 1
+        HN = np.zeros((n_state * V, H)) if H0 is None else np.array(H0, np.float64, copy=True)
     for s in range(L):
         live = slot_row[s] >= 0
-        keep = (1.0 - slot_reset[s].astype(np.float64))[:, None]
+        start = slot_reset[s].astype(bool)
+        if srow is not None and H0 is not None:
+            h[start] = np.asarray(H0, np.float64)[srow[s][start]]
+            if time_kind == "lstm":
+                c[start] = np.asarray(H0, np.float64)[V + srow[s][start]]
+        else:
+            h[start] = 0.0
+            c[start] = 0.0
         x = np.where(live[:, None], Zf[np.maximum(slot_row[s], 0)], 0.0)
         if time_kind == "gru":
-            h = gru_step(params, x, h * keep)
+            h = gru_step(params, x, h)
         else:
-            h, c = lstm_step(params, x, h * keep, c * keep)
+            h, c = lstm_step(params, x, h, c)
         Y[slot_row[s][live]] = h[live]
-    return Y.reshape(T, N, H)
+        if srow is not None:   # the latest state of every sequence; the last write is its final state
+            HN[srow[s][live]] = h[live]
+            if time_kind == "lstm":
+                HN[V + srow[s][live]] = c[live]
+    Y = Y.reshape(T, N, H)
+    return (Y, HN) if (return_state and srow is not None) else Y

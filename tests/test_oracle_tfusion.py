@@ -120,3 +120,68 @@ def test_concatenated_with_mask_equals_separate(kind):
     leaky = tfusion.run_lanes(Z, dict(packing, slot_reset=np.zeros_like(packing["slot_reset"])), P, kind)
     m = ~np.isnan(sep)
     assert np.abs(leaky[m] - sep[m]).max() > 1e-2
+
+
+@pytest.mark.parametrize("kind", ["gru", "lstm"])
+def test_chained_windows_with_state_equal_one_long_window(kind):
+    # two windows over the same vertices, the second started from the first one's final states:
+    # every vertex then sees one sequence over both windows, whatever its gaps
+    T, N, S, H = 8, 40, 5, 4
+    present = synth.presence(6, T, N, 0.0, 1.0)
+    present[:, 3] = 0                        # absent throughout
+    present[:4, 5] = 0                       # absent in the first window only
+    present[4:, 7] = 0                       # absent in the second window only
+    P = _params(kind, S, H)
+    Z = np.random.default_rng(2).standard_normal((T, N, S))
+    whole = [[0, N, 0, T]]
+    first, second = [[0, N, 0, 4]], [[0, N, 4, T]]
+    n_state = 2 if kind == "lstm" else 1
+    H0 = 0.3 * np.random.default_rng(3).standard_normal((n_state * N, H))
+    Yw, HNw = tfusion.run_separate(Z, present, whole, P, kind, H0=H0, return_state=True)
+    Y1, HN1 = tfusion.run_separate(Z, present, first, P, kind, H0=H0, return_state=True)
+    Y2, HN2 = tfusion.run_separate(Z, present, second, P, kind, H0=HN1, return_state=True)
+    np.testing.assert_allclose(np.where(np.isnan(Y1), Y2, Y1), Yw, atol=1e-13, equal_nan=True)
+    np.testing.assert_allclose(HN2, HNw, atol=1e-13)
+    np.testing.assert_array_equal(HNw[3], H0[3])                     # never present: state untouched
+    np.testing.assert_array_equal(HN1[5], H0[5])                     # absent in the first window: carried through
+    np.testing.assert_array_equal(HN2[7], HN1[7])
+    assert np.abs(HNw[0] - H0[0]).max() > 1e-3
+    # the initial state matters, and the library recurrence started from it agrees
+    Y0 = tfusion.run_separate(Z, present, whole, P, kind)
+    m = ~np.isnan(Yw)
+    assert np.abs(Y0[m] - Yw[m]).max() > 1e-3
+    rnn = (torch.nn.GRU if kind == "gru" else torch.nn.LSTM)(S, H).double()
+    with torch.no_grad():
+        rnn.weight_ih_l0.copy_(torch.from_numpy(P["rnn.weight_ih"]))
+        rnn.weight_hh_l0.copy_(torch.from_numpy(P["rnn.weight_hh"]))
+        rnn.bias_ih_l0.copy_(torch.from_numpy(P["rnn.bias_ih"]))
+        rnn.bias_hh_l0.copy_(torch.from_numpy(P["rnn.bias_hh"]))
+        for i in (0, 5, 7, 11):
+            ts = [t for t in range(T) if present[t, i]]
+            if not ts:
+                continue
+            h0 = torch.from_numpy(H0[i])[None, None]
+            st = h0 if kind == "gru" else (h0, torch.from_numpy(H0[N + i])[None, None])
+            out, fin = rnn(torch.from_numpy(Z[ts, i])[:, None, :], st)
+            np.testing.assert_allclose(Yw[ts, i], out[:, 0].numpy(), atol=1e-12)
+            np.testing.assert_allclose(HNw[i], (fin if kind == "gru" else fin[0])[0, 0].numpy(), atol=1e-12)
+            if kind == "lstm":
+                np.testing.assert_allclose(HNw[N + i], fin[1][0, 0].numpy(), atol=1e-12)
+
+
+@pytest.mark.parametrize("kind", ["gru", "lstm"])
+def test_lanes_with_state_equal_separate(kind):
+    T, N, S, H = 8, 61, 5, 4
+    present = synth.presence(7, T, N, 0.0, 1.0)
+    P = _params(kind, S, H)
+    Z = np.random.default_rng(4).standard_normal((T, N, S))
+    V = sum(c[1] - c[0] for c in CHUNKS)
+    H0 = 0.3 * np.random.default_rng(5).standard_normal(((2 if kind == "lstm" else 1) * V, H))
+    Ys, HNs = tfusion.run_separate(Z, present, CHUNKS, P, kind, H0=H0, return_state=True)
+    Yl, HNl = tfusion.run_lanes(Z, tfusion.pack(present, CHUNKS), P, kind, chunks=CHUNKS, H0=H0, return_state=True)
+    np.testing.assert_allclose(Yl, Ys, atol=1e-13, equal_nan=True)
+    np.testing.assert_allclose(HNl, HNs, atol=1e-13)
+    # without H0 the lane run with chunks still returns the final states of zero-started sequences
+    Y0, HN0 = tfusion.run_lanes(Z, tfusion.pack(present, CHUNKS), P, kind, chunks=CHUNKS, return_state=True)
+    Yz, HNz = tfusion.run_separate(Z, present, CHUNKS, P, kind, return_state=True)
+    np.testing.assert_allclose(HN0, HNz, atol=1e-13)
