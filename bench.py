@@ -51,10 +51,10 @@ def make_workload(name: str, seed: int):
         return synth.config2(seed, scale=0.05), "config2 at 1/20 scale"
     if name == "config2tf":
         wl = synth.config2(seed)
-        wl.H0 = None      # fused sequences start from a zero state
         wl.notes["present"] = synth.presence(seed, wl.graph.T, wl.graph.N)
         return wl, ("config2 with temporal fusion: every vertex present in a snapshot with its own probability "
-                    "U(0.15, 1); sequences concatenated into lanes of 8 (first-fit decreasing) instead of padded")
+                    "U(0.15, 1); sequences concatenated into lanes of 8 (first-fit decreasing) instead of padded, each "
+                    "starting from its own row of H0 as in config2")
     if name == "config3w":
         return synth.config3(seed, scale=0.125), ("config3 at 1/8 of its vertex count, one 32-snapshot window: 250k "
                                                   "vertices, 2 GCN layers (172->128->128) + LSTM, 64 uneven ranges")
@@ -320,7 +320,8 @@ def cpu_baseline_tfusion(wl, Y_gpu, seed: int) -> dict:
     mask = np.zeros(present.shape, np.uint8)
     for c, s in zip(wl.chunks, sub):
         mask[c[2]:c[3], s] = present[c[2]:c[3], s]
-    want = tfusion.run_separate(np.nan_to_num(Z).astype(np.float64), mask, wl.chunks, wl.params, wl.time_kind)
+    H0 = None if wl.H0 is None else wl.H0.astype(np.float64)
+    want = tfusion.run_separate(np.nan_to_num(Z).astype(np.float64), mask, wl.chunks, wl.params, wl.time_kind, H0=H0)
     dt = time.perf_counter() - t0
     m = ~np.isnan(want)
     w = want[m]

@@ -174,10 +174,14 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* layer, const void* X, int64_t ldx, c
  * the sequences of a chunk are concatenated into lanes as long as the window (first-fit
  * decreasing: sequences by length descending then vertex ascending, each into the first lane in
  * order of creation with room for all of it) and the first slot of every sequence carries a reset
- * flag (the paper's mask: the state entering that step is zero).  After this call
- * dgc_layer_forward runs the time encoder over the lanes: Y is written only for present rows of
- * the chunks, a vertex's state is carried over the snapshots it is absent from, and H0, HN and
- * reset_mask must be NULL.  For DGC_STRUCT_GCN with DGC_TIME_GRU / DGC_TIME_LSTM; can be called
+ * flag (the paper's mask: the previous sequence's state does not enter that step).  After this
+ * call dgc_layer_forward runs the time encoder over the lanes: Y is written only for present rows
+ * of the chunks and a vertex's state is carried over the snapshots it is absent from.  H0 and HN
+ * keep the layout they have without fusion (one row per (chunk, vertex)): a sequence starts from
+ * its row of H0 (zero if H0 is NULL), HN receives the state after the vertex's last present
+ * snapshot of the window, and a vertex that is absent throughout the window keeps its state
+ * (HN row = H0 row), so chained windows equal one long window.  reset_mask must be NULL
+ * (DGC_ERR_INVALID_ARG).  For DGC_STRUCT_GCN with DGC_TIME_GRU / DGC_TIME_LSTM; can be called
  * once per layer (DGC_ERR_STATE otherwise); `present` is only read during the call.
  * Synchronises `stream`. */
 dgc_status_t dgc_layer_set_presence(dgc_layer_t* layer, const uint8_t* present, void* stream);

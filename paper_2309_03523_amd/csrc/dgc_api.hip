@@ -853,11 +853,15 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* L, const void* Xv, int64_t ldx, cons
     // temporal fusion: the dense + recurrent kernels over the lanes of every chunk with the
     // packing's reset flags, outputs back to their (snapshot, vertex) rows
     const TFusion& tf = L->tf;
-    if (H0 || HN || reset_mask)
-      return fail(DGC_ERR_INVALID_ARG, "with temporal fusion H0, HN and reset_mask must be NULL");
+    if (reset_mask) return fail(DGC_ERR_INVALID_ARG, "with temporal fusion reset_mask must be NULL");
     da.tiles = tf.tiles_v; da.n_tiles = tf.n_tiles_v; da.tiles32 = tf.tiles32_v; da.n_tiles32 = tf.n_tiles32_v;
-    da.chunks = tf.chunks_v; da.N = tf.n_lanes; da.total_state_rows = tf.n_lanes;
-    da.M = tf.Mv; da.reset_mask = tf.slot_reset; da.Y = tf.Yv; da.ldy = out_dim;
+    da.chunks = tf.chunks_v; da.N = tf.n_lanes;
+    da.M = tf.Mv; da.Y = tf.Yv; da.ldy = out_dim;
+    // every sequence starts from its own row of H0 (zero without H0) and leaves its final state in its
+    // row of HN: the states travel through the slot tables; H0 / HN keep the layout they have without fusion
+    da.reset_mask = nullptr; da.seq_in = tf.seq_in; da.seq_out = tf.seq_out;
+    da.total_state_rows = L->total_state_rows;
+    if (HN) tf_carry(tf.seq_len, L->total_state_rows, d.time_kind == DGC_TIME_LSTM ? 2 : 1, d.H, H0, HN, st);
     if (tf.n_lanes > 0 && !launch_dense(da, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
     tf_scatter(tf.Yv, out_dim, tf.slot_row, (int64_t)tf.Lmax * tf.n_lanes, Y, ldy, st);
   } else if (!launch_dense(da, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
@@ -1084,6 +1088,8 @@ dgc_status_t dgc_layer_set_presence(dgc_layer_t* L, const uint8_t* present, void
   DGC_HIP_TRY(dev_alloc(L, &tf.lane_ptr, nc + 1));
   DGC_HIP_TRY(dev_alloc(L, &tf.slot_row, n_slots));
   DGC_HIP_TRY(dev_alloc(L, &tf.slot_reset, n_slots));
+  DGC_HIP_TRY(dev_alloc(L, &tf.seq_in, n_slots));
+  DGC_HIP_TRY(dev_alloc(L, &tf.seq_out, n_slots));
   DGC_HIP_TRY(dev_alloc(L, &tf.row_map, L->total_rows));
   DGC_HIP_TRY(dev_alloc(L, &tf.chunks_v, nc));
   DGC_HIP_TRY(hipMemcpyAsync(d_lane, lane_of.data(), sizeof(int32_t) * lane_of.size(), hipMemcpyHostToDevice, st));
@@ -1091,7 +1097,7 @@ dgc_status_t dgc_layer_set_presence(dgc_layer_t* L, const uint8_t* present, void
   DGC_HIP_TRY(hipMemcpyAsync(tf.lane_ptr, lane_ptr.data(), sizeof(int64_t) * (nc + 1), hipMemcpyHostToDevice, st));
   DGC_HIP_TRY(hipMemcpyAsync(tf.chunks_v, cv.data(), sizeof(ChunkInfo) * nc, hipMemcpyHostToDevice, st));
   tf_fill(present, L->d_chunks, nc, max_nv, L->N, d_lane, d_off, tf.n_lanes, tf.Lmax, tf.chunks_v, L->total_rows,
-          tf.slot_row, tf.row_map, tf.slot_reset, st);
+          tf.slot_row, tf.row_map, tf.slot_reset, tf.seq_in, tf.seq_out, st);
   // tiles of the virtual chunks
   std::vector<DenseTile> t64, t32;
   for (int32_t k = 0; k < nc; ++k) {
@@ -1111,7 +1117,8 @@ dgc_status_t dgc_layer_set_presence(dgc_layer_t* L, const uint8_t* present, void
   DGC_HIP_TRY(dev_alloc(L, &tf.Yv, n_slots * out_dim));
   DGC_HIP_TRY(hipStreamSynchronize(st));
   DGC_HIP_TRY(hipGetLastError());
-  dev_free(L, d_len); dev_free(L, d_lane); dev_free(L, d_off);
+  tf.seq_len = d_len;
+  dev_free(L, d_lane); dev_free(L, d_off);
   tf.built = true;
   return DGC_OK;
 }

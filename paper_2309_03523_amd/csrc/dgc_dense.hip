@@ -130,13 +130,20 @@ __device__ __forceinline__ void mma_k_loop(floatx16 (&acc)[NRB][4], const float*
 // Per step: mask P | Z = act(Q W^T + b) in registers | Z -> Q | gate GEMMs read Q and P | the
 // next step's aggregated rows start loading into registers | gate arithmetic | new h -> Q and
 // the prefetched rows -> P | Q -> Y | swap(P, Q).
-template <int KIND, int NRB, int UPW>
+// SEQ: the rows of a tile hold several sequences one after the other (temporal fusion with
+// states): states enter and leave through the tables seq_in / seq_out instead of at the window's
+// ends; mask_row then holds 1 + the state row of a sequence that starts at this step, end_row
+// 1 + the state row of a sequence that ends at it (0 = none).
+template <int KIND, int NRB, int UPW, bool SEQ>
 __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int ld) {
   extern __shared__ float smem[];
   float* P = smem;
   float* Q = smem + kTileRows * ld;
   int* mask_row = reinterpret_cast<int*>(smem + 2 * kTileRows * ld);   // [64]
-  float* gate_bias = smem + 2 * kTileRows * ld + kTileRows;            // [4][H]
+  int* end_rows = mask_row + kTileRows;                                // [2][64], by step parity: the output
+                                                                       // store of a step still reads its table
+                                                                       // when the next step's is written
+  float* gate_bias = smem + 2 * kTileRows * ld + 3 * kTileRows;        // [4][H]
 
   prio_other();
   const DenseTile tile = a.tiles[blockIdx.x];
@@ -202,14 +209,14 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int ld) {
         for (int v = 0; v < 16; ++v) {
           const int row = (rb0 + rb) * 32 + l32;
           const int col = jb * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-          cst[ui][rb][v] = (a.H0 && u < unitsH && row < nrows) ? a.H0[(V + sbase + row) * H + col] : 0.f;
+          cst[ui][rb][v] = (!SEQ && a.H0 && u < unitsH && row < nrows) ? a.H0[(V + sbase + row) * H + col] : 0.f;
         }
     }
   }
   if constexpr (KIND != DGC_TIME_NONE) {
     for_tile_f4(tid, H / 4, [&](int r, int c4) {
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (a.H0 && r < nrows) v = *reinterpret_cast<const float4*>(a.H0 + (sbase + r) * H + 4 * c4);
+      if (!SEQ && a.H0 && r < nrows) v = *reinterpret_cast<const float4*>(a.H0 + (sbase + r) * H + 4 * c4);
       *reinterpret_cast<float4*>(P + r * ld + 4 * c4) = v;
     });
     // gate biases, pre-summed where the gate adds both: GRU rows r, z, n(input), n(hidden);
@@ -229,10 +236,11 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int ld) {
 
   for (int s = 0; s < ch.w; ++s) {
     const int64_t t = ch.t_lo + s;
+    int* end_row = end_rows + (s & 1) * kTileRows;
     if (s > 0 && !prefetch) load_rows_direct(s, Q);
     // temporal-fusion mask: zero the incoming state of masked rows (same thread <-> element
     // mapping as the Y store at the end of the previous step, so no barrier in between)
-    if constexpr (KIND != DGC_TIME_NONE) {
+    if constexpr (KIND != DGC_TIME_NONE && !SEQ) {
       if (a.reset_mask) {
         for_tile_f4(tid, H / 4, [&](int r, int c4) {
           const int mk = r < nrows ? a.reset_mask[t * a.N + vbase + r] : 0;
@@ -242,6 +250,20 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int ld) {
       } else if (s == 0 && tid < kTileRows) {
         mask_row[tid] = 0;
       }
+    }
+    if constexpr (KIND != DGC_TIME_NONE && SEQ) {
+      for_tile_f4(tid, H / 4, [&](int r, int c4) {
+        const int64_t sr = r < nrows ? a.seq_in[t * a.N + vbase + r] : -1;
+        if (sr >= 0) {   // a sequence starts here: its own state row, or zero
+          float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (a.H0) v = *reinterpret_cast<const float4*>(a.H0 + sr * H + 4 * c4);
+          *reinterpret_cast<float4*>(P + r * ld + 4 * c4) = v;
+        }
+        if (c4 == 0) {
+          mask_row[r] = (int)(sr + 1);
+          end_row[r] = r < nrows ? (int)(a.seq_out[t * a.N + vbase + r] + 1) : 0;
+        }
+      });
     }
     __syncthreads();
 
@@ -365,11 +387,17 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int ld) {
                   o[e] = (1.0f - z) * n + z * hp[e];
                 }
               } else {
-                const bool masked = mask_row[(rb0 + rb) * 32 + l32] != 0;
+                const int mrow = mask_row[(rb0 + rb) * 32 + l32];
+                const bool masked = mrow != 0;
+                float cin[4] = {0.f, 0.f, 0.f, 0.f};
+                if (SEQ && masked && a.H0) {   // the cell row of the sequence that starts here
+                  const float4 c4v = *reinterpret_cast<const float4*>(a.H0 + (V + mrow - 1) * H + c0);
+                  cin[0] = c4v.x; cin[1] = c4v.y; cin[2] = c4v.z; cin[3] = c4v.w;
+                }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                   const int v = 4 * g4 + e;
-                  const float cm = masked ? 0.f : cst[ui][rb][v];
+                  const float cm = masked ? cin[e] : cst[ui][rb][v];
                   const float ig = sigmoid_fast(acc[rb][0][v] + bs[0][e]);
                   const float fg = sigmoid_fast(acc[rb][1][v] + bs[1][e]);
                   const float gg = tanh_fast(acc[rb][2][v] + bs[2][e]);
@@ -377,6 +405,13 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int ld) {
                   const float cn = fg * cm + ig * gg;
                   cst[ui][rb][v] = cn;
                   o[e] = og * tanh_fast(cn);
+                }
+                if constexpr (SEQ) {           // the cell state of a sequence that ends at this step
+                  const int erow = end_row[(rb0 + rb) * 32 + l32];
+                  if (erow != 0 && a.HN)
+                    *reinterpret_cast<float4*>(a.HN + (V + erow - 1) * H + c0) =
+                        make_float4(cst[ui][rb][4 * g4], cst[ui][rb][4 * g4 + 1], cst[ui][rb][4 * g4 + 2],
+                                    cst[ui][rb][4 * g4 + 3]);
                 }
               }
               hnew[ui][rb][g4] = make_float4(o[0], o[1], o[2], o[3]);
@@ -403,12 +438,16 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int ld) {
       }
       __syncthreads();
       // h_t -> Y, whole rows at a time; Q becomes the state buffer of the next step
-      const bool last = (s == ch.w - 1) && a.HN;
+      const bool last = !SEQ && (s == ch.w - 1) && a.HN;
       for_tile_f4(tid, H / 4, [&](int r, int c4) {
         if (r < nrows) {
           const float4 v = *reinterpret_cast<const float4*>(Q + r * ld + 4 * c4);
           *reinterpret_cast<float4*>(a.Y + (t * a.N + vbase + r) * a.ldy + 4 * c4) = v;
           if (last) *reinterpret_cast<float4*>(a.HN + (sbase + r) * H + 4 * c4) = v;
+          if constexpr (SEQ) {
+            const int erow = end_row[r];
+            if (erow != 0 && a.HN) *reinterpret_cast<float4*>(a.HN + (int64_t)(erow - 1) * H + 4 * c4) = v;
+          }
         }
       });
       // P (the old state, no longer read) becomes the next step's Q
@@ -417,7 +456,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int ld) {
     }
   }
 
-  if constexpr (KIND == DGC_TIME_LSTM) {
+  if constexpr (KIND == DGC_TIME_LSTM && !SEQ) {
     if (a.HN) {
 #pragma unroll
       for (int ui = 0; ui < UPW; ++ui) {
@@ -442,18 +481,26 @@ template <int KIND, int NRB, int UPW>
 bool launch_k(const DenseArgs& a, hipStream_t st, std::string* why) {
   const int ld = dense_ld(a.K0, a.S, KIND == DGC_TIME_NONE ? 0 : a.H);
   const size_t lds = dense_lds_bytes(a.K0, a.S, KIND == DGC_TIME_NONE ? 0 : a.H);
+  constexpr bool kSeq = KIND != DGC_TIME_NONE;
   static bool attr_done = false;  // per instantiation
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_dense<KIND, NRB, UPW>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_dense<KIND, NRB, UPW, false>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e == hipSuccess && kSeq)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_dense<KIND, NRB, UPW, kSeq>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) {
       if (why) *why = std::string("hipFuncSetAttribute: ") + hipGetErrorString(e);
       return false;
     }
     attr_done = true;
   }
-  if (a.n_tiles > 0)
-    hipLaunchKernelGGL((k_dense<KIND, NRB, UPW>), (unsigned)a.n_tiles, kThreads, lds, st, a, ld);
+  if (a.n_tiles > 0) {
+    if (kSeq && a.seq_in)
+      hipLaunchKernelGGL((k_dense<KIND, NRB, UPW, kSeq>), (unsigned)a.n_tiles, kThreads, lds, st, a, ld);
+    else
+      hipLaunchKernelGGL((k_dense<KIND, NRB, UPW, false>), (unsigned)a.n_tiles, kThreads, lds, st, a, ld);
+  }
   return true;
 }
 
@@ -479,7 +526,7 @@ int dense_ld(int32_t K0, int32_t S, int32_t H) {
 }
 
 size_t dense_lds_bytes(int32_t K0, int32_t S, int32_t H) {
-  return sizeof(float) * ((size_t)kTileRows * 2 * dense_ld(K0, S, H) + kTileRows + 4 * (size_t)H);
+  return sizeof(float) * ((size_t)kTileRows * 2 * dense_ld(K0, S, H) + 3 * kTileRows + 4 * (size_t)H);
 }
 
 void launch_pack_weight(const float* W, int32_t n_out, int32_t n_in, float4* packed, hipStream_t st) {

@@ -131,7 +131,23 @@ __device__ __forceinline__ void k_loop_reg(floatx16 (&acc)[NG], const float4 (&x
 }
 
 // KIND: DGC_TIME_*;  NJB = S/32 = H/32.
-template <int KIND, int NJB>
+// the state (h, and c for the LSTM) after a sequence's last row goes to that sequence's row of HN
+template <int KIND, int NKB>
+__device__ __forceinline__ void store_state_t(const DenseArgs& a, int64_t idx, int64_t V, int H, int half,
+                                              const float4 (&h)[NKB], const float4 (&c)[NKB]) {
+  if (!a.HN) return;
+  const int64_t so = a.seq_out[idx];
+  if (so < 0) return;
+#pragma unroll
+  for (int kb = 0; kb < NKB; ++kb) {
+    *reinterpret_cast<float4*>(a.HN + so * H + 8 * kb + 4 * half) = h[kb];
+    if constexpr (KIND == DGC_TIME_LSTM) *reinterpret_cast<float4*>(a.HN + (V + so) * H + 8 * kb + 4 * half) = c[kb];
+  }
+}
+
+// SEQ: the rows of a tile hold several sequences one after the other (temporal fusion with
+// states): states enter and leave through the tables seq_in / seq_out instead of at the window's ends.
+template <int KIND, int NJB, bool SEQ>
 __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dense_wave(DenseArgs a) {
   // LDS, private to this wave (the workgroup is one wave):
   //   zbuf [32][ldz] the Z tile | gbias [4][H] gate biases, pre-summed | zbias [S]
@@ -179,7 +195,7 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
   for (int kb = 0; kb < NKB; ++kb) {
     h[kb] = zero4();
     c[kb] = zero4();
-    if constexpr (KIND != DGC_TIME_NONE) {
+    if constexpr (KIND != DGC_TIME_NONE && !SEQ) {
       if (a.H0) {
         h[kb] = *reinterpret_cast<const float4*>(a.H0 + srow * H + 8 * kb + 4 * half);
         if constexpr (KIND == DGC_TIME_LSTM)
@@ -220,15 +236,27 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
           float* y = a.Y + ((t - 1) * a.N + vrow) * a.ldy + 4 * half;
 #pragma unroll
           for (int kb = 0; kb < NKB; ++kb) *reinterpret_cast<float4*>(y + 8 * kb) = h[kb];
+          if constexpr (SEQ) store_state_t<KIND, NKB>(a, (t - 1) * a.N + vrow, V, H, half, h, c);
         }
       }
     }
 
     // temporal-fusion mask on the incoming state (Section 5.1.2)
-    if constexpr (KIND != DGC_TIME_NONE) {
+    if constexpr (KIND != DGC_TIME_NONE && !SEQ) {
       if (a.reset_mask && a.reset_mask[t * a.N + vrow]) {
 #pragma unroll
         for (int kb = 0; kb < NKB; ++kb) { h[kb] = zero4(); c[kb] = zero4(); }
+      }
+    }
+    if constexpr (KIND != DGC_TIME_NONE && SEQ) {
+      const int64_t sr = a.seq_in[t * a.N + vrow];
+      if (sr >= 0) {   // a sequence starts here: its own state row, or zero
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb) {
+          h[kb] = a.H0 ? *reinterpret_cast<const float4*>(a.H0 + sr * H + 8 * kb + 4 * half) : zero4();
+          if constexpr (KIND == DGC_TIME_LSTM)
+            c[kb] = a.H0 ? *reinterpret_cast<const float4*>(a.H0 + (V + sr) * H + 8 * kb + 4 * half) : zero4();
+        }
       }
     }
 
@@ -384,8 +412,9 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
       float* y = a.Y + ((int64_t)(ch.t_lo + ch.w - 1) * a.N + vrow) * a.ldy + 4 * half;
 #pragma unroll
       for (int kb = 0; kb < NKB; ++kb) *reinterpret_cast<float4*>(y + 8 * kb) = h[kb];
+      if constexpr (SEQ) store_state_t<KIND, NKB>(a, (int64_t)(ch.t_lo + ch.w - 1) * a.N + vrow, V, H, half, h, c);
     }
-    if (a.HN && valid) {
+    if (!SEQ && a.HN && valid) {
 #pragma unroll
       for (int kb = 0; kb < NKB; ++kb) {
         *reinterpret_cast<float4*>(a.HN + srow * H + 8 * kb + 4 * half) = h[kb];
@@ -401,8 +430,12 @@ bool launch_w(const DenseArgs& a, hipStream_t st, std::string* why) {
   (void)why;
   constexpr int ldz = NJB * 32 + 4;
   const size_t lds = sizeof(float) * ((KIND == DGC_TIME_NONE ? 0 : kRows * ldz + 4 * NJB * 32) + NJB * 32);
-  if (a.n_tiles32 > 0)
-    hipLaunchKernelGGL((k_dense_wave<KIND, NJB>), (unsigned)a.n_tiles32, kWave, lds, st, a);
+  if (a.n_tiles32 > 0) {
+    if (KIND != DGC_TIME_NONE && a.seq_in)
+      hipLaunchKernelGGL((k_dense_wave<KIND, NJB, KIND != DGC_TIME_NONE>), (unsigned)a.n_tiles32, kWave, lds, st, a);
+    else
+      hipLaunchKernelGGL((k_dense_wave<KIND, NJB, false>), (unsigned)a.n_tiles32, kWave, lds, st, a);
+  }
   return true;
 }
 

@@ -155,6 +155,13 @@ struct DenseArgs {
   const uint8_t* reset_mask;
   float* Y; int64_t ldy;        // [T,N,ldy]
   float* HN;
+  // Sequences inside the window (temporal fusion with states), indexed like reset_mask; both set or
+  // both nullptr.  seq_in[t*N + v] >= 0: the row starts a sequence whose state row that is (the
+  // incoming state becomes H0's row, or zero without H0); seq_out[...] >= 0: the row ends the
+  // sequence of that state row (the new state goes to HN's row).  H0 / HN are then read / written
+  // only through these tables.
+  const int64_t* seq_in;
+  const int64_t* seq_out;
 };
 // returns false if the (S,H,K0) combination has no kernel
 bool launch_dense(const DenseArgs& a, hipStream_t st, std::string* why);
@@ -274,6 +281,9 @@ struct TFusion {
   int64_t* lane_ptr = nullptr;    // [n_chunks+1] first lane of every chunk
   int64_t* slot_row = nullptr;    // [Lmax][n_lanes] t*N + i of the row in the slot, -1 = empty
   int64_t* row_map = nullptr;     // [total rows] inverse: packed row -> row of Mv (lane order), -1 = absent
+  int64_t* seq_in = nullptr;      // [Lmax][n_lanes] state row of the sequence that starts in the slot, else -1
+  int64_t* seq_out = nullptr;     // [Lmax][n_lanes] state row of the sequence that ends in the slot, else -1
+  int32_t* seq_len = nullptr;     // [state rows] present snapshots of every (chunk, vertex)
   uint8_t* slot_reset = nullptr;  // [Lmax][n_lanes] 1 on the first slot of every sequence
   ChunkInfo* chunks_v = nullptr;  // the lanes of chunk k as a chunk: v_lo = first lane, nv = lanes, t_lo = 0
   DenseTile* tiles_v = nullptr; int64_t n_tiles_v = 0;
@@ -285,7 +295,9 @@ void tf_lengths(const uint8_t* present, const ChunkInfo* chunks, int32_t n_chunk
                 int32_t* seq_len, hipStream_t st);
 void tf_fill(const uint8_t* present, const ChunkInfo* chunks, int32_t n_chunks, int64_t max_nv, int64_t N,
              const int32_t* seq_lane, const int32_t* seq_off, int64_t n_lanes, int32_t Lmax, const ChunkInfo* chunks_v,
-             int64_t total_rows, int64_t* slot_row, int64_t* row_map, uint8_t* slot_reset, hipStream_t st);
+             int64_t total_rows, int64_t* slot_row, int64_t* row_map, uint8_t* slot_reset, int64_t* seq_in,
+             int64_t* seq_out, hipStream_t st);
+void tf_carry(const int32_t* seq_len, int64_t V, int32_t n_state, int32_t H, const float* H0, float* HN, hipStream_t st);
 void tf_scatter(const float* Yv, int32_t out_dim, const int64_t* slot_row, int64_t n_slots, float* Y, int64_t ldy,
                 hipStream_t st);
 

@@ -29,7 +29,7 @@ __global__ void k_tf_lengths(const uint8_t* present, const ChunkInfo* chunks, in
 // slot tables from the lane / first slot assigned to every sequence
 __global__ void k_tf_fill(const uint8_t* present, const ChunkInfo* chunks, int64_t N, const int32_t* seq_lane,
                           const int32_t* seq_off, int64_t n_lanes, const ChunkInfo* chunks_v, int64_t* slot_row,
-                          int64_t* row_map, uint8_t* slot_reset) {
+                          int64_t* row_map, uint8_t* slot_reset, int64_t* seq_in, int64_t* seq_out) {
   const ChunkInfo c = chunks[blockIdx.y];
   const ChunkInfo cv = chunks_v[blockIdx.y];
   const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -38,6 +38,7 @@ __global__ void k_tf_fill(const uint8_t* present, const ChunkInfo* chunks, int64
   if (lane < 0) return;
   int32_t slot = seq_off[c.state_off + v];
   slot_reset[(int64_t)slot * n_lanes + lane] = 1;
+  seq_in[(int64_t)slot * n_lanes + lane] = c.state_off + v;     // the sequence's state row enters here
   for (int32_t s = 0; s < c.w; ++s) {
     const int64_t t = c.t_lo + s;
     if (!present[t * N + c.v_lo + v]) continue;
@@ -45,6 +46,20 @@ __global__ void k_tf_fill(const uint8_t* present, const ChunkInfo* chunks, int64
     row_map[c.row_off0 + (int64_t)s * c.nv + v] = cv.row_off0 + (int64_t)slot * cv.nv + (lane - cv.v_lo);
     ++slot;
   }
+  seq_out[(int64_t)(slot - 1) * n_lanes + lane] = c.state_off + v;   // ... and leaves after its last slot
+}
+
+// HN row = H0 row (or zero) for every (chunk, vertex) that is absent throughout its window; one
+// thread per float4, n_state blocks of V rows (hidden, then cell for the LSTM)
+__global__ void k_tf_carry(const int32_t* seq_len, int64_t V, int32_t n_state, int32_t H, const float* H0, float* HN) {
+  const int64_t q = H / 4;
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)n_state * V * q) return;
+  const int64_t row = idx / q, c4 = idx - row * q;
+  if (seq_len[row % V] != 0) return;
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (H0) v = reinterpret_cast<const float4*>(H0 + row * H)[c4];
+  reinterpret_cast<float4*>(HN + row * H)[c4] = v;
 }
 
 __global__ void k_tf_fill_i64(int64_t* p, int64_t v, int64_t n) {
@@ -73,13 +88,23 @@ void tf_lengths(const uint8_t* present, const ChunkInfo* chunks, int32_t n_chunk
 
 void tf_fill(const uint8_t* present, const ChunkInfo* chunks, int32_t n_chunks, int64_t max_nv, int64_t N,
              const int32_t* seq_lane, const int32_t* seq_off, int64_t n_lanes, int32_t Lmax, const ChunkInfo* chunks_v,
-             int64_t total_rows, int64_t* slot_row, int64_t* row_map, uint8_t* slot_reset, hipStream_t st) {
+             int64_t total_rows, int64_t* slot_row, int64_t* row_map, uint8_t* slot_reset, int64_t* seq_in,
+             int64_t* seq_out, hipStream_t st) {
   const int64_t n = (int64_t)Lmax * n_lanes;
-  if (n > 0) hipLaunchKernelGGL(k_tf_fill_i64, nblocks(n, 256), 256, 0, st, slot_row, (int64_t)-1, n);   // no lanes: nobody present
+  if (n > 0) {   // no lanes: nobody present
+    hipLaunchKernelGGL(k_tf_fill_i64, nblocks(n, 256), 256, 0, st, slot_row, (int64_t)-1, n);
+    hipLaunchKernelGGL(k_tf_fill_i64, nblocks(n, 256), 256, 0, st, seq_in, (int64_t)-1, n);
+    hipLaunchKernelGGL(k_tf_fill_i64, nblocks(n, 256), 256, 0, st, seq_out, (int64_t)-1, n);
+  }
   hipLaunchKernelGGL(k_tf_fill_i64, nblocks(total_rows, 256), 256, 0, st, row_map, (int64_t)-1, total_rows);
   if (n > 0) (void)hipMemsetAsync(slot_reset, 0, (size_t)n, st);
   hipLaunchKernelGGL(k_tf_fill, dim3(nblocks(max_nv, 256), n_chunks), 256, 0, st, present, chunks, N, seq_lane, seq_off,
-                     n_lanes, chunks_v, slot_row, row_map, slot_reset);
+                     n_lanes, chunks_v, slot_row, row_map, slot_reset, seq_in, seq_out);
+}
+
+void tf_carry(const int32_t* seq_len, int64_t V, int32_t n_state, int32_t H, const float* H0, float* HN, hipStream_t st) {
+  const int64_t n = (int64_t)n_state * V * (H / 4);
+  if (n > 0) hipLaunchKernelGGL(k_tf_carry, nblocks(n, 256), 256, 0, st, seq_len, V, n_state, H, H0, HN);
 }
 
 void tf_scatter(const float* Yv, int32_t out_dim, const int64_t* slot_row, int64_t n_slots, float* Y, int64_t ldy,
