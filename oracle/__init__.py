@@ -136,10 +136,12 @@ def forward(graph, chunks, params: dict, X: np.ndarray, C: np.ndarray, *, time_k
             n_struct_layers: int = 1, act_hidden: str = "relu", act_out: str = "none",
             C1: Optional[np.ndarray] = None, H0: Optional[np.ndarray] = None,
             reset_mask: Optional[np.ndarray] = None, subset: Optional[list] = None,
-            Y: Optional[np.ndarray] = None, return_state: bool = False):
+            Y: Optional[np.ndarray] = None, return_state: bool = False, input_concat: bool = False):
     """The whole layer over the listed chunks.  Returns Y float32 [T,N,out_dim] (rows not
     covered by a chunk, or outside `subset`, keep the value they had in the `Y` passed in,
-    NaN if none was passed) and optionally the final recurrent states packed like H0."""
+    NaN if none was passed) and optionally the final recurrent states packed like H0.
+    input_concat (two structure layers): the time encoder reads both layers' outputs side by
+    side, first layer first (Section 6, MPNN-LSTM); rnn.weight_ih is then [gH, 2S]."""
     g = _Csr(graph)
     ch = _chunks(chunks)
     T, N = g.T, g.N
@@ -161,7 +163,8 @@ def forward(graph, chunks, params: dict, X: np.ndarray, C: np.ndarray, *, time_k
         bhh = np.ascontiguousarray(params["rnn.bias_hh"], np.float32)
         H = Whh.shape[1]
         gH = {"gru": 3, "lstm": 4}[time_kind] * H
-        assert Wih.shape == (gH, S) and Whh.shape == (gH, H)
+        assert Wih.shape == (gH, 2 * S if input_concat else S) and Whh.shape == (gH, H)
+    assert not input_concat or (n_struct_layers == 2 and time_kind != "none")
     out_dim = H if time_kind != "none" else S
     if Y is None:
         Y = np.full((T, N, out_dim), np.nan, np.float32)
@@ -191,7 +194,7 @@ def forward(graph, chunks, params: dict, X: np.ndarray, C: np.ndarray, *, time_k
         _p(W0, ct.c_float), _p(b0, ct.c_float), _p(W1, ct.c_float), _p(b1, ct.c_float),
         _p(Wih, ct.c_float), _p(Whh, ct.c_float), _p(bih, ct.c_float), _p(bhh, ct.c_float),
         _p(H0, ct.c_float), _p(reset_mask, ct.c_uint8), _p(sub_ptr, ct.c_int64), _p(sub_idx, ct.c_int64),
-        _p(Y, ct.c_float), ct.c_int64(Y.strides[1] // 4), _p(hN, ct.c_float))
+        _p(Y, ct.c_float), ct.c_int64(Y.strides[1] // 4), _p(hN, ct.c_float), ct.c_int32(int(input_concat)))
     if rc:
         raise ValueError(f"dgc_oracle_forward failed: {rc}")
     return (Y, hN) if return_state else Y

@@ -258,6 +258,9 @@ static void lstm_step(const float *Wih, const float *Whh, const float *bih, cons
  *  n_struct_layers 1: Z = act_out(M(X|C) W0^T + b0)
  *                  2: Z1 = act_hidden(M(X|C) W0^T + b0) for every row of the chunk, then
  *                     Z = act_out(M(Z1|C1) W1^T + b1); C1 is the cache of layer-1 inputs.
+ *  input_concat (2 layers with a time encoder): the time encoder's input is the row [Z1, Z]
+ *  of width 2S, both structure layers' outputs side by side as Section 6 describes for
+ *  MPNN-LSTM, and Wih is [gH][2S]; otherwise it is Z and Wih is [gH][S].
  *  time_kind NONE: Y[t,i] = Z;  GRU / LSTM: per vertex recurrence over the chunk's window,
  *  starting from H0 (packed: chunk k's rows start at sum of earlier chunks' vertex counts;
  *  for LSTM the cell states follow all hidden states), Y[t,i] = h_t.
@@ -274,9 +277,12 @@ int dgc_oracle_forward(int32_t T, int64_t N, const int64_t *const *rowptr,
                        const float *W0, const float *b0, const float *W1, const float *b1,
                        const float *Wih, const float *Whh, const float *bih, const float *bhh,
                        const float *H0, const uint8_t *reset_mask, const int64_t *subset_ptr,
-                       const int64_t *subset_idx, float *Y, int64_t ldy, float *hN) {
+                       const int64_t *subset_idx, float *Y, int64_t ldy, float *hN,
+                       int32_t input_concat) {
   if (n_struct_layers < 1 || n_struct_layers > 2) return -3;
   if (n_struct_layers == 2 && (!C1 || !W1)) return -3;
+  if (input_concat && (n_struct_layers != 2 || time_kind == TIME_NONE)) return -3;
+  const int32_t Sx = input_concat ? 2 * S : S;   /* width of the time encoder's input */
   int64_t tot_v = 0;
   for (int32_t k = 0; k < n_chunks; ++k) tot_v += CH_VHI(chunks, k) - CH_VLO(chunks, k);
   int64_t row_base = 0;
@@ -305,9 +311,10 @@ int dgc_oracle_forward(int32_t T, int64_t N, const int64_t *const *rowptr,
       const int64_t i = subset_ptr ? subset_idx[subset_ptr[k] + q] : v_lo + q;
       const int32_t Fl = n_struct_layers == 2 ? S : F;
       const int32_t g = time_kind == TIME_LSTM ? 4 : 3;
-      double *buf = (double *)malloc(sizeof(double) * (size_t)(Fl + S + 2 * g * H + 6 * H + 8));
-      double *m = buf, *z = m + Fl, *gx = z + S, *gh = gx + g * H, *h = gh + g * H, *c = h + H,
+      double *buf = (double *)malloc(sizeof(double) * (size_t)(Fl + 2 * S + 2 * g * H + 6 * H + 8));
+      double *m = buf, *x = m + Fl, *gx = x + 2 * S, *gh = gx + g * H, *h = gh + g * H, *c = h + H,
              *hm = c + H, *cm = hm + H, *h2 = cm + H, *c2 = h2 + H;
+      double *z = input_concat ? x + S : x;   /* the last structure layer's output inside x */
       const int64_t slot = row_base + (i - v_lo);
       for (int32_t j = 0; j < H; ++j) {
         h[j] = (H0 && time_kind != TIME_NONE) ? (double)H0[slot * H + j] : 0.0;
@@ -318,6 +325,8 @@ int dgc_oracle_forward(int32_t T, int64_t N, const int64_t *const *rowptr,
           aggregate_row(N, rowptr[t], col[t], t, i, v_lo, v_hi, NULL, 0,
                         Z1 + (t - t_lo) * nv * (int64_t)S, C1, ldc1, S, m);
           dense_row(W1, b1, S, S, m, act_out, z);
+          if (input_concat)
+            for (int32_t j = 0; j < S; ++j) x[j] = Z1[((t - t_lo) * nv + (i - v_lo)) * (int64_t)S + j];
         } else {
           aggregate_row(N, rowptr[t], col[t], t, i, v_lo, v_hi, X, ldx, NULL, C, ldc, F, m);
           dense_row(W0, b0, S, F, m, act_out, z);
@@ -330,9 +339,9 @@ int dgc_oracle_forward(int32_t T, int64_t N, const int64_t *const *rowptr,
         const double mk = (reset_mask && reset_mask[t * N + i]) ? 0.0 : 1.0;
         for (int32_t j = 0; j < H; ++j) { hm[j] = mk * h[j]; cm[j] = mk * c[j]; }
         if (time_kind == TIME_GRU) {
-          gru_step(Wih, Whh, bih, bhh, S, H, z, hm, gx, gh, h2);
+          gru_step(Wih, Whh, bih, bhh, Sx, H, x, hm, gx, gh, h2);
         } else {
-          lstm_step(Wih, Whh, bih, bhh, S, H, z, hm, cm, gx, gh, h2, c2);
+          lstm_step(Wih, Whh, bih, bhh, Sx, H, x, hm, cm, gx, gh, h2, c2);
           for (int32_t j = 0; j < H; ++j) c[j] = c2[j];
         }
         for (int32_t j = 0; j < H; ++j) { h[j] = h2[j]; y[j] = (float)h[j]; }

@@ -160,9 +160,10 @@ def xavier_uniform(rng: np.random.Generator, fan_out: int, fan_in: int) -> np.nd
 
 
 def layer_params(seed: int, F: int, S: int, H: int, time_kind: str, n_struct_layers: int = 1,
-                 random_bias: bool = False) -> dict:
+                 random_bias: bool = False, input_concat: bool = False) -> dict:
     """Weights in (out, in) row-major order, Xavier-uniform.  Biases are zero unless
-    random_bias (tests use non-zero biases so that a dropped bias fails)."""
+    random_bias (tests use non-zero biases so that a dropped bias fails).  input_concat: the
+    time encoder reads both structure layers' outputs, so its input weights are [gH, 2S]."""
     rng = stream(seed, "param")
     g = {"gru": 3, "lstm": 4, "none": 0}[time_kind]
     p = {}
@@ -171,7 +172,7 @@ def layer_params(seed: int, F: int, S: int, H: int, time_kind: str, n_struct_lay
         p[f"gcn{l}.weight"] = xavier_uniform(rng, S, fin)          # [S, fin]
         p[f"gcn{l}.bias"] = np.zeros(S, np.float32)
     if g:
-        p["rnn.weight_ih"] = xavier_uniform(rng, g * H, S)          # [gH, S]
+        p["rnn.weight_ih"] = xavier_uniform(rng, g * H, 2 * S if input_concat else S)   # [gH, S or 2S]
         p["rnn.weight_hh"] = xavier_uniform(rng, g * H, H)          # [gH, H]
         p["rnn.bias_ih"] = np.zeros(g * H, np.float32)
         p["rnn.bias_hh"] = np.zeros(g * H, np.float32)
@@ -403,7 +404,7 @@ def config4(seed: int = 0, scale: float = 1.0, random_bias: bool = False):
 
 def random_small(seed: int, T: int, N: int, F: int, S: int, H: int, avg_deg: float,
                  chunks: np.ndarray, time_kind: str = "gru", n_struct_layers: int = 1,
-                 hub: bool = False) -> Workload:
+                 hub: bool = False, input_concat: bool = False) -> Workload:
     """Small random workload with arbitrary chunk set and non-zero biases, for tests."""
     g_rng = stream(seed, "graph")
     snaps = []
@@ -431,7 +432,9 @@ def random_small(seed: int, T: int, N: int, F: int, S: int, H: int, avg_deg: flo
     if h0 is not None:  # make every window start non-trivial
         h0 = (0.5 * _normal_f32(stream(seed, "h0b"), h0.shape)).astype(np.float32)
     return Workload(f"small{seed}", graph, chunks, F, S, H, time_kind, n_struct_layers, X, C, C1, h0,
-                    layer_params(seed, F, S, H, time_kind, n_struct_layers, random_bias=True))
+                    layer_params(seed, F, S, H, time_kind, n_struct_layers, random_bias=True,
+                                 input_concat=input_concat),
+                    notes={"input_concat": True} if input_concat else {})
 
 
 # --------------------------------------------------------------------------- bf16 workloads

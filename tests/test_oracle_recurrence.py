@@ -154,3 +154,45 @@ def test_identity_structure_reduces_to_plain_rnn():
     with torch.no_grad():
         out, _ = _torch_rnn("gru", params, D, D)(torch.from_numpy(X).double())
     assert np.abs(Y - out.numpy()).max() < 2e-6
+
+
+@pytest.mark.parametrize("kind", ["lstm", "gru"])
+def test_concatenated_structure_outputs_feed_the_time_encoder(kind):
+    """Section 6 (MPNN-LSTM): the time encoder reads both structure layers' outputs side by
+    side.  Built here from dense matrices and the library recurrence with a 2S-wide input; the
+    two halves of the input weights are scaled differently so that swapped halves fail."""
+    T, N, F, S, H = 4, 19, 5, 6, 7
+    chunks = np.array([[0, 8, 0, 4], [8, 19, 0, 3], [8, 19, 3, 4]], np.int64)
+    wl = synth.random_small(33, T, N, F, S, H, 3.0, chunks, kind, n_struct_layers=2, hub=True, input_concat=True)
+    assert wl.params["rnn.weight_ih"].shape[1] == 2 * S
+    wl.params["rnn.weight_ih"][:, :S] *= 1.7
+    Y, hN = oracle.forward(wl.graph, chunks, wl.params, wl.X, wl.C, time_kind=kind, n_struct_layers=2, C1=wl.C1,
+                           H0=wl.H0, return_state=True, input_concat=True)
+    rnn = _torch_rnn(kind, wl.params, 2 * S, H)
+    P = {k: v.astype(np.float64) for k, v in wl.params.items()}
+    tot = int((chunks[:, 1] - chunks[:, 0]).sum())
+    off = 0
+    for v_lo, v_hi, t_lo, t_hi in chunks.tolist():
+        xs = []
+        for t in range(t_lo, t_hi):
+            Ahat = dense_norm_adj(N, edges_of(wl.graph.snaps[t]))
+            z1 = np.maximum(dense_aggregate(Ahat, wl.X[t], wl.C[t], v_lo, v_hi) @ P["gcn0.weight"].T + P["gcn0.bias"], 0)
+            full = np.zeros((N, S))
+            full[v_lo:v_hi] = z1
+            z2 = dense_aggregate(Ahat, full, wl.C1[t], v_lo, v_hi) @ P["gcn1.weight"].T + P["gcn1.bias"]
+            xs.append(np.concatenate([z1, z2], axis=1))
+        nv = v_hi - v_lo
+        h0 = torch.from_numpy(wl.H0[off:off + nv]).double()[None]
+        with torch.no_grad():
+            if kind == "gru":
+                out, hn = rnn(torch.from_numpy(np.stack(xs)), h0)
+            else:
+                c0 = torch.from_numpy(wl.H0[tot + off:tot + off + nv]).double()[None]
+                out, (hn, cn) = rnn(torch.from_numpy(np.stack(xs)), (h0, c0))
+                assert np.abs(hN[tot + off:tot + off + nv] - cn[0].numpy()).max() < 2e-6
+        assert np.abs(Y[t_lo:t_hi, v_lo:v_hi] - out.numpy()).max() < 2e-6
+        assert np.abs(hN[off:off + nv] - hn[0].numpy()).max() < 2e-6
+        off += nv
+    # without the flag the same call refuses the wide weights
+    with pytest.raises(AssertionError):
+        oracle.forward(wl.graph, chunks, wl.params, wl.X, wl.C, time_kind=kind, n_struct_layers=2, C1=wl.C1)
