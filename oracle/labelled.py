@@ -1,0 +1,93 @@
+"""CPU oracle of the layer over GENERATED chunks (Sections 4.1 and 5.2 of the paper): a chunk is
+whatever set of (snapshot, vertex) pairs carries one label, not a vertex range times a window.
+
+TEST INFRASTRUCTURE ONLY: plain NumPy / Python loops, float64.  Nothing in the product path may
+import this module.
+
+What the paper fixes: a chunk owns the vertices with its label; a spatial neighbour in another
+chunk contributes its stale copy (the embedding cache) instead of its current embedding, and so
+does a temporal neighbour (the same vertex one snapshot earlier) for the time encoder.  Written
+out for label[t, i] (any integers):
+  * structure encoder, row (t, i): the normalised sum over the stored row of snapshot t, taking
+    X[t, j] if label[t, j] == label[t, i] and the cache row C[t, j] otherwise (the self-loop always
+    reads X); degrees are those of the full snapshot.  With two layers the second one reads the
+    first layer's output Z1[t, j] for neighbours with the same label and C1[t, j] otherwise.
+  * time encoder, vertex i, t ascending: the state entering step t is the vertex's own state
+    after step t-1 if label[t-1, i] == label[t, i], else (also at t = 0) the stale copy
+    Hc[t, i] of it - Hc holds one row per (t, i), "the state entering step t" (zero if no Hc is
+    given; for the LSTM the cell rows follow all hidden rows).
+  * states that leave a chunk: HN[t, i] = state after step t wherever the next step belongs to
+    another chunk (t = T-1 or label[t+1, i] != label[t, i]); other rows of HN are NaN.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from .tfusion import gru_step, lstm_step
+
+
+def aggregate(graph, labels: np.ndarray, fresh: np.ndarray, stale: np.ndarray) -> np.ndarray:
+    """[T,N,F] float64: sum_j (d_i d_j)^-1/2 * (fresh[t,j] if same label else stale[t,j])."""
+    T, N = labels.shape
+    out = np.zeros((T, N, fresh.shape[2]))
+    for t, sn in enumerate(graph.snaps):
+        deg = np.diff(sn.rowptr).astype(np.float64)
+        for i in range(N):
+            acc = np.zeros(fresh.shape[2])
+            for j in sn.col[sn.rowptr[i]:sn.rowptr[i + 1]]:
+                src = fresh[t, j] if labels[t, j] == labels[t, i] else stale[t, j]
+                acc += src.astype(np.float64) / np.sqrt(deg[i] * deg[j])
+            out[t, i] = acc
+    return out
+
+
+def forward(graph, labels, params: dict, X, C, *, time_kind: str = "gru", n_struct_layers: int = 1,
+            C1=None, Hc=None, act_hidden: str = "relu", act_out: str = "none"):
+    """Returns Y [T,N,out] float64 and HN [n_state*T*N, H] (NaN where no state leaves a chunk;
+    None without a time encoder)."""
+    labels = np.asarray(labels).reshape(graph.T, graph.N)
+    T, N = labels.shape
+    P = {k: np.asarray(v, np.float64) for k, v in params.items()}
+
+    def act(a, kind):
+        return np.maximum(a, 0.0) if kind == "relu" else a
+
+    M = aggregate(graph, labels, np.asarray(X), np.asarray(C))
+    if n_struct_layers == 2:
+        Z1 = act(M @ P["gcn0.weight"].T + P["gcn0.bias"], act_hidden)
+        M = aggregate(graph, labels, Z1, np.asarray(C1))
+        Z = act(M @ P["gcn1.weight"].T + P["gcn1.bias"], act_out)
+    else:
+        Z = act(M @ P["gcn0.weight"].T + P["gcn0.bias"], act_out)
+    if time_kind == "none":
+        return Z, None
+    H = P["rnn.weight_hh"].shape[1]
+    lstm = time_kind == "lstm"
+    V = T * N
+    Y = np.zeros((T, N, H))
+    HN = np.full(((2 if lstm else 1) * V, H), np.nan)
+    for i in range(N):
+        h = c = None
+        for t in range(T):
+            if t == 0 or labels[t - 1, i] != labels[t, i]:      # the temporal neighbour is in another chunk
+                h = np.zeros((1, H)) if Hc is None else np.asarray(Hc[t * N + i], np.float64)[None]
+                c = np.zeros((1, H)) if Hc is None else np.asarray(Hc[V + t * N + i] if lstm else Hc[0] * 0, np.float64)[None]
+            if lstm:
+                h, c = lstm_step(P, Z[t, i][None], h, c)
+            else:
+                h = gru_step(P, Z[t, i][None], h)
+            Y[t, i] = h[0]
+            if t == T - 1 or labels[t + 1, i] != labels[t, i]:
+                HN[t * N + i] = h[0]
+                if lstm:
+                    HN[V + t * N + i] = c[0]
+    return Y, HN
+
+
+def labels_of_chunks(chunks, T: int, N: int) -> np.ndarray:
+    """label[t, i] = index of the rectangular chunk that covers (t, i); every pair must be covered."""
+    lab = np.full((T, N), -1, np.int64)
+    for k, (v_lo, v_hi, t_lo, t_hi) in enumerate(np.asarray(chunks, np.int64).reshape(-1, 4).tolist()):
+        lab[t_lo:t_hi, v_lo:v_hi] = k
+    assert (lab >= 0).all()
+    return lab
