@@ -29,7 +29,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config2s", "config2tf", "config3w", "config4s", "config4", "config5s", "config5", "stale", "fusion", "chunkgen"])
+    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config2s", "config2tf", "config3w", "config3wc", "config4s", "config4", "config5s", "config5", "stale", "fusion", "chunkgen"])
     ap.add_argument("--gather-mode", default="in_place", choices=["in_place", "staged"])
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -55,9 +55,11 @@ def make_workload(name: str, seed: int):
         return wl, ("config2 with temporal fusion: every vertex present in a snapshot with its own probability "
                     "U(0.15, 1); sequences concatenated into lanes of 8 (first-fit decreasing) instead of padded, each "
                     "starting from its own row of H0 as in config2")
-    if name == "config3w":
-        return synth.config3(seed, scale=0.125), ("config3 at 1/8 of its vertex count, one 32-snapshot window: 250k "
-                                                  "vertices, 2 GCN layers (172->128->128) + LSTM, 64 uneven ranges")
+    if name in ("config3w", "config3wc"):
+        cat = name == "config3wc"
+        return synth.config3(seed, scale=0.125, input_concat=cat), (
+            "config3 at 1/8 of its vertex count, one 32-snapshot window: 250k vertices, 2 GCN layers (172->128->128) + LSTM"
+            + (" reading both GCN layers' outputs (256 wide)" if cat else "") + ", 64 uneven ranges")
     if name in ("config4s", "config4"):
         scale = 0.125 if name == "config4s" else 1.0
         wl, target = synth.config4(seed, scale=scale)
@@ -74,7 +76,8 @@ def flops_per_row(wl) -> dict:
     """Algorithmic flops per snapshot-vertex row of each step of the path."""
     g = {"gru": 3, "lstm": 4, "none": 0}[wl.time_kind]
     dense = 2 * wl.F * wl.S + (2 * wl.S * wl.S if wl.n_struct_layers == 2 else 0)
-    rnn = 2 * wl.S * g * wl.H + 2 * wl.H * g * wl.H
+    s_in = 2 * wl.S if wl.notes.get("input_concat") else wl.S     # width of the time encoder's input
+    rnn = 2 * s_in * g * wl.H + 2 * wl.H * g * wl.H
     return {"transform": dense, "rnn": rnn}
 
 
@@ -169,7 +172,7 @@ def cpu_baseline(wl, Y_gpu, target_seconds: float, seed: int) -> dict:
         t0 = time.perf_counter()
         oracle.forward(wl.graph, chunks, wl.params, wl.X, wl.C, time_kind=wl.time_kind,
                        n_struct_layers=wl.n_struct_layers, C1=wl.C1, H0=wl.H0, subset=sub, Y=Y,
-                       act_hidden="relu", act_out="none")
+                       act_hidden="relu", act_out="none", input_concat=bool(wl.notes.get("input_concat")))
         return Y, time.perf_counter() - t0
 
     # grow the sample until one run takes about target_seconds (at most three tries)

@@ -112,6 +112,11 @@ typedef struct {
   int32_t part_nnz;        /* work list: non-zeros per part of a split row (0 = default 512) */
   int32_t dense_kernel;    /* DGC_DENSE_*                                                    */
   int32_t heads;           /* attention heads (DGC_STRUCT_GAT: 8; otherwise ignored)         */
+  int32_t lstm_input_concat; /* 1: the LSTM reads both GCN layers' outputs side by side, first
+                              layer first (Section 6, MPNN-LSTM); rnn.weight_ih is then
+                              [4H, 2S].  Needs DGC_STRUCT_GCN, two layers, DGC_TIME_LSTM
+                              (else DGC_ERR_INVALID_ARG) and S = H in {32, 64, 128} with
+                              dense_kernel not DGC_DENSE_TILE (else DGC_ERR_UNSUPPORTED)     */
 } dgc_layer_desc_t;
 
 /* Build a layer for a fixed graph and a fixed set of chunks (the paper partitions once per
@@ -130,7 +135,8 @@ dgc_status_t dgc_layer_destroy(dgc_layer_t* layer);
 
 /* Parameters, fp32, (out, in) row-major as in the recurrent units Section 6 names:
  *  "gcn0.weight" [S,F]  "gcn0.bias" [S]   "gcn1.weight" [S,S]  "gcn1.bias" [S]  (2 layers)
- *  "rnn.weight_ih" [gH,S]  "rnn.weight_hh" [gH,H]  "rnn.bias_ih" [gH]  "rnn.bias_hh" [gH]
+ *  "rnn.weight_ih" [gH,S] ([gH,2S] with lstm_input_concat)  "rnn.weight_hh" [gH,H]
+ *  "rnn.bias_ih" [gH]  "rnn.bias_hh" [gH]
  *  g = 3 (GRU, gate order r,z,n) or 4 (LSTM, gate order i,f,g,o).
  * DGC_STRUCT_EVOLVE_GCN_O (needs F = S, time_kind NONE, one layer, act_out RELU) has instead
  *  "evolve.W_init" [F,S] (in, out)   "evolve.U_z" "evolve.V_z" "evolve.U_r" "evolve.V_r"
@@ -185,6 +191,23 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* layer, const void* X, int64_t ldx, c
  * once per layer (DGC_ERR_STATE otherwise); `present` is only read during the call.
  * Synchronises `stream`. */
 dgc_status_t dgc_layer_set_presence(dgc_layer_t* layer, const uint8_t* present, void* stream);
+
+/* Generated chunks as the layer's input (Sections 4.1 and 5.2): labels device int32 [T*N], any
+ * values (what dgc_chunk_generate wrote, for instance); a chunk is the set of (snapshot, vertex)
+ * pairs with one label.  For a layer created with DGC_STRUCT_GCN, DGC_GATHER_IN_PLACE and the
+ * single chunk [0,N) x [0,T) (DGC_ERR_STATE otherwise; the rectangle only says which rows exist).
+ * After this call dgc_layer_forward computes, for every (t, i):
+ *   aggregation: neighbour j of snapshot t contributes X[t,j] (for the second GCN layer the first
+ *     one's output) if labels[t,j] == labels[t,i], else the cache row C[t,j] (C1[t,j]);
+ *   time encoder: the state entering step t is the vertex's own state after step t-1 if
+ *     labels[t-1,i] == labels[t,i]; else, and at t = 0, it is row t*N + i of H0 (zero if H0 is
+ *     NULL): H0 is then the stale-state cache, [n_state * T*N, H], cell rows after all hidden rows;
+ *   HN (optional, same shape): row t*N + i receives the state after step t wherever the next step
+ *     belongs to another chunk (t = T-1 or labels[t+1,i] != labels[t,i]); other rows are not written.
+ * reset_mask must be NULL.  May be called again with other labels; `labels` is only read during
+ * the call.  Not combined with dgc_layer_set_presence (DGC_ERR_STATE).  The packing arrays and
+ * dgc_layer_shared_rows keep describing the single rectangular chunk.  Synchronises `stream`. */
+dgc_status_t dgc_layer_set_labels(dgc_layer_t* layer, const int32_t* labels, void* stream);
 
 /* Backward pass: gradients of a scalar loss with respect to the layer's parameters, for the
  * batch of the last dgc_layer_forward on this layer (the layer keeps the aggregated rows of that

@@ -27,7 +27,7 @@ STATUS = {0: "DGC_OK", 1: "DGC_ERR_INVALID_ARG", 2: "DGC_ERR_BAD_GRAPH", 3: "DGC
 
 EXPORTS = ["dgc_layer_create", "dgc_layer_destroy", "dgc_layer_set_param", "dgc_layer_get_param",
            "dgc_layer_forward", "dgc_layer_backward", "dgc_layer_aggregate", "dgc_layer_gather",
-           "dgc_layer_packing", "dgc_layer_set_presence", "dgc_layer_set_profiling", "dgc_layer_stage_times", "dgc_last_error",
+           "dgc_layer_packing", "dgc_layer_set_presence", "dgc_layer_set_labels", "dgc_layer_set_profiling", "dgc_layer_stage_times", "dgc_last_error",
            "dgc_version", "dgc_stale_theta_factor", "dgc_stale_workspace_bytes", "dgc_stale_filter",
            "dgc_layer_shared_rows", "dgc_fusion_select", "dgc_chunk_assign", "dgc_chunk_generate"]
 THETA_VARIANT = {"printed": 0, "sigmoid": 1}
@@ -53,7 +53,7 @@ class DescT(ct.Structure):
     _fields_ = [(n, ct.c_int32) for n in
                 ("struct_kind", "n_struct_layers", "time_kind", "dtype", "F", "S", "H", "act_hidden",
                  "act_out", "gather_mode", "validate_level", "rows_per_group", "long_nnz", "part_nnz",
-                 "dense_kernel", "heads")]
+                 "dense_kernel", "heads", "lstm_input_concat")]
 
 
 _lib = None
@@ -79,6 +79,7 @@ def load() -> ct.CDLL:
     lib.dgc_layer_gather.argtypes = [vp, vp, i64, vp, i64, vp]
     lib.dgc_layer_packing.argtypes = [vp, ct.c_char_p, vp, i64, ct.POINTER(i64)]
     lib.dgc_layer_set_presence.argtypes = [vp, vp, vp]
+    lib.dgc_layer_set_labels.argtypes = [vp, vp, vp]
     lib.dgc_layer_set_profiling.argtypes = [vp, i32]
     lib.dgc_layer_stage_times.argtypes = [vp, vp]
     lib.dgc_last_error.argtypes = [vp]
@@ -146,7 +147,7 @@ class DgcLayer:
                  n_struct_layers: int = 1, act_hidden: str = "relu", act_out: str = "none",
                  gather_mode: str = "in_place", validate_level: int = 0, rows_per_group: int = 0,
                  long_nnz: int = 0, part_nnz: int = 0, dense_kernel: str = "auto", struct_kind: str = "gcn",
-                 dtype: str = "f32", heads: int = 0, stream=None):
+                 dtype: str = "f32", heads: int = 0, lstm_input_concat: bool = False, stream=None):
         import torch
         lib = load()
         self._lib = lib
@@ -166,7 +167,7 @@ class DgcLayer:
         desc = DescT(STRUCT[struct_kind], n_struct_layers, TIME_KIND[time_kind], DTYPE[dtype], F, S, H, ACT[act_hidden],
                      ACT[act_out],
                      GATHER[gather_mode], validate_level, rows_per_group, long_nnz, part_nnz, DENSE[dense_kernel],
-                     heads)
+                     heads, int(lstm_input_concat))
         rc = lib.dgc_layer_create(ct.byref(desc), ct.byref(graph), carr, len(ch), _stream_ptr(stream),
                                   ct.byref(self._h))
         if rc:
@@ -224,6 +225,14 @@ class DgcLayer:
         if not present.is_cuda or present.dtype.itemsize != 1 or not present.is_contiguous():
             raise ValueError("present must be a contiguous uint8 device tensor [T,N]")
         self._check(self._lib.dgc_layer_set_presence(self._h, _dev(present, "present"), _stream_ptr(stream)))
+
+    def set_labels(self, labels, stream=None):
+        """labels: int32 device tensor [T*N] (or [T,N]), e.g. chunk_generate's output; the layer then
+        runs over the generated chunks."""
+        import torch
+        if not labels.is_cuda or labels.dtype != torch.int32 or not labels.is_contiguous() or labels.numel() != self.T * self.N:
+            raise ValueError("labels must be a contiguous int32 device tensor with T*N entries")
+        self._check(self._lib.dgc_layer_set_labels(self._h, _dev(labels, "labels"), _stream_ptr(stream)))
 
     def aggregate(self, X, C, M, stream=None):
         self._check(self._lib.dgc_layer_aggregate(self._h, _dev(X, "X"), _ld(X, "X"), _dev(C, "C"), _ld(C, "C"),

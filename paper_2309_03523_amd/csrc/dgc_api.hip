@@ -62,6 +62,7 @@ struct dgc_layer {
   hipEvent_t evd[8] = {};                        // its stage boundaries: forward 0..3, backward 4..7
   bool evd_fwd = false, evd_bwd = false;
   TFusion tf{};                                  // temporal-fusion packing (dgc_layer_set_presence)
+  Labelled lab{};                                // generated chunks (dgc_layer_set_labels)
   // input-gradient pass of EvolveGCN-O, allocated by the first backward that asks for dX
   float* d_dM = nullptr;                         // [T*N][F] gradient of the aggregated rows
   int64_t* d_rowidx = nullptr;                   // [total rows] packed row -> t*N + v
@@ -141,6 +142,7 @@ dgc_status_t check_desc(const dgc_layer_desc_t& d, std::string* msg) {
     if (d.validate_level < 0 || d.validate_level > 1) { *msg = "validate_level must be 0 or 1"; return DGC_ERR_INVALID_ARG; }
     if (d.rows_per_group < 0 || d.rows_per_group > 32) { *msg = "rows_per_group must be in [0,32]"; return DGC_ERR_INVALID_ARG; }
     if (d.long_nnz < 0 || d.part_nnz < 0) { *msg = "long_nnz / part_nnz must be >= 0"; return DGC_ERR_INVALID_ARG; }
+    if (d.lstm_input_concat) { *msg = "lstm_input_concat needs a GCN + LSTM layer"; return DGC_ERR_INVALID_ARG; }
     return DGC_OK;
   }
   if (d.struct_kind == DGC_STRUCT_EVOLVE_GCN_O &&
@@ -170,6 +172,16 @@ dgc_status_t check_desc(const dgc_layer_desc_t& d, std::string* msg) {
   auto fits = [&](int32_t K0, int32_t S, int32_t H, int32_t kind) {
     return !tile_kernel_runs(S, H, kind) || dense_lds_bytes(K0, S, kind == DGC_TIME_NONE ? 0 : H) <= 160 * 1024;
   };
+  if (d.lstm_input_concat < 0 || d.lstm_input_concat > 1) { *msg = "lstm_input_concat must be 0 or 1"; return DGC_ERR_INVALID_ARG; }
+  if (d.lstm_input_concat) {
+    if (d.struct_kind != DGC_STRUCT_GCN || d.n_struct_layers != 2 || d.time_kind != DGC_TIME_LSTM) {
+      *msg = "lstm_input_concat needs two GCN layers and the LSTM"; return DGC_ERR_INVALID_ARG;
+    }
+    if (tile_kernel_runs(d.S, d.H, d.time_kind)) {
+      *msg = "lstm_input_concat is built in the wave-private dense kernel: S = H in {32, 64, 128}, dense_kernel not DGC_DENSE_TILE";
+      return DGC_ERR_UNSUPPORTED;
+    }
+  }
   const bool two = d.n_struct_layers == 2;
   if (!fits(two ? d.S : d.F, d.S, d.H, d.time_kind) || (two && !fits(d.F, d.S, 0, DGC_TIME_NONE))) {
     *msg = "these dimensions need the workgroup-tile kernel, whose tile holds max(F rounded up to 8, S, H) <= 304 columns";
@@ -571,7 +583,7 @@ dgc_status_t build_layer(dgc_layer* L, const dgc_graph_t* graph, hipStream_t st)
   }
   if (d.time_kind != DGC_TIME_NONE) {
     const int32_t gH = (d.time_kind == DGC_TIME_LSTM ? 4 : 3) * d.H;
-    if ((rc = add_param(L, "rnn.weight_ih", gH, d.S, st)) != DGC_OK) return rc;
+    if ((rc = add_param(L, "rnn.weight_ih", gH, d.lstm_input_concat ? 2 * d.S : d.S, st)) != DGC_OK) return rc;
     if ((rc = add_param(L, "rnn.weight_hh", gH, d.H, st)) != DGC_OK) return rc;
     if ((rc = add_param(L, "rnn.bias_ih", gH, 0, st)) != DGC_OK) return rc;
     if ((rc = add_param(L, "rnn.bias_hh", gH, 0, st)) != DGC_OK) return rc;
@@ -605,6 +617,7 @@ SpmmArgs spmm_args(dgc_layer* L, const float* fresh, int64_t ld_fresh, const flo
   a.fresh = fresh; a.ld_fresh = ld_fresh;
   a.stale = stale; a.ld_stale = ld_stale;
   a.halo = nullptr; a.ld_halo = 0; a.col_local = nullptr;
+  a.col_signed = L->lab.built ? L->lab.col_signed : nullptr;
   a.F = F;
   a.long_nnz = L->long_nnz; a.part_nnz = L->part_nnz;
   a.partial = L->d_partial;
@@ -849,6 +862,14 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* L, const void* Xv, int64_t ldx, cons
     da.bih = L->params["rnn.bias_ih"].raw; da.bhh = L->params["rnn.bias_hh"].raw;
   }
   da.H0 = H0; da.reset_mask = reset_mask; da.Y = Y; da.ldy = ldy; da.HN = HN;
+  if (d.lstm_input_concat) { da.X2 = L->d_Z1; da.ldx2 = d.S; }   // the LSTM reads [first layer's output, second layer's output]
+  if (L->lab.built) {
+    // generated chunks: a vertex's run of equal labels is a sequence; its state enters from H0's row
+    // of (t, i) and leaves to HN's row of (t, i)
+    if (reset_mask) return fail(DGC_ERR_INVALID_ARG, "with generated chunks reset_mask must be NULL");
+    if (d.time_kind != DGC_TIME_NONE) { da.seq_in = L->lab.seq_in; da.seq_out = L->lab.seq_out; }
+    da.total_state_rows = (int64_t)L->T * L->N;      // one state row per (t, i)
+  }
   if (L->tf.built) {
     // temporal fusion: the dense + recurrent kernels over the lanes of every chunk with the
     // packing's reset flags, outputs back to their (snapshot, vertex) rows
@@ -861,6 +882,7 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* L, const void* Xv, int64_t ldx, cons
     // row of HN: the states travel through the slot tables; H0 / HN keep the layout they have without fusion
     da.reset_mask = nullptr; da.seq_in = tf.seq_in; da.seq_out = tf.seq_out;
     da.total_state_rows = L->total_state_rows;
+    da.x2_map = tf.slot_row;      // a slot's row of the first layer's output
     if (HN) tf_carry(tf.seq_len, L->total_state_rows, d.time_kind == DGC_TIME_LSTM ? 2 : 1, d.H, H0, HN, st);
     if (tf.n_lanes > 0 && !launch_dense(da, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
     tf_scatter(tf.Yv, out_dim, tf.slot_row, (int64_t)tf.Lmax * tf.n_lanes, Y, ldy, st);
@@ -1038,6 +1060,7 @@ dgc_status_t dgc_layer_set_presence(dgc_layer_t* L, const uint8_t* present, void
   if (d.struct_kind != DGC_STRUCT_GCN || d.time_kind == DGC_TIME_NONE)
     return fail(DGC_ERR_UNSUPPORTED, "temporal fusion needs a GCN layer with a recurrent time encoder");
   if (L->tf.built) return fail(DGC_ERR_STATE, "the presence mask of a layer can be set once");
+  if (L->lab.built) return fail(DGC_ERR_STATE, "temporal fusion is not built for generated chunks");
   TFusion& tf = L->tf;
   const int32_t nc = L->n_chunks;
   const std::vector<ChunkInfo>& ci = L->cinfo_host;
@@ -1120,6 +1143,34 @@ dgc_status_t dgc_layer_set_presence(dgc_layer_t* L, const uint8_t* present, void
   tf.seq_len = d_len;
   dev_free(L, d_lane); dev_free(L, d_off);
   tf.built = true;
+  return DGC_OK;
+}
+
+dgc_status_t dgc_layer_set_labels(dgc_layer_t* L, const int32_t* labels, void* stream) {
+  if (!L) return DGC_ERR_INVALID_ARG;
+  Failer fail{L};
+  const dgc_layer_desc_t& d = L->desc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (!labels) return fail(DGC_ERR_INVALID_ARG, "labels is NULL");
+  if (d.struct_kind != DGC_STRUCT_GCN) return fail(DGC_ERR_UNSUPPORTED, "generated chunks are built for GCN layers");
+  if (d.gather_mode != DGC_GATHER_IN_PLACE)
+    return fail(DGC_ERR_UNSUPPORTED, "generated chunks need gather_mode DGC_GATHER_IN_PLACE");
+  if (L->tf.built) return fail(DGC_ERR_STATE, "temporal fusion is not built for generated chunks");
+  const dgc_chunk_t& c = L->chunks[0];
+  if (L->n_chunks != 1 || c.v_lo != 0 || c.v_hi != L->N || c.t_lo != 0 || c.t_hi != L->T)
+    return fail(DGC_ERR_STATE, "labels need a layer created with the single chunk [0,N) x [0,T)");
+  if ((int64_t)L->T * L->N >= INT32_MAX) return fail(DGC_ERR_UNSUPPORTED, "generated chunks need T*N < 2^31");
+  Labelled& lab = L->lab;
+  if (!lab.col_signed) {
+    DGC_HIP_TRY(dev_alloc(L, &lab.col_signed, L->total_nnz));
+    DGC_HIP_TRY(dev_alloc(L, &lab.seq_in, (int64_t)L->T * L->N));
+    DGC_HIP_TRY(dev_alloc(L, &lab.seq_out, (int64_t)L->T * L->N));
+  }
+  labels_build(L->graph_dev(), L->d_segs, labels, lab.col_signed, lab.seq_in, lab.seq_out, st);
+  DGC_HIP_TRY(hipStreamSynchronize(st));
+  DGC_HIP_TRY(hipGetLastError());
+  lab.built = true;
+  L->forward_done = false;
   return DGC_OK;
 }
 

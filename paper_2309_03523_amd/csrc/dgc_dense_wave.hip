@@ -147,7 +147,9 @@ __device__ __forceinline__ void store_state_t(const DenseArgs& a, int64_t idx, i
 
 // SEQ: the rows of a tile hold several sequences one after the other (temporal fusion with
 // states): states enter and leave through the tables seq_in / seq_out instead of at the window's ends.
-template <int KIND, int NJB, bool SEQ>
+// CAT: the time encoder's input is [X2 row, Z] (2S wide): X2 holds the first structure layer's
+// output of the same (snapshot, vertex); it shares the Z tile in LDS, columns 0..S-1.
+template <int KIND, int NJB, bool SEQ, bool CAT>
 __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dense_wave(DenseArgs a) {
   // LDS, private to this wave (the workgroup is one wave):
   //   zbuf [32][ldz] the Z tile | gbias [4][H] gate biases, pre-summed | zbias [S]
@@ -156,7 +158,9 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
   extern __shared__ __align__(16) float zbuf[];
   constexpr int H = NJB * 32;
   constexpr int NKB = NJB * 4;     // k-blocks of 8 over S or H
-  constexpr int ldz = H + 4;       // +4 floats: float4 accesses of 32 rows spread over the banks
+  constexpr int NKX = CAT ? 2 * NKB : NKB;   // k-blocks of the time encoder's input
+  constexpr int zcol = CAT ? H : 0;          // where Z starts in a row of the tile
+  constexpr int ldz = H + zcol + 4;  // +4 floats: float4 accesses of 32 rows spread over the banks
   float* gbias = zbuf + (KIND == DGC_TIME_NONE ? 0 : kRows * ldz);
   float* zbias = gbias + (KIND == DGC_TIME_NONE ? 0 : 4 * H);
   for (int i = threadIdx.x; i < H; i += kWave) {
@@ -183,7 +187,7 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
   const int lane16 = lane * 16;
   const int K0 = a.K0, nkb0 = (K0 + 7) / 8;
   const WeightStream wsg = make_stream(a.Wg, a.wg_bytes);
-  const WeightStream wsi = make_stream(a.Wih, (int64_t)(KIND == DGC_TIME_LSTM ? 4 : 3) * NJB * NKB * 1024);
+  const WeightStream wsi = make_stream(a.Wih, (int64_t)(KIND == DGC_TIME_LSTM ? 4 : 3) * NJB * NKX * 1024);
   const WeightStream wsh = make_stream(a.Whh, (int64_t)(KIND == DGC_TIME_LSTM ? 4 : 3) * NJB * NKB * 1024);
   const int64_t V = a.total_state_rows;
   const int64_t vrow = ch.v_lo + tile.v0 + row;          // this lane's vertex
@@ -221,6 +225,7 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
 #pragma unroll
   for (int jb = 0; jb < NJB; ++jb) wq[jb] = wsg.frag(lane16, soffg[jb]);
 
+  float4 x2[CAT ? NKB : 1];
   for (int s = 0; s < ch.w; ++s) {
     const int64_t t = ch.t_lo + s;
     const float* mrow = mrow0 + s * mstep;
@@ -229,6 +234,15 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
 #pragma unroll
       for (int i = 0; i < kXAhead; ++i)
         if (i < nkb0) xq[i] = load_x(i);
+    }
+    if constexpr (CAT) {   // the other half of the time encoder's input: arrives during the transform
+      int64_t r2 = t * a.N + vrow;
+      if (a.x2_map) r2 = max(a.x2_map[r2], (int64_t)0);    // an empty slot reads row 0; its output is never used
+      const float* p2 = a.X2 + r2 * a.ldx2 + 4 * half;
+#pragma unroll
+      for (int kb = 0; kb < NKB; ++kb) x2[kb] = *reinterpret_cast<const float4*>(p2 + 8 * kb);
+    }
+    if (s > 0) {
       // h_{t-1} -> Y, issued after the loads above: memory operations retire in order, so loads
       // issued behind these stores would wait for them
       if constexpr (KIND != DGC_TIME_NONE) {
@@ -301,7 +315,7 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
       }
     } else {
 #pragma unroll
-      for (int g = 0; g < NG; ++g) wq[g] = wsi.frag(lane16, (g * NJB) * NKB * 1024);  // gates of column block 0
+      for (int g = 0; g < NG; ++g) wq[g] = wsi.frag(lane16, (g * NJB) * NKX * 1024);  // gates of column block 0
     }
     float4 z[NKB];
 #pragma unroll
@@ -325,7 +339,12 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
     } else {
       // Z -> wave-private LDS tile (frees its registers for the gate accumulators)
 #pragma unroll
-      for (int kb = 0; kb < NKB; ++kb) *reinterpret_cast<float4*>(zbuf + l32 * ldz + 8 * kb + 4 * half) = z[kb];
+      for (int kb = 0; kb < NKB; ++kb) *reinterpret_cast<float4*>(zbuf + l32 * ldz + zcol + 8 * kb + 4 * half) = z[kb];
+      if constexpr (CAT) {
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb)   // rebuilt element by element: a whole-struct copy to LDS kept x2 in scratch memory
+          *reinterpret_cast<float4*>(zbuf + l32 * ldz + 8 * kb + 4 * half) = make_float4(x2[kb].x, x2[kb].y, x2[kb].z, x2[kb].w);
+      }
       __syncthreads();  // one wave: orders the LDS writes before the reads below
       const float* ldsZ = zbuf + l32 * ldz + 4 * half;
 
@@ -336,27 +355,27 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
         floatx16 acc[4];
 #pragma unroll
         for (int g = 0; g < 4; ++g) acc[g] = (floatx16)(0.f);
-        int soff[NG];
+        int soff[NG], soffx[NG];   // hidden-side and input-side fragments of this column block
 #pragma unroll
-        for (int g = 0; g < NG; ++g) soff[g] = (g * NJB + jb) * NKB * 1024;
+        for (int g = 0; g < NG; ++g) { soff[g] = (g * NJB + jb) * NKB * 1024; soffx[g] = (g * NJB + jb) * NKX * 1024; }
         // what follows the hidden-state loop: the next column block's gates, or the next
         // step's transform
         int soff_next[NG];
 #pragma unroll
-        for (int g = 0; g < NG; ++g) soff_next[g] = (g * NJB + jb + 1) * NKB * 1024;
+        for (int g = 0; g < NG; ++g) soff_next[g] = (g * NJB + jb + 1) * NKX * 1024;
         if (jb + 1 == NJB) {
 #pragma unroll
           for (int j2 = 0; j2 < NJB; ++j2) soffg[j2] += a.wg_step_bytes;
         }
         if constexpr (KIND == DGC_TIME_GRU) {
           floatx16 ai[3] = {acc[0], acc[1], acc[2]};   // r, z, input part of n
-          k_loop_lds<3, NKB, 3, 4>(ai, ldsZ, wsi, soff, lane16, wq, wsh, soff);
+          k_loop_lds<3, NKX, 3, 4>(ai, ldsZ, wsi, soffx, lane16, wq, wsh, soff);
           floatx16 ah[3] = {ai[0], ai[1], acc[3]};     // r, z, hidden part of n
           if (jb + 1 < NJB) k_loop_reg<3, NKB, 3, 4>(ah, h, wsh, soff, lane16, wq, wsi, soff_next);
           else k_loop_reg<3, NKB, NJB, 4>(ah, h, wsh, soff, lane16, wq, wsg, soffg);
           acc[0] = ah[0]; acc[1] = ah[1]; acc[2] = ai[2]; acc[3] = ah[2];
         } else {
-          k_loop_lds<4, NKB, 4, 4>(acc, ldsZ, wsi, soff, lane16, wq, wsh, soff);
+          k_loop_lds<4, NKX, 4, 4>(acc, ldsZ, wsi, soffx, lane16, wq, wsh, soff);
           if (jb + 1 < NJB) k_loop_reg<4, NKB, 4, 4>(acc, h, wsh, soff, lane16, wq, wsi, soff_next);
           else k_loop_reg<4, NKB, NJB, 4>(acc, h, wsh, soff, lane16, wq, wsg, soffg);
         }
@@ -427,14 +446,22 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
 
 template <int KIND, int NJB>
 bool launch_w(const DenseArgs& a, hipStream_t st, std::string* why) {
-  (void)why;
-  constexpr int ldz = NJB * 32 + 4;
-  const size_t lds = sizeof(float) * ((KIND == DGC_TIME_NONE ? 0 : kRows * ldz + 4 * NJB * 32) + NJB * 32);
+  constexpr bool kLstm = KIND == DGC_TIME_LSTM, kRnn = KIND != DGC_TIME_NONE;
+  const bool cat = a.X2 != nullptr;
+  if (cat && !kLstm) {
+    if (why) *why = "the concatenated input is built for the LSTM";
+    return false;
+  }
+  const int ldz = NJB * 32 * (cat ? 2 : 1) + 4;
+  const size_t lds = sizeof(float) * ((kRnn ? kRows * ldz + 4 * NJB * 32 : 0) + NJB * 32);
   if (a.n_tiles32 > 0) {
-    if (KIND != DGC_TIME_NONE && a.seq_in)
-      hipLaunchKernelGGL((k_dense_wave<KIND, NJB, KIND != DGC_TIME_NONE>), (unsigned)a.n_tiles32, kWave, lds, st, a);
-    else
-      hipLaunchKernelGGL((k_dense_wave<KIND, NJB, false>), (unsigned)a.n_tiles32, kWave, lds, st, a);
+    auto go = [&](auto kernel) {
+      hipLaunchKernelGGL(kernel, (unsigned)a.n_tiles32, kWave, lds, st, a);
+    };
+    if (kRnn && a.seq_in && cat) go(k_dense_wave<KIND, NJB, kRnn, kLstm>);
+    else if (kRnn && a.seq_in) go(k_dense_wave<KIND, NJB, kRnn, false>);
+    else if (cat) go(k_dense_wave<KIND, NJB, false, kLstm>);
+    else go(k_dense_wave<KIND, NJB, false, false>);
   }
   return true;
 }

@@ -108,6 +108,7 @@ struct SpmmArgs {
   const float* stale; int64_t ld_stale;   // [T,N,ld]: cache rows (IN_PLACE)
   const float* halo; int64_t ld_halo;     // packed halo rows (STAGED) or nullptr
   const int32_t* col_local;               // STAGED only
+  const int32_t* col_signed;              // generated chunks: stored columns marked j (fresh) / ~j (cache), or nullptr
   int32_t F;
   int32_t long_nnz, part_nnz;
   float* partial;             // [n_long][ldm] scratch for split rows
@@ -148,7 +149,7 @@ struct DenseArgs {
   int64_t wg_bytes;             // size of the packed GCN weights
   int32_t wg_step_bytes;        // distance between consecutive snapshots' packed weights, or 0
   const float* bg;              // [S]
-  const float4* Wih;            // packed [gH][S]
+  const float4* Wih;            // packed [gH][S] ([gH][2S] with X2)
   const float4* Whh;            // packed [gH][H]
   const float* bih; const float* bhh;
   const float* H0;
@@ -162,6 +163,11 @@ struct DenseArgs {
   // only through these tables.
   const int64_t* seq_in;
   const int64_t* seq_out;
+  // Second half of the time encoder's input (the first structure layer's output), or nullptr: the
+  // time encoder then reads [X2 row, Z] and Wih is packed [gH][2S].  Row of (t, v) in X2:
+  // x2_map[t*N + v] (negative: any row, the output is not used), or t*N + v without a map.
+  const float* X2; int64_t ldx2;
+  const int64_t* x2_map;
 };
 // returns false if the (S,H,K0) combination has no kernel
 bool launch_dense(const DenseArgs& a, hipStream_t st, std::string* why);
@@ -300,5 +306,15 @@ void tf_fill(const uint8_t* present, const ChunkInfo* chunks, int32_t n_chunks, 
 void tf_carry(const int32_t* seq_len, int64_t V, int32_t n_state, int32_t H, const float* H0, float* HN, hipStream_t st);
 void tf_scatter(const float* Yv, int32_t out_dim, const int64_t* slot_row, int64_t n_slots, float* Y, int64_t ldy,
                 hipStream_t st);
+
+// ---- generated chunks (dgc_labels.hip)
+struct Labelled {
+  bool built = false;
+  int32_t* col_signed = nullptr;  // [total nnz] see SpmmArgs
+  int64_t* seq_in = nullptr;      // [T*N] see DenseArgs
+  int64_t* seq_out = nullptr;
+};
+void labels_build(const GraphDev& g, const Segment* segs, const int32_t* labels, int32_t* col_signed,
+                  int64_t* seq_in, int64_t* seq_out, hipStream_t st);
 
 }  // namespace dgc

@@ -3,6 +3,7 @@
 //
 //   M[row of (t,i)] = d_i^-1/2 * sum_j d_j^-1/2 * src(t,j)
 //   src(t,j) = fresh[t,j] if j lies in the row's chunk vertex range, else the cache row.
+// (With generated chunks the stored columns come pre-marked instead: j = fresh, ~j = cache row.)
 //
 // HBM/L2-bound work: one wavefront owns one work item (a group of consecutive rows, or one
 // part of a split row).  The 64 lanes span the feature dimension (1, 2 or 4 floats each), so
@@ -64,8 +65,13 @@ struct RowCtx {
   bool skip_stale;          // neighbours outside the range contribute nothing (input-gradient pass)
 };
 
+// MODE of the neighbour lookup
+constexpr int kInPlace = 0;   // by the segment's vertex range, rows read where they are
+constexpr int kStaged = 1;    // local slots: fresh rows, then the segment's gathered halo rows
+constexpr int kSigned = 2;    // pre-marked columns (j fresh, ~j cache), rows read where they are
+
 // acc += sum over stored non-zeros e in [ea, eb) of dinv[col] * src row, features fi..fi+VEC-1.
-template <int VEC, bool STAGED>
+template <int VEC, int MODE>
 __device__ __forceinline__ void accumulate_edges(const RowCtx& c, int64_t ea, int64_t eb, int lane, int fi,
                                                  bool active, float (&acc)[VEC]) {
   for (int64_t eb0 = ea; eb0 < eb; eb0 += kWave) {
@@ -74,8 +80,8 @@ __device__ __forceinline__ void accumulate_edges(const RowCtx& c, int64_t ea, in
     float wj = 0.f;
     if (lane < m) {
       j = __builtin_nontemporal_load(c.cj + eb0 + lane);  // streamed once
-      wj = c.dinv_t[j];
-      if constexpr (STAGED) loc = __builtin_nontemporal_load(c.cl + (eb0 - c.e0) + lane);
+      wj = c.dinv_t[(MODE == kSigned && j < 0) ? ~j : j];
+      if constexpr (MODE == kStaged) loc = __builtin_nontemporal_load(c.cl + (eb0 - c.e0) + lane);
     }
     for (int k = 0; k < m; k += kInflight) {
       float v[kInflight][VEC];
@@ -89,13 +95,14 @@ __device__ __forceinline__ void accumulate_edges(const RowCtx& c, int64_t ea, in
           const int jj = __builtin_amdgcn_readlane(j, k + u);
           w[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wj), k + u));
           const float* src;
-          if constexpr (STAGED) {
+          if constexpr (MODE == kStaged) {
             const int ll = __builtin_amdgcn_readlane(loc, k + u);
             const int64_t nv = c.v_hi - c.v_lo;
             src = ll < nv ? c.fresh_t + (c.v_lo + ll) * c.ld_fresh : c.stale_t + (ll - nv) * c.ld_stale;
           } else {
-            const bool in = jj >= c.v_lo && jj < c.v_hi;   // wave-uniform
-            src = in ? c.fresh_t + (int64_t)jj * c.ld_fresh : c.stale_t + (int64_t)jj * c.ld_stale;
+            const bool in = MODE == kSigned ? jj >= 0 : (jj >= c.v_lo && jj < c.v_hi);   // wave-uniform
+            const int64_t col = (MODE == kSigned && !in) ? ~jj : jj;
+            src = in ? c.fresh_t + col * c.ld_fresh : c.stale_t + col * c.ld_stale;
             if (!in && c.skip_stale) { w[u] = 0.f; continue; }
           }
           if (active) vload<VEC>(v[u], src + fi);
@@ -109,10 +116,12 @@ __device__ __forceinline__ void accumulate_edges(const RowCtx& c, int64_t ea, in
   }
 }
 
-template <bool STAGED>
+template <int MODE>
 __device__ __forceinline__ RowCtx make_ctx(const SpmmArgs& a, const Segment& sg) {
+  constexpr bool STAGED = MODE == kStaged;
   RowCtx c;
-  c.cj = a.g.colidx[sg.t];
+  // (the marked columns are stored segment after segment; e counts from the snapshot's start)
+  c.cj = MODE == kSigned ? a.col_signed + (sg.nnz_off - sg.e0) : a.g.colidx[sg.t];
   c.cl = STAGED ? a.col_local + sg.nnz_off : nullptr;
   c.dinv_t = a.dinv + (int64_t)sg.t * a.g.N;
   c.fresh_t = a.fresh + (int64_t)sg.t * a.g.N * a.ld_fresh;
@@ -140,7 +149,7 @@ __device__ __forceinline__ void store_row(float* out, int fi, int F, int64_t ldm
 
 // One wave per group of consecutive rows of a segment.  Rows longer than long_nnz are left to
 // the split-row kernels.
-template <int VEC, bool STAGED>
+template <int VEC, int MODE>
 __global__ __launch_bounds__(256) void k_spmm_short(SpmmArgs a) {
   const int lane = threadIdx.x & (kWave - 1);
   const int64_t item = (int64_t)blockIdx.x * (256 / kWave) + (threadIdx.x / kWave);
@@ -149,7 +158,7 @@ __global__ __launch_bounds__(256) void k_spmm_short(SpmmArgs a) {
   const int r0 = uniform(a.work_short[3 * item + 1]);
   const int n = uniform(a.work_short[3 * item + 2]);
   const Segment sg = a.segs[seg];
-  const RowCtx c = make_ctx<STAGED>(a, sg);
+  const RowCtx c = make_ctx<MODE>(a, sg);
   const int64_t* rp = a.g.rowptr[sg.t] + sg.v_lo + r0;
   const int64_t my_rp = lane <= n ? rp[lane] : 0;
   // optional output permutation: row_map[packed row] = row of M to write, < 0 = row not wanted
@@ -166,14 +175,14 @@ __global__ __launch_bounds__(256) void k_spmm_short(SpmmArgs a) {
       float acc[VEC];
 #pragma unroll
       for (int q = 0; q < VEC; ++q) acc[q] = 0.f;
-      accumulate_edges<VEC, STAGED>(c, ea, eb, lane, fi, fi < a.F, acc);
+      accumulate_edges<VEC, MODE>(c, ea, eb, lane, fi, fi < a.F, acc);
       store_row<VEC>(out, fi, a.F, a.ldm, acc, di);
     }
   }
 }
 
 // One wave per part of a split row: unscaled partial sums.
-template <int VEC, bool STAGED>
+template <int VEC, int MODE>
 __global__ __launch_bounds__(256) void k_spmm_long(SpmmArgs a) {
   const int lane = threadIdx.x & (kWave - 1);
   const int64_t item = (int64_t)blockIdx.x * (256 / kWave) + (threadIdx.x / kWave);
@@ -182,7 +191,7 @@ __global__ __launch_bounds__(256) void k_spmm_long(SpmmArgs a) {
   const int row = uniform(a.work_long[4 * item + 1]);
   const int part = uniform(a.work_long[4 * item + 2]);
   const Segment sg = a.segs[seg];
-  const RowCtx c = make_ctx<STAGED>(a, sg);
+  const RowCtx c = make_ctx<MODE>(a, sg);
   const int64_t* rp = a.g.rowptr[sg.t] + sg.v_lo + row;
   const int64_t ra = rp[0], rb = rp[1];
   const int64_t ea = ra + (int64_t)part * a.part_nnz;
@@ -193,7 +202,7 @@ __global__ __launch_bounds__(256) void k_spmm_long(SpmmArgs a) {
     float acc[VEC];
 #pragma unroll
     for (int q = 0; q < VEC; ++q) acc[q] = 0.f;
-    accumulate_edges<VEC, STAGED>(c, ea, eb, lane, fi, fi < a.F, acc);
+    accumulate_edges<VEC, MODE>(c, ea, eb, lane, fi, fi < a.F, acc);
     store_row<VEC>(out, fi, a.F, a.ldm, acc, 1.0f);
   }
 }
@@ -231,15 +240,17 @@ __global__ __launch_bounds__(256) void k_spmm_long_reduce(SpmmArgs a) {
 
 template <int VEC>
 void launch_spmm_v(const SpmmArgs& a, hipStream_t st) {
-  const bool staged = a.halo != nullptr;
+  const int mode = a.halo != nullptr ? kStaged : a.col_signed != nullptr ? kSigned : kInPlace;
   const unsigned gs = (unsigned)((a.n_short + 3) / 4), gl = (unsigned)((a.n_long + 3) / 4);
   if (gs) {
-    if (staged) hipLaunchKernelGGL((k_spmm_short<VEC, true>), gs, 256, 0, st, a);
-    else hipLaunchKernelGGL((k_spmm_short<VEC, false>), gs, 256, 0, st, a);
+    if (mode == kStaged) hipLaunchKernelGGL((k_spmm_short<VEC, kStaged>), gs, 256, 0, st, a);
+    else if (mode == kSigned) hipLaunchKernelGGL((k_spmm_short<VEC, kSigned>), gs, 256, 0, st, a);
+    else hipLaunchKernelGGL((k_spmm_short<VEC, kInPlace>), gs, 256, 0, st, a);
   }
   if (gl) {
-    if (staged) hipLaunchKernelGGL((k_spmm_long<VEC, true>), gl, 256, 0, st, a);
-    else hipLaunchKernelGGL((k_spmm_long<VEC, false>), gl, 256, 0, st, a);
+    if (mode == kStaged) hipLaunchKernelGGL((k_spmm_long<VEC, kStaged>), gl, 256, 0, st, a);
+    else if (mode == kSigned) hipLaunchKernelGGL((k_spmm_long<VEC, kSigned>), gl, 256, 0, st, a);
+    else hipLaunchKernelGGL((k_spmm_long<VEC, kInPlace>), gl, 256, 0, st, a);
     hipLaunchKernelGGL((k_spmm_long_reduce<VEC>), gl, 256, 0, st, a);
   }
 }

@@ -24,7 +24,8 @@ class DeviceWorkload:
         self.layer = DgcLayer(self.rowptr, self.colidx, g.N, wl.chunks, F=wl.F, S=wl.S, H=wl.H,
                               time_kind=wl.time_kind, n_struct_layers=wl.n_struct_layers,
                               act_hidden=act_hidden, act_out=act_out, gather_mode=gather_mode,
-                              validate_level=validate_level, struct_kind=struct_kind, **layer_kw)
+                              validate_level=validate_level, struct_kind=struct_kind,
+                              lstm_input_concat=bool(wl.notes.get("input_concat", False)), **layer_kw)
         self.layer.set_params(wl.params)
 
         def up(a, ld=None):

@@ -341,13 +341,15 @@ def config2(seed: int = 0, scale: float = 1.0, random_bias: bool = False) -> Wor
                                "config2" if scale == 1.0 else f"config2@{scale:g}", random_bias)
 
 
-def config3(seed: int = 0, scale: float = 1.0, windows: int = 1, random_bias: bool = False) -> Workload:
+def config3(seed: int = 0, scale: float = 1.0, windows: int = 1, random_bias: bool = False,
+            input_concat: bool = False) -> Workload:
     """Large 2-layer GCN + LSTM: N = 2,000,000 * scale vertices, mean degree 20 with tail exponent
     2.0, per-snapshot density varying 10x along a sinusoid of period 128 snapshots times
     (1 + 0.1 N(0,1)), F = 172, S = H = 128, windows of 32 snapshots x 64 uneven vertex ranges;
     an edge keeps both endpoints inside one vertex range with probability 0.85.  The full
     config (128 snapshots) is run one 32-snapshot window at a time (memory-capped fusion,
-    Section 5.1.1); `windows` says how many of them this workload holds."""
+    Section 5.1.1); `windows` says how many of them this workload holds.  input_concat: the LSTM
+    reads both GCN layers' outputs (256 wide), as the MPNN-LSTM of Section 6 does."""
     N = max(256, int(2_000_000 * scale))
     T = 32 * windows
     F, S, H = 172, 128, 128
@@ -372,7 +374,8 @@ def config3(seed: int = 0, scale: float = 1.0, windows: int = 1, random_bias: bo
     C1 = _normal_f32(stream(seed, "cache1"), (T, N, S))
     wl = Workload("config3" if scale == 1.0 else f"config3@{scale:g}", graph, chunks, F, S, H, "lstm", 2, X, C, C1,
                   _h0_for(chunks, H, "lstm", stream(seed, "h0")),
-                  layer_params(seed, F, S, H, "lstm", 2, random_bias))
+                  layer_params(seed, F, S, H, "lstm", 2, random_bias, input_concat=input_concat),
+                  notes={"input_concat": True} if input_concat else {})
     return wl
 
 

@@ -33,7 +33,8 @@ def test_exports_every_declared_symbol(lib):
 
 def _create(lib, desc_kw=None, chunks=((0, 4, 0, 2),), T=2, N=4, null_snapshot=False):
     d = dict(struct_kind=0, n_struct_layers=1, time_kind=1, dtype=0, F=8, S=32, H=32, act_hidden=0, act_out=0,
-             gather_mode=0, validate_level=0, rows_per_group=0, long_nnz=0, part_nnz=0, dense_kernel=0, heads=0)
+             gather_mode=0, validate_level=0, rows_per_group=0, long_nnz=0, part_nnz=0, dense_kernel=0, heads=0,
+             lstm_input_concat=0)
     d.update(desc_kw or {})
     desc = binding.DescT(*[d[n] for n, _ in binding.DescT._fields_])
     fake = 0x1000  # never dereferenced: every check below fails before the device is used
@@ -65,6 +66,14 @@ def test_create_rejects_bad_descriptors(lib):
     assert _create(lib, dict(gat), chunks=((0, 5, 0, 2),))[0] == 3
     assert _create(lib, dict(rows_per_group=64))[0] == 1
     assert _create(lib, null_snapshot=True)[0] == 1
+    # the LSTM reading both GCN layers' outputs: two layers, LSTM, the wave-private kernel's sizes
+    cat = dict(lstm_input_concat=1, n_struct_layers=2, time_kind=2)
+    assert _create(lib, dict(cat, time_kind=1))[0] == 1
+    assert _create(lib, dict(cat, n_struct_layers=1))[0] == 1
+    assert _create(lib, dict(cat, lstm_input_concat=2))[0] == 1
+    assert _create(lib, dict(cat, S=96, H=96))[0] == 4
+    assert _create(lib, dict(cat, dense_kernel=1))[0] == 4
+    assert _create(lib, dict(gat, lstm_input_concat=1))[0] == 1
 
 
 def test_create_rejects_bad_chunks(lib):
