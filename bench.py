@@ -29,7 +29,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config2s", "config2tf", "config3w", "config3wc", "config4s", "config4", "config5s", "config5", "stale", "fusion", "chunkgen"])
+    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config2s", "config2tf", "config3w", "config3wc", "config4s", "config4", "config5s", "config5", "stale", "fusion", "chunkgen", "config2lp"])
     ap.add_argument("--gather-mode", default="in_place", choices=["in_place", "staged"])
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -485,6 +485,134 @@ def fusion_main(args):
     print(json.dumps(out))
 
 
+def labelled_main(args):
+    """Config 2 with GENERATED chunks (Sections 4.1, 5.2): the device label propagation partitions
+    the (snapshot, vertex) pairs, the layer runs over those chunks - a neighbour with another
+    label is read from the cache, a vertex whose previous snapshot carries another label starts
+    from the state cache, states that leave a chunk are written out.  One step = one forward."""
+    import numpy as np
+    import torch
+    from paper_2309_03523_amd import binding, synth
+    from paper_2309_03523_amd.runner import DeviceWorkload
+    synth.progress = lambda msg: print(msg, file=sys.stderr, flush=True)
+    w_s, w_t, cap, max_iters = 1, 1, 50_000, 1000        # one structure layer : one time layer; config 2's mean chunk size
+    t0 = time.perf_counter()
+    wl = synth.config2(args.seed)
+    rect = wl.chunks
+    g = wl.graph
+    T, N = g.T, g.N
+    wl.chunks = np.array([[0, N, 0, T]], np.int64)
+    wl.H0 = None
+    Hc_host = synth.stream(args.seed, "state-cache").standard_normal(size=(T * N, wl.H), dtype=np.float32) * np.float32(0.1)
+    t_gen = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    dw = DeviceWorkload(wl, gather_mode="in_place")
+    layer = dw.layer
+    torch.cuda.synchronize()
+    t_create = time.perf_counter() - t0
+    labels = torch.empty(T * N, dtype=torch.int32, device="cuda")
+    t0 = time.perf_counter()
+    iters, conv = binding.chunk_generate(dw.rowptr, dw.colidx, N, w_s=w_s, w_t=w_t, cap=cap, max_iters=max_iters, labels=labels)
+    torch.cuda.synchronize()
+    t_labels = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    layer.set_labels(labels)
+    t_tables = time.perf_counter() - t0
+    Hc = torch.from_numpy(Hc_host).cuda()
+    HN = torch.full((T * N, wl.H), float("nan"), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        layer.forward(dw.X, dw.C, dw.Y, H0=Hc, HN=HN, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    marks[0].record(stream)
+    for k in range(args.steps):
+        step()
+        marks[k + 1].record(stream)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    per = np.array([marks[k].elapsed_time(marks[k + 1]) for k in range(args.steps)])
+    layer.set_profiling(True)
+    stage = np.zeros(13, np.float64)
+    for _ in range(3):
+        step()
+        stage += layer.stage_times()
+    stage /= 3
+    layer.set_profiling(False)
+    rows = T * N
+    ms = 1e3 * elapsed / args.steps
+    # what the partition costs: neighbours and temporal neighbours read from the caches
+    lab = labels.cpu().numpy().reshape(T, N)
+    rect_lab = np.zeros((T, N), np.int32)
+    for k, (a, b, t_lo, t_hi) in enumerate(rect.tolist()):
+        rect_lab[t_lo:t_hi, a:b] = k
+
+    def cut(l):
+        stale_e = sum(int((l[t][np.repeat(np.arange(N), np.diff(sn.rowptr))] != l[t][sn.col]).sum()) for t, sn in enumerate(g.snaps))
+        stale_t = N + int((l[1:] != l[:-1]).sum())
+        return stale_e, stale_t
+
+    se, st_ = cut(lab)
+    re_, rt = cut(rect_lab)
+    nnz = g.nnz
+    sizes = np.bincount(lab.reshape(-1))
+    sizes = sizes[sizes > 0]
+    fl = flops_per_row(wl)
+    dense_flops = (fl["transform"] + fl["rnn"]) * rows
+    dense_ms, agg_ms = float(stage[3]), float(stage[0])
+    achieved = dense_flops / (dense_ms * 1e-3) / 1e12
+    agg_bytes = rows * (wl.F * 4) + nnz * 4 + rows * 8 + rows * (wl.F * 4)
+    traffic = measured_traffic("config2lp", "in_place")
+    out = {"metric": "snapshot-vertex embeddings/s per DGNN layer", "value": rows * args.steps / elapsed, "unit": "embeddings/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "config2 (32 snapshots x 100k vertices, F=S=H=128, GCN+GRU) over chunks generated by the "
+                                  f"device label propagation (w_spatial = {w_s}, w_temporal = {w_t}, size limit {cap})",
+                      "rows": rows, "nnz": nnz, "gather_mode": "in_place", "pass": "forward"},
+           "roofline": {"kernel": "k_dense_wave<GRU, SEQ> (GCN transform + time encoder over every vertex's label runs)",
+                        "bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                        "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic.get("dense"),
+                        "flops_per_launch": dense_flops, "ms_per_launch": dense_ms},
+           "roofline_aggregation": {"kernel": "k_spmm_short + k_spmm_long + k_spmm_long_reduce (pre-marked columns)",
+                                    "bound": "hbm", "achieved": agg_bytes / (agg_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                                    "unit": "GB/s", "frac": agg_bytes / (agg_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                    "traffic": traffic.get("aggregation"), "bytes_per_launch": agg_bytes,
+                                    "ms_per_launch": agg_ms, "gather_traffic_GBs": nnz * wl.F * 4 / (agg_ms * 1e-3) / 1e9},
+           "stage_ms": {"aggregate0": agg_ms, "dense_rnn": dense_ms},
+           "device_ms_per_step": {"median": float(np.median(per)), "min": float(per.min()), "max": float(per.max())},
+           "chunks": {"count": int(sizes.size), "largest": int(sizes.max()), "median": float(np.median(sizes)),
+                      "iterations": iters, "converged": bool(conv),
+                      "stale_neighbour_reads": se, "stale_neighbour_fraction": se / nnz,
+                      "stale_state_reads": st_, "stale_state_fraction": st_ / rows,
+                      "rectangular_64_chunks": {"stale_neighbour_fraction": re_ / nnz, "stale_state_fraction": rt / rows}},
+           "setup_s": {"generate": t_gen, "upload_create_pack": t_create, "label_propagation": t_labels,
+                       "label_tables": t_tables}}
+    if not args.no_cpu_baseline:
+        from oracle import labelled
+        rng = synth.stream(args.seed, "bench-sample")
+        Y_gpu = dw.Y.cpu().numpy()
+        n_v, done, dt, errs = 16, 0, 0.0, []
+        while dt < 12.0 and done < 4096:      # growing seeded samples of vertices, all 32 snapshots each
+            vs = np.sort(rng.choice(N, size=n_v, replace=False))
+            t0 = time.perf_counter()
+            want, _ = labelled.forward(g, lab, wl.params, wl.X, wl.C, time_kind=wl.time_kind, Hc=Hc_host, vertices=vs)
+            dt += time.perf_counter() - t0
+            done += n_v
+            tau = 0.1 * float(np.sqrt(np.mean(want * want)))
+            errs.append(float(np.max(np.abs(Y_gpu[:, vs] - want) / np.maximum(np.abs(want), tau))))
+            n_v = min(2 * n_v, 1024)
+        out["cpu_baseline"] = {"value": done * T / dt, "unit": "embeddings/s", "cores": 1, "kind": "oracle",
+                               "sample": f"{done} seeded random vertices, all {T} snapshots = {done * T} rows, {dt:.1f} s "
+                                         "(plain Python / NumPy loops over rows and edges)",
+                               "gpu_max_rel_err_on_sample": max(errs)}
+    print(json.dumps(out))
+
+
 def chunkgen_main(args):
     """Chunk generation by weighted label propagation (Section 4.1) on config 2's graph: one step =
     one whole generation (all iterations until no label changes)."""
@@ -571,6 +699,12 @@ def main():
             print("bench.py needs a GPU", file=sys.stderr)
             sys.exit(2)
         chunkgen_main(args)
+        return
+    if args.workload == "config2lp":
+        if not torch.cuda.is_available():
+            print("bench.py needs a GPU", file=sys.stderr)
+            sys.exit(2)
+        labelled_main(args)
         return
     if args.workload in ("stale", "fusion"):
         if not torch.cuda.is_available():

@@ -26,36 +26,53 @@ import numpy as np
 from .tfusion import gru_step, lstm_step
 
 
+def aggregate_row(graph, labels: np.ndarray, fresh: np.ndarray, stale: np.ndarray, t: int, i: int) -> np.ndarray:
+    """Row (t, i): sum_j (d_i d_j)^-1/2 * (fresh[t,j] if same label else stale[t,j]), float64."""
+    sn = graph.snaps[t]
+    d_i = float(sn.rowptr[i + 1] - sn.rowptr[i])
+    acc = np.zeros(fresh.shape[2])
+    for j in sn.col[sn.rowptr[i]:sn.rowptr[i + 1]]:
+        d_j = float(sn.rowptr[j + 1] - sn.rowptr[j])
+        src = fresh[t, j] if labels[t, j] == labels[t, i] else stale[t, j]
+        acc += src.astype(np.float64) / np.sqrt(d_i * d_j)
+    return acc
+
+
 def aggregate(graph, labels: np.ndarray, fresh: np.ndarray, stale: np.ndarray) -> np.ndarray:
-    """[T,N,F] float64: sum_j (d_i d_j)^-1/2 * (fresh[t,j] if same label else stale[t,j])."""
+    """All rows, [T,N,F] float64."""
     T, N = labels.shape
     out = np.zeros((T, N, fresh.shape[2]))
-    for t, sn in enumerate(graph.snaps):
-        deg = np.diff(sn.rowptr).astype(np.float64)
+    for t in range(T):
         for i in range(N):
-            acc = np.zeros(fresh.shape[2])
-            for j in sn.col[sn.rowptr[i]:sn.rowptr[i + 1]]:
-                src = fresh[t, j] if labels[t, j] == labels[t, i] else stale[t, j]
-                acc += src.astype(np.float64) / np.sqrt(deg[i] * deg[j])
-            out[t, i] = acc
+            out[t, i] = aggregate_row(graph, labels, fresh, stale, t, i)
     return out
 
 
 def forward(graph, labels, params: dict, X, C, *, time_kind: str = "gru", n_struct_layers: int = 1,
-            C1=None, Hc=None, act_hidden: str = "relu", act_out: str = "none"):
+            C1=None, Hc=None, act_hidden: str = "relu", act_out: str = "none", vertices=None):
     """Returns Y [T,N,out] float64 and HN [n_state*T*N, H] (NaN where no state leaves a chunk;
-    None without a time encoder)."""
+    None without a time encoder).  vertices (one structure layer only): evaluate just these
+    vertices, all snapshots; Y is then [T, len(vertices), out] and HN is not returned."""
     labels = np.asarray(labels).reshape(graph.T, graph.N)
     T, N = labels.shape
     P = {k: np.asarray(v, np.float64) for k, v in params.items()}
+    idx = list(range(N)) if vertices is None else [int(v) for v in vertices]
 
     def act(a, kind):
         return np.maximum(a, 0.0) if kind == "relu" else a
 
-    M = aggregate(graph, labels, np.asarray(X), np.asarray(C))
+    def rows(fresh, stale):
+        M = np.zeros((T, len(idx), fresh.shape[2]))
+        for k, i in enumerate(idx):
+            for t in range(T):
+                M[t, k] = aggregate_row(graph, labels, fresh, stale, t, i)
+        return M
+
+    M = rows(np.asarray(X), np.asarray(C))
     if n_struct_layers == 2:
+        assert vertices is None      # the second layer needs the first one's output of every neighbour
         Z1 = act(M @ P["gcn0.weight"].T + P["gcn0.bias"], act_hidden)
-        M = aggregate(graph, labels, Z1, np.asarray(C1))
+        M = rows(Z1, np.asarray(C1))
         Z = act(M @ P["gcn1.weight"].T + P["gcn1.bias"], act_out)
     else:
         Z = act(M @ P["gcn0.weight"].T + P["gcn0.bias"], act_out)
@@ -64,20 +81,20 @@ def forward(graph, labels, params: dict, X, C, *, time_kind: str = "gru", n_stru
     H = P["rnn.weight_hh"].shape[1]
     lstm = time_kind == "lstm"
     V = T * N
-    Y = np.zeros((T, N, H))
-    HN = np.full(((2 if lstm else 1) * V, H), np.nan)
-    for i in range(N):
+    Y = np.zeros((T, len(idx), H))
+    HN = np.full(((2 if lstm else 1) * V, H), np.nan) if vertices is None else None
+    for k, i in enumerate(idx):
         h = c = None
         for t in range(T):
             if t == 0 or labels[t - 1, i] != labels[t, i]:      # the temporal neighbour is in another chunk
                 h = np.zeros((1, H)) if Hc is None else np.asarray(Hc[t * N + i], np.float64)[None]
-                c = np.zeros((1, H)) if Hc is None else np.asarray(Hc[V + t * N + i] if lstm else Hc[0] * 0, np.float64)[None]
+                c = np.zeros((1, H)) if (Hc is None or not lstm) else np.asarray(Hc[V + t * N + i], np.float64)[None]
             if lstm:
-                h, c = lstm_step(P, Z[t, i][None], h, c)
+                h, c = lstm_step(P, Z[t, k][None], h, c)
             else:
-                h = gru_step(P, Z[t, i][None], h)
-            Y[t, i] = h[0]
-            if t == T - 1 or labels[t + 1, i] != labels[t, i]:
+                h = gru_step(P, Z[t, k][None], h)
+            Y[t, k] = h[0]
+            if HN is not None and (t == T - 1 or labels[t + 1, i] != labels[t, i]):
                 HN[t * N + i] = h[0]
                 if lstm:
                     HN[V + t * N + i] = c[0]

@@ -111,3 +111,14 @@ def test_label_of_the_right_snapshot_decides():
         if t >= 1:
             own = np.diag(np.diag(A)) @ X[t] + (A - np.diag(np.diag(A))) @ C[t]
             assert np.abs(M[t][4] - own[4]).max() < 1e-12
+
+
+def test_vertex_subset_equals_full():
+    wl = synth.random_small(15, T, N, F, S, S, 3.0, [[0, N, 0, T]], "gru")
+    rng = np.random.default_rng(2)
+    lab = rng.integers(0, 4, (T, N))
+    Hc = rng.standard_normal((T * N, S))
+    full, _ = labelled.forward(wl.graph, lab, wl.params, wl.X, wl.C, time_kind="gru", Hc=Hc)
+    sub, hn = labelled.forward(wl.graph, lab, wl.params, wl.X, wl.C, time_kind="gru", Hc=Hc, vertices=[3, 17, 30])
+    assert hn is None
+    np.testing.assert_array_equal(sub, full[:, [3, 17, 30]])
