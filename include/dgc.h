@@ -107,7 +107,8 @@ typedef struct {
   int32_t act_out;         /* activation after the last GCN layer                            */
   int32_t gather_mode;     /* DGC_GATHER_*                                                   */
   int32_t validate_level;  /* 0: O(chunks) checks; 1: also O(nnz) checks of the CSR contract */
-  int32_t rows_per_group;  /* work list: rows per group (0 = default 16, at most 32)         */
+  int32_t rows_per_group;  /* work list: rows per group, at most 32 (0 = default: 16, halved
+                              down to 1 while the batch has fewer than 8192 groups)          */
   int32_t long_nnz;        /* work list: rows longer than this are split (0 = default 1024)  */
   int32_t part_nnz;        /* work list: non-zeros per part of a split row (0 = default 512) */
   int32_t dense_kernel;    /* DGC_DENSE_*                                                    */

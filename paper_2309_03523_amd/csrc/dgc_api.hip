@@ -677,7 +677,15 @@ dgc_status_t dgc_layer_create(const dgc_layer_desc_t* desc, const dgc_graph_t* g
   L->desc = *desc;
   L->T = graph->T; L->N = graph->N; L->n_chunks = n_chunks;
   L->chunks.assign(chunks, chunks + n_chunks);
-  if (desc->rows_per_group) L->rows_per_group = desc->rows_per_group;
+  if (desc->rows_per_group) {
+    L->rows_per_group = desc->rows_per_group;
+  } else {
+    // default 16 rows per wave; a small batch gets shorter groups (8, 4, 2, 1) until it makes at
+    // least 8192 work items, so that its rows spread over the chip instead of queueing in few waves
+    int64_t rows = 0;
+    for (int32_t k = 0; k < n_chunks; ++k) rows += (chunks[k].v_hi - chunks[k].v_lo) * (int64_t)(chunks[k].t_hi - chunks[k].t_lo);
+    while (L->rows_per_group > 1 && rows / L->rows_per_group < 8192) L->rows_per_group >>= 1;
+  }
   if (desc->long_nnz) L->long_nnz = desc->long_nnz;
   if (desc->part_nnz) L->part_nnz = desc->part_nnz;
   rc = build_layer(L, graph, static_cast<hipStream_t>(stream));
