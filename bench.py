@@ -878,7 +878,7 @@ def main():
         out["hip_graph_replay_ms_per_step"] = graph_ms
     if tfuse:
         out["temporal_fusion"] = tfuse
-        out["roofline"]["kernel"] += " over the lanes, incl. the scatter of the outputs back to their rows"
+        out["roofline"]["kernel"] += " over the lanes, every slot's output stored straight to its row"
     if not args.no_cpu_baseline:
         Y_gpu = dw.Y.cpu().numpy()
         if tfuse:

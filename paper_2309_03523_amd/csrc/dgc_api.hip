@@ -885,7 +885,8 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* L, const void* Xv, int64_t ldx, cons
     if (reset_mask) return fail(DGC_ERR_INVALID_ARG, "with temporal fusion reset_mask must be NULL");
     da.tiles = tf.tiles_v; da.n_tiles = tf.n_tiles_v; da.tiles32 = tf.tiles32_v; da.n_tiles32 = tf.n_tiles32_v;
     da.chunks = tf.chunks_v; da.N = tf.n_lanes;
-    da.M = tf.Mv; da.Y = tf.Yv; da.ldy = out_dim;
+    da.M = tf.Mv;
+    da.y_map = tf.slot_row;       // a slot's output goes straight to its (snapshot, vertex) row of Y
     // every sequence starts from its own row of H0 (zero without H0) and leaves its final state in its
     // row of HN: the states travel through the slot tables; H0 / HN keep the layout they have without fusion
     da.reset_mask = nullptr; da.seq_in = tf.seq_in; da.seq_out = tf.seq_out;
@@ -893,7 +894,6 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* L, const void* Xv, int64_t ldx, cons
     da.x2_map = tf.slot_row;      // a slot's row of the first layer's output
     if (HN) tf_carry(tf.seq_len, L->total_state_rows, d.time_kind == DGC_TIME_LSTM ? 2 : 1, d.H, H0, HN, st);
     if (tf.n_lanes > 0 && !launch_dense(da, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
-    tf_scatter(tf.Yv, out_dim, tf.slot_row, (int64_t)tf.Lmax * tf.n_lanes, Y, ldy, st);
   } else if (!launch_dense(da, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
   if (prof) {
     DGC_HIP_TRY(hipEventRecord(L->ev[4], st));
@@ -1068,6 +1068,7 @@ dgc_status_t dgc_layer_set_presence(dgc_layer_t* L, const uint8_t* present, void
   if (d.struct_kind != DGC_STRUCT_GCN || d.time_kind == DGC_TIME_NONE)
     return fail(DGC_ERR_UNSUPPORTED, "temporal fusion needs a GCN layer with a recurrent time encoder");
   if (L->tf.built) return fail(DGC_ERR_STATE, "the presence mask of a layer can be set once");
+  if ((int64_t)L->T * L->N >= INT32_MAX) return fail(DGC_ERR_UNSUPPORTED, "temporal fusion needs T*N < 2^31");
   if (L->lab.built) return fail(DGC_ERR_STATE, "temporal fusion is not built for generated chunks");
   TFusion& tf = L->tf;
   const int32_t nc = L->n_chunks;
@@ -1142,10 +1143,8 @@ dgc_status_t dgc_layer_set_presence(dgc_layer_t* L, const uint8_t* present, void
   DGC_HIP_TRY(dev_alloc(L, &tf.tiles32_v, tf.n_tiles32_v));
   DGC_HIP_TRY(hipMemcpyAsync(tf.tiles_v, t64.data(), sizeof(DenseTile) * t64.size(), hipMemcpyHostToDevice, st));
   DGC_HIP_TRY(hipMemcpyAsync(tf.tiles32_v, t32.data(), sizeof(DenseTile) * t32.size(), hipMemcpyHostToDevice, st));
-  const int32_t out_dim = d.H;
   DGC_HIP_TRY(dev_alloc(L, &tf.Mv, rows_v * L->ldm));
   DGC_HIP_TRY(hipMemsetAsync(tf.Mv, 0, sizeof(float) * (size_t)std::max<int64_t>(rows_v * L->ldm, 1), st));  // empty slots stay zero
-  DGC_HIP_TRY(dev_alloc(L, &tf.Yv, n_slots * out_dim));
   DGC_HIP_TRY(hipStreamSynchronize(st));
   DGC_HIP_TRY(hipGetLastError());
   tf.seq_len = d_len;

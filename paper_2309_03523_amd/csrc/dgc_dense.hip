@@ -442,7 +442,11 @@ __global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int ld) {
       for_tile_f4(tid, H / 4, [&](int r, int c4) {
         if (r < nrows) {
           const float4 v = *reinterpret_cast<const float4*>(Q + r * ld + 4 * c4);
-          *reinterpret_cast<float4*>(a.Y + (t * a.N + vbase + r) * a.ldy + 4 * c4) = v;
+          int64_t yr = t * a.N + vbase + r;
+          if constexpr (SEQ) {
+            if (a.y_map) yr = a.y_map[yr];     // temporal fusion: the slot's own row of Y, or nowhere
+          }
+          if (yr >= 0) *reinterpret_cast<float4*>(a.Y + yr * a.ldy + 4 * c4) = v;
           if (last) *reinterpret_cast<float4*>(a.HN + (sbase + r) * H + 4 * c4) = v;
           if constexpr (SEQ) {
             const int erow = end_row[r];

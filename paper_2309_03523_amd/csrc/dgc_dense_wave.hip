@@ -226,8 +226,15 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
   for (int jb = 0; jb < NJB; ++jb) wq[jb] = wsg.frag(lane16, soffg[jb]);
 
   float4 x2[CAT ? NKB : 1];
+  // SEQ with a row map: row of Y that the output of the previous / the current step goes to (a table
+  // entry < 0: nowhere; the host checks that the rows of Y number less than 2^31)
+  int yrow_prev = 0, yrow = 0;
   for (int s = 0; s < ch.w; ++s) {
     const int64_t t = ch.t_lo + s;
+    if constexpr (SEQ) {
+      yrow_prev = yrow;
+      if (a.y_map) yrow = (int)a.y_map[t * a.N + vrow];   // used one step later: no wait here
+    }
     const float* mrow = mrow0 + s * mstep;
     auto load_x = [&](int kb) -> float4 { return *reinterpret_cast<const float4*>(mrow + 8 * kb); };
     if (s > 0) {
@@ -247,9 +254,12 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
       // issued behind these stores would wait for them
       if constexpr (KIND != DGC_TIME_NONE) {
         if (valid) {
-          float* y = a.Y + ((t - 1) * a.N + vrow) * a.ldy + 4 * half;
+          const int64_t yr = (SEQ && a.y_map) ? (int64_t)yrow_prev : (t - 1) * a.N + vrow;
+          if (yr >= 0) {
+            float* y = a.Y + yr * a.ldy + 4 * half;
 #pragma unroll
-          for (int kb = 0; kb < NKB; ++kb) *reinterpret_cast<float4*>(y + 8 * kb) = h[kb];
+            for (int kb = 0; kb < NKB; ++kb) *reinterpret_cast<float4*>(y + 8 * kb) = h[kb];
+          }
           if constexpr (SEQ) store_state_t<KIND, NKB>(a, (t - 1) * a.N + vrow, V, H, half, h, c);
         }
       }
@@ -428,9 +438,12 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
 
   if constexpr (KIND != DGC_TIME_NONE) {
     if (valid) {  // the last step's output
-      float* y = a.Y + ((int64_t)(ch.t_lo + ch.w - 1) * a.N + vrow) * a.ldy + 4 * half;
+      const int64_t yr = (SEQ && a.y_map) ? (int64_t)yrow : (int64_t)(ch.t_lo + ch.w - 1) * a.N + vrow;
+      if (yr >= 0) {
+        float* y = a.Y + yr * a.ldy + 4 * half;
 #pragma unroll
-      for (int kb = 0; kb < NKB; ++kb) *reinterpret_cast<float4*>(y + 8 * kb) = h[kb];
+        for (int kb = 0; kb < NKB; ++kb) *reinterpret_cast<float4*>(y + 8 * kb) = h[kb];
+      }
       if constexpr (SEQ) store_state_t<KIND, NKB>(a, (int64_t)(ch.t_lo + ch.w - 1) * a.N + vrow, V, H, half, h, c);
     }
     if (!SEQ && a.HN && valid) {

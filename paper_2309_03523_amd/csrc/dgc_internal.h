@@ -163,6 +163,9 @@ struct DenseArgs {
   // only through these tables.
   const int64_t* seq_in;
   const int64_t* seq_out;
+  // With the sequence tables only: y_map[t*N + v] = row of Y (pitch ldy) that the output of (t, v)
+  // goes to, negative = not stored; nullptr = row t*N + v.
+  const int64_t* y_map;
   // Second half of the time encoder's input (the first structure layer's output), or nullptr: the
   // time encoder then reads [X2 row, Z] and Wih is packed [gH][2S].  Row of (t, v) in X2:
   // x2_map[t*N + v] (negative: any row, the output is not used), or t*N + v without a map.
@@ -295,7 +298,6 @@ struct TFusion {
   DenseTile* tiles_v = nullptr; int64_t n_tiles_v = 0;
   DenseTile* tiles32_v = nullptr; int64_t n_tiles32_v = 0;
   float* Mv = nullptr;            // [rows_v][ldm] aggregated rows in lane order
-  float* Yv = nullptr;            // [Lmax][n_lanes][out_dim]
 };
 void tf_lengths(const uint8_t* present, const ChunkInfo* chunks, int32_t n_chunks, int64_t max_nv, int64_t N,
                 int32_t* seq_len, hipStream_t st);
@@ -304,8 +306,6 @@ void tf_fill(const uint8_t* present, const ChunkInfo* chunks, int32_t n_chunks, 
              int64_t total_rows, int64_t* slot_row, int64_t* row_map, uint8_t* slot_reset, int64_t* seq_in,
              int64_t* seq_out, hipStream_t st);
 void tf_carry(const int32_t* seq_len, int64_t V, int32_t n_state, int32_t H, const float* H0, float* HN, hipStream_t st);
-void tf_scatter(const float* Yv, int32_t out_dim, const int64_t* slot_row, int64_t n_slots, float* Y, int64_t ldy,
-                hipStream_t st);
 
 // ---- generated chunks (dgc_labels.hip)
 struct Labelled {

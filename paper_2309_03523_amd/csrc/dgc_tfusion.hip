@@ -2,11 +2,12 @@
 // snapshots of the window in which a vertex is present) are concatenated into lanes as long as
 // the window instead of being padded, and a reset flag on the first slot of every sequence keeps
 // the state of one sequence out of the next (the paper's mask).  The lanes of a chunk form a
-// "virtual chunk" (lanes x window) that the dense + recurrent kernels process unchanged: the
+// "virtual chunk" (lanes x window) that the dense + recurrent kernels walk like any chunk: the
 // aggregation writes its rows directly in lane order (and skips the rows of absent vertices), the
-// outputs are scattered back after.
+// recurrent kernel takes and leaves states per sequence and stores every slot's output straight to
+// its (snapshot, vertex) row.
 //
-// Device side here: sequence lengths, the slot tables and the row map, the copy of the outputs.  The packing
+// Device side here: sequence lengths, the slot tables and the row map, idle vertices' states.  The packing
 // rule itself (first-fit decreasing, see tf_assign_lanes in dgc_api.hip) is host arithmetic on
 // the lengths.
 #include "dgc_internal.h"
@@ -67,18 +68,6 @@ __global__ void k_tf_fill_i64(int64_t* p, int64_t v, int64_t n) {
   if (i < n) p[i] = v;
 }
 
-// Y[slot_row] = Yv[slot, lane]; one thread per float4
-__global__ void k_tf_scatter(const float* Yv, int32_t out_dim, const int64_t* slot_row, int64_t n_slots, float* Y,
-                             int64_t ldy) {
-  const int64_t q = out_dim / 4;
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= n_slots * q) return;
-  const int64_t sl = idx / q, c4 = idx - sl * q;
-  const int64_t row = slot_row[sl];
-  if (row < 0) return;
-  reinterpret_cast<float4*>(Y + row * ldy)[c4] = reinterpret_cast<const float4*>(Yv + sl * out_dim)[c4];
-}
-
 }  // namespace
 
 void tf_lengths(const uint8_t* present, const ChunkInfo* chunks, int32_t n_chunks, int64_t max_nv, int64_t N,
@@ -105,13 +94,6 @@ void tf_fill(const uint8_t* present, const ChunkInfo* chunks, int32_t n_chunks, 
 void tf_carry(const int32_t* seq_len, int64_t V, int32_t n_state, int32_t H, const float* H0, float* HN, hipStream_t st) {
   const int64_t n = (int64_t)n_state * V * (H / 4);
   if (n > 0) hipLaunchKernelGGL(k_tf_carry, nblocks(n, 256), 256, 0, st, seq_len, V, n_state, H, H0, HN);
-}
-
-void tf_scatter(const float* Yv, int32_t out_dim, const int64_t* slot_row, int64_t n_slots, float* Y, int64_t ldy,
-                hipStream_t st) {
-  if (n_slots > 0)
-    hipLaunchKernelGGL(k_tf_scatter, nblocks(n_slots * (out_dim / 4), 256), 256, 0, st, Yv, out_dim, slot_row, n_slots, Y,
-                       ldy);
 }
 
 }  // namespace dgc
