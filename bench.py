@@ -29,7 +29,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config2s", "config2tf", "config3w", "config3wc", "config4s", "config4", "config5s", "config5", "stale", "fusion", "chunkgen", "config2lp"])
+    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config2s", "config2tf", "config3w", "config3wc", "config3h", "config4s", "config4", "config5s", "config5", "stale", "fusion", "chunkgen", "config2lp"])
     ap.add_argument("--gather-mode", default="in_place", choices=["in_place", "staged"])
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -55,10 +55,11 @@ def make_workload(name: str, seed: int):
         return wl, ("config2 with temporal fusion: every vertex present in a snapshot with its own probability "
                     "U(0.15, 1); sequences concatenated into lanes of 8 (first-fit decreasing) instead of padded, each "
                     "starting from its own row of H0 as in config2")
-    if name in ("config3w", "config3wc"):
+    if name in ("config3w", "config3wc", "config3h"):
         cat = name == "config3wc"
-        return synth.config3(seed, scale=0.125, input_concat=cat), (
-            "config3 at 1/8 of its vertex count, one 32-snapshot window: 250k vertices, 2 GCN layers (172->128->128) + LSTM"
+        scale = 0.5 if name == "config3h" else 0.125
+        return synth.config3(seed, scale=scale, input_concat=cat), (
+            f"config3 at 1/{int(1 / scale)} of its vertex count, one 32-snapshot window: {int(2000 * scale)}k vertices, 2 GCN layers (172->128->128) + LSTM"
             + (" reading both GCN layers' outputs (256 wide)" if cat else "") + ", 64 uneven ranges")
     if name in ("config4s", "config4"):
         scale = 0.125 if name == "config4s" else 1.0

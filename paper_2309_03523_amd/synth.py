@@ -365,6 +365,8 @@ def config3(seed: int = 0, scale: float = 1.0, windows: int = 1, random_bias: bo
     for t in range(T):
         n_edges = int(10 * N * dens[t])          # mean degree 20 = 2 * edges / N
         snaps.append(chung_lu_blocked_snapshot(N, n_edges, w, bounds[t // 32], 0.85, g_rng))
+        if N >= 500_000 or (t + 1) % 8 == 0:
+            _say(f"  graph: {t + 1}/{T} snapshots")
     graph = DynamicGraph(N, snaps)
     chunks = grid_chunks(T, 32, bounds)
     X = _normal_f32(stream(seed, "feat"), (T, N, F))
