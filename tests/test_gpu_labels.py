@@ -161,3 +161,32 @@ def test_label_refusals():
     with pytest.raises(ValueError):
         dw.layer.set_labels(lab[:-1])
     dw.layer.destroy()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_shapes_and_labellings(seed):
+    """Tiny and ragged shapes (one vertex, one snapshot, one label, all labels different), both
+    dense kernels, every time encoder, with and without a state cache."""
+    rng = np.random.default_rng(8000 + seed)
+    N = int(rng.choice([1, 2, 31, 33, 64, 97]))
+    T = int(rng.integers(1, 7))
+    kind = str(rng.choice(["gru", "lstm", "none"]))
+    S = int(rng.choice([32, 64, 96]))
+    layers = int(rng.choice([1, 2]))
+    F = int(rng.choice([1, 5, 32, 40]))
+    wl = synth.random_small(8100 + seed, T, N, F, S, S, 3.0, [[0, N, 0, T]], kind, n_struct_layers=layers)
+    mode = seed % 4
+    if mode == 0:
+        lab = np.zeros((T, N), np.int64)                       # one chunk
+    elif mode == 1:
+        lab = np.arange(T * N).reshape(T, N)                   # every pair its own chunk
+    else:
+        lab = _random_labels(rng, T, N, int(rng.integers(2, 6)), float(rng.choice([0.3, 0.8])))
+    n_state = 2 if kind == "lstm" else 1
+    Hc = None
+    if kind != "none" and seed % 2 == 0:
+        Hc = (0.5 * rng.standard_normal((n_state * T * N, S))).astype(np.float32)
+    dw, Y, HN = _device(wl, lab, Hc, dense_kernel=str(rng.choice(["auto", "tile"])))
+    _check(wl, lab, Hc, Y, HN, layers, f"seed {seed}: N={N} T={T} F={F} S={S} {kind} layers={layers} labelling {mode} "
+                                       f"cache={'yes' if Hc is not None else 'no'}")
+    dw.layer.destroy()
