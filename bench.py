@@ -94,6 +94,15 @@ def measured_traffic(workload: str, gather_mode: str) -> dict:
         return {}
 
 
+def with_traffic_rate(k: dict) -> dict:
+    """Adds the rate of the measured HBM traffic (committed rocprofv3 counters) over the launch time
+    measured in this run, next to the algorithmic figure."""
+    if k.get("traffic") and k.get("ms_per_launch"):
+        k["traffic_GBs"] = k["traffic"] / (k["ms_per_launch"] * 1e-3) / 1e9
+        k["traffic_frac_of_hbm_peak"] = k["traffic_GBs"] / PEAK_HBM_GBS
+    return k
+
+
 def evolve_report(args, wl, desc, dw, rows, value, ms_per_step, stage, t_gen, t_create, loss) -> dict:
     """JSON line for the EvolveGCN-O workload: a step is forward + backward."""
     import numpy as np
@@ -870,7 +879,7 @@ def main():
            "data": "synthetic",
            "config": {"workload": desc, "rows": rows, "nnz": nnz, "gather_mode": args.gather_mode,
                       "pass": "forward"},
-           "roofline": roofline, "roofline_aggregation": agg,
+           "roofline": with_traffic_rate(roofline), "roofline_aggregation": with_traffic_rate(agg),
            "stage_ms": {"aggregate0": float(stage[0]), "dense0": float(stage[1]), "aggregate1": float(stage[2]),
                         "dense_rnn": float(stage[3])},
            "device_ms_per_step": step_stats, "measured_hbm_copy_GBs": copy_GBs,
