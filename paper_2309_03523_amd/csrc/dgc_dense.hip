@@ -135,7 +135,9 @@ __device__ __forceinline__ void mma_k_loop(floatx16 (&acc)[NRB][4], const float*
 // ends; mask_row then holds 1 + the state row of a sequence that starts at this step, end_row
 // 1 + the state row of a sequence that ends at it (0 = none).
 template <int KIND, int NRB, int UPW, bool SEQ>
-__global__ __launch_bounds__(kThreads, 2) void k_dense(DenseArgs a, int ld) {
+// (the two-units-per-wave variants, S or H above 128, hold a tile of up to 133 KB in LDS: one
+//  workgroup per CU either way, so they may use the whole register file)
+__global__ __launch_bounds__(kThreads, (UPW >= 2 ? 1 : 2)) void k_dense(DenseArgs a, int ld) {
   extern __shared__ float smem[];
   float* P = smem;
   float* Q = smem + kTileRows * ld;

@@ -364,7 +364,7 @@ __global__ __launch_bounds__(512) void k_temporal_fwd(TemporalArgs a) {
       st = mfma(kh, qh, st);
       float pr[8];
 #pragma unroll
-      for (int p = 0; p < 8; ++p) pr[p] = r.a ? st[8 + p] : st[p];
+      for (int p = 0; p < 8; ++p) pr[p] = pick_half(st, p, m_vert[0], m_vert[1]);
       causal_softmax(pr, r.s, hh);
       bf16x8 ph, plo;
       split8(pr, ph, plo);

@@ -166,7 +166,7 @@ __global__ __launch_bounds__(256) void k_temporal_bwd(TemporalBwdArgs a) {
 #pragma unroll
         for (int p = 0; p < 8; ++p) {
           const int rk = 8 * (p >> 2) + 4 * hh + (p & 3);
-          pr[p] = rk <= r.s ? 0.25f * (r.a ? st[8 + p] : st[p]) : -INFINITY;
+          pr[p] = rk <= r.s ? 0.25f * pick_half(st, p, m_vert[0], m_vert[1]) : -INFINITY;
           mx = fmaxf(mx, pr[p]);
         }
         mx = fmaxf(mx, xor32(mx, hh));
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(256) void k_temporal_bwd(TemporalBwdArgs a) {
 #pragma unroll
         for (int p = 0; p < 8; ++p) {
           pr[p] *= inv;
-          dst[p] = r.a ? dpt[8 + p] : dpt[p];
+          dst[p] = pick_half(dpt, p, m_vert[0], m_vert[1]);
           delta += pr[p] * dst[p];
         }
         delta += xor32(delta, hh);
