@@ -35,7 +35,7 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--with-dx", action="store_true",
-                    help="EvolveGCN-O workloads: the backward pass also computes the gradient of the input rows")
+                    help="config4 / config5 workloads: the backward pass also computes the gradient of the input rows")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain device copy of X (a kernel of known size, to scale rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -244,9 +244,11 @@ def dysat_main(args):
     t_create = time.perf_counter() - t0
     layer, stream = dd.layer, torch.cuda.current_stream()
 
+    dX = torch.empty_like(dd.X) if args.with_dx else None
+
     def step():
         layer.forward(dd.X, dd.C, dd.Y, stream=stream)
-        layer.backward(dd.Y, target=tgt, loss_out=loss, stream=stream)
+        layer.backward(dd.Y, target=tgt, loss_out=loss, dX=dX, stream=stream)
 
     for _ in range(args.warmup):
         step()
@@ -290,7 +292,8 @@ def dysat_main(args):
            "config": {"workload": f"config5{'' if scale == 1.0 else ' at 1/4 of its vertex count'}: graph attention (8 heads x 16) + "
                                   f"causal temporal self-attention, bf16, 16 snapshots x {wl.graph.N} vertices, avg degree 12, "
                                   f"{len(wl.chunks)} uneven chunks, forward + backward (MSE)",
-                      "rows": rows, "nnz": nnz, "pass": "forward+backward"},
+                      "rows": rows, "nnz": nnz,
+                      "pass": "forward+backward" + (" incl. input gradient" if args.with_dx else "")},
            "roofline": dom, "kernels": kernels, "loss": float(loss.item()),
            "setup_s": {"generate": t_gen, "upload_create_pack": t_create}}
     if not args.no_cpu_baseline:

@@ -222,12 +222,13 @@ dgc_status_t dgc_layer_set_labels(dgc_layer_t* layer, const int32_t* labels, voi
  *          chunk are ignored), or
  *   target device [T,N,ldt]: the loss is the mean squared error between Y and target over all
  *          covered elements; *loss_out (device float, may be NULL) receives its value.
- *  dX     device [T,N,lddx] fp32 or NULL: gradient with respect to the input rows, for
- *          DGC_STRUCT_EVOLVE_GCN_O (DGC_ERR_UNSUPPORTED for other layers).  Rows covered by a chunk
- *          are written (a row's gradient comes from the rows of its own chunk that store it as a
- *          neighbour), other rows and the pitch padding are left alone.  Computing it uses up the
- *          aggregated rows the layer kept: a further backward needs a forward first
- *          (DGC_ERR_STATE); the first such call allocates T*N*F floats of workspace.
+ *  dX     device [T,N,lddx], element type as X, or NULL: gradient with respect to the input
+ *          rows.  Rows covered by a chunk are written (a row's gradient comes from the rows of its
+ *          own chunk that store it as a neighbour), other rows and the pitch padding are left
+ *          alone.  DGC_STRUCT_EVOLVE_GCN_O: computing it uses up the aggregated rows the layer
+ *          kept, so a further backward needs a forward first (DGC_ERR_STATE); the first such
+ *          call allocates T*N*F floats of workspace.  DGC_STRUCT_GAT: bfloat16, lddx a multiple
+ *          of 8; one more product per row on top of the parameter gradients.
  * The cache is a constant: no gradient flows into C.  Gradients are read with
  * dgc_layer_get_param(layer, "<name>.grad", ...).  Enqueues work only. */
 dgc_status_t dgc_layer_backward(dgc_layer_t* layer, const void* Y, int64_t ldy, const void* dY,

@@ -113,13 +113,15 @@ def forward(graph, chunks, params, X, C, heads):
     return {"Y": Y.numpy(), "U": U.numpy()}
 
 
-def gradients(graph, chunks, params, X, C, heads, *, target=None, dY=None):
-    """Forward + gradients of the loss with respect to every parameter.  Exactly one of
-    target (mean squared error over the covered elements) and dY (loss = sum(dY * Y) over the
-    covered elements).  The cache is a constant.  Returns dict(Y, loss, grads)."""
+def gradients(graph, chunks, params, X, C, heads, *, target=None, dY=None, want_dx=False):
+    """Forward + gradients of the loss with respect to every parameter (and, with want_dx, the
+    input X: "dX", zero on rows no chunk covers).  Exactly one of target (mean squared error
+    over the covered elements) and dY (loss = sum(dY * Y) over the covered elements).  The cache
+    is a constant.  Returns dict(Y, loss, grads[, dX])."""
     assert (target is None) != (dY is None)
     P = {k: _t64(params[k], True) for k in PARAMS}
-    Y, _, covered = _forward_t(graph, chunks, P, _t64(X), _t64(C), heads)
+    Xt = _t64(X, want_dx)
+    Y, _, covered = _forward_t(graph, chunks, P, Xt, _t64(C), heads)
     cm = covered[:, :, None].to(torch.float64)
     if target is not None:
         count = float(covered.sum().item() * Y.shape[2])
@@ -127,5 +129,8 @@ def gradients(graph, chunks, params, X, C, heads, *, target=None, dY=None):
     else:
         loss = (Y * _t64(dY) * cm).sum()
     loss.backward()
-    return {"Y": Y.detach().numpy(), "loss": float(loss.item()),
-            "grads": {k: P[k].grad.numpy() for k in PARAMS}}
+    out = {"Y": Y.detach().numpy(), "loss": float(loss.item()),
+           "grads": {k: P[k].grad.numpy() for k in PARAMS}}
+    if want_dx:
+        out["dX"] = Xt.grad.numpy()
+    return out

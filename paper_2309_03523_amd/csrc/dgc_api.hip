@@ -327,7 +327,7 @@ dgc_status_t build_dysat(dgc_layer* L, const std::vector<ChunkInfo>& cinfo, hipS
     L->params[std::string(kDysatNames[k]) + ".grad"] = g;
     w.G[k] = g.raw;
   }
-  uint4** frags[7] = {&w.Wp, &w.Wqp, &w.Wkp, &w.Wvp, &w.WqT, &w.WkT, &w.WvT};
+  uint4** frags[9] = {&w.Wp, &w.Wqp, &w.Wkp, &w.Wvp, &w.WqT, &w.WkT, &w.WvT, &w.WT, &w.WTlo};
   for (uint4** f : frags) DGC_HIP_TRY(dev_alloc(L, f, 4 * 8 * 64));
   // snapshots in use, 2-vertex tiles per chunk, owner map
   std::vector<int32_t> used;
@@ -954,8 +954,6 @@ dgc_status_t dgc_layer_backward(dgc_layer_t* L, const void* Yv, int64_t ldy, con
   if (!L->forward_done) return fail(DGC_ERR_STATE, "backward before forward");
   if (d.struct_kind != DGC_STRUCT_EVOLVE_GCN_O && d.struct_kind != DGC_STRUCT_GAT)
     return fail(DGC_ERR_UNSUPPORTED, "backward is built for DGC_STRUCT_EVOLVE_GCN_O and DGC_STRUCT_GAT only");
-  if (dX && d.struct_kind != DGC_STRUCT_EVOLVE_GCN_O)
-    return fail(DGC_ERR_UNSUPPORTED, "input gradients are built for DGC_STRUCT_EVOLVE_GCN_O only: dX must be NULL");
   if ((dYv != nullptr) == (targetv != nullptr))
     return fail(DGC_ERR_INVALID_ARG, "give exactly one of dY and target");
   dgc_status_t rc;
@@ -963,8 +961,10 @@ dgc_status_t dgc_layer_backward(dgc_layer_t* L, const void* Yv, int64_t ldy, con
     if ((rc = check_tensor(fail, "Y", Yv, ldy, d.S, true, 8)) != DGC_OK) return rc;
     if ((rc = check_tensor(fail, "dY", dYv, lddy, d.S, false, 8)) != DGC_OK) return rc;
     if ((rc = check_tensor(fail, "target", targetv, ldt, d.S, false, 8)) != DGC_OK) return rc;
+    if ((rc = check_tensor(fail, "dX", dX, lddx, d.F, false, 8)) != DGC_OK) return rc;
+    if (dX && !L->dy.dzXlo) DGC_HIP_TRY(dev_alloc(L, &L->dy.dzXlo, (int64_t)L->T * L->N * d.S));
     L->evd_bwd = false;
-    dysat_backward(L->dy, Yv, ldy, dYv, lddy, targetv, ldt, loss_out, L->profiling ? L->evd + 4 : nullptr,
+    dysat_backward(L->dy, Yv, ldy, dYv, lddy, targetv, ldt, loss_out, dX, lddx, L->profiling ? L->evd + 4 : nullptr,
                    static_cast<hipStream_t>(stream));
     if (L->profiling) L->evd_bwd = true;
     DGC_HIP_TRY(hipGetLastError());

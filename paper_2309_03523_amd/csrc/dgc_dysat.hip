@@ -17,6 +17,7 @@ namespace {
 //  mode 0: fragment (jb, kb) of W as the 32-row operand: lane l holds W[32 jb + l%32][16 kb + 8 (l/32) + 0..7].
 //  mode 1: fragment (ib, ks) of W^T, for products whose contraction index is W's row index:
 //          lane l holds W[16 ks + 8 (l/32) + 0..7][32 ib + l%32].
+//  mode 2: as mode 1, of what W loses when it is rounded to bf16 (the low part).
 __global__ void k_pack_w_bf16(const float* W, uint4* packed, int mode) {
   const int idx = blockIdx.x * blockDim.x + threadIdx.x;   // (blk * 8 + k) * 64 + lane
   if (idx >= 4 * 8 * 64) return;
@@ -28,7 +29,13 @@ __global__ void k_pack_w_bf16(const float* W, uint4* packed, int mode) {
     if (mode == 0) x[p] = W[(blk * 32 + r32) * kS + k * 16 + 8 * hh + p];
     else x[p] = W[(k * 16 + 8 * hh + p) * kS + blk * 32 + r32];
   }
-  packed[idx] = __builtin_bit_cast(uint4, pack8(x));
+  if (mode == 2) {
+    bf16x8 hi, lo;
+    split8(x, hi, lo);
+    packed[idx] = __builtin_bit_cast(uint4, lo);
+  } else {
+    packed[idx] = __builtin_bit_cast(uint4, pack8(x));
+  }
 }
 
 __global__ void k_fill_i32(int32_t* p, int32_t v, int64_t n) {
@@ -407,6 +414,8 @@ void dysat_pack_params(const DysatWs& ws, hipStream_t st) {
   hipLaunchKernelGGL(k_pack_w_bf16, 8, 256, 0, st, ws.P[DY_WQ], ws.WqT, 1);
   hipLaunchKernelGGL(k_pack_w_bf16, 8, 256, 0, st, ws.P[DY_WK], ws.WkT, 1);
   hipLaunchKernelGGL(k_pack_w_bf16, 8, 256, 0, st, ws.P[DY_WV], ws.WvT, 1);
+  hipLaunchKernelGGL(k_pack_w_bf16, 8, 256, 0, st, ws.P[DY_W], ws.WT, 1);
+  hipLaunchKernelGGL(k_pack_w_bf16, 8, 256, 0, st, ws.P[DY_W], ws.WTlo, 2);
 }
 
 void dysat_forward(const DysatWs& ws, const void* X, int64_t ldx, const void* C, int64_t ldc, void* Y, int64_t ldy,

@@ -688,6 +688,7 @@ struct GatBwdColsArgs {
   const float4* st2;
   const float* a_src; const float* a_dst;
   uint16_t* dzX; uint16_t* dzC;
+  uint16_t* dzXlo;      // nullptr, or: what dzX loses to rounding (for the input gradient)
   float* dss;           // [T*N][16]: d s_src of the row as an in-chunk neighbour [8], as a cache row [8]
 };
 
@@ -806,6 +807,7 @@ __device__ __forceinline__ AttVec att_init(const GatBwdColsArgs& a, int sub) {
   return v;
 }
 
+template <bool LO>   // LO: also keep what dzX loses to rounding (asked for with the input gradient)
 __device__ __forceinline__ void gat_bwd_col_finish(const GatBwdColsArgs& a, int64_t row, const ColOwn& o,
                                                    const ColAcc& r, const AttVec& v, int lane) {
   const int slot = lane >> 4, sub = lane & 15, head = sub >> 1;
@@ -815,7 +817,14 @@ __device__ __forceinline__ void gat_bwd_col_finish(const GatBwdColsArgs& a, int6
     const float dsd = a.st2[row * 8 + head].w;
 #pragma unroll
     for (int d = 0; d < 8; ++d) out[d] = r.ax[d] + dsd * v.ad[d] + r.dsx * v.as[d];
-    *reinterpret_cast<uint4*>(a.dzX + row * kS + 8 * sub) = __builtin_bit_cast(uint4, pack8(out));
+    const bf16x8 hi = pack8(out);
+    *reinterpret_cast<uint4*>(a.dzX + row * kS + 8 * sub) = __builtin_bit_cast(uint4, hi);
+    if constexpr (LO) {
+      float rest[8];
+#pragma unroll
+      for (int d = 0; d < 8; ++d) rest[d] = out[d] - (float)hi[d];
+      *reinterpret_cast<uint4*>(a.dzXlo + row * kS + 8 * sub) = __builtin_bit_cast(uint4, pack8(rest));
+    }
   }
 #pragma unroll
   for (int d = 0; d < 8; ++d) out[d] = r.ac[d] + r.dsc * v.as[d];
@@ -826,6 +835,7 @@ __device__ __forceinline__ void gat_bwd_col_finish(const GatBwdColsArgs& a, int6
   }
 }
 
+template <bool LO>
 __global__ __launch_bounds__(256) void k_gat_bwd_cols(GatBwdColsArgs a) {
   const int lane = threadIdx.x & 63;
   const int64_t N = a.g.N;
@@ -861,7 +871,7 @@ __global__ __launch_bounds__(256) void k_gat_bwd_cols(GatBwdColsArgs a) {
     if (e1 - e0 <= a.long_nnz) {
       const ColOwn o = col_own(a, base + j0 + rr, sub);
       const ColAcc r = gat_bwd_col_range(a, col, code, base, o, e0, e1, il, cl, lane);
-      gat_bwd_col_finish(a, base + j0 + rr, o, r, v, lane);
+      gat_bwd_col_finish<LO>(a, base + j0 + rr, o, r, v, lane);
     }
     e0 = ne0; e1 = ne1; il = nil; cl = ncl;
   }
@@ -897,6 +907,7 @@ __global__ __launch_bounds__(256) void k_gat_bwd_cols_long(GatBwdColsArgs a) {
   }
 }
 
+template <bool LO>
 __global__ __launch_bounds__(256) void k_gat_bwd_cols_merge(GatBwdColsArgs a) {
   const int lane = threadIdx.x & 63;
   const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -921,7 +932,7 @@ __global__ __launch_bounds__(256) void k_gat_bwd_cols_merge(GatBwdColsArgs a) {
     r.dsc += rec[264 + (sub >> 1)];
   }
   const ColOwn o = col_own(a, row, sub);
-  gat_bwd_col_finish(a, row, o, r, v, lane);
+  gat_bwd_col_finish<LO>(a, row, o, r, v, lane);
 }
 
 // Gradients of the attention vectors, a streaming pass over every vertex of the snapshots in use:
@@ -1016,6 +1027,63 @@ namespace {
 constexpr int kDwGroups = 256;     // workgroups (slots) of the weight-gradient kernel
 constexpr int kTbwdWaves = 2048;   // waves (slots) of the temporal backward kernel
 constexpr int kColsBlocks = 1024;  // workgroups of the reverse-edge pass (4 slots each)
+
+// Gradient of the input rows: the projection is z = W x, so dx = W^T dz, i.e. dX[row] = dzX[row] W for
+// every covered row (a row no chunk covers is never an input row; it is not written).  Same
+// tiling as the projection: one wave per 32 vertices of a snapshot, dzX rows as the second operand
+// straight from memory, fragments of W^T as the first.
+struct GatDxArgs {
+  const uint16_t* dzX; const uint16_t* dzXlo;
+  const uint4* WT; const uint4* WTlo;
+  const int32_t* owner; const int32_t* used_t; int32_t n_used; int64_t N;
+  uint16_t* dX; int64_t lddx;
+};
+
+__global__ __launch_bounds__(256) void k_gat_dx(GatDxArgs a) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = lane & 31, hh = lane >> 5;
+  const int64_t tiles_per_t = (a.N + 31) / 32;
+  const int64_t tile = (int64_t)blockIdx.x * 4 + wave;
+  if (tile >= tiles_per_t * a.n_used) return;
+  const int32_t t = a.used_t[tile / tiles_per_t];
+  const int64_t v = (tile % tiles_per_t) * 32 + n;
+  const bool valid = v < a.N;
+  const int64_t row = (int64_t)t * a.N + (valid ? v : a.N - 1);
+  const bool covered = valid && a.owner[row] >= 0;
+  if (__ballot(covered) == 0ull) return;
+  // both operands as a bf16 value plus what it lost to rounding: a row's gradient is one sum of
+  // 128 terms, nothing averages the roundings out as the sums over rows of the weight gradients do
+  bf16x8 gf[8], gl[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    // rows no chunk covers hold no gradient (their dzX was never written): zeros
+    uint4 raw = make_uint4(0, 0, 0, 0), rawl = raw;
+    if (covered) {
+      raw = *reinterpret_cast<const uint4*>(a.dzX + row * kS + ks * 16 + 8 * hh);
+      rawl = *reinterpret_cast<const uint4*>(a.dzXlo + row * kS + ks * 16 + 8 * hh);
+    }
+    gf[ks] = as_frag(raw);
+    gl[ks] = as_frag(rawl);
+  }
+#pragma unroll
+  for (int ib = 0; ib < 4; ++ib) {
+    floatx16 acc = {};
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const bf16x8 wh = as_frag(a.WT[(ib * 8 + ks) * 64 + lane]), wl = as_frag(a.WTlo[(ib * 8 + ks) * 64 + lane]);
+      acc = mfma(wl, gf[ks], acc);
+      acc = mfma(wh, gl[ks], acc);
+      acc = mfma(wh, gf[ks], acc);
+    }
+    if (covered) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        *reinterpret_cast<uint2*>(a.dX + row * a.lddx + ib * 32 + 8 * g + 4 * hh) =
+            pack4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
+    }
+  }
+}
+
 }  // namespace
 
 // scratch layout: [weight-gradient slots | position-gradient slots | attention-vector slots]
@@ -1038,7 +1106,7 @@ void dysat_cols_long(const GraphDev& g, const int32_t* used_t, int32_t n_used, i
 int64_t dysat_loss_partial_elems(const DysatWs&) { return kTbwdWaves; }
 
 void dysat_backward(const DysatWs& ws, const void* Y, int64_t ldy, const void* dY, int64_t lddy, const void* target,
-                    int64_t ldt, float* loss_out, hipEvent_t* ev, hipStream_t st) {
+                    int64_t ldt, float* loss_out, void* dX, int64_t lddx, hipEvent_t* ev, hipStream_t st) {
   float* dw_slots = ws.partial;
   float* dpos_slots = dw_slots + (int64_t)kDwGroups * 3 * kS * kS;
   float* da_slots = dpos_slots + (int64_t)kTbwdWaves * ws.T * kS;
@@ -1123,12 +1191,15 @@ void dysat_backward(const DysatWs& ws, const void* Y, int64_t ldy, const void* d
   ca.st2 = reinterpret_cast<const float4*>(ws.st2);
   ca.a_src = ws.P[DY_ASRC]; ca.a_dst = ws.P[DY_ADST];
   ca.dzX = ws.dzX; ca.dzC = ws.dzC; ca.dss = ws.dss;
+  ca.dzXlo = dX ? ws.dzXlo : nullptr;
   ca.cols_long = ws.cols_long; ca.n_cols_long = ws.n_cols_long; ca.long_nnz = ws.long_nnz; ca.part_nnz = ws.part_nnz;
   ca.long_partial = ws.long_partial;
-  hipLaunchKernelGGL(k_gat_bwd_cols, blocks_for(items, 4), 256, 0, st, ca);
+  if (dX) hipLaunchKernelGGL(k_gat_bwd_cols<true>, blocks_for(items, 4), 256, 0, st, ca);
+  else hipLaunchKernelGGL(k_gat_bwd_cols<false>, blocks_for(items, 4), 256, 0, st, ca);
   if (ws.n_cols_long > 0) {
     hipLaunchKernelGGL(k_gat_bwd_cols_long, blocks_for(ws.n_cols_long, 4), 256, 0, st, ca);
-    hipLaunchKernelGGL(k_gat_bwd_cols_merge, blocks_for(ws.n_cols_long, 4), 256, 0, st, ca);
+    if (dX) hipLaunchKernelGGL(k_gat_bwd_cols_merge<true>, blocks_for(ws.n_cols_long, 4), 256, 0, st, ca);
+    else hipLaunchKernelGGL(k_gat_bwd_cols_merge<false>, blocks_for(ws.n_cols_long, 4), 256, 0, st, ca);
   }
   AttGradArgs ag{};
   ag.used_t = ws.used_t; ag.n_used = ws.n_used; ag.N = ws.N; ag.owner = ws.owner; ag.zX = ws.zX; ag.zC = ws.zC;
@@ -1150,6 +1221,13 @@ void dysat_backward(const DysatWs& ws, const void* Y, int64_t ldy, const void* d
   hipLaunchKernelGGL((k_dw_bf16<1, false>), groups, 512, 0, st, dc);
   hipLaunchKernelGGL(k_reduce_slots, blocks_for(kS * kS, 64), 1024, 0, st, dw_slots, (int64_t)2 * groups,
                      (int64_t)kS * kS, (int64_t)kS * kS, 1.f, ws.G[DY_W]);
+  // (6) optional: the gradient of the input rows, dX = dzX W (covered rows only)
+  if (dX) {
+    GatDxArgs xa{};
+    xa.dzX = ws.dzX; xa.dzXlo = ws.dzXlo; xa.WT = ws.WT; xa.WTlo = ws.WTlo; xa.owner = ws.owner; xa.used_t = ws.used_t; xa.n_used = ws.n_used; xa.N = ws.N;
+    xa.dX = static_cast<uint16_t*>(dX); xa.lddx = lddx;
+    hipLaunchKernelGGL(k_gat_dx, blocks_for((ws.N + 31) / 32 * ws.n_used, 4), 256, 0, st, xa);
+  }
   if (ev) (void)hipEventRecord(ev[3], st);
 }
 

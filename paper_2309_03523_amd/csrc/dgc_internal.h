@@ -239,7 +239,8 @@ struct DysatWs {
   const float* P[DY_NPAR];   // fp32 parameters: gat.weight, att_src, att_dst, pos, W_q, W_k, W_v
   float* G[DY_NPAR];         // their gradients
   uint4 *Wp, *Wqp, *Wkp, *Wvp;   // bf16 operand fragments (row operand)
-  uint4 *WqT, *WkT, *WvT;        // bf16 fragments of the transposes (backward)
+  uint4 *WqT, *WkT, *WvT, *WT;   // bf16 fragments of the transposes (backward)
+  uint4* WTlo;                   // low part of W^T (W minus its bf16 rounding), for the input gradient
   uint16_t *zX, *zC;         // [T*N][128] half-precision projections of input and cache rows
   float *sX, *sC;            // attention scalars
   float* U;                  // [T*N][128] fp32 structure-encoder output before ELU
@@ -248,6 +249,7 @@ struct DysatWs {
   const void* X; int64_t ldx;                // inputs of the last forward (read again by backward)
   const void* C; int64_t ldc;
   uint16_t *dU, *dQ, *dK, *dV, *dzX, *dzC;   // [T*N][128] bf16
+  uint16_t* dzXlo;                           // what dzX lost to rounding, for the input gradient (allocated on demand)
   float* st2;                // [T*N][8][4]: per head (s_dst, lse, c, d s_dst) of every covered row
   float* dss;                // [T*N][16]: d s_src of every vertex, as in-chunk neighbour [8] and as cache row [8]
   float* partial;            // scratch for the parameter-gradient reductions
@@ -274,7 +276,7 @@ void dysat_cols_long(const GraphDev& g, const int32_t* used_t, int32_t n_used, i
 int64_t dysat_loss_partial_elems(const DysatWs& ws);
 // ev: NULL or 4 events recorded around the three backward stages
 void dysat_backward(const DysatWs& ws, const void* Y, int64_t ldy, const void* dY, int64_t lddy, const void* target,
-                    int64_t ldt, float* loss_out, hipEvent_t* ev, hipStream_t st);
+                    int64_t ldt, float* loss_out, void* dX, int64_t lddx, hipEvent_t* ev, hipStream_t st);
 void dysat_build_owner(const Segment* segs, int64_t nseg, int32_t T, int64_t N, int32_t* owner, hipStream_t st);
 void dysat_pack_params(const DysatWs& ws, hipStream_t st);
 // ev: NULL or 4 events recorded around the three forward stages

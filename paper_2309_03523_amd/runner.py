@@ -95,11 +95,12 @@ class DysatDevice:
         torch.cuda.synchronize()
         return self.Y
 
-    def backward(self, *, target=None, dY=None):
-        """Gradients of the seven parameter tensors (dict of host arrays) and the loss (or None)."""
+    def backward(self, *, target=None, dY=None, dX=None):
+        """Gradients of the seven parameter tensors (dict of host arrays) and the loss (or None);
+        dX: optional bfloat16 device tensor [T,N,F] that receives the input gradient."""
         import torch
         loss = torch.zeros(1, device=self.Y.device) if target is not None else None
-        self.layer.backward(self.Y, dY=dY, target=target, loss_out=loss)
+        self.layer.backward(self.Y, dY=dY, target=target, loss_out=loss, dX=dX)
         torch.cuda.synchronize()
         grads = {k: self.layer.get_param(k + ".grad", v.shape) for k, v in self.wl.params.items()}
         return grads, (float(loss.item()) if loss is not None else None)

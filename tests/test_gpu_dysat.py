@@ -120,3 +120,40 @@ def test_attention_argument_errors():
     with pytest.raises(DgcError) as ei:      # window longer than 16 snapshots
         DysatDevice(wl2)
     assert ei.value.code == 4
+
+
+@pytest.mark.parametrize("case", ["ragged", "split", "single"])
+def test_input_gradient_parity(case):
+    """dL/dX of the covered rows (bf16) against the oracle; rows no chunk covers are not written;
+    asking for it does not change the parameter gradients."""
+    import torch
+    from paper_2309_03523_amd.runner import DysatDevice
+    c = CASES[case]
+    wl = synth.dysat_small(40 + len(case), c["T"], c["N"], 128, 8, c["deg"], c["chunks"], hub=True)
+    extra = synth.round_bf16(synth.stream(3, "extra").standard_normal(wl.X.shape).astype(np.float32))
+    dd = DysatDevice(wl, **c.get("kw", {}))
+    dd.forward()
+    dev = torch.from_numpy(extra).cuda().to(torch.bfloat16)
+    plain, _ = dd.backward(dY=dev)
+    dX = torch.full((wl.graph.T, wl.graph.N, 136), float("nan"), dtype=torch.bfloat16, device="cuda")[:, :, :128]
+    grads, _ = dd.backward(dY=dev, dX=dX)
+    for name in dysat.PARAMS:
+        np.testing.assert_array_equal(grads[name], plain[name])
+    want = dysat.gradients(wl.graph, wl.chunks, wl.params, wl.X, wl.C, 8, dY=extra, want_dx=True)["dX"]
+    got = dX.float().cpu().numpy()
+    cov = _covered(wl)
+    g, w = got[cov].astype(np.float64), want[cov]
+    # A row's gradient is one product of that row's dz with W: nothing averages the bf16 roundings
+    # of the stored intermediates out (as the sums over rows of the weight gradients do), and
+    # rows differ in scale by more than 10x (a vertex with only its self-loop keeps all of its
+    # row's gradient).  So every element is measured against its own row's RMS, and each row as a
+    # whole against its norm.
+    row_rms = np.sqrt((w * w).mean(axis=1))
+    assert row_rms.min() > 0
+    e = float((np.abs(g - w) / np.maximum(np.abs(w), row_rms[:, None])).max())
+    e_row = float((np.sqrt(((g - w) ** 2).mean(axis=1)) / row_rms).max())
+    print(f"{case}: dX max element error {e:.3e} (floor: the row's RMS), max row error {e_row:.3e} ({int(cov.sum())} rows)",
+          flush=True)
+    assert e < TOL and e_row < 1e-2
+    assert np.isnan(got[~cov]).all()
+    dd.layer.destroy()

@@ -187,6 +187,32 @@ def test_gradients_match_finite_differences(mode):
             assert abs(fd - an) < 1e-6 * max(1.0, abs(an)), (name, fd, an)
 
 
+def test_input_gradient_matches_finite_differences():
+    """dL/dX by central differences along random directions; rows no chunk covers and the cache
+    get no gradient."""
+    wl = _small(seed=12, chunks=[[0, 5, 0, 4], [5, 8, 1, 3]])
+    rng = np.random.default_rng(3)
+    dY = rng.standard_normal(wl.X.shape)
+    base = dysat.gradients(wl.graph, wl.chunks, wl.params, wl.X, wl.C, 2, dY=dY, want_dx=True)
+    cov = np.zeros(wl.X.shape[:2], bool)
+    for v_lo, v_hi, t_lo, t_hi in np.asarray(wl.chunks).tolist():
+        cov[t_lo:t_hi, v_lo:v_hi] = True
+    assert (~cov).any() and np.abs(base["dX"][~cov]).max() == 0.0
+    assert np.abs(base["dX"][cov]).max() > 1e-3
+
+    def loss_at(X):
+        Y = dysat.forward(wl.graph, wl.chunks, wl.params, X, wl.C, 2)["Y"]
+        return float((Y * dY)[cov].sum())
+
+    X0 = wl.X.astype(np.float64)
+    for _ in range(4):
+        d = rng.standard_normal(X0.shape)
+        eps = 1e-6
+        fd = (loss_at(X0 + eps * d) - loss_at(X0 - eps * d)) / (2 * eps)
+        an = float((base["dX"] * d).sum())
+        assert abs(fd - an) < 1e-6 * max(1.0, abs(an)), (fd, an)
+
+
 def test_cache_is_a_constant_but_its_projection_carries_weight_gradient():
     """Halo rows enter as W c: the gradient of gat.weight changes when the cache changes, and
     uncovered snapshots / vertices contribute nothing."""
