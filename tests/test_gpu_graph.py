@@ -75,3 +75,88 @@ def test_temporal_fusion_replays_from_a_graph():
 
     _capture_and_replay(dw, forward, new_inputs)
     dw.layer.destroy()
+
+
+def _replay_training_step(step, read_grads, new_inputs):
+    """Capture forward + backward once (after an eager step, which also makes the layer's lazy
+    allocations), replay it for changing inputs and compare loss and gradients with eager runs."""
+    import torch
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for k in range(3):
+        new_inputs(k)
+        step()
+        torch.cuda.synchronize()
+        eager = read_grads()
+        graph.replay()
+        torch.cuda.synchronize()
+        replayed = read_grads()
+        for name in eager:
+            np.testing.assert_array_equal(replayed[name], eager[name], err_msg=f"replay {k}: {name}")
+
+
+def test_evolve_training_step_replays_from_a_graph():
+    import torch
+    import oracle
+    from paper_2309_03523_amd.runner import DeviceWorkload
+    T, N, F = 6, 300, 64
+    chunks = [[0, 100, 0, 6], [100, 300, 0, 3], [100, 300, 3, 6]]
+    wl = synth.random_small(9, T, N, F, F, F, 5.0, chunks, "none", hub=True)
+    wl.params = synth.evolve_params(9, F, F, random_bias=True)
+    dw = DeviceWorkload(wl, struct_kind="evolve_gcn_o", act_out="relu")
+    gen = torch.Generator(device="cuda").manual_seed(4)
+    target = torch.randn(T, N, F, device="cuda", generator=gen)
+    loss = torch.zeros(1, device="cuda")
+    dX = torch.zeros(T, N, F, device="cuda")
+
+    def step():
+        dw.layer.forward(dw.X, dw.C, dw.Y)
+        dw.layer.backward(dw.Y, target=target, loss_out=loss, dX=dX)
+
+    def read_grads():
+        out = {n: dw.layer.get_param(n + ".grad", wl.params[n].shape) for n in oracle.EVOLVE_PARAMS}
+        out["loss"] = loss.cpu().numpy()
+        out["dX"] = dX.cpu().numpy()
+        return out
+
+    def new_inputs(k):
+        dw.X.copy_(torch.randn(dw.X.shape, device="cuda", generator=gen))
+        target.mul_(0.5)
+
+    _replay_training_step(step, read_grads, new_inputs)
+    dw.layer.destroy()
+
+
+def test_attention_training_step_replays_from_a_graph():
+    import torch
+    from oracle import dysat
+    from paper_2309_03523_amd.runner import DysatDevice
+    wl = synth.dysat_small(11, 6, 150, 128, 8, 4.0, [[0, 70, 0, 6], [70, 150, 0, 4]], hub=True)
+    dd = DysatDevice(wl)
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    target = torch.randn(dd.X.shape, device="cuda", generator=gen).to(torch.bfloat16)
+    loss = torch.zeros(1, device="cuda")
+    dX = torch.zeros_like(dd.X)
+
+    def step():
+        dd.layer.forward(dd.X, dd.C, dd.Y)
+        dd.layer.backward(dd.Y, target=target, loss_out=loss, dX=dX)
+
+    def read_grads():
+        out = {n: dd.layer.get_param(n + ".grad", wl.params[n].shape) for n in dysat.PARAMS}
+        out["loss"] = loss.cpu().numpy()
+        out["dX"] = dX.float().cpu().numpy()
+        return out
+
+    def new_inputs(k):
+        dd.X.copy_(torch.randn(dd.X.shape, device="cuda", generator=gen).to(torch.bfloat16))
+
+    _replay_training_step(step, read_grads, new_inputs)
+    dd.layer.destroy()
