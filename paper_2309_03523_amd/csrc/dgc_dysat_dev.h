@@ -85,8 +85,6 @@ __device__ __forceinline__ void split8(const float* x, bf16x8& hi, bf16x8& lo) {
   }
 }
 
-// x where m is all ones, zero where m is zero (a select on the packed dwords: selecting on a
-// vector of eight 16-bit elements would be unpacked element by element)
 // Element p of v for a lane whose mask m0 is all ones, element 8 + p where m1 is (exactly one of the
 // two is): a bitwise blend.  Written as a select between two elements of one vector it is turned
 // into a lane-dependent index, which costs a compare and a select per element of the vector.
@@ -94,6 +92,8 @@ __device__ __forceinline__ float pick_half(const floatx16& v, int p, uint32_t m0
   return __uint_as_float((__float_as_uint(v[p]) & m0) | (__float_as_uint(v[8 + p]) & m1));
 }
 
+// x where m is all ones, zero where m is zero (a select on the packed dwords: selecting on a
+// vector of eight 16-bit elements would be unpacked element by element)
 __device__ __forceinline__ bf16x8 and_mask(bf16x8 x, uint32_t m) {
   uint4 u = __builtin_bit_cast(uint4, x);
   u.x &= m; u.y &= m; u.z &= m; u.w &= m;
