@@ -20,6 +20,16 @@
 // several passes over disjoint label classes when the row holds more distinct labels than the
 // table takes; the pass count that worked is remembered per row (labels merge as the propagation
 // goes on) and doubled when a table fills up.
+//
+// Most iterations change few labels.  When a vertex is looked at, the margin by which its own
+// label's score exceeds every other label's score is kept (-1 if it does not: the vertex is looked
+// at again next time).  A neighbour that changes label over an edge of weight w moves w from one
+// label's score to another's, so it can lower that margin by at most 2w: the decide step adds 2w to
+// the vertex's `drift`, and while drift <= margin no candidate can score strictly more than the own
+// label, whatever the sizes and ties - the vertex still does not want to change and is skipped.
+// A vertex that changes its own label is looked at again.  The result is exactly that of looking at
+// every vertex every time; hub rows with a clear majority label stay skipped through many changes
+// of their neighbourhood.
 #include <algorithm>
 
 #include "dgc_internal.h"
@@ -44,6 +54,8 @@ struct CgArgs {
   const int32_t* rows;   // list of the long-row kernel at hand
   int32_t* passes_hint;  // per entry of that list: pass count that last worked (0 = none yet)
   uint32_t salt;         // changes with the iteration: order of the decide step
+  long long* margin;             // [T*N] own score - best other score at the last look, -1 = look again
+  unsigned long long* drift;     // [T*N] twice the weight of the neighbour edges whose far end changed label since
   int32_t* counters;     // [0] vertices changed this iteration, [1] / [2] list fills, [3] hash overflow
 };
 
@@ -67,6 +79,8 @@ __global__ void k_cg_init(CgArgs a, int64_t n) {
   a.labels[x] = (int32_t)x;
   a.size[x] = 1;
   a.want[x] = -1;
+  a.margin[x] = -1;        // everybody is looked at in the first iteration
+  a.drift[x] = 0;
 }
 
 __global__ void k_cg_count_long(CgArgs a, int64_t n, int32_t* mid, int32_t* big) {
@@ -75,6 +89,7 @@ __global__ void k_cg_count_long(CgArgs a, int64_t n, int32_t* mid, int32_t* big)
   const int32_t t = (int32_t)(x / a.g.N);
   const int32_t d = degree_of(a.g, t, x - (int64_t)t * a.g.N);
   if (d <= kShort) return;
+  if (!mid && !big) atomicMax(&a.counters[3], d);   // counting pass: also the largest degree
   const int which = d <= kMid ? 1 : 2;
   const int32_t k = atomicAdd(&a.counters[which], 1);
   int32_t* list = which == 1 ? mid : big;
@@ -97,6 +112,7 @@ __global__ __launch_bounds__(kBlock) void k_cg_propose_short(CgArgs a, int64_t n
   __shared__ uint32_t strip[kShort * kBlock];   // [k][thread]: neighbour label, top bit = temporal edge
   const int64_t x = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (x >= n) return;
+  if (a.margin[x] >= 0 && a.drift[x] <= (unsigned long long)a.margin[x]) return;   // want[x] stays -1
   const int32_t t = (int32_t)(x / a.g.N);
   const int64_t i = x - (int64_t)t * a.g.N;
   const int64_t* rp = a.g.rowptr[t];
@@ -114,7 +130,7 @@ __global__ __launch_bounds__(kBlock) void k_cg_propose_short(CgArgs a, int64_t n
   if (t > 0 && k < kShort) { s[k * kBlock] = (uint32_t)a.labels[x - a.g.N] | kTemporal; ++k; }
   if (t + 1 < a.g.T && k < kShort) { s[k * kBlock] = (uint32_t)a.labels[x + a.g.N] | kTemporal; ++k; }
   const int32_t own_label = a.labels[x];
-  uint32_t own = 0;
+  uint32_t own = 0, max_other = 0;
   Best best{0u, 0, -1};
   for (int p = 0; p < k; ++p) {
     const uint32_t lp = s[p * kBlock] & ~kTemporal;
@@ -129,12 +145,15 @@ __global__ __launch_bounds__(kBlock) void k_cg_propose_short(CgArgs a, int64_t n
     }
     if (!first || score == 0) continue;
     if ((int32_t)lp == own_label) { own = score; continue; }
+    max_other = max(max_other, score);
     const int32_t sz = a.size[lp];
     if (sz >= a.cap) continue;
     const Best c{score, sz, (int32_t)lp};
     if (best.label < 0 || better(c, best)) best = c;
   }
   a.want[x] = (best.label >= 0 && best.score > own) ? best.label : -1;
+  a.margin[x] = own >= max_other ? (long long)(own - max_other) : -1;
+  a.drift[x] = 0;
 }
 
 __device__ __forceinline__ void apply_change(const CgArgs& a, int64_t x, int32_t to) {
@@ -143,6 +162,7 @@ __device__ __forceinline__ void apply_change(const CgArgs& a, int64_t x, int32_t
   atomicAdd(&a.size[to], 1);
   atomicSub(&a.size[from], 1);
   atomicAdd(&a.counters[0], 1);
+  a.margin[x] = -1;          // (its neighbours' drift is raised by the caller)
 }
 
 __global__ __launch_bounds__(kBlock) void k_cg_decide_short(CgArgs a, int64_t n) {
@@ -164,6 +184,11 @@ __global__ __launch_bounds__(kBlock) void k_cg_decide_short(CgArgs a, int64_t n)
     if (j != i && a.want[base + j] >= 0 && before(a.salt, base + j, x)) return;
   }
   apply_change(a, x, w);
+  const unsigned long long ds = 2ull * (unsigned long long)a.w_s, dt = 2ull * (unsigned long long)a.w_t;
+  for (int64_t e = e0; e < e1; ++e)
+    if (col[e] != i) atomicAdd(&a.drift[base + col[e]], ds);
+  if (t > 0) atomicAdd(&a.drift[x - a.g.N], dt);
+  if (t + 1 < a.g.T) atomicAdd(&a.drift[x + a.g.N], dt);
 }
 
 // ---- long rows: one workgroup of THREADS per row, hash table of at most SLOTS entries
@@ -192,7 +217,9 @@ __global__ __launch_bounds__(THREADS) void k_cg_propose_long(CgArgs a) {
   __shared__ uint32_t own_score;
   __shared__ int n_keys;
   __shared__ int overflow;
+  __shared__ uint32_t max_other;
   const int64_t x = a.rows[blockIdx.x];
+  if (a.margin[x] >= 0 && a.drift[x] <= (unsigned long long)a.margin[x]) return;   // the same for the whole workgroup
   const int32_t t = (int32_t)(x / a.g.N);
   const int64_t i = x - (int64_t)t * a.g.N;
   const int64_t e0 = a.g.rowptr[t][i], e1 = a.g.rowptr[t][i + 1];
@@ -208,7 +235,7 @@ __global__ __launch_bounds__(THREADS) void k_cg_propose_long(CgArgs a) {
   uint32_t passes = hint > 0 ? (uint32_t)max(1, hint / 2) : (uint32_t)((n_sp + 2 + limit - 1) / limit);
   for (;;) {                                     // again with twice the passes if a table filled up
     Best best{0u, 0, -1};
-    if (threadIdx.x == 0) { own_score = 0; overflow = 0; }
+    if (threadIdx.x == 0) { own_score = 0; overflow = 0; max_other = 0; }
     for (uint32_t p = 0; p < passes; ++p) {
       for (int sidx = threadIdx.x; sidx < slots; sidx += THREADS) { key[sidx] = -1; val[sidx] = 0; }
       if (threadIdx.x == 0) n_keys = 0;
@@ -243,6 +270,7 @@ __global__ __launch_bounds__(THREADS) void k_cg_propose_long(CgArgs a) {
         const int32_t lab = key[sidx];
         if (lab < 0) continue;
         if (lab == own_label) { own_score = val[sidx]; continue; }
+        atomicMax(&max_other, val[sidx]);
         const int32_t sz = a.size[lab];
         if (sz >= a.cap) continue;
         const Best c{val[sidx], sz, lab};
@@ -256,6 +284,8 @@ __global__ __launch_bounds__(THREADS) void k_cg_propose_long(CgArgs a) {
     if (!ovf) {
       if (threadIdx.x == 0) {
         a.want[x] = (best.label >= 0 && best.score > own) ? best.label : -1;
+        a.margin[x] = own >= max_other ? (long long)(own - max_other) : -1;
+        a.drift[x] = 0;
         a.passes_hint[blockIdx.x] = (int32_t)passes;
       }
       return;
@@ -288,7 +318,15 @@ __global__ __launch_bounds__(THREADS) void k_cg_decide_long(CgArgs a) {
     if (j != i && a.want[base + j] >= 0 && before(a.salt, base + j, x)) blocked = 1;
   }
   __syncthreads();
-  if (threadIdx.x == 0 && !blocked) apply_change(a, x, w);
+  if (blocked) return;                           // the same for the whole workgroup
+  const unsigned long long ds = 2ull * (unsigned long long)a.w_s, dt = 2ull * (unsigned long long)a.w_t;
+  if (threadIdx.x == 0) {
+    apply_change(a, x, w);
+    if (t > 0) atomicAdd(&a.drift[x - a.g.N], dt);
+    if (t + 1 < a.g.T) atomicAdd(&a.drift[x + a.g.N], dt);
+  }
+  for (int64_t e = e0 + threadIdx.x; e < e1; e += THREADS)
+    if (col[e] != i) atomicAdd(&a.drift[base + col[e]], ds);
 }
 
 unsigned grid_of(int64_t n) { return (unsigned)((n + kBlock - 1) / kBlock); }
@@ -332,11 +370,15 @@ extern "C" dgc_status_t dgc_chunk_generate(const dgc_graph_t* graph, int32_t w_s
 
   const int64_t** d_rp = nullptr; const int32_t** d_ci = nullptr;
   int32_t *want = nullptr, *size = nullptr, *counters = nullptr, *mid = nullptr, *big = nullptr, *hints = nullptr;
+  long long* margin = nullptr;
+  unsigned long long* drift = nullptr;
   CG_TRY(alloc((void**)&d_rp, sizeof(void*) * graph->T));
   CG_TRY(alloc((void**)&d_ci, sizeof(void*) * graph->T));
   CG_TRY(alloc((void**)&want, sizeof(int32_t) * n));
   CG_TRY(alloc((void**)&size, sizeof(int32_t) * n));
   CG_TRY(alloc((void**)&counters, sizeof(int32_t) * 4));
+  CG_TRY(alloc((void**)&margin, sizeof(long long) * n));
+  CG_TRY(alloc((void**)&drift, sizeof(unsigned long long) * n));
   CG_TRY(hipMemcpyAsync(d_rp, graph->rowptr, sizeof(void*) * graph->T, hipMemcpyHostToDevice, st));
   CG_TRY(hipMemcpyAsync(d_ci, graph->colidx, sizeof(void*) * graph->T, hipMemcpyHostToDevice, st));
   CG_TRY(hipMemsetAsync(counters, 0, sizeof(int32_t) * 4, st));
@@ -361,12 +403,21 @@ extern "C" dgc_status_t dgc_chunk_generate(const dgc_graph_t* graph, int32_t w_s
   }
   a.w_s = w_s; a.w_t = w_t; a.cap = cap;
   a.labels = labels; a.want = want; a.size = size; a.counters = counters;
+  a.margin = margin; a.drift = drift;
   int32_t host_c[4] = {0, 0, 0, 0};
   hipLaunchKernelGGL(k_cg_init, grid_of(n), kBlock, 0, st, a, n);
   hipLaunchKernelGGL(k_cg_count_long, grid_of(n), kBlock, 0, st, a, n, (int32_t*)nullptr, (int32_t*)nullptr);
   CG_TRY(hipMemcpyAsync(host_c, counters, sizeof(host_c), hipMemcpyDeviceToHost, st));
   CG_TRY(hipStreamSynchronize(st));
   const int32_t n_mid = host_c[1], n_big = host_c[2];
+  {  // scores are 32-bit sums of edge weights over a row
+    const int64_t max_deg = std::max<int64_t>(host_c[3], kShort) + 2;
+    if (max_deg * std::max(w_s, w_t) >= ((int64_t)1 << 32)) {
+      release();
+      return bad(DGC_ERR_UNSUPPORTED, "chunk generate: largest degree x edge weight must stay below 2^32");
+    }
+  }
+  CG_TRY(hipMemsetAsync(counters, 0, sizeof(int32_t) * 4, st));
   if (n_mid + n_big > 0) {
     CG_TRY(alloc((void**)&mid, sizeof(int32_t) * n_mid));
     CG_TRY(alloc((void**)&big, sizeof(int32_t) * n_big));
