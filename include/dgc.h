@@ -289,19 +289,22 @@ dgc_status_t dgc_layer_packing(dgc_layer_t* layer, const char* what, void* host_
  * x = t*N + i per (snapshot, vertex), the spatial edges of every snapshot (weight w_s; the stored
  * self-loops are not edges) and a virtual temporal edge between (t, i) and (t+1, i) (weight w_t);
  * the weights are the traffic an edge of each kind causes in the DGNN at hand, integers in
- * [0, 2^20].  Labels start all different (label of x = x, the section's initialisation with equal
+ * [0, 2^20] with (largest degree + 2) x weight below 2^32 (DGC_ERR_UNSUPPORTED otherwise: scores
+ * are 32-bit sums).  Labels start all different (label of x = x, the section's initialisation with equal
  * snapshot sizes).  Every iteration works on the labels of the one before: a vertex scores each
  * neighbour label by the total weight of the edges to the neighbours carrying it; its candidate is
  * the label carried by fewer than `cap` vertices with the largest score (ties: the label carried
  * by fewer vertices, then the smaller label); it wants to change if the candidate scores strictly
- * more than its own label; of two adjacent vertices that want to change only the one with the
- * smaller x does.  Ends when no vertex wants to change (*converged_out = 1) or after max_iters
+ * more than its own label; of two adjacent vertices that want to change only the one that comes
+ * first in the iteration's order does (iteration r, 0-based: by a fixed 32-bit mix of
+ * x xor (r * 0x9E3779B9 mod 2^32), then by x).  Vertices whose answer cannot have changed are
+ * skipped; the labels are those of looking at every vertex every time.  Ends when no vertex wants to change (*converged_out = 1) or after max_iters
  * iterations.  `cap` is soft: several vertices may join a label in the iteration in which it
  * reaches the limit.
  *  graph: as for dgc_layer_create (host struct of device arrays), checked against the graph contract
  *  (DGC_ERR_BAD_GRAPH); T*N < 2^31.  labels: device int32 [T*N], receives the label of every
  *  super-vertex (vertices with equal labels form a chunk).  iters_out, converged_out: host, may be
- *  NULL.  Allocates its workspace (12 bytes per super-vertex), synchronises `stream` once per
+ *  NULL.  Allocates its workspace (24 bytes per super-vertex), synchronises `stream` once per
  *  iteration.  Errors: text in dgc_last_error(NULL). */
 dgc_status_t dgc_chunk_generate(const dgc_graph_t* graph, int32_t w_s, int32_t w_t, int64_t cap,
                                 int32_t max_iters, int32_t* labels, int32_t* iters_out,
