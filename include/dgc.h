@@ -18,8 +18,11 @@
  *    is the layer's dtype: fp32 (row pitch ld*, in elements, a multiple of 4) or bfloat16 (pitch a
  *    multiple of 8), passed as void*.  Parameters and their gradients are always fp32.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *  - forward / aggregate / gather only enqueue work: they return argument errors at once and
- *    never synchronise the device.  create / set_param / get_param / packing synchronise.
+ *  - forward / backward / aggregate / gather / stale_filter only enqueue work: they return
+ *    argument errors at once and never synchronise the device, so a caller may record them into a
+ *    HIP graph (backward allocates workspace on its first call with dX: make one eager call
+ *    first).  create / set_param / get_param / packing / set_presence / set_labels /
+ *    shared_rows / chunk_generate synchronise.
  *  - Every function returns DGC_OK (0) or an error code; dgc_last_error gives the text.
  *  - A layer object is not thread-safe; different layers may be used from different threads.
  */
