@@ -86,3 +86,28 @@ def test_concat_refusals():
         layer.set_param("rnn.weight_ih", np.zeros((128, 32), np.float32))
     layer.set_param("rnn.weight_ih", np.zeros((128, 64), np.float32))
     layer.destroy()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_concat_random_shapes(seed):
+    """Tiny and ragged shapes: one vertex, one snapshot, windows of one snapshot, F below 8."""
+    from paper_2309_03523_amd.runner import DeviceWorkload
+    rng = np.random.default_rng(9000 + seed)
+    N = int(rng.choice([1, 2, 31, 33, 65]))
+    T = int(rng.integers(1, 6))
+    S = int(rng.choice([32, 64, 128]))
+    F = int(rng.choice([1, 7, 32, 50]))
+    cut = int(rng.integers(0, N + 1))
+    chunks = [c for c in ([0, cut, 0, T], [cut, N, 0, max(1, T // 2)], [cut, N, max(1, T // 2), T]) if c[0] < c[1] and c[2] < c[3]]
+    wl = synth.random_small(9100 + seed, T, N, F, S, S, 3.0, chunks, "lstm", n_struct_layers=2, input_concat=True)
+    dw = DeviceWorkload(wl, gather_mode=str(rng.choice(["in_place", "staged"])))
+    Y, HN = dw.forward(want_state=True)
+    want, want_HN = oracle.forward(wl.graph, wl.chunks, wl.params, wl.X, wl.C, time_kind="lstm", n_struct_layers=2,
+                                   C1=wl.C1, H0=wl.H0, return_state=True, input_concat=True)
+    m = ~np.isnan(want)
+    e_y = rel_err(Y.cpu().numpy()[m], want[m].astype(np.float64))
+    e_h = rel_err(HN.cpu().numpy(), want_HN.astype(np.float64))
+    print(f"seed {seed}: N={N} T={T} F={F} S={S} chunks={len(chunks)}: rel_err Y {e_y:.3e} HN {e_h:.3e}", flush=True)
+    assert e_y < TOL and e_h < TOL
+    assert np.isnan(Y.cpu().numpy()[~m]).all()
+    dw.layer.destroy()
