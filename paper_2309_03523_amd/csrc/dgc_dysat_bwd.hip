@@ -836,7 +836,7 @@ __device__ __forceinline__ void gat_bwd_col_finish(const GatBwdColsArgs& a, int6
 }
 
 template <bool LO>
-__global__ __launch_bounds__(256) void k_gat_bwd_cols(GatBwdColsArgs a) {
+__global__ __launch_bounds__(256, 4) void k_gat_bwd_cols(GatBwdColsArgs a) {   // 4 waves per SIMD: 128 registers
   const int lane = threadIdx.x & 63;
   const int64_t N = a.g.N;
   const int64_t groups_per_t = (N + 15) / 16, n_items = groups_per_t * a.n_used;
