@@ -96,6 +96,73 @@ def test_config5_scaled_forward_and_gradients():
     dd.layer.destroy()
 
 
+def _one_vertex_problem(wl, v, chunk):
+    """The problem whose only covered vertex computes exactly what vertex v of `chunk` does: local
+    vertex 0 is v, the other local vertices are its neighbours of one snapshot each, all outside
+    the one-vertex chunk, so the oracle reads them from the cache handed over here, which holds the
+    row each neighbour is really read from (X inside the chunk's vertex range, the cache outside).
+    Data selection only; all arithmetic stays in the oracle."""
+    v_lo, v_hi, t_lo, t_hi = chunk
+    per_t = []
+    for t in range(t_lo, t_hi):
+        s = wl.graph.snaps[t]
+        per_t.append(s.col[s.rowptr[v]:s.rowptr[v + 1]].astype(np.int64))
+    n_loc = 1 + max(int((c != v).sum()) for c in per_t)
+    w = t_hi - t_lo
+    Xs = np.zeros((w, n_loc, wl.F), np.float32)
+    Cs = np.zeros((w, n_loc, wl.F), np.float32)
+    snaps = []
+    for k, cols in enumerate(per_t):
+        t = t_lo + k
+        Xs[k, 0] = wl.X[t, v]
+        loc = np.zeros(len(cols), np.int32)
+        others = cols != v
+        loc[others] = 1 + np.arange(int(others.sum()), dtype=np.int32)
+        nb = cols[others]
+        inside = (nb >= v_lo) & (nb < v_hi)
+        Cs[k, 1:1 + len(nb)] = np.where(inside[:, None], wl.X[t, nb], wl.C[t, nb])
+        rowptr = np.full(n_loc + 1, len(cols), np.int64)
+        rowptr[0] = 0
+        snaps.append(synth.Snapshot(rowptr, loc))
+    params = dict(wl.params)
+    params["attn.pos"] = wl.params["attn.pos"][t_lo:t_hi]
+    return synth.DynamicGraph(n_loc, snaps), np.array([[0, 1, 0, w]], np.int64), params, Xs, Cs
+
+
+@pytest.mark.timeout(600)            # the full-size case takes about 100 s, most of it generating the inputs
+@pytest.mark.parametrize("scale", [0.25, 1.0])
+def test_config5_sampled(scale):
+    """Config 5 at full size and at a quarter of its vertex count, as bench.py's config5 / config5s
+    workloads launch it (default split thresholds, 128 uneven chunks, hub rows of tens of thousands
+    of neighbours): outputs of a seeded sample of vertices of every chunk, and of the largest hubs,
+    each computed by the oracle on its own."""
+    from paper_2309_03523_amd.runner import DysatDevice
+    wl, _ = synth.config5(seed=0, scale=scale)
+    dd = DysatDevice(wl)
+    got = dd.forward().float().cpu().numpy()
+    assert not np.isnan(got).any()              # the chunks cover every (vertex, snapshot)
+    rng = synth.stream(0, "parity-sample")
+    deg0 = np.diff(wl.graph.snaps[0].rowptr)
+    hubs = set(np.argsort(deg0)[-4:].tolist())
+    worst, n, gs, ws = 0.0, 0, [], []
+    for chunk in wl.chunks.tolist():
+        v_lo, v_hi = chunk[0], chunk[1]
+        pick = set((rng.choice(v_hi - v_lo, size=2, replace=False) + v_lo).tolist()) | {v_lo, v_hi - 1}
+        pick |= {h for h in hubs if v_lo <= h < v_hi}
+        for v in sorted(pick):
+            g1, c1, p1, X1, C1 = _one_vertex_problem(wl, v, chunk)
+            want = dysat.forward(g1, c1, p1, X1, C1, 8)["Y"][:, 0]
+            gs.append(got[chunk[2]:chunk[3], v])
+            ws.append(want)
+            worst = max(worst, rel_err(gs[-1], want, floor=1.0))
+            n += 1
+    e = rel_err(np.stack(gs), np.stack(ws), floor=1.0)
+    print(f"config5@{scale:g}: {n} sampled vertices (largest degree {int(deg0.max())}), Y rel_err {e:.3e} "
+          f"(worst vertex against its own RMS {worst:.3e})", flush=True)
+    assert n >= 128 * 3 and e < TOL and worst < 2 * TOL
+    dd.layer.destroy()
+
+
 def test_attention_argument_errors():
     import torch
     from paper_2309_03523_amd.binding import DgcError
