@@ -206,6 +206,45 @@ def test_config3_scaled(torch_mod):
     dw.layer.destroy()
 
 
+@pytest.mark.timeout(600)            # about 80 s of it generate the inputs
+def test_config3_eighth_size_sampled(torch_mod):
+    """Config 3's window at 1/8 of its vertex count (250k vertices x 32 snapshots, 8 M rows), in the
+    launch configuration bench.py's config3w and config3wc workloads time: outputs and final states
+    of a seeded sample of vertices of every chunk, each computed by the oracle over its whole window,
+    with the LSTM reading the second GCN layer's output and then both layers' outputs."""
+    import dataclasses
+    wl = synth.config3(seed=0, scale=0.125)              # bench.py's workload as it is (zero biases)
+    rng = synth.stream(0, "parity-sample")
+    subset = []
+    for v_lo, v_hi, t_lo, t_hi in wl.chunks.tolist():
+        deg = np.diff(wl.graph.snaps[t_lo].rowptr)[v_lo:v_hi]
+        pick = set(rng.choice(v_hi - v_lo, size=6, replace=False).tolist()) | {0, v_hi - v_lo - 1, int(np.argmax(deg))}
+        subset.append(np.array(sorted(pick)) + v_lo)
+    for concat in (False, True):
+        w = wl if not concat else dataclasses.replace(
+            wl, params=synth.layer_params(0, wl.F, wl.S, wl.H, "lstm", 2, input_concat=True),
+            notes={"input_concat": True})
+        dw = _dw(w, act_hidden="relu", act_out="none")
+        got = dw.forward().cpu().numpy()
+        assert not np.isnan(got).any()          # the chunks cover every (vertex, snapshot)
+        ref = oracle.forward(w.graph, w.chunks, w.params, w.X, w.C, time_kind="lstm", n_struct_layers=2, C1=w.C1,
+                             H0=w.H0, subset=subset, act_hidden="relu", act_out="none", input_concat=concat)
+        m = ~np.isnan(ref)
+        assert m.sum() >= 64 * 7 * 32 * 128
+        err = rel_err(got[m], ref[m])
+        tau = 0.1 * float(np.sqrt(np.mean(ref[m].astype(np.float64) ** 2)))
+        ratio = np.where(m, np.abs(got.astype(np.float64) - ref) / np.maximum(np.abs(ref), tau), 0.0)
+        t_w, v_w, f_w = np.unravel_index(int(np.argmax(ratio)), ratio.shape)
+        per_t = ratio.max(axis=(1, 2))
+        print(f"config3@0.125 concat={concat}: {int(m.sum()) // 128} sampled rows, Y rel_err {err:.3e}; worst at "
+              f"snapshot {t_w}, vertex {v_w} (degree {int(np.diff(wl.graph.snaps[t_w].rowptr)[v_w])}), "
+              f"want {ref[t_w, v_w, f_w]:.4e} got {got[t_w, v_w, f_w]:.4e}, floor {tau:.3e}; per snapshot "
+              + " ".join(f"{x:.1e}" for x in per_t), flush=True)
+        assert err < TOL, err
+        dw.layer.destroy()
+        del dw, got, ref
+
+
 def test_config2_full_size(torch_mod):
     """Config 2 at full size, in the launch configuration bench.py times: packing bit-exact
     against the oracle's packer; outputs compared on a seeded sample of vertices of every chunk
