@@ -9,13 +9,16 @@
 // part of a split row).  The 64 lanes span the feature dimension (1, 2 or 4 floats each), so
 // every neighbour row is one fully coalesced load; column indices and their degree scalings
 // are fetched 64 at a time, one per lane, and handed out with v_readlane so that the row
-// address is wave-uniform.  Eight neighbour rows are in flight per wave.
+// address is wave-uniform.  Eight neighbour rows are in flight per wave.  Rows of 65 to 128
+// floats take the two-rows-per-load variant instead (each half of the wave one neighbour, 16
+// bytes per lane, sixteen rows in flight).
 #include "dgc_internal.h"
 
 namespace dgc {
 namespace {
 
 constexpr int kInflight = 8;
+constexpr int kInflightPair = 8;   // pairs of rows in flight in the two-rows-per-load variant (4 and 12 measured slower)
 
 template <int VEC> struct Vec;
 template <> struct Vec<1> { using T = float; };
@@ -116,6 +119,84 @@ __device__ __forceinline__ void accumulate_edges(const RowCtx& c, int64_t ea, in
   }
 }
 
+template <int VEC>
+__device__ __forceinline__ void store_row(float* out, int fi, int F, int64_t ldm, const float (&acc)[VEC], float scale);
+
+// The same sum for rows of at most 128 floats, two neighbours per load instruction: lanes 0-31 take
+// the even non-zeros of the batch and lanes 32-63 the odd ones, four floats per lane, so that one
+// 16-byte load per lane fetches two whole rows (twice the bytes per instruction of a 64-lane
+// 8-byte load; the aggregation is bound by the rate of load instructions, not by bytes).  Each
+// half ends with the sum over its own neighbours; the caller adds the two halves.
+template <int MODE>
+__device__ __forceinline__ void accumulate_edges_pair(const RowCtx& c, int64_t ea, int64_t eb, int lane, int fi,
+                                                      bool active, float (&acc)[4]) {
+  const bool odd = lane >= 32;
+  for (int64_t eb0 = ea; eb0 < eb; eb0 += kWave) {
+    const int m = (int)((eb - eb0) < kWave ? (eb - eb0) : kWave);
+    int j = 0, loc = 0;
+    float wj = 0.f;
+    if (lane < m) {
+      j = __builtin_nontemporal_load(c.cj + eb0 + lane);  // streamed once
+      wj = c.dinv_t[(MODE == kSigned && j < 0) ? ~j : j];
+      if constexpr (MODE == kStaged) loc = __builtin_nontemporal_load(c.cl + (eb0 - c.e0) + lane);
+    }
+    for (int k = 0; k < m; k += 2 * kInflightPair) {
+      float v[kInflightPair][4];
+      float w[kInflightPair];
+#pragma unroll
+      for (int u = 0; u < kInflightPair; ++u) {
+        w[u] = 0.f;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[u][q] = 0.f;
+        const int e = k + 2 * u;                      // e + 1 <= 63
+        if (e < m) {                                  // wave-uniform
+          const int j0 = __builtin_amdgcn_readlane(j, e), j1 = __builtin_amdgcn_readlane(j, e + 1);
+          const int w0 = __builtin_amdgcn_readlane(__float_as_int(wj), e);
+          const int w1 = __builtin_amdgcn_readlane(__float_as_int(wj), e + 1);
+          const int jj = odd ? j1 : j0;
+          bool take = !odd || e + 1 < m;              // the last non-zero of an odd batch has no partner
+          w[u] = take ? __int_as_float(odd ? w1 : w0) : 0.f;
+          const float* src;
+          if constexpr (MODE == kStaged) {
+            const int l0 = __builtin_amdgcn_readlane(loc, e), l1 = __builtin_amdgcn_readlane(loc, e + 1);
+            const int ll = odd ? l1 : l0;
+            const int64_t nv = c.v_hi - c.v_lo;
+            src = ll < nv ? c.fresh_t + (c.v_lo + ll) * c.ld_fresh : c.stale_t + (ll - nv) * c.ld_stale;
+          } else {
+            const bool in = MODE == kSigned ? jj >= 0 : (jj >= c.v_lo && jj < c.v_hi);
+            const int64_t col = (MODE == kSigned && !in) ? ~jj : jj;
+            src = in ? c.fresh_t + col * c.ld_fresh : c.stale_t + col * c.ld_stale;
+            if (!in && c.skip_stale) { w[u] = 0.f; take = false; }
+          }
+          if (active && take) vload<4>(v[u], src + fi);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kInflightPair; ++u)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[q] = fmaf(w[u], v[u][q], acc[q]);
+    }
+  }
+}
+
+// One output row from the paired sum: halves added, lanes 0-31 store columns 0-127, lanes 32-63
+// zero-fill the pad columns from 128 to the pitch.
+template <int MODE>
+__device__ __forceinline__ void pair_row(const RowCtx& c, int64_t ea, int64_t eb, int lane, int F, int64_t ldm,
+                                         float* out, float scale) {
+  const int fi = (lane & 31) * 4;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  accumulate_edges_pair<MODE>(c, ea, eb, lane, fi, fi < F, acc);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) acc[q] += __shfl_xor(acc[q], 32);
+  if (lane < 32) {
+    store_row<4>(out, fi, F, ldm, acc, scale);
+  } else if (128 + fi < ldm) {
+    const float z[4] = {0.f, 0.f, 0.f, 0.f};
+    vstore<4>(out + 128 + fi, z);
+  }
+}
+
 template <int MODE>
 __device__ __forceinline__ RowCtx make_ctx(const SpmmArgs& a, const Segment& sg) {
   constexpr bool STAGED = MODE == kStaged;
@@ -149,7 +230,7 @@ __device__ __forceinline__ void store_row(float* out, int fi, int F, int64_t ldm
 
 // One wave per group of consecutive rows of a segment.  Rows longer than long_nnz are left to
 // the split-row kernels.
-template <int VEC, int MODE>
+template <int VEC, int MODE, bool PAIR>
 __global__ __launch_bounds__(256) void k_spmm_short(SpmmArgs a) {
   const int lane = threadIdx.x & (kWave - 1);
   const int64_t item = (int64_t)blockIdx.x * (256 / kWave) + (threadIdx.x / kWave);
@@ -170,19 +251,23 @@ __global__ __launch_bounds__(256) void k_spmm_short(SpmmArgs a) {
     if (orow < 0) continue;
     const float di = c.dinv_t[sg.v_lo + r0 + r];
     float* out = a.M + orow * (a.ld_out ? a.ld_out : a.ldm);
-    for (int f0 = 0; f0 < a.ldm; f0 += kWave * VEC) {
-      const int fi = f0 + lane * VEC;
-      float acc[VEC];
+    if constexpr (PAIR) {
+      pair_row<MODE>(c, ea, eb, lane, a.F, a.ldm, out, di);
+    } else {
+      for (int f0 = 0; f0 < a.ldm; f0 += kWave * VEC) {
+        const int fi = f0 + lane * VEC;
+        float acc[VEC];
 #pragma unroll
-      for (int q = 0; q < VEC; ++q) acc[q] = 0.f;
-      accumulate_edges<VEC, MODE>(c, ea, eb, lane, fi, fi < a.F, acc);
-      store_row<VEC>(out, fi, a.F, a.ldm, acc, di);
+        for (int q = 0; q < VEC; ++q) acc[q] = 0.f;
+        accumulate_edges<VEC, MODE>(c, ea, eb, lane, fi, fi < a.F, acc);
+        store_row<VEC>(out, fi, a.F, a.ldm, acc, di);
+      }
     }
   }
 }
 
 // One wave per part of a split row: unscaled partial sums.
-template <int VEC, int MODE>
+template <int VEC, int MODE, bool PAIR>
 __global__ __launch_bounds__(256) void k_spmm_long(SpmmArgs a) {
   const int lane = threadIdx.x & (kWave - 1);
   const int64_t item = (int64_t)blockIdx.x * (256 / kWave) + (threadIdx.x / kWave);
@@ -197,13 +282,17 @@ __global__ __launch_bounds__(256) void k_spmm_long(SpmmArgs a) {
   const int64_t ea = ra + (int64_t)part * a.part_nnz;
   const int64_t eb = (ea + a.part_nnz < rb) ? ea + a.part_nnz : rb;
   float* out = a.partial + item * a.ldm;
-  for (int f0 = 0; f0 < a.ldm; f0 += kWave * VEC) {
-    const int fi = f0 + lane * VEC;
-    float acc[VEC];
+  if constexpr (PAIR) {
+    pair_row<MODE>(c, ea, eb, lane, a.F, a.ldm, out, 1.0f);
+  } else {
+    for (int f0 = 0; f0 < a.ldm; f0 += kWave * VEC) {
+      const int fi = f0 + lane * VEC;
+      float acc[VEC];
 #pragma unroll
-    for (int q = 0; q < VEC; ++q) acc[q] = 0.f;
-    accumulate_edges<VEC, MODE>(c, ea, eb, lane, fi, fi < a.F, acc);
-    store_row<VEC>(out, fi, a.F, a.ldm, acc, 1.0f);
+      for (int q = 0; q < VEC; ++q) acc[q] = 0.f;
+      accumulate_edges<VEC, MODE>(c, ea, eb, lane, fi, fi < a.F, acc);
+      store_row<VEC>(out, fi, a.F, a.ldm, acc, 1.0f);
+    }
   }
 }
 
@@ -238,20 +327,21 @@ __global__ __launch_bounds__(256) void k_spmm_long_reduce(SpmmArgs a) {
   }
 }
 
-template <int VEC>
+template <int VEC, bool PAIR = false>
 void launch_spmm_v(const SpmmArgs& a, hipStream_t st) {
+  constexpr int RV = PAIR ? 2 : VEC;   // the merge of split rows walks the pitch 64 x RV floats at a time
   const int mode = a.halo != nullptr ? kStaged : a.col_signed != nullptr ? kSigned : kInPlace;
   const unsigned gs = (unsigned)((a.n_short + 3) / 4), gl = (unsigned)((a.n_long + 3) / 4);
   if (gs) {
-    if (mode == kStaged) hipLaunchKernelGGL((k_spmm_short<VEC, kStaged>), gs, 256, 0, st, a);
-    else if (mode == kSigned) hipLaunchKernelGGL((k_spmm_short<VEC, kSigned>), gs, 256, 0, st, a);
-    else hipLaunchKernelGGL((k_spmm_short<VEC, kInPlace>), gs, 256, 0, st, a);
+    if (mode == kStaged) hipLaunchKernelGGL((k_spmm_short<VEC, kStaged, PAIR>), gs, 256, 0, st, a);
+    else if (mode == kSigned) hipLaunchKernelGGL((k_spmm_short<VEC, kSigned, PAIR>), gs, 256, 0, st, a);
+    else hipLaunchKernelGGL((k_spmm_short<VEC, kInPlace, PAIR>), gs, 256, 0, st, a);
   }
   if (gl) {
-    if (mode == kStaged) hipLaunchKernelGGL((k_spmm_long<VEC, kStaged>), gl, 256, 0, st, a);
-    else if (mode == kSigned) hipLaunchKernelGGL((k_spmm_long<VEC, kSigned>), gl, 256, 0, st, a);
-    else hipLaunchKernelGGL((k_spmm_long<VEC, kInPlace>), gl, 256, 0, st, a);
-    hipLaunchKernelGGL((k_spmm_long_reduce<VEC>), gl, 256, 0, st, a);
+    if (mode == kStaged) hipLaunchKernelGGL((k_spmm_long<VEC, kStaged, PAIR>), gl, 256, 0, st, a);
+    else if (mode == kSigned) hipLaunchKernelGGL((k_spmm_long<VEC, kSigned, PAIR>), gl, 256, 0, st, a);
+    else hipLaunchKernelGGL((k_spmm_long<VEC, kInPlace, PAIR>), gl, 256, 0, st, a);
+    hipLaunchKernelGGL((k_spmm_long_reduce<RV>), gl, 256, 0, st, a);
   }
 }
 
@@ -278,7 +368,7 @@ __global__ __launch_bounds__(256) void k_gather(const Segment* segs, int64_t nse
 
 void launch_spmm(const SpmmArgs& a, hipStream_t st) {
   if (a.F <= 64) launch_spmm_v<1>(a, st);
-  else if (a.F <= 128) launch_spmm_v<2>(a, st);
+  else if (a.F <= 128) launch_spmm_v<4, true>(a, st);
   else launch_spmm_v<4>(a, st);
 }
 
