@@ -382,6 +382,22 @@ dgc_status_t dgc_stale_filter(const void* E, int64_t lde, void* L, int64_t ldl, 
                               dgc_stale_result_t* result, void* workspace, int64_t workspace_bytes,
                               void* stream);
 
+/* dgc_stale_filter for callers that cannot allocate device memory or hand over a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same filter
+ * with the same arguments and results, except that the block counts and scan temporaries live in a
+ * fixed device array inside the library (272 KiB per GPU, held until the process ends) instead of
+ * `workspace`.  At most dgc_stale_static_max_candidates() = 2^26 candidates (DGC_ERR_UNSUPPORTED
+ * beyond, nothing enqueued).  Calls no hipMalloc / hipFree and no memset; the first call on a
+ * device looks the array's address up (hipGetSymbolAddress, DGC_ERR_DEVICE if that fails).  Every
+ * call on one GPU uses that GPU's one array: calls that overlap in time on the same GPU (two
+ * streams, two threads) race and give undefined send lists - serialise them.  The array keeps the
+ * last call's contents; nothing in it has to start at zero. */
+int64_t dgc_stale_static_max_candidates(void);
+dgc_status_t dgc_stale_filter_static(const void* E, int64_t lde, void* L, int64_t ldl, int64_t R, int32_t F,
+                                     int32_t dtype, const int64_t* rows, int64_t n_rows, double factor,
+                                     double theta, float* dist, int64_t* send_idx, void* send_buf, int64_t lds,
+                                     dgc_stale_result_t* result, void* stream);
+
 /* Text of the last error on this layer, or (layer = NULL) of the last failed create or layer-less
  * call on the calling thread.  Never NULL; valid until the next call on the same layer / thread. */
 const char* dgc_last_error(const dgc_layer_t* layer);

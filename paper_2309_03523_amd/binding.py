@@ -29,6 +29,7 @@ EXPORTS = ["dgc_layer_create", "dgc_layer_destroy", "dgc_layer_set_param", "dgc_
            "dgc_layer_forward", "dgc_layer_backward", "dgc_layer_aggregate", "dgc_layer_gather",
            "dgc_layer_packing", "dgc_layer_set_presence", "dgc_layer_set_labels", "dgc_layer_set_profiling", "dgc_layer_stage_times", "dgc_last_error",
            "dgc_version", "dgc_stale_theta_factor", "dgc_stale_workspace_bytes", "dgc_stale_filter",
+           "dgc_stale_static_max_candidates", "dgc_stale_filter_static",
            "dgc_layer_shared_rows", "dgc_fusion_select", "dgc_chunk_assign", "dgc_chunk_generate"]
 THETA_VARIANT = {"printed": 0, "sigmoid": 1}
 N_STAGES = 13
@@ -95,8 +96,13 @@ def load() -> ct.CDLL:
     lib.dgc_stale_workspace_bytes.restype = i64
     lib.dgc_stale_filter.argtypes = [vp, i64, vp, i64, i64, i32, i32, vp, i64, ct.c_double, ct.c_double, vp, vp, vp, i64,
                                      vp, vp, i64, vp]
+    lib.dgc_stale_filter_static.argtypes = [vp, i64, vp, i64, i64, i32, i32, vp, i64, ct.c_double, ct.c_double, vp, vp, vp,
+                                            i64, vp, vp]
+    lib.dgc_stale_static_max_candidates.argtypes = []
+    lib.dgc_stale_static_max_candidates.restype = i64
     for name in EXPORTS:
-        if name not in ("dgc_last_error", "dgc_version", "dgc_stale_theta_factor", "dgc_stale_workspace_bytes"):
+        if name not in ("dgc_last_error", "dgc_version", "dgc_stale_theta_factor", "dgc_stale_workspace_bytes",
+                        "dgc_stale_static_max_candidates"):
             getattr(lib, name).restype = ct.c_int
     _lib = lib
     return lib
@@ -296,13 +302,18 @@ def stale_workspace_bytes(n_candidates: int) -> int:
     return int(load().dgc_stale_workspace_bytes(int(n_candidates)))
 
 
+def stale_static_max_candidates() -> int:
+    return int(load().dgc_stale_static_max_candidates())
+
+
 def stale_filter(E, L, *, F=None, rows=None, n_rows=None, factor=None, theta=None, dist, send_idx, send_buf=None, result,
-                 workspace, stream=None):
+                 workspace=None, stream=None):
     """dgc_stale_filter on device tensors: E, L [R, ld] fp32 or bfloat16; rows int64 or None (n_rows: how many of
     its entries count, default all; torch gives an empty tensor a NULL pointer, so an empty list is a
     non-empty tensor with n_rows = 0); dist fp32 and
     send_idx int64 with one entry per candidate; send_buf [n, ld] or None; result: 24-byte device
-    tensor (view it with STALE_RESULT_DTYPE after a synchronisation); workspace: device bytes.
+    tensor (view it with STALE_RESULT_DTYPE after a synchronisation); workspace: device bytes, or
+    None for dgc_stale_filter_static (the library's own fixed scratch, nothing allocated).
     Exactly one of factor / theta.  Only enqueues."""
     if (factor is None) == (theta is None):
         raise ValueError("give exactly one of factor and theta")
@@ -312,13 +323,17 @@ def stale_filter(E, L, *, F=None, rows=None, n_rows=None, factor=None, theta=Non
     if E.dtype != L.dtype or (send_buf is not None and send_buf.dtype != E.dtype):
         raise ValueError("E, L and send_buf must have the same element type")
     lib = load()
-    rc = lib.dgc_stale_filter(
-        _dev(E, "E"), int(E.stride(0)), _dev(L, "L"), int(L.stride(0)), int(E.shape[0]),
-        int(E.shape[1] if F is None else F), DTYPE["bf16" if E.element_size() == 2 else "f32"], _dev(rows, "rows"), 0 if rows is None else int(rows.numel() if n_rows is None else n_rows),
-        -1.0 if factor is None else float(factor), 0.0 if theta is None else float(theta), _dev(dist, "dist"),
-        _dev(send_idx, "send_idx"), _dev(send_buf, "send_buf"), 0 if send_buf is None else int(send_buf.stride(0)),
-        _dev(result, "result"), _dev(workspace, "workspace"), int(workspace.numel() * workspace.element_size()),
-        _stream_ptr(stream))
+    head = (_dev(E, "E"), int(E.stride(0)), _dev(L, "L"), int(L.stride(0)), int(E.shape[0]),
+            int(E.shape[1] if F is None else F), DTYPE["bf16" if E.element_size() == 2 else "f32"], _dev(rows, "rows"),
+            0 if rows is None else int(rows.numel() if n_rows is None else n_rows),
+            -1.0 if factor is None else float(factor), 0.0 if theta is None else float(theta), _dev(dist, "dist"),
+            _dev(send_idx, "send_idx"), _dev(send_buf, "send_buf"), 0 if send_buf is None else int(send_buf.stride(0)),
+            _dev(result, "result"))
+    if workspace is None:
+        rc = lib.dgc_stale_filter_static(*head, _stream_ptr(stream))
+    else:
+        rc = lib.dgc_stale_filter(*head, _dev(workspace, "workspace"),
+                                  int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
     if rc != 0:
         raise DgcError(rc, lib.dgc_last_error(None).decode())
 

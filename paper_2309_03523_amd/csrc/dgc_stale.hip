@@ -12,7 +12,17 @@
 //   k_stale_compact   send_idx in ascending order, copies of the selected rows
 #include <cmath>
 
+#include <mutex>
+
 #include "dgc_internal.h"
+
+// Scratch of dgc_stale_filter_static: the block counts, their scan's temporaries and the total, for
+// up to kStaticMaxCandidates candidates.  Every GPU the library runs on holds its own copy until the
+// process ends.  Host code never uses this name as an address: the per-device address comes from
+// hipGetSymbolAddress (static_scratch_ptr below).
+constexpr int64_t kStaticMaxCandidates = int64_t(1) << 26;
+constexpr int64_t kStaticScratchBytes = 272 * 1024;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace dgc {
 namespace {
@@ -261,10 +271,10 @@ int64_t dgc_stale_workspace_bytes(int64_t n_candidates) {
   return 8 * (nb + 1 + scan_tmp_elems(nb) + 1);
 }
 
-dgc_status_t dgc_stale_filter(const void* E, int64_t lde, void* L, int64_t ldl, int64_t R, int32_t F, int32_t dtype,
-                              const int64_t* rows, int64_t n_rows, double factor, double theta, float* dist,
-                              int64_t* send_idx, void* send_buf, int64_t lds, dgc_stale_result_t* result,
-                              void* workspace, int64_t workspace_bytes, void* stream) {
+static dgc_status_t stale_filter_impl(const void* E, int64_t lde, void* L, int64_t ldl, int64_t R, int32_t F, int32_t dtype,
+                                      const int64_t* rows, int64_t n_rows, double factor, double theta, float* dist,
+                                      int64_t* send_idx, void* send_buf, int64_t lds, dgc_stale_result_t* result,
+                                      void* workspace, int64_t workspace_bytes, void* stream) {
   auto bad = [](dgc_status_t code, const char* msg) { set_thread_error(msg); return code; };
   if (!E || !L || !result || !workspace) return bad(DGC_ERR_INVALID_ARG, "stale filter: NULL argument");
   if (R < 0 || F < 1 || F > 4096) return bad(DGC_ERR_INVALID_ARG, "stale filter: R must be >= 0 and F in [1, 4096]");
@@ -307,6 +317,58 @@ dgc_status_t dgc_stale_filter(const void* E, int64_t lde, void* L, int64_t ldl, 
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return bad(DGC_ERR_DEVICE, hipGetErrorString(e));
   return DGC_OK;
+}
+
+dgc_status_t dgc_stale_filter(const void* E, int64_t lde, void* L, int64_t ldl, int64_t R, int32_t F, int32_t dtype,
+                              const int64_t* rows, int64_t n_rows, double factor, double theta, float* dist,
+                              int64_t* send_idx, void* send_buf, int64_t lds, dgc_stale_result_t* result,
+                              void* workspace, int64_t workspace_bytes, void* stream) {
+  return stale_filter_impl(E, lde, L, ldl, R, F, dtype, rows, n_rows, factor, theta, dist, send_idx, send_buf, lds,
+                           result, workspace, workspace_bytes, stream);
+}
+
+int64_t dgc_stale_static_max_candidates(void) { return kStaticMaxCandidates; }
+
+// Address of this device's copy of `scratch`, looked up once per device with that device current.
+static void* static_scratch_ptr(std::string* err) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptr[kMaxDevices] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    *err = std::string("stale filter (static): hipGetDevice: ") + (e != hipSuccess ? hipGetErrorString(e) : "device index out of range");
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      *err = std::string("stale filter (static): hipGetSymbolAddress: ") + hipGetErrorString(e);
+      return nullptr;
+    }
+    ptr[dev] = p;
+  }
+  return ptr[dev];
+}
+
+dgc_status_t dgc_stale_filter_static(const void* E, int64_t lde, void* L, int64_t ldl, int64_t R, int32_t F,
+                                     int32_t dtype, const int64_t* rows, int64_t n_rows, double factor, double theta,
+                                     float* dist, int64_t* send_idx, void* send_buf, int64_t lds,
+                                     dgc_stale_result_t* result, void* stream) {
+  const int64_t n = rows ? n_rows : R;
+  if (n > kStaticMaxCandidates || dgc_stale_workspace_bytes(n > 0 ? n : 0) > kStaticScratchBytes) {
+    set_thread_error("stale filter (static): more than dgc_stale_static_max_candidates() candidates");
+    return DGC_ERR_UNSUPPORTED;
+  }
+  std::string err;
+  void* ws = static_scratch_ptr(&err);
+  if (!ws) { set_thread_error(err); return DGC_ERR_DEVICE; }
+  // Nothing in the scratch has to start at zero: the count kernel writes every block count of this
+  // call, the scan writes its temporaries and the total before anything reads them.
+  return stale_filter_impl(E, lde, L, ldl, R, F, dtype, rows, n_rows, factor, theta, dist, send_idx, send_buf, lds,
+                           result, ws, kStaticScratchBytes, stream);
 }
 
 }  // extern "C"
