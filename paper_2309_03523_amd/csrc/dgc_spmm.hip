@@ -296,7 +296,9 @@ __global__ __launch_bounds__(256) void k_spmm_long(SpmmArgs a) {
   }
 }
 
-// Sum the parts of each split row in part order (fixed order: results are reproducible).
+// Sum the parts of each split row in part order (fixed order: results are reproducible), in
+// double: a hub row's sum runs over tens of thousands of terms, and the merge of its parts is the
+// one place where a wider accumulator costs nothing (a few thousand rows per launch).
 template <int VEC>
 __global__ __launch_bounds__(256) void k_spmm_long_reduce(SpmmArgs a) {
   const int lane = threadIdx.x & (kWave - 1);
@@ -314,16 +316,19 @@ __global__ __launch_bounds__(256) void k_spmm_long_reduce(SpmmArgs a) {
   for (int f0 = 0; f0 < a.ldm; f0 += kWave * VEC) {
     const int fi = f0 + lane * VEC;
     if (fi >= a.ldm) continue;
-    float acc[VEC];
+    double sum[VEC];
 #pragma unroll
-    for (int q = 0; q < VEC; ++q) acc[q] = 0.f;
+    for (int q = 0; q < VEC; ++q) sum[q] = 0.0;
     for (int p = 0; p < parts; ++p) {
       float v[VEC];
       vload<VEC>(v, a.partial + (item + p) * a.ldm + fi);
 #pragma unroll
-      for (int q = 0; q < VEC; ++q) acc[q] += v[q];
+      for (int q = 0; q < VEC; ++q) sum[q] += (double)v[q];
     }
-    store_row<VEC>(out, fi, a.F, a.ldm, acc, di);
+    float acc[VEC];
+#pragma unroll
+    for (int q = 0; q < VEC; ++q) acc[q] = (float)(sum[q] * (double)di);
+    store_row<VEC>(out, fi, a.F, a.ldm, acc, 1.0f);
   }
 }
 

@@ -6,8 +6,10 @@ from typing import Optional
 
 import numpy as np
 
-from . import synth
 from .binding import DgcLayer
+
+# Optional progress sink for large uploads: a callable taking one string, None = silent.
+progress = None
 
 
 class DeviceWorkload:
@@ -37,8 +39,8 @@ class DeviceWorkload:
             buf = torch.full((T, N, ld), float("nan"), dtype=torch.float32, device=dev)
             for t in range(T):      # snapshot by snapshot: no second full-size device copy
                 buf[t, :, :F] = torch.from_numpy(a[t]).to(dev)
-                if a.nbytes >= (1 << 32) and (t + 1) % max(1, T // 4) == 0 and synth.progress:
-                    synth.progress(f"  upload {tuple(a.shape)}: {t + 1}/{T} snapshots")
+                if a.nbytes >= (1 << 32) and (t + 1) % max(1, T // 4) == 0 and progress:
+                    progress(f"  upload {tuple(a.shape)}: {t + 1}/{T} snapshots")
             return buf[:, :, :F] if ld != F else buf
 
         self.X = up(wl.X, pitch)

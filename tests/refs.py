@@ -57,6 +57,30 @@ def brute_pack(graph, chunks) -> dict:
             "col_local": np.array(col_local, np.int32)}
 
 
+def parity(got: np.ndarray, want: np.ndarray) -> dict:
+    """The error figures every comparison reports: the floored relative error at tau = 1e-2 RMS
+    and at tau = 1e-1 RMS (max |got - want| / max(|want|, tau)), the plain largest absolute error
+    in units of RMS(want), and the 99.9th percentile of the unfloored relative error."""
+    got = np.asarray(got, np.float64).ravel()
+    want = np.asarray(want, np.float64).ravel()
+    if not want.size:
+        return {"floor_1e-2": 0.0, "floor_1e-1": 0.0, "max_abs_over_rms": 0.0, "p999_rel": 0.0}
+    rms = max(float(np.sqrt(np.mean(want * want))), 1e-300)
+    d = np.abs(got - want)
+    a = np.abs(want)
+    nz = a > 0
+    return {"floor_1e-2": float(np.max(d / np.maximum(a, 1e-2 * rms))),
+            "floor_1e-1": float(np.max(d / np.maximum(a, 1e-1 * rms))),
+            "max_abs_over_rms": float(d.max() / rms),
+            "p999_rel": float(np.quantile(d[nz] / a[nz], 0.999)) if nz.any() else 0.0}
+
+
+def parity_str(got: np.ndarray, want: np.ndarray) -> str:
+    p = parity(got, want)
+    return (f"rel err floored at 1e-2 RMS {p['floor_1e-2']:.2e}, at 1e-1 RMS {p['floor_1e-1']:.2e}; "
+            f"max abs / RMS {p['max_abs_over_rms']:.2e}; p99.9 unfloored rel {p['p999_rel']:.2e}")
+
+
 def rel_err(got: np.ndarray, want: np.ndarray, floor: float = 1e-1) -> float:
     """max |got - want| / max(|want|, tau), tau = floor * RMS(want): the elementwise relative
     error with a floor, since a plain relative error is unbounded near zero.  floor = 0.1 for

@@ -5,7 +5,7 @@ import pytest
 
 import oracle
 from oracle import tfusion
-from paper_2309_03523_amd import synth
+from workloads import synth
 from refs import rel_err
 
 pytestmark = pytest.mark.gpu

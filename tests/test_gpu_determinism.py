@@ -4,7 +4,7 @@ runs of the same call give the same bits (forward outputs, final states, losses,
 import numpy as np
 import pytest
 
-from paper_2309_03523_amd import synth
+from workloads import synth
 
 pytestmark = pytest.mark.gpu
 

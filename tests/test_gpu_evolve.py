@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 import oracle
-from paper_2309_03523_amd import synth
+from workloads import synth
 from refs import rel_err
 
 pytestmark = pytest.mark.gpu

@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 from oracle import fusion
-from paper_2309_03523_amd import synth
+from workloads import synth
 
 pytestmark = pytest.mark.gpu
 

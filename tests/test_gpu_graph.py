@@ -5,7 +5,7 @@ work and synchronisations between the replays."""
 import numpy as np
 import pytest
 
-from paper_2309_03523_amd import synth
+from workloads import synth
 
 pytestmark = pytest.mark.gpu
 

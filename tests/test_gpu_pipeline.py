@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 from oracle import chunkgen, labelled, stale
-from paper_2309_03523_amd import synth
+from workloads import synth
 from refs import rel_err
 
 pytestmark = pytest.mark.gpu

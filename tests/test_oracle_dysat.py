@@ -9,7 +9,7 @@ import pytest
 import torch
 
 from oracle import dysat
-from paper_2309_03523_amd import synth
+from workloads import synth
 from refs import edges_of
 
 

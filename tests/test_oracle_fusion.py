@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 from oracle import fusion
-from paper_2309_03523_amd import synth
+from workloads import synth
 
 CHUNKS = [[0, 70, 0, 8], [70, 201, 0, 5], [70, 201, 5, 8], [201, 260, 2, 8]]
 

@@ -4,7 +4,7 @@ import pytest
 
 import oracle
 from oracle import labelled
-from paper_2309_03523_amd import synth
+from workloads import synth
 from refs import dense_norm_adj, edges_of
 
 T, N, F, S = 5, 31, 6, 8

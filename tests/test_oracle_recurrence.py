@@ -4,7 +4,7 @@ import pytest
 import torch
 
 import oracle
-from paper_2309_03523_amd import synth
+from workloads import synth
 from refs import dense_aggregate, dense_norm_adj, edges_of
 
 

@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 from oracle import stale
-from paper_2309_03523_amd import synth
+from workloads import synth
 
 
 def test_theta_closed_forms():

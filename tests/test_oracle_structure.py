@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 import oracle
-from paper_2309_03523_amd import synth
+from workloads import synth
 from refs import brute_pack, dense_aggregate, dense_norm_adj, edges_of
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden", "hand_example.txt")

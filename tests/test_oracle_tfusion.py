@@ -9,7 +9,7 @@ import pytest
 import torch
 
 from oracle import tfusion
-from paper_2309_03523_amd import synth
+from workloads import synth
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 

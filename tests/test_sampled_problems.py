@@ -5,7 +5,7 @@ import numpy as np
 
 import oracle
 from oracle import dysat
-from paper_2309_03523_amd import synth
+from workloads import synth
 
 
 def test_sampled_problem_of_the_evolving_gcn_equals_the_whole():

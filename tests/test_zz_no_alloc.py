@@ -6,7 +6,7 @@ call's contents then)."""
 import numpy as np
 import pytest
 
-from paper_2309_03523_amd import synth
+from workloads import synth
 
 pytestmark = pytest.mark.gpu
 
