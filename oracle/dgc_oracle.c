@@ -295,15 +295,36 @@ int dgc_oracle_forward(int32_t T, int64_t N, const int64_t *const *rowptr,
     if (n_struct_layers == 2) {
       Z1 = (double *)malloc(sizeof(double) * (size_t)(w * nv * S));
       if (!Z1) return -1;
+      /* With a subset, only the first-layer rows that a subset vertex reads are evaluated: its
+       * own row and those of its neighbours inside the chunk range, snapshot by snapshot.  The
+       * others would never be looked at; their slots of Z1 stay unset. */
+      uint8_t *need = NULL;
+      if (subset_ptr) {
+        need = (uint8_t *)calloc((size_t)(w * nv), 1);
+        if (!need) { free(Z1); return -1; }
+        for (int64_t q = subset_ptr[k]; q < subset_ptr[k + 1]; ++q) {
+          const int64_t i = subset_idx[q];
+          if (i < v_lo || i >= v_hi) { free(need); free(Z1); return -2; }
+          for (int64_t t = t_lo; t < t_hi; ++t) {
+            need[(t - t_lo) * nv + (i - v_lo)] = 1;
+            for (int64_t e = rowptr[t][i]; e < rowptr[t][i + 1]; ++e) {
+              const int64_t j = col[t][e];
+              if (j >= v_lo && j < v_hi) need[(t - t_lo) * nv + (j - v_lo)] = 1;
+            }
+          }
+        }
+      }
       for (int64_t t = t_lo; t < t_hi; ++t) {
 #pragma omp parallel for schedule(dynamic, 64)
         for (int64_t i = v_lo; i < v_hi; ++i) {
+          if (need && !need[(t - t_lo) * nv + (i - v_lo)]) continue;
           double *m = (double *)malloc(sizeof(double) * (size_t)F);
           aggregate_row(N, rowptr[t], col[t], t, i, v_lo, v_hi, X, ldx, NULL, C, ldc, F, m);
           dense_row(W0, b0, S, F, m, act_hidden, Z1 + ((t - t_lo) * nv + (i - v_lo)) * (int64_t)S);
           free(m);
         }
       }
+      free(need);
     }
     const int64_t n_sub = subset_ptr ? subset_ptr[k + 1] - subset_ptr[k] : nv;
 #pragma omp parallel for schedule(dynamic, 16)

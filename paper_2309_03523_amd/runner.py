@@ -20,10 +20,16 @@ class DeviceWorkload:
         import torch
         dev = torch.device("cuda:0")
         self.wl = wl
-        g = wl.graph
-        self.rowptr = [torch.from_numpy(s.rowptr).to(dev) for s in g.snaps]
-        self.colidx = [torch.from_numpy(s.col).to(dev) for s in g.snaps]
-        self.layer = DgcLayer(self.rowptr, self.colidx, g.N, wl.chunks, F=wl.F, S=wl.S, H=wl.H,
+        on_device = bool(getattr(wl, "on_device", False))   # graph and tensors already in GPU memory
+        if on_device:
+            N, T = wl.N, wl.T
+            self.rowptr, self.colidx = wl.rowptr, wl.col
+        else:
+            g = wl.graph
+            N, T = g.N, g.T
+            self.rowptr = [torch.from_numpy(s.rowptr).to(dev) for s in g.snaps]
+            self.colidx = [torch.from_numpy(s.col).to(dev) for s in g.snaps]
+        self.layer = DgcLayer(self.rowptr, self.colidx, N, wl.chunks, F=wl.F, S=wl.S, H=wl.H,
                               time_kind=wl.time_kind, n_struct_layers=wl.n_struct_layers,
                               act_hidden=act_hidden, act_out=act_out, gather_mode=gather_mode,
                               validate_level=validate_level, struct_kind=struct_kind,
@@ -43,11 +49,14 @@ class DeviceWorkload:
                     progress(f"  upload {tuple(a.shape)}: {t + 1}/{T} snapshots")
             return buf[:, :, :F] if ld != F else buf
 
-        self.X = up(wl.X, pitch)
-        self.C = up(wl.C, pitch)
-        self.C1 = up(wl.C1)
-        self.H0 = torch.from_numpy(wl.H0).to(dev) if wl.H0 is not None else None
-        self.Y = torch.full((g.T, g.N, self.layer.out_dim), float("nan"), dtype=torch.float32, device=dev)
+        if on_device:
+            self.X, self.C, self.C1, self.H0 = wl.X[:, :, :wl.F], wl.C[:, :, :wl.F], wl.C1, wl.H0
+        else:
+            self.X = up(wl.X, pitch)
+            self.C = up(wl.C, pitch)
+            self.C1 = up(wl.C1)
+            self.H0 = torch.from_numpy(wl.H0).to(dev) if wl.H0 is not None else None
+        self.Y = torch.full((T, N, self.layer.out_dim), float("nan"), dtype=torch.float32, device=dev)
 
     def forward(self, *, reset_mask=None, want_state: bool = False, use_h0: bool = True, C=None, C1=None):
         import torch

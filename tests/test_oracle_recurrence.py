@@ -126,15 +126,18 @@ def test_fused_equals_one_chunk_at_a_time(kind):
 
 
 def test_subset_evaluation_equals_full():
+    """A subset evaluates only the first-layer rows its vertices read; what it returns for them is
+    bit for bit what the evaluation of every row returns (one and two structure layers, the time
+    encoder reading the last layer or both)."""
     T, N, F, S, H = 4, 30, 4, 5, 5
     chunks = np.array([[0, 13, 0, 4], [13, 30, 0, 4]], np.int64)
-    for kind, layers in (("gru", 1), ("lstm", 2)):
-        wl = synth.random_small(66, T, N, F, S, H, 3.0, chunks, kind, layers)
+    for kind, layers, cat in (("gru", 1, False), ("lstm", 2, False), ("lstm", 2, True), ("none", 2, False)):
+        wl = synth.random_small(66, T, N, F, S, H, 3.0, chunks, kind, layers, input_concat=cat)
         full = oracle.forward(wl.graph, chunks, wl.params, wl.X, wl.C, time_kind=kind, H0=wl.H0,
-                              n_struct_layers=layers, C1=wl.C1)
+                              n_struct_layers=layers, C1=wl.C1, input_concat=cat)
         subset = [[1, 5, 12], [13, 29]]
         part = oracle.forward(wl.graph, chunks, wl.params, wl.X, wl.C, time_kind=kind, H0=wl.H0,
-                              n_struct_layers=layers, C1=wl.C1, subset=subset)
+                              n_struct_layers=layers, C1=wl.C1, subset=subset, input_concat=cat)
         rows = [1, 5, 12, 13, 29]
         assert np.array_equal(part[:, rows], full[:, rows])
         others = [i for i in range(N) if i not in rows]
