@@ -121,53 +121,8 @@ def test_evolve_long_recurrence(F):
 
 
 def _sampled_problem(wl, picks):
-    """One small problem in which local vertex i, a chunk of its own, computes exactly what the
-    sampled vertex picks[i] = (v, chunk) does.  The other local vertices are copies of the sampled
-    vertices' neighbours, one per (sampled vertex, snapshot, neighbour): each lies outside every
-    one-vertex chunk, so the oracle reads it from the cache handed over here, which holds the row
-    the neighbour is really read from (X inside the real chunk's vertex range, the cache
-    outside), and its row length is the neighbour's real degree, which the normalisation uses.
-    Data selection only; all arithmetic stays in the oracle."""
-    g, T, m = wl.graph, wl.graph.T, len(picks)
-    rows = [[None] * m for _ in range(T)]
-    copies = np.zeros(T, np.int64)
-    for t in range(T):
-        s = g.snaps[t]
-        for i, (v, ch) in enumerate(picks):
-            if ch[2] <= t < ch[3]:
-                rows[t][i] = s.col[s.rowptr[v]:s.rowptr[v + 1]].astype(np.int64)
-                copies[t] += int((rows[t][i] != v).sum())
-    n_loc = m + int(copies.max())
-    Xs = np.zeros((T, n_loc, wl.F), np.float32)
-    Cs = np.zeros((T, n_loc, wl.F), np.float32)
-    snaps = []
-    for t in range(T):
-        deg = np.diff(g.snaps[t].rowptr)
-        row_len = np.zeros(n_loc, np.int64)
-        cols, nxt = [], m
-        for i, (v, ch) in enumerate(picks):
-            c = rows[t][i]
-            if c is None:
-                continue
-            other = c != v
-            nb = c[other]
-            loc = np.full(len(c), i, np.int32)
-            loc[other] = nxt + np.arange(len(nb), dtype=np.int32)
-            inside = (nb >= ch[0]) & (nb < ch[1])
-            Xs[t, i] = wl.X[t, v]
-            Cs[t, nxt:nxt + len(nb)] = np.where(inside[:, None], wl.X[t, nb], wl.C[t, nb])
-            row_len[i] = len(c)
-            row_len[nxt:nxt + len(nb)] = deg[nb]
-            cols.append(loc)
-            nxt += len(nb)
-        rowptr = np.concatenate([[0], np.cumsum(row_len)]).astype(np.int64)
-        col = np.zeros(int(rowptr[-1]), np.int32)          # the copies' own rows are never walked
-        if cols:
-            head = np.concatenate(cols)
-            col[:len(head)] = head
-        snaps.append(synth.Snapshot(rowptr, col))
-    chunks = np.array([[i, i + 1, ch[2], ch[3]] for i, (_, ch) in enumerate(picks)], np.int64)
-    return synth.DynamicGraph(n_loc, snaps), chunks, Xs, Cs
+    from workloads import sampling
+    return sampling.one_hop_problem(wl.graph, picks, wl.X, wl.C, wl.F)
 
 
 @pytest.mark.timeout(600)

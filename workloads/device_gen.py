@@ -138,6 +138,25 @@ class HostMirror:
         self.covered[t][idx] = True
 
 
+class RowFetcher:
+    """Indexable as [t, ids] (ids an integer or an integer array) like a host array [T, N, F]:
+    fetches those rows of a device tensor [T, N, ld]."""
+
+    def __init__(self, dev_tensor, F: int):
+        self.dev, self.F = dev_tensor, F
+
+    def __getitem__(self, key):
+        import torch
+        t, idx = key
+        if np.isscalar(idx) or getattr(idx, "ndim", 1) == 0:
+            return self.dev[int(t), int(idx), :self.F].cpu().numpy()
+        idx = np.asarray(idx, np.int64)
+        if idx.size == 0:
+            return np.zeros((0, self.F), np.float32)
+        sel = torch.from_numpy(idx).to(self.dev.device)
+        return self.dev[int(t)].index_select(0, sel)[:, :self.F].cpu().numpy()
+
+
 def _pitched_normal(T: int, N: int, F: int, ld: int, gen, scale: float = 1.0, base=None, say=None, what=""):
     """[T, N, ld] fp32 on the device: columns < F are scale * N(0,1) (+ base), pad columns NaN."""
     import torch
