@@ -47,6 +47,13 @@ def threads() -> int:
     return int(lib().dgc_oracle_threads())
 
 
+def set_threads(n: int) -> None:
+    """Number of OpenMP threads the oracle's row loops use from now on (bench.py times it on one
+    core and on all of them); the arithmetic does not depend on it."""
+    lib()
+    ct.CDLL("libgomp.so.1").omp_set_num_threads(ct.c_int(int(n)))
+
+
 def _p(a: Optional[np.ndarray], ctype):
     if a is None:
         return ct.cast(None, ct.POINTER(ctype))

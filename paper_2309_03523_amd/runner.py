@@ -29,11 +29,15 @@ class DeviceWorkload:
             N, T = g.N, g.T
             self.rowptr = [torch.from_numpy(s.rowptr).to(dev) for s in g.snaps]
             self.colidx = [torch.from_numpy(s.col).to(dev) for s in g.snaps]
+        import time
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
         self.layer = DgcLayer(self.rowptr, self.colidx, N, wl.chunks, F=wl.F, S=wl.S, H=wl.H,
                               time_kind=wl.time_kind, n_struct_layers=wl.n_struct_layers,
                               act_hidden=act_hidden, act_out=act_out, gather_mode=gather_mode,
                               validate_level=validate_level, struct_kind=struct_kind,
                               lstm_input_concat=bool(wl.notes.get("input_concat", False)), **layer_kw)
+        self.create_s = time.perf_counter() - t0     # dgc_layer_create: validation, packing, workspace (it synchronises)
         self.layer.set_params(wl.params)
 
         def up(a, ld=None):
@@ -86,19 +90,31 @@ class DysatDevice:
     """Device copies (bfloat16) of a graph-attention workload plus a created layer."""
 
     def __init__(self, wl, *, validate_level: int = 0, **layer_kw):
+        import time
         import torch
         dev = torch.device("cuda:0")
         self.wl = wl
-        g = wl.graph
-        self.rowptr = [torch.from_numpy(s.rowptr).to(dev) for s in g.snaps]
-        self.colidx = [torch.from_numpy(s.col).to(dev) for s in g.snaps]
-        self.layer = DgcLayer(self.rowptr, self.colidx, g.N, wl.chunks, F=wl.F, S=wl.S, H=wl.H, time_kind="self_attn",
+        on_device = bool(getattr(wl, "on_device", False))   # graph and bfloat16 tensors already in GPU memory
+        if on_device:
+            N, T = wl.N, wl.T
+            self.rowptr, self.colidx = wl.rowptr, wl.col
+        else:
+            N, T = wl.graph.N, wl.graph.T
+            self.rowptr = [torch.from_numpy(s.rowptr).to(dev) for s in wl.graph.snaps]
+            self.colidx = [torch.from_numpy(s.col).to(dev) for s in wl.graph.snaps]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        self.layer = DgcLayer(self.rowptr, self.colidx, N, wl.chunks, F=wl.F, S=wl.S, H=wl.H, time_kind="self_attn",
                               struct_kind="gat", dtype="bf16", heads=wl.notes["heads"],
                               validate_level=validate_level, **layer_kw)
+        self.create_s = time.perf_counter() - t0
         self.layer.set_params(wl.params)
-        self.X = torch.from_numpy(wl.X).to(dev).to(torch.bfloat16)
-        self.C = torch.from_numpy(wl.C).to(dev).to(torch.bfloat16)
-        self.Y = torch.full((g.T, g.N, wl.S), float("nan"), dtype=torch.bfloat16, device=dev)
+        if on_device:
+            self.X, self.C = wl.X, wl.C
+        else:
+            self.X = torch.from_numpy(wl.X).to(dev).to(torch.bfloat16)
+            self.C = torch.from_numpy(wl.C).to(dev).to(torch.bfloat16)
+        self.Y = torch.full((T, N, wl.S), float("nan"), dtype=torch.bfloat16, device=dev)
 
     def forward(self, C=None):
         import torch

@@ -97,36 +97,8 @@ def test_config5_scaled_forward_and_gradients():
 
 
 def _one_vertex_problem(wl, v, chunk):
-    """The problem whose only covered vertex computes exactly what vertex v of `chunk` does: local
-    vertex 0 is v, the other local vertices are its neighbours of one snapshot each, all outside
-    the one-vertex chunk, so the oracle reads them from the cache handed over here, which holds the
-    row each neighbour is really read from (X inside the chunk's vertex range, the cache outside).
-    Data selection only; all arithmetic stays in the oracle."""
-    v_lo, v_hi, t_lo, t_hi = chunk
-    per_t = []
-    for t in range(t_lo, t_hi):
-        s = wl.graph.snaps[t]
-        per_t.append(s.col[s.rowptr[v]:s.rowptr[v + 1]].astype(np.int64))
-    n_loc = 1 + max(int((c != v).sum()) for c in per_t)
-    w = t_hi - t_lo
-    Xs = np.zeros((w, n_loc, wl.F), np.float32)
-    Cs = np.zeros((w, n_loc, wl.F), np.float32)
-    snaps = []
-    for k, cols in enumerate(per_t):
-        t = t_lo + k
-        Xs[k, 0] = wl.X[t, v]
-        loc = np.zeros(len(cols), np.int32)
-        others = cols != v
-        loc[others] = 1 + np.arange(int(others.sum()), dtype=np.int32)
-        nb = cols[others]
-        inside = (nb >= v_lo) & (nb < v_hi)
-        Cs[k, 1:1 + len(nb)] = np.where(inside[:, None], wl.X[t, nb], wl.C[t, nb])
-        rowptr = np.full(n_loc + 1, len(cols), np.int64)
-        rowptr[0] = 0
-        snaps.append(synth.Snapshot(rowptr, loc))
-    params = dict(wl.params)
-    params["attn.pos"] = wl.params["attn.pos"][t_lo:t_hi]
-    return synth.DynamicGraph(n_loc, snaps), np.array([[0, 1, 0, w]], np.int64), params, Xs, Cs
+    from workloads import sampling
+    return sampling.one_vertex_problem(wl.graph, v, chunk, wl.X, wl.C, wl.F, wl.params)
 
 
 @pytest.mark.timeout(600)            # the full-size case takes about 100 s, most of it generating the inputs

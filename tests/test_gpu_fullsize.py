@@ -27,23 +27,7 @@ def _say(msg):
     print(msg, flush=True)
 
 
-def _release(*objs):
-    """Give device memory back even if a failing test's traceback still refers to the tensors: the
-    full-size cases need most of the GPU's memory each."""
-    import gc
-    import torch
-    for o in objs:
-        if o is None:
-            continue
-        if isinstance(o, torch.Tensor):
-            o.untyped_storage().resize_(0)
-        elif hasattr(o, "layer"):                       # a DeviceWorkload: its inputs are views of the data's
-            o.layer.destroy()
-            _release(o.Y)
-        else:                                           # a DeviceData
-            _release(*[v for v in vars(o).values() if isinstance(v, torch.Tensor)], *o.rowptr, *o.col)
-    gc.collect()
-    torch.cuda.empty_cache()
+_release = device_gen.release
 
 
 def _config3_compare(data, n_random_chunks, per_chunk, all_chunks=False, validate_level=0):
@@ -140,26 +124,6 @@ def _config4_run(data, target):
     return dw, Y, dX, float(loss.item())
 
 
-def _bounded(hg, v, ch, max_deg) -> bool:
-    """All of v's neighbours inside the chunk's range have at most max_deg stored non-zeros in every
-    snapshot of the window (keeps the two-hop stand-in problem small)."""
-    for t in range(ch[2], ch[3]):
-        s = hg.snaps[t]
-        nb = s.col[s.rowptr[v]:s.rowptr[v + 1]].astype(np.int64)
-        nb = nb[(nb >= ch[0]) & (nb < ch[1])]
-        if int((s.rowptr[nb + 1] - s.rowptr[nb]).max()) > max_deg:
-            return False
-    return True
-
-
-def _bounded_pick(hg, ch, rng, max_deg, tries=2000):
-    for _ in range(tries):
-        v = int(rng.integers(ch[0], ch[1]))
-        if _bounded(hg, v, ch, max_deg):
-            return v
-    raise AssertionError("no vertex with bounded neighbours found")
-
-
 def _config4_compare(data, target, n_random, hub_cap, grad_cap):
     import torch
     dw, Y, dX, loss = _config4_run(data, target)
@@ -193,9 +157,9 @@ def _config4_compare_body(data, target, n_random, hub_cap, grad_cap, dw, Y, dX, 
         e = rel_err(g, wv)
         _say(f"{data.name} window {w}: Y of {len(picks)} vertices of {len(win)} chunks, oracle {dt:.1f} s: " + parity_str(g, wv))
         worst_y, n_y = max(worst_y, e), n_y + len(picks)
-        gp = [(_bounded_pick(hg, ch, rng, grad_cap), ch) for ch in win for _ in range(2)]
+        gp = [(sampling.bounded_pick(hg, ch, rng, grad_cap), ch) for ch in win for _ in range(2)]
         last = win[-1]                                              # and the qualifying vertex closest to the end
-        gp.append((next(v for v in range(last[1] - 1, last[0] - 1, -1) if _bounded(hg, v, last, grad_cap)), last))
+        gp.append((next(v for v in range(last[1] - 1, last[0] - 1, -1) if sampling.bounded_neighbours(hg, v, last, grad_cap)), last))
         ys, dxs, held, dt = sampled.evolve_input_gradient_reference(data, hg, gp, data.params, target, data.rows)
         # The ReLU gate [Y > 0] is a decision each side takes on its own sums: where an output lies
         # within rounding of zero the two may decide differently, and the gradient of every row that

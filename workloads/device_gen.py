@@ -108,6 +108,28 @@ class DeviceData:
                                            for r, c in zip(self.rowptr, self.col)])
 
 
+def release(*objs) -> None:
+    """Give device memory back at once, even if something (a failing test's traceback, say) still
+    refers to the tensors: the full-size configurations need most of the GPU's memory each.  Takes
+    tensors, DeviceData objects and anything with a `.layer` and a `.Y` (a created layer's holder:
+    the layer is destroyed, its output tensor released; its inputs are views of the data's)."""
+    import gc
+    import torch
+    for o in objs:
+        if o is None:
+            continue
+        if isinstance(o, torch.Tensor):
+            o.untyped_storage().resize_(0)
+        elif hasattr(o, "layer"):
+            o.layer.destroy()
+            release(getattr(o, "Y", None))
+        else:
+            release(*[v for v in vars(o).values() if isinstance(v, torch.Tensor)], *o.rowptr, *o.col,
+                    *[v for v in o.notes.values() if isinstance(v, torch.Tensor)])
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
 class HostMirror:
     """Host array [T, N, F] of which only the rows asked for hold the device tensor's values (the
     rest is untouched zero pages that take no memory): what the oracle is handed when it computes a
@@ -149,12 +171,12 @@ class RowFetcher:
         import torch
         t, idx = key
         if np.isscalar(idx) or getattr(idx, "ndim", 1) == 0:
-            return self.dev[int(t), int(idx), :self.F].cpu().numpy()
+            return self.dev[int(t), int(idx), :self.F].float().cpu().numpy()
         idx = np.asarray(idx, np.int64)
         if idx.size == 0:
             return np.zeros((0, self.F), np.float32)
         sel = torch.from_numpy(idx).to(self.dev.device)
-        return self.dev[int(t)].index_select(0, sel)[:, :self.F].cpu().numpy()
+        return self.dev[int(t)].index_select(0, sel)[:, :self.F].float().cpu().numpy()
 
 
 def _pitched_normal(T: int, N: int, F: int, ld: int, gen, scale: float = 1.0, base=None, say=None, what=""):
@@ -253,4 +275,51 @@ def config4(seed: int = 0, scale: float = 1.0, say=None):
     torch.cuda.empty_cache()
     data = DeviceData(f"config4@{scale:g}", N, rowptr, col, chunks, F, F, F, "none", 1, X, C, None, None,
                       synth.evolve_params(seed, F, F, False))
+    return data, target
+
+
+def config5(seed: int = 0, scale: float = 1.0, say=None):
+    """Config 5 drawn on the device: 16 snapshots x (1,000,000 * scale) vertices, 6 N edge draws per
+    snapshot with tail exponent 2.1, F = S = 128, 8 heads, 128 uneven vertex ranges x one 16-snapshot
+    window; features, cache = features + 0.1 N(0,1) and targets ~ N(0,1), all bfloat16.
+    Returns (data, target)."""
+    import torch
+    T, F, heads = 16, 128, 8
+    N = max(1024, int(1_000_000 * scale))
+    w = synth.powerlaw_weights(N, 2.1, synth.stream(seed, "perm"))
+    cdf_h = np.cumsum(w)
+    cdf_h[-1] = 1.0
+    cdf = torch.from_numpy(cdf_h).cuda()
+    gen = _gen(seed, "graph-dev")
+    rowptr, col = [], []
+    for t in range(T):
+        rp, cj = chung_lu_dev(N, 6 * N, cdf, gen)
+        rowptr.append(rp)
+        col.append(cj)
+    if say:
+        say(f"  graph: {T} snapshots")
+    del cdf
+    chunks = synth.grid_chunks(T, 16, [synth.uneven_ranges(N, 128, synth.stream(seed, "ranges"))])
+
+    def bf16(gen_name, base=None, scale_=1.0):
+        g = _gen(seed, gen_name)
+        out = torch.empty((T, N, F), dtype=torch.bfloat16, device="cuda")
+        for t in range(T):
+            z = torch.randn((N, F), generator=g, device="cuda", dtype=torch.float32)
+            if base is not None:
+                z = z * scale_ + base[t]
+            out[t] = z.to(torch.bfloat16)
+        return out
+
+    Xf = torch.empty((T, N, F), dtype=torch.float32, device="cuda")
+    g = _gen(seed, "feat-dev")
+    for t in range(T):
+        Xf[t] = torch.randn((N, F), generator=g, device="cuda", dtype=torch.float32)
+    C = bf16("cache-dev", Xf, 0.1)             # the cache drifts from the unrounded features, as in the host recipe
+    X = Xf.to(torch.bfloat16)
+    del Xf
+    target = bf16("target-dev")
+    torch.cuda.empty_cache()
+    data = DeviceData(f"config5@{scale:g}", N, rowptr, col, chunks, F, F, F, "none", 1, X, C, None, None,
+                      synth.dysat_params(seed, T, F, F, heads), notes={"heads": heads})
     return data, target

@@ -80,6 +80,27 @@ def pick_vertices(hg, chunk, n_random: int, rng, with_hub: bool = True) -> np.nd
     return np.array(sorted(pick), np.int64)
 
 
+def bounded_neighbours(hg, v: int, ch, max_deg: int) -> bool:
+    """All of v's neighbours inside the chunk's vertex range have at most max_deg stored non-zeros in
+    every snapshot of the chunk's window (keeps the two-hop stand-in problem small)."""
+    for t in range(ch[2], ch[3]):
+        s = hg.snaps[t]
+        nb = s.col[s.rowptr[v]:s.rowptr[v + 1]].astype(np.int64)
+        nb = nb[(nb >= ch[0]) & (nb < ch[1])]
+        if int((s.rowptr[nb + 1] - s.rowptr[nb]).max()) > max_deg:
+            return False
+    return True
+
+
+def bounded_pick(hg, ch, rng, max_deg: int, tries: int = 2000) -> int:
+    """A seeded random vertex of the chunk with bounded_neighbours."""
+    for _ in range(tries):
+        v = int(rng.integers(ch[0], ch[1]))
+        if bounded_neighbours(hg, v, ch, max_deg):
+            return v
+    raise ValueError("no vertex with bounded neighbours found")
+
+
 # --------------------------------------------------------------------------- stand-in problems
 
 
@@ -133,6 +154,41 @@ def one_hop_problem(g, picks, X, C, F: int):
     chunks = np.array([[i, i + 1, ch[2], ch[3]] for i, (_, ch) in enumerate(picks)], np.int64)
     return synth.DynamicGraph(n_loc, snaps), chunks, Xs, Cs
 
+
+
+def one_vertex_problem(graph, v, chunk, X, C, F: int, params: dict):
+    """The problem (for the attention layer, whose time encoder sees the whole window of one vertex)
+    whose only covered vertex computes exactly what vertex v of `chunk` does: local vertex 0 is v, the
+    other local vertices are its neighbours of one snapshot each, all outside the one-vertex chunk, so
+    the oracle reads them from the cache handed over here, which holds the row each neighbour is really
+    read from (X inside the chunk's vertex range, the cache outside).  The window becomes snapshots
+    0..w-1 and the position table is cut to it.  X, C: indexable as [t, ids] -> fp32 rows."""
+    v_lo, v_hi, t_lo, t_hi = chunk
+    per_t = []
+    for t in range(t_lo, t_hi):
+        s = graph.snaps[t]
+        per_t.append(s.col[s.rowptr[v]:s.rowptr[v + 1]].astype(np.int64))
+    n_loc = 1 + max(int((c != v).sum()) for c in per_t)
+    w = t_hi - t_lo
+    Xs = np.zeros((w, n_loc, F), np.float32)
+    Cs = np.zeros((w, n_loc, F), np.float32)
+    snaps = []
+    for k, cols in enumerate(per_t):
+        t = t_lo + k
+        Xs[k, 0] = X[t, v]
+        loc = np.zeros(len(cols), np.int32)
+        others = cols != v
+        loc[others] = 1 + np.arange(int(others.sum()), dtype=np.int32)
+        nb = cols[others]
+        inside = (nb >= v_lo) & (nb < v_hi)
+        if len(nb):
+            Cs[k, 1:1 + len(nb)] = np.where(inside[:, None], X[t, nb], C[t, nb])
+        rowptr = np.full(n_loc + 1, len(cols), np.int64)
+        rowptr[0] = 0
+        snaps.append(synth.Snapshot(rowptr, loc))
+    p = dict(params)
+    p["attn.pos"] = params["attn.pos"][t_lo:t_hi]
+    return synth.DynamicGraph(n_loc, snaps), np.array([[0, 1, 0, w]], np.int64), p, Xs, Cs
 
 
 def two_hop_problem(hg, picks, fetch_x, fetch_c, fetch_tgt, F: int):
