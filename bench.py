@@ -36,6 +36,9 @@ def parse_args():
                     help="config2 (the default): do not also run configs 1, 3, 4 and 5 for the line's `configs` object")
     ap.add_argument("--config-steps", type=int, default=5, help="timed steps of each extra configuration")
     ap.add_argument("--gather-mode", default="in_place", choices=["in_place", "staged"])
+    ap.add_argument("--agg-kernel", default="table", choices=["table", "walk"],
+                    help="aggregation kernels: the ones that read the edge table built at create (default) or the ones "
+                         "that walk colidx")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
@@ -882,7 +885,7 @@ def gcn_run(args) -> dict:
 
     t0 = time.perf_counter()
     evolve = "evolve.W_init" in wl.params
-    dw = DeviceWorkload(wl, gather_mode=args.gather_mode, act_hidden="relu",
+    dw = DeviceWorkload(wl, gather_mode=args.gather_mode, act_hidden="relu", agg_kernel=args.agg_kernel,
                         act_out="relu" if evolve else "none", struct_kind="evolve_gcn_o" if evolve else "gcn")
     if evolve:
         print("upload target ...", file=sys.stderr, flush=True)
@@ -1031,7 +1034,7 @@ def gcn_run(args) -> dict:
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
            "data": "synthetic",
            "config": {"workload": desc, "rows": rows, "nnz": nnz, "gather_mode": args.gather_mode,
-                      "pass": "forward"},
+                      "agg_kernel": args.agg_kernel, "pass": "forward"},
            "roofline": with_traffic_rate(roofline), "roofline_aggregation": with_traffic_rate(agg),
            "stage_ms": {"aggregate0": float(stage[0]), "dense0": float(stage[1]), "aggregate1": float(stage[2]),
                         "dense_rnn": float(stage[3])},
@@ -1078,7 +1081,7 @@ def config3_run(args) -> dict:
         data = device_gen.config3_window(args.seed, 1.0, window=w, say=say)
         torch.cuda.synchronize()
         t_gen = time.perf_counter() - t0
-        dw = DeviceWorkload(data, gather_mode=args.gather_mode, act_hidden="relu", act_out="none")
+        dw = DeviceWorkload(data, gather_mode=args.gather_mode, act_hidden="relu", act_out="none", agg_kernel=args.agg_kernel)
         layer = dw.layer
 
         def step():

@@ -77,6 +77,13 @@ enum { DGC_GATHER_IN_PLACE = 0, DGC_GATHER_STAGED = 1 };
  *  WAVE  32 vertices per wavefront, hidden state kept in registers, no barriers
  *        (S = H in {32, 64, 128}); DGC_ERR_UNSUPPORTED at forward otherwise. */
 enum { DGC_DENSE_AUTO = 0, DGC_DENSE_TILE = 1, DGC_DENSE_WAVE = 2 };
+/* Which kernels aggregate in IN_PLACE mode (STAGED always takes WALK):
+ *  TABLE  kernels that read a per-non-zero table built at create (8 bytes per stored non-zero: the column,
+ *         marked fresh / cache, and the neighbour's degree scaling); needs equal pitches of X and C and
+ *         F <= 256, else WALK runs;
+ *  WALK   kernels that walk colidx, test the chunk range and look the scaling up (no table).
+ * Results differ only in summation order. */
+enum { DGC_AGG_TABLE = 0, DGC_AGG_WALK = 1 };
 
 /* A chunk: vertices [v_lo, v_hi) over snapshots [t_lo, t_hi). */
 typedef struct {
@@ -121,6 +128,7 @@ typedef struct {
                               [4H, 2S].  Needs DGC_STRUCT_GCN, two layers, DGC_TIME_LSTM
                               (else DGC_ERR_INVALID_ARG) and S = H in {32, 64, 128} with
                               dense_kernel not DGC_DENSE_TILE (else DGC_ERR_UNSUPPORTED)     */
+  int32_t agg_kernel;      /* DGC_AGG_*                                                      */
 } dgc_layer_desc_t;
 
 /* Build a layer for a fixed graph and a fixed set of chunks (the paper partitions once per

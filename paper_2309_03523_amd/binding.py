@@ -19,6 +19,7 @@ TIME_KIND = {"none": 0, "gru": 1, "lstm": 2, "self_attn": 3}
 ACT = {"none": 0, "relu": 1}
 GATHER = {"in_place": 0, "staged": 1}
 DENSE = {"auto": 0, "tile": 1, "wave": 2}
+AGG = {"table": 0, "walk": 1}
 STRUCT = {"gcn": 0, "evolve_gcn_o": 1, "gat": 2}
 DTYPE = {"f32": 0, "bf16": 1}
 
@@ -54,7 +55,7 @@ class DescT(ct.Structure):
     _fields_ = [(n, ct.c_int32) for n in
                 ("struct_kind", "n_struct_layers", "time_kind", "dtype", "F", "S", "H", "act_hidden",
                  "act_out", "gather_mode", "validate_level", "rows_per_group", "long_nnz", "part_nnz",
-                 "dense_kernel", "heads", "lstm_input_concat")]
+                 "dense_kernel", "heads", "lstm_input_concat", "agg_kernel")]
 
 
 _lib = None
@@ -153,7 +154,8 @@ class DgcLayer:
                  n_struct_layers: int = 1, act_hidden: str = "relu", act_out: str = "none",
                  gather_mode: str = "in_place", validate_level: int = 0, rows_per_group: int = 0,
                  long_nnz: int = 0, part_nnz: int = 0, dense_kernel: str = "auto", struct_kind: str = "gcn",
-                 dtype: str = "f32", heads: int = 0, lstm_input_concat: bool = False, stream=None):
+                 dtype: str = "f32", heads: int = 0, lstm_input_concat: bool = False, agg_kernel: str = "table",
+                 stream=None):
         import torch
         lib = load()
         self._lib = lib
@@ -173,7 +175,7 @@ class DgcLayer:
         desc = DescT(STRUCT[struct_kind], n_struct_layers, TIME_KIND[time_kind], DTYPE[dtype], F, S, H, ACT[act_hidden],
                      ACT[act_out],
                      GATHER[gather_mode], validate_level, rows_per_group, long_nnz, part_nnz, DENSE[dense_kernel],
-                     heads, int(lstm_input_concat))
+                     heads, int(lstm_input_concat), AGG[agg_kernel])
         rc = lib.dgc_layer_create(ct.byref(desc), ct.byref(graph), carr, len(ch), _stream_ptr(stream),
                                   ct.byref(self._h))
         if rc:

@@ -52,6 +52,7 @@ struct dgc_layer {
   int32_t* d_col_local = nullptr;
   int32_t* d_work_short = nullptr;
   int32_t* d_work_long = nullptr;
+  int2* d_etab = nullptr;                        // edge table of the aggregation kernels (see SpmmArgs)
   float* d_M = nullptr; int64_t ldm = 0;         // aggregated rows of the current GCN layer
   float* d_partial = nullptr;                    // split-row partial sums
   float* d_halo = nullptr; int64_t ld_halo = 0;  // STAGED: gathered cache rows
@@ -172,6 +173,7 @@ dgc_status_t check_desc(const dgc_layer_desc_t& d, std::string* msg) {
   auto fits = [&](int32_t K0, int32_t S, int32_t H, int32_t kind) {
     return !tile_kernel_runs(S, H, kind) || dense_lds_bytes(K0, S, kind == DGC_TIME_NONE ? 0 : H) <= 160 * 1024;
   };
+  if (d.agg_kernel < DGC_AGG_TABLE || d.agg_kernel > DGC_AGG_WALK) { *msg = "unknown agg_kernel"; return DGC_ERR_INVALID_ARG; }
   if (d.lstm_input_concat < 0 || d.lstm_input_concat > 1) { *msg = "lstm_input_concat must be 0 or 1"; return DGC_ERR_INVALID_ARG; }
   if (d.lstm_input_concat) {
     if (d.struct_kind != DGC_STRUCT_GCN || d.n_struct_layers != 2 || d.time_kind != DGC_TIME_LSTM) {
@@ -535,6 +537,15 @@ dgc_status_t build_layer(dgc_layer* L, const dgc_graph_t* graph, hipStream_t st)
   DGC_HIP_TRY(dev_alloc(L, &L->d_work_long, 4 * L->n_long));
   launch_long_fill(g, L->d_segs, L->nseg, L->total_rows, L->long_nnz, L->part_nnz, d_cnt, L->d_work_long, st);
 
+  // aggregation kernels' edge table and launch order
+  const bool gat_layer = d.struct_kind == DGC_STRUCT_GAT;
+  if (!gat_layer && d.gather_mode == DGC_GATHER_IN_PLACE && d.agg_kernel != DGC_AGG_WALK) {
+    if (dev_alloc(L, &L->d_etab, L->total_nnz + kEtabPad) != hipSuccess)
+      return fail(DGC_ERR_OOM, "no device memory for the aggregation's edge table (8 bytes per stored non-zero); "
+                               "agg_kernel = DGC_AGG_WALK runs without it");
+    launch_edge_table(g, L->d_segs, L->nseg, L->total_nnz, L->d_dinv, nullptr, L->d_etab, st);
+  }
+
   // dense tiles: 64 consecutive vertices of a chunk
   {
     std::vector<DenseTile> tiles;
@@ -625,6 +636,7 @@ SpmmArgs spmm_args(dgc_layer* L, const float* fresh, int64_t ld_fresh, const flo
   a.row_map = nullptr;
   a.ld_out = 0;
   a.skip_stale = false;
+  a.etab = L->d_etab;
   return a;
 }
 
@@ -1174,6 +1186,8 @@ dgc_status_t dgc_layer_set_labels(dgc_layer_t* L, const int32_t* labels, void* s
     DGC_HIP_TRY(dev_alloc(L, &lab.seq_out, (int64_t)L->T * L->N));
   }
   labels_build(L->graph_dev(), L->d_segs, labels, lab.col_signed, lab.seq_in, lab.seq_out, st);
+  if (L->d_etab)      // the aggregation's table follows the labels: marked columns instead of the range test
+    launch_edge_table(L->graph_dev(), L->d_segs, L->nseg, L->total_nnz, L->d_dinv, lab.col_signed, L->d_etab, st);
   DGC_HIP_TRY(hipStreamSynchronize(st));
   DGC_HIP_TRY(hipGetLastError());
   lab.built = true;

@@ -96,6 +96,10 @@ void launch_shared_rows(const Segment* segs, int64_t nseg, const int64_t* halo_p
                         int64_t N, int32_t n_chunks, unsigned long long* mask, unsigned long long* out, hipStream_t st);
 
 // ---- aggregation / gather (dgc_spmm.hip)
+// Spare entries after the last non-zero of the edge table: a lane group reads whole batches of 8
+// entries, up to 8 * (groups per wave) - 1 entries past the end of the row it works on.
+constexpr int64_t kEtabPad = 32;
+
 struct SpmmArgs {
   GraphDev g;
   const Segment* segs;
@@ -116,8 +120,18 @@ struct SpmmArgs {
   const int64_t* row_map;     // nullptr, or [rows]: row of M that packed row r goes to (< 0: skip the row)
   int64_t ld_out;             // pitch of the rows of M if it differs from the written width ldm (0 = ldm)
   bool skip_stale;            // neighbours outside the row's chunk range contribute nothing
+  // Edge table (IN_PLACE and generated chunks): one 8-byte entry per packed non-zero, in packed order
+  // with kEtabPad spare entries at the end: .x = the stored column j if the neighbour is read fresh, ~j if it
+  // is read from the cache; .y = the bits of the neighbour's degree scaling d_j^-1/2.  nullptr: the
+  // kernels walk colidx and look the scaling up.
+  const int2* etab;
 };
 void launch_spmm(const SpmmArgs& a, hipStream_t st);
+// etab[p] for every packed non-zero p (col_signed: the marked columns of generated chunks, or nullptr:
+// mark by the segment's vertex range); the kEtabPad spare entries are (0, 0).
+void launch_edge_table(const GraphDev& g, const Segment* segs, int64_t nseg, int64_t total_nnz, const float* dinv,
+                       const int32_t* col_signed, int2* etab, hipStream_t st);
+
 void launch_gather(const Segment* segs, int64_t nseg, const int32_t* halo_idx, const int64_t* halo_ptr,
                    int64_t total_halo, int64_t N, const float* C, int64_t ldc, int32_t F, float* halo,
                    int64_t ldh, hipStream_t st);

@@ -57,11 +57,7 @@ __global__ void k_mark_halo(GraphDev g, const Segment* segs, int64_t nseg, int64
   const int32_t j = g.colidx[sg.t][sg.e0 + (p - sg.nnz_off)];
   if (j < 0 || j >= g.N) { atomicOr(&flags[1], 1); return; }
   if (j < sg.v_lo || j >= sg.v_hi) {
-    // A halo vertex is named by many rows of its segment (hubs by thousands): look first, and send
-    // the atomic only while the bit is still clear (a stale look only costs a redundant atomic).
-    uint32_t* w = &bitmap[s * wps + (j >> 5)];
-    const uint32_t bit = 1u << (j & 31);
-    if (!(__builtin_nontemporal_load(w) & bit)) atomicOr(w, bit);
+    atomicOr(&bitmap[s * wps + (j >> 5)], 1u << (j & 31));
   }
 }
 

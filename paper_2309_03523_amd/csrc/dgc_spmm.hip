@@ -332,6 +332,240 @@ __global__ __launch_bounds__(256) void k_spmm_long_reduce(SpmmArgs a) {
   }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Second generation of the aggregation kernels (IN_PLACE and generated chunks, equal pitches of the
+// fresh and the cache tensor, rows of at most 256 floats).  The first generation above spends some
+// thirty vector instructions per gathered row on broadcasting column ids, range tests and 64-bit
+// address arithmetic, and is bound by instruction issue, not by memory.  Here the per-non-zero
+// work is prepared once, at packing time, in an edge table (SpmmArgs::etab): a lane reads the
+// marked column and the neighbour's scaling with one 8-byte load at a constant offset from a
+// running pointer, forms the row address with one 64-bit multiply-add, and no value has to be
+// made wave-uniform.  LPR lanes (16, 32 or 64, four floats each) cover a row, so a wave's load
+// instruction fetches G = 64 / LPR neighbour rows, U = 8 such loads in flight per lane group.
+//   One long row:   the G groups split its non-zeros (batches of U * G), partial sums added across
+//                   the groups at the end of the row.
+//   Short rows:     group g takes row r + g of its own (no cross-group sum, no idle half).
+// Slots past the end of a row (and, in the input-gradient pass, neighbours outside the chunk range)
+// load the row's own vertex instead, with weight zero: its stored self-loop makes that a row the
+// sum reads anyway, so nothing the sum does not depend on can leak a NaN into it.  The table has
+// kEtabPad spare entries so that whole batches can always be read.
+constexpr int kU = 8;            // table entries (neighbour rows) in flight per lane group
+constexpr int kSmallRow = 16;    // rows up to this many non-zeros share a wave with their neighbours
+static_assert(kEtabPad >= 4 * kU && kSmallRow <= 2 * kU, "batches of the last rows must stay inside the table's spare entries");
+
+template <int UU, bool TAIL, bool SKIP>
+__device__ __forceinline__ void agg_batch(const int2* p, int n_valid, int self_j, const char* fresh_l, const char* stale_l,
+                                          uint32_t ld_bytes, float (&acc)[4]) {
+  typedef int intx2 __attribute__((ext_vector_type(2)));
+  intx2 ent[UU];       // streamed once
+#pragma unroll
+  for (int u = 0; u < UU; ++u) ent[u] = __builtin_nontemporal_load(reinterpret_cast<const intx2*>(p) + u);
+  float4 v[UU];
+  float w[UU];
+#pragma unroll
+  for (int u = 0; u < UU; ++u) {
+    const bool ok = (!TAIL || u < n_valid) && (!SKIP || ent[u].x >= 0);
+    const int c = ok ? ent[u].x : self_j;
+    const bool in = c >= 0;
+    const uint32_t j = (uint32_t)(in ? c : ~c);
+    const char* base = in ? fresh_l : stale_l;
+    v[u] = *reinterpret_cast<const float4*>(base + (uint64_t)j * ld_bytes);
+    w[u] = ok ? __int_as_float(ent[u].y) : 0.f;
+  }
+#pragma unroll
+  for (int u = 0; u < UU; ++u) {
+    acc[0] = fmaf(w[u], v[u].x, acc[0]);
+    acc[1] = fmaf(w[u], v[u].y, acc[1]);
+    acc[2] = fmaf(w[u], v[u].z, acc[2]);
+    acc[3] = fmaf(w[u], v[u].w, acc[3]);
+  }
+}
+
+// Sum over the table entries [pos, end) of this lane's group, `stride` entries from batch to batch.
+template <int LPR, bool SKIP>
+__device__ __forceinline__ void agg_range(const int2* tab, int pos, int end, int stride, int self_j, const char* fresh_l,
+                                          const char* stale_l, uint32_t ld_bytes, float (&acc)[4]) {
+  constexpr int G = 64 / LPR;
+  for (;;) {
+    const int rem = end - pos;                       // uniform within a lane group
+    int rem_max = __builtin_amdgcn_readlane(rem, 0);
+#pragma unroll
+    for (int g = 1; g < G; ++g) {
+      const int r = __builtin_amdgcn_readlane(rem, g * LPR);
+      rem_max = r > rem_max ? r : rem_max;
+    }
+    if (rem_max <= 0) break;
+    int rem_min = __builtin_amdgcn_readlane(rem, 0);
+#pragma unroll
+    for (int g = 1; g < G; ++g) {
+      const int r = __builtin_amdgcn_readlane(rem, g * LPR);
+      rem_min = r < rem_min ? r : rem_min;
+    }
+    const int2* p = tab + pos;
+    if (rem_min >= kU) agg_batch<kU, false, SKIP>(p, kU, self_j, fresh_l, stale_l, ld_bytes, acc);
+    else if (rem_max > 4) agg_batch<8, true, SKIP>(p, rem, self_j, fresh_l, stale_l, ld_bytes, acc);
+    else if (rem_max > 2) agg_batch<4, true, SKIP>(p, rem, self_j, fresh_l, stale_l, ld_bytes, acc);
+    else if (rem_max > 1) agg_batch<2, true, SKIP>(p, rem, self_j, fresh_l, stale_l, ld_bytes, acc);
+    else agg_batch<1, true, SKIP>(p, rem, self_j, fresh_l, stale_l, ld_bytes, acc);
+    pos += stride;
+  }
+}
+
+// Write one output row: columns < F scaled, columns F .. ldm-1 zero.  Lane l of the writing group
+// owns columns 4l .. 4l+3 and, if the pitch is wider than the group, the same columns of every
+// further stretch of 4 * LPR.
+template <int LPR>
+__device__ __forceinline__ void agg_store(float* out, int l, int F, int64_t ldm, const float (&acc)[4], float scale) {
+  const int fi = 4 * l;
+  if (fi < ldm) {
+    float o[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) o[q] = (fi + q < F) ? acc[q] * scale : 0.f;
+    vstore<4>(out + fi, o);
+  }
+  const float z[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int c = fi + 4 * LPR; c < ldm; c += 4 * LPR) vstore<4>(out + c, z);
+}
+
+template <int LPR>
+__device__ __forceinline__ void agg_reduce_groups(float (&acc)[4]) {
+  constexpr int G = 64 / LPR;
+#pragma unroll
+  for (int m = LPR; m < 64; m <<= 1)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[q] += __shfl_xor(acc[q], m);
+  (void)G;
+}
+
+struct AggCtx {
+  const int2* tab;       // table entry of the work item's first non-zero
+  const char* fresh_l;   // snapshot's fresh rows + this lane's column offset
+  const char* stale_l;
+  uint32_t ld_bytes;
+};
+
+template <int LPR>
+__device__ __forceinline__ AggCtx agg_ctx(const SpmmArgs& a, const Segment& sg, int64_t first_e, int l) {
+  AggCtx c;
+  c.tab = a.etab + sg.nnz_off + (first_e - sg.e0);
+  const int fi = (4 * l < a.F) ? 4 * l : 0;     // lanes past the row's end re-read its first columns (never stored)
+  const int64_t snap = (int64_t)sg.t * a.g.N * a.ld_fresh;
+  c.fresh_l = reinterpret_cast<const char*>(a.fresh + snap + fi);
+  c.stale_l = reinterpret_cast<const char*>(a.stale + snap + fi);
+  c.ld_bytes = (uint32_t)(a.ld_fresh * sizeof(float));
+  return c;
+}
+
+template <int LPR, bool SKIP>
+__global__ __launch_bounds__(256) void k_agg_short(SpmmArgs a) {
+  constexpr int G = 64 / LPR;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t wave = (int64_t)blockIdx.x * (256 / kWave) + (threadIdx.x / kWave);
+  const int64_t item = wave;
+  if (item >= a.n_short) return;
+  const int seg = uniform(a.work_short[3 * item + 0]);
+  const int r0 = uniform(a.work_short[3 * item + 1]);
+  const int n = uniform(a.work_short[3 * item + 2]);
+  const Segment sg = a.segs[seg];
+  const int g = lane / LPR, l = lane % LPR;
+  const int64_t* rp = a.g.rowptr[sg.t] + sg.v_lo + r0;
+  const int64_t rp0 = rp[0];
+  const int my_rel = lane <= n ? (int)(rp[lane] - rp0) : 0;     // lanes 0..n: row offsets relative to the group's start
+  const AggCtx c = agg_ctx<LPR>(a, sg, rp0, l);
+  const float* dinv_rows = a.dinv + (int64_t)sg.t * a.g.N + sg.v_lo + r0;
+  const int64_t prow0 = sg.row_off + r0;
+  const int64_t ldo = a.ld_out ? a.ld_out : a.ldm;
+  int r = 0;
+  while (r < n) {
+    const int e_r = __builtin_amdgcn_readlane(my_rel, r), e_r1 = __builtin_amdgcn_readlane(my_rel, r + 1);
+    const int nnz_r = e_r1 - e_r;
+    if (nnz_r > a.long_nnz) { ++r; continue; }
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    if (G == 1 || nnz_r > kSmallRow) {
+      // one row for the whole wave
+      agg_range<LPR, SKIP>(c.tab, e_r + g * kU, e_r1, kU * G, (int)(sg.v_lo + r0 + r), c.fresh_l, c.stale_l, c.ld_bytes, acc);
+      agg_reduce_groups<LPR>(acc);
+      const int64_t orow = a.row_map ? a.row_map[prow0 + r] : prow0 + r;
+      if (g == 0 && orow >= 0) agg_store<LPR>(a.M + orow * ldo, l, a.F, a.ldm, acc, dinv_rows[r]);
+      ++r;
+    } else {
+      // up to G consecutive small rows, one per lane group
+      int take = 1;
+      while (take < G && r + take < n) {
+        const int nn = __builtin_amdgcn_readlane(my_rel, r + take + 1) - __builtin_amdgcn_readlane(my_rel, r + take);
+        if (nn > kSmallRow) break;
+        ++take;
+      }
+      const int mine = r + (g < take ? g : 0);
+      const int b = __shfl(my_rel, mine), e = __shfl(my_rel, mine + 1);
+      agg_range<LPR, SKIP>(c.tab, b, g < take ? e : b, kU, (int)(sg.v_lo + r0 + mine), c.fresh_l, c.stale_l, c.ld_bytes, acc);
+      const int64_t orow = a.row_map ? a.row_map[prow0 + mine] : prow0 + mine;
+      if (g < take && orow >= 0) agg_store<LPR>(a.M + orow * ldo, l, a.F, a.ldm, acc, dinv_rows[mine]);
+      r += take;
+    }
+  }
+}
+
+// One wave per part of a split row: unscaled partial sums.
+template <int LPR, bool SKIP>
+__global__ __launch_bounds__(256) void k_agg_long(SpmmArgs a) {
+  constexpr int G = 64 / LPR;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t wave = (int64_t)blockIdx.x * (256 / kWave) + (threadIdx.x / kWave);
+  const int64_t item = wave;
+  if (item >= a.n_long) return;
+  const int seg = uniform(a.work_long[4 * item + 0]);
+  const int row = uniform(a.work_long[4 * item + 1]);
+  const int part = uniform(a.work_long[4 * item + 2]);
+  const Segment sg = a.segs[seg];
+  const int g = lane / LPR, l = lane % LPR;
+  const int64_t* rp = a.g.rowptr[sg.t] + sg.v_lo + row;
+  const int64_t ra = rp[0], rb = rp[1];
+  const int64_t ea = ra + (int64_t)part * a.part_nnz;
+  const int len = (int)((ea + a.part_nnz < rb ? ea + a.part_nnz : rb) - ea);
+  const AggCtx c = agg_ctx<LPR>(a, sg, ea, l);
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  agg_range<LPR, SKIP>(c.tab, g * kU, len, kU * G, (int)(sg.v_lo + row), c.fresh_l, c.stale_l, c.ld_bytes, acc);
+  agg_reduce_groups<LPR>(acc);
+  if (g == 0) agg_store<LPR>(a.partial + item * a.ldm, l, a.F, a.ldm, acc, 1.0f);
+}
+
+template <int LPR>
+void launch_agg(const SpmmArgs& a, hipStream_t st) {
+  const unsigned gs = (unsigned)((a.n_short + 3) / 4), gl = (unsigned)((a.n_long + 3) / 4);
+  if (gs) {
+    if (a.skip_stale) hipLaunchKernelGGL((k_agg_short<LPR, true>), gs, 256, 0, st, a);
+    else hipLaunchKernelGGL((k_agg_short<LPR, false>), gs, 256, 0, st, a);
+  }
+  if (gl) {
+    if (a.skip_stale) hipLaunchKernelGGL((k_agg_long<LPR, true>), gl, 256, 0, st, a);
+    else hipLaunchKernelGGL((k_agg_long<LPR, false>), gl, 256, 0, st, a);
+    if (a.ldm <= 64) hipLaunchKernelGGL((k_spmm_long_reduce<1>), gl, 256, 0, st, a);
+    else if (a.ldm <= 128) hipLaunchKernelGGL((k_spmm_long_reduce<2>), gl, 256, 0, st, a);
+    else hipLaunchKernelGGL((k_spmm_long_reduce<4>), gl, 256, 0, st, a);
+  }
+}
+
+// etab[p] = (marked column, scaling of the neighbour) for packed non-zero p
+__global__ __launch_bounds__(256) void k_edge_table(GraphDev g, const Segment* segs, int64_t nseg, int64_t total_nnz,
+                                                    const float* dinv, const int32_t* col_signed, int2* etab) {
+  const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= total_nnz + kEtabPad) return;
+  if (p >= total_nnz) { etab[p] = make_int2(0, 0); return; }
+  int64_t lo = 0, hi = nseg - 1;     // the segment of p: largest s with nnz_off[s] <= p
+  while (lo < hi) {
+    const int64_t mid = (lo + hi + 1) >> 1;
+    if (segs[mid].nnz_off <= p) lo = mid; else hi = mid - 1;
+  }
+  const Segment sg = segs[lo];
+  const int32_t j = g.colidx[sg.t][sg.e0 + (p - sg.nnz_off)];
+  const int32_t marked = col_signed ? col_signed[p] : ((j >= sg.v_lo && j < sg.v_hi) ? j : ~j);
+  const bool valid = j >= 0 && j < g.N;
+  const float w = valid ? dinv[(int64_t)sg.t * g.N + j] : 0.f;
+  etab[p] = make_int2(valid ? marked : 0, __float_as_int(w));
+}
+
 template <int VEC, bool PAIR = false>
 void launch_spmm_v(const SpmmArgs& a, hipStream_t st) {
   constexpr int RV = PAIR ? 2 : VEC;   // the merge of split rows walks the pitch 64 x RV floats at a time
@@ -371,7 +605,21 @@ __global__ __launch_bounds__(256) void k_gather(const Segment* segs, int64_t nse
 
 }  // namespace
 
+void launch_edge_table(const GraphDev& g, const Segment* segs, int64_t nseg, int64_t total_nnz, const float* dinv,
+                       const int32_t* col_signed, int2* etab, hipStream_t st) {
+  const int64_t n = total_nnz + kEtabPad;
+  hipLaunchKernelGGL(k_edge_table, (unsigned)((n + 255) / 256), 256, 0, st, g, segs, nseg, total_nnz, dinv, col_signed, etab);
+}
+
+
 void launch_spmm(const SpmmArgs& a, hipStream_t st) {
+  // the edge-table kernels: rows read in place, one pitch for both sources, at most 256 columns
+  if (a.etab && !a.halo && a.ld_fresh == a.ld_stale && a.F <= 256 && a.ld_fresh * 4 < (int64_t(1) << 31)) {
+    if (a.F <= 64) launch_agg<16>(a, st);
+    else if (a.F <= 128) launch_agg<32>(a, st);
+    else launch_agg<64>(a, st);
+    return;
+  }
   if (a.F <= 64) launch_spmm_v<1>(a, st);
   else if (a.F <= 128) launch_spmm_v<4, true>(a, st);
   else launch_spmm_v<4>(a, st);

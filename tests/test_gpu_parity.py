@@ -60,14 +60,17 @@ def test_packing_bit_exact(torch_mod, seed, N, T, deg, hub):
 # ------------------------------------------------------------------ gather + aggregation
 
 
-@pytest.mark.parametrize("mode", ["in_place", "staged"])
-@pytest.mark.parametrize("F", [5, 32, 100, 172, 300])
+@pytest.mark.parametrize("mode", ["in_place", "in_place_walk", "staged"])
+@pytest.mark.parametrize("F", [5, 32, 64, 100, 128, 172, 256, 300])
 def test_aggregation_matches_oracle(torch_mod, mode, F):
+    """in_place runs the kernels that read the edge table (F <= 256; wider rows fall back),
+    in_place_walk the ones that walk colidx, staged the gathered halo buffer."""
     torch = torch_mod
     N, T = 257, 3
     chunks = _chunks_grid(N, T, [40, 41, 170], [2])
     wl = synth.random_small(10 + F, T, N, F, 32, 32, 6.0, chunks, "gru", hub=True)
-    dw = _dw(wl, gather_mode=mode, rows_per_group=5, long_nnz=24, part_nnz=7)
+    dw = _dw(wl, gather_mode=mode.split("_walk")[0], agg_kernel="walk" if mode.endswith("walk") else "table",
+             rows_per_group=5, long_nnz=24, part_nnz=7)
     ldm = (F + 3) // 4 * 4
     M = torch.full((wl.rows, ldm), float("nan"), device="cuda")
     dw.layer.aggregate(dw.X, dw.C, M)
