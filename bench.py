@@ -1152,7 +1152,7 @@ def config3_run(args) -> dict:
                                   ("" if len(windows) == 4 else f"; the whole config is 4 windows: x {4 / len(windows):g}"),
                       "rows": rows, "nnz": tot["nnz"], "gather_mode": args.gather_mode, "pass": "forward"},
            "roofline": roofline,
-           "kernels": {"first_transform": {"kernel": "k_dense (172 -> 128, workgroup tiles)", "bound": "mfma",
+           "kernels": {"first_transform": {"kernel": "k_dense_wave<NONE> (first GCN layer, 172 -> 128)", "bound": "mfma",
                                            "achieved": first_flops / (float(stage_sum[1]) * 1e-3) / 1e12,
                                            "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                                            "frac": first_flops / (float(stage_sum[1]) * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
