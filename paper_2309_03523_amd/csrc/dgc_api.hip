@@ -27,6 +27,10 @@ namespace dgc {
 void set_thread_error(const std::string& msg) { g_create_error = msg; }
 }  // namespace dgc
 
+// Largest y / z extent of a launch grid: kernels that take one grid row per segment, chunk or snapshot
+// are refused beyond it instead of failing at launch.
+constexpr int64_t kMaxGridYZ = 65535;
+
 struct dgc_layer {
   dgc_layer_desc_t desc{};
   int32_t T = 0;
@@ -1013,6 +1017,8 @@ dgc_status_t dgc_layer_backward(dgc_layer_t* L, const void* Yv, int64_t ldy, con
     int64_t max_nv = 1;
     int32_t max_w = 1;
     for (const ChunkInfo& c : L->cinfo_host) { max_nv = std::max(max_nv, c.nv); max_w = std::max(max_w, c.w); }
+    if (L->n_chunks > kMaxGridYZ || max_w > kMaxGridYZ)   // its kernels take one grid plane per chunk, one row per snapshot
+      return fail(DGC_ERR_UNSUPPORTED, "input gradient: more than 65535 chunks or snapshots per window");
     if (!L->d_dM) {
       DGC_HIP_TRY(dev_alloc(L, &L->d_dM, (int64_t)L->T * L->N * d.F));
       DGC_HIP_TRY(dev_alloc(L, &L->d_rowidx, L->total_rows));
@@ -1050,6 +1056,8 @@ dgc_status_t dgc_layer_shared_rows(dgc_layer_t* L, int64_t* host_out, void* stre
   if (!host_out) return fail(DGC_ERR_INVALID_ARG, "host_out is NULL");
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int32_t n = L->n_chunks;
+  if (L->nseg > kMaxGridYZ)      // the marking kernel takes one grid row per (chunk, snapshot) segment
+    return fail(DGC_ERR_UNSUPPORTED, "shared rows: more than 65535 (chunk, snapshot) segments");
   if (!L->fs_mask) {
     if (dev_alloc(L, &L->fs_mask, shared_rows_mask_words(L->T, L->N, n)) != hipSuccess) {
       L->fs_mask = nullptr;
@@ -1061,7 +1069,9 @@ dgc_status_t dgc_layer_shared_rows(dgc_layer_t* L, int64_t* host_out, void* stre
     }
   }
   launch_shared_rows(L->d_segs, L->nseg, L->d_halo_ptr, L->d_halo_idx, L->T, L->N, n, L->fs_mask, L->fs_out, st);
-  hipError_t e = hipMemcpyAsync(host_out, L->fs_out, sizeof(int64_t) * (size_t)n * n, hipMemcpyDeviceToHost, st);
+  hipError_t e = hipGetLastError();      // a rejected launch would leave the counters at zero
+  if (e != hipSuccess) return fail(DGC_ERR_DEVICE, std::string("shared rows: ") + hipGetErrorString(e));
+  e = hipMemcpyAsync(host_out, L->fs_out, sizeof(int64_t) * (size_t)n * n, hipMemcpyDeviceToHost, st);
   if (e == hipSuccess) e = hipStreamSynchronize(st);
   if (e != hipSuccess) return fail(DGC_ERR_DEVICE, std::string("shared rows: ") + hipGetErrorString(e));
   for (int32_t a = 0; a < n; ++a) {      // the kernel fills the upper triangle
@@ -1082,6 +1092,8 @@ dgc_status_t dgc_layer_set_presence(dgc_layer_t* L, const uint8_t* present, void
   if (L->tf.built) return fail(DGC_ERR_STATE, "the presence mask of a layer can be set once");
   if ((int64_t)L->T * L->N >= INT32_MAX) return fail(DGC_ERR_UNSUPPORTED, "temporal fusion needs T*N < 2^31");
   if (L->lab.built) return fail(DGC_ERR_STATE, "temporal fusion is not built for generated chunks");
+  if (L->n_chunks > kMaxGridYZ)  // its kernels take one grid row per chunk
+    return fail(DGC_ERR_UNSUPPORTED, "temporal fusion: more than 65535 chunks");
   TFusion& tf = L->tf;
   const int32_t nc = L->n_chunks;
   const std::vector<ChunkInfo>& ci = L->cinfo_host;
@@ -1179,6 +1191,7 @@ dgc_status_t dgc_layer_set_labels(dgc_layer_t* L, const int32_t* labels, void* s
   if (L->n_chunks != 1 || c.v_lo != 0 || c.v_hi != L->N || c.t_lo != 0 || c.t_hi != L->T)
     return fail(DGC_ERR_STATE, "labels need a layer created with the single chunk [0,N) x [0,T)");
   if ((int64_t)L->T * L->N >= INT32_MAX) return fail(DGC_ERR_UNSUPPORTED, "generated chunks need T*N < 2^31");
+  if (L->T > kMaxGridYZ) return fail(DGC_ERR_UNSUPPORTED, "generated chunks: more than 65535 snapshots");
   Labelled& lab = L->lab;
   if (!lab.col_signed) {
     DGC_HIP_TRY(dev_alloc(L, &lab.col_signed, L->total_nnz));

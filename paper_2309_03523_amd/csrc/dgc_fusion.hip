@@ -138,29 +138,36 @@ dgc_status_t dgc_fusion_select(int32_t n, const int64_t* shared, const int64_t* 
   return DGC_OK;
 }
 
+// Chunk assignment (Section 4.2, Algorithm 1) with a running traffic table: traffic[m][a] is what
+// chunk a would exchange with the chunks already placed on worker m.  Placing chunk b on m adds
+// h(a, b) to row m for every chunk a still waiting, so scoring a chunk costs O(workers) and the whole
+// procedure O(n^2 + n * workers) instead of summing over every worker's chunk list for every chunk.
+// (The additions happen in placement order, the order in which a sum over the list would run.)
+// Readings the paper leaves open: a worker without chunks, or without traffic to the chunk, scores 0
+// whatever its load; equal scores go to the worker with the smaller assigned load, then the smaller index.
 dgc_status_t dgc_chunk_assign(int32_t n, const double* g, const double* h, int32_t n_gpus, int32_t* x_out) {
   if (n < 1 || n_gpus < 1 || !g || !h || !x_out) { set_thread_error("chunk assign: NULL argument, n < 1 or n_gpus < 1"); return DGC_ERR_INVALID_ARG; }
-  std::vector<int32_t> order(n);
-  for (int32_t a = 0; a < n; ++a) order[a] = a;
-  std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return g[a] > g[b]; });
-  double total = 0.0;
-  for (int32_t a = 0; a < n; ++a) total += g[a];
-  const double g_bar = total / n_gpus;
-  std::vector<std::vector<int32_t>> Q(n_gpus);
-  std::vector<double> load(n_gpus, 0.0);
-  for (int32_t a : order) {
-    int32_t best_m = 0;
-    double best_s = 0.0;
-    for (int32_t m = 0; m < n_gpus; ++m) {
-      double comm = 0.0;
-      for (int32_t b : Q[m]) comm += h[(int64_t)a * n + b];
-      const double s = (g_bar - load[m]) * comm;
-      // larger score, then smaller assigned load, then smaller index
-      if (m == 0 || s > best_s || (s == best_s && load[m] < load[best_m])) { best_s = s; best_m = m; }
+  std::vector<int32_t> by_work(n);
+  for (int32_t a = 0; a < n; ++a) by_work[a] = a;
+  std::stable_sort(by_work.begin(), by_work.end(), [&](int32_t a, int32_t b) { return g[a] > g[b]; });
+  double work_sum = 0.0;
+  for (int32_t a = 0; a < n; ++a) work_sum += g[a];
+  const double fair_share = work_sum / n_gpus;
+  std::vector<double> traffic((size_t)n_gpus * n, 0.0), assigned(n_gpus, 0.0);
+  std::vector<char> waiting(n, 1);
+  for (int32_t a : by_work) {
+    int32_t pick = 0;
+    double pick_score = (fair_share - assigned[0]) * traffic[a];
+    for (int32_t m = 1; m < n_gpus; ++m) {
+      const double score = (fair_share - assigned[m]) * traffic[(size_t)m * n + a];
+      if (score > pick_score || (score == pick_score && assigned[m] < assigned[pick])) { pick = m; pick_score = score; }
     }
-    x_out[a] = best_m;
-    Q[best_m].push_back(a);
-    load[best_m] += g[a];
+    x_out[a] = pick;
+    assigned[pick] += g[a];
+    waiting[a] = 0;
+    double* row = traffic.data() + (size_t)pick * n;
+    for (int32_t c = 0; c < n; ++c)
+      if (waiting[c]) row[c] += h[(int64_t)c * n + a];
   }
   return DGC_OK;
 }
