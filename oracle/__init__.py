@@ -143,12 +143,16 @@ def forward(graph, chunks, params: dict, X: np.ndarray, C: np.ndarray, *, time_k
             n_struct_layers: int = 1, act_hidden: str = "relu", act_out: str = "none",
             C1: Optional[np.ndarray] = None, H0: Optional[np.ndarray] = None,
             reset_mask: Optional[np.ndarray] = None, subset: Optional[list] = None,
-            Y: Optional[np.ndarray] = None, return_state: bool = False, input_concat: bool = False):
+            Y: Optional[np.ndarray] = None, return_state: bool = False, input_concat: bool = False,
+            n_time_layers: int = 1):
     """The whole layer over the listed chunks.  Returns Y float32 [T,N,out_dim] (rows not
     covered by a chunk, or outside `subset`, keep the value they had in the `Y` passed in,
     NaN if none was passed) and optionally the final recurrent states packed like H0.
     input_concat (two structure layers): the time encoder reads both layers' outputs side by
-    side, first layer first (Section 6, MPNN-LSTM); rnn.weight_ih is then [gH, 2S]."""
+    side, first layer first (Section 6, MPNN-LSTM); rnn.weight_ih is then [gH, 2S].
+    n_time_layers = 2: a second recurrent layer ("rnn1.*", input width H) reads the first one's
+    output; Y is its output, and H0 / the returned states hold the first layer's blocks followed
+    by the second layer's."""
     g = _Csr(graph)
     ch = _chunks(chunks)
     T, N = g.T, g.N
@@ -177,7 +181,13 @@ def forward(graph, chunks, params: dict, X: np.ndarray, C: np.ndarray, *, time_k
         Y = np.full((T, N, out_dim), np.nan, np.float32)
     assert Y.shape == (T, N, out_dim) and Y.dtype == np.float32
     tot_v = int((ch[:, 1] - ch[:, 0]).sum())
-    n_state = 2 if time_kind == "lstm" else 1
+    n_state = (2 if time_kind == "lstm" else 1) * n_time_layers
+    W2 = None
+    if n_time_layers == 2:
+        assert time_kind != "none"
+        W2 = [np.ascontiguousarray(params[k], np.float32)
+              for k in ("rnn1.weight_ih", "rnn1.weight_hh", "rnn1.bias_ih", "rnn1.bias_hh")]
+        assert W2[0].shape == (gH, H) and W2[1].shape == (gH, H)
     if H0 is not None:
         H0 = np.ascontiguousarray(H0, np.float32)
         assert H0.shape == (n_state * tot_v, H)
@@ -192,7 +202,12 @@ def forward(graph, chunks, params: dict, X: np.ndarray, C: np.ndarray, *, time_k
         sub_idx = np.ascontiguousarray(np.concatenate([np.asarray(s, np.int64) for s in subset])
                                        if sub_ptr[-1] else np.zeros(0, np.int64))
     hN = np.zeros((n_state * tot_v, H), np.float32) if (return_state and time_kind != "none") else None
-    rc = lib().dgc_oracle_forward(
+    args_tail = [ct.c_int32(int(input_concat))]
+    fn = lib().dgc_oracle_forward
+    if n_time_layers == 2:
+        fn = lib().dgc_oracle_forward_stacked
+        args_tail += [_p(a, ct.c_float) for a in W2]
+    rc = fn(
         ct.c_int32(T), ct.c_int64(N), g.rowptr, g.col, _p(ch, ct.c_int64), ct.c_int32(len(ch)),
         ct.c_int32(n_struct_layers), ct.c_int32(TIME_KIND[time_kind]), ct.c_int32(ACT[act_hidden]),
         ct.c_int32(ACT[act_out]), ct.c_int32(F), ct.c_int32(S), ct.c_int32(H),
@@ -201,7 +216,7 @@ def forward(graph, chunks, params: dict, X: np.ndarray, C: np.ndarray, *, time_k
         _p(W0, ct.c_float), _p(b0, ct.c_float), _p(W1, ct.c_float), _p(b1, ct.c_float),
         _p(Wih, ct.c_float), _p(Whh, ct.c_float), _p(bih, ct.c_float), _p(bhh, ct.c_float),
         _p(H0, ct.c_float), _p(reset_mask, ct.c_uint8), _p(sub_ptr, ct.c_int64), _p(sub_idx, ct.c_int64),
-        _p(Y, ct.c_float), ct.c_int64(Y.strides[1] // 4), _p(hN, ct.c_float), ct.c_int32(int(input_concat)))
+        _p(Y, ct.c_float), ct.c_int64(Y.strides[1] // 4), _p(hN, ct.c_float), *args_tail)
     if rc:
         raise ValueError(f"dgc_oracle_forward failed: {rc}")
     return (Y, hN) if return_state else Y

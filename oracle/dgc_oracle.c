@@ -268,8 +268,13 @@ static void lstm_step(const float *Wih, const float *Whh, const float *bih, cons
  *  subset_ptr/subset_idx (optional): per chunk, the vertices whose time encoder and last
  *  structure layer are evaluated (others are left untouched in Y); NULL = all.
  *  hN (optional): final states, packed like H0.
+ *  n_time_layers 2 (stacked time encoder, as the two LSTM layers of Section 6's MPNN-LSTM): the
+ *  second recurrent layer reads the first one's output h_t of the same step, has its own weights
+ *  Wih2 [gH][H], Whh2 [gH][H], bih2, bhh2 and its own state, and Y[t,i] is ITS h_t.  H0 / hN then
+ *  hold the first layer's states (hidden, then cell for the LSTM) followed by the second layer's,
+ *  each block tot_v rows; the reset mask zeroes the incoming state of both layers.
  * Weights are (out, in) row-major fp32.  Returns 0, or <0 on a bad argument. */
-int dgc_oracle_forward(int32_t T, int64_t N, const int64_t *const *rowptr,
+static int forward_impl(int32_t T, int64_t N, const int64_t *const *rowptr,
                        const int32_t *const *col, const int64_t *chunks, int32_t n_chunks,
                        int32_t n_struct_layers, int32_t time_kind, int32_t act_hidden,
                        int32_t act_out, int32_t F, int32_t S, int32_t H, const float *X,
@@ -278,8 +283,12 @@ int dgc_oracle_forward(int32_t T, int64_t N, const int64_t *const *rowptr,
                        const float *Wih, const float *Whh, const float *bih, const float *bhh,
                        const float *H0, const uint8_t *reset_mask, const int64_t *subset_ptr,
                        const int64_t *subset_idx, float *Y, int64_t ldy, float *hN,
-                       int32_t input_concat) {
+                       int32_t input_concat, int32_t n_time_layers, const float *Wih2,
+                       const float *Whh2, const float *bih2, const float *bhh2) {
   if (n_struct_layers < 1 || n_struct_layers > 2) return -3;
+  if (n_time_layers < 1 || n_time_layers > 2) return -3;
+  if (n_time_layers == 2 && (time_kind == TIME_NONE || !Wih2 || !Whh2 || !bih2 || !bhh2)) return -3;
+  const int64_t n_state = time_kind == TIME_LSTM ? 2 : 1;   /* state blocks per recurrent layer */
   if (n_struct_layers == 2 && (!C1 || !W1)) return -3;
   if (input_concat && (n_struct_layers != 2 || time_kind == TIME_NONE)) return -3;
   const int32_t Sx = input_concat ? 2 * S : S;   /* width of the time encoder's input */
@@ -332,14 +341,17 @@ int dgc_oracle_forward(int32_t T, int64_t N, const int64_t *const *rowptr,
       const int64_t i = subset_ptr ? subset_idx[subset_ptr[k] + q] : v_lo + q;
       const int32_t Fl = n_struct_layers == 2 ? S : F;
       const int32_t g = time_kind == TIME_LSTM ? 4 : 3;
-      double *buf = (double *)malloc(sizeof(double) * (size_t)(Fl + 2 * S + 2 * g * H + 6 * H + 8));
+      double *buf = (double *)malloc(sizeof(double) * (size_t)(Fl + 2 * S + 2 * g * H + 10 * H + 8));
       double *m = buf, *x = m + Fl, *gx = x + 2 * S, *gh = gx + g * H, *h = gh + g * H, *c = h + H,
              *hm = c + H, *cm = hm + H, *h2 = cm + H, *c2 = h2 + H;
+      double *hb = c2 + H, *cb = hb + H, *hb2 = cb + H, *cb2 = hb2 + H;   /* second recurrent layer */
       double *z = input_concat ? x + S : x;   /* the last structure layer's output inside x */
       const int64_t slot = row_base + (i - v_lo);
       for (int32_t j = 0; j < H; ++j) {
         h[j] = (H0 && time_kind != TIME_NONE) ? (double)H0[slot * H + j] : 0.0;
         c[j] = (H0 && time_kind == TIME_LSTM) ? (double)H0[(tot_v + slot) * H + j] : 0.0;
+        hb[j] = (H0 && n_time_layers == 2) ? (double)H0[(n_state * tot_v + slot) * H + j] : 0.0;
+        cb[j] = (H0 && n_time_layers == 2 && time_kind == TIME_LSTM) ? (double)H0[((n_state + 1) * tot_v + slot) * H + j] : 0.0;
       }
       for (int64_t t = t_lo; t < t_hi; ++t) {
         if (n_struct_layers == 2) {
@@ -365,12 +377,29 @@ int dgc_oracle_forward(int32_t T, int64_t N, const int64_t *const *rowptr,
           lstm_step(Wih, Whh, bih, bhh, Sx, H, x, hm, cm, gx, gh, h2, c2);
           for (int32_t j = 0; j < H; ++j) c[j] = c2[j];
         }
-        for (int32_t j = 0; j < H; ++j) { h[j] = h2[j]; y[j] = (float)h[j]; }
+        for (int32_t j = 0; j < H; ++j) h[j] = h2[j];
+        if (n_time_layers == 2) {
+          /* the second recurrent layer: input = the first layer's new hidden state */
+          for (int32_t j = 0; j < H; ++j) { hm[j] = mk * hb[j]; cm[j] = mk * cb[j]; }
+          if (time_kind == TIME_GRU) {
+            gru_step(Wih2, Whh2, bih2, bhh2, H, H, h, hm, gx, gh, hb2);
+          } else {
+            lstm_step(Wih2, Whh2, bih2, bhh2, H, H, h, hm, cm, gx, gh, hb2, cb2);
+            for (int32_t j = 0; j < H; ++j) cb[j] = cb2[j];
+          }
+          for (int32_t j = 0; j < H; ++j) { hb[j] = hb2[j]; y[j] = (float)hb[j]; }
+        } else {
+          for (int32_t j = 0; j < H; ++j) y[j] = (float)h[j];
+        }
       }
       if (hN && time_kind != TIME_NONE) {
         for (int32_t j = 0; j < H; ++j) {
           hN[slot * H + j] = (float)h[j];
           if (time_kind == TIME_LSTM) hN[(tot_v + slot) * H + j] = (float)c[j];
+          if (n_time_layers == 2) {
+            hN[(n_state * tot_v + slot) * H + j] = (float)hb[j];
+            if (time_kind == TIME_LSTM) hN[((n_state + 1) * tot_v + slot) * H + j] = (float)cb[j];
+          }
         }
       }
       free(buf);
@@ -379,6 +408,39 @@ int dgc_oracle_forward(int32_t T, int64_t N, const int64_t *const *rowptr,
     row_base += nv;
   }
   return 0;
+}
+
+int dgc_oracle_forward(int32_t T, int64_t N, const int64_t *const *rowptr,
+                       const int32_t *const *col, const int64_t *chunks, int32_t n_chunks,
+                       int32_t n_struct_layers, int32_t time_kind, int32_t act_hidden,
+                       int32_t act_out, int32_t F, int32_t S, int32_t H, const float *X,
+                       int64_t ldx, const float *C, int64_t ldc, const float *C1, int64_t ldc1,
+                       const float *W0, const float *b0, const float *W1, const float *b1,
+                       const float *Wih, const float *Whh, const float *bih, const float *bhh,
+                       const float *H0, const uint8_t *reset_mask, const int64_t *subset_ptr,
+                       const int64_t *subset_idx, float *Y, int64_t ldy, float *hN,
+                       int32_t input_concat) {
+  return forward_impl(T, N, rowptr, col, chunks, n_chunks, n_struct_layers, time_kind, act_hidden, act_out, F,
+                      S, H, X, ldx, C, ldc, C1, ldc1, W0, b0, W1, b1, Wih, Whh, bih, bhh, H0, reset_mask,
+                      subset_ptr, subset_idx, Y, ldy, hN, input_concat, 1, NULL, NULL, NULL, NULL);
+}
+
+/* The layer with a stacked time encoder (see forward_impl): the same arguments plus the second
+ * recurrent layer's parameters. */
+int dgc_oracle_forward_stacked(int32_t T, int64_t N, const int64_t *const *rowptr,
+                               const int32_t *const *col, const int64_t *chunks, int32_t n_chunks,
+                               int32_t n_struct_layers, int32_t time_kind, int32_t act_hidden,
+                               int32_t act_out, int32_t F, int32_t S, int32_t H, const float *X,
+                               int64_t ldx, const float *C, int64_t ldc, const float *C1, int64_t ldc1,
+                               const float *W0, const float *b0, const float *W1, const float *b1,
+                               const float *Wih, const float *Whh, const float *bih, const float *bhh,
+                               const float *H0, const uint8_t *reset_mask, const int64_t *subset_ptr,
+                               const int64_t *subset_idx, float *Y, int64_t ldy, float *hN,
+                               int32_t input_concat, const float *Wih2, const float *Whh2,
+                               const float *bih2, const float *bhh2) {
+  return forward_impl(T, N, rowptr, col, chunks, n_chunks, n_struct_layers, time_kind, act_hidden, act_out, F,
+                      S, H, X, ldx, C, ldc, C1, ldc1, W0, b0, W1, b1, Wih, Whh, bih, bhh, H0, reset_mask,
+                      subset_ptr, subset_idx, Y, ldy, hN, input_concat, 2, Wih2, Whh2, bih2, bhh2);
 }
 
 int dgc_oracle_threads(void) {

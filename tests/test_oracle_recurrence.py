@@ -199,3 +199,55 @@ def test_concatenated_structure_outputs_feed_the_time_encoder(kind):
     # without the flag the same call refuses the wide weights
     with pytest.raises(AssertionError):
         oracle.forward(wl.graph, chunks, wl.params, wl.X, wl.C, time_kind=kind, n_struct_layers=2, C1=wl.C1)
+
+
+@pytest.mark.parametrize("kind", ["lstm", "gru"])
+def test_stacked_time_encoder_equals_the_two_layer_library_unit(kind):
+    """Section 6 (MPNN-LSTM: two stacked LSTM layers).  Special case -> library routine: structure
+    encoder as dense matrices, then torch.nn.LSTM / GRU with num_layers = 2 (float64), initial and
+    final states of both layers included; the second layer's weights must matter; a reset mask on
+    the stacked layer equals separate runs."""
+    T, N, F, S, H = 5, 19, 6, 7, 5
+    chunks = np.array([[0, 8, 0, 5], [8, 19, 0, 2], [8, 19, 2, 5]], np.int64)
+    wl = synth.random_small(52, T, N, F, S, H, 3.0, chunks, kind, hub=True)
+    wl.params = synth.layer_params(52, F, S, H, kind, 1, random_bias=True, n_time_layers=2)
+    tot = int((chunks[:, 1] - chunks[:, 0]).sum())
+    n_state = 2 if kind == "lstm" else 1
+    H0 = (0.5 * synth.stream(52, "h0-stacked").standard_normal((2 * n_state * tot, H))).astype(np.float32)
+    Y, hN = oracle.forward(wl.graph, chunks, wl.params, wl.X, wl.C, time_kind=kind, H0=H0, return_state=True,
+                           n_time_layers=2)
+    rnn = (torch.nn.GRU if kind == "gru" else torch.nn.LSTM)(S, H, num_layers=2).double()
+    with torch.no_grad():
+        for l, pre in ((0, "rnn"), (1, "rnn1")):
+            for nm in ("weight_ih", "weight_hh", "bias_ih", "bias_hh"):
+                getattr(rnn, f"{nm}_l{l}").copy_(torch.from_numpy(wl.params[f"{pre}.{nm}"]).double())
+    blk = lambda b, a, n: torch.from_numpy(H0[b * tot + a:b * tot + a + n]).double()
+    off = 0
+    for v_lo, v_hi, t_lo, t_hi in chunks.tolist():
+        nv = v_hi - v_lo
+        z = torch.from_numpy(np.stack([_dense_struct(wl, t, v_lo, v_hi, wl.C) for t in range(t_lo, t_hi)]))
+        h0 = torch.stack([blk(0, off, nv), blk(n_state, off, nv)])
+        with torch.no_grad():
+            if kind == "gru":
+                out, hn = rnn(z, h0)
+            else:
+                c0 = torch.stack([blk(1, off, nv), blk(3, off, nv)])
+                out, (hn, cn) = rnn(z, (h0, c0))
+                for l in range(2):
+                    assert np.abs(hN[(l * 2 + 1) * tot + off:(l * 2 + 1) * tot + off + nv] - cn[l].numpy()).max() < 2e-6
+        assert np.abs(Y[t_lo:t_hi, v_lo:v_hi] - out.numpy()).max() < 2e-6
+        for l in range(2):
+            assert np.abs(hN[l * n_state * tot + off:l * n_state * tot + off + nv] - hn[l].numpy()).max() < 2e-6
+        off += nv
+    one = oracle.forward(wl.graph, chunks, wl.params, wl.X, wl.C, time_kind=kind, H0=H0[:n_state * tot])
+    assert np.nanmax(np.abs(one - Y)) > 1e-2          # the second layer is not a pass-through
+    # reset mask: the stacked encoder over the concatenated sequence = separate runs (Section 5.1.2)
+    wl2 = synth.random_small(53, 4, 12, 3, 4, 6, 2.5, [[0, 12, 0, 4]], kind)
+    wl2.params = synth.layer_params(53, 3, 4, 6, kind, 1, random_bias=True, n_time_layers=2)
+    mask = np.zeros((4, 12), np.uint8)
+    mask[2] = 1
+    whole = oracle.forward(wl2.graph, wl2.chunks, wl2.params, wl2.X, wl2.C, time_kind=kind, reset_mask=mask, n_time_layers=2)
+    parts = np.full_like(whole, np.nan)
+    for t0, t1 in ((0, 2), (2, 4)):
+        oracle.forward(wl2.graph, [[0, 12, t0, t1]], wl2.params, wl2.X, wl2.C, time_kind=kind, Y=parts, n_time_layers=2)
+    assert np.array_equal(whole, parts)

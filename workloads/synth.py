@@ -160,7 +160,7 @@ def xavier_uniform(rng: np.random.Generator, fan_out: int, fan_in: int) -> np.nd
 
 
 def layer_params(seed: int, F: int, S: int, H: int, time_kind: str, n_struct_layers: int = 1,
-                 random_bias: bool = False, input_concat: bool = False) -> dict:
+                 random_bias: bool = False, input_concat: bool = False, n_time_layers: int = 1) -> dict:
     """Weights in (out, in) row-major order, Xavier-uniform.  Biases are zero unless
     random_bias (tests use non-zero biases so that a dropped bias fails).  input_concat: the
     time encoder reads both structure layers' outputs, so its input weights are [gH, 2S]."""
@@ -176,6 +176,11 @@ def layer_params(seed: int, F: int, S: int, H: int, time_kind: str, n_struct_lay
         p["rnn.weight_hh"] = xavier_uniform(rng, g * H, H)          # [gH, H]
         p["rnn.bias_ih"] = np.zeros(g * H, np.float32)
         p["rnn.bias_hh"] = np.zeros(g * H, np.float32)
+        if n_time_layers == 2:      # a second recurrent layer on top of the first (input width H)
+            p["rnn1.weight_ih"] = xavier_uniform(rng, g * H, H)
+            p["rnn1.weight_hh"] = xavier_uniform(rng, g * H, H)
+            p["rnn1.bias_ih"] = np.zeros(g * H, np.float32)
+            p["rnn1.bias_hh"] = np.zeros(g * H, np.float32)
     if random_bias:
         for k in p:
             if k.endswith("bias") or ".bias_" in k:
