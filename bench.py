@@ -32,6 +32,9 @@ def parse_args():
     ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config2s", "config2tf", "config3", "config3w", "config3wc", "config3h", "config4s", "config4", "config5s", "config5", "stale", "fusion", "chunkgen", "config2lp"])
     ap.add_argument("--windows", default="0,1,2,3",
                     help="config3: which of its four 32-snapshot windows to run, one fused batch each (memory-capped fusion)")
+    ap.add_argument("--mpnn-lstm", action="store_true",
+                    help="config3: the paper's MPNN-LSTM in full (Section 6): the LSTM reads both GCN layers' outputs and "
+                         "a second LSTM layer is stacked on the first")
     ap.add_argument("--no-configs", action="store_true",
                     help="config2 (the default): do not also run configs 1, 3, 4 and 5 for the line's `configs` object")
     ap.add_argument("--config-steps", type=int, default=5, help="timed steps of each extra configuration")
@@ -1078,10 +1081,12 @@ def config3_run(args) -> dict:
     for w in windows:
         device_gen.release()
         t0 = time.perf_counter()
-        data = device_gen.config3_window(args.seed, 1.0, window=w, say=say)
+        full = bool(getattr(args, "mpnn_lstm", False))
+        data = device_gen.config3_window(args.seed, 1.0, window=w, say=say, input_concat=full, n_time_layers=2 if full else 1)
         torch.cuda.synchronize()
         t_gen = time.perf_counter() - t0
-        dw = DeviceWorkload(data, gather_mode=args.gather_mode, act_hidden="relu", act_out="none", agg_kernel=args.agg_kernel)
+        dw = DeviceWorkload(data, gather_mode=args.gather_mode, act_hidden="relu", act_out="none", agg_kernel=args.agg_kernel,
+                            n_time_layers=2 if full else 1)
         layer = dw.layer
 
         def step():
@@ -1114,7 +1119,8 @@ def config3_run(args) -> dict:
             rng = synth.stream(args.seed, f"bench-sample-{w}")
             ids = sampling.pick_chunks(hg, data.chunks, 4, rng)
             subsets = [sampling.pick_vertices(hg, data.chunks[k], 5, rng) for k in ids]
-            want, where, dt = sampled.two_layer_reference(data, hg, ids, subsets)
+            want, where, dt = sampled.two_layer_reference(data, hg, ids, subsets, input_concat=full,
+                                                          n_time_layers=2 if full else 1)
             got = sampled.device_rows(dw.Y, data.chunks, where, data.H)
             win["parity"] = parity_numbers(got, want)
             win["parity"]["sampled_vertices"] = int(len(where))
@@ -1133,10 +1139,12 @@ def config3_run(args) -> dict:
         device_gen.release(dw, data)
     F, S, H = 172, 128, 128
     rows = tot["rows"]
-    dense_flops = (2 * S * S + 2 * S * 4 * H + 2 * H * 4 * H) * rows
+    full = bool(getattr(args, "mpnn_lstm", False))
+    dense_flops = (2 * S * S + 2 * (2 * S if full else S) * 4 * H + 2 * H * 4 * H + (4 * H * 4 * H if full else 0)) * rows
     dense_ms = float(stage_sum[3])
     ach = dense_flops / (dense_ms * 1e-3) / 1e12
-    roofline = {"kernel": "k_dense_wave<LSTM> (second GCN transform + LSTM, fused over the window)", "bound": "mfma",
+    roofline = {"kernel": "k_dense_wave<LSTM> (second GCN transform + LSTM, fused over the window" +
+                          (", and the second LSTM layer's launch)" if full else ")"), "bound": "mfma",
                 "achieved": ach, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_FP32_MFMA_TFLOPS,
                 "traffic": None, "flops_per_launch": dense_flops / len(windows), "ms_per_launch": dense_ms / len(windows)}
     first_flops = 2 * F * S * rows
@@ -1147,7 +1155,8 @@ def config3_run(args) -> dict:
            "unit": "embeddings/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": f"config3 at its stated size: 2,000,000 vertices, windows {windows} of the four 32-snapshot "
-                                  "windows, each one fused batch of 64 uneven chunks; 2 GCN layers (172->128->128) + LSTM; "
+                                  "windows, each one fused batch of 64 uneven chunks; 2 GCN layers (172->128->128) + " +
+                                  ("2 stacked LSTM layers, the first reading both GCN outputs (the paper's MPNN-LSTM); " if full else "LSTM; ") +
                                   "inputs drawn on the device" +
                                   ("" if len(windows) == 4 else f"; the whole config is 4 windows: x {4 / len(windows):g}"),
                       "rows": rows, "nnz": tot["nnz"], "gather_mode": args.gather_mode, "pass": "forward"},

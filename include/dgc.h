@@ -129,6 +129,13 @@ typedef struct {
                               (else DGC_ERR_INVALID_ARG) and S = H in {32, 64, 128} with
                               dense_kernel not DGC_DENSE_TILE (else DGC_ERR_UNSUPPORTED)     */
   int32_t agg_kernel;      /* DGC_AGG_*                                                      */
+  int32_t n_time_layers;   /* 0 or 1: one recurrent layer; 2: a second GRU / LSTM layer of the same
+                              width stacked on the first (Section 6: MPNN-LSTM has two LSTM layers),
+                              reading its output step by step; Y is the second layer's output.
+                              Needs DGC_STRUCT_GCN, a recurrent time_kind (else
+                              DGC_ERR_INVALID_ARG) and S = H in {32, 64, 128} with dense_kernel not
+                              DGC_DENSE_TILE (else DGC_ERR_UNSUPPORTED); not combined with
+                              dgc_layer_set_presence / dgc_layer_set_labels (DGC_ERR_UNSUPPORTED) */
 } dgc_layer_desc_t;
 
 /* Build a layer for a fixed graph and a fixed set of chunks (the paper partitions once per
@@ -150,6 +157,7 @@ dgc_status_t dgc_layer_destroy(dgc_layer_t* layer);
  *  "rnn.weight_ih" [gH,S] ([gH,2S] with lstm_input_concat)  "rnn.weight_hh" [gH,H]
  *  "rnn.bias_ih" [gH]  "rnn.bias_hh" [gH]
  *  g = 3 (GRU, gate order r,z,n) or 4 (LSTM, gate order i,f,g,o).
+ *  n_time_layers = 2 adds "rnn1.weight_ih" [gH,H] "rnn1.weight_hh" [gH,H] "rnn1.bias_ih" "rnn1.bias_hh".
  * DGC_STRUCT_EVOLVE_GCN_O (needs F = S, time_kind NONE, one layer, act_out RELU) has instead
  *  "evolve.W_init" [F,S] (in, out)   "evolve.U_z" "evolve.V_z" "evolve.U_r" "evolve.V_r"
  *  "evolve.U_h" "evolve.V_h" [F,F]   "evolve.B_z" "evolve.B_r" "evolve.B_h" [F,S]:
@@ -174,7 +182,8 @@ dgc_status_t dgc_layer_get_param(dgc_layer_t* layer, const char* name, float* ho
  *     n_struct_layers = 2.
  *  H0 device [n_state * V, H], V = sum of chunk vertex counts, chunk k's rows starting at the
  *     sum of earlier chunks' vertex counts: state entering each chunk's first snapshot; for
- *     LSTM n_state = 2, hidden states first, then cell states.  NULL = zeros.
+ *     LSTM n_state = 2, hidden states first, then cell states.  With n_time_layers = 2 the second
+ *     layer's n_state blocks follow the first layer's ([2 * n_state * V, H]).  NULL = zeros.
  *  reset_mask device uint8 [T,N] or NULL: a non-zero byte at (t,i) zeroes the state entering
  *     step t of vertex i (Section 5.1.2).
  *  Y  device [T,N,ldy]: output h_t (or the structure encoder's output if time_kind = NONE);

@@ -15,7 +15,7 @@ from workloads import sampling
 from workloads.device_gen import HostMirror, RowFetcher
 
 
-def two_layer_reference(data, hg, chunk_ids, subsets, *, input_concat: bool = False):
+def two_layer_reference(data, hg, chunk_ids, subsets, *, input_concat: bool = False, n_time_layers: int = 1):
     """The two-layer GCN + LSTM layer (config 3) for the vertices subsets[i] of chunk chunk_ids[i]:
     returns (want [n, window, H] float32, where [n, 2] = (chunk id, vertex), seconds of oracle time).
     The oracle reads host mirrors that hold exactly the rows it needs, copied from the device."""
@@ -28,15 +28,15 @@ def two_layer_reference(data, hg, chunk_ids, subsets, *, input_concat: bool = Fa
     off = np.concatenate([[0], np.cumsum(widths)])
     tot = int(off[-1])
     H0 = None
-    if data.H0 is not None:                    # packed per chunk: hidden rows of all chunks, then cell rows
-        hid = [data.H0[off[k]:off[k + 1]].cpu().numpy() for k in chunk_ids]
-        cel = [data.H0[tot + off[k]:tot + off[k + 1]].cpu().numpy() for k in chunk_ids]
-        H0 = np.ascontiguousarray(np.concatenate(hid + cel))
+    if data.H0 is not None:                    # blocks of tot rows: hidden, cell (then the second layer's), packed per chunk
+        blocks = int(data.H0.shape[0]) // tot
+        H0 = np.ascontiguousarray(np.concatenate(
+            [data.H0[b * tot + off[k]:b * tot + off[k + 1]].cpu().numpy() for b in range(blocks) for k in chunk_ids]))
     Y = np.zeros((data.T, data.N, H), np.float32)          # untouched pages stay unallocated
     t0 = time.perf_counter()
     oracle.forward(hg, sel, data.params, mx.host, mc.host, time_kind="lstm", n_struct_layers=2, C1=mc1.host,
                    H0=H0, subset=[np.asarray(s, np.int64) for s in subsets], Y=Y, act_hidden="relu", act_out="none",
-                   input_concat=input_concat)
+                   input_concat=input_concat, n_time_layers=n_time_layers)
     dt = time.perf_counter() - t0
     want, where = [], []
     for k, sub in zip(chunk_ids, subsets):

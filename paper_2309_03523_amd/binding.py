@@ -55,7 +55,7 @@ class DescT(ct.Structure):
     _fields_ = [(n, ct.c_int32) for n in
                 ("struct_kind", "n_struct_layers", "time_kind", "dtype", "F", "S", "H", "act_hidden",
                  "act_out", "gather_mode", "validate_level", "rows_per_group", "long_nnz", "part_nnz",
-                 "dense_kernel", "heads", "lstm_input_concat", "agg_kernel")]
+                 "dense_kernel", "heads", "lstm_input_concat", "agg_kernel", "n_time_layers")]
 
 
 _lib = None
@@ -155,7 +155,7 @@ class DgcLayer:
                  gather_mode: str = "in_place", validate_level: int = 0, rows_per_group: int = 0,
                  long_nnz: int = 0, part_nnz: int = 0, dense_kernel: str = "auto", struct_kind: str = "gcn",
                  dtype: str = "f32", heads: int = 0, lstm_input_concat: bool = False, agg_kernel: str = "table",
-                 stream=None):
+                 n_time_layers: int = 1, stream=None):
         import torch
         lib = load()
         self._lib = lib
@@ -175,13 +175,13 @@ class DgcLayer:
         desc = DescT(STRUCT[struct_kind], n_struct_layers, TIME_KIND[time_kind], DTYPE[dtype], F, S, H, ACT[act_hidden],
                      ACT[act_out],
                      GATHER[gather_mode], validate_level, rows_per_group, long_nnz, part_nnz, DENSE[dense_kernel],
-                     heads, int(lstm_input_concat), AGG[agg_kernel])
+                     heads, int(lstm_input_concat), AGG[agg_kernel], int(n_time_layers))
         rc = lib.dgc_layer_create(ct.byref(desc), ct.byref(graph), carr, len(ch), _stream_ptr(stream),
                                   ct.byref(self._h))
         if rc:
             raise DgcError(rc, lib.dgc_last_error(None).decode())
         self.T, self.N, self.F, self.S, self.H = T, N, F, S, H
-        self.time_kind, self.n_struct_layers = time_kind, n_struct_layers
+        self.time_kind, self.n_struct_layers, self.n_time_layers = time_kind, n_struct_layers, n_time_layers
         self.chunks = ch
         self.out_dim = H if time_kind in ("gru", "lstm") else S
 

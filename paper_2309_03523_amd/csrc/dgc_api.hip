@@ -188,6 +188,16 @@ dgc_status_t check_desc(const dgc_layer_desc_t& d, std::string* msg) {
       return DGC_ERR_UNSUPPORTED;
     }
   }
+  if (d.n_time_layers < 0 || d.n_time_layers > 2) { *msg = "n_time_layers must be 0, 1 or 2"; return DGC_ERR_INVALID_ARG; }
+  if (d.n_time_layers == 2) {
+    if (d.struct_kind != DGC_STRUCT_GCN || (d.time_kind != DGC_TIME_GRU && d.time_kind != DGC_TIME_LSTM)) {
+      *msg = "a stacked time encoder needs a GCN layer with a GRU or LSTM"; return DGC_ERR_INVALID_ARG;
+    }
+    if (tile_kernel_runs(d.S, d.H, d.time_kind)) {
+      *msg = "the stacked time encoder is built in the wave-private dense kernel: S = H in {32, 64, 128}, dense_kernel not DGC_DENSE_TILE";
+      return DGC_ERR_UNSUPPORTED;
+    }
+  }
   const bool two = d.n_struct_layers == 2;
   if (!fits(two ? d.S : d.F, d.S, d.H, d.time_kind) || (two && !fits(d.F, d.S, 0, DGC_TIME_NONE))) {
     *msg = "these dimensions need the workgroup-tile kernel, whose tile holds max(F rounded up to 8, S, H) <= 304 columns";
@@ -602,6 +612,12 @@ dgc_status_t build_layer(dgc_layer* L, const dgc_graph_t* graph, hipStream_t st)
     if ((rc = add_param(L, "rnn.weight_hh", gH, d.H, st)) != DGC_OK) return rc;
     if ((rc = add_param(L, "rnn.bias_ih", gH, 0, st)) != DGC_OK) return rc;
     if ((rc = add_param(L, "rnn.bias_hh", gH, 0, st)) != DGC_OK) return rc;
+    if (d.n_time_layers == 2) {
+      if ((rc = add_param(L, "rnn1.weight_ih", gH, d.H, st)) != DGC_OK) return rc;
+      if ((rc = add_param(L, "rnn1.weight_hh", gH, d.H, st)) != DGC_OK) return rc;
+      if ((rc = add_param(L, "rnn1.bias_ih", gH, 0, st)) != DGC_OK) return rc;
+      if ((rc = add_param(L, "rnn1.bias_hh", gH, 0, st)) != DGC_OK) return rc;
+    }
   }
   }
   DGC_HIP_TRY(hipStreamSynchronize(st));
@@ -911,6 +927,20 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* L, const void* Xv, int64_t ldx, cons
     if (HN) tf_carry(tf.seq_len, L->total_state_rows, d.time_kind == DGC_TIME_LSTM ? 2 : 1, d.H, H0, HN, st);
     if (tf.n_lanes > 0 && !launch_dense(da, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
   } else if (!launch_dense(da, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
+  if (d.n_time_layers == 2) {
+    // The second recurrent layer: the same kernel without a transform, its input rows the first
+    // layer's output, read from Y row by row one step before the row is overwritten with the second
+    // layer's output; its states are the blocks of H0 / HN behind the first layer's.
+    const int64_t block = (int64_t)(d.time_kind == DGC_TIME_LSTM ? 2 : 1) * L->total_state_rows * d.H;
+    da.M = Y; da.ldm = ldy; da.m_by_vertex = true; da.input_is_z = true; da.K0 = 0;
+    da.Wih = L->params["rnn1.weight_ih"].packed; da.Whh = L->params["rnn1.weight_hh"].packed;
+    da.bih = L->params["rnn1.bias_ih"].raw; da.bhh = L->params["rnn1.bias_hh"].raw;
+    da.Wg = da.Wih; da.wg_bytes = sizeof(float) * packed_weight_elems((d.time_kind == DGC_TIME_LSTM ? 4 : 3) * d.H, d.H);
+    da.wg_step_bytes = 0; da.act = DGC_ACT_NONE;
+    da.X2 = nullptr; da.x2_map = nullptr;
+    da.H0 = H0 ? H0 + block : nullptr; da.HN = HN ? HN + block : nullptr;
+    if (!launch_dense(da, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
+  }
   if (prof) {
     DGC_HIP_TRY(hipEventRecord(L->ev[4], st));
     L->ev_valid = true;
@@ -1090,6 +1120,7 @@ dgc_status_t dgc_layer_set_presence(dgc_layer_t* L, const uint8_t* present, void
   if (d.struct_kind != DGC_STRUCT_GCN || d.time_kind == DGC_TIME_NONE)
     return fail(DGC_ERR_UNSUPPORTED, "temporal fusion needs a GCN layer with a recurrent time encoder");
   if (L->tf.built) return fail(DGC_ERR_STATE, "the presence mask of a layer can be set once");
+  if (d.n_time_layers == 2) return fail(DGC_ERR_UNSUPPORTED, "temporal fusion is not built for a stacked time encoder");
   if ((int64_t)L->T * L->N >= INT32_MAX) return fail(DGC_ERR_UNSUPPORTED, "temporal fusion needs T*N < 2^31");
   if (L->lab.built) return fail(DGC_ERR_STATE, "temporal fusion is not built for generated chunks");
   if (L->n_chunks > kMaxGridYZ)  // its kernels take one grid row per chunk
@@ -1187,6 +1218,7 @@ dgc_status_t dgc_layer_set_labels(dgc_layer_t* L, const int32_t* labels, void* s
   if (d.gather_mode != DGC_GATHER_IN_PLACE)
     return fail(DGC_ERR_UNSUPPORTED, "generated chunks need gather_mode DGC_GATHER_IN_PLACE");
   if (L->tf.built) return fail(DGC_ERR_STATE, "temporal fusion is not built for generated chunks");
+  if (d.n_time_layers == 2) return fail(DGC_ERR_UNSUPPORTED, "generated chunks are not built for a stacked time encoder");
   const dgc_chunk_t& c = L->chunks[0];
   if (L->n_chunks != 1 || c.v_lo != 0 || c.v_hi != L->N || c.t_lo != 0 || c.t_hi != L->T)
     return fail(DGC_ERR_STATE, "labels need a layer created with the single chunk [0,N) x [0,T)");

@@ -543,7 +543,7 @@ void launch_pack_weight(const float* W, int32_t n_out, int32_t n_in, float4* pac
 
 bool launch_dense(const DenseArgs& a, hipStream_t st, std::string* why) {
   if (a.variant != DGC_DENSE_TILE && dense_wave_supported(a)) return launch_dense_wave(a, st, why);
-  if (a.variant == DGC_DENSE_WAVE || a.X2) {
+  if (a.variant == DGC_DENSE_WAVE || a.X2 || a.input_is_z || a.m_by_vertex) {
     if (why) *why = "the wave-private dense kernel needs S = H in {32, 64, 128}";
     return false;
   }

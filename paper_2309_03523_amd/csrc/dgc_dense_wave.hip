@@ -211,8 +211,11 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
   // Aggregated rows as B operand, straight from global memory: float4 at column 8*kb + 4*half of
   // this lane's row.  (The library's M buffer has a pitch that is a multiple of 8 with zero pad
   // columns, so a k-block never needs masking.)
-  const float* mrow0 = a.M + (ch.row_off0 + tile.v0 + row) * a.ldm + 4 * half;
-  const int64_t mstep = ch.nv * a.ldm;
+  // (m_by_vertex: the input rows are not the packed aggregated rows but rows t*N + v of a [T,N,ldm]
+  //  tensor - the first recurrent layer's output when this launch runs a stacked second layer)
+  const float* mrow0 = a.m_by_vertex ? a.M + ((int64_t)ch.t_lo * a.N + vrow) * a.ldm + 4 * half
+                                     : a.M + (ch.row_off0 + tile.v0 + row) * a.ldm + 4 * half;
+  const int64_t mstep = a.m_by_vertex ? a.N * a.ldm : ch.nv * a.ldm;
   float4 xq[kXAhead];
 #pragma unroll
   for (int i = 0; i < kXAhead; ++i) xq[i] = i < nkb0 ? *reinterpret_cast<const float4*>(mrow0 + 8 * i) : zero4();
@@ -328,15 +331,22 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
       for (int g = 0; g < NG; ++g) wq[g] = wsi.frag(lane16, (g * NJB) * NKX * 1024);  // gates of column block 0
     }
     float4 z[NKB];
+    if (a.input_is_z) {
+      // no transform (K0 = 0, the loop above did nothing): the input row is the time encoder's input,
+      // and its float4 at column 8*kb + 4*half is exactly this lane's fragment kb
 #pragma unroll
-    for (int kb = 0; kb < NKB; ++kb) {
-      const float4 b = *reinterpret_cast<const float4*>(zbias + 8 * kb + 4 * half);
-      const int jb = kb / 4, g4 = kb % 4;
-      z[kb] = make_float4(zacc[jb][4 * g4 + 0] + b.x, zacc[jb][4 * g4 + 1] + b.y, zacc[jb][4 * g4 + 2] + b.z,
-                          zacc[jb][4 * g4 + 3] + b.w);
-      if (a.act == DGC_ACT_RELU) {
-        z[kb].x = fmaxf(z[kb].x, 0.f); z[kb].y = fmaxf(z[kb].y, 0.f);
-        z[kb].z = fmaxf(z[kb].z, 0.f); z[kb].w = fmaxf(z[kb].w, 0.f);
+      for (int kb = 0; kb < NKB; ++kb) z[kb] = load_x(kb);
+    } else {
+#pragma unroll
+      for (int kb = 0; kb < NKB; ++kb) {
+        const float4 b = *reinterpret_cast<const float4*>(zbias + 8 * kb + 4 * half);
+        const int jb = kb / 4, g4 = kb % 4;
+        z[kb] = make_float4(zacc[jb][4 * g4 + 0] + b.x, zacc[jb][4 * g4 + 1] + b.y, zacc[jb][4 * g4 + 2] + b.z,
+                            zacc[jb][4 * g4 + 3] + b.w);
+        if (a.act == DGC_ACT_RELU) {
+          z[kb].x = fmaxf(z[kb].x, 0.f); z[kb].y = fmaxf(z[kb].y, 0.f);
+          z[kb].z = fmaxf(z[kb].z, 0.f); z[kb].w = fmaxf(z[kb].w, 0.f);
+        }
       }
     }
 
@@ -496,7 +506,8 @@ bool launch_wk(const DenseArgs& a, hipStream_t st, std::string* why) {
 bool dense_wave_supported(const DenseArgs& a) {
   const bool s_ok = a.S == 32 || a.S == 64 || a.S == 128 || (a.S == 256 && a.time_kind == DGC_TIME_NONE);
   const bool m_ok = a.ldm % 8 == 0 && a.ldm >= (a.K0 + 7) / 8 * 8;  // whole k-blocks, zero padded
-  return s_ok && m_ok && (a.time_kind == DGC_TIME_NONE || a.H == a.S);
+  if (a.input_is_z && (a.time_kind == DGC_TIME_NONE || a.K0 != 0 || a.ldm < a.S || a.ldm % 4)) return false;
+  return s_ok && (m_ok || a.input_is_z) && (a.time_kind == DGC_TIME_NONE || a.H == a.S);
 }
 
 bool launch_dense_wave(const DenseArgs& a, hipStream_t st, std::string* why) {

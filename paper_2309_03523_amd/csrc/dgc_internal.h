@@ -185,6 +185,12 @@ struct DenseArgs {
   // x2_map[t*N + v] (negative: any row, the output is not used), or t*N + v without a map.
   const float* X2; int64_t ldx2;
   const int64_t* x2_map;
+  // A stacked recurrent layer (wave-private kernel only): the rows of M are rows t*N + v of a
+  // [T,N,ldm] tensor (m_by_vertex) and are the time encoder's input as they are (input_is_z: no
+  // transform, K0 = 0; Wg must still name readable packed weights, its fragments are prefetched).
+  // M may be Y itself: a wave reads row (t, v) in step t and writes it one step later.
+  bool m_by_vertex;
+  bool input_is_z;
 };
 // returns false if the (S,H,K0) combination has no kernel
 bool launch_dense(const DenseArgs& a, hipStream_t st, std::string* why);

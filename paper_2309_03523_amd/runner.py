@@ -69,7 +69,7 @@ class DeviceWorkload:
             rm = torch.from_numpy(np.ascontiguousarray(reset_mask, np.uint8)).to(self.Y.device)
         HN = None
         if want_state and self.wl.time_kind != "none":
-            n_state = 2 if self.wl.time_kind == "lstm" else 1
+            n_state = (2 if self.wl.time_kind == "lstm" else 1) * max(1, self.layer.n_time_layers)
             tot = int((self.wl.chunks[:, 1] - self.wl.chunks[:, 0]).sum())
             HN = torch.full((n_state * tot, self.wl.H), float("nan"), dtype=torch.float32, device=self.Y.device)
         self.layer.forward(self.X, self.C if C is None else C, self.Y, C1=self.C1 if C1 is None else C1,

@@ -34,7 +34,7 @@ def test_exports_every_declared_symbol(lib):
 def _create(lib, desc_kw=None, chunks=((0, 4, 0, 2),), T=2, N=4, null_snapshot=False):
     d = dict(struct_kind=0, n_struct_layers=1, time_kind=1, dtype=0, F=8, S=32, H=32, act_hidden=0, act_out=0,
              gather_mode=0, validate_level=0, rows_per_group=0, long_nnz=0, part_nnz=0, dense_kernel=0, heads=0,
-             lstm_input_concat=0, agg_kernel=0)
+             lstm_input_concat=0, agg_kernel=0, n_time_layers=0)
     d.update(desc_kw or {})
     desc = binding.DescT(*[d[n] for n, _ in binding.DescT._fields_])
     fake = 0x1000  # never dereferenced: every check below fails before the device is used

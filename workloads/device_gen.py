@@ -198,13 +198,15 @@ def _pitched_normal(T: int, N: int, F: int, ld: int, gen, scale: float = 1.0, ba
     return out
 
 
-def config3_window(seed: int = 0, scale: float = 1.0, window: int = 0, input_concat: bool = False, say=None) -> DeviceData:
+def config3_window(seed: int = 0, scale: float = 1.0, window: int = 0, input_concat: bool = False, say=None,
+                   n_time_layers: int = 1) -> DeviceData:
     """One 32-snapshot window of config 3 (2,000,000 * scale vertices, mean degree 20 with tail
     exponent 2.0, density varying 10x along a sinusoid of period 128 snapshots times (1 + 0.1 N(0,1)),
     85 % of the edge draws inside one of the window's 64 uneven vertex ranges; F = 172 at pitch 176,
     S = H = 128; cache = X + 0.1 N(0,1), second-layer cache N(0,1), window-start states 0.1 N(0,1)
     for windows after the first, zero for the first), drawn on the device.  `window` in 0..3 picks the
-    quarter of the 128-snapshot density curve."""
+    quarter of the 128-snapshot density curve.  input_concat / n_time_layers = 2: parameters (and states)
+    for the LSTM reading both GCN outputs / for two stacked LSTM layers (Section 6's MPNN-LSTM)."""
     import torch
     N = max(256, int(2_000_000 * scale))
     T, F, S, H, ld = 32, 172, 128, 128, 176
@@ -239,11 +241,11 @@ def config3_window(seed: int = 0, scale: float = 1.0, window: int = 0, input_con
     C1 = _pitched_normal(T, N, S, S, _gen(seed, "cache1-dev"), say=say, what="second-layer cache")
     H0 = None
     if window > 0:
-        H0 = 0.1 * torch.randn((2 * N, H), generator=_gen(seed, "h0-dev"), device="cuda", dtype=torch.float32)
+        H0 = 0.1 * torch.randn((2 * n_time_layers * N, H), generator=_gen(seed, "h0-dev"), device="cuda", dtype=torch.float32)
     torch.cuda.empty_cache()
     return DeviceData(f"config3@{scale:g}/window{window}", N, rowptr, col, chunks, F, S, H, "lstm", 2, X, C, C1, H0,
-                      synth.layer_params(seed, F, S, H, "lstm", 2, False, input_concat=input_concat),
-                      notes={"input_concat": True} if input_concat else {})
+                      synth.layer_params(seed, F, S, H, "lstm", 2, False, input_concat=input_concat, n_time_layers=n_time_layers),
+                      notes=dict({"input_concat": True} if input_concat else {}, n_time_layers=n_time_layers))
 
 
 def config4(seed: int = 0, scale: float = 1.0, say=None):
