@@ -149,7 +149,9 @@ __device__ __forceinline__ void store_state_t(const DenseArgs& a, int64_t idx, i
 // states): states enter and leave through the tables seq_in / seq_out instead of at the window's ends.
 // CAT: the time encoder's input is [X2 row, Z] (2S wide): X2 holds the first structure layer's
 // output of the same (snapshot, vertex); it shares the Z tile in LDS, columns 0..S-1.
-template <int KIND, int NJB, bool SEQ, bool CAT>
+// STACK: this launch is a stacked second recurrent layer: no transform, the input rows are rows
+// t*N + v of a [T,N,ldm] tensor (DenseArgs::m_by_vertex and input_is_z, which go together).
+template <int KIND, int NJB, bool SEQ, bool CAT, bool STACK = false>
 __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dense_wave(DenseArgs a) {
   // LDS, private to this wave (the workgroup is one wave):
   //   zbuf [32][ldz] the Z tile | gbias [4][H] gate biases, pre-summed | zbias [S]
@@ -213,9 +215,9 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
   // columns, so a k-block never needs masking.)
   // (m_by_vertex: the input rows are not the packed aggregated rows but rows t*N + v of a [T,N,ldm]
   //  tensor - the first recurrent layer's output when this launch runs a stacked second layer)
-  const float* mrow0 = a.m_by_vertex ? a.M + ((int64_t)ch.t_lo * a.N + vrow) * a.ldm + 4 * half
-                                     : a.M + (ch.row_off0 + tile.v0 + row) * a.ldm + 4 * half;
-  const int64_t mstep = a.m_by_vertex ? a.N * a.ldm : ch.nv * a.ldm;
+  const float* mrow0 = STACK ? a.M + ((int64_t)ch.t_lo * a.N + vrow) * a.ldm + 4 * half
+                             : a.M + (ch.row_off0 + tile.v0 + row) * a.ldm + 4 * half;
+  const int64_t mstep = STACK ? a.N * a.ldm : ch.nv * a.ldm;
   float4 xq[kXAhead];
 #pragma unroll
   for (int i = 0; i < kXAhead; ++i) xq[i] = i < nkb0 ? *reinterpret_cast<const float4*>(mrow0 + 8 * i) : zero4();
@@ -331,7 +333,7 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
       for (int g = 0; g < NG; ++g) wq[g] = wsi.frag(lane16, (g * NJB) * NKX * 1024);  // gates of column block 0
     }
     float4 z[NKB];
-    if (a.input_is_z) {
+    if constexpr (STACK) {
       // no transform (K0 = 0, the loop above did nothing): the input row is the time encoder's input,
       // and its float4 at column 8*kb + 4*half is exactly this lane's fragment kb
 #pragma unroll
@@ -481,7 +483,12 @@ bool launch_w(const DenseArgs& a, hipStream_t st, std::string* why) {
     auto go = [&](auto kernel) {
       hipLaunchKernelGGL(kernel, (unsigned)a.n_tiles32, kWave, lds, st, a);
     };
-    if (kRnn && a.seq_in && cat) go(k_dense_wave<KIND, NJB, kRnn, kLstm>);
+    if (a.input_is_z != a.m_by_vertex || (a.input_is_z && (!kRnn || a.seq_in || cat))) {
+      if (why) *why = "a stacked recurrent layer runs without sequence tables and without the concatenated input";
+      return false;
+    }
+    if (a.input_is_z) go(k_dense_wave<KIND, NJB, false, false, kRnn>);
+    else if (kRnn && a.seq_in && cat) go(k_dense_wave<KIND, NJB, kRnn, kLstm>);
     else if (kRnn && a.seq_in) go(k_dense_wave<KIND, NJB, kRnn, false>);
     else if (cat) go(k_dense_wave<KIND, NJB, false, kLstm>);
     else go(k_dense_wave<KIND, NJB, false, false>);
