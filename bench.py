@@ -505,7 +505,8 @@ def stale_main(args):
     one, so that every step meets the same distances and sends the same rows."""
     import numpy as np
     import torch
-    from paper_2309_03523_amd import binding, synth
+    from paper_2309_03523_amd import binding
+    from workloads import synth
     R, F = 32 * 100_000, 128
     l1, l_prev = 1.0, 0.5
     t0 = time.perf_counter()
@@ -654,7 +655,8 @@ def labelled_main(args):
     from the state cache, states that leave a chunk are written out.  One step = one forward."""
     import numpy as np
     import torch
-    from paper_2309_03523_amd import binding, synth
+    from paper_2309_03523_amd import binding
+    from workloads import synth
     from paper_2309_03523_amd.runner import DeviceWorkload
     synth.progress = lambda msg: print(msg, file=sys.stderr, flush=True)
     w_s, w_t, cap, max_iters = 1, 1, 50_000, 1000        # one structure layer : one time layer; config 2's mean chunk size
@@ -781,7 +783,8 @@ def chunkgen_main(args):
     one whole generation (all iterations until no label changes)."""
     import numpy as np
     import torch
-    from paper_2309_03523_amd import binding, synth
+    from paper_2309_03523_amd import binding
+    from workloads import synth
     synth.progress = lambda msg: print(msg, file=sys.stderr, flush=True)
     w_s, w_t, cap, max_iters = 2, 1, 25_000 * 8, 1000     # two structure layers : one time layer; chunks of config 2's size
     t0 = time.perf_counter()
@@ -1039,8 +1042,9 @@ def gcn_run(args) -> dict:
            "config": {"workload": desc, "rows": rows, "nnz": nnz, "gather_mode": args.gather_mode,
                       "agg_kernel": args.agg_kernel, "pass": "forward"},
            "roofline": with_traffic_rate(roofline), "roofline_aggregation": with_traffic_rate(agg),
-           "stage_ms": {"aggregate0": float(stage[0]), "dense0": float(stage[1]), "aggregate1": float(stage[2]),
-                        "dense_rnn": float(stage[3])},
+           "stage_ms": ({"aggregate0": float(stage[0]), "dense_rnn": float(stage[3])} if wl.n_struct_layers == 1 else
+                        {"aggregate0": float(stage[0]), "dense0": float(stage[1]), "aggregate1": float(stage[2]),
+                         "dense_rnn": float(stage[3])}),
            "device_ms_per_step": step_stats, "measured_hbm_copy_GBs": copy_GBs, "packing": packing,
            "setup_s": {"generate": t_gen, "upload_create_pack": t_create}}
     if graph_ms is not None:

@@ -476,33 +476,38 @@ __global__ __launch_bounds__(256) void k_agg_short(SpmmArgs a) {
   const float* dinv_rows = a.dinv + (int64_t)sg.t * a.g.N + sg.v_lo + r0;
   const int64_t prow0 = sg.row_off + r0;
   const int64_t ldo = a.ld_out ? a.ld_out : a.ldm;
-  int r = 0;
-  while (r < n) {
+  // rows whose output nobody wants (row_map < 0: absent under temporal fusion) are not computed
+  uint64_t todo = __ballot(lane < n && (!a.row_map || a.row_map[prow0 + lane] >= 0));
+  while (todo) {
+    const int r = __builtin_ctzll(todo);
     const int e_r = __builtin_amdgcn_readlane(my_rel, r), e_r1 = __builtin_amdgcn_readlane(my_rel, r + 1);
     const int nnz_r = e_r1 - e_r;
-    if (nnz_r > a.long_nnz) { ++r; continue; }
+    if (nnz_r > a.long_nnz) { todo &= todo - 1; continue; }
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
     if (G == 1 || nnz_r > kSmallRow) {
       // one row for the whole wave
       agg_range<LPR, SKIP>(c.tab, e_r + g * kU, e_r1, kU * G, (int)(sg.v_lo + r0 + r), c.fresh_l, c.stale_l, c.ld_bytes, acc);
       agg_reduce_groups<LPR>(acc);
       const int64_t orow = a.row_map ? a.row_map[prow0 + r] : prow0 + r;
-      if (g == 0 && orow >= 0) agg_store<LPR>(a.M + orow * ldo, l, a.F, a.ldm, acc, dinv_rows[r]);
-      ++r;
+      if (g == 0) agg_store<LPR>(a.M + orow * ldo, l, a.F, a.ldm, acc, dinv_rows[r]);
+      todo &= todo - 1;
     } else {
-      // up to G consecutive small rows, one per lane group
-      int take = 1;
-      while (take < G && r + take < n) {
-        const int nn = __builtin_amdgcn_readlane(my_rel, r + take + 1) - __builtin_amdgcn_readlane(my_rel, r + take);
+      // up to G of the next wanted small rows, one per lane group
+      int take = 0, mine = r;
+      uint64_t m = todo;
+      while (take < G && m) {
+        const int r2 = __builtin_ctzll(m);
+        const int nn = __builtin_amdgcn_readlane(my_rel, r2 + 1) - __builtin_amdgcn_readlane(my_rel, r2);
         if (nn > kSmallRow) break;
+        if (g == take) mine = r2;
         ++take;
+        m &= m - 1;
       }
-      const int mine = r + (g < take ? g : 0);
+      todo = m;
       const int b = __shfl(my_rel, mine), e = __shfl(my_rel, mine + 1);
       agg_range<LPR, SKIP>(c.tab, b, g < take ? e : b, kU, (int)(sg.v_lo + r0 + mine), c.fresh_l, c.stale_l, c.ld_bytes, acc);
       const int64_t orow = a.row_map ? a.row_map[prow0 + mine] : prow0 + mine;
-      if (g < take && orow >= 0) agg_store<LPR>(a.M + orow * ldo, l, a.F, a.ldm, acc, dinv_rows[mine]);
-      r += take;
+      if (g < take) agg_store<LPR>(a.M + orow * ldo, l, a.F, a.ldm, acc, dinv_rows[mine]);
     }
   }
 }
@@ -520,6 +525,7 @@ __global__ __launch_bounds__(256) void k_agg_long(SpmmArgs a) {
   const int part = uniform(a.work_long[4 * item + 2]);
   const Segment sg = a.segs[seg];
   const int g = lane / LPR, l = lane % LPR;
+  if (a.row_map && a.row_map[sg.row_off + row] < 0) return;     // nobody wants this row (the merge skips it too)
   const int64_t* rp = a.g.rowptr[sg.t] + sg.v_lo + row;
   const int64_t ra = rp[0], rb = rp[1];
   const int64_t ea = ra + (int64_t)part * a.part_nnz;
