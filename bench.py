@@ -109,6 +109,10 @@ def parity_numbers(got, want) -> dict:
             "p999_unfloored": float(np.quantile(d[nz] / a[nz], 0.999)) if nz.any() else 0.0}
 
 
+AGG_KERNELS = {"table": "k_agg_short + k_agg_long + k_spmm_long_reduce (edge-table kernels)",
+               "walk": "k_spmm_short + k_spmm_long + k_spmm_long_reduce (column-walking kernels)"}
+
+
 def flops_per_row(wl) -> dict:
     """Algorithmic flops per snapshot-vertex row of each step of the path."""
     g = {"gru": 3, "lstm": 4, "none": 0}[wl.time_kind]
@@ -1029,9 +1033,10 @@ def gcn_run(args) -> dict:
         nnz_agg = nnz
         agg_bytes = rows * (wl.F * 4) + nnz * 4 + rows * 8 + rows * (wl.F * 4)
     agg_ms = float(stage[0])
-    agg = {"kernel": "k_spmm_short + k_spmm_long + k_spmm_long_reduce", "bound": "hbm",
+    agg = {"kernel": AGG_KERNELS[args.agg_kernel], "bound": "hbm",
            "achieved": agg_bytes / (agg_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-           "frac": agg_bytes / (agg_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": traffic.get("aggregation"),
+           "frac": agg_bytes / (agg_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+           "traffic": traffic.get("aggregation") if args.agg_kernel == "table" else None,     # the counters were taken on the default kernels
            "bytes_per_launch": agg_bytes, "ms_per_launch": agg_ms,
            "gather_traffic_GBs": nnz_agg * wl.F * 4 / (agg_ms * 1e-3) / 1e9, "nnz": nnz_agg}
 
@@ -1147,10 +1152,12 @@ def config3_run(args) -> dict:
     dense_flops = (2 * S * S + 2 * (2 * S if full else S) * 4 * H + 2 * H * 4 * H + (4 * H * 4 * H if full else 0)) * rows
     dense_ms = float(stage_sum[3])
     ach = dense_flops / (dense_ms * 1e-3) / 1e12
+    traffic = measured_traffic("config3_mpnn_lstm" if full else "config3", args.gather_mode)     # per window
     roofline = {"kernel": "k_dense_wave<LSTM> (second GCN transform + LSTM, fused over the window" +
                           (", and the second LSTM layer's launch)" if full else ")"), "bound": "mfma",
                 "achieved": ach, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_FP32_MFMA_TFLOPS,
-                "traffic": None, "flops_per_launch": dense_flops / len(windows), "ms_per_launch": dense_ms / len(windows)}
+                "traffic": traffic.get("dense"), "flops_per_launch": dense_flops / len(windows),
+                "ms_per_launch": dense_ms / len(windows)}
     first_flops = 2 * F * S * rows
     agg_bytes = rows * (F * 4) * 2 + rows * (S * 4) * 2 + 2 * (tot["nnz"] * 4 + rows * 8)
     agg_ms = float(stage_sum[0] + stage_sum[2])
@@ -1170,9 +1177,11 @@ def config3_run(args) -> dict:
                                            "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                                            "frac": first_flops / (float(stage_sum[1]) * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
                                            "ms": float(stage_sum[1])}},
-           "roofline_aggregation": {"kernel": "k_spmm_* of both GCN layers", "bound": "hbm",
+           "roofline_aggregation": {"kernel": AGG_KERNELS[args.agg_kernel] + " of both GCN layers, all windows of the step", "bound": "hbm",
                                     "achieved": agg_bytes / (agg_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                    "frac": agg_bytes / (agg_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None,
+                                    "frac": agg_bytes / (agg_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                    "traffic": (len(windows) * (traffic["aggregation"] + traffic["aggregation_second_layer"])
+                                                if "aggregation" in traffic and args.agg_kernel == "table" else None),
                                     "bytes_per_step": agg_bytes, "ms": agg_ms,
                                     "gather_traffic_GBs": tot["nnz"] * (F + S) * 4 / (agg_ms * 1e-3) / 1e9},
            "stage_ms": {"aggregate0": float(stage_sum[0]), "dense0": float(stage_sum[1]),
