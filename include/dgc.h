@@ -59,7 +59,8 @@ enum { DGC_DTYPE_F32 = 0, DGC_DTYPE_BF16 = 1 };
  * DGNN of Sections 2.1 and 6: a one-layer graph attention structure encoder and a one-layer
  * scaled dot-product self-attention time encoder in which every vertex attends, causally, to
  * its own embeddings in the snapshots of the chunk's window.  Built for F = S = 128, heads = 8,
- * windows of at most 16 snapshots; act_hidden / act_out / gather_mode / dense_kernel are ignored
+ * windows of at most 32 snapshots (two vertices share a 32-row tile while every window is at
+ * most 16, else a tile is one vertex); act_hidden / act_out / gather_mode / dense_kernel are ignored
  * (ELU follows the structure encoder; neighbours are read in place):
  *   z = W x for rows inside the chunk range, W c for cache rows;
  *   e_ij^h = LeakyReLU_0.2(a_dst^h . z_i^h + a_src^h . z_j^h), alpha = softmax over the stored row,

@@ -325,8 +325,11 @@ dgc_status_t build_dysat(dgc_layer* L, const std::vector<ChunkInfo>& cinfo, hipS
   w.T = T; w.N = N; w.n_chunks = L->n_chunks;
   w.g = L->graph_dev(); w.segs = L->d_segs; w.nseg = L->nseg; w.chunks = L->d_chunks;
   w.work_short = L->d_work_short; w.n_short = L->n_short; w.total_rows = L->total_rows;
-  for (const ChunkInfo& c : cinfo)
-    if (c.w > 16) return fail(DGC_ERR_UNSUPPORTED, "the temporal self-attention is built for windows of at most 16 snapshots");
+  w.wide = false;
+  for (const ChunkInfo& c : cinfo) {
+    if (c.w > 32) return fail(DGC_ERR_UNSUPPORTED, "the temporal self-attention is built for windows of at most 32 snapshots");
+    if (c.w > 16) w.wide = true;     // one vertex per 32-row tile instead of two
+  }
   if (L->T > 4096) return fail(DGC_ERR_UNSUPPORTED, "the attention layer is built for at most 4096 snapshots");
   const int32_t rows_of[DY_NPAR] = {S, heads, heads, T, S, S, S};
   const int32_t cols_of[DY_NPAR] = {S, S / heads, S / heads, S, S, S, S};
@@ -345,7 +348,7 @@ dgc_status_t build_dysat(dgc_layer* L, const std::vector<ChunkInfo>& cinfo, hipS
   }
   uint4** frags[9] = {&w.Wp, &w.Wqp, &w.Wkp, &w.Wvp, &w.WqT, &w.WkT, &w.WvT, &w.WT, &w.WTlo};
   for (uint4** f : frags) DGC_HIP_TRY(dev_alloc(L, f, 4 * 8 * 64));
-  // snapshots in use, 2-vertex tiles per chunk, owner map
+  // snapshots in use, tiles of the temporal kernels per chunk, owner map
   std::vector<int32_t> used;
   {
     std::vector<char> seen(T, 0);
@@ -355,7 +358,7 @@ dgc_status_t build_dysat(dgc_layer* L, const std::vector<ChunkInfo>& cinfo, hipS
       if (seen[t]) used.push_back(t);
   }
   std::vector<int64_t> tptr(L->n_chunks + 1, 0);
-  for (int32_t k = 0; k < L->n_chunks; ++k) tptr[k + 1] = tptr[k] + (cinfo[k].nv + 1) / 2;
+  for (int32_t k = 0; k < L->n_chunks; ++k) tptr[k + 1] = tptr[k] + (w.wide ? cinfo[k].nv : (cinfo[k].nv + 1) / 2);
   w.n_used = (int32_t)used.size(); w.n_tiles = tptr.back();
   int32_t *d_used = nullptr, *d_owner = nullptr;
   int64_t* d_tptr = nullptr;

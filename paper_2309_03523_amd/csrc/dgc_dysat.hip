@@ -1,6 +1,6 @@
 // Graph-attention structure encoder + causal temporal self-attention time encoder (the
 // DySAT-style DGNN of the paper's Sections 2.1 and 6) over a fused batch of chunks, bf16 storage
-// with fp32 accumulation: forward pass.  S = F = 128, 8 heads of 16 dims, windows of up to 16
+// with fp32 accumulation: forward pass.  S = F = 128, 8 heads of 16 dims, windows of up to 32
 // snapshots.
 //
 //   z = W x (own rows) / W c (cache rows, Section 5.2);  e_ij^h = LeakyReLU_0.2(a_dst^h.z_i^h + a_src^h.z_j^h)
@@ -284,7 +284,7 @@ __global__ __launch_bounds__(256) void k_gat_aggregate_merge(GatArgs a) {
 // values, so that the only roundings to bf16 are those of the stored tensors (z, U, Y).
 struct TemporalArgs {
   const ChunkInfo* chunks; int32_t n_chunks;
-  const int64_t* tile_ptr;   // [n_chunks+1] first 2-vertex tile of every chunk
+  const int64_t* tile_ptr;   // [n_chunks+1] first tile of every chunk (2 vertices per tile; WIDE: 1)
   int64_t n_tiles;
   int64_t N; int32_t T;
   const float* U;
@@ -294,11 +294,13 @@ struct TemporalArgs {
 };
 
 // softmax over the key steps r <= s of the lane's own vertex; x[p] is the raw score against key
-// step r = 8 (p/4) + 4 hh + p%4; returns probabilities (0 for masked positions)
+// step r = 8 (p/4) + 4 hh + p%4 (NP = 8: windows up to 16; NP = 16: up to 32); returns
+// probabilities (0 for masked positions)
+template <int NP>
 __device__ __forceinline__ void causal_softmax(float* x, int s, int hh) {
   float mx = -INFINITY;
 #pragma unroll
-  for (int p = 0; p < 8; ++p) {
+  for (int p = 0; p < NP; ++p) {
     const int r = 8 * (p >> 2) + 4 * hh + (p & 3);
     x[p] = r <= s ? 0.25f * x[p] : -INFINITY;
     mx = fmaxf(mx, x[p]);
@@ -306,14 +308,14 @@ __device__ __forceinline__ void causal_softmax(float* x, int s, int hh) {
   mx = fmaxf(mx, __shfl_xor(mx, 32));
   float sum = 0.f;
 #pragma unroll
-  for (int p = 0; p < 8; ++p) {
+  for (int p = 0; p < NP; ++p) {
     x[p] = __expf(x[p] - mx);
     sum += x[p];
   }
   sum += __shfl_xor(sum, 32);
   const float inv = 1.f / sum;
 #pragma unroll
-  for (int p = 0; p < 8; ++p) x[p] *= inv;
+  for (int p = 0; p < NP; ++p) x[p] *= inv;
 }
 
 // The three weight matrices (96 KB of fragments) are staged in LDS once per workgroup; the
@@ -329,6 +331,10 @@ __device__ __forceinline__ void stage_weights(uint4* lds, const uint4* w0, const
   __syncthreads();
 }
 
+// WIDE: one vertex per tile, windows of up to 32 snapshots: the score block of a head is the whole
+// 32 x 32 product (all 16 registers of a lane are keys of its own vertex), and the product with V
+// contracts over the two halves of the keys (registers 0..7 and 8..15) instead of over two vertices.
+template <bool WIDE>
 __global__ __launch_bounds__(512) void k_temporal_fwd(TemporalArgs a) {
   extern __shared__ uint4 wlds[];
   stage_weights(wlds, a.Wq, a.Wk, a.Wv);
@@ -336,7 +342,7 @@ __global__ __launch_bounds__(512) void k_temporal_fwd(TemporalArgs a) {
   const int hh = lane >> 5, f = lane & 31;
   const uint32_t m_head[2] = {(f >> 4) == 0 ? 0xffffffffu : 0u, (f >> 4) == 1 ? 0xffffffffu : 0u};
   for (int64_t tile = (int64_t)blockIdx.x * nw + (threadIdx.x >> 6); tile < a.n_tiles; tile += (int64_t)gridDim.x * nw) {
-  const TileRow r = tile_row(a.chunks, a.n_chunks, a.tile_ptr, tile, a.N, lane);
+  const TileRow r = tile_row<WIDE>(a.chunks, a.n_chunks, a.tile_ptr, tile, a.N, lane);
   const uint32_t m_vert[2] = {r.a == 0 ? 0xffffffffu : 0u, r.a == 1 ? 0xffffffffu : 0u};
   bf16x8 pf[8], pl[8];
   load_p_frags<true>(a.U, a.pos, r, hh, pf, pl);
@@ -369,21 +375,24 @@ __global__ __launch_bounds__(512) void k_temporal_fwd(TemporalArgs a) {
       st = mfma(kl, qh, st);                 // st[i = key row][j = query row]
       st = mfma(kh, ql, st);
       st = mfma(kh, qh, st);
-      float pr[8];
+      constexpr int NP = WIDE ? 16 : 8;
+      float pr[NP];
 #pragma unroll
-      for (int p = 0; p < 8; ++p) pr[p] = pick_half(st, p, m_vert[0], m_vert[1]);
-      causal_softmax(pr, r.s, hh);
-      bf16x8 ph, plo;
-      split8(pr, ph, plo);
+      for (int p = 0; p < NP; ++p) pr[p] = WIDE ? st[p] : pick_half(st, p, m_vert[0], m_vert[1]);
+      causal_softmax<NP>(pr, r.s, hh);
+      bf16x8 ph[NP / 8], plo[NP / 8];
 #pragma unroll
-      for (int av = 0; av < 2; ++av) {
+      for (int c = 0; c < NP / 8; ++c) split8(pr + 8 * c, ph[c], plo[c]);
+#pragma unroll
+      for (int av = 0; av < 2; ++av) {      // the two vertices, or (WIDE) the two halves of the keys
         bf16x8 vh, vl;
 #pragma unroll
         for (int p = 0; p < 8; ++p) tmp[p] = vt[8 * av + p];
         split8(tmp, vh, vl);
         vh = and_mask(vh, m_head[hd]);
         vl = and_mask(vl, m_head[hd]);
-        const bf16x8 pa = and_mask(ph, m_vert[av]), pb = and_mask(plo, m_vert[av]);
+        const bf16x8 pa = WIDE ? ph[WIDE ? av : 0] : and_mask(ph[0], m_vert[av]);
+        const bf16x8 pb = WIDE ? plo[WIDE ? av : 0] : and_mask(plo[0], m_vert[av]);
         y = mfma(vl, pa, y);
         y = mfma(vh, pb, y);
         y = mfma(vh, pa, y);
@@ -450,12 +459,15 @@ void dysat_forward(const DysatWs& ws, const void* X, int64_t ldx, const void* C,
     static bool attr_set = false;   // dynamic LDS above 64 KB has to be allowed once per kernel
     const size_t lds = sizeof(uint4) * 3 * kFragsPerW;
     if (!attr_set) {
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_temporal_fwd), hipFuncAttributeMaxDynamicSharedMemorySize,
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_temporal_fwd<false>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds);
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_temporal_fwd<true>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds);
       attr_set = true;
     }
     const unsigned grid = (unsigned)std::min<int64_t>(256, (ws.n_tiles + 7) / 8);
-    hipLaunchKernelGGL(k_temporal_fwd, grid, 512, lds, st, ta);
+    if (ws.wide) hipLaunchKernelGGL(k_temporal_fwd<true>, grid, 512, lds, st, ta);
+    else hipLaunchKernelGGL(k_temporal_fwd<false>, grid, 512, lds, st, ta);
   }
   if (ev) (void)hipEventRecord(ev[3], st);
 }

@@ -89,6 +89,11 @@ __device__ __forceinline__ void stage_weights(uint4* lds, const uint4* w0, const
 // registers = query steps): those are obtained by one product each with a selection operand
 // (a 16 x 16 transpose per vertex on the matrix core, exact for the hi and the lo part).
 // All operands are hi + lo pairs.  dQ, dK, dV land in row layout and are stored (bf16).
+// WIDE (one vertex per tile, windows of up to 32 snapshots): a lane's 16 score registers are all
+// keys of its own vertex, the transposes are 32 x 32 (two selection products, one per half of the
+// keys), and the three final products contract over the two halves of the keys / queries instead
+// of over two vertices.
+template <bool WIDE>
 __global__ __launch_bounds__(256) void k_temporal_bwd(TemporalBwdArgs a) {
   extern __shared__ uint4 wlds[];
   stage_weights(wlds, a.Wq, a.Wk, a.Wv);
@@ -97,11 +102,17 @@ __global__ __launch_bounds__(256) void k_temporal_bwd(TemporalBwdArgs a) {
   float sq = 0.f;
   const uint32_t m_head[2] = {(f >> 4) == 0 ? 0xffffffffu : 0u, (f >> 4) == 1 ? 0xffffffffu : 0u};
   const bf16x8 sel0 = sel_frag(0, lane), sel1 = sel_frag(1, lane);
-  bf16x8 selT;     // B operand: element p of lane (j, hh) is 1 where step 8 (p/4) + 4 hh + p%4 == j % 16
+  constexpr int NP = WIDE ? 16 : 8, NH = NP / 8;
+  // B operand: element p of lane (j, hh) is 1 where step 8 (p/4) + 4 hh + p%4 == j % 16 (WIDE: where
+  // step 16 c + ... == j, one operand per half c of the steps)
+  bf16x8 selT[NH];
 #pragma unroll
-  for (int p = 0; p < 8; ++p) selT[p] = (8 * (p >> 2) + 4 * hh + (p & 3) == (lane & 15)) ? (__bf16)1.0f : (__bf16)0.0f;
+  for (int c = 0; c < NH; ++c)
+#pragma unroll
+    for (int p = 0; p < 8; ++p)
+      selT[c][p] = (16 * c + 8 * (p >> 2) + 4 * hh + (p & 3) == (WIDE ? (lane & 31) : (lane & 15))) ? (__bf16)1.0f : (__bf16)0.0f;
   for (int64_t tile = (int64_t)blockIdx.x * nw + wave; tile < a.n_tiles; tile += (int64_t)gridDim.x * nw) {
-    const TileRow r = tile_row(a.chunks, a.n_chunks, a.tile_ptr, tile, a.N, lane);
+    const TileRow r = tile_row<WIDE>(a.chunks, a.n_chunks, a.tile_ptr, tile, a.N, lane);
     const uint32_t m_vert[2] = {r.a == 0 ? 0xffffffffu : 0u, r.a == 1 ? 0xffffffffu : 0u};
     DyRaw raw[2];
     raw[0] = load_dy_raw(a, r.row, 8 * hh, r.valid);
@@ -161,18 +172,18 @@ __global__ __launch_bounds__(256) void k_temporal_bwd(TemporalBwdArgs a) {
         floatx16 st = {}, dpt = {};
         st = mfma3(kh, kl, qh, ql, st);         // [key row][query row]
         dpt = mfma3(vh, vl, dyh, dyl, dpt);
-        float pr[8], dst[8];
+        float pr[NP], dst[NP];
         float mx = -INFINITY;
 #pragma unroll
-        for (int p = 0; p < 8; ++p) {
+        for (int p = 0; p < NP; ++p) {
           const int rk = 8 * (p >> 2) + 4 * hh + (p & 3);
-          pr[p] = rk <= r.s ? 0.25f * pick_half(st, p, m_vert[0], m_vert[1]) : -INFINITY;
+          pr[p] = rk <= r.s ? 0.25f * (WIDE ? st[p] : pick_half(st, p, m_vert[0], m_vert[1])) : -INFINITY;
           mx = fmaxf(mx, pr[p]);
         }
         mx = fmaxf(mx, xor32(mx, hh));
         float sum = 0.f;
 #pragma unroll
-        for (int p = 0; p < 8; ++p) {
+        for (int p = 0; p < NP; ++p) {
           pr[p] = __expf(pr[p] - mx);
           sum += pr[p];
         }
@@ -180,45 +191,57 @@ __global__ __launch_bounds__(256) void k_temporal_bwd(TemporalBwdArgs a) {
         const float inv = 1.f / sum;
         float delta = 0.f;
 #pragma unroll
-        for (int p = 0; p < 8; ++p) {
+        for (int p = 0; p < NP; ++p) {
           pr[p] *= inv;
-          dst[p] = pick_half(dpt, p, m_vert[0], m_vert[1]);
+          dst[p] = WIDE ? dpt[p] : pick_half(dpt, p, m_vert[0], m_vert[1]);
           delta += pr[p] * dst[p];
         }
         delta += xor32(delta, hh);
 #pragma unroll
-        for (int p = 0; p < 8; ++p) dst[p] = 0.25f * pr[p] * (dst[p] - delta);
-        bf16x8 dsth, dstl, prh, prl;
-        split8(dst, dsth, dstl);
-        split8(pr, prh, prl);
+        for (int p = 0; p < NP; ++p) dst[p] = 0.25f * pr[p] * (dst[p] - delta);
+        bf16x8 dsth[NH], dstl[NH], prh[NH], prl[NH];
+#pragma unroll
+        for (int c = 0; c < NH; ++c) {
+          split8(dst + 8 * c, dsth[c], dstl[c]);
+          split8(pr + 8 * c, prh[c], prl[c]);
+        }
         // key-major copies: T[i = query row][j = key row]
         floatx16 t0 = {}, t1 = {}, t2 = {}, t3 = {};
-        t0 = mfma(dsth, selT, t0);
-        t1 = mfma(dstl, selT, t1);
-        t2 = mfma(prh, selT, t2);
-        t3 = mfma(prl, selT, t3);
-        // own-vertex half of the registers, blended arithmetically (a select here gets merged with the
-        // packing below into per-element selects on 16-bit halves)
-        const float fa0 = r.a ? 0.f : 1.f, fa1 = 1.f - fa0;
-        float tx[4][8];
 #pragma unroll
-        for (int p = 0; p < 8; ++p) {
-          tx[0][p] = fa0 * t0[p] + fa1 * t0[8 + p];
-          tx[1][p] = fa0 * t1[p] + fa1 * t1[8 + p];
-          tx[2][p] = fa0 * t2[p] + fa1 * t2[8 + p];
-          tx[3][p] = fa0 * t3[p] + fa1 * t3[8 + p];
+        for (int c = 0; c < NH; ++c) {
+          t0 = mfma(dsth[c], selT[c], t0);
+          t1 = mfma(dstl[c], selT[c], t1);
+          t2 = mfma(prh[c], selT[c], t2);
+          t3 = mfma(prl[c], selT[c], t3);
         }
-        const bf16x8 ds2h = pack8(tx[0]), ds2l = pack8(tx[1]), p2h = pack8(tx[2]), p2l = pack8(tx[3]);
+        // own-vertex half of the registers, blended arithmetically (a select here gets merged with the
+        // packing below into per-element selects on 16-bit halves); WIDE: all 16 are the vertex's own
+        const float fa0 = r.a ? 0.f : 1.f, fa1 = 1.f - fa0;
+        float tx[4][NP];
 #pragma unroll
-        for (int av = 0; av < 2; ++av) {
-          const uint32_t mv = m_vert[av], mh = m_head[hd];
+        for (int p = 0; p < NP; ++p) {
+          tx[0][p] = WIDE ? t0[p] : fa0 * t0[p] + fa1 * t0[8 + (p & 7)];
+          tx[1][p] = WIDE ? t1[p] : fa0 * t1[p] + fa1 * t1[8 + (p & 7)];
+          tx[2][p] = WIDE ? t2[p] : fa0 * t2[p] + fa1 * t2[8 + (p & 7)];
+          tx[3][p] = WIDE ? t3[p] : fa0 * t3[p] + fa1 * t3[8 + (p & 7)];
+        }
+        bf16x8 ds2h[NH], ds2l[NH], p2h[NH], p2l[NH];
+#pragma unroll
+        for (int c = 0; c < NH; ++c) {
+          ds2h[c] = pack8(tx[0] + 8 * c); ds2l[c] = pack8(tx[1] + 8 * c);
+          p2h[c] = pack8(tx[2] + 8 * c); p2l[c] = pack8(tx[3] + 8 * c);
+        }
+#pragma unroll
+        for (int av = 0; av < 2; ++av) {      // the two vertices, or (WIDE) the two halves of the window's steps
+          const uint32_t mv = WIDE ? 0xffffffffu : m_vert[av], mh = m_head[hd];
+          const int c = WIDE ? av : 0;
           bf16x8 ah, al;
           split8v(kt, 8 * av, ah, al);
-          dq = mfma3(and_mask(ah, mh), and_mask(al, mh), and_mask(dsth, mv), and_mask(dstl, mv), dq);
+          dq = mfma3(and_mask(ah, mh), and_mask(al, mh), and_mask(dsth[c], mv), and_mask(dstl[c], mv), dq);
           split8v(qt, 8 * av, ah, al);
-          dk = mfma3(and_mask(ah, mh), and_mask(al, mh), and_mask(ds2h, mv), and_mask(ds2l, mv), dk);
+          dk = mfma3(and_mask(ah, mh), and_mask(al, mh), and_mask(ds2h[c], mv), and_mask(ds2l[c], mv), dk);
           split8v(dyt, 8 * av, ah, al);
-          dv = mfma3(and_mask(ah, mh), and_mask(al, mh), and_mask(p2h, mv), and_mask(p2l, mv), dv);
+          dv = mfma3(and_mask(ah, mh), and_mask(al, mh), and_mask(p2h[c], mv), and_mask(p2l[c], mv), dv);
         }
       }
       if (r.valid) {
@@ -1119,7 +1142,9 @@ void dysat_backward(const DysatWs& ws, const void* Y, int64_t ldy, const void* d
   {
     static bool attr_set = false;   // dynamic LDS above 64 KB has to be allowed once per kernel
     if (!attr_set) {
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_temporal_bwd), hipFuncAttributeMaxDynamicSharedMemorySize,
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_temporal_bwd<false>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds);
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_temporal_bwd<true>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds);
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_temporal_bwd2),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -1142,7 +1167,8 @@ void dysat_backward(const DysatWs& ws, const void* Y, int64_t ldy, const void* d
   ta.scale = 2.0f / (float)count;
   ta.dQ = ws.dQ; ta.dK = ws.dK; ta.dV = ws.dV;
   ta.loss_partial = ws.loss_partial;
-  hipLaunchKernelGGL(k_temporal_bwd, grid_a, 256, lds, st, ta);
+  if (ws.wide) hipLaunchKernelGGL(k_temporal_bwd<true>, grid_a, 256, lds, st, ta);
+  else hipLaunchKernelGGL(k_temporal_bwd<false>, grid_a, 256, lds, st, ta);
   if (target && loss_out)
     hipLaunchKernelGGL(k_reduce_slots, 1, 1024, 0, st, ws.loss_partial, (int64_t)grid_a * 4, (int64_t)1, (int64_t)1,
                        1.0f / (float)count, loss_out);

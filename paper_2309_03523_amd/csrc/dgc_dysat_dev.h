@@ -135,14 +135,17 @@ __device__ __forceinline__ bf16x8 sel_frag(int c, int lane) {
   return s;
 }
 
-// A tile of the temporal kernels: two vertices of one chunk over the chunk's window, 32 rows
-// n = 16 a + s (a = vertex 0/1, s = step).  What a lane needs to know about its row n = lane % 32:
+// A tile of the temporal kernels, 32 rows.  Windows of at most 16 snapshots: two vertices of one
+// chunk over the chunk's window, n = 16 a + s (a = vertex 0/1, s = step).  WIDE (some window of the
+// layer is longer, up to 32): one vertex, n = s.  What a lane needs to know about its row
+// n = lane % 32:
 struct TileRow {
   int64_t row;     // t*N + v (clamped to a valid row when !valid)
   int32_t t, s, a, t_lo;
   bool valid;
 };
 
+template <bool WIDE>
 __device__ __forceinline__ TileRow tile_row(const ChunkInfo* chunks, int32_t n_chunks, const int64_t* tile_ptr,
                                             int64_t tile, int64_t N, int lane) {
   int lo = 0, hi = n_chunks;   // largest k with tile_ptr[k] <= tile
@@ -153,8 +156,8 @@ __device__ __forceinline__ TileRow tile_row(const ChunkInfo* chunks, int32_t n_c
   const ChunkInfo c = chunks[lo];
   const int n = lane & 31;
   TileRow r;
-  r.a = n >> 4; r.s = n & 15; r.t_lo = c.t_lo;
-  const int64_t vl = 2 * (tile - tile_ptr[lo]) + r.a;
+  r.a = WIDE ? 0 : n >> 4; r.s = WIDE ? n : n & 15; r.t_lo = c.t_lo;
+  const int64_t vl = WIDE ? tile - tile_ptr[lo] : 2 * (tile - tile_ptr[lo]) + r.a;
   r.valid = vl < c.nv && r.s < c.w;
   r.t = c.t_lo + (r.s < c.w ? r.s : 0);
   r.row = (int64_t)r.t * N + c.v_lo + (vl < c.nv ? vl : 0);

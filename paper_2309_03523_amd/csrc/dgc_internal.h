@@ -252,7 +252,8 @@ struct DysatWs {
   const Segment* segs; int64_t nseg;
   const ChunkInfo* chunks;
   const int32_t* work_short; int64_t n_short;   // row groups of the segments (segment, first row, rows)
-  const int64_t* tile_ptr; int64_t n_tiles;     // 2-vertex tiles of the temporal kernels, per chunk
+  const int64_t* tile_ptr; int64_t n_tiles;     // tiles of the temporal kernels, per chunk: 2 vertices each, 1 if wide
+  bool wide;                                    // some chunk's window is longer than 16 snapshots (at most 32)
   const int32_t* owner;                         // [T*N] covering chunk or -1
   const int32_t* used_t; int32_t n_used;        // snapshots some chunk covers
   int64_t total_rows;

@@ -28,6 +28,10 @@ CASES = {
     "single": dict(T=3, N=40, deg=3.0, chunks=[[5, 6, 0, 3], [6, 40, 1, 2]]),
     # rows longer than 24 non-zeros (the hub, and more at degree 9) are split into parts of 8
     "split": dict(T=6, N=150, deg=9.0, chunks=[[0, 70, 0, 6], [70, 150, 0, 4]], kw=dict(long_nnz=24, part_nnz=8)),
+    # windows longer than 16 snapshots: one vertex per 32-row tile
+    "wide32": dict(T=32, N=67, deg=4.0, chunks=[[0, 33, 0, 32], [33, 67, 0, 32]]),
+    "wide17": dict(T=17, N=35, deg=3.0, chunks=[[0, 35, 0, 17]]),
+    "wide_mixed": dict(T=24, N=90, deg=5.0, chunks=[[0, 40, 0, 24], [40, 90, 0, 9], [40, 90, 9, 24]]),
 }
 
 
@@ -155,13 +159,13 @@ def test_attention_argument_errors():
         dd.layer.forward(dd.X, dd.C, dd.Y, H0=torch.zeros(40, 128, device="cuda"))
     assert ei.value.code == 1
     dd.layer.destroy()
-    wl2 = synth.dysat_small(4, 20, 40, 128, 8, 3.0, [[0, 40, 0, 20]])
-    with pytest.raises(DgcError) as ei:      # window longer than 16 snapshots
+    wl2 = synth.dysat_small(4, 33, 40, 128, 8, 3.0, [[0, 40, 0, 33]])
+    with pytest.raises(DgcError) as ei:      # window longer than 32 snapshots
         DysatDevice(wl2)
     assert ei.value.code == 4
 
 
-@pytest.mark.parametrize("case", ["ragged", "split", "single"])
+@pytest.mark.parametrize("case", ["ragged", "split", "single", "wide_mixed"])
 def test_input_gradient_parity(case):
     """dL/dX of the covered rows (bf16) against the oracle; rows no chunk covers are not written;
     asking for it does not change the parameter gradients."""
