@@ -18,6 +18,18 @@ out for label[t, i] (any integers):
     given; for the LSTM the cell rows follow all hidden rows).
   * states that leave a chunk: HN[t, i] = state after step t wherever the next step belongs to
     another chunk (t = T-1 or label[t+1, i] != label[t, i]); other rows of HN are NaN.
+
+Temporal fusion on top (Section 5.1.2 together with Section 4.1; `present[t, i]`): a vertex that
+does not exist in a snapshot has no instance in the super-graph, so its label there means
+nothing.  The temporal neighbour of an instance (t, i) is the vertex's previous PRESENT instance
+(t', i); the state is carried from t' to t (over the gap) if the two carry the same label and is
+taken from the stale copy Hc[t, i] otherwise or if there is no earlier instance.  A vertex's
+sequences are thus its maximal runs of present instances with one label; nothing is computed or
+written for an absent row (its rows of Y stay NaN); an absent vertex still counts as a spatial
+neighbour where the adjacency stores the edge.  HN[t, i] = state after the last instance of a
+sequence.  Packing rule for the lanes (this build's own, the rule of the rectangular case with
+one more key): all sequences ordered by (length descending, vertex ascending, first snapshot
+ascending) go first-fit into lanes of T slots.
 """
 from __future__ import annotations
 
@@ -48,13 +60,64 @@ def aggregate(graph, labels: np.ndarray, fresh: np.ndarray, stale: np.ndarray) -
     return out
 
 
+def sequences(labels, present) -> list:
+    """(vertex, [snapshots]) for every maximal run of present instances of a vertex that carry one
+    label, ordered by vertex, then first snapshot."""
+    labels = np.asarray(labels)
+    T, N = labels.shape
+    out = []
+    for i in range(N):
+        ts = []
+        for t in range(T):
+            if not present[t, i]:
+                continue
+            if ts and labels[ts[-1], i] != labels[t, i]:
+                out.append((i, ts))
+                ts = []
+            ts.append(t)
+        if ts:
+            out.append((i, ts))
+    return out
+
+
+def pack(labels, present) -> dict:
+    """Lanes of T slots by the packing rule.  Returns n_lanes, slot_row int64 [T, n_lanes] (t*N + i of
+    the instance in that slot, -1 = empty) and slot_reset uint8 [T, n_lanes] (1 on the first slot
+    of every sequence)."""
+    labels = np.asarray(labels)
+    T, N = labels.shape
+    lanes = []          # [free slots, [sequences]]
+    for i, ts in sorted(sequences(labels, present), key=lambda s: (-len(s[1]), s[0], s[1][0])):
+        for lane in lanes:
+            if lane[0] >= len(ts):
+                lane[0] -= len(ts)
+                lane[1].append((i, ts))
+                break
+        else:
+            lanes.append([T - len(ts), [(i, ts)]])
+    slot_row = np.full((T, len(lanes)), -1, np.int64)
+    slot_reset = np.zeros((T, len(lanes)), np.uint8)
+    for lane, (_, seqs) in enumerate(lanes):
+        s = 0
+        for i, ts in seqs:
+            slot_reset[s, lane] = 1
+            for t in ts:
+                slot_row[s, lane] = t * N + i
+                s += 1
+    return {"n_lanes": len(lanes), "slot_row": slot_row, "slot_reset": slot_reset}
+
+
 def forward(graph, labels, params: dict, X, C, *, time_kind: str = "gru", n_struct_layers: int = 1,
-            C1=None, Hc=None, act_hidden: str = "relu", act_out: str = "none", vertices=None):
+            C1=None, Hc=None, act_hidden: str = "relu", act_out: str = "none", vertices=None, present=None):
     """Returns Y [T,N,out] float64 and HN [n_state*T*N, H] (NaN where no state leaves a chunk;
     None without a time encoder).  vertices (one structure layer only): evaluate just these
-    vertices, all snapshots; Y is then [T, len(vertices), out] and HN is not returned."""
+    vertices, all snapshots; Y is then [T, len(vertices), out] and HN is not returned.
+    present [T,N] (needs a time encoder): rows of absent instances are NaN in Y."""
     labels = np.asarray(labels).reshape(graph.T, graph.N)
     T, N = labels.shape
+    if present is not None:
+        assert time_kind != "none"
+        present = np.asarray(present).reshape(T, N).astype(bool)
     P = {k: np.asarray(v, np.float64) for k, v in params.items()}
     idx = list(range(N)) if vertices is None else [int(v) for v in vertices]
 
@@ -83,10 +146,13 @@ def forward(graph, labels, params: dict, X, C, *, time_kind: str = "gru", n_stru
     V = T * N
     Y = np.zeros((T, len(idx), H))
     HN = np.full(((2 if lstm else 1) * V, H), np.nan) if vertices is None else None
+    if present is not None:
+        Y[:] = np.nan
     for k, i in enumerate(idx):
         h = c = None
-        for t in range(T):
-            if t == 0 or labels[t - 1, i] != labels[t, i]:      # the temporal neighbour is in another chunk
+        ts = [t for t in range(T) if present is None or present[t, i]]      # the vertex's instances
+        for n, t in enumerate(ts):
+            if n == 0 or labels[ts[n - 1], i] != labels[t, i]:      # the temporal neighbour is in another chunk
                 h = np.zeros((1, H)) if Hc is None else np.asarray(Hc[t * N + i], np.float64)[None]
                 c = np.zeros((1, H)) if (Hc is None or not lstm) else np.asarray(Hc[V + t * N + i], np.float64)[None]
             if lstm:
@@ -94,7 +160,7 @@ def forward(graph, labels, params: dict, X, C, *, time_kind: str = "gru", n_stru
             else:
                 h = gru_step(P, Z[t, k][None], h)
             Y[t, k] = h[0]
-            if HN is not None and (t == T - 1 or labels[t + 1, i] != labels[t, i]):
+            if HN is not None and (n == len(ts) - 1 or labels[ts[n + 1], i] != labels[t, i]):
                 HN[t * N + i] = h[0]
                 if lstm:
                     HN[V + t * N + i] = c[0]

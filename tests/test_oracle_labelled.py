@@ -122,3 +122,126 @@ def test_vertex_subset_equals_full():
     sub, hn = labelled.forward(wl.graph, lab, wl.params, wl.X, wl.C, time_kind="gru", Hc=Hc, vertices=[3, 17, 30])
     assert hn is None
     np.testing.assert_array_equal(sub, full[:, [3, 17, 30]])
+
+
+# ---- temporal fusion on top of generated chunks (presence) ------------------------------------
+
+def test_presence_all_ones_changes_nothing():
+    wl = synth.random_small(16, T, N, F, S, S, 3.0, [[0, N, 0, T]], "lstm", n_struct_layers=2)
+    rng = np.random.default_rng(3)
+    lab = rng.integers(0, 3, (T, N))
+    Hc = rng.standard_normal((2 * T * N, S))
+    a, hn_a = labelled.forward(wl.graph, lab, wl.params, wl.X, wl.C, time_kind="lstm", n_struct_layers=2, C1=wl.C1, Hc=Hc)
+    b, hn_b = labelled.forward(wl.graph, lab, wl.params, wl.X, wl.C, time_kind="lstm", n_struct_layers=2, C1=wl.C1, Hc=Hc,
+                               present=np.ones((T, N), np.uint8))
+    np.testing.assert_array_equal(a, b)
+    np.testing.assert_array_equal(hn_a, hn_b)
+
+
+@pytest.mark.parametrize("kind", ["gru", "lstm"])
+def test_presence_with_one_label_is_temporal_fusion_of_one_chunk(kind):
+    """One chunk covering everything: the sequences, the lanes and the outputs are those of the
+    temporal-fusion oracle for the rectangle [0,N) x [0,T) (pinned by the paper's drawn example and
+    the library recurrences), with the state rows re-indexed: a sequence starts from the cache row of
+    its first instance and leaves its state in the row of its last one."""
+    from oracle import tfusion
+    wl = synth.random_small(17, T, N, F, S, S, 3.0, [[0, N, 0, T]], kind)
+    present = synth.presence(4, T, N)
+    lab = np.full((T, N), 5)
+    rect = [[0, N, 0, T]]
+    n_state = 2 if kind == "lstm" else 1
+    H0 = 0.3 * np.random.default_rng(6).standard_normal((n_state * N, S))
+    V = T * N
+    Hc = np.full((n_state * V, S), np.nan)
+    first = {i: int(np.flatnonzero(present[:, i])[0]) for i in range(N) if present[:, i].any()}
+    last = {i: int(np.flatnonzero(present[:, i])[-1]) for i in first}
+    for i, t in first.items():
+        for part in range(n_state):
+            Hc[part * V + t * N + i] = H0[part * N + i]
+    Y, HN = labelled.forward(wl.graph, lab, wl.params, wl.X, wl.C, time_kind=kind, Hc=Hc, present=present)
+    Z, _ = labelled.forward(wl.graph, lab, wl.params, wl.X, wl.C, time_kind="none")
+    want, want_HN = tfusion.run_separate(Z, present, rect, wl.params, kind, H0=H0, return_state=True)
+    assert np.array_equal(np.isnan(Y), np.isnan(want))
+    assert np.nanmax(np.abs(Y - want)) < 1e-12
+    seen = np.zeros(HN.shape[0], bool)
+    for i, t in last.items():
+        for part in range(n_state):
+            assert np.abs(HN[part * V + t * N + i] - want_HN[part * N + i]).max() < 1e-12
+            seen[part * V + t * N + i] = True
+    assert np.isnan(HN[~seen]).all()
+    p, q = labelled.pack(lab, present), tfusion.pack(present, rect)
+    np.testing.assert_array_equal(p["slot_row"], q["slot_row"])
+    np.testing.assert_array_equal(p["slot_reset"], q["slot_reset"])
+
+
+def test_presence_sequences_against_the_library_recurrence():
+    """Random labels and presence: every run of present instances with one label, compressed and run
+    through torch.nn.GRU from its cache row, gives the oracle's rows; the label of an absent
+    instance plays no part (scrambling those labels changes nothing)."""
+    import torch
+    wl = synth.random_small(18, 7, 23, F, S, S, 3.0, [[0, 23, 0, 7]], "gru")
+    Tn, Nn = 7, 23
+    rng = np.random.default_rng(8)
+    lab = rng.integers(0, 2, (Tn, Nn))
+    present = synth.presence(9, Tn, Nn)
+    Hc = rng.standard_normal((Tn * Nn, S))
+    Y, HN = labelled.forward(wl.graph, lab, wl.params, wl.X, wl.C, time_kind="gru", Hc=Hc, present=present)
+    lab2 = np.where(present.astype(bool), lab, rng.integers(5, 9, (Tn, Nn)))
+    Y2, HN2 = labelled.forward(wl.graph, lab2, wl.params, wl.X, wl.C, time_kind="gru", Hc=Hc, present=present)
+    # spatial neighbours that are absent keep their real label's role: compare only the time encoder's part,
+    # i.e. feed both from the same structure output
+    Z, _ = labelled.forward(wl.graph, lab, wl.params, wl.X, wl.C, time_kind="none")
+    gru = torch.nn.GRU(S, S, batch_first=True).double()
+    with torch.no_grad():
+        gru.weight_ih_l0.copy_(torch.from_numpy(wl.params["rnn.weight_ih"].astype(np.float64)))
+        gru.weight_hh_l0.copy_(torch.from_numpy(wl.params["rnn.weight_hh"].astype(np.float64)))
+        gru.bias_ih_l0.copy_(torch.from_numpy(wl.params["rnn.bias_ih"].astype(np.float64)))
+        gru.bias_hh_l0.copy_(torch.from_numpy(wl.params["rnn.bias_hh"].astype(np.float64)))
+    seqs = labelled.sequences(lab, present)
+    assert sum(len(ts) for _, ts in seqs) == int(present.sum())
+    n_multi = 0
+    for i, ts in seqs:
+        assert all(present[t, i] for t in ts) and len({int(lab[t, i]) for t in ts}) == 1
+        n_multi += len(ts) > 1 and ts[-1] - ts[0] + 1 > len(ts)          # a sequence with a gap inside
+        x = torch.from_numpy(Z[ts, i][None])
+        h0 = torch.from_numpy(Hc[ts[0] * Nn + i][None, None])
+        with torch.no_grad():
+            out, hn = gru(x, h0)
+        assert np.abs(out[0].numpy() - Y[ts, i]).max() < 1e-12
+        assert np.abs(hn[0, 0].numpy() - HN[ts[-1] * Nn + i]).max() < 1e-12
+    assert n_multi > 0
+    assert np.isnan(Y[~present.astype(bool)]).all()
+    assert int((~np.isnan(HN[:, 0])).sum()) == len(seqs)
+    # labels of absent instances do not matter for where sequences start and end
+    assert [(i, ts) for i, ts in labelled.sequences(lab2, present)] == seqs
+    assert np.array_equal(np.isnan(HN2), np.isnan(HN))
+
+
+def test_presence_packing_hand_example_and_properties():
+    """T = 4, three vertices.  Vertex 0: present 1111, labels aabb -> sequences [0,1], [2,3];
+    vertex 1: present 1011, labels aaab -> [0,2] (gap carried), [3]; vertex 2: present 0100 -> [1].
+    Order (length desc, vertex, first snapshot): (0,[0,1]) (0,[2,3]) (1,[0,2]) (1,[3]) (2,[1]);
+    first fit into lanes of 4: lane 0 = (0,[0,1]) + (0,[2,3]); lane 1 = (1,[0,2]) + (1,[3]) + (2,[1])."""
+    lab = np.array([[0, 0, 0], [0, 0, 0], [1, 0, 0], [1, 1, 0]])
+    present = np.array([[1, 1, 0], [1, 0, 1], [1, 1, 0], [1, 1, 0]], np.uint8)
+    p = labelled.pack(lab, present)
+    assert p["n_lanes"] == 2
+    np.testing.assert_array_equal(p["slot_row"], np.array([[0, 1], [3, 7], [6, 10], [9, 5]]))
+    np.testing.assert_array_equal(p["slot_reset"], np.array([[1, 1], [0, 0], [1, 1], [0, 1]]))
+    rng = np.random.default_rng(12)
+    Tn, Nn = 9, 40
+    lab = rng.integers(0, 3, (Tn, Nn))
+    present = synth.presence(13, Tn, Nn)
+    p = labelled.pack(lab, present)
+    rows = p["slot_row"][p["slot_row"] >= 0]
+    assert sorted(rows.tolist()) == sorted(np.flatnonzero(present.reshape(-1)).tolist())     # every instance once
+    assert -(-int(present.sum()) // Tn) <= p["n_lanes"] <= len(labelled.sequences(lab, present))
+    for lane in range(p["n_lanes"]):
+        col, rst = p["slot_row"][:, lane], p["slot_reset"][:, lane]
+        n = int((col >= 0).sum())
+        assert (col[:n] >= 0).all() and rst[0] == 1 and (rst[n:] == 0).all()
+        for s in range(1, n):
+            same = col[s] % Nn == col[s - 1] % Nn and col[s] > col[s - 1] and \
+                lab.reshape(-1)[col[s]] == lab.reshape(-1)[col[s - 1]] and \
+                not present[col[s - 1] // Nn + 1: col[s] // Nn, col[s] % Nn].any()
+            assert bool(rst[s]) == (not same)
