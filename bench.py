@@ -35,6 +35,8 @@ def parse_args():
     ap.add_argument("--mpnn-lstm", action="store_true",
                     help="config3: the paper's MPNN-LSTM in full (Section 6): the LSTM reads both GCN layers' outputs and "
                          "a second LSTM layer is stacked on the first")
+    ap.add_argument("--presence", action="store_true",
+                    help="config2lp: also set config2tf's presence matrix (temporal fusion over the generated chunks)")
     ap.add_argument("--no-configs", action="store_true",
                     help="config2 (the default): do not also run configs 1, 3, 4 and 5 for the line's `configs` object")
     ap.add_argument("--config-steps", type=int, default=5, help="timed steps of each extra configuration")
@@ -686,6 +688,16 @@ def labelled_main(args):
     t0 = time.perf_counter()
     layer.set_labels(labels)
     t_tables = time.perf_counter() - t0
+    present = None
+    t_lanes = 0.0
+    if getattr(args, "presence", False):
+        present = synth.presence(args.seed, T, N)
+        p_dev = torch.from_numpy(present).cuda()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        layer.set_presence(p_dev)
+        t_lanes = time.perf_counter() - t0
+        dw.Y.fill_(float("nan"))
     Hc = torch.from_numpy(Hc_host).cuda()
     HN = torch.full((T * N, wl.H), float("nan"), dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
@@ -712,7 +724,7 @@ def labelled_main(args):
         stage += layer.stage_times()
     stage /= 3
     layer.set_profiling(False)
-    rows = T * N
+    rows = T * N if present is None else int(present.sum())
     ms = 1e3 * elapsed / args.steps
     # what the partition costs: neighbours and temporal neighbours read from the caches
     lab = labels.cpu().numpy().reshape(T, N)
@@ -731,16 +743,24 @@ def labelled_main(args):
     sizes = np.bincount(lab.reshape(-1))
     sizes = sizes[sizes > 0]
     fl = flops_per_row(wl)
-    dense_flops = (fl["transform"] + fl["rnn"]) * rows
+    n_lanes = int(layer.packing("lane_ptr")[-1]) if present is not None else 0
+    dense_rows = rows if present is None else n_lanes * T           # the kernel computes every lane slot
+    dense_flops = (fl["transform"] + fl["rnn"]) * dense_rows
     dense_ms, agg_ms = float(stage[3]), float(stage[0])
     achieved = dense_flops / (dense_ms * 1e-3) / 1e12
+    if present is not None:
+        deg = [np.diff(sn.rowptr) for sn in g.snaps]
+        nnz = int(sum(int(d[present[t].astype(bool)].sum()) for t, d in enumerate(deg)))     # non-zeros of the rows computed
     agg_bytes = rows * (wl.F * 4) + nnz * 4 + rows * 8 + rows * (wl.F * 4)
-    traffic = measured_traffic("config2lp", "in_place")
+    traffic = measured_traffic("config2lp", "in_place") if present is None else {}
     out = {"metric": "snapshot-vertex embeddings/s per DGNN layer", "value": rows * args.steps / elapsed, "unit": "embeddings/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": "config2 (32 snapshots x 100k vertices, F=S=H=128, GCN+GRU) over chunks generated by the "
-                                  f"device label propagation (w_spatial = {w_s}, w_temporal = {w_t}, size limit {cap})",
+                                  f"device label propagation (w_spatial = {w_s}, w_temporal = {w_t}, size limit {cap})" +
+                                  ("" if present is None else
+                                   f" with config2tf's presence matrix: temporal fusion over the generated chunks, {n_lanes} lanes of {T} "
+                                   f"slots for {rows} present rows ({rows / max(1, n_lanes * T):.1%} of the slots filled); value counts present rows"),
                       "rows": rows, "nnz": nnz, "gather_mode": "in_place", "pass": "forward"},
            "roofline": {"kernel": "k_dense_wave<GRU, SEQ> (GCN transform + time encoder over every vertex's label runs)",
                         "bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
@@ -759,7 +779,7 @@ def labelled_main(args):
                       "stale_state_reads": st_, "stale_state_fraction": st_ / rows,
                       "rectangular_64_chunks": {"stale_neighbour_fraction": re_ / nnz, "stale_state_fraction": rt / rows}},
            "setup_s": {"generate": t_gen, "upload_create_pack": t_create, "label_propagation": t_labels,
-                       "label_tables": t_tables}}
+                       "label_tables": t_tables, "lanes": t_lanes}}
     if not args.no_cpu_baseline:
         from oracle import labelled
         rng = synth.stream(args.seed, "bench-sample")
@@ -768,10 +788,16 @@ def labelled_main(args):
         while dt < 12.0 and done < 4096:      # growing seeded samples of vertices, all 32 snapshots each
             vs = np.sort(rng.choice(N, size=n_v, replace=False))
             t0 = time.perf_counter()
-            want, _ = labelled.forward(g, lab, wl.params, wl.X, wl.C, time_kind=wl.time_kind, Hc=Hc_host, vertices=vs)
+            want, _ = labelled.forward(g, lab, wl.params, wl.X, wl.C, time_kind=wl.time_kind, Hc=Hc_host, vertices=vs,
+                                       present=present)
             dt += time.perf_counter() - t0
             done += n_v
-            pars.append(parity_numbers(Y_gpu[:, vs], want))
+            got = Y_gpu[:, vs]
+            if present is not None:
+                here = present[:, vs].astype(bool)
+                assert np.array_equal(np.isnan(got).any(-1), ~here) and np.array_equal(np.isnan(want).any(-1), ~here)
+                got, want = got[here], want[here]
+            pars.append(parity_numbers(got, want))
             errs.append(pars[-1]["floor_1e-1_rms"])
             n_v = min(2 * n_v, 1024)
         out["cpu_baseline"] = {"value": done * T / dt, "unit": "embeddings/s", "cores": 1, "kind": "oracle",

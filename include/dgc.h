@@ -211,7 +211,15 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* layer, const void* X, int64_t ldx, c
  * (HN row = H0 row), so chained windows equal one long window.  reset_mask must be NULL
  * (DGC_ERR_INVALID_ARG).  For DGC_STRUCT_GCN with DGC_TIME_GRU / DGC_TIME_LSTM; can be called
  * once per layer (DGC_ERR_STATE otherwise); `present` is only read during the call.
- * Synchronises `stream`. */
+ * Synchronises `stream`.
+ * On a layer that has labels (dgc_layer_set_labels before this call; Sections 5.1.2 and 4.1
+ * together) the sequences are a vertex's maximal runs of PRESENT instances that carry one label
+ * (the label of an absent instance plays no part; the state is carried over the gaps inside a
+ * run); all sequences, ordered by (length descending, vertex ascending, first snapshot ascending),
+ * go first-fit into lanes of T slots.  H0 / HN keep the labelled layer's layout [n_state * T*N, H]:
+ * a sequence starts from row t*N + i of its first instance (zero if H0 is NULL) and HN's row of
+ * its last instance receives its final state; other rows are not written.  The labels cannot be
+ * set again afterwards (DGC_ERR_STATE). */
 dgc_status_t dgc_layer_set_presence(dgc_layer_t* layer, const uint8_t* present, void* stream);
 
 /* Generated chunks as the layer's input (Sections 4.1 and 5.2): labels device int32 [T*N], any
@@ -227,8 +235,9 @@ dgc_status_t dgc_layer_set_presence(dgc_layer_t* layer, const uint8_t* present, 
  *   HN (optional, same shape): row t*N + i receives the state after step t wherever the next step
  *     belongs to another chunk (t = T-1 or labels[t+1,i] != labels[t,i]); other rows are not written.
  * reset_mask must be NULL.  May be called again with other labels; `labels` is only read during
- * the call.  Not combined with dgc_layer_set_presence (DGC_ERR_STATE).  The packing arrays and
- * dgc_layer_shared_rows keep describing the single rectangular chunk.  Synchronises `stream`. */
+ * the call, until dgc_layer_set_presence has been called on the layer (then DGC_ERR_STATE: labels
+ * come first).  The packing arrays of the chunk-fusion packing and dgc_layer_shared_rows keep
+ * describing the single rectangular chunk.  Synchronises `stream`. */
 dgc_status_t dgc_layer_set_labels(dgc_layer_t* layer, const int32_t* labels, void* stream);
 
 /* Backward pass: gradients of a scalar loss with respect to the layer's parameters, for the

@@ -676,6 +676,101 @@ void run_aggregate(dgc_layer* L, const float* fresh, int64_t ld_fresh, const flo
   launch_spmm(a, st);
 }
 
+// First-fit over lanes of `cap` slots: sequences come in packing order with their lengths; returns the
+// number of lanes and fills lane / first slot of each.  by_free[f] = lanes with f free slots.
+int32_t first_fit_lanes(const std::vector<int32_t>& lens, int32_t cap, std::vector<int32_t>* lane, std::vector<int32_t>* off) {
+  std::vector<std::set<int32_t>> by_free(cap + 1);
+  int32_t n_l = 0;
+  lane->resize(lens.size()); off->resize(lens.size());
+  for (size_t q = 0; q < lens.size(); ++q) {
+    const int32_t n = lens[q];
+    int32_t best = -1, bf = 0;
+    for (int32_t f = n; f <= cap; ++f)
+      if (!by_free[f].empty() && (best < 0 || *by_free[f].begin() < best)) { best = *by_free[f].begin(); bf = f; }
+    if (best < 0) { best = n_l++; bf = cap; } else by_free[bf].erase(by_free[bf].begin());
+    (*lane)[q] = best;
+    (*off)[q] = cap - bf;
+    by_free[bf - n].insert(best);
+  }
+  return n_l;
+}
+
+// Temporal fusion over generated chunks (the layer has labels): sequences are a vertex's runs of
+// present instances with one label; all of them, ordered by (length descending, vertex ascending,
+// first snapshot ascending), go first-fit into lanes of T slots.  The states keep the layout of the
+// labelled layer: one row per (t, i), entering at a sequence's first instance, leaving at its last.
+dgc_status_t set_presence_labelled(dgc_layer* L, const uint8_t* present, hipStream_t st) {
+  Failer fail{L};
+  TFusion& tf = L->tf;
+  const int32_t T = L->T;
+  const int64_t N = L->N, TN = (int64_t)T * N;
+  int32_t *d_len = nullptr, *d_first = nullptr, *d_pos = nullptr;
+  uint8_t* d_last = nullptr;
+  DGC_HIP_TRY(dev_alloc(L, &d_len, TN));
+  DGC_HIP_TRY(dev_alloc(L, &d_first, TN));
+  DGC_HIP_TRY(dev_alloc(L, &d_pos, TN));
+  DGC_HIP_TRY(dev_alloc(L, &d_last, TN));
+  lp_sequences(present, L->lab.labels, T, N, d_len, d_first, d_pos, d_last, st);
+  std::vector<int32_t> len(TN);
+  DGC_HIP_TRY(hipMemcpyAsync(len.data(), d_len, sizeof(int32_t) * len.size(), hipMemcpyDeviceToHost, st));
+  DGC_HIP_TRY(hipStreamSynchronize(st));
+  // packing order by a counting sort on the length; within a length by vertex, then first snapshot
+  std::vector<int64_t> count(T + 2, 0);
+  for (int64_t x = 0; x < TN; ++x) count[len[x]]++;
+  int64_t n_seq = TN - count[0];
+  std::vector<int64_t> begin(T + 2, 0);     // sequences of length l start at begin[l]; longest first
+  for (int32_t l = T - 1; l >= 1; --l) begin[l] = begin[l + 1] + count[l + 1];
+  std::vector<int64_t> start_of(n_seq);
+  std::vector<int32_t> lens(n_seq);
+  for (int64_t i = 0; i < N; ++i)
+    for (int32_t t = 0; t < T; ++t) {
+      const int64_t x = (int64_t)t * N + i;
+      if (len[x] > 0) { const int64_t q = begin[len[x]]++; start_of[q] = x; lens[q] = len[x]; }
+    }
+  std::vector<int32_t> lane_q, off_q;
+  const int32_t n_l = first_fit_lanes(lens, T, &lane_q, &off_q);
+  std::vector<int32_t> lane_of(TN, -1), off_of(TN, 0);
+  for (int64_t q = 0; q < n_seq; ++q) { lane_of[start_of[q]] = lane_q[q]; off_of[start_of[q]] = off_q[q]; }
+  tf.n_lanes = n_l; tf.Lmax = T; tf.rows_v = (int64_t)n_l * T;
+  const int64_t n_slots = (int64_t)T * n_l;
+  const std::vector<int64_t> lane_ptr = {0, n_l};
+  const ChunkInfo cv{0, n_l, 0, 0, 0, T};
+  int32_t *d_lane = nullptr, *d_off = nullptr;
+  DGC_HIP_TRY(dev_alloc(L, &d_lane, TN));
+  DGC_HIP_TRY(dev_alloc(L, &d_off, TN));
+  DGC_HIP_TRY(dev_alloc(L, &tf.lane_ptr, 2));
+  DGC_HIP_TRY(dev_alloc(L, &tf.slot_row, n_slots));
+  DGC_HIP_TRY(dev_alloc(L, &tf.slot_reset, n_slots));
+  DGC_HIP_TRY(dev_alloc(L, &tf.seq_in, n_slots));
+  DGC_HIP_TRY(dev_alloc(L, &tf.seq_out, n_slots));
+  DGC_HIP_TRY(dev_alloc(L, &tf.row_map, TN));
+  DGC_HIP_TRY(dev_alloc(L, &tf.chunks_v, 1));
+  DGC_HIP_TRY(hipMemcpyAsync(d_lane, lane_of.data(), sizeof(int32_t) * lane_of.size(), hipMemcpyHostToDevice, st));
+  DGC_HIP_TRY(hipMemcpyAsync(d_off, off_of.data(), sizeof(int32_t) * off_of.size(), hipMemcpyHostToDevice, st));
+  DGC_HIP_TRY(hipMemcpyAsync(tf.lane_ptr, lane_ptr.data(), sizeof(int64_t) * 2, hipMemcpyHostToDevice, st));
+  DGC_HIP_TRY(hipMemcpyAsync(tf.chunks_v, &cv, sizeof(ChunkInfo), hipMemcpyHostToDevice, st));
+  lp_fill(present, d_first, d_pos, d_last, d_lane, d_off, T, N, n_l, tf.slot_row, tf.row_map, tf.slot_reset, tf.seq_in,
+          tf.seq_out, st);
+  std::vector<DenseTile> t64, t32;
+  for (int64_t v0 = 0; v0 < n_l; v0 += kTileRows)
+    t64.push_back(DenseTile{0, (int32_t)v0, (int32_t)std::min<int64_t>(kTileRows, n_l - v0), 0});
+  for (int64_t v0 = 0; v0 < n_l; v0 += kWaveTileRows)
+    t32.push_back(DenseTile{0, (int32_t)v0, (int32_t)std::min<int64_t>(kWaveTileRows, n_l - v0), 0});
+  tf.n_tiles_v = (int64_t)t64.size(); tf.n_tiles32_v = (int64_t)t32.size();
+  DGC_HIP_TRY(dev_alloc(L, &tf.tiles_v, tf.n_tiles_v));
+  DGC_HIP_TRY(dev_alloc(L, &tf.tiles32_v, tf.n_tiles32_v));
+  DGC_HIP_TRY(hipMemcpyAsync(tf.tiles_v, t64.data(), sizeof(DenseTile) * t64.size(), hipMemcpyHostToDevice, st));
+  DGC_HIP_TRY(hipMemcpyAsync(tf.tiles32_v, t32.data(), sizeof(DenseTile) * t32.size(), hipMemcpyHostToDevice, st));
+  DGC_HIP_TRY(dev_alloc(L, &tf.Mv, tf.rows_v * L->ldm));
+  DGC_HIP_TRY(hipMemsetAsync(tf.Mv, 0, sizeof(float) * (size_t)std::max<int64_t>(tf.rows_v * L->ldm, 1), st));  // empty slots stay zero
+  DGC_HIP_TRY(hipStreamSynchronize(st));
+  DGC_HIP_TRY(hipGetLastError());
+  dev_free(L, d_len); dev_free(L, d_first); dev_free(L, d_pos); dev_free(L, d_last); dev_free(L, d_lane); dev_free(L, d_off);
+  tf.built = true;
+  L->forward_done = false;
+  return DGC_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -925,9 +1020,11 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* L, const void* Xv, int64_t ldx, cons
     // every sequence starts from its own row of H0 (zero without H0) and leaves its final state in its
     // row of HN: the states travel through the slot tables; H0 / HN keep the layout they have without fusion
     da.reset_mask = nullptr; da.seq_in = tf.seq_in; da.seq_out = tf.seq_out;
-    da.total_state_rows = L->total_state_rows;
+    // (over generated chunks the states are the labelled layer's: one row per (t, i), only the rows
+    // where a sequence starts are read and only those where one ends are written)
+    da.total_state_rows = L->lab.built ? (int64_t)L->T * L->N : L->total_state_rows;
     da.x2_map = tf.slot_row;      // a slot's row of the first layer's output
-    if (HN) tf_carry(tf.seq_len, L->total_state_rows, d.time_kind == DGC_TIME_LSTM ? 2 : 1, d.H, H0, HN, st);
+    if (HN && !L->lab.built) tf_carry(tf.seq_len, L->total_state_rows, d.time_kind == DGC_TIME_LSTM ? 2 : 1, d.H, H0, HN, st);
     if (tf.n_lanes > 0 && !launch_dense(da, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
   } else if (!launch_dense(da, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
   if (d.n_time_layers == 2) {
@@ -1125,7 +1222,7 @@ dgc_status_t dgc_layer_set_presence(dgc_layer_t* L, const uint8_t* present, void
   if (L->tf.built) return fail(DGC_ERR_STATE, "the presence mask of a layer can be set once");
   if (d.n_time_layers == 2) return fail(DGC_ERR_UNSUPPORTED, "temporal fusion is not built for a stacked time encoder");
   if ((int64_t)L->T * L->N >= INT32_MAX) return fail(DGC_ERR_UNSUPPORTED, "temporal fusion needs T*N < 2^31");
-  if (L->lab.built) return fail(DGC_ERR_STATE, "temporal fusion is not built for generated chunks");
+  if (L->lab.built) return set_presence_labelled(L, present, st);
   if (L->n_chunks > kMaxGridYZ)  // its kernels take one grid row per chunk
     return fail(DGC_ERR_UNSUPPORTED, "temporal fusion: more than 65535 chunks");
   TFusion& tf = L->tf;
@@ -1220,7 +1317,7 @@ dgc_status_t dgc_layer_set_labels(dgc_layer_t* L, const int32_t* labels, void* s
   if (d.struct_kind != DGC_STRUCT_GCN) return fail(DGC_ERR_UNSUPPORTED, "generated chunks are built for GCN layers");
   if (d.gather_mode != DGC_GATHER_IN_PLACE)
     return fail(DGC_ERR_UNSUPPORTED, "generated chunks need gather_mode DGC_GATHER_IN_PLACE");
-  if (L->tf.built) return fail(DGC_ERR_STATE, "temporal fusion is not built for generated chunks");
+  if (L->tf.built) return fail(DGC_ERR_STATE, "the labels of a layer are set before its presence mask, and not again after it");
   if (d.n_time_layers == 2) return fail(DGC_ERR_UNSUPPORTED, "generated chunks are not built for a stacked time encoder");
   const dgc_chunk_t& c = L->chunks[0];
   if (L->n_chunks != 1 || c.v_lo != 0 || c.v_hi != L->N || c.t_lo != 0 || c.t_hi != L->T)
@@ -1232,7 +1329,9 @@ dgc_status_t dgc_layer_set_labels(dgc_layer_t* L, const int32_t* labels, void* s
     DGC_HIP_TRY(dev_alloc(L, &lab.col_signed, L->total_nnz));
     DGC_HIP_TRY(dev_alloc(L, &lab.seq_in, (int64_t)L->T * L->N));
     DGC_HIP_TRY(dev_alloc(L, &lab.seq_out, (int64_t)L->T * L->N));
+    DGC_HIP_TRY(dev_alloc(L, &lab.labels, (int64_t)L->T * L->N));
   }
+  DGC_HIP_TRY(hipMemcpyAsync(lab.labels, labels, sizeof(int32_t) * (size_t)L->T * L->N, hipMemcpyDeviceToDevice, st));
   labels_build(L->graph_dev(), L->d_segs, labels, lab.col_signed, lab.seq_in, lab.seq_out, st);
   if (L->d_etab)      // the aggregation's table follows the labels: marked columns instead of the range test
     launch_edge_table(L->graph_dev(), L->d_segs, L->nseg, L->total_nnz, L->d_dinv, lab.col_signed, L->d_etab, st);

@@ -329,6 +329,12 @@ void tf_fill(const uint8_t* present, const ChunkInfo* chunks, int32_t n_chunks, 
              int64_t total_rows, int64_t* slot_row, int64_t* row_map, uint8_t* slot_reset, int64_t* seq_in,
              int64_t* seq_out, hipStream_t st);
 void tf_carry(const int32_t* seq_len, int64_t V, int32_t n_state, int32_t H, const float* H0, float* HN, hipStream_t st);
+// temporal fusion over generated chunks: sequences = runs of present instances with one label
+void lp_sequences(const uint8_t* present, const int32_t* labels, int32_t T, int64_t N, int32_t* seq_len, int32_t* first_t,
+                  int32_t* pos, uint8_t* last, hipStream_t st);
+void lp_fill(const uint8_t* present, const int32_t* first_t, const int32_t* pos, const uint8_t* last,
+             const int32_t* seq_lane, const int32_t* seq_off, int32_t T, int64_t N, int64_t n_lanes, int64_t* slot_row,
+             int64_t* row_map, uint8_t* slot_reset, int64_t* seq_in, int64_t* seq_out, hipStream_t st);
 
 // ---- generated chunks (dgc_labels.hip)
 struct Labelled {
@@ -336,6 +342,7 @@ struct Labelled {
   int32_t* col_signed = nullptr;  // [total nnz] see SpmmArgs
   int64_t* seq_in = nullptr;      // [T*N] see DenseArgs
   int64_t* seq_out = nullptr;
+  int32_t* labels = nullptr;      // [T*N] copy of the labels (a later dgc_layer_set_presence reads them)
 };
 void labels_build(const GraphDev& g, const Segment* segs, const int32_t* labels, int32_t* col_signed,
                   int64_t* seq_in, int64_t* seq_out, hipStream_t st);

@@ -68,7 +68,70 @@ __global__ void k_tf_fill_i64(int64_t* p, int64_t v, int64_t n) {
   if (i < n) p[i] = v;
 }
 
+// Temporal fusion over generated chunks (Sections 5.1.2 and 4.1 together): a vertex's sequences
+// are its maximal runs of present instances that carry one label (the label of an absent instance
+// plays no part).  One thread per vertex walks its snapshots and writes, per instance x = t*N + i:
+// the snapshot its sequence starts in (-1: absent), its position in the sequence, whether it is the
+// sequence's last instance, and, at a sequence's first instance, the sequence's length (else 0).
+__global__ void k_lp_sequences(const uint8_t* present, const int32_t* labels, int32_t T, int64_t N, int32_t* seq_len,
+                               int32_t* first_t, int32_t* pos, uint8_t* last) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= N) return;
+  int32_t start = -1, n = 0, prev_label = 0;
+  int64_t prev = -1;
+  for (int32_t t = 0; t < T; ++t) {
+    const int64_t x = (int64_t)t * N + i;
+    seq_len[x] = 0; first_t[x] = -1; pos[x] = 0; last[x] = 0;
+    if (!present[x]) continue;
+    const int32_t lab = labels[x];
+    if (start < 0 || lab != prev_label) {
+      if (start >= 0) { seq_len[(int64_t)start * N + i] = n; last[prev] = 1; }
+      start = t; n = 0;
+    }
+    first_t[x] = start; pos[x] = n; ++n;
+    prev = x; prev_label = lab;
+  }
+  if (start >= 0) { seq_len[(int64_t)start * N + i] = n; last[prev] = 1; }
+}
+
+// slot tables from the lane / first slot assigned to every sequence (indexed by the sequence's
+// first instance); one thread per instance.  The layer's single chunk is [0,N) x [0,T), so the
+// packed row of instance x is x itself.
+__global__ void k_lp_fill(const uint8_t* present, const int32_t* first_t, const int32_t* pos, const uint8_t* last,
+                          const int32_t* seq_lane, const int32_t* seq_off, int64_t TN, int64_t N, int64_t n_lanes,
+                          int64_t* slot_row, int64_t* row_map, uint8_t* slot_reset, int64_t* seq_in, int64_t* seq_out) {
+  const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (x >= TN || !present[x]) return;
+  const int64_t start = (int64_t)first_t[x] * N + x % N;
+  const int64_t slot = (int64_t)(seq_off[start] + pos[x]) * n_lanes + seq_lane[start];
+  slot_row[slot] = x;
+  row_map[x] = slot;
+  if (pos[x] == 0) { slot_reset[slot] = 1; seq_in[slot] = x; }      // the state enters from the cache row of (t, i)
+  if (last[x]) seq_out[slot] = x;                                    // ... and leaves to the row of the last instance
+}
+
 }  // namespace
+
+void lp_sequences(const uint8_t* present, const int32_t* labels, int32_t T, int64_t N, int32_t* seq_len, int32_t* first_t,
+                  int32_t* pos, uint8_t* last, hipStream_t st) {
+  hipLaunchKernelGGL(k_lp_sequences, nblocks(N, 256), 256, 0, st, present, labels, T, N, seq_len, first_t, pos, last);
+}
+
+void lp_fill(const uint8_t* present, const int32_t* first_t, const int32_t* pos, const uint8_t* last,
+             const int32_t* seq_lane, const int32_t* seq_off, int32_t T, int64_t N, int64_t n_lanes, int64_t* slot_row,
+             int64_t* row_map, uint8_t* slot_reset, int64_t* seq_in, int64_t* seq_out, hipStream_t st) {
+  const int64_t n = (int64_t)T * n_lanes, TN = (int64_t)T * N;
+  if (n > 0) {
+    hipLaunchKernelGGL(k_tf_fill_i64, nblocks(n, 256), 256, 0, st, slot_row, (int64_t)-1, n);
+    hipLaunchKernelGGL(k_tf_fill_i64, nblocks(n, 256), 256, 0, st, seq_in, (int64_t)-1, n);
+    hipLaunchKernelGGL(k_tf_fill_i64, nblocks(n, 256), 256, 0, st, seq_out, (int64_t)-1, n);
+    (void)hipMemsetAsync(slot_reset, 0, (size_t)n, st);
+  }
+  hipLaunchKernelGGL(k_tf_fill_i64, nblocks(TN, 256), 256, 0, st, row_map, (int64_t)-1, TN);
+  if (n > 0)
+    hipLaunchKernelGGL(k_lp_fill, nblocks(TN, 256), 256, 0, st, present, first_t, pos, last, seq_lane, seq_off, TN, N,
+                       n_lanes, slot_row, row_map, slot_reset, seq_in, seq_out);
+}
 
 void tf_lengths(const uint8_t* present, const ChunkInfo* chunks, int32_t n_chunks, int64_t max_nv, int64_t N,
                 int32_t* seq_len, hipStream_t st) {

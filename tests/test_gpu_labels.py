@@ -152,9 +152,6 @@ def test_label_refusals():
     dw.layer.destroy()
     dw = DeviceWorkload(wl)
     dw.layer.set_labels(lab)
-    with pytest.raises(DgcError) as ei:           # no temporal fusion on top
-        dw.layer.set_presence(torch.ones(T, N, dtype=torch.uint8, device="cuda"))
-    assert ei.value.code == 7
     with pytest.raises(DgcError) as ei:           # the sequences are the labels' own
         dw.forward(use_h0=False, reset_mask=np.zeros((T, N), np.uint8))
     assert ei.value.code == 1
