@@ -108,11 +108,15 @@ def pack(labels, present) -> dict:
 
 
 def forward(graph, labels, params: dict, X, C, *, time_kind: str = "gru", n_struct_layers: int = 1,
-            C1=None, Hc=None, act_hidden: str = "relu", act_out: str = "none", vertices=None, present=None):
+            C1=None, Hc=None, act_hidden: str = "relu", act_out: str = "none", vertices=None, present=None,
+            n_time_layers: int = 1):
     """Returns Y [T,N,out] float64 and HN [n_state*T*N, H] (NaN where no state leaves a chunk;
     None without a time encoder).  vertices (one structure layer only): evaluate just these
     vertices, all snapshots; Y is then [T, len(vertices), out] and HN is not returned.
-    present [T,N] (needs a time encoder): rows of absent instances are NaN in Y."""
+    present [T,N] (needs a time encoder): rows of absent instances are NaN in Y.
+    n_time_layers = 2: a second recurrent layer ("rnn1.*") on the first one's outputs; a temporal
+    neighbour in another chunk is stale for it too, so its state enters and leaves at the same
+    instances, through its own blocks of Hc / HN (after the first layer's); Y is its output."""
     labels = np.asarray(labels).reshape(graph.T, graph.N)
     T, N = labels.shape
     if present is not None:
@@ -145,25 +149,34 @@ def forward(graph, labels, params: dict, X, C, *, time_kind: str = "gru", n_stru
     lstm = time_kind == "lstm"
     V = T * N
     Y = np.zeros((T, len(idx), H))
-    HN = np.full(((2 if lstm else 1) * V, H), np.nan) if vertices is None else None
+    n_state = 2 if lstm else 1
+    HN = np.full((n_time_layers * n_state * V, H), np.nan) if vertices is None else None
     if present is not None:
         Y[:] = np.nan
     for k, i in enumerate(idx):
-        h = c = None
         ts = [t for t in range(T) if present is None or present[t, i]]      # the vertex's instances
-        for n, t in enumerate(ts):
-            if n == 0 or labels[ts[n - 1], i] != labels[t, i]:      # the temporal neighbour is in another chunk
-                h = np.zeros((1, H)) if Hc is None else np.asarray(Hc[t * N + i], np.float64)[None]
-                c = np.zeros((1, H)) if (Hc is None or not lstm) else np.asarray(Hc[V + t * N + i], np.float64)[None]
-            if lstm:
-                h, c = lstm_step(P, Z[t, k][None], h, c)
-            else:
-                h = gru_step(P, Z[t, k][None], h)
-            Y[t, k] = h[0]
-            if HN is not None and (n == len(ts) - 1 or labels[ts[n + 1], i] != labels[t, i]):
-                HN[t * N + i] = h[0]
+        x = {t: Z[t, k][None] for t in ts}
+        for layer in range(n_time_layers):
+            base = layer * n_state * V
+            rnn = "rnn" if layer == 0 else "rnn1"
+            h = c = None
+            out = {}
+            for n, t in enumerate(ts):
+                if n == 0 or labels[ts[n - 1], i] != labels[t, i]:      # the temporal neighbour is in another chunk
+                    h = np.zeros((1, H)) if Hc is None else np.asarray(Hc[base + t * N + i], np.float64)[None]
+                    c = np.zeros((1, H)) if (Hc is None or not lstm) else np.asarray(Hc[base + V + t * N + i], np.float64)[None]
                 if lstm:
-                    HN[V + t * N + i] = c[0]
+                    h, c = lstm_step(P, x[t], h, c, rnn)
+                else:
+                    h = gru_step(P, x[t], h, rnn)
+                out[t] = h
+                if HN is not None and (n == len(ts) - 1 or labels[ts[n + 1], i] != labels[t, i]):
+                    HN[base + t * N + i] = h[0]
+                    if lstm:
+                        HN[base + V + t * N + i] = c[0]
+            x = out
+        for t in ts:
+            Y[t, k] = x[t][0]
     return Y, HN
 
 

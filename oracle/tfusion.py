@@ -78,21 +78,22 @@ def _sig(x):
     return 1.0 / (1.0 + np.exp(-x))
 
 
-def gru_step(P, x, h):
-    """One step of the GRU the paper's time encoders use (Section 6), rows = sequences."""
+def gru_step(P, x, h, rnn: str = "rnn"):
+    """One step of the GRU the paper's time encoders use (Section 6), rows = sequences.  rnn: the
+    parameter prefix ("rnn", or "rnn1" for a stacked second layer)."""
     H = h.shape[1]
-    gi = x @ P["rnn.weight_ih"].T.astype(np.float64) + P["rnn.bias_ih"]
-    gh = h @ P["rnn.weight_hh"].T.astype(np.float64) + P["rnn.bias_hh"]
+    gi = x @ P[rnn + ".weight_ih"].T.astype(np.float64) + P[rnn + ".bias_ih"]
+    gh = h @ P[rnn + ".weight_hh"].T.astype(np.float64) + P[rnn + ".bias_hh"]
     r = _sig(gi[:, :H] + gh[:, :H])
     z = _sig(gi[:, H:2 * H] + gh[:, H:2 * H])
     n = np.tanh(gi[:, 2 * H:] + r * gh[:, 2 * H:])
     return (1.0 - z) * n + z * h
 
 
-def lstm_step(P, x, h, c):
+def lstm_step(P, x, h, c, rnn: str = "rnn"):
     H = h.shape[1]
-    g = (x @ P["rnn.weight_ih"].T.astype(np.float64) + P["rnn.bias_ih"] +
-         h @ P["rnn.weight_hh"].T.astype(np.float64) + P["rnn.bias_hh"])
+    g = (x @ P[rnn + ".weight_ih"].T.astype(np.float64) + P[rnn + ".bias_ih"] +
+         h @ P[rnn + ".weight_hh"].T.astype(np.float64) + P[rnn + ".bias_hh"])
     i, f, gg, o = _sig(g[:, :H]), _sig(g[:, H:2 * H]), np.tanh(g[:, 2 * H:3 * H]), _sig(g[:, 3 * H:])
     c = f * c + i * gg
     return o * np.tanh(c), c
@@ -105,10 +106,12 @@ def state_rows(chunks) -> np.ndarray:
 
 
 def run_separate(Z: np.ndarray, present: np.ndarray, chunks, params: dict, time_kind: str, H0=None,
-                 return_state: bool = False):
+                 return_state: bool = False, n_time_layers: int = 1):
     """Time encoder over every vertex's own sequence, one chunk and one vertex at a time.
     Z [T,N,S] float64: structure-encoder output.  Returns Y [T,N,H], NaN where nothing is computed
-    (and, with return_state, HN laid out like H0)."""
+    (and, with return_state, HN laid out like H0).  n_time_layers = 2 (Section 6: the two LSTM
+    layers of MPNN-LSTM): a second recurrent layer ("rnn1.*") steps through the same sequence on the
+    first one's outputs; its state blocks follow the first layer's in H0 / HN; Y is its output."""
     T, N, _ = Z.shape
     H = params["rnn.weight_hh"].shape[1]
     Y = np.full((T, N, H), np.nan)
@@ -116,21 +119,29 @@ def run_separate(Z: np.ndarray, present: np.ndarray, chunks, params: dict, time_
     off = state_rows(ch)
     V = int(off[-1])
     n_state = 2 if time_kind == "lstm" else 1
-    HN = np.zeros((n_state * V, H)) if H0 is None else np.array(H0, np.float64, copy=True)
+    HN = np.zeros((n_time_layers * n_state * V, H)) if H0 is None else np.array(H0, np.float64, copy=True)
     for k, seqs in enumerate(sequences(present, ch)):
         for i, ts in seqs:
             row = int(off[k] + i - ch[k, 0])
-            h = HN[row][None].copy()
-            c = HN[V + row][None].copy() if time_kind == "lstm" else np.zeros((1, H))
-            for t in ts:
-                if time_kind == "gru":
-                    h = gru_step(params, Z[t, i][None], h)
-                else:
-                    h, c = lstm_step(params, Z[t, i][None], h, c)
-                Y[t, i] = h[0]
-            HN[row] = h[0]
-            if time_kind == "lstm":
-                HN[V + row] = c[0]
+            x = [Z[t, i][None] for t in ts]
+            for layer in range(n_time_layers):
+                base = layer * n_state * V
+                rnn = "rnn" if layer == 0 else "rnn1"
+                h = HN[base + row][None].copy()
+                c = HN[base + V + row][None].copy() if time_kind == "lstm" else np.zeros((1, H))
+                out = []
+                for xt in x:
+                    if time_kind == "gru":
+                        h = gru_step(params, xt, h, rnn)
+                    else:
+                        h, c = lstm_step(params, xt, h, c, rnn)
+                    out.append(h)
+                HN[base + row] = h[0]
+                if time_kind == "lstm":
+                    HN[base + V + row] = c[0]
+                x = out
+            for t, y in zip(ts, x):
+                Y[t, i] = y[0]
     return (Y, HN) if return_state else Y
 
 

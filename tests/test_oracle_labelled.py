@@ -245,3 +245,96 @@ def test_presence_packing_hand_example_and_properties():
                 lab.reshape(-1)[col[s]] == lab.reshape(-1)[col[s - 1]] and \
                 not present[col[s - 1] // Nn + 1: col[s] // Nn, col[s] % Nn].any()
             assert bool(rst[s]) == (not same)
+
+
+# ---- stacked time encoder (two recurrent layers) over sequences ---------------------------------
+
+@pytest.mark.parametrize("kind", ["gru", "lstm"])
+def test_stacked_encoder_over_sequences(kind):
+    """(i) every instance present, rectangular chunks: the temporal-fusion oracle with two recurrent
+    layers is the rectangular layer with two recurrent layers (pinned against the library's
+    two-layer unit elsewhere), states of both layers included; (ii) rectangular labels give the
+    same through the labelled oracle; (iii) with a presence matrix, every sequence compressed and run
+    through torch.nn.GRU / LSTM with num_layers = 2 from its own state rows."""
+    import torch
+    from oracle import tfusion
+    wl = synth.random_small(61, T, N, F, S, S, 3.0, RECT, kind, hub=True)
+    wl.params = synth.layer_params(61, F, S, S, kind, 1, random_bias=True, n_time_layers=2)
+    n_state = 2 if kind == "lstm" else 1
+    tot = int((RECT[:, 1] - RECT[:, 0]).sum())
+    rng = np.random.default_rng(62)
+    H0 = (0.5 * rng.standard_normal((2 * n_state * tot, S))).astype(np.float32)
+    want, want_HN = oracle.forward(wl.graph, RECT, wl.params, wl.X, wl.C, time_kind=kind, H0=H0, return_state=True,
+                                   n_time_layers=2)
+    Z = oracle.forward(wl.graph, RECT, wl.params, wl.X, wl.C, time_kind="none").astype(np.float64)
+    ones = np.ones((T, N), np.uint8)
+    Y, HN = tfusion.run_separate(Z, ones, RECT, wl.params, kind, H0=H0, return_state=True, n_time_layers=2)
+    assert np.abs(Y - want).max() < 2e-6 and np.abs(HN - want_HN).max() < 2e-6
+    # (ii) labelled oracle, state cache rows at the window starts of the rectangles, both layers
+    V = T * N
+    Hc = np.full((2 * n_state * V, S), np.nan)
+    off = 0
+    for v_lo, v_hi, t_lo, _ in RECT.tolist():
+        nv = v_hi - v_lo
+        for blk in range(2 * n_state):
+            Hc[blk * V + t_lo * N + v_lo: blk * V + t_lo * N + v_hi] = H0[blk * tot + off: blk * tot + off + nv]
+        off += nv
+    lab = labelled.labels_of_chunks(RECT, T, N)
+    Yl, HNl = labelled.forward(wl.graph, lab, wl.params, wl.X, wl.C, time_kind=kind, Hc=Hc, n_time_layers=2)
+    assert np.abs(Yl - want).max() < 2e-6
+    off = 0
+    for v_lo, v_hi, _, t_hi in RECT.tolist():
+        nv = v_hi - v_lo
+        for blk in range(2 * n_state):
+            rows = slice(blk * V + (t_hi - 1) * N + v_lo, blk * V + (t_hi - 1) * N + v_hi)
+            assert np.abs(HNl[rows] - want_HN[blk * tot + off: blk * tot + off + nv]).max() < 2e-6
+        off += nv
+    # (iii) presence: the library's two-layer unit on the compressed sequences
+    present = synth.presence(63, T, N)
+    Yp, HNp = tfusion.run_separate(Z, present, RECT, wl.params, kind, H0=H0, return_state=True, n_time_layers=2)
+    rnn = (torch.nn.GRU if kind == "gru" else torch.nn.LSTM)(S, S, num_layers=2, batch_first=True).double()
+    with torch.no_grad():
+        for l, pre in ((0, "rnn"), (1, "rnn1")):
+            for nm in ("weight_ih", "weight_hh", "bias_ih", "bias_hh"):
+                getattr(rnn, f"{nm}_l{l}").copy_(torch.from_numpy(wl.params[f"{pre}.{nm}"]).double())
+    offs = tfusion.state_rows(RECT)
+    n_checked = 0
+    for k, seqs in enumerate(tfusion.sequences(present, RECT)):
+        for i, ts in seqs:
+            row = int(offs[k] + i - RECT[k, 0])
+            x = torch.from_numpy(Z[ts, i][None])
+            h0 = torch.from_numpy(np.stack([H0[row], H0[n_state * tot + row]]).astype(np.float64))[:, None]
+            with torch.no_grad():
+                if kind == "gru":
+                    out, hn = rnn(x, h0)
+                else:
+                    c0 = torch.from_numpy(np.stack([H0[tot + row], H0[3 * tot + row]]).astype(np.float64))[:, None]
+                    out, (hn, cn) = rnn(x, (h0, c0))
+                    for l in range(2):
+                        assert np.abs(HNp[(2 * l + 1) * tot + row] - cn[l, 0].numpy()).max() < 1e-12
+            assert np.abs(out[0].numpy() - Yp[ts, i]).max() < 1e-12
+            for l in range(2):
+                assert np.abs(HNp[l * n_state * tot + row] - hn[l, 0].numpy()).max() < 1e-12
+            n_checked += 1
+    assert n_checked > 30
+    # and the labelled oracle with presence and one label per rectangle agrees with it
+    Ylp, _ = labelled.forward(wl.graph, lab, wl.params, wl.X, wl.C, time_kind=kind, Hc=_hc_first_instances(Hc, H0, present, n_state, tot),
+                              present=present, n_time_layers=2)
+    # (Yp was fed the C oracle's structure output, rounded to float32 on return: hence 1e-7, not 1e-12)
+    assert np.array_equal(np.isnan(Ylp), np.isnan(Yp)) and np.nanmax(np.abs(Ylp - Yp)) < 1e-7
+
+
+def _hc_first_instances(Hc, H0, present, n_state, tot):
+    """State cache for the labelled oracle under a presence matrix: the H0 row of (chunk, vertex) sits at
+    the vertex's first present instance of the chunk's window."""
+    V = T * N
+    out = np.full_like(Hc, np.nan)
+    off = 0
+    for v_lo, v_hi, t_lo, t_hi in RECT.tolist():
+        for i in range(v_lo, v_hi):
+            ts = [t for t in range(t_lo, t_hi) if present[t, i]]
+            if ts:
+                for blk in range(2 * n_state):
+                    out[blk * V + ts[0] * N + i] = H0[blk * tot + off + i - v_lo]
+        off += v_hi - v_lo
+    return out
