@@ -135,8 +135,9 @@ typedef struct {
                               reading its output step by step; Y is the second layer's output.
                               Needs DGC_STRUCT_GCN, a recurrent time_kind (else
                               DGC_ERR_INVALID_ARG) and S = H in {32, 64, 128} with dense_kernel not
-                              DGC_DENSE_TILE (else DGC_ERR_UNSUPPORTED); not combined with
-                              dgc_layer_set_presence / dgc_layer_set_labels (DGC_ERR_UNSUPPORTED) */
+                              DGC_DENSE_TILE (else DGC_ERR_UNSUPPORTED).  With dgc_layer_set_presence /
+                              dgc_layer_set_labels the second layer steps through the same sequences;
+                              its state blocks follow the first layer's in H0 / HN               */
 } dgc_layer_desc_t;
 
 /* Build a layer for a fixed graph and a fixed set of chunks (the paper partitions once per

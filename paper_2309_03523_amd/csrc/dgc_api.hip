@@ -1031,7 +1031,10 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* L, const void* Xv, int64_t ldx, cons
     // The second recurrent layer: the same kernel without a transform, its input rows the first
     // layer's output, read from Y row by row one step before the row is overwritten with the second
     // layer's output; its states are the blocks of H0 / HN behind the first layer's.
-    const int64_t block = (int64_t)(d.time_kind == DGC_TIME_LSTM ? 2 : 1) * L->total_state_rows * d.H;
+    // (over lanes or generated chunks the sequence tables stay as they are: the second layer's
+    //  sequences are the first one's)
+    const int32_t n_st = d.time_kind == DGC_TIME_LSTM ? 2 : 1;
+    const int64_t block = (int64_t)n_st * da.total_state_rows * d.H;
     da.M = Y; da.ldm = ldy; da.m_by_vertex = true; da.input_is_z = true; da.K0 = 0;
     da.Wih = L->params["rnn1.weight_ih"].packed; da.Whh = L->params["rnn1.weight_hh"].packed;
     da.bih = L->params["rnn1.bias_ih"].raw; da.bhh = L->params["rnn1.bias_hh"].raw;
@@ -1039,7 +1042,9 @@ dgc_status_t dgc_layer_forward(dgc_layer_t* L, const void* Xv, int64_t ldx, cons
     da.wg_step_bytes = 0; da.act = DGC_ACT_NONE;
     da.X2 = nullptr; da.x2_map = nullptr;
     da.H0 = H0 ? H0 + block : nullptr; da.HN = HN ? HN + block : nullptr;
-    if (!launch_dense(da, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
+    if (L->tf.built && HN && !L->lab.built)
+      tf_carry(L->tf.seq_len, L->total_state_rows, n_st, d.H, da.H0, da.HN, st);
+    if ((!L->tf.built || L->tf.n_lanes > 0) && !launch_dense(da, st, &why)) return fail(DGC_ERR_UNSUPPORTED, why);
   }
   if (prof) {
     DGC_HIP_TRY(hipEventRecord(L->ev[4], st));
@@ -1220,7 +1225,6 @@ dgc_status_t dgc_layer_set_presence(dgc_layer_t* L, const uint8_t* present, void
   if (d.struct_kind != DGC_STRUCT_GCN || d.time_kind == DGC_TIME_NONE)
     return fail(DGC_ERR_UNSUPPORTED, "temporal fusion needs a GCN layer with a recurrent time encoder");
   if (L->tf.built) return fail(DGC_ERR_STATE, "the presence mask of a layer can be set once");
-  if (d.n_time_layers == 2) return fail(DGC_ERR_UNSUPPORTED, "temporal fusion is not built for a stacked time encoder");
   if ((int64_t)L->T * L->N >= INT32_MAX) return fail(DGC_ERR_UNSUPPORTED, "temporal fusion needs T*N < 2^31");
   if (L->lab.built) return set_presence_labelled(L, present, st);
   if (L->n_chunks > kMaxGridYZ)  // its kernels take one grid row per chunk
@@ -1318,7 +1322,6 @@ dgc_status_t dgc_layer_set_labels(dgc_layer_t* L, const int32_t* labels, void* s
   if (d.gather_mode != DGC_GATHER_IN_PLACE)
     return fail(DGC_ERR_UNSUPPORTED, "generated chunks need gather_mode DGC_GATHER_IN_PLACE");
   if (L->tf.built) return fail(DGC_ERR_STATE, "the labels of a layer are set before its presence mask, and not again after it");
-  if (d.n_time_layers == 2) return fail(DGC_ERR_UNSUPPORTED, "generated chunks are not built for a stacked time encoder");
   const dgc_chunk_t& c = L->chunks[0];
   if (L->n_chunks != 1 || c.v_lo != 0 || c.v_hi != L->N || c.t_lo != 0 || c.t_hi != L->T)
     return fail(DGC_ERR_STATE, "labels need a layer created with the single chunk [0,N) x [0,T)");

@@ -215,7 +215,14 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
   // columns, so a k-block never needs masking.)
   // (m_by_vertex: the input rows are not the packed aggregated rows but rows t*N + v of a [T,N,ldm]
   //  tensor - the first recurrent layer's output when this launch runs a stacked second layer)
-  const float* mrow0 = STACK ? a.M + ((int64_t)ch.t_lo * a.N + vrow) * a.ldm + 4 * half
+  // (STACK over lanes, i.e. with a row map: the input row of a slot is the row of Y the slot's output
+  //  goes to; the map entry of the next step is fetched one step ahead, an empty slot reads row 0)
+  int yrow_next = 0;
+  if constexpr (STACK && SEQ) {
+    if (a.y_map) yrow_next = (int)a.y_map[(int64_t)ch.t_lo * a.N + vrow];
+  }
+  const float* mrow0 = STACK ? a.M + ((STACK && SEQ && a.y_map) ? (int64_t)max(yrow_next, 0)
+                                                                 : (int64_t)ch.t_lo * a.N + vrow) * a.ldm + 4 * half
                              : a.M + (ch.row_off0 + tile.v0 + row) * a.ldm + 4 * half;
   const int64_t mstep = STACK ? a.N * a.ldm : ch.nv * a.ldm;
   float4 xq[kXAhead];
@@ -238,9 +245,16 @@ __global__ __launch_bounds__(kWave, (KIND == DGC_TIME_LSTM ? 1 : 2)) void k_dens
     const int64_t t = ch.t_lo + s;
     if constexpr (SEQ) {
       yrow_prev = yrow;
-      if (a.y_map) yrow = (int)a.y_map[t * a.N + vrow];   // used one step later: no wait here
+      if constexpr (STACK) {
+        if (a.y_map) {
+          yrow = yrow_next;
+          if (s + 1 < ch.w) yrow_next = (int)a.y_map[(t + 1) * a.N + vrow];
+        }
+      } else {
+        if (a.y_map) yrow = (int)a.y_map[t * a.N + vrow];   // used one step later: no wait here
+      }
     }
-    const float* mrow = mrow0 + s * mstep;
+    const float* mrow = (STACK && SEQ && a.y_map) ? a.M + (int64_t)max(yrow, 0) * a.ldm + 4 * half : mrow0 + s * mstep;
     auto load_x = [&](int kb) -> float4 { return *reinterpret_cast<const float4*>(mrow + 8 * kb); };
     if (s > 0) {
 #pragma unroll
@@ -483,11 +497,12 @@ bool launch_w(const DenseArgs& a, hipStream_t st, std::string* why) {
     auto go = [&](auto kernel) {
       hipLaunchKernelGGL(kernel, (unsigned)a.n_tiles32, kWave, lds, st, a);
     };
-    if (a.input_is_z != a.m_by_vertex || (a.input_is_z && (!kRnn || a.seq_in || cat))) {
-      if (why) *why = "a stacked recurrent layer runs without sequence tables and without the concatenated input";
+    if (a.input_is_z != a.m_by_vertex || (a.input_is_z && (!kRnn || cat))) {
+      if (why) *why = "a stacked recurrent layer runs without the concatenated input";
       return false;
     }
-    if (a.input_is_z) go(k_dense_wave<KIND, NJB, false, false, kRnn>);
+    if (a.input_is_z && a.seq_in) go(k_dense_wave<KIND, NJB, kRnn, false, kRnn>);
+    else if (a.input_is_z) go(k_dense_wave<KIND, NJB, false, false, kRnn>);
     else if (kRnn && a.seq_in && cat) go(k_dense_wave<KIND, NJB, kRnn, kLstm>);
     else if (kRnn && a.seq_in) go(k_dense_wave<KIND, NJB, kRnn, false>);
     else if (cat) go(k_dense_wave<KIND, NJB, false, kLstm>);
