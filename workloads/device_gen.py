@@ -280,14 +280,15 @@ def config4(seed: int = 0, scale: float = 1.0, say=None):
     return data, target
 
 
-def config5(seed: int = 0, scale: float = 1.0, say=None):
+def config5(seed: int = 0, scale: float = 1.0, say=None, window: int = 16):
     """Config 5 drawn on the device: 16 snapshots x (1,000,000 * scale) vertices, 6 N edge draws per
     snapshot with tail exponent 2.1, F = S = 128, 8 heads, 128 uneven vertex ranges x one 16-snapshot
     window; features, cache = features + 0.1 N(0,1) and targets ~ N(0,1), all bfloat16.
-    Returns (data, target)."""
+    window != 16: that many snapshots in one window, and 16 / window times the vertices (the same
+    number of rows).  Returns (data, target)."""
     import torch
-    T, F, heads = 16, 128, 8
-    N = max(1024, int(1_000_000 * scale))
+    T, F, heads = int(window), 128, 8
+    N = max(1024, int(1_000_000 * scale * 16 / T))
     w = synth.powerlaw_weights(N, 2.1, synth.stream(seed, "perm"))
     cdf_h = np.cumsum(w)
     cdf_h[-1] = 1.0
@@ -301,7 +302,7 @@ def config5(seed: int = 0, scale: float = 1.0, say=None):
     if say:
         say(f"  graph: {T} snapshots")
     del cdf
-    chunks = synth.grid_chunks(T, 16, [synth.uneven_ranges(N, 128, synth.stream(seed, "ranges"))])
+    chunks = synth.grid_chunks(T, T, [synth.uneven_ranges(N, 128, synth.stream(seed, "ranges"))])
 
     def bf16(gen_name, base=None, scale_=1.0):
         g = _gen(seed, gen_name)
