@@ -48,10 +48,15 @@ def test_evolving_gcn_training_step_twice():
     dw.layer.destroy()
 
 
-def test_attention_training_step_twice():
+@pytest.mark.parametrize("wide", [False, True])
+def test_attention_training_step_twice(wide):
     import torch
     from paper_2309_03523_amd.runner import DysatDevice
-    wl, target = synth.config5(seed=3, scale=0.004)
+    if wide:     # a window of more than 16 snapshots: one vertex per tile in the temporal kernels
+        wl = synth.dysat_small(3, 24, 300, 128, 8, 5.0, [[0, 140, 0, 24], [140, 300, 0, 24]], hub=True)
+        target = synth.round_bf16(synth.stream(3, "target").standard_normal(wl.X.shape).astype(np.float32))
+    else:
+        wl, target = synth.config5(seed=3, scale=0.004)
     dd = DysatDevice(wl, long_nnz=64, part_nnz=16)
     tgt = torch.from_numpy(target).cuda().to(torch.bfloat16)
     runs = []

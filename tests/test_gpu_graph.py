@@ -134,11 +134,13 @@ def test_evolve_training_step_replays_from_a_graph():
     dw.layer.destroy()
 
 
-def test_attention_training_step_replays_from_a_graph():
+@pytest.mark.parametrize("T,chunks", [(6, [[0, 70, 0, 6], [70, 150, 0, 4]]), (20, [[0, 70, 0, 20], [70, 150, 3, 12]])])
+def test_attention_training_step_replays_from_a_graph(T, chunks):
+    """(the second case has a window of more than 16 snapshots: one vertex per tile in the temporal kernels)"""
     import torch
     from oracle import dysat
     from paper_2309_03523_amd.runner import DysatDevice
-    wl = synth.dysat_small(11, 6, 150, 128, 8, 4.0, [[0, 70, 0, 6], [70, 150, 0, 4]], hub=True)
+    wl = synth.dysat_small(11, T, 150, 128, 8, 4.0, chunks, hub=True)
     dd = DysatDevice(wl)
     gen = torch.Generator(device="cuda").manual_seed(5)
     target = torch.randn(dd.X.shape, device="cuda", generator=gen).to(torch.bfloat16)
