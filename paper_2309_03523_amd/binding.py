@@ -229,7 +229,8 @@ class DgcLayer:
             _ld(target, "target"), _dev(loss_out, "loss_out"), _dev(dX, "dX"), _ld(dX, "dX"), _stream_ptr(stream)))
 
     def set_presence(self, present, stream=None):
-        """present: uint8 device tensor [T,N]; switches the layer to temporal fusion."""
+        """present: uint8 device tensor [T,N]; switches the layer to temporal fusion (on a layer that has
+        labels: over the runs of present instances with one label; labels are set first)."""
         if not present.is_cuda or present.dtype.itemsize != 1 or not present.is_contiguous():
             raise ValueError("present must be a contiguous uint8 device tensor [T,N]")
         self._check(self._lib.dgc_layer_set_presence(self._h, _dev(present, "present"), _stream_ptr(stream)))
