@@ -715,6 +715,9 @@ struct GatBwdColsArgs {
   float* dss;           // [T*N][16]: d s_src of the row as an in-chunk neighbour [8], as a cache row [8]
 };
 
+constexpr int kSlotRow = 16;     // rows of at most this many non-zeros are taken one per slot (k_gat_bwd_cols_slot)
+constexpr int kSlotU = 2;        // neighbours in flight per slot there (4 or 8, with fewer waves per SIMD, measured slower)
+constexpr int kSlotWaves = 4;    // waves per SIMD of that kernel
 constexpr int kColsRec = 272;    // floats per scratch record of a part of a split row: dzX[128], dzC[128], dsx[8], dsc[8]
 
 // Lane layout of the reverse-edge pass: lane = 16 * slot + sub.  The four slots work on four
@@ -830,11 +833,11 @@ __device__ __forceinline__ AttVec att_init(const GatBwdColsArgs& a, int sub) {
   return v;
 }
 
-template <bool LO>   // LO: also keep what dzX loses to rounding (asked for with the input gradient)
+template <bool LO, bool EVERY_SLOT = false>   // LO: also keep what dzX loses to rounding (asked for with the input gradient)
 __device__ __forceinline__ void gat_bwd_col_finish(const GatBwdColsArgs& a, int64_t row, const ColOwn& o,
                                                    const ColAcc& r, const AttVec& v, int lane) {
   const int slot = lane >> 4, sub = lane & 15, head = sub >> 1;
-  if (slot != 0) return;
+  if (!EVERY_SLOT && slot != 0) return;      // EVERY_SLOT: each slot holds a row of its own
   float out[8];
   if (o.oj >= 0) {
     const float dsd = a.st2[row * 8 + head].w;
@@ -856,6 +859,83 @@ __device__ __forceinline__ void gat_bwd_col_finish(const GatBwdColsArgs& a, int6
     a.dss[row * 16 + head] = r.dsx;
     a.dss[row * 16 + 8 + head] = r.dsc;
   }
+}
+
+// Rows of at most kSlotRow non-zeros (nine vertices in ten of a power-law graph, a third of the
+// non-zeros): ONE ROW PER SLOT, four rows per wave side by side.  What a row costs apart from its
+// non-zeros (its own projections and scalars, the final combination and stores) is then paid once
+// per four rows, and nothing has to be summed across the slots.  The 16 lanes of a slot first
+// fetch the row's column ids and codes, one neighbour per lane, and hand them round with a
+// shuffle inside the slot; two neighbours per slot are in flight (eight gathered rows per wave).
+template <bool LO>
+__global__ __launch_bounds__(256, kSlotWaves) void k_gat_bwd_cols_slot(GatBwdColsArgs a) {
+  const int lane = threadIdx.x & 63, slot = lane >> 4, sub = lane & 15, head = sub >> 1;
+  const int64_t N = a.g.N;
+  const int64_t quads_per_t = (N + 3) / 4, n_items = quads_per_t * a.n_used;
+  const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (item >= n_items) return;
+  const int32_t t = a.used_t[item / quads_per_t];
+  const int64_t j = (item % quads_per_t) * 4 + slot;
+  const bool live = j < N;
+  const int64_t base = (int64_t)t * N, row = base + (live ? j : N - 1);
+  const int64_t* rp = a.g.rowptr[t] + (live ? j : N - 1);
+  const int64_t e0 = rp[0], len = rp[1] - e0;
+  const int n = (live && len <= kSlotRow && len <= a.long_nnz) ? (int)len : 0;     // 0: not this kernel's row
+  const int32_t* col = a.g.colidx[t];
+  const uint8_t* code = a.ecode + a.ecode_off[t];
+  const int32_t il = sub < n ? col[e0 + sub] : 0;
+  const int32_t cl = sub < n ? code[e0 + sub] : 0;
+  const ColOwn o = col_own(a, row, sub);
+  const AttVec v = att_init(a, sub);
+  int nmax = __builtin_amdgcn_readlane(n, 0);
+  nmax = max(nmax, __builtin_amdgcn_readlane(n, 16));
+  nmax = max(nmax, __builtin_amdgcn_readlane(n, 32));
+  nmax = max(nmax, __builtin_amdgcn_readlane(n, 48));
+  ColAcc r;
+#pragma unroll
+  for (int d = 0; d < 8; ++d) { r.ax[d] = 0.f; r.ac[d] = 0.f; }
+  r.dsx = 0.f; r.dsc = 0.f;
+  for (int k0 = 0; k0 < nmax; k0 += kSlotU) {
+    uint4 dv[kSlotU];
+    float4 st[kSlotU];
+    int32_t cc[kSlotU];
+#pragma unroll
+    for (int u = 0; u < kSlotU; ++u) {
+      const int k = k0 + u;                              // < 16 + 1: the shuffle wraps inside the slot, the code is masked
+      const int32_t ii = __shfl(il, (lane & 48) | (k & 15));
+      const int32_t cs = __shfl(cl, (lane & 48) | (k & 15));
+      cc[u] = k < n ? cs : 0;
+      dv[u] = make_uint4(0, 0, 0, 0);
+      st[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (cc[u] != 0) {
+        dv[u] = *reinterpret_cast<const uint4*>(a.dU + (base + ii) * kS + 8 * sub);
+        st[u] = a.st2[(base + ii) * 8 + head];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kSlotU; ++u) {
+      float du[8];
+      unpack8(dv[u], du);
+      const bool sm = cc[u] == 1;
+      const float e = st[u].x + (sm ? o.ssx : o.ssc);
+      float al = __expf(lrelu(e) - st[u].y);
+      float da = 0.f;
+#pragma unroll
+      for (int d = 0; d < 8; ++d) da += du[d] * (sm ? o.zx[d] : o.zc[d]);
+      da += quad_xor1(da);
+      al = cc[u] != 0 ? al : 0.f;
+      const float dpre = al * (da - st[u].z) * (e > 0.f ? 1.f : kSlope);
+      const float alx = sm ? al : 0.f, alc = sm ? 0.f : al;
+#pragma unroll
+      for (int d = 0; d < 8; ++d) {
+        r.ax[d] += alx * du[d];
+        r.ac[d] += alc * du[d];
+      }
+      r.dsx += sm ? dpre : 0.f;
+      r.dsc += sm ? 0.f : dpre;
+    }
+  }
+  if (n > 0) gat_bwd_col_finish<LO, true>(a, row, o, r, v, lane);
 }
 
 template <bool LO>
@@ -891,7 +971,7 @@ __global__ __launch_bounds__(256, 4) void k_gat_bwd_cols(GatBwdColsArgs a) {   /
       nil = ne0 + lane < ne1 ? col[ne0 + lane] : 0;
       ncl = ne0 + lane < ne1 ? code[ne0 + lane] : 0;
     }
-    if (e1 - e0 <= a.long_nnz) {
+    if (e1 - e0 <= a.long_nnz && e1 - e0 > kSlotRow) {     // shorter rows: k_gat_bwd_cols_slot
       const ColOwn o = col_own(a, base + j0 + rr, sub);
       const ColAcc r = gat_bwd_col_range(a, col, code, base, o, e0, e1, il, cl, lane);
       gat_bwd_col_finish<LO>(a, base + j0 + rr, o, r, v, lane);
@@ -1220,6 +1300,9 @@ void dysat_backward(const DysatWs& ws, const void* Y, int64_t ldy, const void* d
   ca.dzXlo = dX ? ws.dzXlo : nullptr;
   ca.cols_long = ws.cols_long; ca.n_cols_long = ws.n_cols_long; ca.long_nnz = ws.long_nnz; ca.part_nnz = ws.part_nnz;
   ca.long_partial = ws.long_partial;
+  const int64_t quads = (ws.N + 3) / 4 * ws.n_used;
+  if (dX) hipLaunchKernelGGL(k_gat_bwd_cols_slot<true>, blocks_for(quads, 4), 256, 0, st, ca);
+  else hipLaunchKernelGGL(k_gat_bwd_cols_slot<false>, blocks_for(quads, 4), 256, 0, st, ca);
   if (dX) hipLaunchKernelGGL(k_gat_bwd_cols<true>, blocks_for(items, 4), 256, 0, st, ca);
   else hipLaunchKernelGGL(k_gat_bwd_cols<false>, blocks_for(items, 4), 256, 0, st, ca);
   if (ws.n_cols_long > 0) {
