@@ -187,3 +187,44 @@ def labels_of_chunks(chunks, T: int, N: int) -> np.ndarray:
         lab[t_lo:t_hi, v_lo:v_hi] = k
     assert (lab >= 0).all()
     return lab
+
+
+def evolve(graph, labels, params: dict, X, C, target=None, want_dx: bool = False) -> dict:
+    """EvolveGCN-O (the paper's Section 1 names it; weight W_t = matGRU(W_{t-1}), Y_t = relu(M_t W_t),
+    mean-squared-error loss over all T*N*S outputs) over GENERATED chunks: M_t is the aggregation by
+    labels of this module (row (t, i) reads X[t, j] from neighbours with its own label, the cache row
+    otherwise; the cache is a constant).  Written with torch CPU float64 operations on dense per-snapshot
+    matrices, gradients by autograd: the plain definition, for small cases.
+    Returns dict(Y [T,N,S], loss, grads {name: array} and dX [T,N,F] if a target is given)."""
+    import torch
+    labels = np.asarray(labels).reshape(graph.T, graph.N)
+    T, N = labels.shape
+    P = {k: torch.tensor(np.asarray(v, np.float64), requires_grad=target is not None) for k, v in params.items()}
+    Xt = torch.tensor(np.asarray(X, np.float64), requires_grad=want_dx and target is not None)
+    Ct = torch.tensor(np.asarray(C, np.float64))
+    W = P["evolve.W_init"]
+    Ys = []
+    for t in range(T):
+        Zg = torch.sigmoid(P["evolve.U_z"] @ W + P["evolve.V_z"] @ W + P["evolve.B_z"])
+        Rg = torch.sigmoid(P["evolve.U_r"] @ W + P["evolve.V_r"] @ W + P["evolve.B_r"])
+        Wc = torch.tanh(P["evolve.U_h"] @ W + P["evolve.V_h"] @ (Rg * W) + P["evolve.B_h"])
+        W = (1 - Zg) * W + Zg * Wc
+        sn = graph.snaps[t]
+        deg = np.diff(sn.rowptr).astype(np.float64)
+        fresh = np.zeros((N, N))
+        stale = np.zeros((N, N))
+        for i in range(N):
+            for j in sn.col[sn.rowptr[i]:sn.rowptr[i + 1]]:
+                (fresh if labels[t, j] == labels[t, i] else stale)[i, j] = 1.0 / np.sqrt(deg[i] * deg[j])
+        M = torch.from_numpy(fresh) @ Xt[t] + torch.from_numpy(stale) @ Ct[t]
+        Ys.append(torch.relu(M @ W))
+    Y = torch.stack(Ys)
+    out = {"Y": Y.detach().numpy()}
+    if target is not None:
+        loss = ((Y - torch.tensor(np.asarray(target, np.float64))) ** 2).mean()
+        loss.backward()
+        out["loss"] = float(loss.item())
+        out["grads"] = {k: P[k].grad.numpy() for k in params}
+        if want_dx:
+            out["dX"] = Xt.grad.numpy()
+    return out

@@ -338,3 +338,32 @@ def _hc_first_instances(Hc, H0, present, n_state, tot):
                     out[blk * V + ts[0] * N + i] = H0[blk * tot + off + i - v_lo]
         off += v_hi - v_lo
     return out
+
+
+# ---- EvolveGCN-O over generated chunks --------------------------------------------------------
+
+def test_evolving_weights_over_rectangular_labels_equal_the_rectangular_oracle():
+    """Labels that are rectangles: outputs, loss, all ten parameter gradients and the input gradient of
+    the labelled definition (torch autograd, dense matrices) against the C oracle's (loops, hand-written
+    back-propagation; itself pinned by autograd from edge lists and finite differences).  And labels
+    matter: moving one vertex to another chunk changes its neighbours' rows."""
+    Fe = 6
+    wl = synth.random_small(71, T, N, Fe, 32, 32, 3.0, RECT, "none", hub=True)
+    params = synth.evolve_params(8, Fe, Fe, random_bias=True)
+    target = synth.stream(8, "target").standard_normal((T, N, Fe)).astype(np.float32)
+    want = oracle.evolve(wl.graph, RECT, params, wl.X, wl.C, target, want_grads=True, want_dx=True)
+    lab = labelled.labels_of_chunks(RECT, T, N)
+    got = labelled.evolve(wl.graph, lab, params, wl.X, wl.C, target, want_dx=True)
+    assert np.abs(got["Y"] - want["Y"]).max() < 1e-5                  # the C oracle returns float32
+    assert abs(got["loss"] - want["loss"]) < 1e-10 * max(1.0, want["loss"])
+    for k in oracle.EVOLVE_PARAMS:
+        assert np.abs(got["grads"][k] - want["grads"][k]).max() < 1e-10 * max(1.0, np.abs(want["grads"][k]).max()), k
+    assert np.abs(got["dX"] - want["dX"]).max() < 1e-12 * max(1.0, np.abs(want["dX"]).max())
+    lab2 = lab.copy()
+    lab2[2, 3] = 99
+    moved = labelled.evolve(wl.graph, lab2, params, wl.X, wl.C)["Y"]
+    sn = wl.graph.snaps[2]
+    nb = [int(j) for j in sn.col[sn.rowptr[3]:sn.rowptr[4]] if j != 3 and lab[2, j] == lab[2, 3]]
+    changed = np.flatnonzero(np.abs(moved[2] - got["Y"][2]).max(axis=1) > 0)
+    assert set(changed.tolist()) <= set(nb + [3]) and (not nb or len(changed) > 0)
+    assert np.array_equal(moved[[0, 1, 3, 4]], got["Y"][[0, 1, 3, 4]])
