@@ -225,7 +225,9 @@ dgc_status_t dgc_layer_set_presence(dgc_layer_t* layer, const uint8_t* present, 
 
 /* Generated chunks as the layer's input (Sections 4.1 and 5.2): labels device int32 [T*N], any
  * values (what dgc_chunk_generate wrote, for instance); a chunk is the set of (snapshot, vertex)
- * pairs with one label.  For a layer created with DGC_STRUCT_GCN, DGC_GATHER_IN_PLACE and the
+ * pairs with one label.  For a layer created with DGC_STRUCT_GCN or DGC_STRUCT_EVOLVE_GCN_O (there
+ * only the aggregation changes: forward, backward and the input gradient read a neighbour's fresh
+ * row where the labels agree and the cache row, a constant, where they do not), DGC_GATHER_IN_PLACE and the
  * single chunk [0,N) x [0,T) (DGC_ERR_STATE otherwise; the rectangle only says which rows exist).
  * After this call dgc_layer_forward computes, for every (t, i):
  *   aggregation: neighbour j of snapshot t contributes X[t,j] (for the second GCN layer the first

@@ -1318,7 +1318,8 @@ dgc_status_t dgc_layer_set_labels(dgc_layer_t* L, const int32_t* labels, void* s
   const dgc_layer_desc_t& d = L->desc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (!labels) return fail(DGC_ERR_INVALID_ARG, "labels is NULL");
-  if (d.struct_kind != DGC_STRUCT_GCN) return fail(DGC_ERR_UNSUPPORTED, "generated chunks are built for GCN layers");
+  if (d.struct_kind != DGC_STRUCT_GCN && d.struct_kind != DGC_STRUCT_EVOLVE_GCN_O)
+    return fail(DGC_ERR_UNSUPPORTED, "generated chunks are built for GCN and EvolveGCN-O layers");
   if (d.gather_mode != DGC_GATHER_IN_PLACE)
     return fail(DGC_ERR_UNSUPPORTED, "generated chunks need gather_mode DGC_GATHER_IN_PLACE");
   if (L->tf.built) return fail(DGC_ERR_STATE, "the labels of a layer are set before its presence mask, and not again after it");

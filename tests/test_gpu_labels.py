@@ -187,3 +187,36 @@ def test_random_shapes_and_labellings(seed):
     _check(wl, lab, Hc, Y, HN, layers, f"seed {seed}: N={N} T={T} F={F} S={S} {kind} layers={layers} labelling {mode} "
                                        f"cache={'yes' if Hc is not None else 'no'}")
     dw.layer.destroy()
+
+
+@pytest.mark.parametrize("F,agg", [(32, "table"), (64, "walk"), (128, "table"), (256, "table")])
+def test_evolving_weights_over_generated_chunks(F, agg):
+    """EvolveGCN-O with labels: outputs, loss, the ten parameter gradients and the input gradient against
+    the labelled oracle (torch float64 autograd on the definition); split hub rows included."""
+    import torch
+    from paper_2309_03523_amd.runner import DeviceWorkload
+    T, N = 5, 140
+    wl = synth.random_small(400 + F, T, N, F, F, F, 4.0, [[0, N, 0, T]], "none", hub=True)
+    wl.params = synth.evolve_params(400 + F, F, F, random_bias=True)
+    rng = np.random.default_rng(F)
+    lab = _random_labels(rng, T, N, 5, 0.7)
+    target = synth.stream(F, "target-lab").standard_normal((T, N, F)).astype(np.float32)
+    dw = DeviceWorkload(wl, struct_kind="evolve_gcn_o", act_out="relu", agg_kernel=agg, long_nnz=24, part_nnz=8)
+    dw.layer.set_labels(torch.from_numpy(lab.astype(np.int32).reshape(-1)).cuda())
+    Y = dw.forward()
+    want = labelled.evolve(wl.graph, lab, wl.params, wl.X, wl.C, target, want_dx=True)
+    e_y = rel_err(Y.cpu().numpy(), want["Y"])
+    tgt = torch.from_numpy(target).cuda()
+    loss = torch.zeros(1, device="cuda")
+    dX = torch.full((T, N, F), float("nan"), device="cuda")
+    dw.layer.backward(Y, target=tgt, loss_out=loss, dX=dX)
+    torch.cuda.synchronize()
+    assert e_y < TOL and abs(loss.item() - want["loss"]) < 1e-5 * want["loss"]
+    worst = 0.0
+    for name in oracle.EVOLVE_PARAMS:
+        g = dw.layer.get_param(name + ".grad", wl.params[name].shape)
+        worst = max(worst, rel_err(g, want["grads"][name]))
+    e_x = rel_err(dX.cpu().numpy(), want["dX"])
+    print(f"EvolveGCN-O over labels F={F} {agg}: Y {e_y:.2e}, parameter gradients {worst:.2e}, dX {e_x:.2e}", flush=True)
+    assert worst < TOL and e_x < TOL
+    dw.layer.destroy()
